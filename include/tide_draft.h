@@ -1,0 +1,202 @@
+/*
+ * tide_draft.h -- C ABI of the TIDE online draft-training step for AMD MI355X (gfx950).
+ *
+ * The operation.  TIDE keeps a speculative-decoding draft model aligned with a
+ * served target model by fine-tuning the draft on hidden states that the target
+ * already produced while serving, instead of running the target a second time
+ * (paper Sec. 3.3, "Online Draft Model Adaptation").  The draft is one decoder
+ * layer plus an LM head that reads the concatenation of the target's hidden
+ * states at a low, a middle and a high layer (Sec. 3.2, "Serving-Time Training
+ * Signal Extraction") and predicts, over the target's own vocabulary (Sec. 5.1,
+ * "Draft Model Configuration"), the token the target emitted (Fig. 7 caption:
+ * accuracy is the top-1 match with the target).  One call of
+ * tide_draft_train_step is one optimizer step of that fine-tuning on one batch
+ * of captured signals:
+ *
+ *   x0 = Hcat W_fc^T                                 feature projection
+ *   a  = rmsnorm(x0; g1); [q|k|v] = a W_qkv^T; rotate-half RoPE on q, k
+ *   A  = causal grouped-query softmax attention(q, k, v)
+ *   x1 = x0 + A W_o^T
+ *   b  = rmsnorm(x1; g2); h = silu(b W_gate^T) * (b W_up^T); x2 = x1 + h W_down^T
+ *   y  = rmsnorm(x2; g3); z = y W_lm^T   (computed by row block, never whole)
+ *   loss = (1/N) sum_t keep_t (logsumexp(z_t) - z_t[tokens_t]),  N = max(1, sum keep)
+ *   keep_t = loss_mask_t != 0 and 0 <= tokens_t < vocab
+ *   grads = d loss / d params (no gradient w.r.t. the captured states), then AdamW.
+ *
+ * The paper gives no layer equations; the block internals above are the
+ * standard definitions of those blocks (no biases anywhere, RMSNorm epsilon
+ * inside the square root, softmax scale 1/sqrt(head_dim), AdamW with bias
+ * correction and decoupled decay applied to every tensor).
+ *
+ * Conventions common to all entry points
+ *   - Every pointer marked DEVICE is GPU memory owned by the caller; the library
+ *     allocates and frees nothing.  Buffers must stay valid until the work
+ *     enqueued on `stream` has completed.  Calls are asynchronous: no host
+ *     synchronisation is performed; outputs are valid after the stream is
+ *     synchronised.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Matrices are row-major; weights are stored [out_features, in_features].
+ *   - dtype TIDE_DTYPE_FP32: params, hidden_buf are float.  dtype TIDE_DTYPE_BF16:
+ *     params and hidden_buf are bfloat16 (raw 16-bit), compute accumulates in
+ *     fp32.  Gradients, Adam moments and master weights are always float.
+ *   - Return value: 0 on success, a negative TIDE_ERR_* code otherwise, with
+ *     tide_last_error() describing the problem.  Arguments are validated before
+ *     any work is enqueued: on TIDE_ERR_NULL / _CONFIG / _WORKSPACE nothing has
+ *     been enqueued.  On TIDE_ERR_HIP (a launch failed midway) earlier kernels of
+ *     the call may already be queued and the outputs are undefined.  On any error
+ *     adam_state->step is unchanged.  The library never aborts and never throws
+ *     across this boundary.
+ */
+#ifndef TIDE_DRAFT_H
+#define TIDE_DRAFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TIDE_OK             0
+#define TIDE_ERR_NULL      (-1)  /* a required pointer is NULL */
+#define TIDE_ERR_CONFIG    (-2)  /* inconsistent or unsupported tide_draft_config */
+#define TIDE_ERR_WORKSPACE (-3)  /* workspace too small or not 256-byte aligned */
+#define TIDE_ERR_HIP       (-4)  /* a HIP call or kernel launch failed */
+
+#define TIDE_DTYPE_FP32 0
+#define TIDE_DTYPE_BF16 1
+
+/* Shape and hyper-parameters of the draft (host memory, read on every call).
+ * Requirements: all sizes > 0; hidden == n_heads*head_dim; n_heads % n_kv_heads
+ * == 0; head_dim even; rms_eps > 0; rope_theta > 0; dtype is one of TIDE_DTYPE_*.
+ * batch*seq*max(vocab, ...) must fit the 32-bit tile arithmetic documented in
+ * the sources (batch*seq <= 2^22 positions, every dimension < 2^24). */
+typedef struct tide_draft_config {
+  int32_t batch, seq;                 /* B, S: hidden_buf is [B, S, n_capture*target_hidden] */
+  int32_t n_capture, target_hidden;   /* K (3 in the paper) captured layers of width H_t */
+  int32_t hidden;                     /* d: draft width (projection output) */
+  int32_t n_heads, n_kv_heads, head_dim;
+  int32_t ffn;                        /* F: SwiGLU inner width */
+  int32_t vocab;                      /* V: the target's vocabulary */
+  float rope_theta, rms_eps;
+  float beta1, beta2, adam_eps, weight_decay;
+  int32_t dtype;
+} tide_draft_config;
+
+/* The ten tensors of the draft; the same struct describes parameters, gradients,
+ * Adam moments and master weights (identical shapes).  All DEVICE pointers. */
+typedef struct tide_draft_tensors {
+  void *w_fc;    /* [d, K*H_t] */
+  void *g1;      /* [d]   gain of the attention-input RMSNorm */
+  void *w_qkv;   /* [(n_heads + 2*n_kv_heads)*head_dim, d]: q rows, then k rows, then v rows */
+  void *w_o;     /* [d, n_heads*head_dim] */
+  void *g2;      /* [d]   gain of the MLP-input RMSNorm */
+  void *w_gate;  /* [F, d] */
+  void *w_up;    /* [F, d] */
+  void *w_down;  /* [d, F] */
+  void *g3;      /* [d]   gain of the final RMSNorm */
+  void *w_lm;    /* [V, d] */
+} tide_draft_tensors;
+
+/* Optimizer state.  m, v: float first/second moments.  master: float master
+ * copy of the parameters, used and updated only in bf16 mode (the bf16 params
+ * are re-rounded from it every step); ignored (may be all NULL) in fp32 mode.
+ * step: number of updates applied so far; host memory, incremented by a
+ * successful tide_draft_train_step. */
+typedef struct tide_adam_state {
+  tide_draft_tensors m, v, master;
+  int64_t step;
+} tide_adam_state;
+
+/* Bytes of DEVICE scratch the two calls below need for this config (the larger
+ * of the two).  Returns 0 if the config is invalid (see tide_last_error). */
+size_t tide_draft_workspace_bytes(const tide_draft_config *cfg);
+
+/* Forward only (what the evaluation step of the paper's Algorithm 1 runs on held-out signals):
+ * writes the masked mean cross-entropy to *loss_out (DEVICE float) and, if
+ * top1_out (DEVICE int32 [B*S]) is not NULL, the arg-max token of every
+ * position (lowest index on exact ties).  Mutates nothing else.
+ *   hidden_buf DEVICE [B,S,K*H_t] (dtype per cfg), read-only
+ *   tokens     DEVICE int32 [B,S]: the token the target emitted after position s
+ *              (the caller aligns labels; the library does not shift)
+ *   loss_mask  DEVICE uint8 [B,S]: non-zero = position contributes to the loss
+ *   workspace  DEVICE, >= tide_draft_workspace_bytes(cfg), 256-byte aligned */
+int tide_draft_forward(const tide_draft_config *cfg, const tide_draft_tensors *params,
+                       const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                       float *loss_out, int32_t *top1_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* One training step: forward, full backward, AdamW (Sec. 3.3: the draft is
+ * fine-tuned on the signals accumulated from serving).
+ *   params     in/out: updated in place (bf16 mode: re-rounded from master)
+ *   grads      out: float gradients of this batch, overwritten (not accumulated)
+ *   adam_state in/out: m, v (and master) updated; step incremented on success
+ *   lr         learning rate of this step
+ *   loss_out   DEVICE float: loss of this batch before the update
+ * Other arguments as in tide_draft_forward. */
+int tide_draft_train_step(const tide_draft_config *cfg, tide_draft_tensors *params,
+                          tide_draft_tensors *grads, tide_adam_state *adam_state,
+                          const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                          float lr, float *loss_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Message of the last error on the calling thread (static storage, never NULL). */
+const char *tide_last_error(void);
+
+/* Byte offset, inside the workspace, of a named intermediate of the last call
+ * with this config ("x0", "a", "qkv", "A", "x1", "bn", "gt", "u", "h", "x2",
+ * "yhat", "lse", "dyhat", "dx2", "dx1", "dx0", "dqkv", ...; activations have the
+ * config's dtype, "lse"/"r1"/"r2"/"r3" are float); "lm_rows" returns the number
+ * of rows per logits block instead.  -1 if the name or config is unknown.  After
+ * a training step "gt"/"u" hold their gradients.  For tests and profiling. */
+int64_t tide_draft_workspace_offset(const tide_draft_config *cfg, const char *name);
+
+/* ---- Building blocks, exported for per-kernel parity tests and profiling ----
+ * Each runs the same kernels the two calls above use.  Same conventions. */
+
+/* C[M,N] = alpha * op(A) op(B)^T-style product in the three layouts the step uses
+ * (Sec. 3.3 training: forward Y = X W^T, input gradient dX = dY W, weight
+ * gradient dW = dY^T X):
+ *   layout 0 ("NT"): C = A[M,K] * B[N,K]^T
+ *   layout 1 ("NN"): C = A[M,K] * B[K,N]
+ *   layout 2 ("TN"): C = A[K,M]^T * B[K,N]
+ * in_dtype: dtype of A and B; out_dtype: dtype of C (TIDE_DTYPE_*).  accumulate
+ * != 0 adds to C instead of overwriting.  residual (may be NULL) is a [M,N]
+ * matrix of out_dtype added to the result.  workspace may be NULL when
+ * tide_gemm_workspace_bytes returns 0 for the call. */
+size_t tide_gemm_workspace_bytes(int layout, int64_t M, int64_t N, int64_t K, int in_dtype);
+int tide_gemm(int layout, int64_t M, int64_t N, int64_t K, float alpha,
+              const void *A, const void *B, void *C, const void *residual,
+              int in_dtype, int out_dtype, int accumulate,
+              void *workspace, size_t workspace_bytes, void *stream);
+
+/* y = g * x * rsqrt(mean(x^2) + eps) over rows of x [rows, d]; rstd_out [rows] float. */
+int tide_rmsnorm_fwd(int64_t rows, int64_t d, const void *x, const void *g, float eps,
+                     void *y, float *rstd_out, int dtype, void *stream);
+/* dx = (residual_grad or 0) + rmsnorm input gradient; dg [d] float (overwritten).
+ * dg_partial: DEVICE float scratch of tide_rmsnorm_bwd_scratch_bytes(rows, d). */
+size_t tide_rmsnorm_bwd_scratch_bytes(int64_t rows, int64_t d);
+int tide_rmsnorm_bwd(int64_t rows, int64_t d, const void *dy, const void *x, const void *g,
+                     const float *rstd, const void *residual_grad, void *dx, float *dg,
+                     void *dg_partial, int dtype, void *stream);
+
+/* Causal grouped-query attention on a packed activation qkv [B*S, (n_heads+2*n_kv_heads)*head_dim]
+ * (q heads, then k heads, then v heads; RoPE already applied).  out [B*S, n_heads*head_dim];
+ * lse [B, n_heads, S] float = log-sum-exp of the scaled scores of each query row. */
+int tide_attention_fwd(int B, int S, int n_heads, int n_kv_heads, int head_dim,
+                       const void *qkv, void *out, float *lse, int dtype, void *stream);
+/* dqkv has the layout of qkv.  delta: DEVICE float scratch [B, n_heads, S]. */
+int tide_attention_bwd(int B, int S, int n_heads, int n_kv_heads, int head_dim,
+                       const void *qkv, const void *out, const void *dout, const float *lse,
+                       float *delta, void *dqkv, int dtype, void *stream);
+
+/* In-place rotate-half RoPE of the q and k heads of a packed qkv activation;
+ * inverse != 0 rotates by the negative angle (the backward pass).
+ * table: DEVICE float scratch of S*head_dim elements (cos/sin table, overwritten). */
+int tide_rope(int B, int S, int n_heads, int n_kv_heads, int head_dim, float theta,
+              void *qkv, float *table, int inverse, int dtype, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIDE_DRAFT_H */

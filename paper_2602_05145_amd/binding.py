@@ -1,0 +1,191 @@
+"""ctypes binding of libtide_draft.so: the same names as the C ABI, argument marshalling only.
+
+Every step of the draft-training path runs in the library's HIP kernels; nothing here computes.
+Importing this module fails loudly if the library has not been built (there is no fallback path).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtide_draft.so")
+
+TIDE_OK = 0
+TIDE_ERR_NULL = -1
+TIDE_ERR_CONFIG = -2
+TIDE_ERR_WORKSPACE = -3
+TIDE_ERR_HIP = -4
+TIDE_DTYPE_FP32 = 0
+TIDE_DTYPE_BF16 = 1
+LAYOUT_NT, LAYOUT_NN, LAYOUT_TN = 0, 1, 2
+
+TENSOR_NAMES = ("w_fc", "g1", "w_qkv", "w_o", "g2", "w_gate", "w_up", "w_down", "g3", "w_lm")
+
+
+class TideDraftConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "seq", "n_capture", "target_hidden", "hidden",
+                                         "n_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + \
+               [(n, C.c_float) for n in ("rope_theta", "rms_eps", "beta1", "beta2", "adam_eps",
+                                         "weight_decay")] + [("dtype", C.c_int32)]
+
+
+class TideDraftTensors(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in TENSOR_NAMES]
+
+
+class TideAdamState(C.Structure):
+    _fields_ = [("m", TideDraftTensors), ("v", TideDraftTensors), ("master", TideDraftTensors),
+                ("step", C.c_int64)]
+
+
+class TideError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"tide error {code}: {msg}")
+        self.code = code
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2602_05145_amd.build or "
+            "__graft_entry__.build()); there is no non-HIP fallback")
+    return C.CDLL(LIB_PATH)
+
+
+_lib = _load()
+_cfgp, _tp, _ap = C.POINTER(TideDraftConfig), C.POINTER(TideDraftTensors), C.POINTER(TideAdamState)
+_vp, _i64, _i32, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_float, C.c_size_t
+
+_lib.tide_last_error.restype = C.c_char_p
+_lib.tide_last_error.argtypes = []
+_lib.tide_draft_workspace_bytes.restype = _sz
+_lib.tide_draft_workspace_bytes.argtypes = [_cfgp]
+_lib.tide_draft_workspace_offset.restype = _i64
+_lib.tide_draft_workspace_offset.argtypes = [_cfgp, C.c_char_p]
+_lib.tide_draft_forward.restype = _i32
+_lib.tide_draft_forward.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.tide_draft_train_step.restype = _i32
+_lib.tide_draft_train_step.argtypes = [_cfgp, _tp, _tp, _ap, _vp, _vp, _vp, _f32, _vp, _vp, _sz, _vp]
+_lib.tide_gemm_workspace_bytes.restype = _sz
+_lib.tide_gemm_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32]
+_lib.tide_gemm.restype = _i32
+_lib.tide_gemm.argtypes = [_i32, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _sz, _vp]
+_lib.tide_rmsnorm_fwd.restype = _i32
+_lib.tide_rmsnorm_fwd.argtypes = [_i64, _i64, _vp, _vp, _f32, _vp, _vp, _i32, _vp]
+_lib.tide_rmsnorm_bwd_scratch_bytes.restype = _sz
+_lib.tide_rmsnorm_bwd_scratch_bytes.argtypes = [_i64, _i64]
+_lib.tide_rmsnorm_bwd.restype = _i32
+_lib.tide_rmsnorm_bwd.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]
+_lib.tide_attention_fwd.restype = _i32
+_lib.tide_attention_fwd.argtypes = [_i32] * 5 + [_vp, _vp, _vp, _i32, _vp]
+_lib.tide_attention_bwd.restype = _i32
+_lib.tide_attention_bwd.argtypes = [_i32] * 5 + [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]
+_lib.tide_rope.restype = _i32
+_lib.tide_rope.argtypes = [_i32] * 5 + [_f32, _vp, _vp, _i32, _i32, _vp]
+
+EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
+            "tide_draft_forward", "tide_draft_train_step", "tide_gemm_workspace_bytes", "tide_gemm",
+            "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd",
+            "tide_attention_fwd", "tide_attention_bwd", "tide_rope")
+
+
+def tide_last_error() -> str:
+    return _lib.tide_last_error().decode()
+
+
+def _check(rc):
+    if rc != TIDE_OK:
+        raise TideError(rc, tide_last_error())
+    return rc
+
+
+def make_config(cfg: dict) -> TideDraftConfig:
+    """dict (see workloads.CONFIGS) -> C struct."""
+    c = TideDraftConfig()
+    for n in ("batch", "seq", "n_capture", "target_hidden", "hidden", "n_heads", "n_kv_heads",
+              "head_dim", "ffn", "vocab"):
+        setattr(c, n, int(cfg[n]))
+    for n in ("rope_theta", "rms_eps", "beta1", "beta2", "adam_eps", "weight_decay"):
+        setattr(c, n, float(cfg[n]))
+    dt = cfg["dtype"]
+    c.dtype = {"fp32": TIDE_DTYPE_FP32, "bf16": TIDE_DTYPE_BF16}.get(dt, dt)
+    return c
+
+
+def _ptr(x):
+    """device pointer of a torch tensor / raw int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def make_tensors(d) -> TideDraftTensors:
+    """dict name -> torch tensor (or int pointer); missing names become NULL."""
+    t = TideDraftTensors()
+    for n in TENSOR_NAMES:
+        setattr(t, n, _ptr(d.get(n)) if d is not None else None)
+    return t
+
+
+def tide_draft_workspace_bytes(cfg: TideDraftConfig) -> int:
+    return int(_lib.tide_draft_workspace_bytes(C.byref(cfg)))
+
+
+def tide_draft_workspace_offset(cfg: TideDraftConfig, name: str) -> int:
+    return int(_lib.tide_draft_workspace_offset(C.byref(cfg), name.encode()))
+
+
+def tide_draft_forward(cfg, params, hidden_buf, tokens, loss_mask, loss_out, top1_out, workspace,
+                       workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_forward(C.byref(cfg) if cfg is not None else None,
+                                 C.byref(params) if params is not None else None,
+                                 _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(loss_out),
+                                 _ptr(top1_out), _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_draft_train_step(cfg, params, grads, adam_state, hidden_buf, tokens, loss_mask, lr, loss_out,
+                          workspace, workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_train_step(C.byref(cfg) if cfg is not None else None,
+                                    C.byref(params) if params is not None else None,
+                                    C.byref(grads) if grads is not None else None,
+                                    C.byref(adam_state) if adam_state is not None else None,
+                                    _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), float(lr),
+                                    _ptr(loss_out), _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_gemm(layout, M, N, K, alpha, A, B, Cmat, residual, in_dtype, out_dtype, accumulate, stream,
+              check=True):
+    rc = _lib.tide_gemm(layout, M, N, K, float(alpha), _ptr(A), _ptr(B), _ptr(Cmat), _ptr(residual),
+                        in_dtype, out_dtype, int(accumulate), None, 0, stream)
+    return _check(rc) if check else rc
+
+
+def tide_rmsnorm_fwd(rows, d, x, g, eps, y, rstd, dtype, stream):
+    return _check(_lib.tide_rmsnorm_fwd(rows, d, _ptr(x), _ptr(g), float(eps), _ptr(y), _ptr(rstd), dtype, stream))
+
+
+def tide_rmsnorm_bwd_scratch_bytes(rows, d):
+    return int(_lib.tide_rmsnorm_bwd_scratch_bytes(rows, d))
+
+
+def tide_rmsnorm_bwd(rows, d, dy, x, g, rstd, residual_grad, dx, dg, dg_partial, dtype, stream):
+    return _check(_lib.tide_rmsnorm_bwd(rows, d, _ptr(dy), _ptr(x), _ptr(g), _ptr(rstd), _ptr(residual_grad),
+                                        _ptr(dx), _ptr(dg), _ptr(dg_partial), dtype, stream))
+
+
+def tide_attention_fwd(B, S, nh, nkv, dh, qkv, out, lse, dtype, stream):
+    return _check(_lib.tide_attention_fwd(B, S, nh, nkv, dh, _ptr(qkv), _ptr(out), _ptr(lse), dtype, stream))
+
+
+def tide_attention_bwd(B, S, nh, nkv, dh, qkv, out, dout, lse, delta, dqkv, dtype, stream):
+    return _check(_lib.tide_attention_bwd(B, S, nh, nkv, dh, _ptr(qkv), _ptr(out), _ptr(dout), _ptr(lse),
+                                          _ptr(delta), _ptr(dqkv), dtype, stream))
+
+
+def tide_rope(B, S, nh, nkv, dh, theta, qkv, table, inverse, dtype, stream):
+    return _check(_lib.tide_rope(B, S, nh, nkv, dh, float(theta), _ptr(qkv), _ptr(table), int(inverse), dtype, stream))

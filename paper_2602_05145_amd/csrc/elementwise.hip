@@ -1,0 +1,580 @@
+// HBM-bound kernels of the TIDE draft-training step for gfx950: mask count, RMSNorm forward and
+// backward, RoPE, SwiGLU, cross-entropy row statistics and logit gradient, loss reduction, fused AdamW.
+// All are coalesced 16-byte-per-lane streaming kernels with 64-wide wavefront reductions; arithmetic is
+// fp32 whatever the storage type.
+#include "kernels.h"
+#include "tide_common.h"
+
+namespace tide {
+
+// ----------------------------------------------------------------------------------------------
+// N = max(1, number of positions with loss_mask != 0 and 0 <= token < V)
+// ----------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void count_valid_kernel(const int32_t* __restrict__ tokens,
+                                                           const uint8_t* __restrict__ mask, int64_t T,
+                                                           int V, float* __restrict__ scal) {
+  __shared__ float red[32];
+  float c = 0.f;
+  for (int64_t i = threadIdx.x; i < T; i += blockDim.x) {
+    int tk = tokens[i];
+    c += (mask[i] != 0 && tk >= 0 && tk < V) ? 1.f : 0.f;  // exact in fp32 up to 2^24 positions
+  }
+  float tot = block_sum(c, red);
+  if (threadIdx.x == 0) {
+    float n = fmaxf(tot, 1.f);
+    scal[0] = n;
+    scal[1] = 1.f / n;
+  }
+}
+
+hipError_t launch_count_valid(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, float* scal,
+                              hipStream_t s) {
+  hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, tokens, mask, T, V, scal);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// RMSNorm forward: one 256-thread block per row.
+// ----------------------------------------------------------------------------------------------
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ x,
+                                                          const T* __restrict__ g, float eps,
+                                                          T* __restrict__ y, float* __restrict__ rstd,
+                                                          int d) {
+  __shared__ float red[32];
+  const size_t row = blockIdx.x;
+  const T* xr = x + row * (size_t)d;
+  T* yr = y + row * (size_t)d;
+  float ss = 0.f;
+  if (VEC) {
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+      float v[8];
+      ld8(xr, c, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
+    }
+  } else {
+    for (int c = threadIdx.x; c < d; c += 256) {
+      float v = ldf(xr, c);
+      ss += v * v;
+    }
+  }
+  float tot = block_sum(ss, red);
+  float r = 1.0f / sqrtf(tot / (float)d + eps);
+  if (threadIdx.x == 0) rstd[row] = r;
+  if (VEC) {
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+      float v[8], gg[8], o[8];
+      ld8(xr, c, v);
+      ld8(g, c, gg);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] = gg[j] * v[j] * r;
+      st8(yr, c, o);
+    }
+  } else {
+    for (int c = threadIdx.x; c < d; c += 256) stf(yr, c, ldf(g, c) * ldf(xr, c) * r);
+  }
+}
+
+hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g, float eps, void* y,
+                              float* rstd, int dtype, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  dim3 grid((unsigned)rows), blk(256);
+  const bool vec = (d % 8) == 0;
+  if (dtype == kBF16) {
+    if (vec) hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)x, (const bf16_t*)g, eps, (bf16_t*)y, rstd, d);
+    else hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)x, (const bf16_t*)g, eps, (bf16_t*)y, rstd, d);
+  } else {
+    if (vec) hipLaunchKernelGGL((rmsnorm_fwd_kernel<float, true>), grid, blk, 0, s, (const float*)x, (const float*)g, eps, (float*)y, rstd, d);
+    else hipLaunchKernelGGL((rmsnorm_fwd_kernel<float, false>), grid, blk, 0, s, (const float*)x, (const float*)g, eps, (float*)y, rstd, d);
+  }
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// RMSNorm backward.  u = g*dy; dx = r*u - x*r^3*<u,x>/d (+ residual gradient);
+// dg[c] = sum_rows dy*x*r, reduced in two stages: each block owns kRowsPerBlock rows and keeps its
+// column partials in registers, then a column-sum kernel folds the per-block partials.
+// Vector path: d % 8 == 0 and d <= 8192.  Scalar path: d <= 1024.
+// ----------------------------------------------------------------------------------------------
+constexpr int kRowsPerBlock = 32;
+
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ dy,
+                                                          const T* __restrict__ x,
+                                                          const T* __restrict__ g,
+                                                          const float* __restrict__ rstd,
+                                                          const T* __restrict__ res, T* __restrict__ dx,
+                                                          float* __restrict__ dg_partial, int64_t rows,
+                                                          int d) {
+  __shared__ float red[32];
+  constexpr int NIT = 4;
+  constexpr int W = VEC ? 8 : 1;
+  float acc[NIT][W];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it)
+#pragma unroll
+    for (int j = 0; j < W; ++j) acc[it][j] = 0.f;
+
+  const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlock;
+  const int64_t r1 = min(rows, r0 + (int64_t)kRowsPerBlock);
+  const float inv_d = 1.0f / (float)d;
+  for (int64_t row = r0; row < r1; ++row) {
+    const size_t base = (size_t)row * (size_t)d;
+    const float r = rstd[row];
+    float uv[NIT][W], xv[NIT][W], dyv[NIT][W];
+    float dot = 0.f;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = (threadIdx.x + it * 256) * W;
+      if (c < d) {
+        if (VEC) {
+          float gg[8], a[8], b[8];
+          ld8(dy, base + c, a);
+          ld8(x, base + c, b);
+          ld8(g, c, gg);
+#pragma unroll
+          for (int j = 0; j < W; ++j) {
+            dyv[it][j] = a[j];
+            xv[it][j] = b[j];
+            uv[it][j] = gg[j] * a[j];
+            dot += uv[it][j] * b[j];
+          }
+        } else {
+          dyv[it][0] = ldf(dy, base + c);
+          xv[it][0] = ldf(x, base + c);
+          uv[it][0] = ldf(g, c) * dyv[it][0];
+          dot += uv[it][0] * xv[it][0];
+        }
+      }
+    }
+    const float tot = block_sum(dot, red);
+    const float coef = r * r * r * tot * inv_d;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = (threadIdx.x + it * 256) * W;
+      if (c < d) {
+        if (VEC) {
+          float o[8];
+          if (res) ld8(res, base + c, o);
+          else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = 0.f;
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            o[j] += r * uv[it][j] - xv[it][j] * coef;
+            acc[it][j] += dyv[it][j] * xv[it][j] * r;
+          }
+          st8(dx, base + c, o);
+        } else {
+          float o = res ? ldf(res, base + c) : 0.f;
+          o += r * uv[it][0] - xv[it][0] * coef;
+          acc[it][0] += dyv[it][0] * xv[it][0] * r;
+          stf(dx, base + c, o);
+        }
+      }
+    }
+  }
+  float* out = dg_partial + (size_t)blockIdx.x * (size_t)d;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int c = (threadIdx.x + it * 256) * W;
+    if (c < d) {
+#pragma unroll
+      for (int j = 0; j < W; ++j) out[c + j] = acc[it][j];
+    }
+  }
+}
+
+// out[c] = sum_r part[r, c]; 64 columns x 4 row lanes per block
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ part, int64_t nrows, int d,
+                                                     float* __restrict__ out) {
+  __shared__ float sm[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int rl = threadIdx.x >> 6;
+  float a = 0.f;
+  if (c < d)
+    for (int64_t r = rl; r < nrows; r += 4) a += part[(size_t)r * d + c];
+  sm[rl][threadIdx.x & 63] = a;
+  __syncthreads();
+  if (rl == 0 && c < d) out[c] = (sm[0][threadIdx.x] + sm[1][threadIdx.x]) + (sm[2][threadIdx.x] + sm[3][threadIdx.x]);
+}
+
+size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d) {
+  int64_t nblk = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
+  return (size_t)nblk * (size_t)d * sizeof(float);
+}
+
+hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x, const void* g,
+                              const float* rstd, const void* res, void* dx, float* dg, float* dg_partial,
+                              int dtype, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  const bool vec = (d % 8) == 0 && d <= 8192;
+  if (!vec && d > 1024) return hipErrorInvalidValue;
+  const int64_t nblk = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
+  dim3 grid((unsigned)nblk), blk(256);
+  if (dtype == kBF16) {
+    if (vec) hipLaunchKernelGGL((rmsnorm_bwd_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)g, rstd, (const bf16_t*)res, (bf16_t*)dx, dg_partial, rows, d);
+    else hipLaunchKernelGGL((rmsnorm_bwd_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)g, rstd, (const bf16_t*)res, (bf16_t*)dx, dg_partial, rows, d);
+  } else {
+    if (vec) hipLaunchKernelGGL((rmsnorm_bwd_kernel<float, true>), grid, blk, 0, s, (const float*)dy, (const float*)x, (const float*)g, rstd, (const float*)res, (float*)dx, dg_partial, rows, d);
+    else hipLaunchKernelGGL((rmsnorm_bwd_kernel<float, false>), grid, blk, 0, s, (const float*)dy, (const float*)x, (const float*)g, rstd, (const float*)res, (float*)dx, dg_partial, rows, d);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_kernel, dim3((d + 63) / 64), dim3(256), 0, s, dg_partial, nblk, d, dg);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// RoPE.  The cos/sin table is built once per call in double precision (positions reach 16384, where
+// an fp32 angle would already be off by ~1e-3 rad), then applied in place to the q and k heads.
+// ----------------------------------------------------------------------------------------------
+__global__ void rope_table_kernel(int S, int half, int dh, double theta, float* __restrict__ cs) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= S * half) return;
+  const int pos = idx / half, i = idx % half;
+  const double inv = pow(theta, -2.0 * (double)i / (double)dh);
+  const double ang = (double)pos * inv;
+  cs[2 * (size_t)idx] = (float)cos(ang);
+  cs[2 * (size_t)idx + 1] = (float)sin(ang);
+}
+
+hipError_t launch_rope_table(int S, int dh, float theta, float* cs, hipStream_t s) {
+  const int half = dh / 2;
+  const int n = S * half;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, S, half, dh, (double)theta, cs);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const float* __restrict__ cs,
+                                                   int S, int nrot_heads, int dh, int ld, float sgn,
+                                                   int64_t total) {
+  // one thread per (row t, head, i < dh/2); q heads then k heads are the first nrot_heads heads of a row
+  const int half = dh >> 1;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int i = (int)(idx % half);
+  const int64_t th = idx / half;
+  const int hd = (int)(th % nrot_heads);
+  const int64_t t = th / nrot_heads;
+  const int pos = (int)(t % S);
+  const float c = cs[2 * ((size_t)pos * half + i)];
+  const float sn = sgn * cs[2 * ((size_t)pos * half + i) + 1];
+  const size_t o = (size_t)t * ld + (size_t)hd * dh + i;
+  const float x1 = ldf(qkv, o), x2 = ldf(qkv, o + half);
+  stf(qkv, o, x1 * c - x2 * sn);
+  stf(qkv, o + half, x2 * c + x1 * sn);
+}
+
+hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, void* qkv, int inverse,
+                       int dtype, hipStream_t s) {
+  const int nrot = nh + nkv;
+  const int ld = (nh + 2 * nkv) * dh;
+  const int64_t total = (int64_t)B * S * nrot * (dh / 2);
+  if (total <= 0) return hipSuccess;
+  dim3 grid((unsigned)((total + 255) / 256)), blk(256);
+  const float sgn = inverse ? -1.f : 1.f;
+  if (dtype == kBF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total);
+  else hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// SwiGLU
+// ----------------------------------------------------------------------------------------------
+__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + __expf(-x)); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T* __restrict__ gt, const T* __restrict__ u,
+                                                         T* __restrict__ h, int64_t n) {
+  const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i0 + 8 <= n) {
+    float a[8], b[8], o[8];
+    ld8(gt, i0, a);
+    ld8(u, i0, b);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = a[j] * sigmoidf_(a[j]) * b[j];
+    st8(h, i0, o);
+  } else {
+    for (int64_t i = i0; i < n; ++i) {
+      float a = ldf(gt, i);
+      stf(h, i, a * sigmoidf_(a) * ldf(u, i));
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ dh, const T* gt, const T* u,
+                                                         T* dgt, T* du, int64_t n) {
+  // dgt/du may alias gt/u: every element is read before it is written by the same thread
+  const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i0 + 8 <= n) {
+    float a[8], b[8], c[8], o1[8], o2[8];
+    ld8(gt, i0, a);
+    ld8(u, i0, b);
+    ld8(dh, i0, c);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float sg = sigmoidf_(a[j]);
+      o1[j] = c[j] * b[j] * sg * (1.f + a[j] * (1.f - sg));
+      o2[j] = c[j] * a[j] * sg;
+    }
+    st8(dgt, i0, o1);
+    st8(du, i0, o2);
+  } else {
+    for (int64_t i = i0; i < n; ++i) {
+      float a = ldf(gt, i), b = ldf(u, i), c = ldf(dh, i);
+      float sg = sigmoidf_(a);
+      stf(dgt, i, c * b * sg * (1.f + a * (1.f - sg)));
+      stf(du, i, c * a * sg);
+    }
+  }
+}
+
+hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  dim3 grid((unsigned)((n + 2047) / 2048)), blk(256);
+  if (dtype == kBF16) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)gt, (const bf16_t*)u, (bf16_t*)h, n);
+  else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, grid, blk, 0, s, (const float*)gt, (const float*)u, (float*)h, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_bwd(int64_t n, const void* dh, const void* gt, const void* u, void* dgt, void* du,
+                             int dtype, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  dim3 grid((unsigned)((n + 2047) / 2048)), blk(256);
+  if (dtype == kBF16) hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)dh, (const bf16_t*)gt, (const bf16_t*)u, (bf16_t*)dgt, (bf16_t*)du, n);
+  else hipLaunchKernelGGL(swiglu_bwd_kernel<float>, grid, blk, 0, s, (const float*)dh, (const float*)gt, (const float*)u, (float*)dgt, (float*)du, n);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// Cross-entropy over a block of logits z [rows, ldz] (ldz % 8 == 0, rows 16-byte aligned).
+// Statistics: one block per row, online (max, sum-exp) per thread, then a block combine.
+// ----------------------------------------------------------------------------------------------
+template <typename T, bool TOP1>
+__global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ z, int64_t ldz, int V,
+                                                       const int32_t* __restrict__ tokens,
+                                                       const uint8_t* __restrict__ mask,
+                                                       float* __restrict__ lse,
+                                                       float* __restrict__ loss_rows,
+                                                       int32_t* __restrict__ top1) {
+  __shared__ float sm_m[4], sm_s[4], sm_bv[4];
+  __shared__ int sm_bi[4];
+  const size_t row = blockIdx.x;
+  const T* zr = z + row * (size_t)ldz;
+  float m = -INFINITY, ssum = 0.f;
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int c = threadIdx.x * 8; c < V; c += 256 * 8) {
+    float v[8];
+    if (c + 8 <= V) {
+      ld8(zr, c, v);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = (c + j < V) ? ldf(zr, c + j) : -INFINITY;
+    }
+    float cm = v[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) cm = fmaxf(cm, v[j]);
+    if (TOP1) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (v[j] > bv) { bv = v[j]; bi = c + j; }  // ascending c: first maximum is kept
+    }
+    const float nm = fmaxf(m, cm);
+    float part = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part += __expf(v[j] - nm);
+    ssum = ssum * __expf(m - nm) + part;
+    m = nm;
+  }
+  // wave combine
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float om = __shfl_xor(m, o, 64), os = __shfl_xor(ssum, o, 64);
+    float nm = fmaxf(m, om);
+    float sa = (m == -INFINITY) ? 0.f : ssum * __expf(m - nm);
+    float sb = (om == -INFINITY) ? 0.f : os * __expf(om - nm);
+    ssum = sa + sb;
+    m = nm;
+    if (TOP1) {
+      float obv = __shfl_xor(bv, o, 64);
+      int obi = __shfl_xor(bi, o, 64);
+      if (obv > bv || (obv == bv && obi < bi)) { bv = obv; bi = obi; }
+    }
+  }
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    sm_m[w] = m; sm_s[w] = ssum; sm_bv[w] = bv; sm_bi[w] = bi;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float M = sm_m[0], Sx = sm_s[0], BV = sm_bv[0];
+    int BI = sm_bi[0];
+    for (int i = 1; i < 4; ++i) {
+      float om = sm_m[i], os = sm_s[i];
+      float nm = fmaxf(M, om);
+      float sa = (M == -INFINITY) ? 0.f : Sx * __expf(M - nm);
+      float sb = (om == -INFINITY) ? 0.f : os * __expf(om - nm);
+      Sx = sa + sb;
+      M = nm;
+      if (sm_bv[i] > BV || (sm_bv[i] == BV && sm_bi[i] < BI)) { BV = sm_bv[i]; BI = sm_bi[i]; }
+    }
+    const float l = M + logf(Sx);
+    lse[row] = l;
+    const int tk = tokens[row];
+    const bool keep = mask[row] != 0 && tk >= 0 && tk < V;
+    loss_rows[row] = keep ? (l - ldf(zr, (size_t)tk)) : 0.f;
+    if (TOP1) top1[row] = BI;
+  }
+}
+
+hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, const int32_t* tokens,
+                           const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1, int dtype,
+                           hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  dim3 grid((unsigned)rows), blk(256);
+  if (dtype == kBF16) {
+    if (top1) hipLaunchKernelGGL((ce_stats_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
+    else hipLaunchKernelGGL((ce_stats_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
+  } else {
+    if (top1) hipLaunchKernelGGL((ce_stats_kernel<float, true>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
+    else hipLaunchKernelGGL((ce_stats_kernel<float, false>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
+  }
+  return hipGetLastError();
+}
+
+// dz = keep * (exp(z - lse) - onehot); grid (ceil(V / 2048), rows).  Columns in [V, ldz) are zeroed so
+// the padded tail never contributes to the products that read dz with K = V rounded up.
+template <typename T>
+__global__ __launch_bounds__(256) void ce_dz_kernel(T* __restrict__ z, int64_t ldz, int V,
+                                                    const int32_t* __restrict__ tokens,
+                                                    const uint8_t* __restrict__ mask,
+                                                    const float* __restrict__ lse) {
+  const size_t row = blockIdx.y;
+  const int c = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (c >= ldz) return;
+  T* zr = z + row * (size_t)ldz;
+  const int tk = tokens[row];
+  const bool keep = mask[row] != 0 && tk >= 0 && tk < V;
+  const float l = lse[row];
+  float v[8], o[8];
+  ld8(zr, c, v);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    float p = __expf(v[j] - l) - ((c + j == tk) ? 1.f : 0.f);
+    o[j] = (keep && (c + j < V)) ? p : 0.f;
+  }
+  st8(zr, c, o);
+}
+
+hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t* tokens,
+                        const uint8_t* mask, const float* lse, int dtype, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (ldz % 8 != 0) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((ldz + 2047) / 2048), (unsigned)rows), blk(256);
+  if (dtype == kBF16) hipLaunchKernelGGL(ce_dz_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)z, ldz, V, tokens, mask, lse);
+  else hipLaunchKernelGGL(ce_dz_kernel<float>, grid, blk, 0, s, (float*)z, ldz, V, tokens, mask, lse);
+  return hipGetLastError();
+}
+
+// loss = (1/N) * sum_t loss_rows[t]   (single block, fixed summation order: deterministic)
+__global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restrict__ loss_rows, int64_t T,
+                                                           const float* __restrict__ scal,
+                                                           float* __restrict__ loss_out) {
+  __shared__ float red[32];
+  float a = 0.f;
+  for (int64_t i = threadIdx.x; i < T; i += 1024) a += loss_rows[i];
+  float tot = block_sum(a, red);
+  if (threadIdx.x == 0) *loss_out = tot * scal[1];
+}
+
+hipError_t launch_loss_reduce(int64_t T, const float* loss_rows, const float* scal, float* loss_out,
+                              hipStream_t s) {
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, T, scal, loss_out);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// Fused multi-tensor AdamW.  One launch covers all tensors: block b works on 2048 consecutive
+// elements of the tensor its index falls in.  m, v and (bf16 mode) the master weights are fp32; the
+// bf16 parameters are re-rounded from the master copy.  The caller passes 1/(1-beta1^t) and
+// 1/sqrt(1-beta2^t) computed in double on the host.
+// ----------------------------------------------------------------------------------------------
+struct AdamDev {
+  AdamTensor t[10];
+  int64_t blk_start[11];
+  int nt;
+  float lr, beta1, beta2, eps, decay, inv_bc1, inv_sqrt_bc2;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void adamw_kernel(AdamDev a) {
+  int ti = 0;
+  const int64_t b = blockIdx.x;
+#pragma unroll
+  for (int i = 1; i < 10; ++i)
+    if (i < a.nt && b >= a.blk_start[i]) ti = i;
+  const AdamTensor t = a.t[ti];
+  const int64_t i0 = ((b - a.blk_start[ti]) * 256 + threadIdx.x) * 8;
+  if (i0 >= t.n) return;
+  T* p = (T*)t.p;
+  float* w = (sizeof(T) == 2) ? t.master : (float*)t.p;
+  const float omb1 = 1.f - a.beta1, omb2 = 1.f - a.beta2;
+  if (i0 + 8 <= t.n) {
+    float g[8], m[8], v[8], th[8];
+    ld8(t.g, i0, g);
+    ld8((const float*)t.m, i0, m);
+    ld8((const float*)t.v, i0, v);
+    ld8((const float*)w, i0, th);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      m[j] = a.beta1 * m[j] + omb1 * g[j];
+      v[j] = a.beta2 * v[j] + omb2 * g[j] * g[j];
+      const float denom = sqrtf(v[j]) * a.inv_sqrt_bc2 + a.eps;
+      th[j] = th[j] * a.decay - a.lr * (m[j] * a.inv_bc1) / denom;
+    }
+    st8(t.m, i0, m);
+    st8(t.v, i0, v);
+    st8(w, i0, th);
+    if (sizeof(T) == 2) st8(p, i0, th);
+  } else {
+    for (int64_t i = i0; i < t.n; ++i) {
+      const float g = t.g[i];
+      const float m = a.beta1 * t.m[i] + omb1 * g;
+      const float v = a.beta2 * t.v[i] + omb2 * g * g;
+      const float denom = sqrtf(v) * a.inv_sqrt_bc2 + a.eps;
+      const float th = w[i] * a.decay - a.lr * (m * a.inv_bc1) / denom;
+      t.m[i] = m;
+      t.v[i] = v;
+      w[i] = th;
+      if (sizeof(T) == 2) stf(p, i, th);
+    }
+  }
+}
+
+hipError_t launch_adamw(const AdamArgs& a, hipStream_t s) {
+  AdamDev d;
+  d.nt = a.nt;
+  int64_t nb = 0;
+  for (int i = 0; i < a.nt; ++i) {
+    d.t[i] = a.t[i];
+    d.blk_start[i] = nb;
+    nb += (a.t[i].n + 2047) / 2048;
+  }
+  for (int i = a.nt; i < 10; ++i) d.t[i] = AdamTensor{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  for (int i = a.nt; i <= 10; ++i) d.blk_start[i] = nb;
+  d.lr = a.lr; d.beta1 = a.beta1; d.beta2 = a.beta2; d.eps = a.eps;
+  d.decay = 1.0f - a.lr * a.wd;
+  d.inv_bc1 = a.inv_bc1; d.inv_sqrt_bc2 = a.inv_sqrt_bc2;
+  if (nb <= 0) return hipSuccess;
+  if (a.dtype == kBF16) hipLaunchKernelGGL(adamw_kernel<bf16_t>, dim3((unsigned)nb), dim3(256), 0, s, d);
+  else hipLaunchKernelGGL(adamw_kernel<float>, dim3((unsigned)nb), dim3(256), 0, s, d);
+  return hipGetLastError();
+}
+
+}  // namespace tide

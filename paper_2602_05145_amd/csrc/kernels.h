@@ -1,0 +1,87 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tide {
+
+enum : int { kF32 = 0, kBF16 = 1 };
+enum : int { kNT = 0, kNN = 1, kTN = 2 };
+
+inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
+
+// ---- gemm_mfma.hip / gemm_simple.hip ---------------------------------------------------------
+// C[M,N] (ldc) = alpha * sum over operand pairs of op(A) op(B)  (+ residual) (+ C if accumulate)
+// layout NT: A[M,K] lda, B[N,K] ldb.  NN: A[M,K], B[K,N].  TN: A[K,M], B[K,N].
+// A second operand pair (A2,B2,K2; same layout and leading dims) extends the contraction.
+struct GemmArgs {
+  int layout;
+  int64_t M, N, K;
+  const void* A; int64_t lda;
+  const void* B; int64_t ldb;
+  const void* A2; const void* B2; int64_t K2;
+  void* C; int64_t ldc;
+  const void* residual; int64_t ldr;
+  float alpha;
+  const float* alpha_dev;   // optional device scalar multiplied into alpha
+  int in_dtype, out_dtype;
+  int accumulate;
+};
+bool gemm_mfma_supported(const GemmArgs& a);
+hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);
+hipError_t launch_gemm_simple(const GemmArgs& a, hipStream_t s);
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);  // picks the MFMA path when supported
+
+// ---- elementwise.hip ------------------------------------------------------------------------
+// scal[0] = N = max(1, #kept), scal[1] = 1/N
+hipError_t launch_count_valid(const int32_t* tokens, const uint8_t* mask, int64_t T, int V,
+                              float* scal, hipStream_t s);
+hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g, float eps, void* y,
+                              float* rstd, int dtype, hipStream_t s);
+size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d);
+hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x, const void* g,
+                              const float* rstd, const void* res, void* dx, float* dg,
+                              float* dg_partial, int dtype, hipStream_t s);
+hipError_t launch_rope_table(int S, int dh, float theta, float* cs, hipStream_t s);  // cs [S, dh/2, 2]
+hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, void* qkv, int inverse,
+                       int dtype, hipStream_t s);
+hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, hipStream_t s);
+hipError_t launch_swiglu_bwd(int64_t n, const void* dh, const void* gt, const void* u, void* dgt,
+                             void* du, int dtype, hipStream_t s);
+// z [rows, ldz]: per-row log-sum-exp, loss term keep*(lse - z[label]) and optional arg-max
+hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, const int32_t* tokens,
+                           const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1, int dtype,
+                           hipStream_t s);
+// dz = keep * (exp(z - lse) - onehot(label)), written over z (unscaled by 1/N)
+hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t* tokens,
+                        const uint8_t* mask, const float* lse, int dtype, hipStream_t s);
+hipError_t launch_loss_reduce(int64_t T, const float* loss_rows, const float* scal, float* loss_out,
+                              hipStream_t s);
+
+struct AdamTensor { void* p; const float* g; float* m; float* v; float* master; int64_t n; };
+struct AdamArgs {
+  AdamTensor t[10];
+  int nt;
+  float lr, beta1, beta2, eps, wd, inv_bc1, inv_sqrt_bc2;
+  int dtype;
+};
+hipError_t launch_adamw(const AdamArgs& a, hipStream_t s);
+
+// ---- attention_simple.hip / attention_mfma.hip ----------------------------------------------
+struct AttnArgs {
+  int B, S, nh, nkv, dh;
+  const void* qkv; void* out; float* lse;           // forward
+  const void* dout; float* delta; void* dqkv;       // backward
+  int dtype;
+};
+bool attn_mfma_supported(const AttnArgs& a);
+hipError_t launch_attn_delta(const AttnArgs& a, hipStream_t s);  // delta = rowsum(dO * O)
+hipError_t launch_attn_fwd_simple(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_bwd_simple(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
+
+}  // namespace tide

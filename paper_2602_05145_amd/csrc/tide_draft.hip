@@ -1,0 +1,455 @@
+// C ABI of the TIDE draft-training step (see include/tide_draft.h): argument validation, workspace
+// carving and the order in which the gfx950 kernels are enqueued.  Host code only; every arithmetic
+// step runs in the kernels of this directory.
+#include "../../include/tide_draft.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "kernels.h"
+
+using namespace tide;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(TIDE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define TIDE_HIP(call, what)                          \
+  do {                                                \
+    hipError_t e__ = (call);                          \
+    if (e__ != hipSuccess) return hip_fail(e__, what); \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool check_config(const tide_draft_config* c) {
+  if (!c) { fail(TIDE_ERR_NULL, "config is NULL"); return false; }
+  if (c->batch <= 0 || c->seq <= 0 || c->n_capture <= 0 || c->target_hidden <= 0 || c->hidden <= 0 ||
+      c->n_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->ffn <= 0 || c->vocab <= 0) {
+    fail(TIDE_ERR_CONFIG, "all sizes must be positive");
+    return false;
+  }
+  if (c->dtype != TIDE_DTYPE_FP32 && c->dtype != TIDE_DTYPE_BF16) { fail(TIDE_ERR_CONFIG, "dtype must be TIDE_DTYPE_FP32 or TIDE_DTYPE_BF16"); return false; }
+  if (c->n_heads % c->n_kv_heads) { fail(TIDE_ERR_CONFIG, "n_heads (%d) must be a multiple of n_kv_heads (%d)", c->n_heads, c->n_kv_heads); return false; }
+  if ((int64_t)c->n_heads * c->head_dim != c->hidden) { fail(TIDE_ERR_CONFIG, "hidden (%d) must equal n_heads*head_dim (%d*%d)", c->hidden, c->n_heads, c->head_dim); return false; }
+  if (c->head_dim % 2) { fail(TIDE_ERR_CONFIG, "head_dim must be even"); return false; }
+  if (c->head_dim > 256) { fail(TIDE_ERR_CONFIG, "head_dim must be <= 256"); return false; }
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) { fail(TIDE_ERR_CONFIG, "rms_eps and rope_theta must be > 0"); return false; }
+  if (!(c->beta1 >= 0.f && c->beta1 < 1.f && c->beta2 >= 0.f && c->beta2 < 1.f) || !(c->adam_eps >= 0.f) || !(c->weight_decay >= 0.f)) { fail(TIDE_ERR_CONFIG, "invalid AdamW constants"); return false; }
+  const bool norm_ok = (c->hidden % 8 == 0 && c->hidden <= 8192) || c->hidden <= 1024;
+  if (!norm_ok) { fail(TIDE_ERR_CONFIG, "hidden must be <= 1024, or a multiple of 8 that is <= 8192"); return false; }
+  const int64_t T = (int64_t)c->batch * c->seq;
+  if (T > ((int64_t)1 << 22) || c->batch > 65535) { fail(TIDE_ERR_CONFIG, "batch*seq must be <= 2^22 and batch <= 65535"); return false; }
+  const int64_t lim = (int64_t)1 << 21;
+  if (c->vocab >= lim || c->ffn >= lim || (int64_t)c->n_capture * c->target_hidden >= lim) { fail(TIDE_ERR_CONFIG, "vocab, ffn and n_capture*target_hidden must be < 2^21"); return false; }
+  return true;
+}
+
+// ---- workspace plan ----------------------------------------------------------------------------
+struct Plan {
+  int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows;
+  size_t es;  // activation element size
+  // offsets (bytes)
+  size_t scal, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, z;
+  size_t fwd_end;
+  size_t dyhat, dx2, dx1, dx0, dh, dbn, dA, dqkv, da, delta, dg_partial;
+  size_t total;
+};
+
+struct Bump {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  }
+};
+
+Plan make_plan(const tide_draft_config* c) {
+  Plan p;
+  p.T = (int64_t)c->batch * c->seq;
+  p.KH = (int64_t)c->n_capture * c->target_hidden;
+  p.d = c->hidden;
+  p.nq = (int64_t)c->n_heads * c->head_dim;
+  p.nk = (int64_t)c->n_kv_heads * c->head_dim;
+  p.nqkv = p.nq + 2 * p.nk;
+  p.F = c->ffn;
+  p.V = c->vocab;
+  p.ldz = (int64_t)align_up((size_t)p.V, 64);
+  p.es = c->dtype == TIDE_DTYPE_BF16 ? 2 : 4;
+  // The logits exist only for a block of rows at a time: a quarter of the batch, at most 8192 rows.
+  int64_t rows = (int64_t)align_up((size_t)((p.T + 3) / 4), 64);
+  if (rows > 8192) rows = 8192;
+  while (rows > 256 && (size_t)rows * p.ldz * p.es > ((size_t)3 << 30)) rows /= 2;
+  if (rows > p.T) rows = p.T;
+  p.lm_rows = rows;
+  const size_t T = (size_t)p.T, es = p.es;
+  Bump b;
+  p.scal = b.take(64);
+  p.rope_cs = b.take((size_t)c->seq * c->head_dim * sizeof(float));
+  p.x0 = b.take(T * p.d * es);
+  p.r1 = b.take(T * 4);
+  p.a = b.take(T * p.d * es);
+  p.qkv = b.take(T * p.nqkv * es);
+  p.attn_lse = b.take((size_t)c->batch * c->n_heads * c->seq * 4);
+  p.A = b.take(T * p.nq * es);
+  p.x1 = b.take(T * p.d * es);
+  p.r2 = b.take(T * 4);
+  p.bn = b.take(T * p.d * es);
+  p.gt = b.take(T * p.F * es);
+  p.u = b.take(T * p.F * es);
+  p.h = b.take(T * p.F * es);
+  p.x2 = b.take(T * p.d * es);
+  p.r3 = b.take(T * 4);
+  p.yhat = b.take(T * p.d * es);
+  p.lse = b.take(T * 4);
+  p.loss_rows = b.take(T * 4);
+  p.z = b.take((size_t)p.lm_rows * p.ldz * es);
+  p.fwd_end = b.off;
+  p.dyhat = b.take(T * p.d * es);
+  p.dx2 = b.take(T * p.d * es);
+  p.dx1 = b.take(T * p.d * es);
+  p.dx0 = b.take(T * p.d * es);
+  p.dh = b.take(T * p.F * es);
+  p.dbn = b.take(T * p.d * es);
+  p.dA = b.take(T * p.nq * es);
+  p.dqkv = b.take(T * p.nqkv * es);
+  p.da = b.take(T * p.d * es);
+  p.delta = b.take((size_t)c->batch * c->n_heads * c->seq * 4);
+  p.dg_partial = b.take(rmsnorm_bwd_scratch_bytes(p.T, (int)p.d));
+  p.total = b.off;
+  return p;
+}
+
+bool tensors_ok(const tide_draft_tensors* t, const char* what) {
+  if (!t) { fail(TIDE_ERR_NULL, "%s is NULL", what); return false; }
+  const void* ptrs[10] = {t->w_fc, t->g1, t->w_qkv, t->w_o, t->g2, t->w_gate, t->w_up, t->w_down, t->g3, t->w_lm};
+  for (int i = 0; i < 10; ++i)
+    if (!ptrs[i]) { fail(TIDE_ERR_NULL, "%s has a NULL tensor (index %d)", what, i); return false; }
+  return true;
+}
+
+int check_common(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
+                 const int32_t* tokens, const uint8_t* loss_mask, float* loss_out, void* workspace,
+                 size_t workspace_bytes, const Plan& p) {
+  if (!tensors_ok(params, "params")) return TIDE_ERR_NULL;
+  if (!hidden_buf || !tokens || !loss_mask || !loss_out) return fail(TIDE_ERR_NULL, "hidden_buf, tokens, loss_mask and loss_out must not be NULL");
+  if (!workspace) return fail(TIDE_ERR_NULL, "workspace is NULL");
+  if (((uintptr_t)workspace & 255) != 0) return fail(TIDE_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < p.total) return fail(TIDE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, p.total);
+  (void)cfg;
+  return TIDE_OK;
+}
+
+GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                   int64_t ldb, void* C, int64_t ldc, int in_dt, int out_dt) {
+  GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.layout = layout; g.M = M; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+  g.alpha = 1.0f; g.in_dtype = in_dt; g.out_dtype = out_dt;
+  return g;
+}
+
+// Forward pass up to the final RMSNorm (everything except the LM head).
+int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const void* hidden_buf,
+                  const int32_t* tokens, const uint8_t* mask, char* ws, const Plan& p, hipStream_t s) {
+  const int dt = c->dtype;
+  const int64_t T = p.T;
+  float* scal = (float*)(ws + p.scal);
+  TIDE_HIP(launch_count_valid(tokens, mask, T, c->vocab, scal, s), "count_valid");
+  // x0 = Hcat W_fc^T
+  TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.x0, p.d, dt, dt), s), "gemm fc");
+  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x0, P->g1, c->rms_eps, ws + p.a, (float*)(ws + p.r1), dt, s), "rmsnorm1");
+  TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.nqkv, p.d, ws + p.a, p.d, P->w_qkv, p.d, ws + p.qkv, p.nqkv, dt, dt), s), "gemm qkv");
+  TIDE_HIP(launch_rope_table(c->seq, c->head_dim, c->rope_theta, (float*)(ws + p.rope_cs), s), "rope table");
+  TIDE_HIP(launch_rope(c->batch, c->seq, c->n_heads, c->n_kv_heads, c->head_dim, (const float*)(ws + p.rope_cs), ws + p.qkv, 0, dt, s), "rope");
+  AttnArgs at;
+  std::memset(&at, 0, sizeof(at));
+  at.B = c->batch; at.S = c->seq; at.nh = c->n_heads; at.nkv = c->n_kv_heads; at.dh = c->head_dim;
+  at.qkv = ws + p.qkv; at.out = ws + p.A; at.lse = (float*)(ws + p.attn_lse); at.dtype = dt;
+  TIDE_HIP(launch_attn_fwd(at, s), "attention fwd");
+  // x1 = x0 + A W_o^T
+  {
+    GemmArgs g = gemm_args(kNT, T, p.d, p.nq, ws + p.A, p.nq, P->w_o, p.nq, ws + p.x1, p.d, dt, dt);
+    g.residual = ws + p.x0; g.ldr = p.d;
+    TIDE_HIP(launch_gemm(g, s), "gemm o");
+  }
+  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x1, P->g2, c->rms_eps, ws + p.bn, (float*)(ws + p.r2), dt, s), "rmsnorm2");
+  TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.F, p.d, ws + p.bn, p.d, P->w_gate, p.d, ws + p.gt, p.F, dt, dt), s), "gemm gate");
+  TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.F, p.d, ws + p.bn, p.d, P->w_up, p.d, ws + p.u, p.F, dt, dt), s), "gemm up");
+  TIDE_HIP(launch_swiglu_fwd(T * p.F, ws + p.gt, ws + p.u, ws + p.h, dt, s), "swiglu");
+  {
+    GemmArgs g = gemm_args(kNT, T, p.d, p.F, ws + p.h, p.F, P->w_down, p.F, ws + p.x2, p.d, dt, dt);
+    g.residual = ws + p.x1; g.ldr = p.d;
+    TIDE_HIP(launch_gemm(g, s), "gemm down");
+  }
+  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x2, P->g3, c->rms_eps, ws + p.yhat, (float*)(ws + p.r3), dt, s), "rmsnorm3");
+  return TIDE_OK;
+}
+
+// LM head by row blocks: logits of one block, row statistics, and (training) the logit gradient and the
+// two products that consume it.  The full [T,V] logits never exist.
+int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tide_draft_tensors* G,
+                    const int32_t* tokens, const uint8_t* mask, int32_t* top1, char* ws, const Plan& p,
+                    bool train, hipStream_t s) {
+  const int dt = c->dtype;
+  float* scal = (float*)(ws + p.scal);
+  float* lse = (float*)(ws + p.lse);
+  float* loss_rows = (float*)(ws + p.loss_rows);
+  char* yhat = ws + p.yhat;
+  char* z = ws + p.z;
+  int blk = 0;
+  for (int64_t r0 = 0; r0 < p.T; r0 += p.lm_rows, ++blk) {
+    const int64_t rows = (p.T - r0 < p.lm_rows) ? (p.T - r0) : p.lm_rows;
+    const char* yb = yhat + (size_t)r0 * p.d * p.es;
+    TIDE_HIP(launch_gemm(gemm_args(kNT, rows, p.V, p.d, yb, p.d, P->w_lm, p.d, z, p.ldz, dt, dt), s), "gemm lm_head");
+    TIDE_HIP(launch_ce_stats(rows, (int)p.V, z, p.ldz, tokens + r0, mask + r0, lse + r0, loss_rows + r0, top1 ? top1 + r0 : nullptr, dt, s), "ce stats");
+    if (!train) continue;
+    TIDE_HIP(launch_ce_dz(rows, (int)p.V, z, p.ldz, tokens + r0, mask + r0, lse + r0, dt, s), "ce dz");
+    {
+      // dyhat = (1/N) dZ W_lm
+      GemmArgs g = gemm_args(kNN, rows, p.d, p.V, z, p.ldz, P->w_lm, p.d, ws + p.dyhat + (size_t)r0 * p.d * p.es, p.d, dt, dt);
+      g.alpha_dev = scal + 1;
+      TIDE_HIP(launch_gemm(g, s), "gemm dyhat");
+    }
+    {
+      // dW_lm (+)= (1/N) dZ^T yhat
+      GemmArgs g = gemm_args(kTN, p.V, p.d, rows, z, p.ldz, yb, p.d, G->w_lm, p.d, dt, kF32);
+      g.alpha_dev = scal + 1;
+      g.accumulate = blk > 0;
+      TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
+    }
+  }
+  return TIDE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tide_last_error(void) { return g_err; }
+
+size_t tide_draft_workspace_bytes(const tide_draft_config* cfg) {
+  if (!check_config(cfg)) return 0;
+  return make_plan(cfg).total;
+}
+
+// Byte offset of a named intermediate inside the workspace (for tests and profiling); -1 if unknown.
+int64_t tide_draft_workspace_offset(const tide_draft_config* cfg, const char* name) {
+  if (!check_config(cfg) || !name) return -1;
+  const Plan p = make_plan(cfg);
+  struct { const char* n; size_t o; } tab[] = {
+      {"scal", p.scal}, {"x0", p.x0}, {"r1", p.r1}, {"a", p.a}, {"qkv", p.qkv}, {"attn_lse", p.attn_lse},
+      {"A", p.A}, {"x1", p.x1}, {"r2", p.r2}, {"bn", p.bn}, {"gt", p.gt}, {"u", p.u}, {"h", p.h},
+      {"x2", p.x2}, {"r3", p.r3}, {"yhat", p.yhat}, {"lse", p.lse}, {"loss_rows", p.loss_rows}, {"z", p.z},
+      {"dyhat", p.dyhat}, {"dx2", p.dx2}, {"dx1", p.dx1}, {"dx0", p.dx0}, {"dh", p.dh}, {"dbn", p.dbn},
+      {"dA", p.dA}, {"dqkv", p.dqkv}, {"da", p.da}};
+  for (auto& e : tab)
+    if (std::strcmp(e.n, name) == 0) return (int64_t)e.o;
+  if (std::strcmp(name, "lm_rows") == 0) return p.lm_rows;
+  return -1;
+}
+
+int tide_draft_forward(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
+                       const int32_t* tokens, const uint8_t* loss_mask, float* loss_out, int32_t* top1_out,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const Plan p = make_plan(cfg);
+  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, ws, p, s);
+  if (rc) return rc;
+  rc = enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, top1_out, ws, p, false, s);
+  if (rc) return rc;
+  TIDE_HIP(launch_loss_reduce(p.T, (const float*)(ws + p.loss_rows), (const float*)(ws + p.scal), loss_out, s), "loss reduce");
+  return TIDE_OK;
+}
+
+int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                          tide_adam_state* st, const void* hidden_buf, const int32_t* tokens,
+                          const uint8_t* loss_mask, float lr, float* loss_out, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const Plan p = make_plan(cfg);
+  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
+  if (rc) return rc;
+  if (!tensors_ok(grads, "grads")) return TIDE_ERR_NULL;
+  if (!st) return fail(TIDE_ERR_NULL, "adam_state is NULL");
+  if (!tensors_ok(&st->m, "adam_state.m") || !tensors_ok(&st->v, "adam_state.v")) return TIDE_ERR_NULL;
+  const int dt = cfg->dtype;
+  if (dt == TIDE_DTYPE_BF16 && !tensors_ok(&st->master, "adam_state.master")) return TIDE_ERR_NULL;
+  if (st->step < 0) return fail(TIDE_ERR_CONFIG, "adam_state.step must be >= 0");
+  if (!(lr >= 0.f)) return fail(TIDE_ERR_CONFIG, "lr must be >= 0");
+
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  const tide_draft_tensors* P = params;
+  tide_draft_tensors* G = grads;
+  const int64_t T = p.T;
+
+  rc = enqueue_trunk(cfg, P, hidden_buf, tokens, loss_mask, ws, p, s);
+  if (rc) return rc;
+  rc = enqueue_lm_head(cfg, P, G, tokens, loss_mask, nullptr, ws, p, true, s);
+  if (rc) return rc;
+  TIDE_HIP(launch_loss_reduce(T, (const float*)(ws + p.loss_rows), (const float*)(ws + p.scal), loss_out, s), "loss reduce");
+
+  float* dgp = (float*)(ws + p.dg_partial);
+  // final norm
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dyhat, ws + p.x2, P->g3, (const float*)(ws + p.r3), nullptr, ws + p.dx2, (float*)G->g3, dgp, dt, s), "rmsnorm3 bwd");
+  // x2 = x1 + h W_down^T
+  TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.F, p.d, ws + p.dx2, p.d, P->w_down, p.F, ws + p.dh, p.F, dt, dt), s), "gemm dh");
+  TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.F, T, ws + p.dx2, p.d, ws + p.h, p.F, G->w_down, p.F, dt, kF32), s), "gemm dW_down");
+  TIDE_HIP(launch_swiglu_bwd(T * p.F, ws + p.dh, ws + p.gt, ws + p.u, ws + p.gt, ws + p.u, dt, s), "swiglu bwd");
+  {
+    // d bn = dGate W_gate + dUp W_up: one contraction over both operand pairs
+    GemmArgs g = gemm_args(kNN, T, p.d, p.F, ws + p.gt, p.F, P->w_gate, p.d, ws + p.dbn, p.d, dt, dt);
+    g.A2 = ws + p.u; g.B2 = P->w_up; g.K2 = p.F;
+    TIDE_HIP(launch_gemm(g, s), "gemm dbn");
+  }
+  TIDE_HIP(launch_gemm(gemm_args(kTN, p.F, p.d, T, ws + p.gt, p.F, ws + p.bn, p.d, G->w_gate, p.d, dt, kF32), s), "gemm dW_gate");
+  TIDE_HIP(launch_gemm(gemm_args(kTN, p.F, p.d, T, ws + p.u, p.F, ws + p.bn, p.d, G->w_up, p.d, dt, kF32), s), "gemm dW_up");
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dbn, ws + p.x1, P->g2, (const float*)(ws + p.r2), ws + p.dx2, ws + p.dx1, (float*)G->g2, dgp, dt, s), "rmsnorm2 bwd");
+  // x1 = x0 + A W_o^T
+  TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.nq, p.d, ws + p.dx1, p.d, P->w_o, p.nq, ws + p.dA, p.nq, dt, dt), s), "gemm dA");
+  TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.nq, T, ws + p.dx1, p.d, ws + p.A, p.nq, G->w_o, p.nq, dt, kF32), s), "gemm dW_o");
+  {
+    AttnArgs at;
+    std::memset(&at, 0, sizeof(at));
+    at.B = cfg->batch; at.S = cfg->seq; at.nh = cfg->n_heads; at.nkv = cfg->n_kv_heads; at.dh = cfg->head_dim;
+    at.qkv = ws + p.qkv; at.out = ws + p.A; at.lse = (float*)(ws + p.attn_lse);
+    at.dout = ws + p.dA; at.delta = (float*)(ws + p.delta); at.dqkv = ws + p.dqkv; at.dtype = dt;
+    TIDE_HIP(launch_attn_bwd(at, s), "attention bwd");
+  }
+  TIDE_HIP(launch_rope(cfg->batch, cfg->seq, cfg->n_heads, cfg->n_kv_heads, cfg->head_dim, (const float*)(ws + p.rope_cs), ws + p.dqkv, 1, dt, s), "rope bwd");
+  TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.nqkv, ws + p.dqkv, p.nqkv, P->w_qkv, p.d, ws + p.da, p.d, dt, dt), s), "gemm da");
+  TIDE_HIP(launch_gemm(gemm_args(kTN, p.nqkv, p.d, T, ws + p.dqkv, p.nqkv, ws + p.a, p.d, G->w_qkv, p.d, dt, kF32), s), "gemm dW_qkv");
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.da, ws + p.x0, P->g1, (const float*)(ws + p.r1), ws + p.dx1, ws + p.dx0, (float*)G->g1, dgp, dt, s), "rmsnorm1 bwd");
+  // x0 = Hcat W_fc^T: weight gradient only, the captured states are data
+  TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.KH, T, ws + p.dx0, p.d, hidden_buf, p.KH, G->w_fc, p.KH, dt, kF32), s), "gemm dW_fc");
+
+  // AdamW over all ten tensors in one launch
+  {
+    AdamArgs a;
+    std::memset(&a, 0, sizeof(a));
+    void* pp[10] = {params->w_fc, params->g1, params->w_qkv, params->w_o, params->g2, params->w_gate, params->w_up, params->w_down, params->g3, params->w_lm};
+    void* gg[10] = {G->w_fc, G->g1, G->w_qkv, G->w_o, G->g2, G->w_gate, G->w_up, G->w_down, G->g3, G->w_lm};
+    void* mm[10] = {st->m.w_fc, st->m.g1, st->m.w_qkv, st->m.w_o, st->m.g2, st->m.w_gate, st->m.w_up, st->m.w_down, st->m.g3, st->m.w_lm};
+    void* vv[10] = {st->v.w_fc, st->v.g1, st->v.w_qkv, st->v.w_o, st->v.g2, st->v.w_gate, st->v.w_up, st->v.w_down, st->v.g3, st->v.w_lm};
+    void* ms[10] = {st->master.w_fc, st->master.g1, st->master.w_qkv, st->master.w_o, st->master.g2, st->master.w_gate, st->master.w_up, st->master.w_down, st->master.g3, st->master.w_lm};
+    const int64_t nn[10] = {p.d * p.KH, p.d, p.nqkv * p.d, p.d * p.nq, p.d, p.F * p.d, p.F * p.d, p.d * p.F, p.d, p.V * p.d};
+    for (int i = 0; i < 10; ++i) a.t[i] = AdamTensor{pp[i], (const float*)gg[i], (float*)mm[i], (float*)vv[i], dt == TIDE_DTYPE_BF16 ? (float*)ms[i] : nullptr, nn[i]};
+    a.nt = 10;
+    const double t = (double)(st->step + 1);
+    a.lr = lr; a.beta1 = cfg->beta1; a.beta2 = cfg->beta2; a.eps = cfg->adam_eps; a.wd = cfg->weight_decay;
+    a.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta1, t)));
+    a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)cfg->beta2, t)));
+    a.dtype = dt;
+    TIDE_HIP(launch_adamw(a, s), "adamw");
+  }
+  st->step += 1;
+  return TIDE_OK;
+}
+
+// ---- building blocks ---------------------------------------------------------------------------
+size_t tide_gemm_workspace_bytes(int, int64_t, int64_t, int64_t, int) { return 0; }
+
+int tide_gemm(int layout, int64_t M, int64_t N, int64_t K, float alpha, const void* A, const void* B, void* C,
+              const void* residual, int in_dtype, int out_dtype, int accumulate, void* workspace,
+              size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (!A || !B || !C) return fail(TIDE_ERR_NULL, "A, B and C must not be NULL");
+  if (layout < 0 || layout > 2 || M <= 0 || N <= 0 || K <= 0) return fail(TIDE_ERR_CONFIG, "bad layout or sizes");
+  if ((in_dtype != 0 && in_dtype != 1) || (out_dtype != 0 && out_dtype != 1) || (in_dtype == 0 && out_dtype == 1))
+    return fail(TIDE_ERR_CONFIG, "unsupported dtype combination");
+  const int64_t lda = layout == kTN ? M : K, ldb = layout == kNT ? K : N;
+  GemmArgs g = gemm_args(layout, M, N, K, A, lda, B, ldb, C, N, in_dtype, out_dtype);
+  g.alpha = alpha; g.residual = residual; g.ldr = N; g.accumulate = accumulate;
+  TIDE_HIP(launch_gemm(g, (hipStream_t)stream), "gemm");
+  return TIDE_OK;
+}
+
+int tide_rmsnorm_fwd(int64_t rows, int64_t d, const void* x, const void* g, float eps, void* y, float* rstd,
+                     int dtype, void* stream) {
+  if (!x || !g || !y || !rstd) return fail(TIDE_ERR_NULL, "NULL argument");
+  if (rows <= 0 || d <= 0 || d > (1 << 24)) return fail(TIDE_ERR_CONFIG, "bad sizes");
+  TIDE_HIP(launch_rmsnorm_fwd(rows, (int)d, x, g, eps, y, rstd, dtype, (hipStream_t)stream), "rmsnorm fwd");
+  return TIDE_OK;
+}
+
+size_t tide_rmsnorm_bwd_scratch_bytes(int64_t rows, int64_t d) { return rmsnorm_bwd_scratch_bytes(rows, (int)d); }
+
+int tide_rmsnorm_bwd(int64_t rows, int64_t d, const void* dy, const void* x, const void* g, const float* rstd,
+                     const void* residual_grad, void* dx, float* dg, void* dg_partial, int dtype, void* stream) {
+  if (!dy || !x || !g || !rstd || !dx || !dg || !dg_partial) return fail(TIDE_ERR_NULL, "NULL argument");
+  const bool ok = (d % 8 == 0 && d <= 8192) || d <= 1024;
+  if (rows <= 0 || d <= 0 || !ok) return fail(TIDE_ERR_CONFIG, "bad sizes");
+  TIDE_HIP(launch_rmsnorm_bwd(rows, (int)d, dy, x, g, rstd, residual_grad, dx, dg, (float*)dg_partial, dtype, (hipStream_t)stream), "rmsnorm bwd");
+  return TIDE_OK;
+}
+
+static int attn_check(int B, int S, int nh, int nkv, int dh) {
+  if (B <= 0 || S <= 0 || nh <= 0 || nkv <= 0 || dh <= 0 || nh % nkv || dh > 256 || B > 65535) return fail(TIDE_ERR_CONFIG, "bad attention shape");
+  return 0;
+}
+
+int tide_attention_fwd(int B, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse, int dtype,
+                       void* stream) {
+  if (!qkv || !out || !lse) return fail(TIDE_ERR_NULL, "NULL argument");
+  if (attn_check(B, S, nh, nkv, dh)) return TIDE_ERR_CONFIG;
+  AttnArgs at;
+  std::memset(&at, 0, sizeof(at));
+  at.B = B; at.S = S; at.nh = nh; at.nkv = nkv; at.dh = dh; at.qkv = qkv; at.out = out; at.lse = lse; at.dtype = dtype;
+  TIDE_HIP(launch_attn_fwd(at, (hipStream_t)stream), "attention fwd");
+  return TIDE_OK;
+}
+
+int tide_attention_bwd(int B, int S, int nh, int nkv, int dh, const void* qkv, const void* out, const void* dout,
+                       const float* lse, float* delta, void* dqkv, int dtype, void* stream) {
+  if (!qkv || !out || !dout || !lse || !delta || !dqkv) return fail(TIDE_ERR_NULL, "NULL argument");
+  if (attn_check(B, S, nh, nkv, dh)) return TIDE_ERR_CONFIG;
+  AttnArgs at;
+  std::memset(&at, 0, sizeof(at));
+  at.B = B; at.S = S; at.nh = nh; at.nkv = nkv; at.dh = dh; at.qkv = qkv; at.out = const_cast<void*>(out);
+  at.lse = const_cast<float*>(lse); at.dout = dout; at.delta = delta; at.dqkv = dqkv; at.dtype = dtype;
+  TIDE_HIP(launch_attn_bwd(at, (hipStream_t)stream), "attention bwd");
+  return TIDE_OK;
+}
+
+int tide_rope(int B, int S, int nh, int nkv, int dh, float theta, void* qkv, float* table, int inverse, int dtype,
+              void* stream) {
+  if (!qkv || !table) return fail(TIDE_ERR_NULL, "NULL argument");
+  if (B <= 0 || S <= 0 || nh <= 0 || nkv <= 0 || dh <= 0 || dh % 2) return fail(TIDE_ERR_CONFIG, "bad rope shape");
+  TIDE_HIP(launch_rope_table(S, dh, theta, table, (hipStream_t)stream), "rope table");
+  TIDE_HIP(launch_rope(B, S, nh, nkv, dh, table, qkv, inverse, dtype, (hipStream_t)stream), "rope");
+  return TIDE_OK;
+}
+
+}  // extern "C"
+
+namespace tide {
+hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
+  if (attn_mfma_supported(a)) return launch_attn_fwd_mfma(a, s);
+  return launch_attn_fwd_simple(a, s);
+}
+hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
+  if (attn_mfma_supported(a)) return launch_attn_bwd_mfma(a, s);
+  return launch_attn_bwd_simple(a, s);
+}
+}  // namespace tide

@@ -1,0 +1,100 @@
+"""Device-memory plumbing around the C ABI: PyTorch is used only to own HBM buffers and streams.
+
+DraftTrainer uploads a host workload (numpy) once, keeps params / grads / Adam state / workspace
+resident, and forwards each call to the library.  It performs no arithmetic of the method.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workloads as W
+
+
+def _np_to_dev(x, dtype, device):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype == "bf16" and t.dtype == torch.float32:
+        # values are already bf16-representable (workloads.round_to_bf16): the cast is exact
+        return t.to(device).to(torch.bfloat16)
+    return t.to(device)
+
+
+class DraftTrainer:
+    def __init__(self, cfg: dict, params: dict, device="cuda:0"):
+        self.cfg = dict(cfg)
+        self.device = torch.device(device)
+        self.dtype = cfg["dtype"]
+        self.ccfg = B.make_config(cfg)
+        dt = self.dtype
+        self.params = {k: _np_to_dev(np.asarray(v, np.float32), dt, self.device) for k, v in params.items()}
+        f32 = dict(dtype=torch.float32, device=self.device)
+        self.grads = {k: torch.zeros(v.shape, **f32) for k, v in self.params.items()}
+        self.m = {k: torch.zeros(v.shape, **f32) for k, v in self.params.items()}
+        self.v = {k: torch.zeros(v.shape, **f32) for k, v in self.params.items()}
+        self.master = ({k: v.to(torch.float32) for k, v in self.params.items()} if dt == "bf16" else None)
+        self.ws_bytes = B.tide_draft_workspace_bytes(self.ccfg)
+        if self.ws_bytes == 0:
+            raise B.TideError(B.TIDE_ERR_CONFIG, B.tide_last_error())
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.loss = torch.zeros(1, **f32)
+        self.c_params = B.make_tensors(self.params)
+        self.c_grads = B.make_tensors(self.grads)
+        self.c_adam = B.TideAdamState()
+        self.c_adam.m = B.make_tensors(self.m)
+        self.c_adam.v = B.make_tensors(self.v)
+        self.c_adam.master = B.make_tensors(self.master)
+        self.c_adam.step = 0
+        self.hidden = self.tokens = self.mask = None
+
+    # ---- inputs ----
+    def set_batch(self, hidden, tokens, mask):
+        """numpy (host) or torch (device) inputs; kept resident."""
+        if isinstance(hidden, np.ndarray):
+            hidden = _np_to_dev(hidden.astype(np.float32, copy=False), self.dtype, self.device)
+        if isinstance(tokens, np.ndarray):
+            tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(self.device)
+        if isinstance(mask, np.ndarray):
+            mask = torch.from_numpy(np.ascontiguousarray(mask, dtype=np.uint8)).to(self.device)
+        self.hidden, self.tokens, self.mask = hidden.contiguous(), tokens.contiguous(), mask.contiguous()
+
+    def _stream(self):
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    # ---- calls ----
+    def forward(self, want_top1=False):
+        top1 = (torch.empty(self.cfg["batch"] * self.cfg["seq"], dtype=torch.int32, device=self.device)
+                if want_top1 else None)
+        B.tide_draft_forward(self.ccfg, self.c_params, self.hidden, self.tokens, self.mask, self.loss, top1,
+                             self.workspace, self.ws_bytes, self._stream())
+        return (self.loss, top1) if want_top1 else self.loss
+
+    def train_step(self, lr):
+        B.tide_draft_train_step(self.ccfg, self.c_params, self.c_grads, self.c_adam, self.hidden, self.tokens,
+                                self.mask, lr, self.loss, self.workspace, self.ws_bytes, self._stream())
+        return self.loss
+
+    @property
+    def step(self):
+        return int(self.c_adam.step)
+
+    # ---- read-back helpers for tests ----
+    def intermediate(self, name, shape, kind="act"):
+        """View of a named workspace buffer; kind: 'act' (config dtype) or 'f32'."""
+        off = B.tide_draft_workspace_offset(self.ccfg, name)
+        if off < 0:
+            raise KeyError(name)
+        tdt = torch.float32 if (kind == "f32" or self.dtype == "fp32") else torch.bfloat16
+        n = int(np.prod(shape))
+        nbytes = n * (4 if tdt == torch.float32 else 2)
+        return self.workspace[off:off + nbytes].view(tdt).view(*shape)
+
+    def host(self, d):
+        return {k: v.detach().to(torch.float32).cpu().numpy().astype(np.float64) for k, v in d.items()}
+
+
+def trainer_from_workload(cfg, wl, device="cuda:0"):
+    tr = DraftTrainer(cfg, wl["params"], device=device)
+    tr.set_batch(wl["hidden"], wl["tokens"], wl["mask"])
+    return tr

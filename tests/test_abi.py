@@ -1,0 +1,62 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the header
+declares, and validates configurations before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_05145_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_05145_amd import binding
+    return binding
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tide_draft.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tide_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    lib = ctypes.CDLL(B.LIB_PATH)
+    names = _declared_symbols()
+    assert "tide_draft_forward" in names and "tide_draft_train_step" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(B.EXPORTED)
+
+
+def test_workspace_sizes_and_config_validation(B):
+    for name in W.CONFIGS:
+        c = B.make_config(W.get_config(name))
+        assert B.tide_draft_workspace_bytes(c) > 0, name
+    c = B.make_config(W.get_config("8b"))
+    assert B.tide_draft_workspace_offset(c, "lm_rows") == 8192        # logits exist for 1/4 of the rows
+    assert B.tide_draft_workspace_offset(c, "nonsense") == -1
+    bad = [("n_heads", 3, "multiple"), ("hidden", 250, "hidden"), ("head_dim", 63, "hidden"),
+           ("vocab", 0, "positive"), ("dtype", 7, "dtype"), ("rms_eps", 0.0, "rms_eps"), ("batch", -1, "positive")]
+    for field, val, word in bad:
+        c = B.make_config(W.get_config("tiny"))
+        setattr(c, field, val)
+        assert B.tide_draft_workspace_bytes(c) == 0, field
+        assert word in B.tide_last_error(), (field, B.tide_last_error())
+
+
+def test_calls_reject_bad_arguments_before_touching_the_device(B):
+    c = B.make_config(W.get_config("tiny"))
+    t = B.make_tensors(None)
+    rc = B.tide_draft_forward(c, t, 256, 256, 256, 256, None, 256, 1 << 40, None, check=False)
+    assert rc == B.TIDE_ERR_NULL and "params" in B.tide_last_error()
+    rc = B.tide_draft_forward(None, t, 256, 256, 256, 256, None, 256, 1 << 40, None, check=False)
+    assert rc == B.TIDE_ERR_NULL
+    c.n_kv_heads = 3
+    rc = B.tide_draft_train_step(c, t, t, B.TideAdamState(), 256, 256, 256, 1e-4, 256, 256, 1 << 40, None, check=False)
+    assert rc == B.TIDE_ERR_CONFIG
+    with pytest.raises(B.TideError):
+        B.tide_draft_train_step(c, t, t, B.TideAdamState(), 256, 256, 256, 1e-4, 256, 256, 1 << 40, None)

@@ -1,0 +1,200 @@
+"""Per-kernel parity: each HIP building block, called through the C ABI, against the matching
+function of the CPU oracle on the same seeded inputs.  Shapes span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tide_oracle as O
+from tests.gpu_util import DEV, cosine, quantize, rel_max, stream, sync, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+DT = {"fp32": 0, "bf16": 1}
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_05145_amd import binding
+    return binding
+
+
+# ------------------------------------------------------------------ GEMM
+def _gemm_case(B, layout, M, N, K, in_dt, out_dt, seed, residual=False, accumulate=False, alpha=1.0):
+    rng = np.random.default_rng(seed)
+    shapeA = (K, M) if layout == B.LAYOUT_TN else (M, K)
+    shapeB = (N, K) if layout == B.LAYOUT_NT else (K, N)
+    A = quantize(rng.standard_normal(shapeA), in_dt)
+    Bm = quantize(rng.standard_normal(shapeB), in_dt)
+    C0 = quantize(rng.standard_normal((M, N)), out_dt)
+    R = quantize(rng.standard_normal((M, N)), out_dt)
+    opA = A.T if layout == B.LAYOUT_TN else A
+    opB = Bm.T if layout == B.LAYOUT_NT else Bm
+    ref = alpha * (opA @ opB)
+    if residual:
+        ref = ref + R
+    if accumulate:
+        ref = ref + C0
+    dA, dB = to_dev(A, in_dt), to_dev(Bm, in_dt)
+    dC, dR = to_dev(C0, out_dt), to_dev(R, out_dt)
+    print(f"gemm layout={layout} M={M} N={N} K={K} {in_dt}->{out_dt} res={residual} acc={accumulate}", flush=True)
+    B.tide_gemm(layout, M, N, K, alpha, dA, dB, dC, dR if residual else None, DT[in_dt], DT[out_dt],
+                accumulate, stream())
+    sync()
+    return to_host(dC), ref
+
+
+@pytest.mark.parametrize("layout", [0, 1, 2])
+@pytest.mark.parametrize("shape", [(300, 520, 136), (64, 72, 64), (8, 8, 8), (1000, 264, 1096)])
+def test_gemm_bf16_small_tiles(B, layout, shape):
+    M, N, K = shape
+    got, ref = _gemm_case(B, layout, M, N, K, "bf16", "fp32", seed=11 + layout)
+    assert rel_max(got, ref) < 2e-5
+    got, ref = _gemm_case(B, layout, M, N, K, "bf16", "bf16", seed=21 + layout, residual=True, alpha=0.5)
+    assert rel_max(got, ref) < 6e-3      # bf16 output rounding (2^-9 relative)
+    assert cosine(got, ref) > 0.99999
+
+
+@pytest.mark.parametrize("layout", [0, 1, 2])
+def test_gemm_bf16_large_tiles_ragged(B, layout):
+    # >= 200 tiles of 256x256 selects the large-tile kernel; M, N, K all ragged w.r.t. 256 / 64
+    M, N, K = 3720, 3656, 200
+    got, ref = _gemm_case(B, layout, M, N, K, "bf16", "fp32", seed=31 + layout, accumulate=True)
+    assert rel_max(got, ref) < 2e-5
+    got, ref = _gemm_case(B, layout, M, N, K, "bf16", "bf16", seed=41 + layout)
+    assert rel_max(got, ref) < 6e-3
+    assert cosine(got, ref) > 0.99999
+
+
+@pytest.mark.parametrize("layout", [0, 1, 2])
+def test_gemm_unaligned_falls_back(B, layout):
+    # K, M, N not multiples of 8: the shape-agnostic kernel takes over
+    got, ref = _gemm_case(B, layout, 77, 53, 101, "bf16", "fp32", seed=51 + layout)
+    assert rel_max(got, ref) < 2e-5
+    got, ref = _gemm_case(B, layout, 77, 53, 101, "fp32", "fp32", seed=61 + layout, residual=True, accumulate=True, alpha=-1.5)
+    assert rel_max(got, ref) < 2e-6
+
+
+def test_gemm_bad_arguments(B):
+    a = torch.zeros(64, device=DEV)
+    assert B.tide_gemm(0, 8, 8, 8, 1.0, None, a, a, None, 0, 0, 0, stream(), check=False) == B.TIDE_ERR_NULL
+    assert B.tide_gemm(5, 8, 8, 8, 1.0, a, a, a, None, 0, 0, 0, stream(), check=False) == B.TIDE_ERR_CONFIG
+    assert B.tide_gemm(0, 0, 8, 8, 1.0, a, a, a, None, 0, 0, 0, stream(), check=False) == B.TIDE_ERR_CONFIG
+    assert "layout" in B.tide_last_error() or "size" in B.tide_last_error()
+
+
+# ------------------------------------------------------------------ RMSNorm
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("rows,d", [(70, 256), (33, 4096), (5, 24), (40, 100)])
+def test_rmsnorm_fwd_bwd(B, dtype, rows, d):
+    rng = np.random.default_rng(rows * 1000 + d)
+    x = quantize(rng.standard_normal((rows, d)) * 3, dtype)
+    x[rows // 2] = 0.0  # a pad row: finite output, zero gradient contribution
+    g = quantize(1 + 0.2 * rng.standard_normal(d), dtype)
+    dy = quantize(rng.standard_normal((rows, d)), dtype)
+    res = quantize(rng.standard_normal((rows, d)), dtype)
+    eps = 1e-5
+    y_ref, r_ref = O.rmsnorm_fwd(x, g, eps)
+    dx_ref, dg_ref = O.rmsnorm_bwd(dy, x, g, r_ref)
+    dx_ref = dx_ref + res
+    dx_, dg_, y_ = to_dev(np.zeros_like(x), dtype), torch.zeros(d, device=DEV), to_dev(np.zeros_like(x), dtype)
+    rstd = torch.zeros(rows, device=DEV)
+    xd, gd, dyd, resd = to_dev(x, dtype), to_dev(g, dtype), to_dev(dy, dtype), to_dev(res, dtype)
+    print(f"rmsnorm rows={rows} d={d} {dtype}", flush=True)
+    B.tide_rmsnorm_fwd(rows, d, xd, gd, eps, y_, rstd, DT[dtype], stream())
+    scratch = torch.empty(B.tide_rmsnorm_bwd_scratch_bytes(rows, d), dtype=torch.uint8, device=DEV)
+    B.tide_rmsnorm_bwd(rows, d, dyd, xd, gd, rstd, resd, dx_, dg_, scratch, DT[dtype], stream())
+    sync()
+    tol = 1e-5 if dtype == "fp32" else 8e-3
+    assert rel_max(to_host(rstd), r_ref[:, 0]) < 1e-5
+    assert rel_max(to_host(y_), y_ref) < tol
+    assert rel_max(to_host(dx_), dx_ref) < tol
+    assert rel_max(to_host(dg_), dg_ref) < 1e-5
+    assert np.all(to_host(y_)[rows // 2] == 0.0)
+
+
+# ------------------------------------------------------------------ RoPE
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_rope_forward_and_inverse(B, dtype):
+    Bn, S, nh, nkv, dh, theta = 2, 300, 4, 2, 64, 5e5
+    rng = np.random.default_rng(5)
+    ld = (nh + 2 * nkv) * dh
+    qkv = quantize(rng.standard_normal((Bn * S, ld)), dtype)
+    cos, sin = O.rope_angles(S, dh, theta)
+    q = qkv[:, :nh * dh].reshape(Bn, S, nh, dh)
+    k = qkv[:, nh * dh:(nh + nkv) * dh].reshape(Bn, S, nkv, dh)
+    ref = qkv.copy()
+    ref[:, :nh * dh] = O.rope_apply(q, cos, sin).reshape(Bn * S, -1)
+    ref[:, nh * dh:(nh + nkv) * dh] = O.rope_apply(k, cos, sin).reshape(Bn * S, -1)
+    d = to_dev(qkv, dtype)
+    table = torch.empty(S * dh, device=DEV)
+    B.tide_rope(Bn, S, nh, nkv, dh, theta, d, table, 0, DT[dtype], stream())
+    sync()
+    got = to_host(d)
+    tol = 2e-6 if dtype == "fp32" else 8e-3
+    assert rel_max(got, ref) < tol
+    assert np.array_equal(got[:, (nh + nkv) * dh:], qkv[:, (nh + nkv) * dh:])  # v untouched
+    # inverse rotation = the backward pass
+    refi = qkv.copy()
+    refi[:, :nh * dh] = O.rope_apply(q, cos, sin, inverse=True).reshape(Bn * S, -1)
+    refi[:, nh * dh:(nh + nkv) * dh] = O.rope_apply(k, cos, sin, inverse=True).reshape(Bn * S, -1)
+    d = to_dev(qkv, dtype)
+    B.tide_rope(Bn, S, nh, nkv, dh, theta, d, table, 1, DT[dtype], stream())
+    sync()
+    assert rel_max(to_host(d), refi) < tol
+
+
+# ------------------------------------------------------------------ attention
+def _attn_case(B, dtype, Bn, S, nh, nkv, dh, seed):
+    rng = np.random.default_rng(seed)
+    ld = (nh + 2 * nkv) * dh
+    qkv = quantize(rng.standard_normal((Bn * S, ld)), dtype)
+    dout = quantize(rng.standard_normal((Bn * S, nh * dh)), dtype)
+    q = qkv[:, :nh * dh].reshape(Bn, S, nh, dh)
+    k = qkv[:, nh * dh:(nh + nkv) * dh].reshape(Bn, S, nkv, dh)
+    v = qkv[:, (nh + nkv) * dh:].reshape(Bn, S, nkv, dh)
+    A, P = O.attention_fwd(q, k, v)
+    qd = to_dev(qkv, dtype)
+    out = to_dev(np.zeros((Bn * S, nh * dh)), dtype)
+    lse = torch.zeros(Bn * nh * S, device=DEV)
+    print(f"attention {dtype} B={Bn} S={S} nh={nh} nkv={nkv} dh={dh}", flush=True)
+    B.tide_attention_fwd(Bn, S, nh, nkv, dh, qd, out, lse, DT[dtype], stream())
+    sync()
+    # backward consumes the forward's own (rounded) output, like the training step does
+    A_dev = to_host(out).reshape(Bn, S, nh, dh)
+    dq, dk, dv = O.attention_bwd(dout.reshape(Bn, S, nh, dh), q, k, v, P)
+    dref = np.concatenate([dq.reshape(Bn * S, -1), dk.reshape(Bn * S, -1), dv.reshape(Bn * S, -1)], 1)
+    dqkv = to_dev(np.zeros_like(qkv), dtype)
+    delta = torch.zeros(Bn * nh * S, device=DEV)
+    B.tide_attention_bwd(Bn, S, nh, nkv, dh, qd, out, to_dev(dout, dtype), lse, delta, dqkv, DT[dtype], stream())
+    sync()
+    # lse reference from the scores
+    scale = 1 / np.sqrt(dh)
+    G = nh // nkv
+    lse_ref = np.empty((Bn, nh, S))
+    for b in range(Bn):
+        for h in range(nh):
+            sc = (q[b, :, h] @ k[b, :, h // G].T) * scale
+            sc[np.triu(np.ones((S, S), bool), 1)] = -np.inf
+            m = sc.max(-1)
+            lse_ref[b, h] = m + np.log(np.exp(sc - m[:, None]).sum(-1))
+    return (A_dev.reshape(Bn * S, -1), A.reshape(Bn * S, -1), to_host(lse).reshape(Bn, nh, S), lse_ref,
+            to_host(dqkv), dref, (nh * dh, nkv * dh))
+
+
+@pytest.mark.parametrize("dtype,shape", [
+    ("fp32", (2, 70, 4, 2, 64)), ("fp32", (1, 1, 2, 1, 8)), ("fp32", (1, 130, 2, 2, 16)),
+    ("bf16", (2, 70, 4, 2, 64)), ("bf16", (1, 200, 4, 1, 128)), ("bf16", (2, 333, 4, 2, 128)),
+])
+def test_attention_fwd_bwd(B, dtype, shape):
+    got, ref, lse, lse_ref, dgot, dref, (nq, nk) = _attn_case(B, dtype, *shape, seed=sum(shape))
+    if dtype == "fp32":
+        assert rel_max(got, ref) < 1e-5
+        assert np.max(np.abs(lse - lse_ref)) < 1e-5
+        for sl in (slice(0, nq), slice(nq, nq + nk), slice(nq + nk, None)):
+            assert rel_max(dgot[:, sl], dref[:, sl]) < 2e-5
+    else:
+        assert rel_max(got, ref) < 1e-2
+        assert np.max(np.abs(lse - lse_ref)) < 2e-2
+        for sl in (slice(0, nq), slice(nq, nq + nk), slice(nq + nk, None)):
+            assert cosine(dgot[:, sl], dref[:, sl]) > 0.9995
+            assert rel_max(dgot[:, sl], dref[:, sl]) < 3e-2
