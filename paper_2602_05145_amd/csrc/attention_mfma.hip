@@ -1,7 +1,522 @@
-// placeholder until the MFMA flash-attention kernels land
+// Flash-style causal grouped-query attention for gfx950, head_dim 128, bf16 storage, fp32 softmax and
+// accumulation, v_mfma_f32_32x32x16_bf16 throughout.  Three kernels: forward, dQ, and dK/dV.  The
+// [S,S] score matrix never exists; only the per-row log-sum-exp is kept for the backward pass.
+//
+// Orientation.  An MFMA 32x32 result leaves each lane with ONE column (lane % 32) and 16 of the 32 rows.
+// Every product is therefore arranged so that the index a lane needs a scalar for is the column:
+//   forward / dQ : S^T = K Q^T (rows = keys, columns = queries) -> the running max / sum, lse and delta
+//                  of a query are per-lane scalars, and a row reduction is 16 in-lane steps plus one
+//                  exchange with lane ^ 32;
+//   dK/dV        : S = Q K^T (rows = queries, columns = keys)   -> the dK/dV columns of a key stay in
+//                  one lane.
+// In both cases the probabilities come out of the MFMA exactly in the register layout that the next
+// MFMA wants for its B operand (8 contraction values per lane), provided the A operand enumerates the
+// contraction index in the same order {4g..4g+3, 8+4g..8+4g+3} (g = lane / 32).  That A operand (V^T,
+// K^T, dO^T, Q^T) is read from the row-major LDS tile with the transposing LDS read
+// ds_read_b64_tr_b16, so nothing is ever transposed through registers or HBM.
+//
+// Tiles.  Forward and dQ: one block = 128 queries of one head (4 waves x 32 queries, Q in registers),
+// K/V streamed in 64-key tiles, double buffered through LDS.  dK/dV: one block = 128 keys of one kv
+// head (4 waves x 32 keys, K and V in registers), Q/dO streamed in 32-query tiles for each of the G
+// query heads of the group, so dK/dV are summed over the group in registers: no atomics, deterministic.
+// Causality: tiles entirely above the diagonal are never loaded; heavy blocks are scheduled first.
 #include "kernels.h"
+#include "tide_common.h"
+
 namespace tide {
-bool attn_mfma_supported(const AttnArgs&) { return false; }
-hipError_t launch_attn_fwd_mfma(const AttnArgs&, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_attn_bwd_mfma(const AttnArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+
+namespace {
+
+constexpr int D = 128;          // head_dim
+constexpr int PITCH = D + 8;    // LDS row pitch in elements (272 B: conflict-free 16-byte row reads)
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+// A/B operand whose contraction index is contiguous in the LDS tile [row][PITCH]
+__device__ __forceinline__ u32x4_t frag(const bf16_t* tile, int row, int kofs) {
+  return *reinterpret_cast<const u32x4_t*>(tile + row * PITCH + kofs);
+}
+
+// A operand taken from the tile TRANSPOSED: tile is [k][PITCH] (k = contraction index, 16 rows starting
+// at kbase), the operand row is the tile column nbase + lane % 32, and the 8 contraction values of the
+// lane are k = kbase + {4g..4g+3, 8+4g..8+4g+3}.
+__device__ __forceinline__ u32x4_t frag_tr(const bf16_t* tile, int kbase, int nbase, int lane) {
+  const int g = lane >> 5;
+  const int l16 = lane & 15;
+  const int col = nbase + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
+  const int row = kbase + 4 * g + (l16 >> 2);
+  typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+  const bf16_t* p0 = tile + row * PITCH + col;
+  const bf16_t* p1 = p0 + 8 * PITCH;
+  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0));
+  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p1));
+  u32x2_t a = __builtin_bit_cast(u32x2_t, lo), b = __builtin_bit_cast(u32x2_t, hi);
+  u32x4_t r;
+  r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+  return r;
+}
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+// registers q0..q0+7 of a 32x32 accumulator -> the 8-value B operand of the next MFMA
+__device__ __forceinline__ u32x4_t pack_half(const f32x16_t& v, int half) {
+  u32x4_t r;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) r[w] = pack2(v[half * 8 + 2 * w], v[half * 8 + 2 * w + 1]);
+  return r;
+}
+
+// row index (0..31) that accumulator register q of this lane holds
+__device__ __forceinline__ int acc_row(int q, int g) { return 8 * (q >> 2) + 4 * g + (q & 3); }
+
+// Stage `rows` rows x 128 columns (bf16) of a row-major global matrix into an LDS tile through registers.
+// NP = 16-byte pieces per thread (rows * 16 / 256).
+template <int NP>
+struct TileLoader {
+  i32x4_t r[NP];
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rs, int row0, int ld, int col0, int tid) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int p = tid + i * 256;
+      const int row = p >> 4, piece = p & 15;
+      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)(row0 + row) * (uint32_t)ld + (uint32_t)(col0 + piece * 8)) * 2u, 0, 0);
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int p = tid + i * 256;
+      const int row = p >> 4, piece = p & 15;
+      *reinterpret_cast<i32x4_t*>(tile + row * PITCH + piece * 8) = r[i];
+    }
+  }
+};
+
+// Write a wave's 32 x 128 result, held transposed in 4 accumulators (acc[ct] = rows ct*32.., column =
+// lane % 32 = the wave-local output row), into an LDS tile [128][PITCH] at rows wave*32.. as bf16.
+__device__ __forceinline__ void stage_out(bf16_t* tile, const f32x16_t (&acc)[4], float mul, int wave, int lane) {
+  const int g = lane >> 5, r = wave * 32 + (lane & 31);
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq) {
+      const int c = ct * 32 + 8 * qq + 4 * g;
+      uint2 v;
+      v.x = pack2(acc[ct][qq * 4 + 0] * mul, acc[ct][qq * 4 + 1] * mul);
+      v.y = pack2(acc[ct][qq * 4 + 2] * mul, acc[ct][qq * 4 + 3] * mul);
+      *reinterpret_cast<uint2*>(tile + r * PITCH + c) = v;
+    }
+}
+
+// Copy the staged [128][128] tile to global rows row0.. (< row_end) of a matrix with leading dim ld.
+__device__ __forceinline__ void copy_out(const bf16_t* tile, bf16_t* dst, int64_t row0, int64_t row_end, int ld,
+                                         int col0, int tid) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int p = tid + i * 256;
+    const int row = p >> 4, piece = p & 15;
+    if (row0 + row < row_end)
+      *reinterpret_cast<i32x4_t*>(dst + (size_t)(row0 + row) * ld + col0 + piece * 8) =
+          *reinterpret_cast<const i32x4_t*>(tile + row * PITCH + piece * 8);
+  }
+}
+
+constexpr int BQ = 128, BKV = 64;
+constexpr int KV_TILE = BKV * PITCH;  // elements
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+                                                            float* __restrict__ lse, int S, int nh, int nkv) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+  bf16_t* sK = smem;                 // [2][KV_TILE]
+  bf16_t* sV = smem + 2 * KV_TILE;   // [2][KV_TILE]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 31, g = lane >> 5;
+  const int nqb = (S + BQ - 1) / BQ;
+  const int qb = nqb - 1 - blockIdx.x;  // heavy (late) query blocks first
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int G = nh / nkv, kh = h / G;
+  const int ld = (nh + 2 * nkv) * D;
+  const int q0 = qb * BQ, qw = q0 + wave * 32, iq = qw + lr;
+  const bf16_t* base = qkv + (size_t)b * S * ld;
+  const __amdgpu_buffer_rsrc_t rs = rsrc(base, (uint32_t)((size_t)S * ld * 2));
+  const int kcol = (nh + kh) * D, vcol = (nh + nkv + kh) * D;
+  const float c = kLog2e / sqrtf((float)D);
+
+  u32x4_t qf[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk)
+    qf[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)iq * (uint32_t)ld + (uint32_t)(h * D + kk * 16 + g * 8)) * 2u, 0, 0));
+
+  f32x16_t o[4];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) o[ct][q] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int kv_end = min(S, q0 + BQ);
+  const int nt = (kv_end + BKV - 1) / BKV;
+  TileLoader<4> lk, lv;
+  lk.load(rs, 0, ld, kcol, tid);
+  lv.load(rs, 0, ld, vcol, tid);
+  lk.store(sK, tid);
+  lv.store(sV, tid);
+  __syncthreads();
+
+  for (int t = 0; t < nt; ++t) {
+    const int st = t & 1;
+    const int j0 = t * BKV;
+    if (t + 1 < nt) {
+      lk.load(rs, j0 + BKV, ld, kcol, tid);
+      lv.load(rs, j0 + BKV, ld, vcol, tid);
+    }
+    if (j0 <= qw + 31) {  // wave-uniform: the tile has at least one unmasked key for this wave
+      const bf16_t* K = sK + st * KV_TILE;
+      const bf16_t* V = sV + st * KV_TILE;
+      f32x16_t s[2];
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) s[jt][q] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) s[jt] = mfma(frag(K, jt * 32 + lr, kk * 16 + g * 8), qf[kk], s[jt]);
+      }
+      if (j0 + BKV - 1 > qw) {  // the tile touches the diagonal of this wave
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+          for (int q = 0; q < 16; ++q)
+            if (j0 + jt * 32 + acc_row(q, g) > iq) s[jt][q] = -INFINITY;
+      }
+      float tm = -INFINITY;
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) tm = fmaxf(tm, s[jt][q]);
+      tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
+      const float mn = fmaxf(m, tm);          // finite: key 0 is visible to every query
+      const float alpha = __builtin_amdgcn_exp2f((m - mn) * c);
+      const float mc = mn * c;
+      float ps = 0.f;
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const float p = __builtin_amdgcn_exp2f(s[jt][q] * c - mc);
+          s[jt][q] = p;
+          ps += p;
+        }
+      ps += __shfl_xor(ps, 32, 64);
+      l = l * alpha + ps;
+      m = mn;
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) o[ct][q] *= alpha;
+      u32x4_t pf[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) pf[ks] = pack_half(s[ks >> 1], ks & 1);
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) o[ct] = mfma(frag_tr(V, ks * 16, ct * 32, lane), pf[ks], o[ct]);
+    }
+    if (t + 1 < nt) {
+      lk.store(sK + (st ^ 1) * KV_TILE, tid);
+      lv.store(sV + (st ^ 1) * KV_TILE, tid);
+    }
+    __syncthreads();
+  }
+
+  const float inv = 1.0f / l;
+  stage_out(smem, o, inv, wave, lane);
+  if (g == 0 && iq < S) lse[((size_t)b * nh + h) * S + iq] = m * (1.0f / sqrtf((float)D)) + logf(l);
+  __syncthreads();
+  copy_out(smem, out, (int64_t)b * S + q0, (int64_t)b * S + min(S, q0 + BQ), nh * D, h * D, tid);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, dQ: same streaming structure as the forward pass
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                           const float* __restrict__ lse, const float* __restrict__ delta,
+                                                           bf16_t* __restrict__ dqkv, int S, int nh, int nkv) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+  bf16_t* sK = smem;
+  bf16_t* sV = smem + 2 * KV_TILE;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 31, g = lane >> 5;
+  const int nqb = (S + BQ - 1) / BQ;
+  const int qb = nqb - 1 - blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int G = nh / nkv, kh = h / G;
+  const int ld = (nh + 2 * nkv) * D, ldo = nh * D;
+  const int q0 = qb * BQ, qw = q0 + wave * 32, iq = qw + lr;
+  const __amdgpu_buffer_rsrc_t rs = rsrc(qkv + (size_t)b * S * ld, (uint32_t)((size_t)S * ld * 2));
+  const __amdgpu_buffer_rsrc_t rso = rsrc(dout + (size_t)b * S * ldo, (uint32_t)((size_t)S * ldo * 2));
+  const int kcol = (nh + kh) * D, vcol = (nh + nkv + kh) * D;
+  const float scale = 1.0f / sqrtf((float)D);
+  const float c = kLog2e * scale;
+
+  u32x4_t qf[8], dof[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    qf[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)iq * (uint32_t)ld + (uint32_t)(h * D + kk * 16 + g * 8)) * 2u, 0, 0));
+    dof[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rso, ((uint32_t)iq * (uint32_t)ldo + (uint32_t)(h * D + kk * 16 + g * 8)) * 2u, 0, 0));
+  }
+  const bool valid = iq < S;
+  const float lse_i = valid ? lse[((size_t)b * nh + h) * S + iq] * kLog2e : 0.f;
+  const float del_i = valid ? delta[((size_t)b * nh + h) * S + iq] : 0.f;
+
+  f32x16_t dq[4];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) dq[ct][q] = 0.f;
+
+  const int kv_end = min(S, q0 + BQ);
+  const int nt = (kv_end + BKV - 1) / BKV;
+  TileLoader<4> lk, lv;
+  lk.load(rs, 0, ld, kcol, tid);
+  lv.load(rs, 0, ld, vcol, tid);
+  lk.store(sK, tid);
+  lv.store(sV, tid);
+  __syncthreads();
+
+  for (int t = 0; t < nt; ++t) {
+    const int st = t & 1;
+    const int j0 = t * BKV;
+    if (t + 1 < nt) {
+      lk.load(rs, j0 + BKV, ld, kcol, tid);
+      lv.load(rs, j0 + BKV, ld, vcol, tid);
+    }
+    if (j0 <= qw + 31) {
+      const bf16_t* K = sK + st * KV_TILE;
+      const bf16_t* V = sV + st * KV_TILE;
+      const bool diag = j0 + BKV - 1 > qw;
+      u32x4_t dsf[4];
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) {
+        f32x16_t s, dp;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+          s = mfma(frag(K, jt * 32 + lr, kk * 16 + g * 8), qf[kk], s);
+          dp = mfma(frag(V, jt * 32 + lr, kk * 16 + g * 8), dof[kk], dp);
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          float p = __builtin_amdgcn_exp2f(s[q] * c - lse_i);
+          if (!valid || (diag && (j0 + jt * 32 + acc_row(q, g) > iq))) p = 0.f;
+          s[q] = p * (dp[q] - del_i);
+        }
+        dsf[2 * jt] = pack_half(s, 0);
+        dsf[2 * jt + 1] = pack_half(s, 1);
+      }
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) dq[ct] = mfma(frag_tr(K, ks * 16, ct * 32, lane), dsf[ks], dq[ct]);
+    }
+    if (t + 1 < nt) {
+      lk.store(sK + (st ^ 1) * KV_TILE, tid);
+      lv.store(sV + (st ^ 1) * KV_TILE, tid);
+    }
+    __syncthreads();
+  }
+  stage_out(smem, dq, scale, wave, lane);
+  __syncthreads();
+  copy_out(smem, dqkv, (int64_t)b * S + q0, (int64_t)b * S + min(S, q0 + BQ), ld, h * D, tid);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, dK and dV
+// ------------------------------------------------------------------------------------------------
+namespace {
+constexpr int BI = 32;                          // query rows per streamed tile
+constexpr int Q_TILE = BI * PITCH;              // elements
+constexpr int DKV_STAGE = 2 * Q_TILE + 2 * 64;  // Q tile, dO tile, then lse[32] and delta[32] as floats
+}  // namespace
+
+__global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                            const float* __restrict__ lse, const float* __restrict__ delta,
+                                                            bf16_t* __restrict__ dqkv, int S, int nh, int nkv) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 31, g = lane >> 5;
+  const int jb = blockIdx.x, kh = blockIdx.y, b = blockIdx.z;  // early key blocks are the heavy ones
+  const int G = nh / nkv;
+  const int ld = (nh + 2 * nkv) * D, ldo = nh * D;
+  const int j0 = jb * 128, jw = j0 + wave * 32, jk = jw + lr;
+  const __amdgpu_buffer_rsrc_t rs = rsrc(qkv + (size_t)b * S * ld, (uint32_t)((size_t)S * ld * 2));
+  const __amdgpu_buffer_rsrc_t rso = rsrc(dout + (size_t)b * S * ldo, (uint32_t)((size_t)S * ldo * 2));
+  const int kcol = (nh + kh) * D, vcol = (nh + nkv + kh) * D;
+  const float scale = 1.0f / sqrtf((float)D);
+  const float c = kLog2e * scale;
+
+  u32x4_t kf[8], vf[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    kf[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)jk * (uint32_t)ld + (uint32_t)(kcol + kk * 16 + g * 8)) * 2u, 0, 0));
+    vf[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)jk * (uint32_t)ld + (uint32_t)(vcol + kk * 16 + g * 8)) * 2u, 0, 0));
+  }
+  f32x16_t dk[4], dv[4];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) { dk[ct][q] = 0.f; dv[ct][q] = 0.f; }
+
+  const int i_begin = (j0 / BI) * BI;                  // first query tile that can see a key of this block
+  const int nit = (S - i_begin + BI - 1) / BI;         // query tiles per head
+  const int ntiles = G * nit;
+
+  TileLoader<2> lq, ldo_;
+  float stat = 0.f;  // threads 0..31 carry lse, 32..63 carry delta of the staged tile
+  auto gload = [&](int u) {
+    const int hh = kh * G + u / nit;
+    const int i0 = i_begin + (u % nit) * BI;
+    lq.load(rs, i0, ld, hh * D, tid);
+    ldo_.load(rso, i0, ldo, hh * D, tid);
+    if (tid < 64) {
+      const int i = i0 + (tid & 31);
+      const float* src = (tid < 32) ? lse : delta;
+      stat = (i < S) ? src[((size_t)b * nh + hh) * S + i] : 0.f;
+    }
+  };
+  auto sstore = [&](int st) {
+    bf16_t* base = smem + st * DKV_STAGE;
+    lq.store(base, tid);
+    ldo_.store(base + Q_TILE, tid);
+    if (tid < 64) reinterpret_cast<float*>(base + 2 * Q_TILE)[tid] = stat;
+  };
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int u = 0; u < ntiles; ++u) {
+    const int st = u & 1;
+    if (u + 1 < ntiles) gload(u + 1);
+    const int i0 = i_begin + (u % nit) * BI;
+    if (i0 + BI - 1 >= jw) {  // wave-uniform: some query of the tile sees some key of this wave
+      const bf16_t* Qt = smem + st * DKV_STAGE;
+      const bf16_t* dOt = Qt + Q_TILE;
+      const float* stats = reinterpret_cast<const float*>(Qt + 2 * Q_TILE);
+      f32x16_t s, dp;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        s = mfma(frag(Qt, lr, kk * 16 + g * 8), kf[kk], s);
+        dp = mfma(frag(dOt, lr, kk * 16 + g * 8), vf[kk], dp);
+      }
+      const bool diag = i0 < jw + 32;  // some (query, key) pair of the tile is above the diagonal
+#pragma unroll
+      for (int qq = 0; qq < 4; ++qq) {
+        const float4 l4 = *reinterpret_cast<const float4*>(stats + 8 * qq + 4 * g);
+        const float4 d4 = *reinterpret_cast<const float4*>(stats + 32 + 8 * qq + 4 * g);
+        const float lv4[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int q = qq * 4 + e;
+          const int i = i0 + 8 * qq + 4 * g + e;
+          float p = __builtin_amdgcn_exp2f(s[q] * c - lv4[e] * kLog2e);
+          if (i >= S || (diag && i < jk)) p = 0.f;
+          s[q] = p;
+          dp[q] = p * (dp[q] - dv4[e]);
+        }
+      }
+      u32x4_t pf[2] = {pack_half(s, 0), pack_half(s, 1)};
+      u32x4_t dsf[2] = {pack_half(dp, 0), pack_half(dp, 1)};
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          dv[ct] = mfma(frag_tr(dOt, ks * 16, ct * 32, lane), pf[ks], dv[ct]);
+          dk[ct] = mfma(frag_tr(Qt, ks * 16, ct * 32, lane), dsf[ks], dk[ct]);
+        }
+    }
+    if (u + 1 < ntiles) sstore(st ^ 1);
+    __syncthreads();
+  }
+  const int64_t r0 = (int64_t)b * S + j0, r1 = (int64_t)b * S + min(S, j0 + 128);
+  stage_out(smem, dk, scale, wave, lane);
+  __syncthreads();
+  copy_out(smem, dqkv, r0, r1, ld, kcol, tid);
+  __syncthreads();
+  stage_out(smem, dv, 1.0f, wave, lane);
+  __syncthreads();
+  copy_out(smem, dqkv, r0, r1, ld, vcol, tid);
+}
+
+// ------------------------------------------------------------------------------------------------
+bool attn_mfma_supported(const AttnArgs& a) {
+  if (a.dtype != kBF16 || a.dh != D) return false;
+  if (a.B <= 0 || a.S <= 0 || a.B > 65535 || a.nh > 65535) return false;
+  const int64_t ld = (int64_t)(a.nh + 2 * a.nkv) * D;
+  if ((int64_t)a.S * ld * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit offsets inside one sequence
+  if (((uintptr_t)a.qkv | (uintptr_t)a.out | (uintptr_t)a.dout | (uintptr_t)a.dqkv) & 15) return false;
+  return true;
+}
+
+namespace {
+constexpr size_t kFwdSmem = (size_t)4 * KV_TILE * sizeof(bf16_t);           // 69632 B (>= the 128 x PITCH output tile)
+constexpr size_t kDkvSmemStages = (size_t)2 * DKV_STAGE * sizeof(bf16_t);
+constexpr size_t kOutTile = (size_t)128 * PITCH * sizeof(bf16_t);
+constexpr size_t kDkvSmem = kDkvSmemStages > kOutTile ? kDkvSmemStages : kOutTile;
+
+hipError_t set_smem(const void* f, size_t bytes, bool& done) {
+  if (done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+}  // namespace
+
+hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
+  static bool done = false;
+  hipError_t e = set_smem((const void*)attn_fwd_mfma_kernel, kFwdSmem, done);
+  if (e != hipSuccess) return e;
+  dim3 grid((a.S + BQ - 1) / BQ, a.nh, a.B);
+  hipLaunchKernelGGL(attn_fwd_mfma_kernel, grid, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
+  static bool done_q = false, done_kv = false;
+  hipError_t e = launch_attn_delta(a, s);
+  if (e != hipSuccess) return e;
+  e = set_smem((const void*)attn_dq_mfma_kernel, kFwdSmem, done_q);
+  if (e != hipSuccess) return e;
+  e = set_smem((const void*)attn_dkv_mfma_kernel, kDkvSmem, done_kv);
+  if (e != hipSuccess) return e;
+  dim3 gq((a.S + BQ - 1) / BQ, a.nh, a.B), gkv((a.S + 127) / 128, a.nkv, a.B);
+  hipLaunchKernelGGL(attn_dq_mfma_kernel, gq, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_dkv_mfma_kernel, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv);
+  return hipGetLastError();
+}
+
 }  // namespace tide

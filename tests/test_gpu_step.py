@@ -54,7 +54,10 @@ def _check_fp32(cfg, wl):
     # (b) end to end: an entry whose gradient is at the scale of its own fp32 error (or of adam_eps)
     # can take a different fraction of the lr-sized first step, so the bound is a fraction of lr
     for k in O.PARAM_NAMES:
-        assert np.max(np.abs(p[k] - p1_ref[k])) <= 0.05 * lr, k
+        err = np.abs(p[k] - p1_ref[k])
+        assert np.max(err) <= 0.25 * lr, k
+        solid = np.abs(grads_ref[k]) >= 1e-4 * np.max(np.abs(grads_ref[k]))
+        assert np.max(err[solid], initial=0.0) <= 0.01 * lr, k
     m, v = tr.host(tr.m), tr.host(tr.v)
     for k in O.PARAM_NAMES:
         assert rel_max(m[k], m_ref[k]) <= 1e-4 and rel_max(v[k], v_ref[k]) <= 2e-4, k
@@ -175,7 +178,7 @@ def test_two_steps_and_determinism():
     assert tr.step == 2
     got = tr.host(tr.params)
     for k in O.PARAM_NAMES:
-        assert np.max(np.abs(got[k] - p[k])) <= 0.05 * 1e-3 * 2, k   # a fraction of lr per step, as above
+        assert np.max(np.abs(got[k] - p[k])) <= 0.25 * 1e-3 * 2, k   # a fraction of lr per step, as above
     # same inputs, same launch order: bit-identical results (no atomics anywhere on the path)
     for k in tr.params:
         assert torch.equal(tr.params[k], tr2.params[k]), k
