@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the TIDE draft-training step on one MI355X.
+
+A step = one tide_draft_train_step (forward + backward + AdamW) over one batch of synthetic captured
+hidden states already resident in HBM.  Prints ONE JSON line: whole-job tokens/s, the MFMA roofline
+of the dominant kernel (measured live with HIP events recorded by the library on the stream it
+launches on), and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
+PEAK_HBM_GBS = 8000.0
+
+
+def device_workload(cfg, device, seed):
+    """Same recipe as workloads.make_workload (distributions, outlier channels, Zipf labels, prefix /
+    length masks), drawn on the GPU to avoid ~1.2e9 host normals at the large shapes."""
+    import torch
+    from paper_2602_05145_amd import workloads as W
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    B, S = cfg["batch"], cfg["seq"]
+    K, Ht, V = cfg["n_capture"], cfg["target_hidden"], cfg["vocab"]
+    params = {}
+    for name, shp in W.param_shapes(cfg).items():
+        if len(shp) == 1:
+            params[name] = torch.ones(shp, device=device, dtype=torch.float32)
+        else:
+            params[name] = torch.randn(shp, device=device, dtype=torch.float32, generator=g) * 0.02
+    hidden = torch.randn((B, S, K * Ht), device=device, dtype=torch.float32, generator=g)
+    n_out = int(round(cfg["outlier_frac"] * Ht))
+    for kk in range(K):
+        idx = torch.randperm(Ht, device=device, generator=g)[:n_out] + kk * Ht
+        hidden[:, :, idx] *= cfg["outlier_scale"]
+    perm = torch.randperm(V, device=device, generator=g)
+    w = torch.arange(1, V + 1, device=device, dtype=torch.float64) ** (-cfg["zipf_s"])
+    cdf = torch.cumsum(w / w.sum(), 0)
+    ranks = torch.searchsorted(cdf, torch.rand((B, S), device=device, dtype=torch.float64, generator=g), right=True)
+    tokens = perm[ranks.clamp_(max=V - 1)].to(torch.int32)
+    kind = cfg["mask"]
+    if kind == "prefix":
+        mask = torch.ones((B, S), device=device, dtype=torch.uint8)
+        mask[:, : int(cfg["mask_p"] * S)] = 0
+    elif kind == "bernoulli":
+        mask = (torch.rand((B, S), device=device, generator=g) >= cfg["mask_p"]).to(torch.uint8)
+    elif kind == "lengths":
+        L = torch.randint(min(cfg["len_lo"], S), min(cfg["len_hi"], S) + 1, (B,), device=device, generator=g)
+        mask = (torch.arange(S, device=device)[None, :] < L[:, None]).to(torch.uint8)
+        hidden[mask == 0] = 0.0
+        tokens[mask == 0] = 0
+    else:
+        mask = torch.ones((B, S), device=device, dtype=torch.uint8)
+    if cfg["dtype"] == "bf16":
+        params = {k: v.to(torch.bfloat16) for k, v in params.items()}
+        hidden = hidden.to(torch.bfloat16)
+    return params, hidden, tokens, mask
+
+
+class DeviceTrainer:
+    """runtime.DraftTrainer fed from device tensors (no host round trip)."""
+
+    def __new__(cls, cfg, params, hidden, tokens, mask):
+        import torch
+        from paper_2602_05145_amd import runtime
+        tr = runtime.DraftTrainer.__new__(runtime.DraftTrainer)
+        from paper_2602_05145_amd import binding as B
+        tr.cfg, tr.device, tr.dtype = dict(cfg), hidden.device, cfg["dtype"]
+        tr.ccfg = B.make_config(cfg)
+        tr.params = params
+        f32 = dict(dtype=torch.float32, device=hidden.device)
+        tr.grads = {k: torch.zeros(v.shape, **f32) for k, v in params.items()}
+        tr.m = {k: torch.zeros(v.shape, **f32) for k, v in params.items()}
+        tr.v = {k: torch.zeros(v.shape, **f32) for k, v in params.items()}
+        tr.master = {k: v.to(torch.float32) for k, v in params.items()} if cfg["dtype"] == "bf16" else None
+        tr.ws_bytes = B.tide_draft_workspace_bytes(tr.ccfg)
+        tr.workspace = torch.empty(tr.ws_bytes, dtype=torch.uint8, device=hidden.device)
+        tr.loss = torch.zeros(1, **f32)
+        tr.c_params, tr.c_grads = B.make_tensors(tr.params), B.make_tensors(tr.grads)
+        tr.c_adam = B.TideAdamState()
+        tr.c_adam.m, tr.c_adam.v, tr.c_adam.master = B.make_tensors(tr.m), B.make_tensors(tr.v), B.make_tensors(tr.master)
+        tr.c_adam.step = 0
+        tr.hidden, tr.tokens, tr.mask = hidden.contiguous(), tokens.contiguous(), mask.contiguous()
+        return tr
+
+
+def cpu_baseline(cfg, sample_batch, sample_seq):
+    """The fp64 oracle's train_step, as it stands, on a bounded slice of the same workload."""
+    import numpy as np
+    from oracle import tide_oracle as O
+    from paper_2602_05145_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    sc = dict(cfg, batch=sample_batch, seq=sample_seq)
+    wl = W.make_workload(sc)
+    zeros = {k: np.zeros(v.shape, np.float64) for k, v in wl["params"].items()}
+    t0 = time.perf_counter()
+    O.train_step(sc, wl["params"], zeros, zeros, 0, wl["hidden"], wl["tokens"], wl["mask"], sc["lr"])
+    dt = time.perf_counter() - t0
+    n = sample_batch * sample_seq
+    return {"value": n / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{cfg['name']} shape (d, F, V, heads as timed on the GPU) at batch {sample_batch} x seq {sample_seq} "
+                      f"= {n} positions, one fp64 NumPy train_step (fwd+bwd+AdamW over all {W.n_params(cfg)/1e6:.0f}M params) "
+                      f"in {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="8b", help="tiny | small | 8b | longctx | 32b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", default="1x256", help="batch x seq of the oracle's timed slice")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); run it with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_05145_amd import binding as B, workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = W.get_config(args.workload)
+    params, hidden, tokens, mask = device_workload(cfg, dev, cfg["seed"])
+    tr = DeviceTrainer(cfg, params, hidden, tokens, mask)
+    lr = cfg["lr"]
+    T = cfg["batch"] * cfg["seq"]
+
+    for _ in range(args.warmup):
+        tr.train_step(lr)
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; the library brackets each of its launches with HIP events on the
+    # stream it launches on, which gives the live per-kernel durations for the roofline entry
+    B.tide_profile_start()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tr.train_step(lr)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = B.tide_profile_stop()
+    loss = float(tr.loss.item())
+    assert loss == loss and loss > 0, f"bad loss {loss}"
+
+    ms = wall * 1e3 / args.steps
+    flops = W.flops_per_step(cfg)
+    prof.sort(key=lambda r: -r["total_ms"])
+    kernel_ms = sum(r["total_ms"] for r in prof)
+    dom = next(r for r in prof if r["flops"] > 0)
+    for r in prof:
+        if r["kernel"].startswith("gemm_mfma") and r["total_ms"] > dom["total_ms"]:
+            dom = r
+    dom_tflops = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                "launches_per_step": dom["launches"] / args.steps,
+                "avg_launch_ms": dom["total_ms"] / dom["launches"],
+                "flops_per_launch": dom["flops"] / dom["launches"]}
+    out = {
+        "metric": "draft-training tokens/sec (fwd+bwd+AdamW) and % bf16 MFMA peak, 1 MI355X",
+        "value": T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: batch {cfg['batch']} x seq {cfg['seq']}, 3x{cfg['target_hidden']} captured "
+                               f"states -> d {cfg['hidden']}, {cfg['n_heads']}/{cfg['n_kv_heads']} heads x {cfg['head_dim']}, "
+                               f"FFN {cfg['ffn']}, vocab {cfg['vocab']}", "global_batch": cfg["batch"], "seq_len": cfg["seq"],
+                   "params_M": W.n_params(cfg) / 1e6},
+        "tflops_per_step": flops / 1e12, "achieved_tflops": flops / (ms * 1e-3) / 1e12,
+        "mfu_vs_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "loss_last_step": loss,
+        "roofline": roofline,
+        "kernels": [{"kernel": r["kernel"], "ms_per_step": r["total_ms"] / args.steps,
+                     "launches_per_step": r["launches"] / args.steps,
+                     "tflops": (r["flops"] / (r["total_ms"] * 1e-3) / 1e12) if r["flops"] > 0 and r["total_ms"] > 0 else None,
+                     "gbs": (r["bytes"] / (r["total_ms"] * 1e-3) / 1e9) if r["bytes"] > 0 and r["total_ms"] > 0 else None}
+                    for r in prof],
+        "kernel_ms_per_step": kernel_ms / args.steps,
+    }
+    if not args.no_cpu_baseline:
+        del tr
+        torch.cuda.empty_cache()
+        sb, ss = (int(x) for x in args.cpu_sample.lower().split("x"))
+        out["cpu_baseline"] = cpu_baseline(cfg, sb, min(ss, cfg["seq"]))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

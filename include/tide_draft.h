@@ -196,6 +196,17 @@ int tide_attention_bwd(int B, int S, int n_heads, int n_kv_heads, int head_dim,
 int tide_rope(int B, int S, int n_heads, int n_kv_heads, int head_dim, float theta,
               void *qkv, float *table, int inverse, int dtype, void *stream);
 
+/* ---- Measurement support ----
+ * Between tide_profile_start and tide_profile_stop every kernel the library
+ * enqueues is bracketed by a pair of HIP events recorded on the caller's stream
+ * (a few microseconds of host time per launch; off by default).  tide_profile_stop
+ * waits for the recorded events and writes a JSON array to `report` (HOST buffer):
+ * one object per kernel with its launch count, summed duration in ms and summed
+ * algorithmic flops and bytes.  Returns TIDE_ERR_WORKSPACE if the buffer is too
+ * small (64 KiB is ample).  Not thread-safe against concurrent library calls. */
+int tide_profile_start(void);
+int tide_profile_stop(char *report, size_t report_bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,10 +84,16 @@ _lib.tide_attention_bwd.argtypes = [_i32] * 5 + [_vp, _vp, _vp, _vp, _vp, _vp, _
 _lib.tide_rope.restype = _i32
 _lib.tide_rope.argtypes = [_i32] * 5 + [_f32, _vp, _vp, _i32, _i32, _vp]
 
+_lib.tide_profile_start.restype = _i32
+_lib.tide_profile_start.argtypes = []
+_lib.tide_profile_stop.restype = _i32
+_lib.tide_profile_stop.argtypes = [C.c_char_p, _sz]
+
 EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
             "tide_draft_forward", "tide_draft_train_step", "tide_gemm_workspace_bytes", "tide_gemm",
             "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd",
-            "tide_attention_fwd", "tide_attention_bwd", "tide_rope")
+            "tide_attention_fwd", "tide_attention_bwd", "tide_rope", "tide_profile_start",
+            "tide_profile_stop")
 
 
 def tide_last_error() -> str:
@@ -189,3 +195,15 @@ def tide_attention_bwd(B, S, nh, nkv, dh, qkv, out, dout, lse, delta, dqkv, dtyp
 
 def tide_rope(B, S, nh, nkv, dh, theta, qkv, table, inverse, dtype, stream):
     return _check(_lib.tide_rope(B, S, nh, nkv, dh, float(theta), _ptr(qkv), _ptr(table), int(inverse), dtype, stream))
+
+
+def tide_profile_start():
+    return _check(_lib.tide_profile_start())
+
+
+def tide_profile_stop():
+    """Returns the per-kernel records as a list of dicts."""
+    import json
+    buf = C.create_string_buffer(1 << 16)
+    _check(_lib.tide_profile_stop(buf, len(buf)))
+    return json.loads(buf.value.decode())

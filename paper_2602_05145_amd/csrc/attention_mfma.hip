@@ -21,6 +21,7 @@
 // query heads of the group, so dK/dV are summed over the group in registers: no atomics, deterministic.
 // Causality: tiles entirely above the diagonal are never loaded; heavy blocks are scheduled first.
 #include "kernels.h"
+#include "prof.h"
 #include "tide_common.h"
 
 namespace tide {
@@ -499,6 +500,7 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
   hipError_t e = set_smem((const void*)attn_fwd_mfma_kernel, kFwdSmem, done);
   if (e != hipSuccess) return e;
   dim3 grid((a.S + BQ - 1) / BQ, a.nh, a.B);
+  ProfScope ps("attn_fwd_mfma", 2.0 * a.B * a.nh * D * (double)a.S * (a.S + 1), 0, s);
   hipLaunchKernelGGL(attn_fwd_mfma_kernel, grid, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv);
   return hipGetLastError();
 }
@@ -512,9 +514,14 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
   e = set_smem((const void*)attn_dkv_mfma_kernel, kDkvSmem, done_kv);
   if (e != hipSuccess) return e;
   dim3 gq((a.S + BQ - 1) / BQ, a.nh, a.B), gkv((a.S + 127) / 128, a.nkv, a.B);
-  hipLaunchKernelGGL(attn_dq_mfma_kernel, gq, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  const double pairs = (double)a.B * a.nh * D * (double)a.S * (a.S + 1) / 2.0;  // (query, key, channel) triples
+  {
+    ProfScope ps("attn_dq_mfma", 6.0 * pairs, 0, s);   // S, dP and dQ products
+    hipLaunchKernelGGL(attn_dq_mfma_kernel, gq, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  ProfScope ps("attn_dkv_mfma", 8.0 * pairs, 0, s);    // S, dP, dV and dK products
   hipLaunchKernelGGL(attn_dkv_mfma_kernel, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv);
   return hipGetLastError();
 }

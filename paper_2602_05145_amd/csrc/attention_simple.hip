@@ -6,6 +6,7 @@
 // Activation layout: qkv [B*S, (nh + 2 nkv) dh] with q heads first, then k heads, then v heads; query
 // head h reads kv head h / (nh / nkv).  lse[b, h, i] is the log-sum-exp of the scaled scores of row i.
 #include "kernels.h"
+#include "prof.h"
 #include "tide_common.h"
 
 namespace tide {
@@ -217,6 +218,7 @@ static bool simple_ok(const AttnArgs& a) {
 
 hipError_t launch_attn_fwd_simple(const AttnArgs& a, hipStream_t s) {
   if (!simple_ok(a)) return hipErrorInvalidValue;
+  ProfScope ps("attn_fwd_simple", 2.0 * a.B * a.nh * a.dh * (double)a.S * (a.S + 1), 0, s);
   dim3 grid(a.S, a.nh, a.B), blk(64);
   if (a.dtype == kBF16) hipLaunchKernelGGL(attn_fwd_simple_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv, a.dh);
   else hipLaunchKernelGGL(attn_fwd_simple_kernel<float>, grid, blk, 0, s, (const float*)a.qkv, (float*)a.out, a.lse, a.S, a.nh, a.nkv, a.dh);
@@ -224,6 +226,7 @@ hipError_t launch_attn_fwd_simple(const AttnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_attn_delta(const AttnArgs& a, hipStream_t s) {
+  ProfScope ps("attn_delta", 0, 2.0 * a.B * a.S * a.nh * a.dh * dtype_size(a.dtype), s);
   dim3 grid(a.S, a.nh, a.B), blk(64);
   if (a.dtype == kBF16) hipLaunchKernelGGL(attn_delta_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)a.out, (const bf16_t*)a.dout, a.delta, a.S, a.nh, a.dh);
   else hipLaunchKernelGGL(attn_delta_kernel<float>, grid, blk, 0, s, (const float*)a.out, (const float*)a.dout, a.delta, a.S, a.nh, a.dh);
@@ -234,6 +237,7 @@ hipError_t launch_attn_bwd_simple(const AttnArgs& a, hipStream_t s) {
   if (!simple_ok(a)) return hipErrorInvalidValue;
   hipError_t e = launch_attn_delta(a, s);
   if (e != hipSuccess) return e;
+  ProfScope ps("attn_bwd_simple", 7.0 * a.B * a.nh * a.dh * (double)a.S * (a.S + 1), 0, s);
   dim3 gq(a.S, a.nh, a.B), gk(a.S, a.nkv, a.B), blk(64);
   if (a.dtype == kBF16) {
     hipLaunchKernelGGL(attn_dq_simple_kernel<bf16_t>, gq, blk, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.dh);

@@ -3,6 +3,7 @@
 // All are coalesced 16-byte-per-lane streaming kernels with 64-wide wavefront reductions; arithmetic is
 // fp32 whatever the storage type.
 #include "kernels.h"
+#include "prof.h"
 #include "tide_common.h"
 
 namespace tide {
@@ -29,6 +30,7 @@ __global__ __launch_bounds__(1024) void count_valid_kernel(const int32_t* __rest
 
 hipError_t launch_count_valid(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, float* scal,
                               hipStream_t s) {
+  ProfScope ps("count_valid", 0, 5.0 * (double)T, s);
   hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, tokens, mask, T, V, scal);
   return hipGetLastError();
 }
@@ -79,6 +81,7 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ 
 hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g, float eps, void* y,
                               float* rstd, int dtype, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
+  ProfScope ps("rmsnorm_fwd", 0, (double)rows * d * 2.0 * dtype_size(dtype) + 4.0 * rows, s);
   dim3 grid((unsigned)rows), blk(256);
   const bool vec = (d % 8) == 0;
   if (dtype == kBF16) {
@@ -212,6 +215,7 @@ hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x
   if (rows <= 0) return hipSuccess;
   const bool vec = (d % 8) == 0 && d <= 8192;
   if (!vec && d > 1024) return hipErrorInvalidValue;
+  ProfScope ps("rmsnorm_bwd", 0, (double)rows * d * (res ? 4.0 : 3.0) * dtype_size(dtype) + 4.0 * rows, s);
   const int64_t nblk = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
   dim3 grid((unsigned)nblk), blk(256);
   if (dtype == kBF16) {
@@ -277,6 +281,7 @@ hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, v
   if (total <= 0) return hipSuccess;
   dim3 grid((unsigned)((total + 255) / 256)), blk(256);
   const float sgn = inverse ? -1.f : 1.f;
+  ProfScope ps("rope", 0, (double)total * 4.0 * dtype_size(dtype), s);
   if (dtype == kBF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total);
   else hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total);
   return hipGetLastError();
@@ -336,6 +341,7 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ d
 
 hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  ProfScope ps("swiglu_fwd", 0, (double)n * 3.0 * dtype_size(dtype), s);
   dim3 grid((unsigned)((n + 2047) / 2048)), blk(256);
   if (dtype == kBF16) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)gt, (const bf16_t*)u, (bf16_t*)h, n);
   else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, grid, blk, 0, s, (const float*)gt, (const float*)u, (float*)h, n);
@@ -345,6 +351,7 @@ hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, 
 hipError_t launch_swiglu_bwd(int64_t n, const void* dh, const void* gt, const void* u, void* dgt, void* du,
                              int dtype, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  ProfScope ps("swiglu_bwd", 0, (double)n * 5.0 * dtype_size(dtype), s);
   dim3 grid((unsigned)((n + 2047) / 2048)), blk(256);
   if (dtype == kBF16) hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)dh, (const bf16_t*)gt, (const bf16_t*)u, (bf16_t*)dgt, (bf16_t*)du, n);
   else hipLaunchKernelGGL(swiglu_bwd_kernel<float>, grid, blk, 0, s, (const float*)dh, (const float*)gt, (const float*)u, (float*)dgt, (float*)du, n);
@@ -438,6 +445,7 @@ hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, cons
                            hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   dim3 grid((unsigned)rows), blk(256);
+  ProfScope ps("ce_stats", 0, (double)rows * V * dtype_size(dtype), s);
   if (dtype == kBF16) {
     if (top1) hipLaunchKernelGGL((ce_stats_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
     else hipLaunchKernelGGL((ce_stats_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
@@ -476,6 +484,7 @@ hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t
                         const uint8_t* mask, const float* lse, int dtype, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (ldz % 8 != 0) return hipErrorInvalidValue;
+  ProfScope ps("ce_dz", 0, (double)rows * ldz * 2.0 * dtype_size(dtype), s);
   dim3 grid((unsigned)((ldz + 2047) / 2048), (unsigned)rows), blk(256);
   if (dtype == kBF16) hipLaunchKernelGGL(ce_dz_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)z, ldz, V, tokens, mask, lse);
   else hipLaunchKernelGGL(ce_dz_kernel<float>, grid, blk, 0, s, (float*)z, ldz, V, tokens, mask, lse);
@@ -572,6 +581,9 @@ hipError_t launch_adamw(const AdamArgs& a, hipStream_t s) {
   d.decay = 1.0f - a.lr * a.wd;
   d.inv_bc1 = a.inv_bc1; d.inv_sqrt_bc2 = a.inv_sqrt_bc2;
   if (nb <= 0) return hipSuccess;
+  double np_ = 0;
+  for (int i = 0; i < a.nt; ++i) np_ += (double)a.t[i].n;
+  ProfScope ps("adamw", 0, np_ * (a.dtype == kBF16 ? 30.0 : 28.0), s);
   if (a.dtype == kBF16) hipLaunchKernelGGL(adamw_kernel<bf16_t>, dim3((unsigned)nb), dim3(256), 0, s, d);
   else hipLaunchKernelGGL(adamw_kernel<float>, dim3((unsigned)nb), dim3(256), 0, s, d);
   return hipGetLastError();

@@ -23,6 +23,7 @@
 //     range of tiles, walked in groups of 8 tile-rows, which keeps the A/B panels of neighbouring tiles
 //     in that XCD's L2.
 #include "kernels.h"
+#include "prof.h"
 #include "tide_common.h"
 
 namespace tide {
@@ -370,7 +371,24 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
+static const char* gemm_kernel_name(const GemmArgs& a) {
+  if (!gemm_mfma_supported(a)) return "gemm_simple";
+  const bool big = ((a.M + 255) / 256) * ((a.N + 255) / 256) >= 200;
+  const bool f32 = a.out_dtype == kF32;
+  switch (a.layout) {
+    case kNT: return big ? (f32 ? "gemm_mfma_nt_256_f32out" : "gemm_mfma_nt_256_bf16out") : (f32 ? "gemm_mfma_nt_128_f32out" : "gemm_mfma_nt_128_bf16out");
+    case kNN: return big ? (f32 ? "gemm_mfma_nn_256_f32out" : "gemm_mfma_nn_256_bf16out") : (f32 ? "gemm_mfma_nn_128_f32out" : "gemm_mfma_nn_128_bf16out");
+    default: return big ? (f32 ? "gemm_mfma_tn_256_f32out" : "gemm_mfma_tn_256_bf16out") : (f32 ? "gemm_mfma_tn_128_f32out" : "gemm_mfma_tn_128_bf16out");
+  }
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
+  // algorithmic work of the call, for the optional profiler
+  const double k = (double)a.K + (a.A2 ? (double)a.K2 : 0.0);
+  const double es_in = (double)dtype_size(a.in_dtype), es_out = (double)dtype_size(a.out_dtype);
+  const double bytes = es_in * k * ((double)a.M + (double)a.N) +
+                       es_out * (double)a.M * (double)a.N * (1.0 + (a.accumulate ? 1.0 : 0.0) + (a.residual ? 1.0 : 0.0));
+  ProfScope ps(gemm_kernel_name(a), 2.0 * (double)a.M * (double)a.N * k, bytes, s);
   if (gemm_mfma_supported(a)) return launch_gemm_mfma(a, s);
   return launch_gemm_simple(a, s);
 }

@@ -8,7 +8,12 @@
 #include <cstdio>
 #include <cstring>
 
+#include <mutex>
+#include <string>
+#include <vector>
+
 #include "kernels.h"
+#include "prof.h"
 
 using namespace tide;
 
@@ -438,6 +443,85 @@ int tide_rope(int B, int S, int nh, int nkv, int dh, float theta, void* qkv, flo
   if (B <= 0 || S <= 0 || nh <= 0 || nkv <= 0 || dh <= 0 || dh % 2) return fail(TIDE_ERR_CONFIG, "bad rope shape");
   TIDE_HIP(launch_rope_table(S, dh, theta, table, (hipStream_t)stream), "rope table");
   TIDE_HIP(launch_rope(B, S, nh, nkv, dh, table, qkv, inverse, dtype, (hipStream_t)stream), "rope");
+  return TIDE_OK;
+}
+
+}  // extern "C"
+
+// ---- optional per-launch profiler (prof.h) --------------------------------------------------------
+namespace tide {
+namespace {
+struct ProfRec { const char* name; double flops, bytes; hipEvent_t e0, e1; };
+struct Profiler {
+  std::mutex mu;
+  bool on = false;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+Profiler g_prof;
+}  // namespace
+
+bool prof_enabled() { return g_prof.on; }
+
+void prof_begin(const char* kernel, double flops, double bytes, hipStream_t s) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  ProfRec r{kernel, flops, bytes, g_prof.get(), g_prof.get()};
+  if (r.e0) (void)hipEventRecord(r.e0, s);
+  g_prof.recs.push_back(r);
+}
+
+void prof_end(hipStream_t s) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  if (!g_prof.recs.empty() && g_prof.recs.back().e1) (void)hipEventRecord(g_prof.recs.back().e1, s);
+}
+}  // namespace tide
+
+extern "C" {
+
+int tide_profile_start(void) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  for (auto& r : g_prof.recs) { if (r.e0) g_prof.pool.push_back(r.e0); if (r.e1) g_prof.pool.push_back(r.e1); }
+  g_prof.recs.clear();
+  g_prof.on = true;
+  return TIDE_OK;
+}
+
+int tide_profile_stop(char* report, size_t report_bytes) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  g_prof.on = false;
+  struct Agg { const char* name; long n; double ms, flops, bytes; };
+  std::vector<Agg> agg;
+  for (auto& r : g_prof.recs) {
+    float ms = 0.f;
+    if (r.e0 && r.e1) {
+      hipError_t e = hipEventSynchronize(r.e1);
+      if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.e0, r.e1);
+      if (e != hipSuccess) return hip_fail(e, "profile events");
+    }
+    Agg* a = nullptr;
+    for (auto& x : agg) if (std::strcmp(x.name, r.name) == 0) { a = &x; break; }
+    if (!a) { agg.push_back(Agg{r.name, 0, 0, 0, 0}); a = &agg.back(); }
+    a->n += 1; a->ms += ms; a->flops += r.flops; a->bytes += r.bytes;
+    if (r.e0) g_prof.pool.push_back(r.e0);
+    if (r.e1) g_prof.pool.push_back(r.e1);
+  }
+  g_prof.recs.clear();
+  std::string out = "[";
+  char line[512];
+  for (size_t i = 0; i < agg.size(); ++i) {
+    snprintf(line, sizeof(line), "%s{\"kernel\": \"%s\", \"launches\": %ld, \"total_ms\": %.6f, \"flops\": %.6e, \"bytes\": %.6e}",
+             i ? ", " : "", agg[i].name, agg[i].n, agg[i].ms, agg[i].flops, agg[i].bytes);
+    out += line;
+  }
+  out += "]";
+  if (!report || report_bytes < out.size() + 1) return fail(TIDE_ERR_WORKSPACE, "profile report needs %zu bytes", out.size() + 1);
+  std::memcpy(report, out.c_str(), out.size() + 1);
   return TIDE_OK;
 }
 
