@@ -4,24 +4,41 @@
 //   TN  C = A[K,M]^T B[K,N]   weight gradients dW = dY^T X  (both operands contracted over rows)
 //
 // Design
-//   * One 256-thread block (4 wavefronts, 2x2) computes a BM x BN tile (256x256 or 128x128) with
-//     v_mfma_f32_32x32x16_bf16; each wave owns a (BM/2)x(BN/2) sub-tile = TMxTN MFMA tiles.
-//   * K is walked in slabs of 64.  Slabs go global -> registers (buffer loads, 16 B per lane, hardware
-//     zero-fill outside the tile's valid extent, so ragged M/N/K need no special code) -> LDS, double
-//     buffered: the loads of slab k+1 are in flight while the MFMAs of slab k run.
-//   * An operand whose contraction index is contiguous in memory ("K-major") is kept as [row][k] in LDS
-//     (row pitch 64+8 elements: conflict-free 16-byte reads) and fetched as one 16-byte read per MFMA
-//     operand.  An operand whose contraction index is the slow one ("row-major over K", the B of NN and
-//     both operands of TN) is kept exactly as in memory, [k][row], and transposed on the way to the
-//     MFMA: each lane reads TM consecutive rows for 8 consecutive k (8 narrow LDS reads) and regroups
-//     the 16-bit halves with v_perm_b32.  The MFMA tile i of a wave then covers rows {TM*r + i}, an
-//     interleaving the epilogue undoes.  No transposed copy of any operand is ever written to HBM.
-//   * The contraction may run over two operand pairs back to back (used for
-//     d b = dGate W_gate + dUp W_up), and the epilogue fuses alpha (host and device scalar), a
-//     residual add, accumulation into C, and the output cast.
+//   * A block computes a BM x BN tile (256x256 with 8 wavefronts = 2 per SIMD, or 128x128 with 4) with
+//     v_mfma_f32_32x32x16_bf16; a wave owns TM x TN MFMA tiles (4x2 or 2x2).  Two waves per SIMD matter:
+//     one wave alone cannot issue MFMAs back to back (measured ~83 % of the multi-wave MFMA rate).
+//   * K is walked in slabs of 32 through a ring of FOUR LDS stages that are filled by LDS-DMA buffer loads
+//     (global -> LDS without passing through registers, hardware zero-fill outside the valid extent, so
+//     ragged M / N / K need no special code).  The loads of slab k+3 are issued while slab k is being
+//     multiplied, which covers the ~2 us loaded-HBM latency that a two-stage register-staged pipeline
+//     could not (that version waited ~50 % of its cycles).
+//   * Synchronisation is manual: one `s_waitcnt vmcnt(n)` (own DMA of the next slab has landed; two younger
+//     slabs stay in flight) and one `s_barrier` per slab, placed between the two k16 halves of a slab so
+//     that the operand reads of the next slab are issued under the MFMAs of the current one.  Each stage
+//     is its own __shared__ array: the compiler can then tell that the operand reads do not alias the
+//     DMA writes in flight and does not drain vmcnt before them.  Slabs past K are dummies (their loads
+//     fall outside the buffer and zero-fill a free stage) so the steady state has no branches.
+//   * Instruction order inside a half-slab is pinned with sched_group_barrier: MFMA / LDS read (or DMA
+//     issue) alternate, so LDS and address traffic hides in the MFMA shadow.
+//   * LDS layout.  A "K-major" operand (contraction index contiguous in memory) is stored [row][32] with
+//     the four 16-byte pieces of a row XOR-swizzled by (row >> 2) & 3: DMA can only write 1 KiB
+//     contiguous per instruction, so padding is impossible, and the swizzle makes the 16-byte operand
+//     reads of 16 consecutive rows hit 16 different bank groups.  An operand whose contraction index is
+//     the slow one (B of NN, both operands of TN) is stored exactly as in memory, [k][row], and
+//     transposed on the way to the MFMA: each lane reads T consecutive rows for 8 consecutive k (8 narrow
+//     LDS reads) and regroups the 16-bit halves with v_perm_b32; MFMA tile i of a wave then covers rows
+//     {T*r + i}, an interleaving the epilogue undoes.  No transposed copy of an operand ever exists in HBM.
+//   * The contraction may run over two operand pairs back to back (d b = dGate W_gate + dUp W_up), and
+//     the epilogue fuses alpha (host and device scalar), a residual add, accumulation into C and the cast.
+//     When B is N-contiguous a lane owns TN consecutive output columns and stores them as one vector;
+//     NT results without residual/accumulate go through a wave-private LDS patch to leave as 16-byte
+//     row segments.
 //   * Work-groups are renumbered so that each of the 8 XCDs (round-robin dispatch) gets a contiguous
-//     range of tiles, walked in groups of 8 tile-rows, which keeps the A/B panels of neighbouring tiles
-//     in that XCD's L2.
+//     range of tiles, walked in groups of 8 tile-rows: neighbouring tiles share A/B panels in that
+//     XCD's L2.
+#include <type_traits>
+#include <utility>
+
 #include "kernels.h"
 #include "prof.h"
 #include "tide_common.h"
@@ -30,11 +47,13 @@ namespace tide {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
-typedef int i32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_vp;
 
-constexpr int BK = 64;
-constexpr int KPAD = 8;  // LDS row padding in elements (16 bytes)
+namespace {
+
+constexpr int BK = 32;    // K per LDS stage
+constexpr int NST = 4;    // LDS stages
 
 struct MfmaParams {
   const bf16_t* A; const bf16_t* B; const bf16_t* A2; const bf16_t* B2;
@@ -50,24 +69,151 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
-template <int BM, int BN, bool AMM, bool BNM, typename TO>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaParams p) {
-  constexpr int WM = BM / 2, WN = BN / 2;
+// wait until at most n of this wave's vector-memory operations are outstanding (vmcnt only)
+#define TIDE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+constexpr uint32_t kOobOffset = 0x7FFFFFF0u;  // beyond any buffer extent used here: the load returns zeros
+
+// One operand (A or B) of one block: R rows (BM or BN) of the tile, either K-major or row-major over K.
+template <int R, int NW, bool RMAJ, int T>   // T = MFMA tiles per wave along this dimension
+struct Operand {
+  static constexpr int STAGE = R * BK;                                   // elements per stage
+  static constexpr int CHUNKS = STAGE * 2 / 1024;                        // 1 KiB DMA instructions per stage
+  static constexpr int PER_WAVE = CHUNKS / NW;
+  static_assert(CHUNKS % NW == 0 && PER_WAVE >= 1, "DMA chunks must split evenly over the waves");
+  static constexpr int PPR = R / 8;                                      // 16-byte pieces per k-row (row-major)
+  static constexpr int RPC = 64 / PPR;                                   // k-rows per DMA chunk (row-major)
+  static constexpr int kReadsPerHalf = RMAJ ? 8 : T;                     // LDS read instructions per k16 half
+
+  // Stateless on purpose: the tile pointers and extents stay plain kernel locals (SGPRs).  Bundling them
+  // in a struct with the per-lane offsets made the compiler keep that struct in scratch memory, the
+  // buffer descriptors then lived in VGPRs and every DMA load became a waterfall loop.
+
+  // per-lane byte offsets of this wave's DMA chunks, without the k0 term; K-major also yields the 16-byte
+  // piece of a row that this lane fetches (swizzled)
+  static __device__ __forceinline__ void lane_offsets(int ld, int wave, int lane, uint32_t (&off)[PER_WAVE], int& piece) {
+    if (RMAJ) {
+      const int kr = lane / PPR, pc = lane % PPR;
+#pragma unroll
+      for (int i = 0; i < PER_WAVE; ++i)
+        off[i] = (uint32_t)((((wave * PER_WAVE + i) * RPC + kr) * ld + pc * 8) * 2);
+      piece = 0;
+    } else {
+      const int drow = lane >> 2, slot = lane & 3;
+      piece = slot ^ ((drow >> 2) & 3);
+#pragma unroll
+      for (int i = 0; i < PER_WAVE; ++i)
+        off[i] = (uint32_t)((((wave * PER_WAVE + i) * 16 + drow) * ld + piece * 8) * 2);
+    }
+  }
+
+  // Issue the DMA loads of the slab [k0, k0+32) into `stage`.  tile = operand pointer already offset to
+  // the tile's first row (K-major) or first column (row-major); rows_valid = tile rows inside the matrix
+  // (K-major) ; cols_left = matrix columns from the tile's first column on (row-major); Kc = contraction
+  // length.  A slab with k0 >= Kc is a dummy: every load is out of range and writes zeros.
+  static __device__ __forceinline__ void issue(bf16_t* stage, const bf16_t* tile, int ld, int rows_valid, int cols_left,
+                                               int k0, int Kc, const uint32_t (&off)[PER_WAVE], int piece, int wave) {
+    if (RMAJ) {
+      const int kv = min(BK, Kc - k0);   // valid k-rows of this slab (<= 0 for a dummy slab)
+      const bf16_t* base = tile + (size_t)(kv > 0 ? k0 : 0) * ld;
+      const uint32_t bytes = kv > 0 ? (uint32_t)(((int64_t)(kv - 1) * ld + cols_left) * 2) : 0u;
+      const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, bytes);
+#pragma unroll
+      for (int i = 0; i < PER_WAVE; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_vp)(stage + (wave * PER_WAVE + i) * 512), 16, off[i], 0, 0, 0);
+    } else {
+      const uint32_t bytes = (uint32_t)(((int64_t)(rows_valid - 1) * ld + Kc) * 2);
+      const __amdgpu_buffer_rsrc_t rs = make_rsrc(tile, bytes);
+      const bool kin = (k0 + piece * 8) < Kc;
+#pragma unroll
+      for (int i = 0; i < PER_WAVE; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_vp)(stage + (wave * PER_WAVE + i) * 512), 16,
+                                                 kin ? off[i] + (uint32_t)(k0 * 2) : kOobOffset, 0, 0, 0);
+    }
+  }
+
+  // MFMA operand fragments of k16 half `kk` for the wave whose first tile row is wbase
+  static __device__ __forceinline__ void frags(const bf16_t* stage, int kk, int wbase, int lr, int lg, u32x4_t (&f)[T]) {
+    if (RMAJ) {
+      const bf16_t* src = stage + (kk * 16 + lg * 8) * R + wbase + T * lr;
+      if (T == 4) {
+        uint2 r[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const uint2*>(src + j * R);
+#pragma unroll
+        for (int i = 0; i < T; ++i)
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const uint32_t lo = (i < 2) ? r[2 * w].x : r[2 * w].y;
+            const uint32_t hi = (i < 2) ? r[2 * w + 1].x : r[2 * w + 1].y;
+            f[i][w] = __builtin_amdgcn_perm(hi, lo, (i & 1) ? 0x07060302u : 0x05040100u);
+          }
+      } else {
+        uint32_t r[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const uint32_t*>(src + j * R);
+#pragma unroll
+        for (int i = 0; i < T; ++i)
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            f[i][w] = __builtin_amdgcn_perm(r[2 * w + 1], r[2 * w], (i & 1) ? 0x07060302u : 0x05040100u);
+      }
+    } else {
+      const int sw = (lr >> 2) & 3;
+      const bf16_t* src = stage + (wbase + lr) * BK + (((kk * 2 + lg) ^ sw) * 8);
+#pragma unroll
+      for (int i = 0; i < T; ++i) f[i] = *reinterpret_cast<const u32x4_t*>(src + i * 32 * BK);
+    }
+  }
+};
+
+template <int N>
+struct Int : std::integral_constant<int, N> {};
+
+// Pin the instruction order of one k16 half: after MFMA number I come its share of the NDS LDS reads
+// and, for the last NVM MFMAs of a first half, one DMA issue each.
+template <int I, int NMF, int NDS, int NVM, int SYNC, bool WITH_DMA>
+__device__ __forceinline__ void sched_slot() {
+  __builtin_amdgcn_sched_group_barrier(0x008, 1, SYNC);   // MFMA
+  constexpr int nds = NDS / NMF + (I < NDS % NMF ? 1 : 0);
+  if constexpr (nds > 0) __builtin_amdgcn_sched_group_barrier(0x100, nds, SYNC);   // LDS reads
+  if constexpr (WITH_DMA && I >= NMF - NVM) __builtin_amdgcn_sched_group_barrier(0x020, 1, SYNC);   // DMA issue
+}
+template <int NMF, int NDS, int NVM, int SYNC, bool WITH_DMA, int... I>
+__device__ __forceinline__ void sched_slots(std::integer_sequence<int, I...>) {
+  (sched_slot<I, NMF, NDS, NVM, SYNC, WITH_DMA>(), ...);
+}
+
+}  // namespace
+
+template <int BM, int BN, int NW, bool AMM, bool BNM, typename TO>
+__global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
+  constexpr int WAVES_N = (NW == 8) ? 4 : 2, WAVES_M = NW / WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int A_PITCH = AMM ? (BM + KPAD) : (BK + KPAD);
-  constexpr int B_PITCH = BNM ? (BN + KPAD) : (BK + KPAD);
-  constexpr int A_STAGE = AMM ? BK * A_PITCH : BM * A_PITCH;  // elements
-  constexpr int B_STAGE = BNM ? BK * B_PITCH : BN * B_PITCH;
-  constexpr int NLA = BM * BK / 8 / 256;  // 16-byte pieces per thread per slab
-  constexpr int NLB = BN * BK / 8 / 256;
+  static_assert(TM == 4 || TM == 2, "wave tile height must be 128 or 64");
+  static_assert(TN == 4 || TN == 2, "wave tile width must be 128 or 64");
+  using OpA = Operand<BM, NW, AMM, TM>;
+  using OpB = Operand<BN, NW, BNM, TN>;
+  constexpr int A_STAGE = OpA::STAGE, B_STAGE = OpB::STAGE;
+  constexpr int NVM = OpA::PER_WAVE + OpB::PER_WAVE;            // DMA instructions per wave per slab
+  constexpr int NDS = OpA::kReadsPerHalf + OpB::kReadsPerHalf;  // LDS reads per wave per k16 half
+  constexpr int NMF = TM * TN;                                  // MFMAs per wave per k16 half
+  static_assert(NVM <= NMF, "one DMA issue per MFMA slot at most");
 
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  bf16_t* sA = smem;                 // [2][A_STAGE]
-  bf16_t* sB = smem + 2 * A_STAGE;   // [2][B_STAGE]
+  __shared__ __attribute__((aligned(1024))) bf16_t s0[A_STAGE + B_STAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t s1[A_STAGE + B_STAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t s2[A_STAGE + B_STAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t s3[A_STAGE + B_STAGE];
+  auto stage = [&](auto ST) -> bf16_t* {
+    if constexpr (decltype(ST)::value == 0) return s0;
+    else if constexpr (decltype(ST)::value == 1) return s1;
+    else if constexpr (decltype(ST)::value == 2) return s2;
+    else return s3;
+  };
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave >> 1, wave_n = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
   const int lr = lane & 31, lg = lane >> 5;
 
   // ---- XCD-aware tile numbering ----
@@ -89,6 +235,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaParams p) {
   }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
+  // tile pointers of both operand pairs (uniform) and this lane's DMA offsets
+  const bf16_t* a_tile0 = AMM ? p.A + m0 : p.A + (size_t)m0 * p.lda;
+  const bf16_t* b_tile0 = BNM ? p.B + n0 : p.B + (size_t)n0 * p.ldb;
+  const bf16_t* a_tile1 = p.A2 ? (AMM ? p.A2 + m0 : p.A2 + (size_t)m0 * p.lda) : a_tile0;
+  const bf16_t* b_tile1 = p.B2 ? (BNM ? p.B2 + n0 : p.B2 + (size_t)n0 * p.ldb) : b_tile0;
+  const int a_rows = min(BM, p.M - m0), b_rows = min(BN, p.N - n0);
+  uint32_t a_off[OpA::PER_WAVE], b_off[OpB::PER_WAVE];
+  int a_piece, b_piece;
+  OpA::lane_offsets(p.lda, wave, lane, a_off, a_piece);
+  OpB::lane_offsets(p.ldb, wave, lane, b_off, b_piece);
+
   f32x16_t acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -100,212 +257,175 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaParams p) {
   const int nk1 = (p.K + BK - 1) / BK;
   const int nk2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
   const int nk = nk1 + nk2;
+  const int nk4 = (nk + 3) & ~3;   // slabs nk .. nk4+2 are dummies
 
-  i32x4_t ra[NLA], rb[NLB];
-
-  // global -> registers for slab kt
-  auto gload = [&](int kt) {
-    const bool second = kt >= nk1;
-    const bf16_t* Ab = second ? p.A2 : p.A;
-    const bf16_t* Bb = second ? p.B2 : p.B;
-    const int Kc = second ? p.K2 : p.K;
-    const int k0 = (second ? kt - nk1 : kt) * BK;
-    if (AMM) {
-      constexpr int PPR = BM / 8;        // pieces per k-row
-      constexpr int RSTEP = 256 / PPR;   // k-rows covered per pass
-      const int rows_valid = min(BK, Kc - k0);
-      const bf16_t* base = Ab + (size_t)k0 * p.lda + m0;
-      const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, (uint32_t)(((int64_t)(rows_valid - 1) * p.lda + (p.M - m0)) * 2));
-      const int piece = tid % PPR, kr = tid / PPR;
-#pragma unroll
-      for (int i = 0; i < NLA; ++i)
-        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (uint32_t)(((kr + i * RSTEP) * p.lda + piece * 8) * 2), 0, 0);
-    } else {
-      const int rows_valid = min(BM, p.M - m0);
-      const bf16_t* base = Ab + (size_t)m0 * p.lda;
-      const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, (uint32_t)(((int64_t)(rows_valid - 1) * p.lda + Kc) * 2));
-      const int piece = tid & 7, row = tid >> 3;
-      const int kc = k0 + piece * 8;
-#pragma unroll
-      for (int i = 0; i < NLA; ++i) {
-        uint32_t off = (uint32_t)(((row + i * 32) * p.lda + kc) * 2);
-        if (kc >= Kc) off = 0x7FFFFFF0u;
-        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
-      }
+  auto issue = [&](auto ST, int kt) {
+    bf16_t* sb = stage(ST);
+    int pr = 0, k0 = kt * BK, Kc = p.K;
+    if (kt >= nk1) {
+      if (kt < nk) { pr = 1; k0 = (kt - nk1) * BK; Kc = p.K2; }
+      else { k0 = p.K + BK; }   // dummy slab: everything out of range
     }
-    if (BNM) {
-      constexpr int PPR = BN / 8;
-      constexpr int RSTEP = 256 / PPR;
-      const int rows_valid = min(BK, Kc - k0);
-      const bf16_t* base = Bb + (size_t)k0 * p.ldb + n0;
-      const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, (uint32_t)(((int64_t)(rows_valid - 1) * p.ldb + (p.N - n0)) * 2));
-      const int piece = tid % PPR, kr = tid / PPR;
-#pragma unroll
-      for (int i = 0; i < NLB; ++i)
-        rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (uint32_t)(((kr + i * RSTEP) * p.ldb + piece * 8) * 2), 0, 0);
-    } else {
-      const int rows_valid = min(BN, p.N - n0);
-      const bf16_t* base = Bb + (size_t)n0 * p.ldb;
-      const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, (uint32_t)(((int64_t)(rows_valid - 1) * p.ldb + Kc) * 2));
-      const int piece = tid & 7, row = tid >> 3;
-      const int kc = k0 + piece * 8;
-#pragma unroll
-      for (int i = 0; i < NLB; ++i) {
-        uint32_t off = (uint32_t)(((row + i * 32) * p.ldb + kc) * 2);
-        if (kc >= Kc) off = 0x7FFFFFF0u;
-        rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
-      }
-    }
+    OpA::issue(sb, pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc, a_off, a_piece, wave);
+    OpB::issue(sb + A_STAGE, pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc, b_off, b_piece, wave);
   };
-
-  // registers -> LDS stage st
-  auto sstore = [&](int st) {
-    bf16_t* a = sA + st * A_STAGE;
-    bf16_t* b = sB + st * B_STAGE;
-    if (AMM) {
-      constexpr int PPR = BM / 8;
-      constexpr int RSTEP = 256 / PPR;
-      const int piece = tid % PPR, kr = tid / PPR;
-#pragma unroll
-      for (int i = 0; i < NLA; ++i)
-        *reinterpret_cast<i32x4_t*>(a + (kr + i * RSTEP) * A_PITCH + piece * 8) = ra[i];
-    } else {
-      const int piece = tid & 7, row = tid >> 3;
-#pragma unroll
-      for (int i = 0; i < NLA; ++i)
-        *reinterpret_cast<i32x4_t*>(a + (row + i * 32) * A_PITCH + piece * 8) = ra[i];
-    }
-    if (BNM) {
-      constexpr int PPR = BN / 8;
-      constexpr int RSTEP = 256 / PPR;
-      const int piece = tid % PPR, kr = tid / PPR;
-#pragma unroll
-      for (int i = 0; i < NLB; ++i)
-        *reinterpret_cast<i32x4_t*>(b + (kr + i * RSTEP) * B_PITCH + piece * 8) = rb[i];
-    } else {
-      const int piece = tid & 7, row = tid >> 3;
-#pragma unroll
-      for (int i = 0; i < NLB; ++i)
-        *reinterpret_cast<i32x4_t*>(b + (row + i * 32) * B_PITCH + piece * 8) = rb[i];
-    }
+  auto frags = [&](auto ST, int kk, u32x4_t (&fa)[TM], u32x4_t (&fb)[TN]) {
+    const bf16_t* sb = stage(ST);
+    OpA::frags(sb, kk, wave_m * WM, lr, lg, fa);
+    OpB::frags(sb + A_STAGE, kk, wave_n * WN, lr, lg, fb);
   };
-
-  // LDS -> MFMA operand fragments for k16 step kk of stage st
-  auto frag_load = [&](int st, int kk, u32x4_t (&fa)[TM], u32x4_t (&fb)[TN]) {
-    const bf16_t* a = sA + st * A_STAGE;
-    const bf16_t* b = sB + st * B_STAGE;
-    if (AMM) {
-      const bf16_t* src = a + (kk * 16 + lg * 8) * A_PITCH + wave_m * WM + TM * lr;
-      if (TM == 4) {
-        uint2 r[8];
+  auto mma = [&](u32x4_t (&fa)[TM], u32x4_t (&fb)[TN]) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const uint2*>(src + j * A_PITCH);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const uint32_t lo = (i < 2) ? r[2 * w].x : r[2 * w].y;
-            const uint32_t hi = (i < 2) ? r[2 * w + 1].x : r[2 * w + 1].y;
-            fa[i][w] = __builtin_amdgcn_perm(hi, lo, (i & 1) ? 0x07060302u : 0x05040100u);
-          }
-      } else {
-        uint32_t r[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const uint32_t*>(src + j * A_PITCH);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int w = 0; w < 4; ++w)
-            fa[i][w] = __builtin_amdgcn_perm(r[2 * w + 1], r[2 * w], (i & 1) ? 0x07060302u : 0x05040100u);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = *reinterpret_cast<const u32x4_t*>(a + (wave_m * WM + 32 * i + lr) * A_PITCH + kk * 16 + lg * 8);
-    }
-    if (BNM) {
-      const bf16_t* src = b + (kk * 16 + lg * 8) * B_PITCH + wave_n * WN + TN * lr;
-      if (TN == 4) {
-        uint2 r[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const uint2*>(src + j * B_PITCH);
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const uint32_t lo = (i < 2) ? r[2 * w].x : r[2 * w].y;
-            const uint32_t hi = (i < 2) ? r[2 * w + 1].x : r[2 * w + 1].y;
-            fb[i][w] = __builtin_amdgcn_perm(hi, lo, (i & 1) ? 0x07060302u : 0x05040100u);
-          }
-      } else {
-        uint32_t r[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const uint32_t*>(src + j * B_PITCH);
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-#pragma unroll
-          for (int w = 0; w < 4; ++w)
-            fb[i][w] = __builtin_amdgcn_perm(r[2 * w + 1], r[2 * w], (i & 1) ? 0x07060302u : 0x05040100u);
-      }
-    } else {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        fb[j] = *reinterpret_cast<const u32x4_t*>(b + (wave_n * WN + 32 * j + lr) * B_PITCH + kk * 16 + lg * 8);
-    }
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[i]),
+                                                            __builtin_bit_cast(bf16x8_t, fb[j]), acc[i][j], 0, 0, 0);
   };
 
-  if (nk > 0) {
-    gload(0);
-    sstore(0);
-  }
-  __syncthreads();
+  issue(Int<0>{}, 0);
+  issue(Int<1>{}, 1);
+  issue(Int<2>{}, 2);
+  u32x4_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  TIDE_WAIT_VMCNT(2 * NVM);
+  __builtin_amdgcn_s_barrier();
+  frags(Int<0>{}, 0, fa0, fb0);
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int st = kt & 1;
-    if (kt + 1 < nk) gload(kt + 1);
-    u32x4_t fa[2][TM], fb[2][TN];
-    frag_load(st, 0, fa[0], fb[0]);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) frag_load(st, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-      // keep the operand reads of step kk+1 ahead of the MFMAs of step kk (the scheduler would
-      // otherwise sink each read next to its first use and expose the LDS latency)
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8_t, fa[kk & 1][i]), __builtin_bit_cast(bf16x8_t, fb[kk & 1][j]),
-              acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (kt + 1 < nk) sstore(st ^ 1);
-    __syncthreads();
+  // One pipeline step: slab kt lives in stage ST, slab kt+1 in SN, and slab kt+3 goes to SP (the stage
+  // slab kt-1 just vacated).
+  auto step = [&](auto ST, auto SN, auto SP, int kt) {
+    // first half: MFMAs of k16 half 0 hide the operand reads of half 1 and the DMA issue of slab kt+3
+    frags(ST, 1, fa1, fb1);
+    issue(SP, kt + NST - 1);
+    mma(fa0, fb0);
+    sched_slots<NMF, NDS, NVM, 0, true>(std::make_integer_sequence<int, NMF>{});
+    __builtin_amdgcn_sched_barrier(0);
+    TIDE_WAIT_VMCNT(2 * NVM);          // this wave's part of slab kt+1 has landed (two younger slabs in flight)
+    __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done reading slab kt-1
+    __builtin_amdgcn_sched_barrier(0);
+    // second half: MFMAs of half 1 hide the operand reads of the next slab's half 0
+    frags(SN, 0, fa0, fb0);
+    mma(fa1, fb1);
+    sched_slots<NMF, NDS, NVM, 1, false>(std::make_integer_sequence<int, NMF>{});
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  for (int kt = 0; kt < nk4; kt += 4) {
+    step(Int<0>{}, Int<1>{}, Int<3>{}, kt);
+    step(Int<1>{}, Int<2>{}, Int<0>{}, kt + 1);
+    step(Int<2>{}, Int<3>{}, Int<1>{}, kt + 2);
+    step(Int<3>{}, Int<0>{}, Int<2>{}, kt + 3);
   }
+  TIDE_WAIT_VMCNT(0);   // the dummy slabs still in flight write LDS: let them land before the block retires
 
   // ---- epilogue ----
   float alpha = p.alpha;
   if (p.alpha_dev) alpha *= *p.alpha_dev;
   TO* C = (TO*)p.C;
   const TO* R = (const TO*)p.R;
+  const int wm0 = m0 + wave_m * WM, wn0 = n0 + wave_n * WN;
+
+  if constexpr (BNM) {
+    // a lane owns TN consecutive columns: vector stores
+    const int gn = wn0 + TN * lr;
+    const bool vec_ok = (gn + TN <= p.N) && ((p.ldc % TN) == 0) && (!R || (p.ldr % TN) == 0);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
-      const int gm = m0 + wave_m * WM + (AMM ? (TM * rr + i) : (32 * i + rr));
-      if (gm >= p.M) continue;
+      for (int q = 0; q < 16; ++q) {
+        const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
+        const int gm = wm0 + (AMM ? (TM * rr + i) : (32 * i + rr));
+        if (gm >= p.M) continue;
+        float v[TN];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int gn = n0 + wave_n * WN + (BNM ? (TN * lr + j) : (32 * j + lr));
-        if (gn >= p.N) continue;
-        float v = alpha * acc[i][j][q];
-        if (R) v += ldf(R, (size_t)gm * p.ldr + gn);
-        if (p.accumulate) v += ldf(C, (size_t)gm * p.ldc + gn);
-        stf(C, (size_t)gm * p.ldc + gn, v);
+        for (int j = 0; j < TN; ++j) v[j] = alpha * acc[i][j][q];
+        if (vec_ok) {
+          TO* dst = C + (size_t)gm * p.ldc + gn;
+          if (R) {
+            const TO* rs = R + (size_t)gm * p.ldr + gn;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) v[j] += ldf(rs, j);
+          }
+          if (p.accumulate) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) v[j] += ldf(dst, j);
+          }
+          if constexpr (sizeof(TO) == 4) {
+            if constexpr (TN == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            else *reinterpret_cast<float2*>(dst) = make_float2(v[0], v[1]);
+          } else {
+            const uint32_t w0 = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+            if constexpr (TN == 4) {
+              const uint32_t w1 = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+              *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
+            } else {
+              *reinterpret_cast<uint32_t*>(dst) = w0;
+            }
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            if (gn + j >= p.N) continue;
+            float x = v[j];
+            if (R) x += ldf(R, (size_t)gm * p.ldr + gn + j);
+            if (p.accumulate) x += ldf(C, (size_t)gm * p.ldc + gn + j);
+            stf(C, (size_t)gm * p.ldc + gn + j, x);
+          }
+        }
+      }
+  } else {
+  // B is K-major: a lane owns one column per MFMA tile.
+  bool staged = false;
+  if constexpr (sizeof(TO) == 2 && !AMM) {
+  if (!R && !p.accumulate && (p.ldc % 8) == 0 && (p.N % 8) == 0) {
+    staged = true;
+    // bf16 result through a wave-private LDS patch so that it leaves as 16-byte row segments.
+    // All stages are free here: every wave passed the last barrier after its last real operand read,
+    // and the barrier below orders the (zero) operand reads of the final dummy step before the writes.
+    __builtin_amdgcn_s_barrier();
+    constexpr int PP = WN + 8;                       // patch pitch (elements)
+    static_assert((NW / 2) * 32 * PP <= A_STAGE + B_STAGE, "epilogue patches of half the waves must fit in one stage");
+    bf16_t* patch = (wave < NW / 2 ? s0 : s1) + (wave % (NW / 2)) * (32 * PP);   // 32 x WN per wave
+    constexpr int PIECES = WN / 8;                   // 16-byte pieces per patch row
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
+          patch[rr * PP + 32 * j + lr] = f2bf(alpha * acc[i][j][q]);
+        }
+#pragma unroll
+      for (int t = 0; t < 32 * PIECES / 64; ++t) {
+        const int pc = lane + 64 * t;
+        const int row = pc / PIECES, piece = pc % PIECES;
+        const int gm = wm0 + 32 * i + row, gn = wn0 + piece * 8;
+        const u32x4_t val = *reinterpret_cast<const u32x4_t*>(patch + row * PP + piece * 8);
+        if (gm < p.M && gn < p.N)
+          *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(C) + (size_t)gm * p.ldc + gn) = val;
       }
     }
+  }
+  }
+  if (!staged) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
+        const int gm = wm0 + (AMM ? (TM * rr + i) : (32 * i + rr));
+        if (gm >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int gn = wn0 + 32 * j + lr;
+          if (gn >= p.N) continue;
+          float v = alpha * acc[i][j][q];
+          if (R) v += ldf(R, (size_t)gm * p.ldr + gn);
+          if (p.accumulate) v += ldf(C, (size_t)gm * p.ldc + gn);
+          stf(C, (size_t)gm * p.ldc + gn, v);
+        }
+      }
+  }
   }
 }
 
@@ -318,7 +438,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
   // 32-bit byte offsets inside one tile
   const int64_t lim = (int64_t)1 << 21;
   if (a.lda >= lim || a.ldb >= lim || a.ldc >= lim) return false;
-  if (a.M >= ((int64_t)1 << 24) || a.N >= ((int64_t)1 << 24) || a.K >= ((int64_t)1 << 24)) return false;
+  if (a.M >= ((int64_t)1 << 24) || a.N >= ((int64_t)1 << 24) || a.K >= ((int64_t)1 << 24) || a.K2 >= ((int64_t)1 << 24)) return false;
   if (a.layout == kNN || a.layout == kTN) {
     if (a.N % 8) return false;  // B rows are read in 16-byte pieces along N
   }
@@ -326,33 +446,38 @@ bool gemm_mfma_supported(const GemmArgs& a) {
   return true;
 }
 
-template <int BM, int BN, bool AMM, bool BNM, typename TO>
-static hipError_t launch_cfg(const MfmaParams& p, hipStream_t s) {
-  constexpr int A_PITCH = AMM ? (BM + KPAD) : (BK + KPAD);
-  constexpr int B_PITCH = BNM ? (BN + KPAD) : (BK + KPAD);
-  constexpr int A_STAGE = AMM ? BK * A_PITCH : BM * A_PITCH;
-  constexpr int B_STAGE = BNM ? BK * B_PITCH : BN * B_PITCH;
-  constexpr size_t smem = (size_t)2 * (A_STAGE + B_STAGE) * sizeof(bf16_t);
-  auto kern = gemm_mfma_kernel<BM, BN, AMM, BNM, TO>;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+namespace {
+
+template <int BM, int BN, int NW, bool AMM, bool BNM, typename TO>
+hipError_t launch_cfg(const MfmaParams& p, hipStream_t s) {
   MfmaParams q = p;
   q.tiles_m = (p.M + BM - 1) / BM;
   q.tiles_n = (p.N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(256), smem, s, q);
+  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, NW, AMM, BNM, TO>), dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(NW * 64), 0,
+                     s, q);
   return hipGetLastError();
 }
 
+bool use_big_tiles(int64_t M, int64_t N) { return ((M + 255) / 256) * ((N + 255) / 256) >= 200; }
+
 template <bool AMM, bool BNM, typename TO>
-static hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
-  const int64_t big_tiles = (int64_t)((p.M + 255) / 256) * ((p.N + 255) / 256);
-  if (big_tiles >= 200) return launch_cfg<256, 256, AMM, BNM, TO>(p, s);
-  return launch_cfg<128, 128, AMM, BNM, TO>(p, s);
+hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
+  if (use_big_tiles(p.M, p.N)) return launch_cfg<256, 256, 8, AMM, BNM, TO>(p, s);
+  return launch_cfg<128, 128, 4, AMM, BNM, TO>(p, s);
 }
+
+const char* gemm_kernel_name(const GemmArgs& a) {
+  if (!gemm_mfma_supported(a)) return "gemm_simple";
+  const bool big = use_big_tiles(a.M, a.N);
+  const bool f32 = a.out_dtype == kF32;
+  switch (a.layout) {
+    case kNT: return big ? (f32 ? "gemm_mfma_nt_256_f32out" : "gemm_mfma_nt_256_bf16out") : (f32 ? "gemm_mfma_nt_128_f32out" : "gemm_mfma_nt_128_bf16out");
+    case kNN: return big ? (f32 ? "gemm_mfma_nn_256_f32out" : "gemm_mfma_nn_256_bf16out") : (f32 ? "gemm_mfma_nn_128_f32out" : "gemm_mfma_nn_128_bf16out");
+    default: return big ? (f32 ? "gemm_mfma_tn_256_f32out" : "gemm_mfma_tn_256_bf16out") : (f32 ? "gemm_mfma_tn_128_f32out" : "gemm_mfma_tn_128_bf16out");
+  }
+}
+
+}  // namespace
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   MfmaParams p;
@@ -369,17 +494,6 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
     case kTN: return f32out ? launch_layout<true, true, float>(p, s) : launch_layout<true, true, bf16_t>(p, s);
   }
   return hipErrorInvalidValue;
-}
-
-static const char* gemm_kernel_name(const GemmArgs& a) {
-  if (!gemm_mfma_supported(a)) return "gemm_simple";
-  const bool big = ((a.M + 255) / 256) * ((a.N + 255) / 256) >= 200;
-  const bool f32 = a.out_dtype == kF32;
-  switch (a.layout) {
-    case kNT: return big ? (f32 ? "gemm_mfma_nt_256_f32out" : "gemm_mfma_nt_256_bf16out") : (f32 ? "gemm_mfma_nt_128_f32out" : "gemm_mfma_nt_128_bf16out");
-    case kNN: return big ? (f32 ? "gemm_mfma_nn_256_f32out" : "gemm_mfma_nn_256_bf16out") : (f32 ? "gemm_mfma_nn_128_f32out" : "gemm_mfma_nn_128_bf16out");
-    default: return big ? (f32 ? "gemm_mfma_tn_256_f32out" : "gemm_mfma_tn_256_bf16out") : (f32 ? "gemm_mfma_tn_128_f32out" : "gemm_mfma_tn_128_bf16out");
-  }
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
