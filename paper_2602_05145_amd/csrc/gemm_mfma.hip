@@ -7,21 +7,24 @@
 //   * A block computes a BM x BN tile (256x256 with 8 wavefronts = 2 per SIMD, or 128x128 with 4) with
 //     v_mfma_f32_32x32x16_bf16; a wave owns TM x TN MFMA tiles (4x2 or 2x2).  Two waves per SIMD matter:
 //     one wave alone cannot issue MFMAs back to back (measured ~83 % of the multi-wave MFMA rate).
-//   * K is walked in slabs of 32 through a ring of FOUR LDS stages that are filled by LDS-DMA buffer loads
-//     (global -> LDS without passing through registers, hardware zero-fill outside the valid extent, so
-//     ragged M / N / K need no special code).  The loads of slab k+3 are issued while slab k is being
-//     multiplied, which covers the ~2 us loaded-HBM latency that a two-stage register-staged pipeline
-//     could not (that version waited ~50 % of its cycles).
-//   * Synchronisation is manual: one `s_waitcnt vmcnt(n)` (own DMA of the next slab has landed; two younger
-//     slabs stay in flight) and one `s_barrier` per slab, placed between the two k16 halves of a slab so
-//     that the operand reads of the next slab are issued under the MFMAs of the current one.  Each stage
-//     is its own __shared__ array: the compiler can then tell that the operand reads do not alias the
-//     DMA writes in flight and does not drain vmcnt before them.  Slabs past K are dummies (their loads
-//     fall outside the buffer and zero-fill a free stage) so the steady state has no branches.
-//   * Instruction order inside a half-slab is pinned with sched_group_barrier: MFMA / LDS read (or DMA
+//   * K is walked in slabs through an LDS ring that always holds 128 k-columns and is filled by LDS-DMA
+//     buffer loads (global -> LDS without passing through registers, hardware zero-fill outside the valid
+//     extent, so ragged M / N / K need no special code).  What bounds this kernel is the number of L2
+//     requests a CU can keep in flight, so the ring shape follows the operand layout: with a K-major
+//     operand the slab is 64 deep (TWO stages): each of its rows then fetches one whole 128-byte line
+//     instead of two 64-byte halves (+3-6 % measured); when both operands are row-major over K (TN) their
+//     rows are contiguous anyway and FOUR stages of 32 win (+30 % over two of 64) because the loads of
+//     slab k+3 are issued while slab k is multiplied.  Register-staged loads (no DMA) waited ~50 % of
+//     their cycles.
+//   * Synchronisation is manual: one `s_waitcnt vmcnt(n)` (own DMA of the next slab has landed, younger
+//     slabs stay in flight) and one `s_barrier` per slab.  Each stage is its own __shared__ array: the compiler can then tell that the
+//     operand reads do not alias the DMA writes in flight and does not drain vmcnt before them.  Slabs
+//     past K are dummies (their loads fall outside the buffer and zero-fill the free stage) so the steady
+//     state has no branches.
+//   * Instruction order inside a k16 quarter is pinned with sched_group_barrier: MFMA / LDS read (or DMA
 //     issue) alternate, so LDS and address traffic hides in the MFMA shadow.
-//   * LDS layout.  A "K-major" operand (contraction index contiguous in memory) is stored [row][32] with
-//     the four 16-byte pieces of a row XOR-swizzled by (row >> 2) & 3: DMA can only write 1 KiB
+//   * LDS layout.  A "K-major" operand (contraction index contiguous in memory) is stored [row][BK] with
+//     the 16-byte pieces of a row XOR-swizzled by (row >> 1) & 7 (BK 64) or (row >> 2) & 3 (BK 32): DMA can only write 1 KiB
 //     contiguous per instruction, so padding is impossible, and the swizzle makes the 16-byte operand
 //     reads of 16 consecutive rows hit 16 different bank groups.  An operand whose contraction index is
 //     the slow one (B of NN, both operands of TN) is stored exactly as in memory, [k][row], and
@@ -52,8 +55,6 @@ typedef __attribute__((address_space(3))) void* lds_vp;
 
 namespace {
 
-constexpr int BK = 32;    // K per LDS stage
-constexpr int NST = 4;    // LDS stages
 
 struct MfmaParams {
   const bf16_t* A; const bf16_t* B; const bf16_t* A2; const bf16_t* B2;
@@ -75,7 +76,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 constexpr uint32_t kOobOffset = 0x7FFFFFF0u;  // beyond any buffer extent used here: the load returns zeros
 
 // One operand (A or B) of one block: R rows (BM or BN) of the tile, either K-major or row-major over K.
-template <int R, int NW, bool RMAJ, int T>   // T = MFMA tiles per wave along this dimension
+template <int R, int NW, bool RMAJ, int T, int BK>   // T = MFMA tiles per wave along this dimension; BK = slab depth
 struct Operand {
   static constexpr int STAGE = R * BK;                                   // elements per stage
   static constexpr int CHUNKS = STAGE * 2 / 1024;                        // 1 KiB DMA instructions per stage
@@ -83,7 +84,10 @@ struct Operand {
   static_assert(CHUNKS % NW == 0 && PER_WAVE >= 1, "DMA chunks must split evenly over the waves");
   static constexpr int PPR = R / 8;                                      // 16-byte pieces per k-row (row-major)
   static constexpr int RPC = 64 / PPR;                                   // k-rows per DMA chunk (row-major)
-  static constexpr int kReadsPerHalf = RMAJ ? 8 : T;                     // LDS read instructions per k16 half
+  static constexpr int KPIECES = BK / 8;                                 // 16-byte pieces per K-major row (4 or 8)
+  static constexpr int KROWS = 64 / KPIECES;                             // K-major rows per DMA chunk (16 or 8)
+  static constexpr int SWZ_SHIFT = (BK == 32) ? 2 : 1;                   // swizzle: piece ^= (row >> shift) & (KPIECES-1)
+  static constexpr int kReadsPerQuarter = RMAJ ? 8 : T;                  // LDS read instructions per k16 quarter
 
   // Stateless on purpose: the tile pointers and extents stay plain kernel locals (SGPRs).  Bundling them
   // in a struct with the per-lane offsets made the compiler keep that struct in scratch memory, the
@@ -91,28 +95,34 @@ struct Operand {
 
   // per-lane byte offsets of this wave's DMA chunks, without the k0 term; K-major also yields the 16-byte
   // piece of a row that this lane fetches (swizzled)
-  static __device__ __forceinline__ void lane_offsets(int ld, int wave, int lane, uint32_t (&off)[PER_WAVE], int& piece) {
+  static __device__ __forceinline__ void lane_offsets(int ld, int wave, int lane, uint32_t (&off)[PER_WAVE],
+                                                      int (&piece)[PER_WAVE]) {
     if (RMAJ) {
       const int kr = lane / PPR, pc = lane % PPR;
 #pragma unroll
-      for (int i = 0; i < PER_WAVE; ++i)
+      for (int i = 0; i < PER_WAVE; ++i) {
         off[i] = (uint32_t)((((wave * PER_WAVE + i) * RPC + kr) * ld + pc * 8) * 2);
-      piece = 0;
+        piece[i] = 0;
+      }
     } else {
-      const int drow = lane >> 2, slot = lane & 3;
-      piece = slot ^ ((drow >> 2) & 3);
+      // chunk = KROWS rows x (BK*2) bytes; LDS slot (row, s) holds piece s ^ swizzle(row) of that row
+      const int rl = lane / KPIECES, slot = lane % KPIECES;
 #pragma unroll
-      for (int i = 0; i < PER_WAVE; ++i)
-        off[i] = (uint32_t)((((wave * PER_WAVE + i) * 16 + drow) * ld + piece * 8) * 2);
+      for (int i = 0; i < PER_WAVE; ++i) {
+        const int row = (wave * PER_WAVE + i) * KROWS + rl;
+        piece[i] = slot ^ ((row >> SWZ_SHIFT) & (KPIECES - 1));
+        off[i] = (uint32_t)((row * ld + piece[i] * 8) * 2);
+      }
     }
   }
 
-  // Issue the DMA loads of the slab [k0, k0+32) into `stage`.  tile = operand pointer already offset to
+  // Issue the DMA loads of the slab [k0, k0+BK) into `stage`.  tile = operand pointer already offset to
   // the tile's first row (K-major) or first column (row-major); rows_valid = tile rows inside the matrix
   // (K-major) ; cols_left = matrix columns from the tile's first column on (row-major); Kc = contraction
   // length.  A slab with k0 >= Kc is a dummy: every load is out of range and writes zeros.
   static __device__ __forceinline__ void issue(bf16_t* stage, const bf16_t* tile, int ld, int rows_valid, int cols_left,
-                                               int k0, int Kc, const uint32_t (&off)[PER_WAVE], int piece, int wave) {
+                                               int k0, int Kc, const uint32_t (&off)[PER_WAVE],
+                                               const int (&piece)[PER_WAVE], int wave) {
     if (RMAJ) {
       const int kv = min(BK, Kc - k0);   // valid k-rows of this slab (<= 0 for a dummy slab)
       const bf16_t* base = tile + (size_t)(kv > 0 ? k0 : 0) * ld;
@@ -124,15 +134,16 @@ struct Operand {
     } else {
       const uint32_t bytes = (uint32_t)(((int64_t)(rows_valid - 1) * ld + Kc) * 2);
       const __amdgpu_buffer_rsrc_t rs = make_rsrc(tile, bytes);
-      const bool kin = (k0 + piece * 8) < Kc;
 #pragma unroll
-      for (int i = 0; i < PER_WAVE; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_vp)(stage + (wave * PER_WAVE + i) * 512), 16,
-                                                 kin ? off[i] + (uint32_t)(k0 * 2) : kOobOffset, 0, 0, 0);
+      for (int i = 0; i < PER_WAVE; ++i) {
+        const bool kin = (k0 + piece[i] * 8) < Kc;
+        const uint32_t o = kin ? off[i] + (uint32_t)(k0 * 2) : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_vp)(stage + (wave * PER_WAVE + i) * 512), 16, o, 0, 0, 0);
+      }
     }
   }
 
-  // MFMA operand fragments of k16 half `kk` for the wave whose first tile row is wbase
+  // MFMA operand fragments of k16 step `kk` (< BK/16) for the wave whose first tile row is wbase
   static __device__ __forceinline__ void frags(const bf16_t* stage, int kk, int wbase, int lr, int lg, u32x4_t (&f)[T]) {
     if (RMAJ) {
       const bf16_t* src = stage + (kk * 16 + lg * 8) * R + wbase + T * lr;
@@ -159,7 +170,7 @@ struct Operand {
             f[i][w] = __builtin_amdgcn_perm(r[2 * w + 1], r[2 * w], (i & 1) ? 0x07060302u : 0x05040100u);
       }
     } else {
-      const int sw = (lr >> 2) & 3;
+      const int sw = (lr >> SWZ_SHIFT) & (KPIECES - 1);
       const bf16_t* src = stage + (wbase + lr) * BK + (((kk * 2 + lg) ^ sw) * 8);
 #pragma unroll
       for (int i = 0; i < T; ++i) f[i] = *reinterpret_cast<const u32x4_t*>(src + i * 32 * BK);
@@ -170,41 +181,44 @@ struct Operand {
 template <int N>
 struct Int : std::integral_constant<int, N> {};
 
-// Pin the instruction order of one k16 half: after MFMA number I come its share of the NDS LDS reads
-// and, for the last NVM MFMAs of a first half, one DMA issue each.
-template <int I, int NMF, int NDS, int NVM, int SYNC, bool WITH_DMA>
+// Pin the instruction order of one k16 quarter: after MFMA number I come its share of NDS LDS reads and
+// of NVM DMA issues.
+template <int I, int NMF, int NDS, int NVM, int SYNC>
 __device__ __forceinline__ void sched_slot() {
   __builtin_amdgcn_sched_group_barrier(0x008, 1, SYNC);   // MFMA
   constexpr int nds = NDS / NMF + (I < NDS % NMF ? 1 : 0);
   if constexpr (nds > 0) __builtin_amdgcn_sched_group_barrier(0x100, nds, SYNC);   // LDS reads
-  if constexpr (WITH_DMA && I >= NMF - NVM) __builtin_amdgcn_sched_group_barrier(0x020, 1, SYNC);   // DMA issue
+  constexpr int nvm = NVM / NMF + (I < NVM % NMF ? 1 : 0);
+  if constexpr (nvm > 0) __builtin_amdgcn_sched_group_barrier(0x020, nvm, SYNC);   // DMA issues
 }
-template <int NMF, int NDS, int NVM, int SYNC, bool WITH_DMA, int... I>
+template <int NMF, int NDS, int NVM, int SYNC, int... I>
 __device__ __forceinline__ void sched_slots(std::integer_sequence<int, I...>) {
-  (sched_slot<I, NMF, NDS, NVM, SYNC, WITH_DMA>(), ...);
+  (sched_slot<I, NMF, NDS, NVM, SYNC>(), ...);
 }
 
 }  // namespace
 
-template <int BM, int BN, int NW, bool AMM, bool BNM, typename TO>
+template <int BM, int BN, int NW, bool AMM, bool BNM, typename TO, int BK>
 __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
+  static_assert(BK == 32 || BK == 64, "slab depth");
+  constexpr int NST = (BK == 32) ? 4 : 2;   // LDS stages: the ring always holds 128 k-columns
   constexpr int WAVES_N = (NW == 8) ? 4 : 2, WAVES_M = NW / WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
   static_assert(TM == 4 || TM == 2, "wave tile height must be 128 or 64");
   static_assert(TN == 4 || TN == 2, "wave tile width must be 128 or 64");
-  using OpA = Operand<BM, NW, AMM, TM>;
-  using OpB = Operand<BN, NW, BNM, TN>;
+  using OpA = Operand<BM, NW, AMM, TM, BK>;
+  using OpB = Operand<BN, NW, BNM, TN, BK>;
   constexpr int A_STAGE = OpA::STAGE, B_STAGE = OpB::STAGE;
   constexpr int NVM = OpA::PER_WAVE + OpB::PER_WAVE;            // DMA instructions per wave per slab
-  constexpr int NDS = OpA::kReadsPerHalf + OpB::kReadsPerHalf;  // LDS reads per wave per k16 half
-  constexpr int NMF = TM * TN;                                  // MFMAs per wave per k16 half
-  static_assert(NVM <= NMF, "one DMA issue per MFMA slot at most");
+  constexpr int NDS = OpA::kReadsPerQuarter + OpB::kReadsPerQuarter;  // LDS reads per wave per k16 quarter
+  constexpr int NMF = TM * TN;                                        // MFMAs per wave per k16 quarter
 
+  constexpr int STAGE34 = (NST == 4) ? A_STAGE + B_STAGE : 8;   // stages 2, 3 exist only in the four-stage ring
   __shared__ __attribute__((aligned(1024))) bf16_t s0[A_STAGE + B_STAGE];
   __shared__ __attribute__((aligned(1024))) bf16_t s1[A_STAGE + B_STAGE];
-  __shared__ __attribute__((aligned(1024))) bf16_t s2[A_STAGE + B_STAGE];
-  __shared__ __attribute__((aligned(1024))) bf16_t s3[A_STAGE + B_STAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t s2[STAGE34];
+  __shared__ __attribute__((aligned(1024))) bf16_t s3[STAGE34];
   auto stage = [&](auto ST) -> bf16_t* {
     if constexpr (decltype(ST)::value == 0) return s0;
     else if constexpr (decltype(ST)::value == 1) return s1;
@@ -242,7 +256,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
   const bf16_t* b_tile1 = p.B2 ? (BNM ? p.B2 + n0 : p.B2 + (size_t)n0 * p.ldb) : b_tile0;
   const int a_rows = min(BM, p.M - m0), b_rows = min(BN, p.N - n0);
   uint32_t a_off[OpA::PER_WAVE], b_off[OpB::PER_WAVE];
-  int a_piece, b_piece;
+  int a_piece[OpA::PER_WAVE], b_piece[OpB::PER_WAVE];
   OpA::lane_offsets(p.lda, wave, lane, a_off, a_piece);
   OpB::lane_offsets(p.ldb, wave, lane, b_off, b_piece);
 
@@ -255,9 +269,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
   const int nk1 = (p.K + BK - 1) / BK;
-  const int nk2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
-  const int nk = nk1 + nk2;
-  const int nk4 = (nk + 3) & ~3;   // slabs nk .. nk4+2 are dummies
+  const int nkp2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
+  const int nk = nk1 + nkp2;
+  const int nk_round = (nk + NST - 1) / NST * NST;   // slabs past nk are dummies
 
   auto issue = [&](auto ST, int kt) {
     bf16_t* sb = stage(ST);
@@ -283,37 +297,70 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
                                                             __builtin_bit_cast(bf16x8_t, fb[j]), acc[i][j], 0, 0, 0);
   };
 
-  issue(Int<0>{}, 0);
-  issue(Int<1>{}, 1);
-  issue(Int<2>{}, 2);
   u32x4_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  TIDE_WAIT_VMCNT(2 * NVM);
-  __builtin_amdgcn_s_barrier();
-  frags(Int<0>{}, 0, fa0, fb0);
-
-  // One pipeline step: slab kt lives in stage ST, slab kt+1 in SN, and slab kt+3 goes to SP (the stage
-  // slab kt-1 just vacated).
-  auto step = [&](auto ST, auto SN, auto SP, int kt) {
-    // first half: MFMAs of k16 half 0 hide the operand reads of half 1 and the DMA issue of slab kt+3
-    frags(ST, 1, fa1, fb1);
-    issue(SP, kt + NST - 1);
-    mma(fa0, fb0);
-    sched_slots<NMF, NDS, NVM, 0, true>(std::make_integer_sequence<int, NMF>{});
-    __builtin_amdgcn_sched_barrier(0);
-    TIDE_WAIT_VMCNT(2 * NVM);          // this wave's part of slab kt+1 has landed (two younger slabs in flight)
-    __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done reading slab kt-1
-    __builtin_amdgcn_sched_barrier(0);
-    // second half: MFMAs of half 1 hide the operand reads of the next slab's half 0
-    frags(SN, 0, fa0, fb0);
-    mma(fa1, fb1);
-    sched_slots<NMF, NDS, NVM, 1, false>(std::make_integer_sequence<int, NMF>{});
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  for (int kt = 0; kt < nk4; kt += 4) {
-    step(Int<0>{}, Int<1>{}, Int<3>{}, kt);
-    step(Int<1>{}, Int<2>{}, Int<0>{}, kt + 1);
-    step(Int<2>{}, Int<3>{}, Int<1>{}, kt + 2);
-    step(Int<3>{}, Int<0>{}, Int<2>{}, kt + 3);
+  if constexpr (BK == 64) {
+    // ---- two stages of 64: used when an operand is K-major (its rows then fetch whole 128-byte lines) ----
+    issue(Int<0>{}, 0);
+    // One pipeline step: slab kt lives in stage ST; slab kt+1 is loaded into the other stage SO meanwhile.
+    auto step = [&](auto ST, auto SO, int kt) {
+      TIDE_WAIT_VMCNT(0);                // this wave's part of slab kt (issued one step ago) has landed
+      __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done reading stage SO
+      __builtin_amdgcn_sched_barrier(0);
+      // quarter 0: its MFMAs hide the DMA issue of slab kt+1
+      issue(SO, kt + 1);
+      frags(ST, 0, fa0, fb0);
+      frags(ST, 1, fa1, fb1);
+      mma(fa0, fb0);
+      sched_slots<NMF, 0, NVM, 0>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+      // quarters 1 and 2: MFMAs hide the operand reads of the following quarter
+      frags(ST, 2, fa0, fb0);
+      mma(fa1, fb1);
+      sched_slots<NMF, NDS, 0, 1>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+      frags(ST, 3, fa1, fb1);
+      mma(fa0, fb0);
+      sched_slots<NMF, NDS, 0, 2>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int kt = 0; kt < nk_round; kt += 2) {
+      step(Int<0>{}, Int<1>{}, kt);
+      step(Int<1>{}, Int<0>{}, kt + 1);
+    }
+  } else {
+    // ---- four stages of 32: used when both operands are row-major over K (their rows are contiguous
+    // anyway, so the deeper ring is what helps); the loads of slab k+3 are issued while slab k is multiplied
+    issue(Int<0>{}, 0);
+    issue(Int<1>{}, 1);
+    issue(Int<2>{}, 2);
+    TIDE_WAIT_VMCNT(2 * NVM);
+    __builtin_amdgcn_s_barrier();
+    frags(Int<0>{}, 0, fa0, fb0);
+    // One pipeline step: slab kt lives in stage ST, slab kt+1 in SN, and slab kt+3 goes to SP (the stage
+    // slab kt-1 just vacated).  The barrier sits between the two k16 halves so that the operand reads of
+    // the next slab are issued under the MFMAs of this one.
+    auto step = [&](auto ST, auto SN, auto SP, int kt) {
+      frags(ST, 1, fa1, fb1);
+      issue(SP, kt + NST - 1);
+      mma(fa0, fb0);
+      sched_slots<NMF, NDS, NVM, 0>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+      TIDE_WAIT_VMCNT(2 * NVM);          // this wave's part of slab kt+1 has landed (two younger slabs in flight)
+      __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done reading slab kt-1
+      __builtin_amdgcn_sched_barrier(0);
+      frags(SN, 0, fa0, fb0);
+      mma(fa1, fb1);
+      sched_slots<NMF, NDS, 0, 1>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int kt = 0; kt < nk_round; kt += 4) {
+      step(Int<0>{}, Int<1>{}, Int<3>{}, kt);
+      step(Int<1>{}, Int<2>{}, Int<0>{}, kt + 1);
+      step(Int<2>{}, Int<3>{}, Int<1>{}, kt + 2);
+      step(Int<3>{}, Int<0>{}, Int<2>{}, kt + 3);
+    }
   }
   TIDE_WAIT_VMCNT(0);   // the dummy slabs still in flight write LDS: let them land before the block retires
 
@@ -448,12 +495,12 @@ bool gemm_mfma_supported(const GemmArgs& a) {
 
 namespace {
 
-template <int BM, int BN, int NW, bool AMM, bool BNM, typename TO>
+template <int BM, int BN, int NW, bool AMM, bool BNM, typename TO, int BK>
 hipError_t launch_cfg(const MfmaParams& p, hipStream_t s) {
   MfmaParams q = p;
   q.tiles_m = (p.M + BM - 1) / BM;
   q.tiles_n = (p.N + BN - 1) / BN;
-  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, NW, AMM, BNM, TO>), dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(NW * 64), 0,
+  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, NW, AMM, BNM, TO, BK>), dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(NW * 64), 0,
                      s, q);
   return hipGetLastError();
 }
@@ -462,8 +509,10 @@ bool use_big_tiles(int64_t M, int64_t N) { return ((M + 255) / 256) * ((N + 255)
 
 template <bool AMM, bool BNM, typename TO>
 hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
-  if (use_big_tiles(p.M, p.N)) return launch_cfg<256, 256, 8, AMM, BNM, TO>(p, s);
-  return launch_cfg<128, 128, 4, AMM, BNM, TO>(p, s);
+  // slab depth: 64 (two stages) as soon as one operand is K-major, else 32 (four stages)
+  constexpr int BK = (AMM && BNM) ? 32 : 64;
+  if (use_big_tiles(p.M, p.N)) return launch_cfg<256, 256, 8, AMM, BNM, TO, BK>(p, s);
+  return launch_cfg<128, 128, 4, AMM, BNM, TO, BK>(p, s);
 }
 
 const char* gemm_kernel_name(const GemmArgs& a) {
