@@ -15,7 +15,8 @@
 // K^T, dO^T, Q^T) is read from the row-major LDS tile with the transposing LDS read
 // ds_read_b64_tr_b16, so nothing is ever transposed through registers or HBM.
 //
-// Tiles.  Forward and dQ: one block = 128 queries of one head (4 waves x 32 queries, Q in registers),
+// Tiles.  Forward and dQ: one block = 128 queries of one head (4 waves x 32 queries, Q in registers; capped
+// at 256 VGPRs so that two blocks share a CU and one block's softmax overlaps the other's MFMAs),
 // K/V streamed in 64-key tiles, double buffered through LDS.  dK/dV: one block = 128 keys of one kv
 // head (4 waves x 32 keys, K and V in registers), Q/dO streamed in 32-query tiles for each of the G
 // query heads of the group, so dK/dV are summed over the group in registers: no atomics, deterministic.
@@ -146,7 +147,7 @@ constexpr int KV_TILE = BKV * PITCH;  // elements
 // ------------------------------------------------------------------------------------------------
 // forward
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                             float* __restrict__ lse, int S, int nh, int nkv) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   bf16_t* sK = smem;                 // [2][KV_TILE]
@@ -231,10 +232,12 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
       ps += __shfl_xor(ps, 32, 64);
       l = l * alpha + ps;
       m = mn;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // wave-uniform: some row's running max moved
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) o[ct][q] *= alpha;
+          for (int q = 0; q < 16; ++q) o[ct][q] *= alpha;
+      }
       u32x4_t pf[4];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) pf[ks] = pack_half(s[ks >> 1], ks & 1);
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
 // ------------------------------------------------------------------------------------------------
 // backward, dQ: same streaming structure as the forward pass
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+__global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, int S, int nh, int nkv) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];

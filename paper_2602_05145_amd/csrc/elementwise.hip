@@ -9,29 +9,143 @@
 namespace tide {
 
 // ----------------------------------------------------------------------------------------------
-// N = max(1, number of positions with loss_mask != 0 and 0 <= token < V)
+// Row plan of the LM head: N = max(1, #keep) with keep_t = mask_t != 0 and 0 <= token_t < V, and the
+// ascending list of rows the LM head processes (the kept rows; every row when select_all is set, which
+// the forward pass with arg-max output needs).  Rows that carry no loss contribute exactly nothing to the
+// loss or to any gradient, so the vocabulary-sized products skip them.  One block, fixed order:
+// deterministic.
 // ----------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void count_valid_kernel(const int32_t* __restrict__ tokens,
-                                                           const uint8_t* __restrict__ mask, int64_t T,
-                                                           int V, float* __restrict__ scal) {
-  __shared__ float red[32];
-  float c = 0.f;
-  for (int64_t i = threadIdx.x; i < T; i += blockDim.x) {
-    int tk = tokens[i];
-    c += (mask[i] != 0 && tk >= 0 && tk < V) ? 1.f : 0.f;  // exact in fp32 up to 2^24 positions
+__global__ __launch_bounds__(1024) void plan_rows_kernel(const int32_t* __restrict__ tokens,
+                                                         const uint8_t* __restrict__ mask, int64_t T, int V,
+                                                         int select_all, float* __restrict__ scal,
+                                                         int* __restrict__ cnt, int32_t* __restrict__ kept_idx,
+                                                         int32_t* __restrict__ row_pos) {
+  __shared__ int wsum_sel[16], wsum_keep[16];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int64_t per = (T + 1023) / 1024;
+  const int64_t t0 = (int64_t)tid * per, t1 = min(T, t0 + per);
+  int nsel = 0, nkeep = 0;
+  for (int64_t t = t0; t < t1; ++t) {
+    const int tk = tokens[t];
+    const int keep = (mask[t] != 0 && tk >= 0 && tk < V) ? 1 : 0;
+    nkeep += keep;
+    nsel += select_all ? 1 : keep;
   }
-  float tot = block_sum(c, red);
-  if (threadIdx.x == 0) {
-    float n = fmaxf(tot, 1.f);
+  // inclusive scan of nsel inside the wave, totals of nsel / nkeep per wave
+  int incl = nsel;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+  int ksum = nkeep;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ksum += __shfl_xor(ksum, o, 64);
+  if (lane == 63) wsum_sel[w] = incl;
+  if (lane == 0) wsum_keep[w] = ksum;
+  __syncthreads();
+  int base = 0, total_sel = 0, total_keep = 0;
+  for (int i = 0; i < 16; ++i) {
+    if (i < w) base += wsum_sel[i];
+    total_sel += wsum_sel[i];
+    total_keep += wsum_keep[i];
+  }
+  int pos = base + incl - nsel;   // exclusive prefix of this thread
+  for (int64_t t = t0; t < t1; ++t) {
+    const int tk = tokens[t];
+    const int keep = (mask[t] != 0 && tk >= 0 && tk < V) ? 1 : 0;
+    const int sel = select_all ? 1 : keep;
+    if (sel) {
+      kept_idx[pos] = (int32_t)t;
+      row_pos[t] = pos;
+      ++pos;
+    } else {
+      row_pos[t] = -1;
+    }
+  }
+  if (tid == 0) {
+    const float n = fmaxf((float)total_keep, 1.f);
     scal[0] = n;
     scal[1] = 1.f / n;
+    cnt[0] = total_sel;
   }
 }
 
-hipError_t launch_count_valid(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, float* scal,
-                              hipStream_t s) {
-  ProfScope ps("count_valid", 0, 5.0 * (double)T, s);
-  hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, tokens, mask, T, V, scal);
+hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
+                            float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, hipStream_t s) {
+  ProfScope ps("plan_rows", 0, 13.0 * (double)T, s);
+  hipLaunchKernelGGL(plan_rows_kernel, dim3(1), dim3(1024), 0, s, tokens, mask, T, V, select_all, scal, cnt, kept_idx, row_pos);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const T* __restrict__ src, const int32_t* __restrict__ tokens,
+                                                          const uint8_t* __restrict__ mask,
+                                                          const int32_t* __restrict__ kept_idx,
+                                                          const int* __restrict__ cnt, T* __restrict__ dst,
+                                                          int32_t* __restrict__ tokens_c, uint8_t* __restrict__ mask_c,
+                                                          int d) {
+  const int i = blockIdx.x;
+  if (i >= *cnt) return;
+  const size_t r = (size_t)kept_idx[i];
+  const T* a = src + r * (size_t)d;
+  T* b = dst + (size_t)i * (size_t)d;
+  if ((d & 7) == 0) {
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+      float v[8];
+      ld8(a, c, v);
+      st8(b, c, v);
+    }
+  } else {
+    for (int c = threadIdx.x; c < d; c += 256) b[c] = a[c];
+  }
+  if (threadIdx.x == 0) {
+    tokens_c[i] = tokens[r];
+    mask_c[i] = mask[r];
+  }
+}
+
+hipError_t launch_gather_rows(int64_t T, int d, const void* src, const int32_t* tokens, const uint8_t* mask,
+                              const int32_t* kept_idx, const int* cnt, void* dst, int32_t* tokens_c,
+                              uint8_t* mask_c, int dtype, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  ProfScope ps("gather_rows", 0, 2.0 * (double)T * d * dtype_size(dtype), s);
+  prof_dynamic(cnt, 0, T);
+  dim3 grid((unsigned)T), blk(256);
+  if (dtype == kBF16) hipLaunchKernelGGL(gather_rows_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)src, tokens, mask, kept_idx, cnt, (bf16_t*)dst, tokens_c, mask_c, d);
+  else hipLaunchKernelGGL(gather_rows_kernel<float>, grid, blk, 0, s, (const float*)src, tokens, mask, kept_idx, cnt, (float*)dst, tokens_c, mask_c, d);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const T* __restrict__ src, const int32_t* __restrict__ row_pos,
+                                                           T* __restrict__ dst, int d) {
+  const size_t t = blockIdx.x;
+  const int p = row_pos[t];
+  T* b = dst + t * (size_t)d;
+  const T* a = src + (size_t)(p < 0 ? 0 : p) * (size_t)d;
+  if ((d & 7) == 0) {
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+      float v[8];
+      if (p >= 0) ld8(a, c, v);
+      else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = 0.f;
+      }
+      st8(b, c, v);
+    }
+  } else {
+    for (int c = threadIdx.x; c < d; c += 256) stf(b, c, p >= 0 ? ldf(a, c) : 0.f);
+  }
+}
+
+hipError_t launch_scatter_rows(int64_t T, int d, const void* src, const int32_t* row_pos, void* dst, int dtype,
+                               hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  ProfScope ps("scatter_rows", 0, 2.0 * (double)T * d * dtype_size(dtype), s);
+  dim3 grid((unsigned)T), blk(256);
+  if (dtype == kBF16) hipLaunchKernelGGL(scatter_rows_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)src, row_pos, (bf16_t*)dst, d);
+  else hipLaunchKernelGGL(scatter_rows_kernel<float>, grid, blk, 0, s, (const float*)src, row_pos, (float*)dst, d);
   return hipGetLastError();
 }
 
@@ -368,10 +482,13 @@ __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ z, 
                                                        const uint8_t* __restrict__ mask,
                                                        float* __restrict__ lse,
                                                        float* __restrict__ loss_rows,
-                                                       int32_t* __restrict__ top1) {
+                                                       int32_t* __restrict__ top1,
+                                                       const int32_t* __restrict__ top1_idx,
+                                                       const int* __restrict__ rows_dev, int rows_off) {
   __shared__ float sm_m[4], sm_s[4], sm_bv[4];
   __shared__ int sm_bi[4];
   const size_t row = blockIdx.x;
+  if (rows_dev && (int)row >= *rows_dev - rows_off) return;
   const T* zr = z + row * (size_t)ldz;
   float m = -INFINITY, ssum = 0.f;
   float bv = -INFINITY;
@@ -436,22 +553,26 @@ __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ z, 
     const int tk = tokens[row];
     const bool keep = mask[row] != 0 && tk >= 0 && tk < V;
     loss_rows[row] = keep ? (l - ldf(zr, (size_t)tk)) : 0.f;
-    if (TOP1) top1[row] = BI;
+    if (TOP1) top1[top1_idx ? top1_idx[row] : (int)row] = BI;
   }
 }
 
 hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, const int32_t* tokens,
-                           const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1, int dtype,
+                           const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1,
+                           const int32_t* top1_idx, const int* rows_dev, int64_t rows_off, int dtype,
                            hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  dim3 grid((unsigned)rows), blk(256);
+  if (ldz % 8 != 0) return hipErrorInvalidValue;
   ProfScope ps("ce_stats", 0, (double)rows * V * dtype_size(dtype), s);
+  if (rows_dev) prof_dynamic(rows_dev, rows_off, rows);
+  dim3 grid((unsigned)rows), blk(256);
+  const int ro = (int)rows_off;
   if (dtype == kBF16) {
-    if (top1) hipLaunchKernelGGL((ce_stats_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
-    else hipLaunchKernelGGL((ce_stats_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
+    if (top1) hipLaunchKernelGGL((ce_stats_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, rows_dev, ro);
+    else hipLaunchKernelGGL((ce_stats_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, rows_dev, ro);
   } else {
-    if (top1) hipLaunchKernelGGL((ce_stats_kernel<float, true>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
-    else hipLaunchKernelGGL((ce_stats_kernel<float, false>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1);
+    if (top1) hipLaunchKernelGGL((ce_stats_kernel<float, true>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, rows_dev, ro);
+    else hipLaunchKernelGGL((ce_stats_kernel<float, false>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, rows_dev, ro);
   }
   return hipGetLastError();
 }
@@ -462,8 +583,10 @@ template <typename T>
 __global__ __launch_bounds__(256) void ce_dz_kernel(T* __restrict__ z, int64_t ldz, int V,
                                                     const int32_t* __restrict__ tokens,
                                                     const uint8_t* __restrict__ mask,
-                                                    const float* __restrict__ lse) {
+                                                    const float* __restrict__ lse,
+                                                    const int* __restrict__ rows_dev, int rows_off) {
   const size_t row = blockIdx.y;
+  if (rows_dev && (int)row >= *rows_dev - rows_off) return;
   const int c = (blockIdx.x * 256 + threadIdx.x) * 8;
   if (c >= ldz) return;
   T* zr = z + row * (size_t)ldz;
@@ -481,30 +604,35 @@ __global__ __launch_bounds__(256) void ce_dz_kernel(T* __restrict__ z, int64_t l
 }
 
 hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t* tokens,
-                        const uint8_t* mask, const float* lse, int dtype, hipStream_t s) {
+                        const uint8_t* mask, const float* lse, const int* rows_dev, int64_t rows_off, int dtype,
+                        hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  if (ldz % 8 != 0) return hipErrorInvalidValue;
+  if (ldz % 8 != 0 || rows > 65535) return hipErrorInvalidValue;
   ProfScope ps("ce_dz", 0, (double)rows * ldz * 2.0 * dtype_size(dtype), s);
+  if (rows_dev) prof_dynamic(rows_dev, rows_off, rows);
   dim3 grid((unsigned)((ldz + 2047) / 2048), (unsigned)rows), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(ce_dz_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)z, ldz, V, tokens, mask, lse);
-  else hipLaunchKernelGGL(ce_dz_kernel<float>, grid, blk, 0, s, (float*)z, ldz, V, tokens, mask, lse);
+  const int ro = (int)rows_off;
+  if (dtype == kBF16) hipLaunchKernelGGL(ce_dz_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)z, ldz, V, tokens, mask, lse, rows_dev, ro);
+  else hipLaunchKernelGGL(ce_dz_kernel<float>, grid, blk, 0, s, (float*)z, ldz, V, tokens, mask, lse, rows_dev, ro);
   return hipGetLastError();
 }
 
-// loss = (1/N) * sum_t loss_rows[t]   (single block, fixed summation order: deterministic)
-__global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restrict__ loss_rows, int64_t T,
+// loss = (1/N) * sum of loss_rows[0 .. *cnt)   (single block, fixed summation order: deterministic)
+__global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restrict__ loss_rows,
+                                                           const int* __restrict__ cnt,
                                                            const float* __restrict__ scal,
                                                            float* __restrict__ loss_out) {
   __shared__ float red[32];
+  const int n = *cnt;
   float a = 0.f;
-  for (int64_t i = threadIdx.x; i < T; i += 1024) a += loss_rows[i];
+  for (int i = threadIdx.x; i < n; i += 1024) a += loss_rows[i];
   float tot = block_sum(a, red);
   if (threadIdx.x == 0) *loss_out = tot * scal[1];
 }
 
-hipError_t launch_loss_reduce(int64_t T, const float* loss_rows, const float* scal, float* loss_out,
+hipError_t launch_loss_reduce(const float* loss_rows, const int* cnt, const float* scal, float* loss_out,
                               hipStream_t s) {
-  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, T, scal, loss_out);
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, cnt, scal, loss_out);
   return hipGetLastError();
 }
 

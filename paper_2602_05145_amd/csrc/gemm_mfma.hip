@@ -64,6 +64,8 @@ struct MfmaParams {
   float alpha;
   int accumulate;
   int tiles_m, tiles_n;
+  const int* m_dev; int m_off;   // optional device-side M: effective M = clamp(*m_dev - m_off, 0, M)
+  const int* k_dev; int k_off;   // optional device-side K (pair 0 only)
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
@@ -230,11 +232,18 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
   const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
   const int lr = lane & 31, lg = lane >> 5;
 
-  // ---- XCD-aware tile numbering ----
+  // sizes that are only known on the device (block-uniform)
+  if (p.m_dev) p.M = max(0, min(p.M, *p.m_dev - p.m_off));
+  if (p.k_dev) p.K = max(0, min(p.K, *p.k_dev - p.k_off));
+  if (p.K == 0 && p.K2 == 0 && p.accumulate) return;   // nothing to add
+
+  // ---- XCD-aware tile numbering over the tiles that exist for the effective M ----
   int tile_m, tile_n;
   {
-    const int nb = p.tiles_m * p.tiles_n;
+    const int tiles_m = (p.M + BM - 1) / BM;   // <= p.tiles_m, the grid's worst case
+    const int nb = tiles_m * p.tiles_n;
     const int pid = blockIdx.x;
+    if (pid >= nb) return;                     // whole block, before any barrier
     const int xcd = pid & 7, idx = pid >> 3;
     const int q = nb >> 3, r = nb & 7;
     const int v = xcd * q + min(xcd, r) + idx;  // contiguous range per XCD
@@ -242,7 +251,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
     const int per_group = GROUP * p.tiles_n;
     const int gid = v / per_group;
     const int first_m = gid * GROUP;
-    const int gsz = min(p.tiles_m - first_m, GROUP);
+    const int gsz = min(tiles_m - first_m, GROUP);
     const int in_g = v - gid * per_group;
     tile_m = first_m + in_g % gsz;
     tile_n = in_g / gsz;
@@ -480,7 +489,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
   if (a.in_dtype != kBF16) return false;
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
   if (a.lda % 8 || a.ldb % 8 || a.K % 8) return false;
-  if (a.A2 && (a.K2 <= 0 || a.K2 % 8 || !a.B2)) return false;
+  if (a.A2 && (a.K2 <= 0 || a.K2 % 8 || !a.B2 || a.k_dev)) return false;
   if (((uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.A2 | (uintptr_t)a.B2) & 15) return false;
   // 32-bit byte offsets inside one tile
   const int64_t lim = (int64_t)1 << 21;
@@ -536,6 +545,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K; p.K2 = a.A2 ? (int)a.K2 : 0;
   p.lda = (int)a.lda; p.ldb = (int)a.ldb; p.ldc = (int)a.ldc; p.ldr = (int)a.ldr;
   p.alpha = a.alpha; p.accumulate = a.accumulate; p.tiles_m = p.tiles_n = 0;
+  p.m_dev = a.m_dev; p.m_off = (int)a.m_off; p.k_dev = a.k_dev; p.k_off = (int)a.k_off;
   const bool f32out = a.out_dtype == kF32;
   switch (a.layout) {
     case kNT: return f32out ? launch_layout<false, false, float>(p, s) : launch_layout<false, false, bf16_t>(p, s);
@@ -552,6 +562,8 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   const double bytes = es_in * k * ((double)a.M + (double)a.N) +
                        es_out * (double)a.M * (double)a.N * (1.0 + (a.accumulate ? 1.0 : 0.0) + (a.residual ? 1.0 : 0.0));
   ProfScope ps(gemm_kernel_name(a), 2.0 * (double)a.M * (double)a.N * k, bytes, s);
+  if (a.m_dev) prof_dynamic(a.m_dev, a.m_off, a.M);
+  else if (a.k_dev) prof_dynamic(a.k_dev, a.k_off, a.K);
   if (gemm_mfma_supported(a)) return launch_gemm_mfma(a, s);
   return launch_gemm_simple(a, s);
 }

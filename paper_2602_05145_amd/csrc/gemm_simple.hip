@@ -14,6 +14,8 @@ struct SimpleGemmParams {
   int64_t sam, sak, sbn, sbk, ldc, ldr;
   float alpha;
   int accumulate;
+  const int* m_dev; int64_t m_off;
+  const int* k_dev; int64_t k_off;
 };
 
 template <typename TI, typename TO>
@@ -23,6 +25,11 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(SimpleGemmParams p) {
   __shared__ float Bs[BK][BN + 4];
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+  // sizes that are only known on the device (block-uniform)
+  if (p.m_dev) p.M = max((int64_t)0, min(p.M, (int64_t)*p.m_dev - p.m_off));
+  if (p.k_dev) p.K = max((int64_t)0, min(p.K, (int64_t)*p.k_dev - p.k_off));
+  if (m0 >= p.M) return;
+  if (p.K == 0 && p.K2 == 0 && p.accumulate) return;
   float acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -91,6 +98,7 @@ hipError_t launch_gemm_simple(const GemmArgs& a, hipStream_t s) {
   p.A = a.A; p.B = a.B; p.A2 = a.A2; p.B2 = a.B2; p.C = a.C; p.R = a.residual; p.alpha_dev = a.alpha_dev;
   p.M = a.M; p.N = a.N; p.K = a.K; p.K2 = a.A2 ? a.K2 : 0;
   p.ldc = a.ldc; p.ldr = a.ldr; p.alpha = a.alpha; p.accumulate = a.accumulate;
+  p.m_dev = a.m_dev; p.m_off = a.m_off; p.k_dev = a.k_dev; p.k_off = a.k_off;
   switch (a.layout) {
     case kNT: p.sam = a.lda; p.sak = 1; p.sbn = a.ldb; p.sbk = 1; break;
     case kNN: p.sam = a.lda; p.sak = 1; p.sbn = 1; p.sbk = a.ldb; break;

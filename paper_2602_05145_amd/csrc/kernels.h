@@ -27,6 +27,11 @@ struct GemmArgs {
   const float* alpha_dev;   // optional device scalar multiplied into alpha
   int in_dtype, out_dtype;
   int accumulate;
+  // Optional device-side sizes (the LM head works on the rows that carry loss, whose number is only known
+  // on the GPU): effective M = clamp(*m_dev - m_off, 0, M), effective K = clamp(*k_dev - k_off, 0, K).
+  // M / K above stay the upper bounds the grid is sized for; tiles past the effective size exit at once.
+  const int* m_dev; int64_t m_off;
+  const int* k_dev; int64_t k_off;
 };
 bool gemm_mfma_supported(const GemmArgs& a);
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);
@@ -34,9 +39,18 @@ hipError_t launch_gemm_simple(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);  // picks the MFMA path when supported
 
 // ---- elementwise.hip ------------------------------------------------------------------------
-// scal[0] = N = max(1, #kept), scal[1] = 1/N
-hipError_t launch_count_valid(const int32_t* tokens, const uint8_t* mask, int64_t T, int V,
-                              float* scal, hipStream_t s);
+// Row plan of the LM head.  keep_t = mask_t != 0 and 0 <= token_t < V.  scal[0] = N = max(1, #keep),
+// scal[1] = 1/N.  The rows the LM head processes are the kept ones (or all of them if select_all):
+// kept_idx[0..cnt[0]) lists them in ascending order, row_pos[t] is the position of row t in that list or -1.
+hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
+                            float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, hipStream_t s);
+// dst[i] = src[kept_idx[i]] for i < *cnt (rows of width d), same for tokens and mask
+hipError_t launch_gather_rows(int64_t T, int d, const void* src, const int32_t* tokens, const uint8_t* mask,
+                              const int32_t* kept_idx, const int* cnt, void* dst, int32_t* tokens_c,
+                              uint8_t* mask_c, int dtype, hipStream_t s);
+// dst[t] = row_pos[t] >= 0 ? src[row_pos[t]] : 0
+hipError_t launch_scatter_rows(int64_t T, int d, const void* src, const int32_t* row_pos, void* dst, int dtype,
+                               hipStream_t s);
 hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g, float eps, void* y,
                               float* rstd, int dtype, hipStream_t s);
 size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d);
@@ -50,13 +64,18 @@ hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, 
 hipError_t launch_swiglu_bwd(int64_t n, const void* dh, const void* gt, const void* u, void* dgt,
                              void* du, int dtype, hipStream_t s);
 // z [rows, ldz]: per-row log-sum-exp, loss term keep*(lse - z[label]) and optional arg-max
+// rows is an upper bound; rows_dev/rows_off (optional) give the effective count clamp(*rows_dev - rows_off, 0, rows).
+// top1 (optional) is written through top1_idx: top1[top1_idx[row]] = arg-max of row.
 hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, const int32_t* tokens,
-                           const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1, int dtype,
+                           const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1,
+                           const int32_t* top1_idx, const int* rows_dev, int64_t rows_off, int dtype,
                            hipStream_t s);
 // dz = keep * (exp(z - lse) - onehot(label)), written over z (unscaled by 1/N)
 hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t* tokens,
-                        const uint8_t* mask, const float* lse, int dtype, hipStream_t s);
-hipError_t launch_loss_reduce(int64_t T, const float* loss_rows, const float* scal, float* loss_out,
+                        const uint8_t* mask, const float* lse, const int* rows_dev, int64_t rows_off, int dtype,
+                        hipStream_t s);
+// loss = scal[1] * sum of loss_rows[0 .. *cnt)
+hipError_t launch_loss_reduce(const float* loss_rows, const int* cnt, const float* scal, float* loss_out,
                               hipStream_t s);
 
 struct AdamTensor { void* p; const float* g; float* m; float* v; float* master; int64_t n; };

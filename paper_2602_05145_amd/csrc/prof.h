@@ -7,6 +7,8 @@ namespace tide {
 
 bool prof_enabled();
 void prof_begin(const char* kernel, double flops, double bytes, hipStream_t s);
+// the launch just begun works on clamp(*dev - off, 0, maxv) of the maxv units its flops/bytes were computed for
+void prof_dynamic(const int* dev, long long off, long long maxv);
 void prof_end(hipStream_t s);
 
 struct ProfScope {

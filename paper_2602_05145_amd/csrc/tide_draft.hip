@@ -69,7 +69,7 @@ struct Plan {
   int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows;
   size_t es;  // activation element size
   // offsets (bytes)
-  size_t scal, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, z;
+  size_t scal, cnt, kept_idx, row_pos, tokens_c, mask_c, yhat_c, dyhat_c, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, z;
   size_t fwd_end;
   size_t dyhat, dx2, dx1, dx0, dh, dbn, dA, dqkv, da, delta, dg_partial;
   size_t total;
@@ -105,6 +105,11 @@ Plan make_plan(const tide_draft_config* c) {
   const size_t T = (size_t)p.T, es = p.es;
   Bump b;
   p.scal = b.take(64);
+  p.cnt = b.take(64);
+  p.kept_idx = b.take(T * 4);
+  p.row_pos = b.take(T * 4);
+  p.tokens_c = b.take(T * 4);
+  p.mask_c = b.take(T);
   p.rope_cs = b.take((size_t)c->seq * c->head_dim * sizeof(float));
   p.x0 = b.take(T * p.d * es);
   p.r1 = b.take(T * 4);
@@ -121,11 +126,13 @@ Plan make_plan(const tide_draft_config* c) {
   p.x2 = b.take(T * p.d * es);
   p.r3 = b.take(T * 4);
   p.yhat = b.take(T * p.d * es);
+  p.yhat_c = b.take(T * p.d * es);
   p.lse = b.take(T * 4);
   p.loss_rows = b.take(T * 4);
   p.z = b.take((size_t)p.lm_rows * p.ldz * es);
   p.fwd_end = b.off;
   p.dyhat = b.take(T * p.d * es);
+  p.dyhat_c = b.take(T * p.d * es);
   p.dx2 = b.take(T * p.d * es);
   p.dx1 = b.take(T * p.d * es);
   p.dx0 = b.take(T * p.d * es);
@@ -172,11 +179,12 @@ GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const void* A, i
 
 // Forward pass up to the final RMSNorm (everything except the LM head).
 int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const void* hidden_buf,
-                  const int32_t* tokens, const uint8_t* mask, char* ws, const Plan& p, hipStream_t s) {
+                  const int32_t* tokens, const uint8_t* mask, int select_all, char* ws, const Plan& p,
+                  hipStream_t s) {
   const int dt = c->dtype;
   const int64_t T = p.T;
   float* scal = (float*)(ws + p.scal);
-  TIDE_HIP(launch_count_valid(tokens, mask, T, c->vocab, scal, s), "count_valid");
+  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), s), "plan_rows");
   // x0 = Hcat W_fc^T
   TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.x0, p.d, dt, dt), s), "gemm fc");
   TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x0, P->g1, c->rms_eps, ws + p.a, (float*)(ws + p.r1), dt, s), "rmsnorm1");
@@ -207,29 +215,41 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
   return TIDE_OK;
 }
 
-// LM head by row blocks: logits of one block, row statistics, and (training) the logit gradient and the
-// two products that consume it.  The full [T,V] logits never exist.
+// LM head by row blocks over the rows that carry loss (compacted; every row when arg-max ids are wanted):
+// logits of one block, row statistics, and (training) the logit gradient and the two products that
+// consume it.  The full [T,V] logits never exist.  The number of compacted rows lives on the device, so
+// every launch is sized for the worst case and trims itself.
 int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tide_draft_tensors* G,
-                    const int32_t* tokens, const uint8_t* mask, int32_t* top1, char* ws, const Plan& p,
-                    bool train, hipStream_t s) {
+                    const int32_t* tokens, const uint8_t* mask, int32_t* top1, float* loss_out, char* ws,
+                    const Plan& p, bool train, hipStream_t s) {
   const int dt = c->dtype;
   float* scal = (float*)(ws + p.scal);
+  const int* cnt = (const int*)(ws + p.cnt);
+  const int32_t* kept_idx = (const int32_t*)(ws + p.kept_idx);
+  const int32_t* tokens_c = (const int32_t*)(ws + p.tokens_c);
+  const uint8_t* mask_c = (const uint8_t*)(ws + p.mask_c);
   float* lse = (float*)(ws + p.lse);
   float* loss_rows = (float*)(ws + p.loss_rows);
-  char* yhat = ws + p.yhat;
+  char* yhat_c = ws + p.yhat_c;
   char* z = ws + p.z;
+  TIDE_HIP(launch_gather_rows(p.T, (int)p.d, ws + p.yhat, tokens, mask, kept_idx, cnt, yhat_c, (int32_t*)(ws + p.tokens_c), (uint8_t*)(ws + p.mask_c), dt, s), "gather rows");
   int blk = 0;
   for (int64_t r0 = 0; r0 < p.T; r0 += p.lm_rows, ++blk) {
     const int64_t rows = (p.T - r0 < p.lm_rows) ? (p.T - r0) : p.lm_rows;
-    const char* yb = yhat + (size_t)r0 * p.d * p.es;
-    TIDE_HIP(launch_gemm(gemm_args(kNT, rows, p.V, p.d, yb, p.d, P->w_lm, p.d, z, p.ldz, dt, dt), s), "gemm lm_head");
-    TIDE_HIP(launch_ce_stats(rows, (int)p.V, z, p.ldz, tokens + r0, mask + r0, lse + r0, loss_rows + r0, top1 ? top1 + r0 : nullptr, dt, s), "ce stats");
+    const char* yb = yhat_c + (size_t)r0 * p.d * p.es;
+    {
+      GemmArgs g = gemm_args(kNT, rows, p.V, p.d, yb, p.d, P->w_lm, p.d, z, p.ldz, dt, dt);
+      g.m_dev = cnt; g.m_off = r0;
+      TIDE_HIP(launch_gemm(g, s), "gemm lm_head");
+    }
+    TIDE_HIP(launch_ce_stats(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, loss_rows + r0, top1, top1 ? kept_idx + r0 : nullptr, cnt, r0, dt, s), "ce stats");
     if (!train) continue;
-    TIDE_HIP(launch_ce_dz(rows, (int)p.V, z, p.ldz, tokens + r0, mask + r0, lse + r0, dt, s), "ce dz");
+    TIDE_HIP(launch_ce_dz(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, cnt, r0, dt, s), "ce dz");
     {
       // dyhat = (1/N) dZ W_lm
-      GemmArgs g = gemm_args(kNN, rows, p.d, p.V, z, p.ldz, P->w_lm, p.d, ws + p.dyhat + (size_t)r0 * p.d * p.es, p.d, dt, dt);
+      GemmArgs g = gemm_args(kNN, rows, p.d, p.V, z, p.ldz, P->w_lm, p.d, ws + p.dyhat_c + (size_t)r0 * p.d * p.es, p.d, dt, dt);
       g.alpha_dev = scal + 1;
+      g.m_dev = cnt; g.m_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm dyhat");
     }
     {
@@ -237,9 +257,13 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
       GemmArgs g = gemm_args(kTN, p.V, p.d, rows, z, p.ldz, yb, p.d, G->w_lm, p.d, dt, kF32);
       g.alpha_dev = scal + 1;
       g.accumulate = blk > 0;
+      g.k_dev = cnt; g.k_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
     }
   }
+  TIDE_HIP(launch_loss_reduce(loss_rows, cnt, scal, loss_out, s), "loss reduce");
+  if (train)   // back to one row per position (zero where no loss is taken)
+    TIDE_HIP(launch_scatter_rows(p.T, (int)p.d, ws + p.dyhat_c, (const int32_t*)(ws + p.row_pos), ws + p.dyhat, dt, s), "scatter rows");
   return TIDE_OK;
 }
 
@@ -262,7 +286,7 @@ int64_t tide_draft_workspace_offset(const tide_draft_config* cfg, const char* na
       {"scal", p.scal}, {"x0", p.x0}, {"r1", p.r1}, {"a", p.a}, {"qkv", p.qkv}, {"attn_lse", p.attn_lse},
       {"A", p.A}, {"x1", p.x1}, {"r2", p.r2}, {"bn", p.bn}, {"gt", p.gt}, {"u", p.u}, {"h", p.h},
       {"x2", p.x2}, {"r3", p.r3}, {"yhat", p.yhat}, {"lse", p.lse}, {"loss_rows", p.loss_rows}, {"z", p.z},
-      {"dyhat", p.dyhat}, {"dx2", p.dx2}, {"dx1", p.dx1}, {"dx0", p.dx0}, {"dh", p.dh}, {"dbn", p.dbn},
+      {"dyhat", p.dyhat}, {"yhat_c", p.yhat_c}, {"dyhat_c", p.dyhat_c}, {"cnt", p.cnt}, {"kept_idx", p.kept_idx}, {"dx2", p.dx2}, {"dx1", p.dx1}, {"dx0", p.dx0}, {"dh", p.dh}, {"dbn", p.dbn},
       {"dA", p.dA}, {"dqkv", p.dqkv}, {"da", p.da}};
   for (auto& e : tab)
     if (std::strcmp(e.n, name) == 0) return (int64_t)e.o;
@@ -279,12 +303,9 @@ int tide_draft_forward(const tide_draft_config* cfg, const tide_draft_tensors* p
   if (rc) return rc;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, ws, p, s);
+  rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, top1_out != nullptr, ws, p, s);
   if (rc) return rc;
-  rc = enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, top1_out, ws, p, false, s);
-  if (rc) return rc;
-  TIDE_HIP(launch_loss_reduce(p.T, (const float*)(ws + p.loss_rows), (const float*)(ws + p.scal), loss_out, s), "loss reduce");
-  return TIDE_OK;
+  return enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, top1_out, loss_out, ws, p, false, s);
 }
 
 int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
@@ -309,11 +330,10 @@ int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* para
   tide_draft_tensors* G = grads;
   const int64_t T = p.T;
 
-  rc = enqueue_trunk(cfg, P, hidden_buf, tokens, loss_mask, ws, p, s);
+  rc = enqueue_trunk(cfg, P, hidden_buf, tokens, loss_mask, 0, ws, p, s);
   if (rc) return rc;
-  rc = enqueue_lm_head(cfg, P, G, tokens, loss_mask, nullptr, ws, p, true, s);
+  rc = enqueue_lm_head(cfg, P, G, tokens, loss_mask, nullptr, loss_out, ws, p, true, s);
   if (rc) return rc;
-  TIDE_HIP(launch_loss_reduce(T, (const float*)(ws + p.loss_rows), (const float*)(ws + p.scal), loss_out, s), "loss reduce");
 
   float* dgp = (float*)(ws + p.dg_partial);
   // final norm
@@ -451,7 +471,7 @@ int tide_rope(int B, int S, int nh, int nkv, int dh, float theta, void* qkv, flo
 // ---- optional per-launch profiler (prof.h) --------------------------------------------------------
 namespace tide {
 namespace {
-struct ProfRec { const char* name; double flops, bytes; hipEvent_t e0, e1; };
+struct ProfRec { const char* name; double flops, bytes; hipEvent_t e0, e1; const int* dyn; long long dyn_off, dyn_max; };
 struct Profiler {
   std::mutex mu;
   bool on = false;
@@ -471,9 +491,18 @@ bool prof_enabled() { return g_prof.on; }
 
 void prof_begin(const char* kernel, double flops, double bytes, hipStream_t s) {
   std::lock_guard<std::mutex> lk(g_prof.mu);
-  ProfRec r{kernel, flops, bytes, g_prof.get(), g_prof.get()};
+  ProfRec r{kernel, flops, bytes, g_prof.get(), g_prof.get(), nullptr, 0, 0};
   if (r.e0) (void)hipEventRecord(r.e0, s);
   g_prof.recs.push_back(r);
+}
+
+void prof_dynamic(const int* dev, long long off, long long maxv) {
+  if (!g_prof.on) return;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  if (g_prof.recs.empty()) return;
+  g_prof.recs.back().dyn = dev;
+  g_prof.recs.back().dyn_off = off;
+  g_prof.recs.back().dyn_max = maxv;
 }
 
 void prof_end(hipStream_t s) {
@@ -507,7 +536,17 @@ int tide_profile_stop(char* report, size_t report_bytes) {
     Agg* a = nullptr;
     for (auto& x : agg) if (std::strcmp(x.name, r.name) == 0) { a = &x; break; }
     if (!a) { agg.push_back(Agg{r.name, 0, 0, 0, 0}); a = &agg.back(); }
-    a->n += 1; a->ms += ms; a->flops += r.flops; a->bytes += r.bytes;
+    double scale = 1.0;
+    if (r.dyn && r.dyn_max > 0) {
+      // the launch trimmed itself to a device-side size: read it back (events are complete, value is final)
+      int v = 0;
+      hipError_t e = hipMemcpy(&v, r.dyn, sizeof(int), hipMemcpyDeviceToHost);
+      if (e != hipSuccess) return hip_fail(e, "profile size read-back");
+      long long eff = (long long)v - r.dyn_off;
+      eff = eff < 0 ? 0 : (eff > r.dyn_max ? r.dyn_max : eff);
+      scale = (double)eff / (double)r.dyn_max;
+    }
+    a->n += 1; a->ms += ms; a->flops += r.flops * scale; a->bytes += r.bytes * scale;
     if (r.e0) g_prof.pool.push_back(r.e0);
     if (r.e1) g_prof.pool.push_back(r.e1);
   }
