@@ -159,13 +159,18 @@ def main():
     assert loss == loss and loss > 0, f"bad loss {loss}"
 
     ms = wall * 1e3 / args.steps
-    flops = W.flops_per_step(cfg)
+    # FLOPs.  "all positions" is the algorithmic count of the whole step (2 flop/MAC, causal attention at
+    # S(S+1)/2, no projection input gradient, no logits recompute).  The library skips the three
+    # vocabulary-sized products for positions that carry no loss (they contribute exactly zero), so the
+    # "executed" count removes 6*d*V flop for each of them; MFU is quoted on the executed count.
+    flops_all = W.flops_per_step(cfg)
+    n_loss = int(((tr.mask != 0) & (tr.tokens >= 0) & (tr.tokens < cfg["vocab"])).sum().item())
+    flops = flops_all - 6.0 * cfg["hidden"] * cfg["vocab"] * (T - n_loss)
     prof.sort(key=lambda r: -r["total_ms"])
     kernel_ms = sum(r["total_ms"] for r in prof)
-    dom = next(r for r in prof if r["flops"] > 0)
-    for r in prof:
-        if r["kernel"].startswith("gemm_mfma") and r["total_ms"] > dom["total_ms"]:
-            dom = r
+    dom = max((r for r in prof if r["kernel"].startswith("gemm_mfma")), key=lambda r: r["total_ms"], default=None)
+    if dom is None:
+        dom = next(r for r in prof if r["flops"] > 0)
     dom_tflops = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": None,
@@ -180,9 +185,11 @@ def main():
         "config": {"workload": f"{cfg['name']}: batch {cfg['batch']} x seq {cfg['seq']}, 3x{cfg['target_hidden']} captured "
                                f"states -> d {cfg['hidden']}, {cfg['n_heads']}/{cfg['n_kv_heads']} heads x {cfg['head_dim']}, "
                                f"FFN {cfg['ffn']}, vocab {cfg['vocab']}", "global_batch": cfg["batch"], "seq_len": cfg["seq"],
-                   "params_M": W.n_params(cfg) / 1e6},
-        "tflops_per_step": flops / 1e12, "achieved_tflops": flops / (ms * 1e-3) / 1e12,
+                   "params_M": W.n_params(cfg) / 1e6, "loss_positions": n_loss, "positions": T},
+        "tflops_per_step_executed": flops / 1e12, "tflops_per_step_all_positions": flops_all / 1e12,
+        "achieved_tflops": flops / (ms * 1e-3) / 1e12,
         "mfu_vs_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "mfu_vs_bf16_peak_all_positions": flops_all / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "loss_last_step": loss,
         "roofline": roofline,
         "kernels": [{"kernel": r["kernel"], "ms_per_step": r["total_ms"] / args.steps,
