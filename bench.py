@@ -20,6 +20,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the GEMM instantiations at the 8B shape, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
+# WRITE_SIZE x 1.0 after calibration against a plain copy): profiles/gemm_tn_8b_hbm_traffic.txt
+MEASURED_TRAFFIC_8B = {"gemm_mfma_tn_256_f32out": 9.58e9, "gemm_mfma_nt_256_bf16out": 8.54e9,
+                       "gemm_mfma_nn_256_bf16out": 8.39e9}
 
 
 def device_workload(cfg, device, seed):
@@ -124,6 +128,8 @@ def main():
     ap.add_argument("--workload", default="8b", help="tiny | small | 8b | longctx | 32b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", default="1x256", help="batch x seq of the oracle's timed slice")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); run it with --gpus 1",
@@ -155,6 +161,13 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     prof = B.tide_profile_stop()
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     loss = float(tr.loss.item())
     assert loss == loss and loss > 0, f"bad loss {loss}"
 
@@ -173,7 +186,8 @@ def main():
         dom = next(r for r in prof if r["flops"] > 0)
     dom_tflops = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": dom_tflops / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_8B.get(dom["kernel"]) if cfg["name"] == "8b" else None,
                 "launches_per_step": dom["launches"] / args.steps,
                 "avg_launch_ms": dom["total_ms"] / dom["launches"],
                 "flops_per_launch": dom["flops"] / dom["launches"]}
