@@ -126,6 +126,16 @@ int tide_draft_forward(const tide_draft_config *cfg, const tide_draft_tensors *p
                        float *loss_out, int32_t *top1_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* Evaluation pass of the paper's Algorithm 1 (the held-out check that gates deployment of a newly trained
+ * draft) in the paper's accuracy metric (Fig. 7 caption: top-1 match rate between draft and target): writes
+ * the masked mean cross-entropy to *loss_out and, to *accuracy_out (DEVICE float), the fraction of the N
+ * loss-carrying positions whose arg-max token (lowest index on ties) equals tokens.  Forward only, LM head on
+ * the loss-carrying rows only.  Arguments as in tide_draft_forward. */
+int tide_draft_eval(const tide_draft_config *cfg, const tide_draft_tensors *params,
+                    const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                    float *loss_out, float *accuracy_out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
 /* One training step: forward, full backward, AdamW (Sec. 3.3: the draft is
  * fine-tuned on the signals accumulated from serving).
  *   params     in/out: updated in place (bf16 mode: re-rounded from master)

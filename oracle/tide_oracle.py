@@ -197,6 +197,15 @@ def lmhead_ce_fwd(yhat, w_lm, tokens, loss_mask, row_chunk=1024, want_top1=False
     return out + (top1,) if want_top1 else out
 
 
+def top1_accuracy(top1, tokens, loss_mask, vocab):
+    """Fraction of the N = max(1, #kept) loss-carrying positions whose arg-max equals the label: the paper's
+    training-accuracy metric (Fig. 7 caption) and what Algorithm 1's evaluation step reports."""
+    tok = np.asarray(tokens).reshape(-1)
+    keep = effective_mask(tok, loss_mask, vocab)
+    N = max(1, int(keep.sum()))
+    return float(np.sum(keep & (np.asarray(top1).reshape(-1) == tok))) / N
+
+
 def lmhead_ce_bwd(yhat, w_lm, tokens, loss_mask, lse, row_chunk=1024):
     """dz = (keep/N) (softmax(z) - onehot(y));  dyhat = dz W_lm;  dW_lm = dz^T yhat."""
     T = yhat.shape[0]

@@ -65,6 +65,8 @@ _lib.tide_draft_workspace_offset.restype = _i64
 _lib.tide_draft_workspace_offset.argtypes = [_cfgp, C.c_char_p]
 _lib.tide_draft_forward.restype = _i32
 _lib.tide_draft_forward.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.tide_draft_eval.restype = _i32
+_lib.tide_draft_eval.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.tide_draft_train_step.restype = _i32
 _lib.tide_draft_train_step.argtypes = [_cfgp, _tp, _tp, _ap, _vp, _vp, _vp, _f32, _vp, _vp, _sz, _vp]
 _lib.tide_gemm_workspace_bytes.restype = _sz
@@ -90,7 +92,7 @@ _lib.tide_profile_stop.restype = _i32
 _lib.tide_profile_stop.argtypes = [C.c_char_p, _sz]
 
 EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
-            "tide_draft_forward", "tide_draft_train_step", "tide_gemm_workspace_bytes", "tide_gemm",
+            "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_gemm_workspace_bytes", "tide_gemm",
             "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd",
             "tide_attention_fwd", "tide_attention_bwd", "tide_rope", "tide_profile_start",
             "tide_profile_stop")
@@ -150,6 +152,15 @@ def tide_draft_forward(cfg, params, hidden_buf, tokens, loss_mask, loss_out, top
                                  C.byref(params) if params is not None else None,
                                  _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(loss_out),
                                  _ptr(top1_out), _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_draft_eval(cfg, params, hidden_buf, tokens, loss_mask, loss_out, accuracy_out, workspace,
+                    workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_eval(C.byref(cfg) if cfg is not None else None,
+                              C.byref(params) if params is not None else None,
+                              _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(loss_out),
+                              _ptr(accuracy_out), _ptr(workspace), int(workspace_bytes), stream)
     return _check(rc) if check else rc
 
 

@@ -484,6 +484,7 @@ __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ z, 
                                                        float* __restrict__ loss_rows,
                                                        int32_t* __restrict__ top1,
                                                        const int32_t* __restrict__ top1_idx,
+                                                       float* __restrict__ hit_rows,
                                                        const int* __restrict__ rows_dev, int rows_off) {
   __shared__ float sm_m[4], sm_s[4], sm_bv[4];
   __shared__ int sm_bi[4];
@@ -553,14 +554,17 @@ __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ z, 
     const int tk = tokens[row];
     const bool keep = mask[row] != 0 && tk >= 0 && tk < V;
     loss_rows[row] = keep ? (l - ldf(zr, (size_t)tk)) : 0.f;
-    if (TOP1) top1[top1_idx ? top1_idx[row] : (int)row] = BI;
+    if (TOP1) {
+      if (top1) top1[top1_idx ? top1_idx[row] : (int)row] = BI;
+      if (hit_rows) hit_rows[row] = (keep && BI == tk) ? 1.f : 0.f;
+    }
   }
 }
 
 hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, const int32_t* tokens,
                            const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1,
-                           const int32_t* top1_idx, const int* rows_dev, int64_t rows_off, int dtype,
-                           hipStream_t s) {
+                           const int32_t* top1_idx, float* hit_rows, const int* rows_dev, int64_t rows_off,
+                           int dtype, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (ldz % 8 != 0) return hipErrorInvalidValue;
   ProfScope ps("ce_stats", 0, (double)rows * V * dtype_size(dtype), s);
@@ -568,11 +572,11 @@ hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, cons
   dim3 grid((unsigned)rows), blk(256);
   const int ro = (int)rows_off;
   if (dtype == kBF16) {
-    if (top1) hipLaunchKernelGGL((ce_stats_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, rows_dev, ro);
-    else hipLaunchKernelGGL((ce_stats_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, rows_dev, ro);
+    if (top1 || hit_rows) hipLaunchKernelGGL((ce_stats_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, hit_rows, rows_dev, ro);
+    else hipLaunchKernelGGL((ce_stats_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, hit_rows, rows_dev, ro);
   } else {
-    if (top1) hipLaunchKernelGGL((ce_stats_kernel<float, true>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, rows_dev, ro);
-    else hipLaunchKernelGGL((ce_stats_kernel<float, false>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, rows_dev, ro);
+    if (top1 || hit_rows) hipLaunchKernelGGL((ce_stats_kernel<float, true>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, hit_rows, rows_dev, ro);
+    else hipLaunchKernelGGL((ce_stats_kernel<float, false>), grid, blk, 0, s, (const float*)z, ldz, V, tokens, mask, lse, loss_rows, top1, top1_idx, hit_rows, rows_dev, ro);
   }
   return hipGetLastError();
 }
@@ -617,22 +621,32 @@ hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t
   return hipGetLastError();
 }
 
-// loss = (1/N) * sum of loss_rows[0 .. *cnt)   (single block, fixed summation order: deterministic)
+// loss = (1/N) * sum of loss_rows[0 .. *cnt) and, optionally, accuracy = (1/N) * sum of hit_rows[0 .. *cnt)
+// (single block, fixed summation order: deterministic)
 __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restrict__ loss_rows,
+                                                           const float* __restrict__ hit_rows,
                                                            const int* __restrict__ cnt,
                                                            const float* __restrict__ scal,
-                                                           float* __restrict__ loss_out) {
+                                                           float* __restrict__ loss_out,
+                                                           float* __restrict__ acc_out) {
   __shared__ float red[32];
   const int n = *cnt;
-  float a = 0.f;
-  for (int i = threadIdx.x; i < n; i += 1024) a += loss_rows[i];
-  float tot = block_sum(a, red);
+  float a = 0.f, h = 0.f;
+  for (int i = threadIdx.x; i < n; i += 1024) {
+    a += loss_rows[i];
+    if (hit_rows) h += hit_rows[i];
+  }
+  const float tot = block_sum(a, red);
   if (threadIdx.x == 0) *loss_out = tot * scal[1];
+  if (hit_rows && acc_out) {
+    const float hits = block_sum(h, red);
+    if (threadIdx.x == 0) *acc_out = hits * scal[1];
+  }
 }
 
-hipError_t launch_loss_reduce(const float* loss_rows, const int* cnt, const float* scal, float* loss_out,
-                              hipStream_t s) {
-  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, cnt, scal, loss_out);
+hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, const int* cnt, const float* scal,
+                              float* loss_out, float* acc_out, hipStream_t s) {
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, hit_rows, cnt, scal, loss_out, acc_out);
   return hipGetLastError();
 }
 

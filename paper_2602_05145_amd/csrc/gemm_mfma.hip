@@ -6,36 +6,40 @@
 // Design
 //   * A block computes a BM x BN tile (256x256 with 8 wavefronts = 2 per SIMD, or 128x128 with 4) with
 //     v_mfma_f32_32x32x16_bf16; a wave owns TM x TN MFMA tiles (4x2 or 2x2).  Two waves per SIMD matter:
-//     one wave alone cannot issue MFMAs back to back (measured ~83 % of the multi-wave MFMA rate).
+//     one wave alone cannot issue MFMAs back to back (measured ~83 % of the multi-wave MFMA rate), and a
+//     four-wave 256x256 variant (128x128 per wave, less LDS traffic) measured 10-20 % slower.
 //   * K is walked in slabs through an LDS ring that always holds 128 k-columns and is filled by LDS-DMA
 //     buffer loads (global -> LDS without passing through registers, hardware zero-fill outside the valid
-//     extent, so ragged M / N / K need no special code).  What bounds this kernel is the number of L2
-//     requests a CU can keep in flight, so the ring shape follows the operand layout: with a K-major
-//     operand the slab is 64 deep (TWO stages): each of its rows then fetches one whole 128-byte line
-//     instead of two 64-byte halves (+3-6 % measured); when both operands are row-major over K (TN) their
-//     rows are contiguous anyway and FOUR stages of 32 win (+30 % over two of 64) because the loads of
-//     slab k+3 are issued while slab k is multiplied.  Register-staged loads (no DMA) waited ~50 % of
-//     their cycles.
+//     extent, so ragged M / N / K need no special code).  What bounds this kernel is the memory side: with
+//     every operand row aliased to one line (all loads hit) the same code runs 25-40 % faster.  The ring
+//     shape follows the operand layout: with a K-major operand the slab is 64 deep (TWO stages): each of
+//     its rows then fetches one whole 128-byte line instead of two 64-byte halves; when both operands are
+//     row-major over K (TN) their rows are contiguous anyway and FOUR stages of 32 win because the loads
+//     of slab k+3 are issued while slab k is multiplied.
 //   * Synchronisation is manual: one `s_waitcnt vmcnt(n)` (own DMA of the next slab has landed, younger
-//     slabs stay in flight) and one `s_barrier` per slab.  Each stage is its own __shared__ array: the compiler can then tell that the
-//     operand reads do not alias the DMA writes in flight and does not drain vmcnt before them.  Slabs
-//     past K are dummies (their loads fall outside the buffer and zero-fill the free stage) so the steady
-//     state has no branches.
+//     slabs stay in flight) and one `s_barrier` per slab.  Each stage is its own __shared__ array and every
+//     read address is "array + per-lane offset + constant": the compiler can then tell that the operand
+//     reads do not alias the DMA writes in flight and does not drain vmcnt before them (it loses that
+//     information on address chains more than a few steps long, and then silently waits).  Slabs past K
+//     are dummies (their loads fall outside the buffer and zero-fill the free stage) so the steady state
+//     has no branches.
+//   * The two-stage loop is software-pipelined across slabs: the barrier of a slab sits before its last
+//     k16 quarter, when every wave holds that quarter's operands in registers; the DMA of slab k+2 and the
+//     first operand reads of slab k+1 are issued in the shadow of that quarter's MFMAs.
 //   * Instruction order inside a k16 quarter is pinned with sched_group_barrier: MFMA / LDS read (or DMA
 //     issue) alternate, so LDS and address traffic hides in the MFMA shadow.
 //   * LDS layout.  A "K-major" operand (contraction index contiguous in memory) is stored [row][BK] with
-//     the 16-byte pieces of a row XOR-swizzled by (row >> 1) & 7 (BK 64) or (row >> 2) & 3 (BK 32): DMA can only write 1 KiB
-//     contiguous per instruction, so padding is impossible, and the swizzle makes the 16-byte operand
-//     reads of 16 consecutive rows hit 16 different bank groups.  An operand whose contraction index is
-//     the slow one (B of NN, both operands of TN) is stored exactly as in memory, [k][row], and
-//     transposed on the way to the MFMA: each lane reads T consecutive rows for 8 consecutive k (8 narrow
-//     LDS reads) and regroups the 16-bit halves with v_perm_b32; MFMA tile i of a wave then covers rows
-//     {T*r + i}, an interleaving the epilogue undoes.  No transposed copy of an operand ever exists in HBM.
+//     the 16-byte pieces of a row XOR-swizzled by (row >> 1) & 7 (BK 64) or (row >> 2) & 3 (BK 32): DMA can
+//     only write 1 KiB contiguous per instruction, so padding is impossible, and the swizzle makes the
+//     16-byte operand reads of 16 consecutive rows hit 16 different bank groups.  An operand whose
+//     contraction index is the slow one (B of NN, both operands of TN) is stored as in memory, [k][row],
+//     and transposed on the way to the MFMA by ds_read_b64_tr_b16 (two per MFMA operand: four k each);
+//     the pieces of k-row k are XOR-swizzled by (k & 3) << 2 so that the four k-rows of one such read lie
+//     in different banks.  No transposed copy of an operand ever exists in HBM.
 //   * The contraction may run over two operand pairs back to back (d b = dGate W_gate + dUp W_up), and
 //     the epilogue fuses alpha (host and device scalar), a residual add, accumulation into C and the cast.
-//     When B is N-contiguous a lane owns TN consecutive output columns and stores them as one vector;
-//     NT results without residual/accumulate go through a wave-private LDS patch to leave as 16-byte
-//     row segments.
+//     bf16 results without residual/accumulate go through a wave-private LDS patch to leave as 16-byte
+//     row segments; everything else is stored straight from the accumulators (128-byte row segments).
 //   * Work-groups are renumbered so that each of the 8 XCDs (round-robin dispatch) gets a contiguous
 //     range of tiles, walked in groups of 8 tile-rows: neighbouring tiles share A/B panels in that
 //     XCD's L2.
@@ -75,6 +79,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // wait until at most n of this wave's vector-memory operations are outstanding (vmcnt only)
 #define TIDE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
+// swizzle of a row-major stage: 16-byte piece index ^= (k-row & 3) << 2, i.e. the four k-rows that one
+// transposing read touches sit in four different 64-byte bank groups
+#define TIDE_RSWZ(kq) ((kq) << 2)
 constexpr uint32_t kOobOffset = 0x7FFFFFF0u;  // beyond any buffer extent used here: the load returns zeros
 
 // One operand (A or B) of one block: R rows (BM or BN) of the tile, either K-major or row-major over K.
@@ -89,7 +96,7 @@ struct Operand {
   static constexpr int KPIECES = BK / 8;                                 // 16-byte pieces per K-major row (4 or 8)
   static constexpr int KROWS = 64 / KPIECES;                             // K-major rows per DMA chunk (16 or 8)
   static constexpr int SWZ_SHIFT = (BK == 32) ? 2 : 1;                   // swizzle: piece ^= (row >> shift) & (KPIECES-1)
-  static constexpr int kReadsPerQuarter = RMAJ ? 8 : T;                  // LDS read instructions per k16 quarter
+  static constexpr int kReadsPerQuarter = RMAJ ? 2 * T : T;              // LDS read instructions per k16 quarter
 
   // Stateless on purpose: the tile pointers and extents stay plain kernel locals (SGPRs).  Bundling them
   // in a struct with the per-lane offsets made the compiler keep that struct in scratch memory, the
@@ -100,10 +107,12 @@ struct Operand {
   static __device__ __forceinline__ void lane_offsets(int ld, int wave, int lane, uint32_t (&off)[PER_WAVE],
                                                       int (&piece)[PER_WAVE]) {
     if (RMAJ) {
+      // chunk = RPC k-rows x (R*2) bytes; LDS slot (krow, s) holds piece s ^ ((krow & 3) << 2) of that k-row
       const int kr = lane / PPR, pc = lane % PPR;
 #pragma unroll
       for (int i = 0; i < PER_WAVE; ++i) {
-        off[i] = (uint32_t)((((wave * PER_WAVE + i) * RPC + kr) * ld + pc * 8) * 2);
+        const int krow = (wave * PER_WAVE + i) * RPC + kr;
+        off[i] = (uint32_t)((krow * ld + (pc ^ TIDE_RSWZ(krow & 3)) * 8) * 2);
         piece[i] = 0;
       }
     } else {
@@ -145,37 +154,49 @@ struct Operand {
     }
   }
 
-  // MFMA operand fragments of k16 step `kk` (< BK/16) for the wave whose first tile row is wbase
-  static __device__ __forceinline__ void frags(const bf16_t* stage, int kk, int wbase, int lr, int lg, u32x4_t (&f)[T]) {
+  // Per-lane element offsets of the operand reads inside a stage, computed once.  K-major: one per k16
+  // step (the swizzle is an XOR, not additive in the step); row-major: one per MFMA tile.  The values are
+  // made opaque to the optimiser: every read address is then "stage array + offset + constant", a short
+  // chain that keeps the no-alias information of the stage arrays (longer chains lose it, and a read
+  // without it waits for all DMA writes in flight).
+  static constexpr int NRO = RMAJ ? T : BK / 16;
+  static __device__ __forceinline__ void read_offsets(int wbase, int lane, uint32_t (&ro)[NRO]) {
+    const int lr = lane & 31, lg = lane >> 5;
     if (RMAJ) {
-      const bf16_t* src = stage + (kk * 16 + lg * 8) * R + wbase + T * lr;
-      if (T == 4) {
-        uint2 r[8];
+      // transposing LDS reads: a group of 16 lanes addresses 4 k-rows x 16 tile rows (lane j: k-row j / 4,
+      // rows 4 * (j % 4) .. +3) and lane i of the group receives tile row i for those 4 k
+      const int hb = (lane >> 4) & 1, kq = (lane >> 2) & 3, rq = lane & 3;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const uint2*>(src + j * R);
-#pragma unroll
-        for (int i = 0; i < T; ++i)
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const uint32_t lo = (i < 2) ? r[2 * w].x : r[2 * w].y;
-            const uint32_t hi = (i < 2) ? r[2 * w + 1].x : r[2 * w + 1].y;
-            f[i][w] = __builtin_amdgcn_perm(hi, lo, (i & 1) ? 0x07060302u : 0x05040100u);
-          }
-      } else {
-        uint32_t r[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const uint32_t*>(src + j * R);
-#pragma unroll
-        for (int i = 0; i < T; ++i)
-#pragma unroll
-          for (int w = 0; w < 4; ++w)
-            f[i][w] = __builtin_amdgcn_perm(r[2 * w + 1], r[2 * w], (i & 1) ? 0x07060302u : 0x05040100u);
+      for (int i = 0; i < T; ++i) {
+        const int col = wbase + 32 * i + 16 * hb + 4 * rq;
+        ro[i] = (uint32_t)((lg * 8 + kq) * R + ((((col >> 3) ^ TIDE_RSWZ(kq)) << 3) | (col & 7)));
       }
     } else {
       const int sw = (lr >> SWZ_SHIFT) & (KPIECES - 1);
-      const bf16_t* src = stage + (wbase + lr) * BK + (((kk * 2 + lg) ^ sw) * 8);
 #pragma unroll
-      for (int i = 0; i < T; ++i) f[i] = *reinterpret_cast<const u32x4_t*>(src + i * 32 * BK);
+      for (int kk = 0; kk < NRO; ++kk) ro[kk] = (uint32_t)((wbase + lr) * BK + (((kk * 2 + lg) ^ sw) * 8));
+    }
+#pragma unroll
+    for (int i = 0; i < NRO; ++i) asm("" : "+v"(ro[i]));
+  }
+
+  // MFMA operand fragments of k16 step `kk` (< BK/16)
+  template <typename StagePtr>
+  static __device__ __forceinline__ void frags(StagePtr stage, int kk, const uint32_t (&ro)[NRO], u32x4_t (&f)[T]) {
+    if (RMAJ) {
+      typedef short s16x4_t __attribute__((ext_vector_type(4)));
+      typedef __attribute__((address_space(3))) s16x4_t* lds_tr_t;
+#pragma unroll
+      for (int i = 0; i < T; ++i) {
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_t)(stage + ro[i] + (kk * 16) * R));
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_t)(stage + ro[i] + (kk * 16 + 4) * R));
+        const uint2 a = __builtin_bit_cast(uint2, lo), b2 = __builtin_bit_cast(uint2, hi);
+        f[i][0] = a.x; f[i][1] = a.y; f[i][2] = b2.x; f[i][3] = b2.y;
+      }
+    } else {
+      typedef __attribute__((address_space(3))) const u32x4_t* lds_v4_t;
+#pragma unroll
+      for (int i = 0; i < T; ++i) f[i] = *(lds_v4_t)(stage + ro[kk] + i * 32 * BK);
     }
   }
 };
@@ -227,6 +248,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
     else if constexpr (decltype(ST)::value == 2) return s2;
     else return s3;
   };
+  typedef __attribute__((address_space(3))) const bf16_t* lds_bf_t;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
@@ -292,10 +314,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
     OpA::issue(sb, pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc, a_off, a_piece, wave);
     OpB::issue(sb + A_STAGE, pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc, b_off, b_piece, wave);
   };
+  uint32_t a_ro[OpA::NRO], b_ro[OpB::NRO];
+  OpA::read_offsets(wave_m * WM, lane, a_ro);
+  OpB::read_offsets(wave_n * WN, lane, b_ro);
   auto frags = [&](auto ST, int kk, u32x4_t (&fa)[TM], u32x4_t (&fb)[TN]) {
-    const bf16_t* sb = stage(ST);
-    OpA::frags(sb, kk, wave_m * WM, lr, lg, fa);
-    OpB::frags(sb + A_STAGE, kk, wave_n * WN, lr, lg, fb);
+    const lds_bf_t sb = (lds_bf_t)stage(ST);
+    OpA::frags(sb, kk, a_ro, fa);
+    OpB::frags(sb + A_STAGE, kk, b_ro, fb);
   };
   auto mma = [&](u32x4_t (&fa)[TM], u32x4_t (&fb)[TN]) {
 #pragma unroll
@@ -308,21 +333,25 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
 
   u32x4_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
   if constexpr (BK == 64) {
-    // ---- two stages of 64: used when an operand is K-major (its rows then fetch whole 128-byte lines) ----
+    // ---- two stages of 64 ----
+    // Software-pipelined across slabs: the single barrier of a step sits before its LAST k16 quarter.  By
+    // then every wave holds the operands of that quarter in registers, so the stage is free: the DMA of slab
+    // kt+2 is issued into it and the first operands of slab kt+1 are read, both in the shadow of the last
+    // quarter's MFMAs.  No MFMA ever waits for an LDS read that was issued after a barrier.
     issue(Int<0>{}, 0);
-    // One pipeline step: slab kt lives in stage ST; slab kt+1 is loaded into the other stage SO meanwhile.
+    TIDE_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    frags(Int<0>{}, 0, fa0, fb0);
+    issue(Int<1>{}, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    // One step: slab kt lives in stage ST (its quarter-0 operands are already in fa0/fb0), slab kt+1 is in
+    // flight into SO.
     auto step = [&](auto ST, auto SO, int kt) {
-      TIDE_WAIT_VMCNT(0);                // this wave's part of slab kt (issued one step ago) has landed
-      __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done reading stage SO
-      __builtin_amdgcn_sched_barrier(0);
-      // quarter 0: its MFMAs hide the DMA issue of slab kt+1
-      issue(SO, kt + 1);
-      frags(ST, 0, fa0, fb0);
       frags(ST, 1, fa1, fb1);
       mma(fa0, fb0);
-      sched_slots<NMF, 0, NVM, 0>(std::make_integer_sequence<int, NMF>{});
+      sched_slots<NMF, NDS, 0, 0>(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
-      // quarters 1 and 2: MFMAs hide the operand reads of the following quarter
       frags(ST, 2, fa0, fb0);
       mma(fa1, fb1);
       sched_slots<NMF, NDS, 0, 1>(std::make_integer_sequence<int, NMF>{});
@@ -331,7 +360,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
       mma(fa0, fb0);
       sched_slots<NMF, NDS, 0, 2>(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
+      // all operand reads of this wave from ST have returned; its part of slab kt+1 has landed
+      __builtin_amdgcn_s_waitcnt(0);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      frags(SO, 0, fa0, fb0);
+      issue(ST, kt + 2);
       mma(fa1, fb1);
+      // all operand reads ahead of the DMA issues: a read that lost its no-alias information on the way
+      // through the compiler would otherwise wait for the loads just issued
+      __builtin_amdgcn_sched_group_barrier(0x100, NDS, 3);
+      sched_slots<NMF, 0, NVM, 3>(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
     };
     for (int kt = 0; kt < nk_round; kt += 2) {
@@ -380,88 +419,39 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
   const TO* R = (const TO*)p.R;
   const int wm0 = m0 + wave_m * WM, wn0 = n0 + wave_n * WN;
 
-  if constexpr (BNM) {
-    // a lane owns TN consecutive columns: vector stores
-    const int gn = wn0 + TN * lr;
-    const bool vec_ok = (gn + TN <= p.N) && ((p.ldc % TN) == 0) && (!R || (p.ldr % TN) == 0);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
-        const int gm = wm0 + (AMM ? (TM * rr + i) : (32 * i + rr));
-        if (gm >= p.M) continue;
-        float v[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) v[j] = alpha * acc[i][j][q];
-        if (vec_ok) {
-          TO* dst = C + (size_t)gm * p.ldc + gn;
-          if (R) {
-            const TO* rs = R + (size_t)gm * p.ldr + gn;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) v[j] += ldf(rs, j);
-          }
-          if (p.accumulate) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) v[j] += ldf(dst, j);
-          }
-          if constexpr (sizeof(TO) == 4) {
-            if constexpr (TN == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-            else *reinterpret_cast<float2*>(dst) = make_float2(v[0], v[1]);
-          } else {
-            const uint32_t w0 = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
-            if constexpr (TN == 4) {
-              const uint32_t w1 = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
-              *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
-            } else {
-              *reinterpret_cast<uint32_t*>(dst) = w0;
-            }
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            if (gn + j >= p.N) continue;
-            float x = v[j];
-            if (R) x += ldf(R, (size_t)gm * p.ldr + gn + j);
-            if (p.accumulate) x += ldf(C, (size_t)gm * p.ldc + gn + j);
-            stf(C, (size_t)gm * p.ldc + gn + j, x);
-          }
-        }
-      }
-  } else {
-  // B is K-major: a lane owns one column per MFMA tile.
+  // MFMA tile (i, j) of the wave: accumulator register q of lane (lr, lg) is row 8*(q/4) + 4*lg + q%4, column lr.
   bool staged = false;
-  if constexpr (sizeof(TO) == 2 && !AMM) {
-  if (!R && !p.accumulate && (p.ldc % 8) == 0 && (p.N % 8) == 0) {
-    staged = true;
-    // bf16 result through a wave-private LDS patch so that it leaves as 16-byte row segments.
-    // All stages are free here: every wave passed the last barrier after its last real operand read,
-    // and the barrier below orders the (zero) operand reads of the final dummy step before the writes.
-    __builtin_amdgcn_s_barrier();
-    constexpr int PP = WN + 8;                       // patch pitch (elements)
-    static_assert((NW / 2) * 32 * PP <= A_STAGE + B_STAGE, "epilogue patches of half the waves must fit in one stage");
-    bf16_t* patch = (wave < NW / 2 ? s0 : s1) + (wave % (NW / 2)) * (32 * PP);   // 32 x WN per wave
-    constexpr int PIECES = WN / 8;                   // 16-byte pieces per patch row
+  if constexpr (sizeof(TO) == 2) {
+    if (!R && !p.accumulate && (p.ldc % 8) == 0 && (p.N % 8) == 0) {
+      staged = true;
+      // bf16 result through a wave-private LDS patch so that it leaves as 16-byte row segments.
+      // All stages are free here: every wave waited for its own DMA above, and the barrier below orders the
+      // (unused) operand reads of the final dummy slab before the patch writes.
+      __builtin_amdgcn_s_barrier();
+      constexpr int PP = WN + 8;                       // patch pitch (elements)
+      static_assert((NW / 2) * 32 * PP <= A_STAGE + B_STAGE, "epilogue patches of half the waves must fit in one stage");
+      bf16_t* patch = (wave < NW / 2 ? s0 : s1) + (wave % (NW / 2)) * (32 * PP);   // 32 x WN per wave
+      constexpr int PIECES = WN / 8;                   // 16-byte pieces per patch row
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
-          patch[rr * PP + 32 * j + lr] = f2bf(alpha * acc[i][j][q]);
+          for (int q = 0; q < 16; ++q) {
+            const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
+            patch[rr * PP + 32 * j + lr] = f2bf(alpha * acc[i][j][q]);
+          }
+#pragma unroll
+        for (int t = 0; t < 32 * PIECES / 64; ++t) {
+          const int pc = lane + 64 * t;
+          const int row = pc / PIECES, piece = pc % PIECES;
+          const int gm = wm0 + 32 * i + row, gn = wn0 + piece * 8;
+          const u32x4_t val = *reinterpret_cast<const u32x4_t*>(patch + row * PP + piece * 8);
+          if (gm < p.M && gn < p.N)
+            *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(C) + (size_t)gm * p.ldc + gn) = val;
         }
-#pragma unroll
-      for (int t = 0; t < 32 * PIECES / 64; ++t) {
-        const int pc = lane + 64 * t;
-        const int row = pc / PIECES, piece = pc % PIECES;
-        const int gm = wm0 + 32 * i + row, gn = wn0 + piece * 8;
-        const u32x4_t val = *reinterpret_cast<const u32x4_t*>(patch + row * PP + piece * 8);
-        if (gm < p.M && gn < p.N)
-          *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(C) + (size_t)gm * p.ldc + gn) = val;
       }
     }
-  }
   }
   if (!staged) {
 #pragma unroll
@@ -469,7 +459,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
-        const int gm = wm0 + (AMM ? (TM * rr + i) : (32 * i + rr));
+        const int gm = wm0 + 32 * i + rr;
         if (gm >= p.M) continue;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
@@ -481,7 +471,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
           stf(C, (size_t)gm * p.ldc + gn, v);
         }
       }
-  }
   }
 }
 

@@ -65,18 +65,19 @@ hipError_t launch_swiglu_bwd(int64_t n, const void* dh, const void* gt, const vo
                              void* du, int dtype, hipStream_t s);
 // z [rows, ldz]: per-row log-sum-exp, loss term keep*(lse - z[label]) and optional arg-max
 // rows is an upper bound; rows_dev/rows_off (optional) give the effective count clamp(*rows_dev - rows_off, 0, rows).
-// top1 (optional) is written through top1_idx: top1[top1_idx[row]] = arg-max of row.
+// top1 (optional) is written through top1_idx: top1[top1_idx[row]] = arg-max of row; hit_rows (optional)
+// gets 1 where a kept row's arg-max equals its label, else 0.
 hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, const int32_t* tokens,
                            const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1,
-                           const int32_t* top1_idx, const int* rows_dev, int64_t rows_off, int dtype,
-                           hipStream_t s);
+                           const int32_t* top1_idx, float* hit_rows, const int* rows_dev, int64_t rows_off,
+                           int dtype, hipStream_t s);
 // dz = keep * (exp(z - lse) - onehot(label)), written over z (unscaled by 1/N)
 hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t* tokens,
                         const uint8_t* mask, const float* lse, const int* rows_dev, int64_t rows_off, int dtype,
                         hipStream_t s);
-// loss = scal[1] * sum of loss_rows[0 .. *cnt)
-hipError_t launch_loss_reduce(const float* loss_rows, const int* cnt, const float* scal, float* loss_out,
-                              hipStream_t s);
+// loss = scal[1] * sum of loss_rows[0 .. *cnt); optionally accuracy = scal[1] * sum of hit_rows[0 .. *cnt)
+hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, const int* cnt, const float* scal,
+                              float* loss_out, float* acc_out, hipStream_t s);
 
 struct AdamTensor { void* p; const float* g; float* m; float* v; float* master; int64_t n; };
 struct AdamArgs {

@@ -69,7 +69,7 @@ struct Plan {
   int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows;
   size_t es;  // activation element size
   // offsets (bytes)
-  size_t scal, cnt, kept_idx, row_pos, tokens_c, mask_c, yhat_c, dyhat_c, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, z;
+  size_t scal, cnt, kept_idx, row_pos, tokens_c, mask_c, yhat_c, dyhat_c, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
   size_t fwd_end;
   size_t dyhat, dx2, dx1, dx0, dh, dbn, dA, dqkv, da, delta, dg_partial;
   size_t total;
@@ -129,6 +129,7 @@ Plan make_plan(const tide_draft_config* c) {
   p.yhat_c = b.take(T * p.d * es);
   p.lse = b.take(T * 4);
   p.loss_rows = b.take(T * 4);
+  p.hit_rows = b.take(T * 4);
   p.z = b.take((size_t)p.lm_rows * p.ldz * es);
   p.fwd_end = b.off;
   p.dyhat = b.take(T * p.d * es);
@@ -220,8 +221,8 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
 // consume it.  The full [T,V] logits never exist.  The number of compacted rows lives on the device, so
 // every launch is sized for the worst case and trims itself.
 int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tide_draft_tensors* G,
-                    const int32_t* tokens, const uint8_t* mask, int32_t* top1, float* loss_out, char* ws,
-                    const Plan& p, bool train, hipStream_t s) {
+                    const int32_t* tokens, const uint8_t* mask, int32_t* top1, float* loss_out, float* acc_out,
+                    char* ws, const Plan& p, bool train, hipStream_t s) {
   const int dt = c->dtype;
   float* scal = (float*)(ws + p.scal);
   const int* cnt = (const int*)(ws + p.cnt);
@@ -230,6 +231,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
   const uint8_t* mask_c = (const uint8_t*)(ws + p.mask_c);
   float* lse = (float*)(ws + p.lse);
   float* loss_rows = (float*)(ws + p.loss_rows);
+  float* hit_rows = acc_out ? (float*)(ws + p.hit_rows) : nullptr;
   char* yhat_c = ws + p.yhat_c;
   char* z = ws + p.z;
   TIDE_HIP(launch_gather_rows(p.T, (int)p.d, ws + p.yhat, tokens, mask, kept_idx, cnt, yhat_c, (int32_t*)(ws + p.tokens_c), (uint8_t*)(ws + p.mask_c), dt, s), "gather rows");
@@ -242,7 +244,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
       g.m_dev = cnt; g.m_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm lm_head");
     }
-    TIDE_HIP(launch_ce_stats(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, loss_rows + r0, top1, top1 ? kept_idx + r0 : nullptr, cnt, r0, dt, s), "ce stats");
+    TIDE_HIP(launch_ce_stats(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, loss_rows + r0, top1, top1 ? kept_idx + r0 : nullptr, hit_rows ? hit_rows + r0 : nullptr, cnt, r0, dt, s), "ce stats");
     if (!train) continue;
     TIDE_HIP(launch_ce_dz(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, cnt, r0, dt, s), "ce dz");
     {
@@ -261,7 +263,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
       TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
     }
   }
-  TIDE_HIP(launch_loss_reduce(loss_rows, cnt, scal, loss_out, s), "loss reduce");
+  TIDE_HIP(launch_loss_reduce(loss_rows, hit_rows, cnt, scal, loss_out, acc_out, s), "loss reduce");
   if (train)   // back to one row per position (zero where no loss is taken)
     TIDE_HIP(launch_scatter_rows(p.T, (int)p.d, ws + p.dyhat_c, (const int32_t*)(ws + p.row_pos), ws + p.dyhat, dt, s), "scatter rows");
   return TIDE_OK;
@@ -305,7 +307,22 @@ int tide_draft_forward(const tide_draft_config* cfg, const tide_draft_tensors* p
   char* ws = (char*)workspace;
   rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, top1_out != nullptr, ws, p, s);
   if (rc) return rc;
-  return enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, top1_out, loss_out, ws, p, false, s);
+  return enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, top1_out, loss_out, nullptr, ws, p, false, s);
+}
+
+int tide_draft_eval(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
+                    const int32_t* tokens, const uint8_t* loss_mask, float* loss_out, float* accuracy_out,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const Plan p = make_plan(cfg);
+  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
+  if (rc) return rc;
+  if (!accuracy_out) return fail(TIDE_ERR_NULL, "accuracy_out is NULL");
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, 0, ws, p, s);
+  if (rc) return rc;
+  return enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, nullptr, loss_out, accuracy_out, ws, p, false, s);
 }
 
 int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
@@ -332,7 +349,7 @@ int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* para
 
   rc = enqueue_trunk(cfg, P, hidden_buf, tokens, loss_mask, 0, ws, p, s);
   if (rc) return rc;
-  rc = enqueue_lm_head(cfg, P, G, tokens, loss_mask, nullptr, loss_out, ws, p, true, s);
+  rc = enqueue_lm_head(cfg, P, G, tokens, loss_mask, nullptr, loss_out, nullptr, ws, p, true, s);
   if (rc) return rc;
 
   float* dgp = (float*)(ws + p.dg_partial);

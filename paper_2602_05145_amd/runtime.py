@@ -70,6 +70,13 @@ class DraftTrainer:
                              self.workspace, self.ws_bytes, self._stream())
         return (self.loss, top1) if want_top1 else self.loss
 
+    def eval(self):
+        """(loss, top-1 accuracy over the loss-carrying positions), device scalars."""
+        acc = torch.zeros(1, dtype=torch.float32, device=self.device)
+        B.tide_draft_eval(self.ccfg, self.c_params, self.hidden, self.tokens, self.mask, self.loss, acc,
+                          self.workspace, self.ws_bytes, self._stream())
+        return self.loss, acc
+
     def train_step(self, lr):
         B.tide_draft_train_step(self.ccfg, self.c_params, self.c_grads, self.c_adam, self.hidden, self.tokens,
                                 self.mask, lr, self.loss, self.workspace, self.ws_bytes, self._stream())

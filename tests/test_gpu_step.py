@@ -201,3 +201,35 @@ def test_error_codes_on_device_arguments():
                                  tr.loss, tr.workspace, tr.ws_bytes, s, check=False)
     assert rc == B.TIDE_ERR_NULL
     assert tr.step == 0
+
+
+def test_eval_pass_loss_and_accuracy():
+    """Evaluation entry point (forward on the loss rows + top-1 accuracy) against the oracle."""
+    from paper_2602_05145_amd import runtime
+    for name, kw in (("tiny", {}), ("small", dict(batch=2, seq=96, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1,
+                                                 head_dim=128, ffn=256, vocab=512))):
+        cfg = W.get_config(name, **kw)
+        wl = W.make_workload(cfg)
+        # labels: the oracle's own arg-max on every other position, so that the reference accuracy is near 1/2
+        # and not the ~1/V of random labels
+        p64 = {k: np.asarray(v, np.float64) for k, v in wl["params"].items()}
+        _, c0 = O.forward(cfg, p64, wl["hidden"].astype(np.float64), wl["tokens"], wl["mask"], want_top1=True)
+        tok = np.array(wl["tokens"]).reshape(-1).copy()
+        tok[::2] = c0["top1"][::2]
+        wl["tokens"] = tok.reshape(np.asarray(wl["tokens"]).shape).astype(np.int32)
+        tr = runtime.trainer_from_workload(cfg, wl)
+        params_now = p64
+        loss_d, acc_d = tr.eval()
+        sync()
+        loss_ref, cache = O.forward(cfg, params_now, wl["hidden"].astype(np.float64), wl["tokens"], wl["mask"], want_top1=True)
+        tol = 1e-4 if cfg["dtype"] == "fp32" else 1e-2
+        assert abs(float(loss_d.item()) - loss_ref) <= tol * abs(loss_ref)
+        acc_ref = O.top1_accuracy(cache["top1"], wl["tokens"], wl["mask"], cfg["vocab"])
+        # positions whose top-2 margin is inside the arithmetic noise may flip: bound the difference by them
+        z = cache["yhat"] @ params_now["w_lm"].T
+        srt = np.sort(z, axis=-1)
+        keep = O.effective_mask(wl["tokens"], wl["mask"], cfg["vocab"])
+        unclear = int(np.sum(keep & ((srt[:, -1] - srt[:, -2]) < (1e-4 if cfg["dtype"] == "fp32" else 5e-2))))
+        N = max(1, int(keep.sum()))
+        assert 0.3 < acc_ref < 0.8
+        assert abs(float(acc_d.item()) - acc_ref) <= unclear / N + 1e-6, (float(acc_d.item()), acc_ref, unclear, N)

@@ -465,3 +465,21 @@ def test_top1_lowest_index_on_ties():
         best = max(range(9), key=lambda j: (z[t, j], -j))
         assert top1[t] == best
         assert top1[t] != 7
+
+
+def test_top1_accuracy_definition():
+    # brute force on a tiny case, and the two extremes
+    rng = np.random.default_rng(10)
+    T, V = 12, 7
+    z = rng.standard_normal((T, V))
+    tok = rng.integers(0, V, T)
+    mask = (rng.random(T) > 0.3).astype(np.uint8)
+    top1 = np.array([max(range(V), key=lambda j: (z[t, j], -j)) for t in range(T)])
+    hits = sum(1 for t in range(T) if mask[t] and top1[t] == tok[t])
+    assert O.top1_accuracy(top1, tok, mask, V) == hits / max(1, int(mask.sum()))
+    assert O.top1_accuracy(tok.copy(), tok, mask, V) == 1.0
+    assert O.top1_accuracy((tok + 1) % V, tok, mask, V) == 0.0
+    assert O.top1_accuracy(tok, tok, np.zeros(T, np.uint8), V) == 0.0        # N = max(1, 0): no position counts
+    bad = tok.copy(); bad[0] = V + 3                                          # out-of-range label never counts
+    m1 = np.ones(T, np.uint8)
+    assert O.top1_accuracy(bad, bad, m1, V) == (T - 1) / (T - 1)
