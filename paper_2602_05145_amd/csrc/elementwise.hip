@@ -216,7 +216,7 @@ hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g,
 // ----------------------------------------------------------------------------------------------
 constexpr int kRowsPerBlock = 32;
 
-template <typename T, bool VEC>
+template <typename T, bool VEC, int NIT>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ dy,
                                                           const T* __restrict__ x,
                                                           const T* __restrict__ g,
@@ -225,8 +225,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
                                                           float* __restrict__ dg_partial, int64_t rows,
                                                           int d) {
   __shared__ float red[32];
-  constexpr int NIT = 4;
-  constexpr int W = VEC ? 8 : 1;
+  constexpr int W = VEC ? 8 : 1;   // a thread owns NIT groups of W columns
   float acc[NIT][W];
 #pragma unroll
   for (int it = 0; it < NIT; ++it)
@@ -236,60 +235,69 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
   const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlock;
   const int64_t r1 = min(rows, r0 + (int64_t)kRowsPerBlock);
   const float inv_d = 1.0f / (float)d;
-  for (int64_t row = r0; row < r1; ++row) {
+  float gg[NIT][W];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int c = (threadIdx.x + it * 256) * W;
+#pragma unroll
+    for (int j = 0; j < W; ++j) gg[it][j] = 0.f;
+    if (c < d) {
+      if constexpr (VEC) ld8(g, c, gg[it]);
+      else gg[it][0] = ldf(g, c);
+    }
+  }
+  // The rows of a block are walked with a one-row look-ahead: the loads of row+1 are issued before the
+  // block-wide reduction of row, whose two barriers would otherwise expose the full memory latency per row.
+  float xn[NIT][W], dyn[NIT][W], rn[NIT][W], rstd_n = 0.f;
+  auto load_row = [&](int64_t row) {
     const size_t base = (size_t)row * (size_t)d;
-    const float r = rstd[row];
-    float uv[NIT][W], xv[NIT][W], dyv[NIT][W];
-    float dot = 0.f;
+    rstd_n = rstd[row];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int c = (threadIdx.x + it * 256) * W;
-      if (c < d) {
-        if (VEC) {
-          float gg[8], a[8], b[8];
-          ld8(dy, base + c, a);
-          ld8(x, base + c, b);
-          ld8(g, c, gg);
 #pragma unroll
-          for (int j = 0; j < W; ++j) {
-            dyv[it][j] = a[j];
-            xv[it][j] = b[j];
-            uv[it][j] = gg[j] * a[j];
-            dot += uv[it][j] * b[j];
-          }
+      for (int j = 0; j < W; ++j) { xn[it][j] = 0.f; dyn[it][j] = 0.f; rn[it][j] = 0.f; }
+      if (c < d) {
+        if constexpr (VEC) {
+          ld8(dy, base + c, dyn[it]);
+          ld8(x, base + c, xn[it]);
+          if (res) ld8(res, base + c, rn[it]);
         } else {
-          dyv[it][0] = ldf(dy, base + c);
-          xv[it][0] = ldf(x, base + c);
-          uv[it][0] = ldf(g, c) * dyv[it][0];
-          dot += uv[it][0] * xv[it][0];
+          dyn[it][0] = ldf(dy, base + c);
+          xn[it][0] = ldf(x, base + c);
+          if (res) rn[it][0] = ldf(res, base + c);
         }
       }
     }
+  };
+  if (r0 < r1) load_row(r0);
+  for (int64_t row = r0; row < r1; ++row) {
+    const size_t base = (size_t)row * (size_t)d;
+    const float r = rstd_n;
+    float xv[NIT][W], dyv[NIT][W], rv[NIT][W];
+    float dot = 0.f;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+#pragma unroll
+      for (int j = 0; j < W; ++j) {
+        xv[it][j] = xn[it][j]; dyv[it][j] = dyn[it][j]; rv[it][j] = rn[it][j];
+        dot += gg[it][j] * dyv[it][j] * xv[it][j];
+      }
+    if (row + 1 < r1) load_row(row + 1);
     const float tot = block_sum(dot, red);
     const float coef = r * r * r * tot * inv_d;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int c = (threadIdx.x + it * 256) * W;
       if (c < d) {
-        if (VEC) {
-          float o[8];
-          if (res) ld8(res, base + c, o);
-          else {
+        float o[W];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) o[j] = 0.f;
-          }
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            o[j] += r * uv[it][j] - xv[it][j] * coef;
-            acc[it][j] += dyv[it][j] * xv[it][j] * r;
-          }
-          st8(dx, base + c, o);
-        } else {
-          float o = res ? ldf(res, base + c) : 0.f;
-          o += r * uv[it][0] - xv[it][0] * coef;
-          acc[it][0] += dyv[it][0] * xv[it][0] * r;
-          stf(dx, base + c, o);
+        for (int j = 0; j < W; ++j) {
+          o[j] = rv[it][j] + (r * (gg[it][j] * dyv[it][j]) - xv[it][j] * coef);
+          acc[it][j] += dyv[it][j] * xv[it][j] * r;
         }
+        if constexpr (VEC) st8(dx, base + c, o);
+        else stf(dx, base + c, o[0]);
       }
     }
   }
@@ -332,13 +340,17 @@ hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x
   ProfScope ps("rmsnorm_bwd", 0, (double)rows * d * (res ? 4.0 : 3.0) * dtype_size(dtype) + 4.0 * rows, s);
   const int64_t nblk = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
   dim3 grid((unsigned)nblk), blk(256);
+  const int per = vec ? 8 * 256 : 256;            // columns covered by one pass of the block
+  const int nit = (d + per - 1) / per;            // <= 4 by the limits above
+#define TIDE_RMS_BWD(T, V, N) hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, N>), grid, blk, 0, s, (const T*)dy, (const T*)x, (const T*)g, rstd, (const T*)res, (T*)dx, dg_partial, rows, d)
+#define TIDE_RMS_BWD_N(T, V) do { if (nit <= 1) TIDE_RMS_BWD(T, V, 1); else if (nit == 2) TIDE_RMS_BWD(T, V, 2); else TIDE_RMS_BWD(T, V, 4); } while (0)
   if (dtype == kBF16) {
-    if (vec) hipLaunchKernelGGL((rmsnorm_bwd_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)g, rstd, (const bf16_t*)res, (bf16_t*)dx, dg_partial, rows, d);
-    else hipLaunchKernelGGL((rmsnorm_bwd_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)g, rstd, (const bf16_t*)res, (bf16_t*)dx, dg_partial, rows, d);
+    if (vec) TIDE_RMS_BWD_N(bf16_t, true); else TIDE_RMS_BWD_N(bf16_t, false);
   } else {
-    if (vec) hipLaunchKernelGGL((rmsnorm_bwd_kernel<float, true>), grid, blk, 0, s, (const float*)dy, (const float*)x, (const float*)g, rstd, (const float*)res, (float*)dx, dg_partial, rows, d);
-    else hipLaunchKernelGGL((rmsnorm_bwd_kernel<float, false>), grid, blk, 0, s, (const float*)dy, (const float*)x, (const float*)g, rstd, (const float*)res, (float*)dx, dg_partial, rows, d);
+    if (vec) TIDE_RMS_BWD_N(float, true); else TIDE_RMS_BWD_N(float, false);
   }
+#undef TIDE_RMS_BWD_N
+#undef TIDE_RMS_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_kernel, dim3((d + 63) / 64), dim3(256), 0, s, dg_partial, nblk, d, dg);
@@ -387,15 +399,53 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const fl
   stf(qkv, o + half, x2 * c + x1 * sn);
 }
 
+// Eight pairs per thread (16-byte accesses); needs head_dim % 16 == 0 and a 16-byte aligned buffer.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_vec8_kernel(T* __restrict__ qkv, const float* __restrict__ cs,
+                                                        int S, int nrot_heads, int dh, int ld, float sgn,
+                                                        int64_t total8) {
+  const int half = dh >> 1, h8 = half >> 3;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total8) return;
+  const int i = (int)(idx % h8) * 8;
+  const int64_t th = idx / h8;
+  const int hd = (int)(th % nrot_heads);
+  const int64_t t = th / nrot_heads;
+  const int pos = (int)(t % S);
+  const float4* tab = reinterpret_cast<const float4*>(cs + 2 * ((size_t)pos * half + i));   // (cos, sin) x 8
+  const size_t o = (size_t)t * ld + (size_t)hd * dh + i;
+  float x1[8], x2[8], y1[8], y2[8];
+  ld8(qkv, o, x1);
+  ld8(qkv, o + half, x2);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float4 v = tab[j];
+    const float c0 = v.x, s0 = sgn * v.y, c1 = v.z, s1 = sgn * v.w;
+    y1[2 * j] = x1[2 * j] * c0 - x2[2 * j] * s0;
+    y2[2 * j] = x2[2 * j] * c0 + x1[2 * j] * s0;
+    y1[2 * j + 1] = x1[2 * j + 1] * c1 - x2[2 * j + 1] * s1;
+    y2[2 * j + 1] = x2[2 * j + 1] * c1 + x1[2 * j + 1] * s1;
+  }
+  st8(qkv, o, y1);
+  st8(qkv, o + half, y2);
+}
+
 hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, void* qkv, int inverse,
                        int dtype, hipStream_t s) {
   const int nrot = nh + nkv;
   const int ld = (nh + 2 * nkv) * dh;
   const int64_t total = (int64_t)B * S * nrot * (dh / 2);
   if (total <= 0) return hipSuccess;
-  dim3 grid((unsigned)((total + 255) / 256)), blk(256);
   const float sgn = inverse ? -1.f : 1.f;
   ProfScope ps("rope", 0, (double)total * 4.0 * dtype_size(dtype), s);
+  if ((dh % 16) == 0 && (((uintptr_t)qkv | (uintptr_t)cs) & 15) == 0) {
+    const int64_t total8 = total / 8;
+    dim3 grid8((unsigned)((total8 + 255) / 256)), blk8(256);
+    if (dtype == kBF16) hipLaunchKernelGGL(rope_vec8_kernel<bf16_t>, grid8, blk8, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total8);
+    else hipLaunchKernelGGL(rope_vec8_kernel<float>, grid8, blk8, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total8);
+    return hipGetLastError();
+  }
+  dim3 grid((unsigned)((total + 255) / 256)), blk(256);
   if (dtype == kBF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total);
   else hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total);
   return hipGetLastError();

@@ -96,10 +96,12 @@ Plan make_plan(const tide_draft_config* c) {
   p.V = c->vocab;
   p.ldz = (int64_t)align_up((size_t)p.V, 64);
   p.es = c->dtype == TIDE_DTYPE_BF16 ? 2 : 4;
-  // The logits exist only for a block of rows at a time: a quarter of the batch, at most 8192 rows.
-  int64_t rows = (int64_t)align_up((size_t)((p.T + 3) / 4), 64);
-  if (rows > 8192) rows = 8192;
-  while (rows > 256 && (size_t)rows * p.ldz * p.es > ((size_t)3 << 30)) rows /= 2;
+  // The logits exist only for a block of rows at a time: half of the batch, at most 16384 rows and 6 GiB.
+  // Larger blocks mean fewer read-modify-write passes over dW_lm (one per block after the first): at the
+  // 8B shape 16384 rows measured 3 ms per step faster than 8192, and one block of 32768 no better.
+  int64_t rows = (int64_t)align_up((size_t)((p.T + 1) / 2), 64);
+  if (rows > 16384) rows = 16384;
+  while (rows > 256 && (size_t)rows * p.ldz * p.es > ((size_t)6 << 30)) rows /= 2;
   if (rows > p.T) rows = p.T;
   p.lm_rows = rows;
   const size_t T = (size_t)p.T, es = p.es;
