@@ -1,4 +1,4 @@
-"""Builds libtide_draft.so (gfx950 HIP kernels + C ABI) in-tree with hipcc."""
+"""Builds libtide_draft.so (gfx950 HIP kernels + C ABI) with hipcc and libtide_control.so (host-only C) in-tree."""
 from __future__ import annotations
 
 import os
@@ -9,6 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtide_draft.so")
+CONTROL_LIB = os.path.join(HERE, "libtide_control.so")
 SOURCES = ["tide_draft.hip", "elementwise.hip", "gemm_simple.hip", "gemm_mfma.hip",
            "attention_simple.hip", "attention_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -47,7 +48,18 @@ def build(verbose=True, jobs=None):
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
+    build_control()
     return LIB
+
+
+def build_control():
+    """Host-only adaptive-control library (plain C, no GPU code)."""
+    cmd = [os.environ.get("CC", "gcc"), "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
+           os.path.join(CSRC, "tide_control.c"), "-o", CONTROL_LIB, "-lm"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"control library build failed:\n{r.stderr}")
+    return CONTROL_LIB
 
 
 if __name__ == "__main__":
