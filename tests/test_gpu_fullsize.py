@@ -1,5 +1,5 @@
 """Parity at the full size of the benchmarked workload (8B-shaped, batch 16 x seq 2048, in the launch
-configuration bench.py times).  The fp64 oracle cannot run 155 TFLOP, so the checks are (a) sampled
+configuration bench.py times) and of the two other large configurations (long context 2 x 16384, 32B-shaped).  The fp64 oracle cannot run 155 TFLOP, so the checks are (a) sampled
 outputs the oracle CAN compute exactly, thanks to causality: the first positions of one sequence depend
 only on that prefix, so an oracle forward over the prefix alone gives their final-norm output, log-sum-exp,
 loss terms and arg-max; and (b) properties that hold at any size (zero column sums of the LM-head
@@ -15,16 +15,17 @@ from tests.gpu_util import cosine, sync
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def full():
+@pytest.fixture(scope="module", params=["8b", "longctx", "32b"])
+def full(request):
     import bench
-    cfg = W.get_config("8b")
+    name = request.param
+    cfg = W.get_config(name)
     dev = torch.device("cuda:0")
-    print("generating 8B-shaped workload on the device", flush=True)
+    print(f"generating the {name} workload on the device", flush=True)
     params, hidden, tokens, mask = bench.device_workload(cfg, dev, cfg["seed"])
     p0 = {k: v.clone() for k, v in params.items()}
     tr = bench.DeviceTrainer(cfg, params, hidden, tokens, mask)
-    print("forward (all rows, arg-max) at full size", flush=True)
+    print(f"{name}: forward (all rows, arg-max) at full size", flush=True)
     loss_f, top1 = tr.forward(want_top1=True)
     sync()
     T, d = cfg["batch"] * cfg["seq"], cfg["hidden"]
@@ -32,23 +33,26 @@ def full():
                 yhat=tr.intermediate("yhat", (T, d)).float().cpu().numpy(),
                 lse=tr.intermediate("lse", (T,), kind="f32").cpu().numpy().copy(),
                 loss_rows=tr.intermediate("loss_rows", (T,), kind="f32").cpu().numpy().copy())
-    print("train step at full size", flush=True)
+    print(f"{name}: train step at full size", flush=True)
     tr.train_step(cfg["lr"])
     sync()
     snap["loss_train"] = float(tr.loss.item())
-    return cfg, tr, p0, snap
+    yield cfg, tr, p0, snap
+    del tr, p0, snap, params, hidden, tokens, mask
+    torch.cuda.empty_cache()
 
 
 def test_prefix_of_one_sequence_against_oracle(full):
     cfg, tr, p0, snap = full
-    b, L = 3, 384                                    # 307 masked prompt positions + 77 loss positions
-    S = cfg["seq"]
+    b, S = cfg["batch"] - 1, cfg["seq"]
+    first_loss = int(torch.nonzero(tr.mask[b] != 0)[0].item())      # end of the masked prompt
+    L = first_loss + 72                                             # the prompt + 72 loss positions
     sub = dict(cfg, batch=1, seq=L)
     params64 = {k: v.float().cpu().numpy().astype(np.float64) for k, v in p0.items()}
     hid = tr.hidden[b, :L].float().cpu().numpy().astype(np.float64)[None]
     tok = tr.tokens[b, :L].cpu().numpy()[None]
     msk = tr.mask[b, :L].cpu().numpy()[None]
-    print("oracle forward over the 384-position prefix", flush=True)
+    print(f"oracle forward over the {L}-position prefix", flush=True)
     _, cache = O.forward(sub, params64, hid, tok, msk, want_top1=True)
     rows = slice(b * S, b * S + L)
     # final-norm output feeding the LM head
