@@ -126,6 +126,32 @@ int tide_draft_forward(const tide_draft_config *cfg, const tide_draft_tensors *p
                        float *loss_out, int32_t *top1_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* Packed (variable-length) batches.  The paper's training signals are the hidden states of the tokens the
+ * target accepted (Sec. 3.2, Fig. 3 caption): segments of different lengths.  Instead of right-padding
+ * every segment to `seq`, the T = batch*seq rows of hidden_buf / tokens / loss_mask hold the segments back to
+ * back: sequence i owns rows [cu_seqlens[i], cu_seqlens[i+1]).  cu_seqlens is a DEVICE array of n_seqs+1
+ * ascending int32 values with cu_seqlens[0] >= 0 and cu_seqlens[n_seqs] <= T (neither can be checked without
+ * a sync: rows outside [cu_seqlens[0], cu_seqlens[n_seqs]) are padding, they must hold finite values and
+ * never carry loss; an empty sequence is allowed).  max_seqlen (host) bounds every sequence length: it sizes
+ * the attention grid and the RoPE table, and a longer sequence gives undefined results for its tail.
+ * Attention is causal inside each sequence and never crosses a boundary; RoPE positions restart at 0 in each
+ * sequence; everything else is per row, so the result for a sequence equals that of the same sequence
+ * right-padded in a fixed batch (loss and gradients are normalised by the N of the whole batch either way).
+ * cfg.batch and cfg.seq only fix the row capacity T and the workspace size here.  Other arguments, errors
+ * and ownership as in tide_draft_forward / tide_draft_train_step; extra errors: TIDE_ERR_NULL for a NULL
+ * cu_seqlens, TIDE_ERR_CONFIG for n_seqs outside [1, 65535] or max_seqlen outside [1, T]. */
+int tide_draft_forward_packed(const tide_draft_config *cfg, const tide_draft_tensors *params,
+                              const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                              const int32_t *cu_seqlens, int32_t n_seqs, int32_t max_seqlen,
+                              float *loss_out, int32_t *top1_out,
+                              void *workspace, size_t workspace_bytes, void *stream);
+int tide_draft_train_step_packed(const tide_draft_config *cfg, tide_draft_tensors *params,
+                                 tide_draft_tensors *grads, tide_adam_state *adam_state,
+                                 const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                                 const int32_t *cu_seqlens, int32_t n_seqs, int32_t max_seqlen,
+                                 float lr, float *loss_out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
 /* Evaluation pass of the paper's Algorithm 1 (the held-out check that gates deployment of a newly trained
  * draft) in the paper's accuracy metric (Fig. 7 caption: top-1 match rate between draft and target): writes
  * the masked mean cross-entropy to *loss_out and, to *accuracy_out (DEVICE float), the fraction of the N

@@ -353,3 +353,42 @@ def train_step(cfg, params, m, v, step, hidden_buf, tokens, loss_mask, lr):
     grads = backward(cfg, params, cache, tokens, loss_mask)
     np_, nm, nv, t = adamw_step(cfg, params, grads, m, v, step, lr)
     return loss, grads, np_, nm, nv, t
+
+
+def train_quantities_packed(cfg, params, hidden_rows, tokens, loss_mask, cu_seqlens, want_top1=False):
+    """Loss and gradients of a PACKED batch: row t of hidden_rows [T, K*H_t] / tokens [T] / loss_mask [T]
+    belongs to sequence i iff cu_seqlens[i] <= t < cu_seqlens[i+1]; rows outside [cu[0], cu[-1]) are padding.
+
+    Sequences are independent samples (attention and RoPE positions never cross a boundary), and the loss
+    is the mean over the loss-carrying positions of the whole batch (Sec. 3.2, 3.3: the signals are
+    per-request segments of accepted tokens).  So this runs the single-sequence definition above on every
+    sequence by itself and combines them with their share keep_i / N of the N loss positions.
+    Returns (loss, grads, top1 [T] or None); top1 of padding rows is -1."""
+    cu = [int(c) for c in cu_seqlens]
+    T = np.asarray(tokens).reshape(-1).shape[0]
+    hidden_rows = np.asarray(hidden_rows, F64).reshape(T, -1)
+    tokens = np.asarray(tokens).reshape(-1)
+    mask = np.asarray(loss_mask).reshape(-1).copy()
+    inside = np.zeros(T, bool)
+    inside[cu[0]:cu[-1]] = True
+    keep = effective_mask(tokens, mask, cfg["vocab"]) & inside
+    N = max(1, int(keep.sum()))
+    loss = 0.0
+    grads = {k: np.zeros(np.asarray(v).shape, F64) for k, v in params.items()}
+    top1 = np.full(T, -1, np.int64) if want_top1 else None
+    for i in range(len(cu) - 1):
+        a, b = cu[i], cu[i + 1]
+        if b <= a:
+            continue
+        sub = dict(cfg, batch=1, seq=b - a)
+        l_i, cache = forward(sub, params, hidden_rows[a:b][None], tokens[a:b][None], mask[a:b][None], want_top1=want_top1)
+        if want_top1:
+            top1[a:b] = cache["top1"]
+        n_i = int(keep[a:b].sum())
+        if n_i == 0:
+            continue
+        g_i = backward(sub, params, cache, tokens[a:b][None], mask[a:b][None])
+        loss += l_i * n_i / N
+        for k in grads:
+            grads[k] += g_i[k] * (n_i / N)
+    return float(loss), grads, top1

@@ -65,6 +65,11 @@ _lib.tide_draft_workspace_offset.restype = _i64
 _lib.tide_draft_workspace_offset.argtypes = [_cfgp, C.c_char_p]
 _lib.tide_draft_forward.restype = _i32
 _lib.tide_draft_forward.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.tide_draft_forward_packed.restype = _i32
+_lib.tide_draft_forward_packed.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
+_lib.tide_draft_train_step_packed.restype = _i32
+_lib.tide_draft_train_step_packed.argtypes = [_cfgp, _tp, _tp, _ap, _vp, _vp, _vp, _vp, _i32, _i32,
+                                              C.c_float, _vp, _vp, _sz, _vp]
 _lib.tide_draft_eval.restype = _i32
 _lib.tide_draft_eval.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.tide_draft_train_step.restype = _i32
@@ -92,7 +97,8 @@ _lib.tide_profile_stop.restype = _i32
 _lib.tide_profile_stop.argtypes = [C.c_char_p, _sz]
 
 EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
-            "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_gemm_workspace_bytes", "tide_gemm",
+            "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_draft_forward_packed",
+    "tide_draft_train_step_packed", "tide_gemm_workspace_bytes", "tide_gemm",
             "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd",
             "tide_attention_fwd", "tide_attention_bwd", "tide_rope", "tide_profile_start",
             "tide_profile_stop")
@@ -152,6 +158,28 @@ def tide_draft_forward(cfg, params, hidden_buf, tokens, loss_mask, loss_out, top
                                  C.byref(params) if params is not None else None,
                                  _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(loss_out),
                                  _ptr(top1_out), _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_draft_forward_packed(cfg, params, hidden_buf, tokens, loss_mask, cu_seqlens, n_seqs, max_seqlen, loss_out,
+                              top1_out, workspace, workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_forward_packed(C.byref(cfg) if cfg is not None else None,
+                                        C.byref(params) if params is not None else None,
+                                        _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(cu_seqlens),
+                                        int(n_seqs), int(max_seqlen), _ptr(loss_out), _ptr(top1_out),
+                                        _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_draft_train_step_packed(cfg, params, grads, adam_state, hidden_buf, tokens, loss_mask, cu_seqlens, n_seqs,
+                                 max_seqlen, lr, loss_out, workspace, workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_train_step_packed(C.byref(cfg) if cfg is not None else None,
+                                           C.byref(params) if params is not None else None,
+                                           C.byref(grads) if grads is not None else None,
+                                           C.byref(adam_state) if adam_state is not None else None,
+                                           _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(cu_seqlens),
+                                           int(n_seqs), int(max_seqlen), float(lr), _ptr(loss_out),
+                                           _ptr(workspace), int(workspace_bytes), stream)
     return _check(rc) if check else rc
 
 

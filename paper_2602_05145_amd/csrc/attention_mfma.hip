@@ -148,19 +148,23 @@ constexpr int KV_TILE = BKV * PITCH;  // elements
 // forward
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
-                                                            float* __restrict__ lse, int S, int nh, int nkv) {
+                                                            float* __restrict__ lse, int Smax, int nh, int nkv,
+                                                            const int* __restrict__ cu, int64_t T) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   bf16_t* sK = smem;                 // [2][KV_TILE]
   bf16_t* sV = smem + 2 * KV_TILE;   // [2][KV_TILE]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  const int nqb = (S + BQ - 1) / BQ;
+  const int nqb = (Smax + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;  // heavy (late) query blocks first
   const int h = blockIdx.y, b = blockIdx.z;
+  const SeqView sv = seq_view(cu, b, Smax);
+  const int S = sv.len;
   const int G = nh / nkv, kh = h / G;
   const int ld = (nh + 2 * nkv) * D;
   const int q0 = qb * BQ, qw = q0 + wave * 32, iq = qw + lr;
-  const bf16_t* base = qkv + (size_t)b * S * ld;
+  if (q0 >= S) return;   // the whole block, before any barrier: this sequence is shorter
+  const bf16_t* base = qkv + (size_t)sv.row0 * ld;
   const __amdgpu_buffer_rsrc_t rs = rsrc(base, (uint32_t)((size_t)S * ld * 2));
   const int kcol = (nh + kh) * D, vcol = (nh + nkv + kh) * D;
   const float c = kLog2e / sqrtf((float)D);
@@ -255,9 +259,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
 
   const float inv = 1.0f / l;
   stage_out(smem, o, inv, wave, lane);
-  if (g == 0 && iq < S) lse[((size_t)b * nh + h) * S + iq] = m * (1.0f / sqrtf((float)D)) + logf(l);
+  if (g == 0 && iq < S) lse[stat_index(cu, T, sv, b, h, nh, Smax, iq)] = m * (1.0f / sqrtf((float)D)) + logf(l);
   __syncthreads();
-  copy_out(smem, out, (int64_t)b * S + q0, (int64_t)b * S + min(S, q0 + BQ), nh * D, h * D, tid);
+  copy_out(smem, out, sv.row0 + q0, sv.row0 + min(S, q0 + BQ), nh * D, h * D, tid);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -265,20 +269,24 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16_t* __restrict__ dqkv, int S, int nh, int nkv) {
+                                                           bf16_t* __restrict__ dqkv, int Smax, int nh, int nkv,
+                                                           const int* __restrict__ cu, int64_t T) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   bf16_t* sK = smem;
   bf16_t* sV = smem + 2 * KV_TILE;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  const int nqb = (S + BQ - 1) / BQ;
+  const int nqb = (Smax + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
+  const SeqView sv = seq_view(cu, b, Smax);
+  const int S = sv.len;
   const int G = nh / nkv, kh = h / G;
   const int ld = (nh + 2 * nkv) * D, ldo = nh * D;
   const int q0 = qb * BQ, qw = q0 + wave * 32, iq = qw + lr;
-  const __amdgpu_buffer_rsrc_t rs = rsrc(qkv + (size_t)b * S * ld, (uint32_t)((size_t)S * ld * 2));
-  const __amdgpu_buffer_rsrc_t rso = rsrc(dout + (size_t)b * S * ldo, (uint32_t)((size_t)S * ldo * 2));
+  if (q0 >= S) return;   // the whole block, before any barrier
+  const __amdgpu_buffer_rsrc_t rs = rsrc(qkv + (size_t)sv.row0 * ld, (uint32_t)((size_t)S * ld * 2));
+  const __amdgpu_buffer_rsrc_t rso = rsrc(dout + (size_t)sv.row0 * ldo, (uint32_t)((size_t)S * ldo * 2));
   const int kcol = (nh + kh) * D, vcol = (nh + nkv + kh) * D;
   const float scale = 1.0f / sqrtf((float)D);
   const float c = kLog2e * scale;
@@ -290,8 +298,8 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
     dof[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rso, ((uint32_t)iq * (uint32_t)ldo + (uint32_t)(h * D + kk * 16 + g * 8)) * 2u, 0, 0));
   }
   const bool valid = iq < S;
-  const float lse_i = valid ? lse[((size_t)b * nh + h) * S + iq] * kLog2e : 0.f;
-  const float del_i = valid ? delta[((size_t)b * nh + h) * S + iq] : 0.f;
+  const float lse_i = valid ? lse[stat_index(cu, T, sv, b, h, nh, Smax, iq)] * kLog2e : 0.f;
+  const float del_i = valid ? delta[stat_index(cu, T, sv, b, h, nh, Smax, iq)] : 0.f;
 
   f32x16_t dq[4];
 #pragma unroll
@@ -352,7 +360,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
   }
   stage_out(smem, dq, scale, wave, lane);
   __syncthreads();
-  copy_out(smem, dqkv, (int64_t)b * S + q0, (int64_t)b * S + min(S, q0 + BQ), ld, h * D, tid);
+  copy_out(smem, dqkv, sv.row0 + q0, sv.row0 + min(S, q0 + BQ), ld, h * D, tid);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -366,16 +374,20 @@ constexpr int DKV_STAGE = 2 * Q_TILE + 2 * 64;  // Q tile, dO tile, then lse[32]
 
 __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
-                                                            bf16_t* __restrict__ dqkv, int S, int nh, int nkv) {
+                                                            bf16_t* __restrict__ dqkv, int Smax, int nh, int nkv,
+                                                            const int* __restrict__ cu, int64_t T) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int jb = blockIdx.x, kh = blockIdx.y, b = blockIdx.z;  // early key blocks are the heavy ones
+  const SeqView sv = seq_view(cu, b, Smax);
+  const int S = sv.len;
   const int G = nh / nkv;
   const int ld = (nh + 2 * nkv) * D, ldo = nh * D;
   const int j0 = jb * 128, jw = j0 + wave * 32, jk = jw + lr;
-  const __amdgpu_buffer_rsrc_t rs = rsrc(qkv + (size_t)b * S * ld, (uint32_t)((size_t)S * ld * 2));
-  const __amdgpu_buffer_rsrc_t rso = rsrc(dout + (size_t)b * S * ldo, (uint32_t)((size_t)S * ldo * 2));
+  if (j0 >= S) return;   // the whole block, before any barrier
+  const __amdgpu_buffer_rsrc_t rs = rsrc(qkv + (size_t)sv.row0 * ld, (uint32_t)((size_t)S * ld * 2));
+  const __amdgpu_buffer_rsrc_t rso = rsrc(dout + (size_t)sv.row0 * ldo, (uint32_t)((size_t)S * ldo * 2));
   const int kcol = (nh + kh) * D, vcol = (nh + nkv + kh) * D;
   const float scale = 1.0f / sqrtf((float)D);
   const float c = kLog2e * scale;
@@ -406,7 +418,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
     if (tid < 64) {
       const int i = i0 + (tid & 31);
       const float* src = (tid < 32) ? lse : delta;
-      stat = (i < S) ? src[((size_t)b * nh + hh) * S + i] : 0.f;
+      stat = (i < S) ? src[stat_index(cu, T, sv, b, hh, nh, Smax, i)] : 0.f;
     }
   };
   auto sstore = [&](int st) {
@@ -464,7 +476,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
     if (u + 1 < ntiles) sstore(st ^ 1);
     __syncthreads();
   }
-  const int64_t r0 = (int64_t)b * S + j0, r1 = (int64_t)b * S + min(S, j0 + 128);
+  const int64_t r0 = sv.row0 + j0, r1 = sv.row0 + min(S, j0 + 128);
   stage_out(smem, dk, scale, wave, lane);
   __syncthreads();
   copy_out(smem, dqkv, r0, r1, ld, kcol, tid);
@@ -504,7 +516,7 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
   if (e != hipSuccess) return e;
   dim3 grid((a.S + BQ - 1) / BQ, a.nh, a.B);
   ProfScope ps("attn_fwd_mfma", 2.0 * a.B * a.nh * D * (double)a.S * (a.S + 1), 0, s);
-  hipLaunchKernelGGL(attn_fwd_mfma_kernel, grid, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv);
+  hipLaunchKernelGGL(attn_fwd_mfma_kernel, grid, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
   return hipGetLastError();
 }
 
@@ -520,12 +532,12 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
   const double pairs = (double)a.B * a.nh * D * (double)a.S * (a.S + 1) / 2.0;  // (query, key, channel) triples
   {
     ProfScope ps("attn_dq_mfma", 6.0 * pairs, 0, s);   // S, dP and dQ products
-    hipLaunchKernelGGL(attn_dq_mfma_kernel, gq, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv);
+    hipLaunchKernelGGL(attn_dq_mfma_kernel, gq, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   ProfScope ps("attn_dkv_mfma", 8.0 * pairs, 0, s);    // S, dP, dV and dK products
-  hipLaunchKernelGGL(attn_dkv_mfma_kernel, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv);
+  hipLaunchKernelGGL(attn_dkv_mfma_kernel, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
   return hipGetLastError();
 }
 

@@ -5,6 +5,7 @@
 //
 // Activation layout: qkv [B*S, (nh + 2 nkv) dh] with q heads first, then k heads, then v heads; query
 // head h reads kv head h / (nh / nkv).  lse[b, h, i] is the log-sum-exp of the scaled scores of row i.
+// Packed batches (cu_seqlens given): sequence b owns rows [cu[b], cu[b+1]) and lse / delta are [nh, T].
 #include "kernels.h"
 #include "prof.h"
 #include "tide_common.h"
@@ -16,16 +17,19 @@ constexpr int kDhSlots = kMaxDh / 64;
 
 template <typename T>
 __global__ __launch_bounds__(64) void attn_fwd_simple_kernel(const T* __restrict__ qkv, T* __restrict__ out,
-                                                             float* __restrict__ lse, int S, int nh, int nkv,
-                                                             int dh) {
+                                                             float* __restrict__ lse, int Smax, int nh, int nkv,
+                                                             int dh, const int* __restrict__ cu, int64_t Trows) {
   __shared__ float qs[kMaxDh];
   __shared__ float ps[64];
   const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const SeqView sv = seq_view(cu, b, Smax);
+  if (i >= sv.len) return;   // whole block: the sequence is shorter than the grid
+  const size_t row0 = (size_t)sv.row0;
   const int lane = threadIdx.x;
   const int G = nh / nkv, kh = h / G;
   const int ld = (nh + 2 * nkv) * dh;
   const float scale = 1.0f / sqrtf((float)dh);
-  const size_t rowq = ((size_t)b * S + i) * ld;
+  const size_t rowq = (row0 + i) * ld;
   for (int c = lane; c < dh; c += 64) qs[c] = ldf(qkv, rowq + (size_t)h * dh + c) * scale;
   __syncthreads();
   const size_t koff = (size_t)(nh + kh) * dh, voff = (size_t)(nh + nkv + kh) * dh;
@@ -37,7 +41,7 @@ __global__ __launch_bounds__(64) void attn_fwd_simple_kernel(const T* __restrict
     const int j = j0 + lane;
     float sc = -INFINITY;
     if (j <= i) {
-      const size_t rk = ((size_t)b * S + j) * ld + koff;
+      const size_t rk = (row0 + j) * ld + koff;
       float a = 0.f;
       for (int c = 0; c < dh; ++c) a = fmaf(qs[c], ldf(qkv, rk + c), a);
       sc = a;
@@ -57,7 +61,7 @@ __global__ __launch_bounds__(64) void attn_fwd_simple_kernel(const T* __restrict
       if (c < dh) {
         float a = o[t] * corr;
         for (int jj = 0; jj < jn; ++jj)
-          a = fmaf(ps[jj], ldf(qkv, ((size_t)b * S + j0 + jj) * ld + voff + c), a);
+          a = fmaf(ps[jj], ldf(qkv, (row0 + j0 + jj) * ld + voff + c), a);
         o[t] = a;
       }
     }
@@ -66,45 +70,53 @@ __global__ __launch_bounds__(64) void attn_fwd_simple_kernel(const T* __restrict
 #pragma unroll
   for (int t = 0; t < kDhSlots; ++t) {
     const int c = lane + 64 * t;
-    if (c < dh) stf(out, ((size_t)b * S + i) * ((size_t)nh * dh) + (size_t)h * dh + c, o[t] * inv);
+    if (c < dh) stf(out, (row0 + i) * ((size_t)nh * dh) + (size_t)h * dh + c, o[t] * inv);
   }
-  if (lane == 0) lse[((size_t)b * nh + h) * S + i] = m + logf(l);
+  if (lane == 0) lse[stat_index(cu, Trows, sv, b, h, nh, Smax, i)] = m + logf(l);
 }
 
 // delta[b,h,i] = sum_c dO[i,h,c] * O[i,h,c]
 template <typename T>
 __global__ __launch_bounds__(64) void attn_delta_kernel(const T* __restrict__ out, const T* __restrict__ dout,
-                                                        float* __restrict__ delta, int S, int nh, int dh) {
+                                                        float* __restrict__ delta, int Smax, int nh, int dh,
+                                                        const int* __restrict__ cu, int64_t Trows) {
   const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const size_t base = ((size_t)b * S + i) * ((size_t)nh * dh) + (size_t)h * dh;
+  const SeqView sv = seq_view(cu, b, Smax);
+  if (i >= sv.len) return;
+  const size_t row0 = (size_t)sv.row0;
+  const size_t base = (row0 + i) * ((size_t)nh * dh) + (size_t)h * dh;
   float a = 0.f;
   for (int c = threadIdx.x; c < dh; c += 64) a += ldf(out, base + c) * ldf(dout, base + c);
   a = wave_sum(a);
-  if (threadIdx.x == 0) delta[((size_t)b * nh + h) * S + i] = a;
+  if (threadIdx.x == 0) delta[stat_index(cu, Trows, sv, b, h, nh, Smax, i)] = a;
 }
 
 template <typename T>
 __global__ __launch_bounds__(64) void attn_dq_simple_kernel(const T* __restrict__ qkv, const T* __restrict__ dout,
                                                             const float* __restrict__ lse,
                                                             const float* __restrict__ delta, T* __restrict__ dqkv,
-                                                            int S, int nh, int nkv, int dh) {
+                                                            int Smax, int nh, int nkv, int dh,
+                                                            const int* __restrict__ cu, int64_t Trows) {
   __shared__ float qs[kMaxDh], dos[kMaxDh];
   __shared__ float dss[64];
   const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const SeqView sv = seq_view(cu, b, Smax);
+  if (i >= sv.len) return;
+  const size_t row0 = (size_t)sv.row0;
   const int lane = threadIdx.x;
   const int G = nh / nkv, kh = h / G;
   const int ld = (nh + 2 * nkv) * dh;
   const float scale = 1.0f / sqrtf((float)dh);
-  const size_t rowq = ((size_t)b * S + i) * ld;
-  const size_t rowo = ((size_t)b * S + i) * ((size_t)nh * dh) + (size_t)h * dh;
+  const size_t rowq = (row0 + i) * ld;
+  const size_t rowo = (row0 + i) * ((size_t)nh * dh) + (size_t)h * dh;
   for (int c = lane; c < dh; c += 64) {
     qs[c] = ldf(qkv, rowq + (size_t)h * dh + c) * scale;
     dos[c] = ldf(dout, rowo + c);
   }
   __syncthreads();
   const size_t koff = (size_t)(nh + kh) * dh, voff = (size_t)(nh + nkv + kh) * dh;
-  const float L = lse[((size_t)b * nh + h) * S + i];
-  const float D = delta[((size_t)b * nh + h) * S + i];
+  const float L = lse[stat_index(cu, Trows, sv, b, h, nh, Smax, i)];
+  const float D = delta[stat_index(cu, Trows, sv, b, h, nh, Smax, i)];
   float dq[kDhSlots];
 #pragma unroll
   for (int t = 0; t < kDhSlots; ++t) dq[t] = 0.f;
@@ -112,7 +124,7 @@ __global__ __launch_bounds__(64) void attn_dq_simple_kernel(const T* __restrict_
     const int j = j0 + lane;
     float ds = 0.f;
     if (j <= i) {
-      const size_t rk = ((size_t)b * S + j) * ld;
+      const size_t rk = (row0 + j) * ld;
       float a = 0.f, dp = 0.f;
       for (int c = 0; c < dh; ++c) {
         a = fmaf(qs[c], ldf(qkv, rk + koff + c), a);
@@ -130,7 +142,7 @@ __global__ __launch_bounds__(64) void attn_dq_simple_kernel(const T* __restrict_
       if (c < dh) {
         float a = dq[t];
         for (int jj = 0; jj < jn; ++jj)
-          a = fmaf(dss[jj], ldf(qkv, ((size_t)b * S + j0 + jj) * ld + koff + c), a);
+          a = fmaf(dss[jj], ldf(qkv, (row0 + j0 + jj) * ld + koff + c), a);
         dq[t] = a;
       }
     }
@@ -146,16 +158,21 @@ template <typename T>
 __global__ __launch_bounds__(64) void attn_dkv_simple_kernel(const T* __restrict__ qkv, const T* __restrict__ dout,
                                                              const float* __restrict__ lse,
                                                              const float* __restrict__ delta, T* __restrict__ dqkv,
-                                                             int S, int nh, int nkv, int dh) {
+                                                             int Smax, int nh, int nkv, int dh,
+                                                             const int* __restrict__ cu, int64_t Trows) {
   __shared__ float ks[kMaxDh], vs[kMaxDh];
   __shared__ float pss[64], dss[64];
   const int j = blockIdx.x, kh = blockIdx.y, b = blockIdx.z;
+  const SeqView sv = seq_view(cu, b, Smax);
+  const int S = sv.len;
+  if (j >= S) return;
+  const size_t row0 = (size_t)sv.row0;
   const int lane = threadIdx.x;
   const int G = nh / nkv;
   const int ld = (nh + 2 * nkv) * dh;
   const float scale = 1.0f / sqrtf((float)dh);
   const size_t koff = (size_t)(nh + kh) * dh, voff = (size_t)(nh + nkv + kh) * dh;
-  const size_t rowk = ((size_t)b * S + j) * ld;
+  const size_t rowk = (row0 + j) * ld;
   for (int c = lane; c < dh; c += 64) {
     ks[c] = ldf(qkv, rowk + koff + c) * scale;
     vs[c] = ldf(qkv, rowk + voff + c);
@@ -170,15 +187,15 @@ __global__ __launch_bounds__(64) void attn_dkv_simple_kernel(const T* __restrict
       const int i = i0 + lane;
       float pv = 0.f, ds = 0.f;
       if (i < S) {
-        const size_t rq = ((size_t)b * S + i) * ld + (size_t)h * dh;
-        const size_t ro = ((size_t)b * S + i) * ((size_t)nh * dh) + (size_t)h * dh;
+        const size_t rq = (row0 + i) * ld + (size_t)h * dh;
+        const size_t ro = (row0 + i) * ((size_t)nh * dh) + (size_t)h * dh;
         float a = 0.f, dp = 0.f;
         for (int c = 0; c < dh; ++c) {
           a = fmaf(ks[c], ldf(qkv, rq + c), a);
           dp = fmaf(vs[c], ldf(dout, ro + c), dp);
         }
-        pv = __expf(a - lse[((size_t)b * nh + h) * S + i]);
-        ds = pv * (dp - delta[((size_t)b * nh + h) * S + i]);
+        pv = __expf(a - lse[stat_index(cu, Trows, sv, b, h, nh, Smax, i)]);
+        ds = pv * (dp - delta[stat_index(cu, Trows, sv, b, h, nh, Smax, i)]);
       }
       __syncthreads();
       pss[lane] = pv;
@@ -191,8 +208,8 @@ __global__ __launch_bounds__(64) void attn_dkv_simple_kernel(const T* __restrict
         if (c < dh) {
           float a = dv[t], bb = dk[t];
           for (int ii = 0; ii < in; ++ii) {
-            const size_t rq = ((size_t)b * S + i0 + ii) * ld + (size_t)h * dh;
-            const size_t ro = ((size_t)b * S + i0 + ii) * ((size_t)nh * dh) + (size_t)h * dh;
+            const size_t rq = (row0 + i0 + ii) * ld + (size_t)h * dh;
+            const size_t ro = (row0 + i0 + ii) * ((size_t)nh * dh) + (size_t)h * dh;
             a = fmaf(pss[ii], ldf(dout, ro + c), a);
             bb = fmaf(dss[ii], ldf(qkv, rq + c), bb);
           }
@@ -220,16 +237,16 @@ hipError_t launch_attn_fwd_simple(const AttnArgs& a, hipStream_t s) {
   if (!simple_ok(a)) return hipErrorInvalidValue;
   ProfScope ps("attn_fwd_simple", 2.0 * a.B * a.nh * a.dh * (double)a.S * (a.S + 1), 0, s);
   dim3 grid(a.S, a.nh, a.B), blk(64);
-  if (a.dtype == kBF16) hipLaunchKernelGGL(attn_fwd_simple_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv, a.dh);
-  else hipLaunchKernelGGL(attn_fwd_simple_kernel<float>, grid, blk, 0, s, (const float*)a.qkv, (float*)a.out, a.lse, a.S, a.nh, a.nkv, a.dh);
+  if (a.dtype == kBF16) hipLaunchKernelGGL(attn_fwd_simple_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv, a.dh, a.cu_seqlens, a.total_rows);
+  else hipLaunchKernelGGL(attn_fwd_simple_kernel<float>, grid, blk, 0, s, (const float*)a.qkv, (float*)a.out, a.lse, a.S, a.nh, a.nkv, a.dh, a.cu_seqlens, a.total_rows);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_delta(const AttnArgs& a, hipStream_t s) {
   ProfScope ps("attn_delta", 0, 2.0 * a.B * a.S * a.nh * a.dh * dtype_size(a.dtype), s);
   dim3 grid(a.S, a.nh, a.B), blk(64);
-  if (a.dtype == kBF16) hipLaunchKernelGGL(attn_delta_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)a.out, (const bf16_t*)a.dout, a.delta, a.S, a.nh, a.dh);
-  else hipLaunchKernelGGL(attn_delta_kernel<float>, grid, blk, 0, s, (const float*)a.out, (const float*)a.dout, a.delta, a.S, a.nh, a.dh);
+  if (a.dtype == kBF16) hipLaunchKernelGGL(attn_delta_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)a.out, (const bf16_t*)a.dout, a.delta, a.S, a.nh, a.dh, a.cu_seqlens, a.total_rows);
+  else hipLaunchKernelGGL(attn_delta_kernel<float>, grid, blk, 0, s, (const float*)a.out, (const float*)a.dout, a.delta, a.S, a.nh, a.dh, a.cu_seqlens, a.total_rows);
   return hipGetLastError();
 }
 
@@ -240,11 +257,11 @@ hipError_t launch_attn_bwd_simple(const AttnArgs& a, hipStream_t s) {
   ProfScope ps("attn_bwd_simple", 7.0 * a.B * a.nh * a.dh * (double)a.S * (a.S + 1), 0, s);
   dim3 gq(a.S, a.nh, a.B), gk(a.S, a.nkv, a.B), blk(64);
   if (a.dtype == kBF16) {
-    hipLaunchKernelGGL(attn_dq_simple_kernel<bf16_t>, gq, blk, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.dh);
-    hipLaunchKernelGGL(attn_dkv_simple_kernel<bf16_t>, gk, blk, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.dh);
+    hipLaunchKernelGGL(attn_dq_simple_kernel<bf16_t>, gq, blk, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.dh, a.cu_seqlens, a.total_rows);
+    hipLaunchKernelGGL(attn_dkv_simple_kernel<bf16_t>, gk, blk, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.dh, a.cu_seqlens, a.total_rows);
   } else {
-    hipLaunchKernelGGL(attn_dq_simple_kernel<float>, gq, blk, 0, s, (const float*)a.qkv, (const float*)a.dout, a.lse, a.delta, (float*)a.dqkv, a.S, a.nh, a.nkv, a.dh);
-    hipLaunchKernelGGL(attn_dkv_simple_kernel<float>, gk, blk, 0, s, (const float*)a.qkv, (const float*)a.dout, a.lse, a.delta, (float*)a.dqkv, a.S, a.nh, a.nkv, a.dh);
+    hipLaunchKernelGGL(attn_dq_simple_kernel<float>, gq, blk, 0, s, (const float*)a.qkv, (const float*)a.dout, a.lse, a.delta, (float*)a.dqkv, a.S, a.nh, a.nkv, a.dh, a.cu_seqlens, a.total_rows);
+    hipLaunchKernelGGL(attn_dkv_simple_kernel<float>, gk, blk, 0, s, (const float*)a.qkv, (const float*)a.dout, a.lse, a.delta, (float*)a.dqkv, a.S, a.nh, a.nkv, a.dh, a.cu_seqlens, a.total_rows);
   }
   return hipGetLastError();
 }

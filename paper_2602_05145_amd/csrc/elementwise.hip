@@ -19,15 +19,19 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(const int32_t* __restri
                                                          const uint8_t* __restrict__ mask, int64_t T, int V,
                                                          int select_all, float* __restrict__ scal,
                                                          int* __restrict__ cnt, int32_t* __restrict__ kept_idx,
-                                                         int32_t* __restrict__ row_pos) {
+                                                         int32_t* __restrict__ row_pos,
+                                                         const int* __restrict__ cu, int nseq,
+                                                         uint8_t* __restrict__ mask_eff) {
   __shared__ int wsum_sel[16], wsum_keep[16];
+  // packed batches: only rows inside [cu[0], cu[nseq]) belong to a sequence; the rest is padding
+  const int64_t v0 = cu ? cu[0] : 0, v1 = cu ? min((int64_t)cu[nseq], T) : T;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int64_t per = (T + 1023) / 1024;
   const int64_t t0 = (int64_t)tid * per, t1 = min(T, t0 + per);
   int nsel = 0, nkeep = 0;
   for (int64_t t = t0; t < t1; ++t) {
     const int tk = tokens[t];
-    const int keep = (mask[t] != 0 && tk >= 0 && tk < V) ? 1 : 0;
+    const int keep = (mask[t] != 0 && tk >= 0 && tk < V && t >= v0 && t < v1) ? 1 : 0;
     nkeep += keep;
     nsel += select_all ? 1 : keep;
   }
@@ -53,8 +57,9 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(const int32_t* __restri
   int pos = base + incl - nsel;   // exclusive prefix of this thread
   for (int64_t t = t0; t < t1; ++t) {
     const int tk = tokens[t];
-    const int keep = (mask[t] != 0 && tk >= 0 && tk < V) ? 1 : 0;
+    const int keep = (mask[t] != 0 && tk >= 0 && tk < V && t >= v0 && t < v1) ? 1 : 0;
     const int sel = select_all ? 1 : keep;
+    mask_eff[t] = (uint8_t)keep;
     if (sel) {
       kept_idx[pos] = (int32_t)t;
       row_pos[t] = pos;
@@ -72,9 +77,53 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(const int32_t* __restri
 }
 
 hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
-                            float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, hipStream_t s) {
-  ProfScope ps("plan_rows", 0, 13.0 * (double)T, s);
-  hipLaunchKernelGGL(plan_rows_kernel, dim3(1), dim3(1024), 0, s, tokens, mask, T, V, select_all, scal, cnt, kept_idx, row_pos);
+                            float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, const int* cu, int nseq,
+                            uint8_t* mask_eff, hipStream_t s) {
+  ProfScope ps("plan_rows", 0, 14.0 * (double)T, s);
+  hipLaunchKernelGGL(plan_rows_kernel, dim3(1), dim3(1024), 0, s, tokens, mask, T, V, select_all, scal, cnt, kept_idx, row_pos, cu, nseq, mask_eff);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------------
+// Packed batches: position of every row inside its sequence (for RoPE), 0 for padding rows; and a fill
+// that zeroes the rows no sequence owns (attention writes only rows of sequences, and everything that is
+// later contracted over all T rows must be finite there).
+// ----------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void seq_pos_kernel(const int* __restrict__ cu, int nseq, int64_t T,
+                                                      int32_t* __restrict__ pos) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  int p = 0;
+  if (t >= cu[0] && t < cu[nseq]) {
+    int lo = 0, hi = nseq;               // largest b with cu[b] <= t (empty sequences share offsets: any owner gives the same start)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (cu[mid] <= t) lo = mid; else hi = mid;
+    }
+    p = (int)(t - cu[lo]);
+  }
+  pos[t] = p;
+}
+
+hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int32_t* pos, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  hipLaunchKernelGGL(seq_pos_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, cu, nseq, T, pos);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void zero_padding_rows_kernel(uint32_t* __restrict__ p, const int* __restrict__ cu, int nseq,
+                                                                int64_t T, int64_t row_words) {
+  const int64_t t = blockIdx.x;
+  if (t >= cu[0] && t < cu[nseq]) return;
+  uint32_t* r = p + t * row_words;
+  for (int64_t c = threadIdx.x; c < row_words; c += 256) r[c] = 0u;
+}
+
+// rows outside [cu[0], cu[nseq]) of a [T, row_bytes] array (row_bytes % 4 == 0) become zero
+hipError_t launch_zero_padding_rows(void* p, const int* cu, int nseq, int64_t T, int64_t row_bytes, hipStream_t s) {
+  if (T <= 0 || row_bytes <= 0) return hipSuccess;
+  if (row_bytes % 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(zero_padding_rows_kernel, dim3((unsigned)T), dim3(256), 0, s, (uint32_t*)p, cu, nseq, T, row_bytes / 4);
   return hipGetLastError();
 }
 
@@ -381,7 +430,7 @@ hipError_t launch_rope_table(int S, int dh, float theta, float* cs, hipStream_t 
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const float* __restrict__ cs,
                                                    int S, int nrot_heads, int dh, int ld, float sgn,
-                                                   int64_t total) {
+                                                   int64_t total, const int32_t* __restrict__ row_pos) {
   // one thread per (row t, head, i < dh/2); q heads then k heads are the first nrot_heads heads of a row
   const int half = dh >> 1;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -390,7 +439,7 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const fl
   const int64_t th = idx / half;
   const int hd = (int)(th % nrot_heads);
   const int64_t t = th / nrot_heads;
-  const int pos = (int)(t % S);
+  const int pos = row_pos ? row_pos[t] : (int)(t % S);
   const float c = cs[2 * ((size_t)pos * half + i)];
   const float sn = sgn * cs[2 * ((size_t)pos * half + i) + 1];
   const size_t o = (size_t)t * ld + (size_t)hd * dh + i;
@@ -403,7 +452,7 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const fl
 template <typename T>
 __global__ __launch_bounds__(256) void rope_vec8_kernel(T* __restrict__ qkv, const float* __restrict__ cs,
                                                         int S, int nrot_heads, int dh, int ld, float sgn,
-                                                        int64_t total8) {
+                                                        int64_t total8, const int32_t* __restrict__ row_pos) {
   const int half = dh >> 1, h8 = half >> 3;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total8) return;
@@ -411,7 +460,7 @@ __global__ __launch_bounds__(256) void rope_vec8_kernel(T* __restrict__ qkv, con
   const int64_t th = idx / h8;
   const int hd = (int)(th % nrot_heads);
   const int64_t t = th / nrot_heads;
-  const int pos = (int)(t % S);
+  const int pos = row_pos ? row_pos[t] : (int)(t % S);
   const float4* tab = reinterpret_cast<const float4*>(cs + 2 * ((size_t)pos * half + i));   // (cos, sin) x 8
   const size_t o = (size_t)t * ld + (size_t)hd * dh + i;
   float x1[8], x2[8], y1[8], y2[8];
@@ -431,7 +480,7 @@ __global__ __launch_bounds__(256) void rope_vec8_kernel(T* __restrict__ qkv, con
 }
 
 hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, void* qkv, int inverse,
-                       int dtype, hipStream_t s) {
+                       int dtype, const int32_t* row_pos, hipStream_t s) {
   const int nrot = nh + nkv;
   const int ld = (nh + 2 * nkv) * dh;
   const int64_t total = (int64_t)B * S * nrot * (dh / 2);
@@ -441,13 +490,13 @@ hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, v
   if ((dh % 16) == 0 && (((uintptr_t)qkv | (uintptr_t)cs) & 15) == 0) {
     const int64_t total8 = total / 8;
     dim3 grid8((unsigned)((total8 + 255) / 256)), blk8(256);
-    if (dtype == kBF16) hipLaunchKernelGGL(rope_vec8_kernel<bf16_t>, grid8, blk8, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total8);
-    else hipLaunchKernelGGL(rope_vec8_kernel<float>, grid8, blk8, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total8);
+    if (dtype == kBF16) hipLaunchKernelGGL(rope_vec8_kernel<bf16_t>, grid8, blk8, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total8, row_pos);
+    else hipLaunchKernelGGL(rope_vec8_kernel<float>, grid8, blk8, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total8, row_pos);
     return hipGetLastError();
   }
   dim3 grid((unsigned)((total + 255) / 256)), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total);
-  else hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total);
+  if (dtype == kBF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total, row_pos);
+  else hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total, row_pos);
   return hipGetLastError();
 }
 

@@ -43,7 +43,12 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);  // picks the MFMA pat
 // scal[1] = 1/N.  The rows the LM head processes are the kept ones (or all of them if select_all):
 // kept_idx[0..cnt[0]) lists them in ascending order, row_pos[t] is the position of row t in that list or -1.
 hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
-                            float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, hipStream_t s);
+                            float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, const int* cu, int nseq,
+                            uint8_t* mask_eff, hipStream_t s);
+// packed batches (cu = device offsets of nseq sequences): position of each row in its sequence, and zeroing
+// of the rows of a [T, row_bytes] array that no sequence owns
+hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int32_t* pos, hipStream_t s);
+hipError_t launch_zero_padding_rows(void* p, const int* cu, int nseq, int64_t T, int64_t row_bytes, hipStream_t s);
 // dst[i] = src[kept_idx[i]] for i < *cnt (rows of width d), same for tokens and mask
 hipError_t launch_gather_rows(int64_t T, int d, const void* src, const int32_t* tokens, const uint8_t* mask,
                               const int32_t* kept_idx, const int* cnt, void* dst, int32_t* tokens_c,
@@ -58,8 +63,9 @@ hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x
                               const float* rstd, const void* res, void* dx, float* dg,
                               float* dg_partial, int dtype, hipStream_t s);
 hipError_t launch_rope_table(int S, int dh, float theta, float* cs, hipStream_t s);  // cs [S, dh/2, 2]
+// row_pos (optional, device): position of every row in its sequence; NULL = row % S
 hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, void* qkv, int inverse,
-                       int dtype, hipStream_t s);
+                       int dtype, const int32_t* row_pos, hipStream_t s);
 hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, hipStream_t s);
 hipError_t launch_swiglu_bwd(int64_t n, const void* dh, const void* gt, const void* u, void* dgt,
                              void* du, int dtype, hipStream_t s);
@@ -94,6 +100,11 @@ struct AttnArgs {
   const void* qkv; void* out; float* lse;           // forward
   const void* dout; float* delta; void* dqkv;       // backward
   int dtype;
+  // packed batches: device offsets of the B sequences (B+1 ascending values, the last <= total_rows) and
+  // the row count of the activations; S is then the longest sequence allowed.  NULL = B x S fixed layout.
+  // lse / delta are [B, nh, S] in the fixed layout and [nh, total_rows] when packed.
+  const int* cu_seqlens = nullptr;
+  int64_t total_rows = 0;
 };
 bool attn_mfma_supported(const AttnArgs& a);
 hipError_t launch_attn_delta(const AttnArgs& a, hipStream_t s);  // delta = rowsum(dO * O)

@@ -74,4 +74,22 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
+// The rows of sequence b: fixed-length batches keep sequence b in rows [b*Smax, (b+1)*Smax); packed batches
+// give the row range through cu_seqlens (device, n_seqs+1 ascending offsets) and may hold empty sequences.
+struct SeqView {
+  int64_t row0;   // first row of the sequence in the [T, ...] activations
+  int len;        // its length
+};
+__device__ __forceinline__ SeqView seq_view(const int* cu, int b, int Smax) {
+  if (cu) {
+    const int s0 = cu[b];
+    return SeqView{(int64_t)s0, cu[b + 1] - s0};
+  }
+  return SeqView{(int64_t)b * Smax, Smax};
+}
+// index of (sequence b, head h, position i) in lse / delta: [B, nh, S] for fixed-length batches, [nh, T] packed
+__device__ __forceinline__ size_t stat_index(const int* cu, int64_t T, const SeqView& v, int b, int h, int nh, int Smax, int i) {
+  return cu ? (size_t)h * (size_t)T + (size_t)v.row0 + i : ((size_t)b * nh + h) * (size_t)Smax + i;
+}
+
 }  // namespace tide

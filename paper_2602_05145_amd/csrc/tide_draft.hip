@@ -69,7 +69,7 @@ struct Plan {
   int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows;
   size_t es;  // activation element size
   // offsets (bytes)
-  size_t scal, cnt, kept_idx, row_pos, tokens_c, mask_c, yhat_c, dyhat_c, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
+  size_t scal, cnt, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, yhat_c, dyhat_c, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
   size_t fwd_end;
   size_t dyhat, dx2, dx1, dx0, dh, dbn, dA, dqkv, da, delta, dg_partial;
   size_t total;
@@ -112,7 +112,9 @@ Plan make_plan(const tide_draft_config* c) {
   p.row_pos = b.take(T * 4);
   p.tokens_c = b.take(T * 4);
   p.mask_c = b.take(T);
-  p.rope_cs = b.take((size_t)c->seq * c->head_dim * sizeof(float));
+  p.mask_eff = b.take(T);
+  p.seq_pos = b.take(T * 4);
+  p.rope_cs = b.take(T * c->head_dim * sizeof(float));   // up to T positions: one packed sequence may fill the batch
   p.x0 = b.take(T * p.d * es);
   p.r1 = b.take(T * 4);
   p.a = b.take(T * p.d * es);
@@ -180,25 +182,62 @@ GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const void* A, i
   return g;
 }
 
+// How the T = batch * seq rows split into sequences: the fixed layout (cu == nullptr: `n` sequences of
+// `max_len` rows each) or a packed batch (cu = device offsets of n sequences, none longer than max_len;
+// rows outside [cu[0], cu[n]) are padding).
+struct Seqs {
+  const int* cu;
+  int n, max_len;
+};
+
+Seqs fixed_seqs(const tide_draft_config* c) { return Seqs{nullptr, c->batch, c->seq}; }
+
+int check_packed(const tide_draft_config* c, const int32_t* cu_seqlens, int32_t n_seqs, int32_t max_seqlen) {
+  if (!cu_seqlens) return fail(TIDE_ERR_NULL, "cu_seqlens is NULL");
+  const int64_t T = (int64_t)c->batch * c->seq;
+  if (n_seqs < 1 || n_seqs > 65535) return fail(TIDE_ERR_CONFIG, "n_seqs must be in [1, 65535]");
+  if (max_seqlen < 1 || max_seqlen > T) return fail(TIDE_ERR_CONFIG, "max_seqlen must be in [1, batch*seq]");
+  return TIDE_OK;
+}
+
+AttnArgs attn_args(const tide_draft_config* c, const Seqs& q, char* ws, const Plan& p) {
+  AttnArgs at;
+  std::memset(&at, 0, sizeof(at));
+  at.B = q.n; at.S = q.max_len; at.nh = c->n_heads; at.nkv = c->n_kv_heads; at.dh = c->head_dim;
+  at.qkv = ws + p.qkv; at.out = ws + p.A; at.lse = (float*)(ws + p.attn_lse); at.dtype = c->dtype;
+  at.cu_seqlens = q.cu; at.total_rows = p.T;
+  return at;
+}
+
+// RoPE over all T rows: position = row % seq in the fixed layout, the planned per-row position when packed
+int enqueue_rope(const tide_draft_config* c, const Seqs& q, char* ws, const Plan& p, void* qkv, int inverse, hipStream_t s) {
+  const float* cs = (const float*)(ws + p.rope_cs);
+  if (q.cu) TIDE_HIP(launch_rope(1, (int)p.T, c->n_heads, c->n_kv_heads, c->head_dim, cs, qkv, inverse, c->dtype, (const int32_t*)(ws + p.seq_pos), s), "rope");
+  else TIDE_HIP(launch_rope(c->batch, c->seq, c->n_heads, c->n_kv_heads, c->head_dim, cs, qkv, inverse, c->dtype, nullptr, s), "rope");
+  return TIDE_OK;
+}
+
 // Forward pass up to the final RMSNorm (everything except the LM head).
 int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const void* hidden_buf,
-                  const int32_t* tokens, const uint8_t* mask, int select_all, char* ws, const Plan& p,
+                  const int32_t* tokens, const uint8_t* mask, int select_all, const Seqs& q, char* ws, const Plan& p,
                   hipStream_t s) {
   const int dt = c->dtype;
   const int64_t T = p.T;
   float* scal = (float*)(ws + p.scal);
-  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), s), "plan_rows");
+  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), q.cu, q.n, (uint8_t*)(ws + p.mask_eff), s), "plan_rows");
+  if (q.cu) TIDE_HIP(launch_seq_pos(q.cu, q.n, T, (int32_t*)(ws + p.seq_pos), s), "sequence positions");
   // x0 = Hcat W_fc^T
   TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.x0, p.d, dt, dt), s), "gemm fc");
   TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x0, P->g1, c->rms_eps, ws + p.a, (float*)(ws + p.r1), dt, s), "rmsnorm1");
   TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.nqkv, p.d, ws + p.a, p.d, P->w_qkv, p.d, ws + p.qkv, p.nqkv, dt, dt), s), "gemm qkv");
-  TIDE_HIP(launch_rope_table(c->seq, c->head_dim, c->rope_theta, (float*)(ws + p.rope_cs), s), "rope table");
-  TIDE_HIP(launch_rope(c->batch, c->seq, c->n_heads, c->n_kv_heads, c->head_dim, (const float*)(ws + p.rope_cs), ws + p.qkv, 0, dt, s), "rope");
-  AttnArgs at;
-  std::memset(&at, 0, sizeof(at));
-  at.B = c->batch; at.S = c->seq; at.nh = c->n_heads; at.nkv = c->n_kv_heads; at.dh = c->head_dim;
-  at.qkv = ws + p.qkv; at.out = ws + p.A; at.lse = (float*)(ws + p.attn_lse); at.dtype = dt;
-  TIDE_HIP(launch_attn_fwd(at, s), "attention fwd");
+  TIDE_HIP(launch_rope_table(q.max_len, c->head_dim, c->rope_theta, (float*)(ws + p.rope_cs), s), "rope table");
+  { const int rc = enqueue_rope(c, q, ws, p, ws + p.qkv, 0, s); if (rc) return rc; }
+  {
+    const AttnArgs at = attn_args(c, q, ws, p);
+    TIDE_HIP(launch_attn_fwd(at, s), "attention fwd");
+    // padding rows are written by no sequence: make them finite (they enter weight-gradient contractions)
+    if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.A, q.cu, q.n, T, (int64_t)(p.nq * p.es), s), "zero padding rows");
+  }
   // x1 = x0 + A W_o^T
   {
     GemmArgs g = gemm_args(kNT, T, p.d, p.nq, ws + p.A, p.nq, P->w_o, p.nq, ws + p.x1, p.d, dt, dt);
@@ -236,7 +275,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
   float* hit_rows = acc_out ? (float*)(ws + p.hit_rows) : nullptr;
   char* yhat_c = ws + p.yhat_c;
   char* z = ws + p.z;
-  TIDE_HIP(launch_gather_rows(p.T, (int)p.d, ws + p.yhat, tokens, mask, kept_idx, cnt, yhat_c, (int32_t*)(ws + p.tokens_c), (uint8_t*)(ws + p.mask_c), dt, s), "gather rows");
+  TIDE_HIP(launch_gather_rows(p.T, (int)p.d, ws + p.yhat, tokens, (const uint8_t*)(ws + p.mask_eff), kept_idx, cnt, yhat_c, (int32_t*)(ws + p.tokens_c), (uint8_t*)(ws + p.mask_c), dt, s), "gather rows");
   int blk = 0;
   for (int64_t r0 = 0; r0 < p.T; r0 += p.lm_rows, ++blk) {
     const int64_t rows = (p.T - r0 < p.lm_rows) ? (p.T - r0) : p.lm_rows;
@@ -298,41 +337,52 @@ int64_t tide_draft_workspace_offset(const tide_draft_config* cfg, const char* na
   return -1;
 }
 
+static int forward_impl(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
+                        const int32_t* tokens, const uint8_t* loss_mask, const Seqs* packed, float* loss_out,
+                        int32_t* top1_out, float* accuracy_out, void* workspace, size_t workspace_bytes, void* stream) {
+  const Plan p = make_plan(cfg);
+  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
+  if (rc) return rc;
+  const Seqs q = packed ? *packed : fixed_seqs(cfg);
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, top1_out != nullptr, q, ws, p, s);
+  if (rc) return rc;
+  return enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, top1_out, loss_out, accuracy_out, ws, p, false, s);
+}
+
 int tide_draft_forward(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
                        const int32_t* tokens, const uint8_t* loss_mask, float* loss_out, int32_t* top1_out,
                        void* workspace, size_t workspace_bytes, void* stream) {
   if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
-  const Plan p = make_plan(cfg);
-  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
+  return forward_impl(cfg, params, hidden_buf, tokens, loss_mask, nullptr, loss_out, top1_out, nullptr, workspace, workspace_bytes, stream);
+}
+
+int tide_draft_forward_packed(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
+                              const int32_t* tokens, const uint8_t* loss_mask, const int32_t* cu_seqlens,
+                              int32_t n_seqs, int32_t max_seqlen, float* loss_out, int32_t* top1_out,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const int rc = check_packed(cfg, cu_seqlens, n_seqs, max_seqlen);
   if (rc) return rc;
-  hipStream_t s = (hipStream_t)stream;
-  char* ws = (char*)workspace;
-  rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, top1_out != nullptr, ws, p, s);
-  if (rc) return rc;
-  return enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, top1_out, loss_out, nullptr, ws, p, false, s);
+  const Seqs q{cu_seqlens, n_seqs, max_seqlen};
+  return forward_impl(cfg, params, hidden_buf, tokens, loss_mask, &q, loss_out, top1_out, nullptr, workspace, workspace_bytes, stream);
 }
 
 int tide_draft_eval(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
                     const int32_t* tokens, const uint8_t* loss_mask, float* loss_out, float* accuracy_out,
                     void* workspace, size_t workspace_bytes, void* stream) {
   if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
-  const Plan p = make_plan(cfg);
-  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
-  if (rc) return rc;
   if (!accuracy_out) return fail(TIDE_ERR_NULL, "accuracy_out is NULL");
-  hipStream_t s = (hipStream_t)stream;
-  char* ws = (char*)workspace;
-  rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, 0, ws, p, s);
-  if (rc) return rc;
-  return enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, nullptr, loss_out, accuracy_out, ws, p, false, s);
+  return forward_impl(cfg, params, hidden_buf, tokens, loss_mask, nullptr, loss_out, nullptr, accuracy_out, workspace, workspace_bytes, stream);
 }
 
-int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
-                          tide_adam_state* st, const void* hidden_buf, const int32_t* tokens,
-                          const uint8_t* loss_mask, float lr, float* loss_out, void* workspace,
-                          size_t workspace_bytes, void* stream) {
-  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                      tide_adam_state* st, const void* hidden_buf, const int32_t* tokens,
+                      const uint8_t* loss_mask, const Seqs* packed, float lr, float* loss_out, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   const Plan p = make_plan(cfg);
+  const Seqs q = packed ? *packed : fixed_seqs(cfg);
   int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
   if (rc) return rc;
   if (!tensors_ok(grads, "grads")) return TIDE_ERR_NULL;
@@ -349,7 +399,7 @@ int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* para
   tide_draft_tensors* G = grads;
   const int64_t T = p.T;
 
-  rc = enqueue_trunk(cfg, P, hidden_buf, tokens, loss_mask, 0, ws, p, s);
+  rc = enqueue_trunk(cfg, P, hidden_buf, tokens, loss_mask, 0, q, ws, p, s);
   if (rc) return rc;
   rc = enqueue_lm_head(cfg, P, G, tokens, loss_mask, nullptr, loss_out, nullptr, ws, p, true, s);
   if (rc) return rc;
@@ -374,14 +424,12 @@ int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* para
   TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.nq, p.d, ws + p.dx1, p.d, P->w_o, p.nq, ws + p.dA, p.nq, dt, dt), s), "gemm dA");
   TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.nq, T, ws + p.dx1, p.d, ws + p.A, p.nq, G->w_o, p.nq, dt, kF32), s), "gemm dW_o");
   {
-    AttnArgs at;
-    std::memset(&at, 0, sizeof(at));
-    at.B = cfg->batch; at.S = cfg->seq; at.nh = cfg->n_heads; at.nkv = cfg->n_kv_heads; at.dh = cfg->head_dim;
-    at.qkv = ws + p.qkv; at.out = ws + p.A; at.lse = (float*)(ws + p.attn_lse);
-    at.dout = ws + p.dA; at.delta = (float*)(ws + p.delta); at.dqkv = ws + p.dqkv; at.dtype = dt;
+    AttnArgs at = attn_args(cfg, q, ws, p);
+    at.dout = ws + p.dA; at.delta = (float*)(ws + p.delta); at.dqkv = ws + p.dqkv;
     TIDE_HIP(launch_attn_bwd(at, s), "attention bwd");
+    if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.dqkv, q.cu, q.n, T, (int64_t)(p.nqkv * p.es), s), "zero padding rows");
   }
-  TIDE_HIP(launch_rope(cfg->batch, cfg->seq, cfg->n_heads, cfg->n_kv_heads, cfg->head_dim, (const float*)(ws + p.rope_cs), ws + p.dqkv, 1, dt, s), "rope bwd");
+  { const int rc2 = enqueue_rope(cfg, q, ws, p, ws + p.dqkv, 1, s); if (rc2) return rc2; }
   TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.nqkv, ws + p.dqkv, p.nqkv, P->w_qkv, p.d, ws + p.da, p.d, dt, dt), s), "gemm da");
   TIDE_HIP(launch_gemm(gemm_args(kTN, p.nqkv, p.d, T, ws + p.dqkv, p.nqkv, ws + p.a, p.d, G->w_qkv, p.d, dt, kF32), s), "gemm dW_qkv");
   TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.da, ws + p.x0, P->g1, (const float*)(ws + p.r1), ws + p.dx1, ws + p.dx0, (float*)G->g1, dgp, dt, s), "rmsnorm1 bwd");
@@ -409,6 +457,26 @@ int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* para
   }
   st->step += 1;
   return TIDE_OK;
+}
+
+int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                          tide_adam_state* st, const void* hidden_buf, const int32_t* tokens,
+                          const uint8_t* loss_mask, float lr, float* loss_out, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  return train_impl(cfg, params, grads, st, hidden_buf, tokens, loss_mask, nullptr, lr, loss_out, workspace, workspace_bytes, stream);
+}
+
+int tide_draft_train_step_packed(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                                 tide_adam_state* st, const void* hidden_buf, const int32_t* tokens,
+                                 const uint8_t* loss_mask, const int32_t* cu_seqlens, int32_t n_seqs,
+                                 int32_t max_seqlen, float lr, float* loss_out, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const int rc = check_packed(cfg, cu_seqlens, n_seqs, max_seqlen);
+  if (rc) return rc;
+  const Seqs q{cu_seqlens, n_seqs, max_seqlen};
+  return train_impl(cfg, params, grads, st, hidden_buf, tokens, loss_mask, &q, lr, loss_out, workspace, workspace_bytes, stream);
 }
 
 // ---- building blocks ---------------------------------------------------------------------------
@@ -481,7 +549,7 @@ int tide_rope(int B, int S, int nh, int nkv, int dh, float theta, void* qkv, flo
   if (!qkv || !table) return fail(TIDE_ERR_NULL, "NULL argument");
   if (B <= 0 || S <= 0 || nh <= 0 || nkv <= 0 || dh <= 0 || dh % 2) return fail(TIDE_ERR_CONFIG, "bad rope shape");
   TIDE_HIP(launch_rope_table(S, dh, theta, table, (hipStream_t)stream), "rope table");
-  TIDE_HIP(launch_rope(B, S, nh, nkv, dh, table, qkv, inverse, dtype, (hipStream_t)stream), "rope");
+  TIDE_HIP(launch_rope(B, S, nh, nkv, dh, table, qkv, inverse, dtype, nullptr, (hipStream_t)stream), "rope");
   return TIDE_OK;
 }
 

@@ -77,6 +77,27 @@ class DraftTrainer:
                           self.workspace, self.ws_bytes, self._stream())
         return self.loss, acc
 
+    # ---- packed (variable-length) batches: the batch*seq rows hold sequences back to back ----
+    def set_packed(self, cu_seqlens, max_seqlen=None):
+        """cu_seqlens: n_seqs+1 ascending offsets into the rows (host list / numpy); kept resident on the device."""
+        cu = np.ascontiguousarray(np.asarray(cu_seqlens, dtype=np.int32))
+        self.n_seqs = int(cu.shape[0] - 1)
+        self.max_seqlen = int(max_seqlen if max_seqlen is not None else max(1, int(np.max(np.diff(cu))) if self.n_seqs else 1))
+        self.cu = torch.from_numpy(cu).to(self.device)
+
+    def forward_packed(self, want_top1=False):
+        top1 = (torch.empty(self.cfg["batch"] * self.cfg["seq"], dtype=torch.int32, device=self.device)
+                if want_top1 else None)
+        B.tide_draft_forward_packed(self.ccfg, self.c_params, self.hidden, self.tokens, self.mask, self.cu, self.n_seqs,
+                                    self.max_seqlen, self.loss, top1, self.workspace, self.ws_bytes, self._stream())
+        return (self.loss, top1) if want_top1 else self.loss
+
+    def train_step_packed(self, lr):
+        B.tide_draft_train_step_packed(self.ccfg, self.c_params, self.c_grads, self.c_adam, self.hidden, self.tokens,
+                                       self.mask, self.cu, self.n_seqs, self.max_seqlen, lr, self.loss,
+                                       self.workspace, self.ws_bytes, self._stream())
+        return self.loss
+
     def train_step(self, lr):
         B.tide_draft_train_step(self.ccfg, self.c_params, self.c_grads, self.c_adam, self.hidden, self.tokens,
                                 self.mask, lr, self.loss, self.workspace, self.ws_bytes, self._stream())

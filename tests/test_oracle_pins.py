@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from oracle import tide_oracle as O
+from paper_2602_05145_amd import workloads as W
 from tests.helpers import micro_cfg, micro_workload
 
 
@@ -483,3 +484,65 @@ def test_top1_accuracy_definition():
     bad = tok.copy(); bad[0] = V + 3                                          # out-of-range label never counts
     m1 = np.ones(T, np.uint8)
     assert O.top1_accuracy(bad, bad, m1, V) == (T - 1) / (T - 1)
+
+
+def _tiny_ragged(seed=21):
+    """A small fp64 problem with ragged sequences: (cfg, params, per-sequence lists)."""
+    cfg = dict(W.get_config("tiny"), hidden=32, n_heads=4, n_kv_heads=2, head_dim=8, ffn=48, vocab=50,
+               target_hidden=12, n_capture=3)
+    rng = np.random.default_rng(seed)
+    params = W.make_params(cfg, rng)
+    params = {k: np.asarray(v, np.float64) for k, v in params.items()}
+    lens = [5, 1, 7, 3]
+    KH = cfg["n_capture"] * cfg["target_hidden"]
+    hid = [rng.standard_normal((n, KH)) for n in lens]
+    tok = [rng.integers(0, cfg["vocab"], n) for n in lens]
+    msk = [(rng.random(n) > 0.3).astype(np.uint8) for n in lens]
+    msk[1][:] = 0                      # a sequence without any loss position
+    return cfg, params, lens, hid, tok, msk
+
+
+def test_packed_equals_fixed_batch_when_lengths_are_equal():
+    cfg = dict(W.get_config("tiny"), hidden=32, n_heads=4, n_kv_heads=2, head_dim=8, ffn=48, vocab=50,
+               target_hidden=12, n_capture=3, batch=3, seq=6)
+    rng = np.random.default_rng(5)
+    params = {k: np.asarray(v, np.float64) for k, v in W.make_params(cfg, rng).items()}
+    KH = cfg["n_capture"] * cfg["target_hidden"]
+    hid = rng.standard_normal((3, 6, KH))
+    tok = rng.integers(0, cfg["vocab"], (3, 6))
+    msk = (rng.random((3, 6)) > 0.25).astype(np.uint8)
+    loss, cache = O.forward(cfg, params, hid, tok, msk)
+    g = O.backward(cfg, params, cache, tok, msk)
+    loss_p, g_p, _ = O.train_quantities_packed(cfg, params, hid.reshape(18, KH), tok.reshape(-1), msk.reshape(-1), [0, 6, 12, 18])
+    assert loss_p == pytest.approx(loss, rel=1e-13)
+    for k in g:
+        assert np.max(np.abs(g_p[k] - g[k])) <= 1e-13 * max(1.0, np.max(np.abs(g[k]))), k
+
+
+def test_packed_equals_right_padded_batch():
+    # the same ragged sequences, once packed back to back and once right-padded to the longest with the pads
+    # masked: causality keeps the pads from reaching any real position, so loss and gradients agree
+    cfg, params, lens, hid, tok, msk = _tiny_ragged()
+    S, B, KH = max(lens), len(lens), hid[0].shape[1]
+    hp = np.zeros((B, S, KH)); tp = np.zeros((B, S), np.int64); mp = np.zeros((B, S), np.uint8)
+    for i, n in enumerate(lens):
+        hp[i, :n], tp[i, :n], mp[i, :n] = hid[i], tok[i], msk[i]
+    cpad = dict(cfg, batch=B, seq=S)
+    loss, cache = O.forward(cpad, params, hp, tp, mp)
+    g = O.backward(cpad, params, cache, tp, mp)
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    T = int(cu[-1]) + 3                                   # three padding rows at the end of the packed buffer
+    hr = np.concatenate(hid + [np.full((3, KH), 7.0)]); tr = np.concatenate(tok + [np.array([1, 2, 3])])
+    mr = np.concatenate(msk + [np.ones(3, np.uint8)])     # the caller left the mask set on padding rows: ignored
+    loss_p, g_p, top1 = O.train_quantities_packed(dict(cfg, batch=1, seq=T), params, hr, tr, mr, cu, want_top1=True)
+    assert loss_p == pytest.approx(loss, rel=1e-12)
+    for k in g:
+        assert np.max(np.abs(g_p[k] - g[k])) <= 1e-12 * max(1.0, np.max(np.abs(g[k]))), k
+    assert np.all(top1[int(cu[-1]):] == -1) and np.all(top1[:int(cu[-1])] >= 0)
+    # an empty sequence in the middle changes nothing
+    cu2 = [0, 5, 5, 6, 13, 16]
+    loss_q, g_q, _ = O.train_quantities_packed(dict(cfg, batch=1, seq=T), params, hr, tr, mr, cu2)
+    assert loss_q == pytest.approx(loss_p, rel=1e-14)
+    # moving a boundary does change the result (the attention span of the moved rows differs)
+    loss_r, _, _ = O.train_quantities_packed(dict(cfg, batch=1, seq=T), params, hr, tr, mr, [0, 4, 6, 13, 16])
+    assert abs(loss_r - loss_p) > 1e-6
