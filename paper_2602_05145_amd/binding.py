@@ -98,7 +98,9 @@ _lib.tide_profile_stop.argtypes = [C.c_char_p, _sz]
 
 EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
             "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_draft_forward_packed",
-    "tide_draft_train_step_packed", "tide_gemm_workspace_bytes", "tide_gemm",
+    "tide_draft_train_step_packed",
+    "tide_ingest_create", "tide_ingest_destroy", "tide_ingest_acquire", "tide_ingest_submit", "tide_ingest_wait",
+    "tide_ingest_done", "tide_ingest_last_error", "tide_gemm_workspace_bytes", "tide_gemm",
             "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd",
             "tide_attention_fwd", "tide_attention_bwd", "tide_rope", "tide_profile_start",
             "tide_profile_stop")
@@ -246,3 +248,55 @@ def tide_profile_stop():
     buf = C.create_string_buffer(1 << 16)
     _check(_lib.tide_profile_stop(buf, len(buf)))
     return json.loads(buf.value.decode())
+
+
+# ---- signal ingest ring (include/tide_ingest.h) ----
+TIDE_INGEST_ERR_NULL, TIDE_INGEST_ERR_ARG, TIDE_INGEST_ERR_HIP, TIDE_INGEST_ERR_BUSY = -1, -2, -4, -5
+_lib.tide_ingest_create.restype = _i32
+_lib.tide_ingest_create.argtypes = [C.POINTER(_vp), _sz, _i32]
+_lib.tide_ingest_destroy.restype = _i32
+_lib.tide_ingest_destroy.argtypes = [_vp]
+_lib.tide_ingest_acquire.restype = _i32
+_lib.tide_ingest_acquire.argtypes = [_vp, C.POINTER(C.c_int32), C.POINTER(_vp)]
+_lib.tide_ingest_submit.restype = _i32
+_lib.tide_ingest_submit.argtypes = [_vp, _i32, _vp, _sz]
+_lib.tide_ingest_wait.restype = _i32
+_lib.tide_ingest_wait.argtypes = [_vp, _i32, _vp]
+_lib.tide_ingest_done.restype = _i32
+_lib.tide_ingest_done.argtypes = [_vp, _i32]
+_lib.tide_ingest_last_error.restype = C.c_char_p
+_lib.tide_ingest_last_error.argtypes = []
+
+
+def tide_ingest_create(slot_bytes, n_slots):
+    """Returns (rc, handle)."""
+    h = _vp()
+    rc = _lib.tide_ingest_create(C.byref(h), int(slot_bytes), int(n_slots))
+    return rc, h
+
+
+def tide_ingest_destroy(h):
+    return _lib.tide_ingest_destroy(h)
+
+
+def tide_ingest_acquire(h):
+    """Returns (rc, slot, host address)."""
+    slot, ptr = C.c_int32(-1), _vp()
+    rc = _lib.tide_ingest_acquire(h, C.byref(slot), C.byref(ptr))
+    return rc, int(slot.value), ptr.value
+
+
+def tide_ingest_submit(h, slot, device_dst, nbytes):
+    return _lib.tide_ingest_submit(h, int(slot), _ptr(device_dst), int(nbytes))
+
+
+def tide_ingest_wait(h, slot, stream):
+    return _lib.tide_ingest_wait(h, int(slot), stream)
+
+
+def tide_ingest_done(h, slot):
+    return _lib.tide_ingest_done(h, int(slot))
+
+
+def tide_ingest_last_error() -> str:
+    return _lib.tide_ingest_last_error().decode()

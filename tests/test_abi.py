@@ -18,15 +18,20 @@ def B():
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "tide_draft.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tide_[a-z0-9_]+)\s*\(", text)))
+    """Every function declared by the two headers that libtide_draft.so implements (tide_control.h belongs
+    to the host-only libtide_control.so and is checked in test_control_parity.py)."""
+    names = set()
+    for hdr in ("tide_draft.h", "tide_ingest.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(tide_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol(B):
     lib = ctypes.CDLL(B.LIB_PATH)
     names = _declared_symbols()
-    assert "tide_draft_forward" in names and "tide_draft_train_step" in names
+    assert "tide_draft_forward" in names and "tide_draft_train_step" in names and "tide_ingest_submit" in names
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(B.EXPORTED)
@@ -60,3 +65,7 @@ def test_calls_reject_bad_arguments_before_touching_the_device(B):
     assert rc == B.TIDE_ERR_CONFIG
     with pytest.raises(B.TideError):
         B.tide_draft_train_step(c, t, t, B.TideAdamState(), 256, 256, 256, 1e-4, 256, 256, 1 << 40, None)
+
+
+def test_every_header_in_include_is_covered():
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["tide_control.h", "tide_draft.h", "tide_ingest.h"]
