@@ -451,6 +451,43 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
             *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(C) + (size_t)gm * p.ldc + gn) = val;
         }
       }
+    } else if constexpr ((NW / 2) * 32 * (WN + 4) * 2 <= A_STAGE + B_STAGE) {
+      if (R && !p.accumulate && (p.ldc % 8) == 0 && (p.ldr % 8) == 0 && (p.N % 8) == 0) {
+        staged = true;
+        // bf16 result plus residual: the patch keeps fp32 so that alpha*acc + residual is rounded once, as in
+        // the direct path; residual and result move as 16-byte row segments.
+        __builtin_amdgcn_s_barrier();
+        constexpr int PF = WN + 4;                     // patch pitch (floats)
+        float* patch = reinterpret_cast<float*>(wave < NW / 2 ? s0 : s1) + (wave % (NW / 2)) * (32 * PF);
+        constexpr int PIECES = WN / 8;
+        const bf16_t* Rb = reinterpret_cast<const bf16_t*>(R);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+              const int rr = 8 * (q >> 2) + 4 * lg + (q & 3);
+              patch[rr * PF + 32 * j + lr] = alpha * acc[i][j][q];
+            }
+#pragma unroll
+          for (int t = 0; t < 32 * PIECES / 64; ++t) {
+            const int pc = lane + 64 * t;
+            const int row = pc / PIECES, piece = pc % PIECES;
+            const int gm = wm0 + 32 * i + row, gn = wn0 + piece * 8;
+            if (gm < p.M && gn < p.N) {
+              float v[8], r[8];
+              const float4 a0 = *reinterpret_cast<const float4*>(patch + row * PF + piece * 8);
+              const float4 a1 = *reinterpret_cast<const float4*>(patch + row * PF + piece * 8 + 4);
+              v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
+              ld8(Rb, (size_t)gm * p.ldr + gn, r);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += r[e];
+              st8(reinterpret_cast<bf16_t*>(C), (size_t)gm * p.ldc + gn, v);
+            }
+          }
+        }
+      }
     }
   }
   if (!staged) {
