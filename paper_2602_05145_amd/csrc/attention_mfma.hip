@@ -73,14 +73,25 @@ __device__ __forceinline__ u32x4_t frag_tr(const bf16_t* tile, int kbase, int nb
 }
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+  return f2bf2(lo, hi);
+}
+
+// the same rounding (nearest even) in integer arithmetic: the dK/dV kernel keeps more values live than it has
+// registers, and there the packed hardware conversion measured 21 % slower (its operands stay live longer)
+__device__ __forceinline__ uint32_t pack2_int(float lo, float hi) {
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7FFFu + ((a >> 16) & 1u);
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xFFFF0000u);
 }
 
 // registers q0..q0+7 of a 32x32 accumulator -> the 8-value B operand of the next MFMA
+template <bool INT_ROUND = false>
 __device__ __forceinline__ u32x4_t pack_half(const f32x16_t& v, int half) {
   u32x4_t r;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) r[w] = pack2(v[half * 8 + 2 * w], v[half * 8 + 2 * w + 1]);
+  for (int w = 0; w < 4; ++w)
+    r[w] = INT_ROUND ? pack2_int(v[half * 8 + 2 * w], v[half * 8 + 2 * w + 1]) : pack2(v[half * 8 + 2 * w], v[half * 8 + 2 * w + 1]);
   return r;
 }
 
@@ -112,6 +123,7 @@ struct TileLoader {
 
 // Write a wave's 32 x 128 result, held transposed in 4 accumulators (acc[ct] = rows ct*32.., column =
 // lane % 32 = the wave-local output row), into an LDS tile [128][PITCH] at rows wave*32.. as bf16.
+template <bool INT_ROUND = false>
 __device__ __forceinline__ void stage_out(bf16_t* tile, const f32x16_t (&acc)[4], float mul, int wave, int lane) {
   const int g = lane >> 5, r = wave * 32 + (lane & 31);
 #pragma unroll
@@ -120,8 +132,8 @@ __device__ __forceinline__ void stage_out(bf16_t* tile, const f32x16_t (&acc)[4]
     for (int qq = 0; qq < 4; ++qq) {
       const int c = ct * 32 + 8 * qq + 4 * g;
       uint2 v;
-      v.x = pack2(acc[ct][qq * 4 + 0] * mul, acc[ct][qq * 4 + 1] * mul);
-      v.y = pack2(acc[ct][qq * 4 + 2] * mul, acc[ct][qq * 4 + 3] * mul);
+      v.x = INT_ROUND ? pack2_int(acc[ct][qq * 4 + 0] * mul, acc[ct][qq * 4 + 1] * mul) : pack2(acc[ct][qq * 4 + 0] * mul, acc[ct][qq * 4 + 1] * mul);
+      v.y = INT_ROUND ? pack2_int(acc[ct][qq * 4 + 2] * mul, acc[ct][qq * 4 + 3] * mul) : pack2(acc[ct][qq * 4 + 2] * mul, acc[ct][qq * 4 + 3] * mul);
       *reinterpret_cast<uint2*>(tile + r * PITCH + c) = v;
     }
 }
@@ -463,8 +475,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
           dp[q] = p * (dp[q] - dv4[e]);
         }
       }
-      u32x4_t pf[2] = {pack_half(s, 0), pack_half(s, 1)};
-      u32x4_t dsf[2] = {pack_half(dp, 0), pack_half(dp, 1)};
+      u32x4_t pf[2] = {pack_half<true>(s, 0), pack_half<true>(s, 1)};
+      u32x4_t dsf[2] = {pack_half<true>(dp, 0), pack_half<true>(dp, 1)};
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -477,11 +489,11 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
     __syncthreads();
   }
   const int64_t r0 = sv.row0 + j0, r1 = sv.row0 + min(S, j0 + 128);
-  stage_out(smem, dk, scale, wave, lane);
+  stage_out<true>(smem, dk, scale, wave, lane);
   __syncthreads();
   copy_out(smem, dqkv, r0, r1, ld, kcol, tid);
   __syncthreads();
-  stage_out(smem, dv, 1.0f, wave, lane);
+  stage_out<true>(smem, dv, 1.0f, wave, lane);
   __syncthreads();
   copy_out(smem, dqkv, r0, r1, ld, vcol, tid);
 }

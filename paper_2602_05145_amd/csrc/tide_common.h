@@ -10,11 +10,13 @@ typedef uint16_t bf16_t;  // raw bfloat16 storage
 constexpr int kWave = 64;  // CDNA wavefront width
 
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  // round to nearest even (inputs on this path are finite)
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// fp32 -> bf16, round to nearest even: the hardware conversion of gfx950 (v_cvt_pk_bf16_f32)
+typedef __bf16 hw_bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values in one instruction: lo in bits 0..15, hi in bits 16..31
+__device__ __forceinline__ uint32_t f2bf2(float lo, float hi) {
+  const hw_bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
 }
 
 __device__ __forceinline__ float ldf(const float* p, size_t i) { return p[i]; }
@@ -46,7 +48,7 @@ __device__ __forceinline__ void st8(float* p, size_t i, const float (&v)[8]) {
 __device__ __forceinline__ void st8(bf16_t* p, size_t i, const float (&v)[8]) {
   uint32_t w[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) w[j] = (uint32_t)f2bf(v[2 * j]) | ((uint32_t)f2bf(v[2 * j + 1]) << 16);
+  for (int j = 0; j < 4; ++j) w[j] = f2bf2(v[2 * j], v[2 * j + 1]);
   *reinterpret_cast<uint4*>(p + i) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
