@@ -206,6 +206,18 @@ def main():
     loss = float(tr.loss.item())
     assert loss == loss and loss > 0, f"bad loss {loss}"
 
+    # what the matrix pipes sustain on this machine with nothing else going on (registers only): the practical ceiling
+    sink = torch.empty(2048 * 512, dtype=torch.float32, device=dev)
+    B.tide_mfma_probe(2048, 200, sink, tr._stream())
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    probe_flops = B.tide_mfma_probe(2048, 4000, sink, tr._stream())
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_probe_tflops = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    del sink
+
     ms = wall * 1e3 / args.steps
     # FLOPs.  "all positions" is the algorithmic count of the whole step (2 flop/MAC, causal attention at
     # S(S+1)/2, no projection input gradient, no logits recompute).  The library skips the three
@@ -225,7 +237,8 @@ def main():
                 "traffic": MEASURED_TRAFFIC_8B.get(dom["kernel"]) if cfg["name"] == "8b" else None,
                 "launches_per_step": dom["launches"] / args.steps,
                 "avg_launch_ms": dom["total_ms"] / dom["launches"],
-                "flops_per_launch": dom["flops"] / dom["launches"]}
+                "flops_per_launch": dom["flops"] / dom["launches"],
+                "measured_mfma_peak": mfma_probe_tflops, "frac_of_measured_mfma_peak": dom_tflops / mfma_probe_tflops}
     out = {
         "metric": "draft-training tokens/sec (fwd+bwd+AdamW) and % bf16 MFMA peak, 1 MI355X",
         "value": T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

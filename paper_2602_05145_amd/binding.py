@@ -99,11 +99,17 @@ _lib.tide_profile_stop.argtypes = [C.c_char_p, _sz]
 EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
             "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_draft_forward_packed",
     "tide_draft_train_step_packed",
+    "tide_mfma_probe",
     "tide_ingest_create", "tide_ingest_destroy", "tide_ingest_acquire", "tide_ingest_submit", "tide_ingest_wait",
     "tide_ingest_done", "tide_ingest_last_error", "tide_gemm_workspace_bytes", "tide_gemm",
             "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd",
             "tide_attention_fwd", "tide_attention_bwd", "tide_rope", "tide_profile_start",
             "tide_profile_stop")
+
+
+def lib():
+    """The loaded ctypes library (for calls that need raw arguments)."""
+    return _lib
 
 
 def tide_last_error() -> str:
@@ -248,6 +254,17 @@ def tide_profile_stop():
     buf = C.create_string_buffer(1 << 16)
     _check(_lib.tide_profile_stop(buf, len(buf)))
     return json.loads(buf.value.decode())
+
+
+_lib.tide_mfma_probe.restype = _i32
+_lib.tide_mfma_probe.argtypes = [_i32, _i32, _vp, C.POINTER(C.c_double), _vp]
+
+
+def tide_mfma_probe(blocks, iters, sink, stream):
+    """Enqueues the pure-MFMA probe; returns the flop count of the launch."""
+    fl = C.c_double(0.0)
+    _check(_lib.tide_mfma_probe(int(blocks), int(iters), _ptr(sink), C.byref(fl), stream))
+    return float(fl.value)
 
 
 # ---- signal ingest ring (include/tide_ingest.h) ----

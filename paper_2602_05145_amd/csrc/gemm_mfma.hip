@@ -594,4 +594,37 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   return launch_gemm_simple(a, s);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Pure-MFMA probe: what the matrix pipes deliver with nothing else going on (operands in registers, no
+// LDS, no memory).  8 waves per block, 8 independent accumulators per wave.  The measured rate is the
+// practical ceiling for the GEMM above at the clock the chip sustains under MFMA load.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void mfma_probe_kernel(float* __restrict__ sink, int iters) {
+  const int lane = threadIdx.x & 63;
+  // 2^-4 everywhere except a lane-dependent sign: keeps the products representable and the data non-trivial
+  const uint32_t w = (lane & 1) ? 0xBD803D80u : 0x3D803D80u;   // two bf16 values of +-2^-4
+  const u32x4_t a = {w, w, w, w}, b = {0x3D803D80u, 0x3D803D80u, w, w};
+  f32x16_t acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[j][q] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), acc[j], 0, 0, 0);
+  }
+  float v = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v += acc[j][q];
+  sink[(size_t)blockIdx.x * 512 + threadIdx.x] = v;
+}
+
+hipError_t launch_mfma_probe(int blocks, int iters, float* sink, hipStream_t s) {
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)blocks), dim3(512), 0, s, sink, iters);
+  return hipGetLastError();
+}
+
 }  // namespace tide

@@ -115,4 +115,7 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 
+// pure-MFMA rate probe: blocks x 8 waves x iters x 8 MFMAs of 2*32*32*16 flop; sink holds blocks*512 floats
+hipError_t launch_mfma_probe(int blocks, int iters, float* sink, hipStream_t s);
+
 }  // namespace tide

@@ -600,6 +600,14 @@ void prof_end(hipStream_t s) {
 
 extern "C" {
 
+int tide_mfma_probe(int32_t blocks, int32_t iters, float* sink, double* flops_out, void* stream) {
+  if (!sink) return fail(TIDE_ERR_NULL, "sink is NULL");
+  if (blocks < 1 || blocks > (1 << 20) || iters < 1 || iters > (1 << 24)) return fail(TIDE_ERR_CONFIG, "blocks must be in [1, 2^20] and iters in [1, 2^24]");
+  if (flops_out) *flops_out = (double)blocks * 8.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+  TIDE_HIP(launch_mfma_probe(blocks, iters, sink, (hipStream_t)stream), "mfma probe");
+  return TIDE_OK;
+}
+
 int tide_profile_start(void) {
   std::lock_guard<std::mutex> lk(g_prof.mu);
   for (auto& r : g_prof.recs) { if (r.e0) g_prof.pool.push_back(r.e0); if (r.e1) g_prof.pool.push_back(r.e1); }
