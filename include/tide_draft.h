@@ -184,7 +184,11 @@ const char *tide_last_error(void);
  * "yhat", "lse", "dyhat", "dx2", "dx1", "dx0", "dqkv", ...; activations have the
  * config's dtype, "lse"/"r1"/"r2"/"r3" are float); "lm_rows" returns the number
  * of rows per logits block instead.  -1 if the name or config is unknown.  After
- * a training step "gt"/"u" hold their gradients.  For tests and profiling. */
+ * a training step "gt"/"u" hold their gradients.  For tests and profiling.  *
+ * "status" names a device int32 that every forward / eval / train call rewrites: 0 when all is well, else
+ * bit 0 (value 1) = the loss came out NaN or infinite, bit 1 (value 2) = packed batch whose cu_seqlens is not
+ * ascending inside [0, batch*seq] or holds a sequence longer than max_seqlen (the kernels clamp such offsets
+ * so that no access leaves the buffers; the numbers are then meaningless).  Read it after synchronising. */
 int64_t tide_draft_workspace_offset(const tide_draft_config *cfg, const char *name);
 
 /* ---- Building blocks, exported for per-kernel parity tests and profiling ----

@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
   const int nqb = (Smax + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;  // heavy (late) query blocks first
   const int h = blockIdx.y, b = blockIdx.z;
-  const SeqView sv = seq_view(cu, b, Smax);
+  const SeqView sv = seq_view(cu, b, Smax, T);
   const int S = sv.len;
   const int G = nh / nkv, kh = h / G;
   const int ld = (nh + 2 * nkv) * D;
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
   const int nqb = (Smax + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
-  const SeqView sv = seq_view(cu, b, Smax);
+  const SeqView sv = seq_view(cu, b, Smax, T);
   const int S = sv.len;
   const int G = nh / nkv, kh = h / G;
   const int ld = (nh + 2 * nkv) * D, ldo = nh * D;
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int jb = blockIdx.x, kh = blockIdx.y, b = blockIdx.z;  // early key blocks are the heavy ones
-  const SeqView sv = seq_view(cu, b, Smax);
+  const SeqView sv = seq_view(cu, b, Smax, T);
   const int S = sv.len;
   const int G = nh / nkv;
   const int ld = (nh + 2 * nkv) * D, ldo = nh * D;

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(64) void attn_fwd_simple_kernel(const T* __restrict
   __shared__ float qs[kMaxDh];
   __shared__ float ps[64];
   const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const SeqView sv = seq_view(cu, b, Smax);
+  const SeqView sv = seq_view(cu, b, Smax, Trows);
   if (i >= sv.len) return;   // whole block: the sequence is shorter than the grid
   const size_t row0 = (size_t)sv.row0;
   const int lane = threadIdx.x;
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(64) void attn_delta_kernel(const T* __restrict__ ou
                                                         float* __restrict__ delta, int Smax, int nh, int dh,
                                                         const int* __restrict__ cu, int64_t Trows) {
   const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const SeqView sv = seq_view(cu, b, Smax);
+  const SeqView sv = seq_view(cu, b, Smax, Trows);
   if (i >= sv.len) return;
   const size_t row0 = (size_t)sv.row0;
   const size_t base = (row0 + i) * ((size_t)nh * dh) + (size_t)h * dh;
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(64) void attn_dq_simple_kernel(const T* __restrict_
   __shared__ float qs[kMaxDh], dos[kMaxDh];
   __shared__ float dss[64];
   const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const SeqView sv = seq_view(cu, b, Smax);
+  const SeqView sv = seq_view(cu, b, Smax, Trows);
   if (i >= sv.len) return;
   const size_t row0 = (size_t)sv.row0;
   const int lane = threadIdx.x;
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(64) void attn_dkv_simple_kernel(const T* __restrict
   __shared__ float ks[kMaxDh], vs[kMaxDh];
   __shared__ float pss[64], dss[64];
   const int j = blockIdx.x, kh = blockIdx.y, b = blockIdx.z;
-  const SeqView sv = seq_view(cu, b, Smax);
+  const SeqView sv = seq_view(cu, b, Smax, Trows);
   const int S = sv.len;
   if (j >= S) return;
   const size_t row0 = (size_t)sv.row0;

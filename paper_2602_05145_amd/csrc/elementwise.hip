@@ -20,11 +20,30 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(const int32_t* __restri
                                                          int select_all, float* __restrict__ scal,
                                                          int* __restrict__ cnt, int32_t* __restrict__ kept_idx,
                                                          int32_t* __restrict__ row_pos,
-                                                         const int* __restrict__ cu, int nseq,
-                                                         uint8_t* __restrict__ mask_eff) {
+                                                         const int* __restrict__ cu, int nseq, int max_len,
+                                                         uint8_t* __restrict__ mask_eff, int* __restrict__ status) {
   __shared__ int wsum_sel[16], wsum_keep[16];
+  __shared__ int bad_cu;
   // packed batches: only rows inside [cu[0], cu[nseq]) belong to a sequence; the rest is padding
-  const int64_t v0 = cu ? cu[0] : 0, v1 = cu ? min((int64_t)cu[nseq], T) : T;
+  const int64_t v0 = cu ? min(max((int64_t)cu[0], (int64_t)0), T) : 0;
+  const int64_t v1 = cu ? min(max((int64_t)cu[nseq], v0), T) : T;
+  // the offsets live on the device: check them here and report through the status word (bit 1)
+  if (threadIdx.x == 0) bad_cu = 0;
+  __syncthreads();
+  if (cu) {
+    int bad = 0;
+    for (int i = threadIdx.x; i <= nseq; i += 1024) {
+      const int c = cu[i];
+      if (c < 0 || c > T) bad = 1;
+      if (i < nseq) {
+        const int n = cu[i + 1] - c;
+        if (n < 0 || n > max_len) bad = 1;
+      }
+    }
+    if (bad) bad_cu = 1;   // benign race: every writer stores 1
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) *status = bad_cu ? kStatusBadSeqlens : 0;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int64_t per = (T + 1023) / 1024;
   const int64_t t0 = (int64_t)tid * per, t1 = min(T, t0 + per);
@@ -78,9 +97,9 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(const int32_t* __restri
 
 hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
                             float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, const int* cu, int nseq,
-                            uint8_t* mask_eff, hipStream_t s) {
+                            int max_len, uint8_t* mask_eff, int* status, hipStream_t s) {
   ProfScope ps("plan_rows", 0, 14.0 * (double)T, s);
-  hipLaunchKernelGGL(plan_rows_kernel, dim3(1), dim3(1024), 0, s, tokens, mask, T, V, select_all, scal, cnt, kept_idx, row_pos, cu, nseq, mask_eff);
+  hipLaunchKernelGGL(plan_rows_kernel, dim3(1), dim3(1024), 0, s, tokens, mask, T, V, select_all, scal, cnt, kept_idx, row_pos, cu, nseq, max_len, mask_eff, status);
   return hipGetLastError();
 }
 
@@ -89,7 +108,7 @@ hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t 
 // that zeroes the rows no sequence owns (attention writes only rows of sequences, and everything that is
 // later contracted over all T rows must be finite there).
 // ----------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void seq_pos_kernel(const int* __restrict__ cu, int nseq, int64_t T,
+__global__ __launch_bounds__(256) void seq_pos_kernel(const int* __restrict__ cu, int nseq, int64_t T, int max_len,
                                                       int32_t* __restrict__ pos) {
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= T) return;
@@ -102,12 +121,12 @@ __global__ __launch_bounds__(256) void seq_pos_kernel(const int* __restrict__ cu
     }
     p = (int)(t - cu[lo]);
   }
-  pos[t] = p;
+  pos[t] = min(max(p, 0), max_len - 1);   // inside the RoPE table whatever the offsets hold
 }
 
-hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int32_t* pos, hipStream_t s) {
+hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int max_len, int32_t* pos, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  hipLaunchKernelGGL(seq_pos_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, cu, nseq, T, pos);
+  hipLaunchKernelGGL(seq_pos_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, cu, nseq, T, max_len, pos);
   return hipGetLastError();
 }
 
@@ -727,7 +746,7 @@ __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restri
                                                            const int* __restrict__ cnt,
                                                            const float* __restrict__ scal,
                                                            float* __restrict__ loss_out,
-                                                           float* __restrict__ acc_out) {
+                                                           float* __restrict__ acc_out, int* __restrict__ status) {
   __shared__ float red[32];
   const int n = *cnt;
   float a = 0.f, h = 0.f;
@@ -736,7 +755,11 @@ __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restri
     if (hit_rows) h += hit_rows[i];
   }
   const float tot = block_sum(a, red);
-  if (threadIdx.x == 0) *loss_out = tot * scal[1];
+  if (threadIdx.x == 0) {
+    const float loss = tot * scal[1];
+    *loss_out = loss;
+    if (!(fabsf(loss) <= 3.0e38f)) *status |= kStatusLossNotFinite;   // NaN or infinity (single thread: no race)
+  }
   if (hit_rows && acc_out) {
     const float hits = block_sum(h, red);
     if (threadIdx.x == 0) *acc_out = hits * scal[1];
@@ -744,8 +767,8 @@ __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restri
 }
 
 hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, const int* cnt, const float* scal,
-                              float* loss_out, float* acc_out, hipStream_t s) {
-  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, hit_rows, cnt, scal, loss_out, acc_out);
+                              float* loss_out, float* acc_out, int* status, hipStream_t s) {
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, hit_rows, cnt, scal, loss_out, acc_out, status);
   return hipGetLastError();
 }
 

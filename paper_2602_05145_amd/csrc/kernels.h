@@ -44,10 +44,10 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);  // picks the MFMA pat
 // kept_idx[0..cnt[0]) lists them in ascending order, row_pos[t] is the position of row t in that list or -1.
 hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
                             float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, const int* cu, int nseq,
-                            uint8_t* mask_eff, hipStream_t s);
+                            int max_len, uint8_t* mask_eff, int* status, hipStream_t s);
 // packed batches (cu = device offsets of nseq sequences): position of each row in its sequence, and zeroing
 // of the rows of a [T, row_bytes] array that no sequence owns
-hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int32_t* pos, hipStream_t s);
+hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int max_len, int32_t* pos, hipStream_t s);
 hipError_t launch_zero_padding_rows(void* p, const int* cu, int nseq, int64_t T, int64_t row_bytes, hipStream_t s);
 // dst[i] = src[kept_idx[i]] for i < *cnt (rows of width d), same for tokens and mask
 hipError_t launch_gather_rows(int64_t T, int d, const void* src, const int32_t* tokens, const uint8_t* mask,
@@ -83,7 +83,7 @@ hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t
                         hipStream_t s);
 // loss = scal[1] * sum of loss_rows[0 .. *cnt); optionally accuracy = scal[1] * sum of hit_rows[0 .. *cnt)
 hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, const int* cnt, const float* scal,
-                              float* loss_out, float* acc_out, hipStream_t s);
+                              float* loss_out, float* acc_out, int* status, hipStream_t s);
 
 struct AdamTensor { void* p; const float* g; float* m; float* v; float* master; int64_t n; };
 struct AdamArgs {
@@ -95,6 +95,10 @@ struct AdamArgs {
 hipError_t launch_adamw(const AdamArgs& a, hipStream_t s);
 
 // ---- attention_simple.hip / attention_mfma.hip ----------------------------------------------
+// bits of the device status word of a step (written by plan_rows, OR-ed by loss_reduce)
+constexpr int kStatusLossNotFinite = 1;   // the loss came out NaN or infinite
+constexpr int kStatusBadSeqlens = 2;      // packed batch: cu_seqlens not ascending inside [0, T] or a sequence longer than max_seqlen
+
 struct AttnArgs {
   int B, S, nh, nkv, dh;
   const void* qkv; void* out; float* lse;           // forward

@@ -82,10 +82,14 @@ struct SeqView {
   int64_t row0;   // first row of the sequence in the [T, ...] activations
   int len;        // its length
 };
-__device__ __forceinline__ SeqView seq_view(const int* cu, int b, int Smax) {
+// Packed: the offsets come from device memory the library cannot check on the host, so they are clamped
+// here: whatever they hold, the view stays inside the T rows and is at most Smax long (no access can
+// leave the buffers; a malformed list only gives wrong numbers, and the row plan raises a status bit).
+__device__ __forceinline__ SeqView seq_view(const int* cu, int b, int Smax, int64_t T) {
   if (cu) {
-    const int s0 = cu[b];
-    return SeqView{(int64_t)s0, cu[b + 1] - s0};
+    const int64_t s0 = min(max((int64_t)cu[b], (int64_t)0), T);
+    const int64_t s1 = min(max((int64_t)cu[b + 1], s0), T);
+    return SeqView{s0, (int)min(s1 - s0, (int64_t)Smax)};
   }
   return SeqView{(int64_t)b * Smax, Smax};
 }

@@ -69,7 +69,7 @@ struct Plan {
   int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows;
   size_t es;  // activation element size
   // offsets (bytes)
-  size_t scal, cnt, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, yhat_c, dyhat_c, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
+  size_t scal, cnt, status, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, yhat_c, dyhat_c, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
   size_t fwd_end;
   size_t dyhat, dx2, dx1, dx0, dh, dbn, dA, dqkv, da, delta, dg_partial;
   size_t total;
@@ -108,6 +108,7 @@ Plan make_plan(const tide_draft_config* c) {
   Bump b;
   p.scal = b.take(64);
   p.cnt = b.take(64);
+  p.status = b.take(64);
   p.kept_idx = b.take(T * 4);
   p.row_pos = b.take(T * 4);
   p.tokens_c = b.take(T * 4);
@@ -224,8 +225,8 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
   const int dt = c->dtype;
   const int64_t T = p.T;
   float* scal = (float*)(ws + p.scal);
-  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), q.cu, q.n, (uint8_t*)(ws + p.mask_eff), s), "plan_rows");
-  if (q.cu) TIDE_HIP(launch_seq_pos(q.cu, q.n, T, (int32_t*)(ws + p.seq_pos), s), "sequence positions");
+  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), q.cu, q.n, q.max_len, (uint8_t*)(ws + p.mask_eff), (int*)(ws + p.status), s), "plan_rows");
+  if (q.cu) TIDE_HIP(launch_seq_pos(q.cu, q.n, T, q.max_len, (int32_t*)(ws + p.seq_pos), s), "sequence positions");
   // x0 = Hcat W_fc^T
   TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.x0, p.d, dt, dt), s), "gemm fc");
   TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x0, P->g1, c->rms_eps, ws + p.a, (float*)(ws + p.r1), dt, s), "rmsnorm1");
@@ -304,7 +305,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
       TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
     }
   }
-  TIDE_HIP(launch_loss_reduce(loss_rows, hit_rows, cnt, scal, loss_out, acc_out, s), "loss reduce");
+  TIDE_HIP(launch_loss_reduce(loss_rows, hit_rows, cnt, scal, loss_out, acc_out, (int*)(ws + p.status), s), "loss reduce");
   if (train)   // back to one row per position (zero where no loss is taken)
     TIDE_HIP(launch_scatter_rows(p.T, (int)p.d, ws + p.dyhat_c, (const int32_t*)(ws + p.row_pos), ws + p.dyhat, dt, s), "scatter rows");
   return TIDE_OK;
@@ -326,7 +327,7 @@ int64_t tide_draft_workspace_offset(const tide_draft_config* cfg, const char* na
   if (!check_config(cfg) || !name) return -1;
   const Plan p = make_plan(cfg);
   struct { const char* n; size_t o; } tab[] = {
-      {"scal", p.scal}, {"x0", p.x0}, {"r1", p.r1}, {"a", p.a}, {"qkv", p.qkv}, {"attn_lse", p.attn_lse},
+      {"scal", p.scal}, {"status", p.status}, {"x0", p.x0}, {"r1", p.r1}, {"a", p.a}, {"qkv", p.qkv}, {"attn_lse", p.attn_lse},
       {"A", p.A}, {"x1", p.x1}, {"r2", p.r2}, {"bn", p.bn}, {"gt", p.gt}, {"u", p.u}, {"h", p.h},
       {"x2", p.x2}, {"r3", p.r3}, {"yhat", p.yhat}, {"lse", p.lse}, {"loss_rows", p.loss_rows}, {"z", p.z},
       {"dyhat", p.dyhat}, {"yhat_c", p.yhat_c}, {"dyhat_c", p.dyhat_c}, {"cnt", p.cnt}, {"kept_idx", p.kept_idx}, {"dx2", p.dx2}, {"dx1", p.dx1}, {"dx0", p.dx0}, {"dh", p.dh}, {"dbn", p.dbn},

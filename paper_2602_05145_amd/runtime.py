@@ -103,6 +103,11 @@ class DraftTrainer:
                                 self.mask, lr, self.loss, self.workspace, self.ws_bytes, self._stream())
         return self.loss
 
+    def status(self):
+        """Device status word of the last call (0 = fine, 1 = loss not finite, 2 = malformed cu_seqlens); synchronises."""
+        off = B.tide_draft_workspace_offset(self.ccfg, "status")
+        return int(self.workspace[off:off + 4].view(torch.int32).item())
+
     @property
     def step(self):
         return int(self.c_adam.step)

@@ -113,3 +113,34 @@ def test_checkpoint_resume():
     for k in O.PARAM_NAMES:
         assert torch.equal(c.params[k], a.params[k]), k
         assert torch.equal(c.m[k], a.m[k]) and torch.equal(c.v[k], a.v[k]) and torch.equal(c.master[k], a.master[k]), k
+
+
+def test_status_word_flags_malformed_offsets_and_non_finite_loss():
+    """What the host cannot check is checked on the device and reported; malformed offsets are clamped so that
+    every access stays inside the buffers (the results are then meaningless, but nothing faults)."""
+    from paper_2602_05145_amd import runtime
+    cfg = W.get_config("small", batch=1, seq=400, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128,
+                       ffn=256, vocab=512)
+    wl = W.make_workload(cfg)
+    tr = runtime.trainer_from_workload(cfg, wl)
+    tr.set_packed([0, 130, 131, 390])
+    tr.forward_packed()
+    sync()
+    assert tr.status() == 0
+    for bad in ([0, 200, 100, 390], [-5, 100, 390], [0, 100, 500], [0, 10, 390]):
+        tr.set_packed(bad, max_seqlen=260)           # the last list is ascending but holds a 380-row sequence
+        tr.forward_packed()
+        sync()
+        assert tr.status() == 2, bad
+    tr.set_packed([0, 130, 131, 390])
+    tr.forward_packed()
+    sync()
+    assert tr.status() == 0                          # rewritten by every call
+    # fixed layout: a NaN in the captured states reaches the loss and raises bit 0
+    tr.forward()
+    sync()
+    assert tr.status() == 0
+    tr.hidden[0, 5, 7] = float("nan")
+    tr.forward()
+    sync()
+    assert tr.status() == 1 and not np.isfinite(float(tr.loss.item()))
