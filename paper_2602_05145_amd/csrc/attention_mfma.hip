@@ -18,8 +18,12 @@
 // Tiles.  Forward and dQ: one block = 128 queries of one head (4 waves x 32 queries, Q in registers; capped
 // at 256 VGPRs so that two blocks share a CU and one block's softmax overlaps the other's MFMAs),
 // K/V streamed in 64-key tiles, double buffered through LDS.  dK/dV: one block = 128 keys of one kv
-// head (4 waves x 32 keys, K and V in registers), Q/dO streamed in 32-query tiles for each of the G
+// head (4 waves x 32 keys, K [and V] in registers), Q/dO streamed in 32-query tiles for each of the G
 // query heads of the group, so dK/dV are summed over the group in registers: no atomics, deterministic.
+// dV and dK are two launches of one template: a fused pass needs 350 registers (K, V fragments and two
+// 32x128 accumulators), i.e. one block per CU with nothing to hide the exponentials behind; the two
+// halves need 162 and 222, run 3 and 2 blocks per CU, and together take 0.7x the fused time although
+// S = Q K^T is computed twice.
 // Causality: tiles entirely above the diagonal are never loaded; heavy blocks are scheduled first.
 #include "kernels.h"
 #include "prof.h"
@@ -76,22 +80,12 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return f2bf2(lo, hi);
 }
 
-// the same rounding (nearest even) in integer arithmetic: the dK/dV kernel keeps more values live than it has
-// registers, and there the packed hardware conversion measured 21 % slower (its operands stay live longer)
-__device__ __forceinline__ uint32_t pack2_int(float lo, float hi) {
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7FFFu + ((a >> 16) & 1u);
-  b += 0x7FFFu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xFFFF0000u);
-}
-
 // registers q0..q0+7 of a 32x32 accumulator -> the 8-value B operand of the next MFMA
-template <bool INT_ROUND = false>
 __device__ __forceinline__ u32x4_t pack_half(const f32x16_t& v, int half) {
   u32x4_t r;
 #pragma unroll
   for (int w = 0; w < 4; ++w)
-    r[w] = INT_ROUND ? pack2_int(v[half * 8 + 2 * w], v[half * 8 + 2 * w + 1]) : pack2(v[half * 8 + 2 * w], v[half * 8 + 2 * w + 1]);
+    r[w] = pack2(v[half * 8 + 2 * w], v[half * 8 + 2 * w + 1]);
   return r;
 }
 
@@ -123,7 +117,6 @@ struct TileLoader {
 
 // Write a wave's 32 x 128 result, held transposed in 4 accumulators (acc[ct] = rows ct*32.., column =
 // lane % 32 = the wave-local output row), into an LDS tile [128][PITCH] at rows wave*32.. as bf16.
-template <bool INT_ROUND = false>
 __device__ __forceinline__ void stage_out(bf16_t* tile, const f32x16_t (&acc)[4], float mul, int wave, int lane) {
   const int g = lane >> 5, r = wave * 32 + (lane & 31);
 #pragma unroll
@@ -132,8 +125,8 @@ __device__ __forceinline__ void stage_out(bf16_t* tile, const f32x16_t (&acc)[4]
     for (int qq = 0; qq < 4; ++qq) {
       const int c = ct * 32 + 8 * qq + 4 * g;
       uint2 v;
-      v.x = INT_ROUND ? pack2_int(acc[ct][qq * 4 + 0] * mul, acc[ct][qq * 4 + 1] * mul) : pack2(acc[ct][qq * 4 + 0] * mul, acc[ct][qq * 4 + 1] * mul);
-      v.y = INT_ROUND ? pack2_int(acc[ct][qq * 4 + 2] * mul, acc[ct][qq * 4 + 3] * mul) : pack2(acc[ct][qq * 4 + 2] * mul, acc[ct][qq * 4 + 3] * mul);
+      v.x = pack2(acc[ct][qq * 4 + 0] * mul, acc[ct][qq * 4 + 1] * mul);
+      v.y = pack2(acc[ct][qq * 4 + 2] * mul, acc[ct][qq * 4 + 3] * mul);
       *reinterpret_cast<uint2*>(tile + r * PITCH + c) = v;
     }
 }
@@ -384,7 +377,11 @@ constexpr int Q_TILE = BI * PITCH;              // elements
 constexpr int DKV_STAGE = 2 * Q_TILE + 2 * 64;  // Q tile, dO tile, then lse[32] and delta[32] as floats
 }  // namespace
 
-__global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+// One gradient per pass (WHICH = 0: dV, 1: dK).  Half the accumulators and, for dV, half the operand
+// registers of the fused kernel: the pass fits 256 VGPRs, two blocks share a CU, and one block's
+// exponentials overlap the other's MFMAs.  The price is that S = Q K^T is computed in both passes.
+template <int WHICH>
+__global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16_t* __restrict__ dqkv, int Smax, int nh, int nkv,
                                                             const int* __restrict__ cu, int64_t T) {
@@ -404,17 +401,18 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   const float scale = 1.0f / sqrtf((float)D);
   const float c = kLog2e * scale;
 
-  u32x4_t kf[8], vf[8];
+  constexpr bool DK = WHICH == 1;
+  u32x4_t kf[8], vf[DK ? 8 : 1];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
     kf[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)jk * (uint32_t)ld + (uint32_t)(kcol + kk * 16 + g * 8)) * 2u, 0, 0));
-    vf[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)jk * (uint32_t)ld + (uint32_t)(vcol + kk * 16 + g * 8)) * 2u, 0, 0));
+    if constexpr (DK) vf[kk] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)jk * (uint32_t)ld + (uint32_t)(vcol + kk * 16 + g * 8)) * 2u, 0, 0));
   }
-  f32x16_t dk[4], dv[4];
+  f32x16_t dacc[4];   // dK or dV of this wave's 32 keys
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-    for (int q = 0; q < 16; ++q) { dk[ct][q] = 0.f; dv[ct][q] = 0.f; }
+    for (int q = 0; q < 16; ++q) dacc[ct][q] = 0.f;
 
   const int i_begin = (j0 / BI) * BI;                  // first query tile that can see a key of this block
   const int nit = (S - i_begin + BI - 1) / BI;         // query tiles per head
@@ -457,7 +455,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         s = mfma(frag(Qt, lr, kk * 16 + g * 8), kf[kk], s);
-        dp = mfma(frag(dOt, lr, kk * 16 + g * 8), vf[kk], dp);
+        if constexpr (DK) dp = mfma(frag(dOt, lr, kk * 16 + g * 8), vf[kk], dp);
       }
       const bool diag = i0 < jw + 32;  // some (query, key) pair of the tile is above the diagonal
 #pragma unroll
@@ -471,32 +469,25 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
           const int i = i0 + 8 * qq + 4 * g + e;
           float p = __builtin_amdgcn_exp2f(s[q] * c - lv4[e] * kLog2e);
           if (i >= S || (diag && i < jk)) p = 0.f;
-          s[q] = p;
-          dp[q] = p * (dp[q] - dv4[e]);
+          s[q] = DK ? p * (dp[q] - dv4[e]) : p;   // dS for the dK pass, P for the dV pass
         }
       }
-      u32x4_t pf[2] = {pack_half<true>(s, 0), pack_half<true>(s, 1)};
-      u32x4_t dsf[2] = {pack_half<true>(dp, 0), pack_half<true>(dp, 1)};
+      const u32x4_t pf[2] = {pack_half(s, 0), pack_half(s, 1)};
+      const bf16_t* Xt = DK ? Qt : dOt;   // dK += dS^T Q, dV += P^T dO
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-          dv[ct] = mfma(frag_tr(dOt, ks * 16, ct * 32, lane), pf[ks], dv[ct]);
-          dk[ct] = mfma(frag_tr(Qt, ks * 16, ct * 32, lane), dsf[ks], dk[ct]);
-        }
+        for (int ks = 0; ks < 2; ++ks) dacc[ct] = mfma(frag_tr(Xt, ks * 16, ct * 32, lane), pf[ks], dacc[ct]);
     }
     if (u + 1 < ntiles) sstore(st ^ 1);
     __syncthreads();
   }
   const int64_t r0 = sv.row0 + j0, r1 = sv.row0 + min(S, j0 + 128);
-  stage_out<true>(smem, dk, scale, wave, lane);
+  stage_out(smem, dacc, DK ? scale : 1.0f, wave, lane);
   __syncthreads();
-  copy_out(smem, dqkv, r0, r1, ld, kcol, tid);
-  __syncthreads();
-  stage_out<true>(smem, dv, 1.0f, wave, lane);
-  __syncthreads();
-  copy_out(smem, dqkv, r0, r1, ld, vcol, tid);
+  copy_out(smem, dqkv, r0, r1, ld, DK ? kcol : vcol, tid);
 }
+
 
 // ------------------------------------------------------------------------------------------------
 bool attn_mfma_supported(const AttnArgs& a) {
@@ -533,12 +524,10 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
-  static bool done_q = false, done_kv = false;
+  static bool done_q = false;
   hipError_t e = launch_attn_delta(a, s);
   if (e != hipSuccess) return e;
   e = set_smem((const void*)attn_dq_mfma_kernel, kFwdSmem, done_q);
-  if (e != hipSuccess) return e;
-  e = set_smem((const void*)attn_dkv_mfma_kernel, kDkvSmem, done_kv);
   if (e != hipSuccess) return e;
   dim3 gq((a.S + BQ - 1) / BQ, a.nh, a.B), gkv((a.S + 127) / 128, a.nkv, a.B);
   const double pairs = (double)a.B * a.nh * D * (double)a.S * (a.S + 1) / 2.0;  // (query, key, channel) triples
@@ -548,8 +537,14 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  ProfScope ps("attn_dkv_mfma", 8.0 * pairs, 0, s);    // S, dP, dV and dK products
-  hipLaunchKernelGGL(attn_dkv_mfma_kernel, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
+  static bool done_v = false, done_k = false;
+  e = set_smem((const void*)attn_dkv_mfma_kernel<0>, kDkvSmem, done_v);
+  if (e != hipSuccess) return e;
+  e = set_smem((const void*)attn_dkv_mfma_kernel<1>, kDkvSmem, done_k);
+  if (e != hipSuccess) return e;
+  ProfScope ps("attn_dkv_mfma", 10.0 * pairs, 0, s);   // dV pass: S, dV; dK pass: S, dP, dK
+  hipLaunchKernelGGL(attn_dkv_mfma_kernel<0>, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
+  hipLaunchKernelGGL(attn_dkv_mfma_kernel<1>, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
   return hipGetLastError();
 }
 
