@@ -141,6 +141,7 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    import numpy as np
     import torch
     from paper_2602_05145_amd import binding as B, workloads as W
 
@@ -220,12 +221,15 @@ def main():
 
     ms = wall * 1e3 / args.steps
     # FLOPs.  "all positions" is the algorithmic count of the whole step (2 flop/MAC, causal attention at
-    # S(S+1)/2, no projection input gradient, no logits recompute).  The library skips the three
-    # vocabulary-sized products for positions that carry no loss (they contribute exactly zero), so the
-    # "executed" count removes 6*d*V flop for each of them; MFU is quoted on the executed count.
+    # S(S+1)/2, no projection input gradient, no logits recompute).  A position that carries no loss
+    # matters only through its key and value, so the library runs everything after the attention (output
+    # projection, MLP, LM head: forward and backward) on the loss positions alone; the "executed" count
+    # removes those products, 6 flop per weight, for every other position.  MFU is quoted on the executed count.
     flops_all = W.flops_per_step(cfg)
     n_loss = int(((tr.mask != 0) & (tr.tokens >= 0) & (tr.tokens < cfg["vocab"])).sum().item())
-    flops = flops_all - 6.0 * cfg["hidden"] * cfg["vocab"] * (T - n_loss)
+    ps = {k: int(np.prod(v)) for k, v in W.param_shapes(cfg).items()}
+    after_attention = ps["w_o"] + ps["w_gate"] + ps["w_up"] + ps["w_down"] + ps["w_lm"]
+    flops = flops_all - 6.0 * after_attention * (T - n_loss)
     prof.sort(key=lambda r: -r["total_ms"])
     kernel_ms = sum(r["total_ms"] for r in prof)
     dom = max((r for r in prof if r["kernel"].startswith("gemm_mfma")), key=lambda r: r["total_ms"], default=None)

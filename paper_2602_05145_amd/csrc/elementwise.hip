@@ -9,11 +9,11 @@
 namespace tide {
 
 // ----------------------------------------------------------------------------------------------
-// Row plan of the LM head: N = max(1, #keep) with keep_t = mask_t != 0 and 0 <= token_t < V, and the
-// ascending list of rows the LM head processes (the kept rows; every row when select_all is set, which
-// the forward pass with arg-max output needs).  Rows that carry no loss contribute exactly nothing to the
-// loss or to any gradient, so the vocabulary-sized products skip them.  One block, fixed order:
-// deterministic.
+// Row plan: N = max(1, #keep) with keep_t = mask_t != 0 and 0 <= token_t < V, the ascending list of the
+// selected rows (the kept rows; every row when select_all is set, which the forward pass with arg-max
+// output needs) and its inverse row_pos (-1 for rows not selected).  A row that carries no loss reaches
+// the loss and the gradients only through its key and value, so everything after the attention runs on
+// the selected rows alone.  One block, fixed order: deterministic.
 // ----------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void plan_rows_kernel(const int32_t* __restrict__ tokens,
                                                          const uint8_t* __restrict__ mask, int64_t T, int V,
@@ -146,18 +146,13 @@ hipError_t launch_zero_padding_rows(void* p, const int* cu, int nseq, int64_t T,
   return hipGetLastError();
 }
 
+// Row compaction.  Everything after the attention (output projection, MLP, final norm, LM head) is only
+// needed for the rows the LM head processes: a row without loss influences the result through its key and
+// value alone.  gather copies those rows (kept_idx, ascending) of up to two arrays into dense arrays and
+// compacts labels and mask alongside; scatter is the inverse for gradients, writing zeros to the rows that
+// were not selected.  The number of selected rows lives on the device.
 template <typename T>
-__global__ __launch_bounds__(256) void gather_rows_kernel(const T* __restrict__ src, const int32_t* __restrict__ tokens,
-                                                          const uint8_t* __restrict__ mask,
-                                                          const int32_t* __restrict__ kept_idx,
-                                                          const int* __restrict__ cnt, T* __restrict__ dst,
-                                                          int32_t* __restrict__ tokens_c, uint8_t* __restrict__ mask_c,
-                                                          int d) {
-  const int i = blockIdx.x;
-  if (i >= *cnt) return;
-  const size_t r = (size_t)kept_idx[i];
-  const T* a = src + r * (size_t)d;
-  T* b = dst + (size_t)i * (size_t)d;
+__device__ __forceinline__ void copy_row(const T* a, T* b, int d) {
   if ((d & 7) == 0) {
     for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
       float v[8];
@@ -167,53 +162,71 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const T* __restrict__ 
   } else {
     for (int c = threadIdx.x; c < d; c += 256) b[c] = a[c];
   }
+}
+
+template <typename T>
+__device__ __forceinline__ void zero_row(T* b, int d) {
+  if ((d & 7) == 0) {
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) st8(b, c, v);
+  } else {
+    for (int c = threadIdx.x; c < d; c += 256) stf(b, c, 0.f);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const T* __restrict__ src0, T* __restrict__ dst0, int d0,
+                                                          const T* __restrict__ src1, T* __restrict__ dst1, int d1,
+                                                          const int32_t* __restrict__ tokens,
+                                                          const uint8_t* __restrict__ mask,
+                                                          const int32_t* __restrict__ kept_idx,
+                                                          const int* __restrict__ cnt,
+                                                          int32_t* __restrict__ tokens_c, uint8_t* __restrict__ mask_c) {
+  const int i = blockIdx.x;
+  if (i >= *cnt) return;
+  const size_t r = (size_t)kept_idx[i];
+  copy_row(src0 + r * (size_t)d0, dst0 + (size_t)i * (size_t)d0, d0);
+  if (src1) copy_row(src1 + r * (size_t)d1, dst1 + (size_t)i * (size_t)d1, d1);
   if (threadIdx.x == 0) {
     tokens_c[i] = tokens[r];
     mask_c[i] = mask[r];
   }
 }
 
-hipError_t launch_gather_rows(int64_t T, int d, const void* src, const int32_t* tokens, const uint8_t* mask,
-                              const int32_t* kept_idx, const int* cnt, void* dst, int32_t* tokens_c,
-                              uint8_t* mask_c, int dtype, hipStream_t s) {
+hipError_t launch_gather_rows(int64_t T, int d0, const void* src0, void* dst0, int d1, const void* src1, void* dst1,
+                              const int32_t* tokens, const uint8_t* mask, const int32_t* kept_idx, const int* cnt,
+                              int32_t* tokens_c, uint8_t* mask_c, int dtype, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  ProfScope ps("gather_rows", 0, 2.0 * (double)T * d * dtype_size(dtype), s);
+  ProfScope ps("gather_rows", 0, 2.0 * (double)T * (d0 + (src1 ? d1 : 0)) * dtype_size(dtype), s);
   prof_dynamic(cnt, 0, T);
   dim3 grid((unsigned)T), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(gather_rows_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)src, tokens, mask, kept_idx, cnt, (bf16_t*)dst, tokens_c, mask_c, d);
-  else hipLaunchKernelGGL(gather_rows_kernel<float>, grid, blk, 0, s, (const float*)src, tokens, mask, kept_idx, cnt, (float*)dst, tokens_c, mask_c, d);
+  if (dtype == kBF16) hipLaunchKernelGGL(gather_rows_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)src0, (bf16_t*)dst0, d0, (const bf16_t*)src1, (bf16_t*)dst1, d1, tokens, mask, kept_idx, cnt, tokens_c, mask_c);
+  else hipLaunchKernelGGL(gather_rows_kernel<float>, grid, blk, 0, s, (const float*)src0, (float*)dst0, d0, (const float*)src1, (float*)dst1, d1, tokens, mask, kept_idx, cnt, tokens_c, mask_c);
   return hipGetLastError();
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void scatter_rows_kernel(const T* __restrict__ src, const int32_t* __restrict__ row_pos,
-                                                           T* __restrict__ dst, int d) {
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const T* __restrict__ src0, T* __restrict__ dst0, int d0,
+                                                           const T* __restrict__ src1, T* __restrict__ dst1, int d1,
+                                                           const int32_t* __restrict__ row_pos) {
   const size_t t = blockIdx.x;
   const int p = row_pos[t];
-  T* b = dst + t * (size_t)d;
-  const T* a = src + (size_t)(p < 0 ? 0 : p) * (size_t)d;
-  if ((d & 7) == 0) {
-    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
-      float v[8];
-      if (p >= 0) ld8(a, c, v);
-      else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = 0.f;
-      }
-      st8(b, c, v);
-    }
+  if (p >= 0) {
+    copy_row(src0 + (size_t)p * (size_t)d0, dst0 + t * (size_t)d0, d0);
+    if (src1) copy_row(src1 + (size_t)p * (size_t)d1, dst1 + t * (size_t)d1, d1);
   } else {
-    for (int c = threadIdx.x; c < d; c += 256) stf(b, c, p >= 0 ? ldf(a, c) : 0.f);
+    zero_row(dst0 + t * (size_t)d0, d0);
+    if (src1) zero_row(dst1 + t * (size_t)d1, d1);
   }
 }
 
-hipError_t launch_scatter_rows(int64_t T, int d, const void* src, const int32_t* row_pos, void* dst, int dtype,
-                               hipStream_t s) {
+hipError_t launch_scatter_rows(int64_t T, int d0, const void* src0, void* dst0, int d1, const void* src1, void* dst1,
+                               const int32_t* row_pos, int dtype, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  ProfScope ps("scatter_rows", 0, 2.0 * (double)T * d * dtype_size(dtype), s);
+  ProfScope ps("scatter_rows", 0, 2.0 * (double)T * (d0 + (src1 ? d1 : 0)) * dtype_size(dtype), s);
   dim3 grid((unsigned)T), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(scatter_rows_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)src, row_pos, (bf16_t*)dst, d);
-  else hipLaunchKernelGGL(scatter_rows_kernel<float>, grid, blk, 0, s, (const float*)src, row_pos, (float*)dst, d);
+  if (dtype == kBF16) hipLaunchKernelGGL(scatter_rows_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)src0, (bf16_t*)dst0, d0, (const bf16_t*)src1, (bf16_t*)dst1, d1, row_pos);
+  else hipLaunchKernelGGL(scatter_rows_kernel<float>, grid, blk, 0, s, (const float*)src0, (float*)dst0, d0, (const float*)src1, (float*)dst1, d1, row_pos);
   return hipGetLastError();
 }
 
@@ -224,9 +237,10 @@ template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ x,
                                                           const T* __restrict__ g, float eps,
                                                           T* __restrict__ y, float* __restrict__ rstd,
-                                                          int d) {
+                                                          int d, const int* __restrict__ rows_dev) {
   __shared__ float red[32];
   const size_t row = blockIdx.x;
+  if (rows_dev && (int64_t)row >= (int64_t)*rows_dev) return;   // whole block, before any barrier
   const T* xr = x + row * (size_t)d;
   T* yr = y + row * (size_t)d;
   float ss = 0.f;
@@ -261,17 +275,18 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ 
 }
 
 hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g, float eps, void* y,
-                              float* rstd, int dtype, hipStream_t s) {
+                              float* rstd, int dtype, const int* rows_dev, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   ProfScope ps("rmsnorm_fwd", 0, (double)rows * d * 2.0 * dtype_size(dtype) + 4.0 * rows, s);
+  if (rows_dev) prof_dynamic(rows_dev, 0, rows);
   dim3 grid((unsigned)rows), blk(256);
   const bool vec = (d % 8) == 0;
   if (dtype == kBF16) {
-    if (vec) hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)x, (const bf16_t*)g, eps, (bf16_t*)y, rstd, d);
-    else hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)x, (const bf16_t*)g, eps, (bf16_t*)y, rstd, d);
+    if (vec) hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16_t, true>), grid, blk, 0, s, (const bf16_t*)x, (const bf16_t*)g, eps, (bf16_t*)y, rstd, d, rows_dev);
+    else hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16_t, false>), grid, blk, 0, s, (const bf16_t*)x, (const bf16_t*)g, eps, (bf16_t*)y, rstd, d, rows_dev);
   } else {
-    if (vec) hipLaunchKernelGGL((rmsnorm_fwd_kernel<float, true>), grid, blk, 0, s, (const float*)x, (const float*)g, eps, (float*)y, rstd, d);
-    else hipLaunchKernelGGL((rmsnorm_fwd_kernel<float, false>), grid, blk, 0, s, (const float*)x, (const float*)g, eps, (float*)y, rstd, d);
+    if (vec) hipLaunchKernelGGL((rmsnorm_fwd_kernel<float, true>), grid, blk, 0, s, (const float*)x, (const float*)g, eps, (float*)y, rstd, d, rows_dev);
+    else hipLaunchKernelGGL((rmsnorm_fwd_kernel<float, false>), grid, blk, 0, s, (const float*)x, (const float*)g, eps, (float*)y, rstd, d, rows_dev);
   }
   return hipGetLastError();
 }
@@ -291,8 +306,9 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
                                                           const float* __restrict__ rstd,
                                                           const T* __restrict__ res, T* __restrict__ dx,
                                                           float* __restrict__ dg_partial, int64_t rows,
-                                                          int d) {
+                                                          int d, const int* __restrict__ rows_dev) {
   __shared__ float red[32];
+  if (rows_dev) rows = min(rows, (int64_t)max(*rows_dev, 0));   // blocks past the end write zero partials
   constexpr int W = VEC ? 8 : 1;   // a thread owns NIT groups of W columns
   float acc[NIT][W];
 #pragma unroll
@@ -401,16 +417,17 @@ size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d) {
 
 hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x, const void* g,
                               const float* rstd, const void* res, void* dx, float* dg, float* dg_partial,
-                              int dtype, hipStream_t s) {
+                              int dtype, const int* rows_dev, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   const bool vec = (d % 8) == 0 && d <= 8192;
   if (!vec && d > 1024) return hipErrorInvalidValue;
   ProfScope ps("rmsnorm_bwd", 0, (double)rows * d * (res ? 4.0 : 3.0) * dtype_size(dtype) + 4.0 * rows, s);
+  if (rows_dev) prof_dynamic(rows_dev, 0, rows);
   const int64_t nblk = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
   dim3 grid((unsigned)nblk), blk(256);
   const int per = vec ? 8 * 256 : 256;            // columns covered by one pass of the block
   const int nit = (d + per - 1) / per;            // <= 4 by the limits above
-#define TIDE_RMS_BWD(T, V, N) hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, N>), grid, blk, 0, s, (const T*)dy, (const T*)x, (const T*)g, rstd, (const T*)res, (T*)dx, dg_partial, rows, d)
+#define TIDE_RMS_BWD(T, V, N) hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, N>), grid, blk, 0, s, (const T*)dy, (const T*)x, (const T*)g, rstd, (const T*)res, (T*)dx, dg_partial, rows, d, rows_dev)
 #define TIDE_RMS_BWD_N(T, V) do { if (nit <= 1) TIDE_RMS_BWD(T, V, 1); else if (nit == 2) TIDE_RMS_BWD(T, V, 2); else TIDE_RMS_BWD(T, V, 4); } while (0)
   if (dtype == kBF16) {
     if (vec) TIDE_RMS_BWD_N(bf16_t, true); else TIDE_RMS_BWD_N(bf16_t, false);
@@ -526,7 +543,9 @@ __device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + __ex
 
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T* __restrict__ gt, const T* __restrict__ u,
-                                                         T* __restrict__ h, int64_t n) {
+                                                         T* __restrict__ h, int64_t n, int64_t per_row,
+                                                         const int* __restrict__ rows_dev) {
+  if (rows_dev) n = min(n, (int64_t)max(*rows_dev, 0) * per_row);
   const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (i0 + 8 <= n) {
     float a[8], b[8], o[8];
@@ -545,8 +564,10 @@ __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T* __restrict__ g
 
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ dh, const T* gt, const T* u,
-                                                         T* dgt, T* du, int64_t n) {
+                                                         T* dgt, T* du, int64_t n, int64_t per_row,
+                                                         const int* __restrict__ rows_dev) {
   // dgt/du may alias gt/u: every element is read before it is written by the same thread
+  if (rows_dev) n = min(n, (int64_t)max(*rows_dev, 0) * per_row);
   const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (i0 + 8 <= n) {
     float a[8], b[8], c[8], o1[8], o2[8];
@@ -571,22 +592,28 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ d
   }
 }
 
-hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, hipStream_t s) {
+// n = rows * per_row elements; with rows_dev only the first *rows_dev rows are touched
+hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, int64_t per_row,
+                             const int* rows_dev, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  if (rows_dev && (per_row <= 0 || n % per_row)) return hipErrorInvalidValue;
   ProfScope ps("swiglu_fwd", 0, (double)n * 3.0 * dtype_size(dtype), s);
+  if (rows_dev) prof_dynamic(rows_dev, 0, n / per_row);
   dim3 grid((unsigned)((n + 2047) / 2048)), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)gt, (const bf16_t*)u, (bf16_t*)h, n);
-  else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, grid, blk, 0, s, (const float*)gt, (const float*)u, (float*)h, n);
+  if (dtype == kBF16) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)gt, (const bf16_t*)u, (bf16_t*)h, n, per_row, rows_dev);
+  else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, grid, blk, 0, s, (const float*)gt, (const float*)u, (float*)h, n, per_row, rows_dev);
   return hipGetLastError();
 }
 
 hipError_t launch_swiglu_bwd(int64_t n, const void* dh, const void* gt, const void* u, void* dgt, void* du,
-                             int dtype, hipStream_t s) {
+                             int dtype, int64_t per_row, const int* rows_dev, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  if (rows_dev && (per_row <= 0 || n % per_row)) return hipErrorInvalidValue;
   ProfScope ps("swiglu_bwd", 0, (double)n * 5.0 * dtype_size(dtype), s);
+  if (rows_dev) prof_dynamic(rows_dev, 0, n / per_row);
   dim3 grid((unsigned)((n + 2047) / 2048)), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)dh, (const bf16_t*)gt, (const bf16_t*)u, (bf16_t*)dgt, (bf16_t*)du, n);
-  else hipLaunchKernelGGL(swiglu_bwd_kernel<float>, grid, blk, 0, s, (const float*)dh, (const float*)gt, (const float*)u, (float*)dgt, (float*)du, n);
+  if (dtype == kBF16) hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)dh, (const bf16_t*)gt, (const bf16_t*)u, (bf16_t*)dgt, (bf16_t*)du, n, per_row, rows_dev);
+  else hipLaunchKernelGGL(swiglu_bwd_kernel<float>, grid, blk, 0, s, (const float*)dh, (const float*)gt, (const float*)u, (float*)dgt, (float*)du, n, per_row, rows_dev);
   return hipGetLastError();
 }
 

@@ -49,26 +49,30 @@ hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t 
 // of the rows of a [T, row_bytes] array that no sequence owns
 hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int max_len, int32_t* pos, hipStream_t s);
 hipError_t launch_zero_padding_rows(void* p, const int* cu, int nseq, int64_t T, int64_t row_bytes, hipStream_t s);
-// dst[i] = src[kept_idx[i]] for i < *cnt (rows of width d), same for tokens and mask
-hipError_t launch_gather_rows(int64_t T, int d, const void* src, const int32_t* tokens, const uint8_t* mask,
-                              const int32_t* kept_idx, const int* cnt, void* dst, int32_t* tokens_c,
-                              uint8_t* mask_c, int dtype, hipStream_t s);
-// dst[t] = row_pos[t] >= 0 ? src[row_pos[t]] : 0
-hipError_t launch_scatter_rows(int64_t T, int d, const void* src, const int32_t* row_pos, void* dst, int dtype,
-                               hipStream_t s);
+// dst0[i] = src0[kept_idx[i]] for i < *cnt (rows of width d0), likewise src1 -> dst1 (width d1; src1 may be
+// NULL), tokens and mask
+hipError_t launch_gather_rows(int64_t T, int d0, const void* src0, void* dst0, int d1, const void* src1, void* dst1,
+                              const int32_t* tokens, const uint8_t* mask, const int32_t* kept_idx, const int* cnt,
+                              int32_t* tokens_c, uint8_t* mask_c, int dtype, hipStream_t s);
+// dst0[t] = row_pos[t] >= 0 ? src0[row_pos[t]] : 0, likewise src1 -> dst1 (src1 may be NULL)
+hipError_t launch_scatter_rows(int64_t T, int d0, const void* src0, void* dst0, int d1, const void* src1, void* dst1,
+                               const int32_t* row_pos, int dtype, hipStream_t s);
+// rows_dev (optional, device): only the first min(rows, *rows_dev) rows are processed
 hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g, float eps, void* y,
-                              float* rstd, int dtype, hipStream_t s);
+                              float* rstd, int dtype, const int* rows_dev, hipStream_t s);
 size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d);
 hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x, const void* g,
                               const float* rstd, const void* res, void* dx, float* dg,
-                              float* dg_partial, int dtype, hipStream_t s);
+                              float* dg_partial, int dtype, const int* rows_dev, hipStream_t s);
 hipError_t launch_rope_table(int S, int dh, float theta, float* cs, hipStream_t s);  // cs [S, dh/2, 2]
 // row_pos (optional, device): position of every row in its sequence; NULL = row % S
 hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, void* qkv, int inverse,
                        int dtype, const int32_t* row_pos, hipStream_t s);
-hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, hipStream_t s);
+// n = rows * per_row elements; rows_dev (optional, device): only the first *rows_dev rows are processed
+hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, int64_t per_row,
+                             const int* rows_dev, hipStream_t s);
 hipError_t launch_swiglu_bwd(int64_t n, const void* dh, const void* gt, const void* u, void* dgt,
-                             void* du, int dtype, hipStream_t s);
+                             void* du, int dtype, int64_t per_row, const int* rows_dev, hipStream_t s);
 // z [rows, ldz]: per-row log-sum-exp, loss term keep*(lse - z[label]) and optional arg-max
 // rows is an upper bound; rows_dev/rows_off (optional) give the effective count clamp(*rows_dev - rows_off, 0, rows).
 // top1 (optional) is written through top1_idx: top1[top1_idx[row]] = arg-max of row; hit_rows (optional)

@@ -69,9 +69,9 @@ struct Plan {
   int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows;
   size_t es;  // activation element size
   // offsets (bytes)
-  size_t scal, cnt, status, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, yhat_c, dyhat_c, rope_cs, x0, r1, a, qkv, attn_lse, A, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
+  size_t scal, cnt, status, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, rope_cs, x0, r1, a, qkv, attn_lse, A, A_c, x0_c, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
   size_t fwd_end;
-  size_t dyhat, dx2, dx1, dx0, dh, dbn, dA, dqkv, da, delta, dg_partial;
+  size_t dyhat, dx2, dx1_c, dx1, dx0, dh, dbn, dA_c, dA, dqkv, da, delta, dg_partial;
   size_t total;
 };
 
@@ -122,6 +122,9 @@ Plan make_plan(const tide_draft_config* c) {
   p.qkv = b.take(T * p.nqkv * es);
   p.attn_lse = b.take((size_t)c->batch * c->n_heads * c->seq * 4);
   p.A = b.take(T * p.nq * es);
+  // from here to the LM head the arrays hold the selected rows only, densely (at most T of them)
+  p.A_c = b.take(T * p.nq * es);
+  p.x0_c = b.take(T * p.d * es);
   p.x1 = b.take(T * p.d * es);
   p.r2 = b.take(T * 4);
   p.bn = b.take(T * p.d * es);
@@ -131,19 +134,19 @@ Plan make_plan(const tide_draft_config* c) {
   p.x2 = b.take(T * p.d * es);
   p.r3 = b.take(T * 4);
   p.yhat = b.take(T * p.d * es);
-  p.yhat_c = b.take(T * p.d * es);
   p.lse = b.take(T * 4);
   p.loss_rows = b.take(T * 4);
   p.hit_rows = b.take(T * 4);
   p.z = b.take((size_t)p.lm_rows * p.ldz * es);
   p.fwd_end = b.off;
   p.dyhat = b.take(T * p.d * es);
-  p.dyhat_c = b.take(T * p.d * es);
   p.dx2 = b.take(T * p.d * es);
+  p.dx1_c = b.take(T * p.d * es);
   p.dx1 = b.take(T * p.d * es);
   p.dx0 = b.take(T * p.d * es);
   p.dh = b.take(T * p.F * es);
   p.dbn = b.take(T * p.d * es);
+  p.dA_c = b.take(T * p.nq * es);
   p.dA = b.take(T * p.nq * es);
   p.dqkv = b.take(T * p.nqkv * es);
   p.da = b.take(T * p.d * es);
@@ -229,7 +232,7 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
   if (q.cu) TIDE_HIP(launch_seq_pos(q.cu, q.n, T, q.max_len, (int32_t*)(ws + p.seq_pos), s), "sequence positions");
   // x0 = Hcat W_fc^T
   TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.x0, p.d, dt, dt), s), "gemm fc");
-  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x0, P->g1, c->rms_eps, ws + p.a, (float*)(ws + p.r1), dt, s), "rmsnorm1");
+  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x0, P->g1, c->rms_eps, ws + p.a, (float*)(ws + p.r1), dt, nullptr, s), "rmsnorm1");
   TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.nqkv, p.d, ws + p.a, p.d, P->w_qkv, p.d, ws + p.qkv, p.nqkv, dt, dt), s), "gemm qkv");
   TIDE_HIP(launch_rope_table(q.max_len, c->head_dim, c->rope_theta, (float*)(ws + p.rope_cs), s), "rope table");
   { const int rc = enqueue_rope(c, q, ws, p, ws + p.qkv, 0, s); if (rc) return rc; }
@@ -239,26 +242,36 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
     // padding rows are written by no sequence: make them finite (they enter weight-gradient contractions)
     if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.A, q.cu, q.n, T, (int64_t)(p.nq * p.es), s), "zero padding rows");
   }
+  // Only the selected rows go on (see gather_rows): their number *cnt is known on the device alone, so every
+  // launch below is sized for T rows and trims itself.
+  const int* cnt = (const int*)(ws + p.cnt);
+  TIDE_HIP(launch_gather_rows(T, (int)p.nq, ws + p.A, ws + p.A_c, (int)p.d, ws + p.x0, ws + p.x0_c, tokens, (const uint8_t*)(ws + p.mask_eff),
+                              (const int32_t*)(ws + p.kept_idx), cnt, (int32_t*)(ws + p.tokens_c), (uint8_t*)(ws + p.mask_c), dt, s), "gather rows");
+  auto rows_gemm = [&](int layout, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc) {
+    GemmArgs g = gemm_args(layout, T, N, K, A, lda, B, ldb, C, ldc, dt, dt);
+    g.m_dev = cnt;
+    return g;
+  };
   // x1 = x0 + A W_o^T
   {
-    GemmArgs g = gemm_args(kNT, T, p.d, p.nq, ws + p.A, p.nq, P->w_o, p.nq, ws + p.x1, p.d, dt, dt);
-    g.residual = ws + p.x0; g.ldr = p.d;
+    GemmArgs g = rows_gemm(kNT, p.d, p.nq, ws + p.A_c, p.nq, P->w_o, p.nq, ws + p.x1, p.d);
+    g.residual = ws + p.x0_c; g.ldr = p.d;
     TIDE_HIP(launch_gemm(g, s), "gemm o");
   }
-  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x1, P->g2, c->rms_eps, ws + p.bn, (float*)(ws + p.r2), dt, s), "rmsnorm2");
-  TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.F, p.d, ws + p.bn, p.d, P->w_gate, p.d, ws + p.gt, p.F, dt, dt), s), "gemm gate");
-  TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.F, p.d, ws + p.bn, p.d, P->w_up, p.d, ws + p.u, p.F, dt, dt), s), "gemm up");
-  TIDE_HIP(launch_swiglu_fwd(T * p.F, ws + p.gt, ws + p.u, ws + p.h, dt, s), "swiglu");
+  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x1, P->g2, c->rms_eps, ws + p.bn, (float*)(ws + p.r2), dt, cnt, s), "rmsnorm2");
+  TIDE_HIP(launch_gemm(rows_gemm(kNT, p.F, p.d, ws + p.bn, p.d, P->w_gate, p.d, ws + p.gt, p.F), s), "gemm gate");
+  TIDE_HIP(launch_gemm(rows_gemm(kNT, p.F, p.d, ws + p.bn, p.d, P->w_up, p.d, ws + p.u, p.F), s), "gemm up");
+  TIDE_HIP(launch_swiglu_fwd(T * p.F, ws + p.gt, ws + p.u, ws + p.h, dt, p.F, cnt, s), "swiglu");
   {
-    GemmArgs g = gemm_args(kNT, T, p.d, p.F, ws + p.h, p.F, P->w_down, p.F, ws + p.x2, p.d, dt, dt);
+    GemmArgs g = rows_gemm(kNT, p.d, p.F, ws + p.h, p.F, P->w_down, p.F, ws + p.x2, p.d);
     g.residual = ws + p.x1; g.ldr = p.d;
     TIDE_HIP(launch_gemm(g, s), "gemm down");
   }
-  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x2, P->g3, c->rms_eps, ws + p.yhat, (float*)(ws + p.r3), dt, s), "rmsnorm3");
+  TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x2, P->g3, c->rms_eps, ws + p.yhat, (float*)(ws + p.r3), dt, cnt, s), "rmsnorm3");
   return TIDE_OK;
 }
 
-// LM head by row blocks over the rows that carry loss (compacted; every row when arg-max ids are wanted):
+// LM head by row blocks over the selected rows (those that carry loss; every row when arg-max ids are wanted):
 // logits of one block, row statistics, and (training) the logit gradient and the two products that
 // consume it.  The full [T,V] logits never exist.  The number of compacted rows lives on the device, so
 // every launch is sized for the worst case and trims itself.
@@ -274,9 +287,9 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
   float* lse = (float*)(ws + p.lse);
   float* loss_rows = (float*)(ws + p.loss_rows);
   float* hit_rows = acc_out ? (float*)(ws + p.hit_rows) : nullptr;
-  char* yhat_c = ws + p.yhat_c;
+  char* yhat_c = ws + p.yhat;   // dense over the selected rows, as everything after the attention
   char* z = ws + p.z;
-  TIDE_HIP(launch_gather_rows(p.T, (int)p.d, ws + p.yhat, tokens, (const uint8_t*)(ws + p.mask_eff), kept_idx, cnt, yhat_c, (int32_t*)(ws + p.tokens_c), (uint8_t*)(ws + p.mask_c), dt, s), "gather rows");
+  (void)tokens; (void)mask;
   int blk = 0;
   for (int64_t r0 = 0; r0 < p.T; r0 += p.lm_rows, ++blk) {
     const int64_t rows = (p.T - r0 < p.lm_rows) ? (p.T - r0) : p.lm_rows;
@@ -291,7 +304,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
     TIDE_HIP(launch_ce_dz(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, cnt, r0, dt, s), "ce dz");
     {
       // dyhat = (1/N) dZ W_lm
-      GemmArgs g = gemm_args(kNN, rows, p.d, p.V, z, p.ldz, P->w_lm, p.d, ws + p.dyhat_c + (size_t)r0 * p.d * p.es, p.d, dt, dt);
+      GemmArgs g = gemm_args(kNN, rows, p.d, p.V, z, p.ldz, P->w_lm, p.d, ws + p.dyhat + (size_t)r0 * p.d * p.es, p.d, dt, dt);
       g.alpha_dev = scal + 1;
       g.m_dev = cnt; g.m_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm dyhat");
@@ -306,8 +319,6 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
     }
   }
   TIDE_HIP(launch_loss_reduce(loss_rows, hit_rows, cnt, scal, loss_out, acc_out, (int*)(ws + p.status), s), "loss reduce");
-  if (train)   // back to one row per position (zero where no loss is taken)
-    TIDE_HIP(launch_scatter_rows(p.T, (int)p.d, ws + p.dyhat_c, (const int32_t*)(ws + p.row_pos), ws + p.dyhat, dt, s), "scatter rows");
   return TIDE_OK;
 }
 
@@ -330,7 +341,7 @@ int64_t tide_draft_workspace_offset(const tide_draft_config* cfg, const char* na
       {"scal", p.scal}, {"status", p.status}, {"x0", p.x0}, {"r1", p.r1}, {"a", p.a}, {"qkv", p.qkv}, {"attn_lse", p.attn_lse},
       {"A", p.A}, {"x1", p.x1}, {"r2", p.r2}, {"bn", p.bn}, {"gt", p.gt}, {"u", p.u}, {"h", p.h},
       {"x2", p.x2}, {"r3", p.r3}, {"yhat", p.yhat}, {"lse", p.lse}, {"loss_rows", p.loss_rows}, {"z", p.z},
-      {"dyhat", p.dyhat}, {"yhat_c", p.yhat_c}, {"dyhat_c", p.dyhat_c}, {"cnt", p.cnt}, {"kept_idx", p.kept_idx}, {"dx2", p.dx2}, {"dx1", p.dx1}, {"dx0", p.dx0}, {"dh", p.dh}, {"dbn", p.dbn},
+      {"dyhat", p.dyhat}, {"A_c", p.A_c}, {"x0_c", p.x0_c}, {"dx1_c", p.dx1_c}, {"dA_c", p.dA_c}, {"row_pos", p.row_pos}, {"cnt", p.cnt}, {"kept_idx", p.kept_idx}, {"dx2", p.dx2}, {"dx1", p.dx1}, {"dx0", p.dx0}, {"dh", p.dh}, {"dbn", p.dbn},
       {"dA", p.dA}, {"dqkv", p.dqkv}, {"da", p.da}};
   for (auto& e : tab)
     if (std::strcmp(e.n, name) == 0) return (int64_t)e.o;
@@ -406,24 +417,40 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
   if (rc) return rc;
 
   float* dgp = (float*)(ws + p.dg_partial);
+  const int* cnt = (const int*)(ws + p.cnt);
+  // Backward over the selected rows (dense, *cnt of them) down to the attention output.  dX products trim
+  // their M, dW products their K.
+  auto rows_dx = [&](int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc) {
+    GemmArgs g = gemm_args(kNN, T, N, K, A, lda, B, ldb, C, ldc, dt, dt);
+    g.m_dev = cnt;
+    return g;
+  };
+  auto rows_dw = [&](int64_t M, int64_t N, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc) {
+    GemmArgs g = gemm_args(kTN, M, N, T, A, lda, B, ldb, C, ldc, dt, kF32);
+    g.k_dev = cnt;
+    return g;
+  };
   // final norm
-  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dyhat, ws + p.x2, P->g3, (const float*)(ws + p.r3), nullptr, ws + p.dx2, (float*)G->g3, dgp, dt, s), "rmsnorm3 bwd");
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dyhat, ws + p.x2, P->g3, (const float*)(ws + p.r3), nullptr, ws + p.dx2, (float*)G->g3, dgp, dt, cnt, s), "rmsnorm3 bwd");
   // x2 = x1 + h W_down^T
-  TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.F, p.d, ws + p.dx2, p.d, P->w_down, p.F, ws + p.dh, p.F, dt, dt), s), "gemm dh");
-  TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.F, T, ws + p.dx2, p.d, ws + p.h, p.F, G->w_down, p.F, dt, kF32), s), "gemm dW_down");
-  TIDE_HIP(launch_swiglu_bwd(T * p.F, ws + p.dh, ws + p.gt, ws + p.u, ws + p.gt, ws + p.u, dt, s), "swiglu bwd");
+  TIDE_HIP(launch_gemm(rows_dx(p.F, p.d, ws + p.dx2, p.d, P->w_down, p.F, ws + p.dh, p.F), s), "gemm dh");
+  TIDE_HIP(launch_gemm(rows_dw(p.d, p.F, ws + p.dx2, p.d, ws + p.h, p.F, G->w_down, p.F), s), "gemm dW_down");
+  TIDE_HIP(launch_swiglu_bwd(T * p.F, ws + p.dh, ws + p.gt, ws + p.u, ws + p.gt, ws + p.u, dt, p.F, cnt, s), "swiglu bwd");
   {
     // d bn = dGate W_gate + dUp W_up: one contraction over both operand pairs
-    GemmArgs g = gemm_args(kNN, T, p.d, p.F, ws + p.gt, p.F, P->w_gate, p.d, ws + p.dbn, p.d, dt, dt);
+    GemmArgs g = rows_dx(p.d, p.F, ws + p.gt, p.F, P->w_gate, p.d, ws + p.dbn, p.d);
     g.A2 = ws + p.u; g.B2 = P->w_up; g.K2 = p.F;
     TIDE_HIP(launch_gemm(g, s), "gemm dbn");
   }
-  TIDE_HIP(launch_gemm(gemm_args(kTN, p.F, p.d, T, ws + p.gt, p.F, ws + p.bn, p.d, G->w_gate, p.d, dt, kF32), s), "gemm dW_gate");
-  TIDE_HIP(launch_gemm(gemm_args(kTN, p.F, p.d, T, ws + p.u, p.F, ws + p.bn, p.d, G->w_up, p.d, dt, kF32), s), "gemm dW_up");
-  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dbn, ws + p.x1, P->g2, (const float*)(ws + p.r2), ws + p.dx2, ws + p.dx1, (float*)G->g2, dgp, dt, s), "rmsnorm2 bwd");
+  TIDE_HIP(launch_gemm(rows_dw(p.F, p.d, ws + p.gt, p.F, ws + p.bn, p.d, G->w_gate, p.d), s), "gemm dW_gate");
+  TIDE_HIP(launch_gemm(rows_dw(p.F, p.d, ws + p.u, p.F, ws + p.bn, p.d, G->w_up, p.d), s), "gemm dW_up");
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dbn, ws + p.x1, P->g2, (const float*)(ws + p.r2), ws + p.dx2, ws + p.dx1_c, (float*)G->g2, dgp, dt, cnt, s), "rmsnorm2 bwd");
   // x1 = x0 + A W_o^T
-  TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.nq, p.d, ws + p.dx1, p.d, P->w_o, p.nq, ws + p.dA, p.nq, dt, dt), s), "gemm dA");
-  TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.nq, T, ws + p.dx1, p.d, ws + p.A, p.nq, G->w_o, p.nq, dt, kF32), s), "gemm dW_o");
+  TIDE_HIP(launch_gemm(rows_dx(p.nq, p.d, ws + p.dx1_c, p.d, P->w_o, p.nq, ws + p.dA_c, p.nq), s), "gemm dA");
+  TIDE_HIP(launch_gemm(rows_dw(p.d, p.nq, ws + p.dx1_c, p.d, ws + p.A_c, p.nq, G->w_o, p.nq), s), "gemm dW_o");
+  // back to one row per position: rows that were not selected get no gradient from above (only, through
+  // the attention, from the later rows that read their key and value)
+  TIDE_HIP(launch_scatter_rows(T, (int)p.nq, ws + p.dA_c, ws + p.dA, (int)p.d, ws + p.dx1_c, ws + p.dx1, (const int32_t*)(ws + p.row_pos), dt, s), "scatter rows");
   {
     AttnArgs at = attn_args(cfg, q, ws, p);
     at.dout = ws + p.dA; at.delta = (float*)(ws + p.delta); at.dqkv = ws + p.dqkv;
@@ -433,7 +460,7 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
   { const int rc2 = enqueue_rope(cfg, q, ws, p, ws + p.dqkv, 1, s); if (rc2) return rc2; }
   TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.nqkv, ws + p.dqkv, p.nqkv, P->w_qkv, p.d, ws + p.da, p.d, dt, dt), s), "gemm da");
   TIDE_HIP(launch_gemm(gemm_args(kTN, p.nqkv, p.d, T, ws + p.dqkv, p.nqkv, ws + p.a, p.d, G->w_qkv, p.d, dt, kF32), s), "gemm dW_qkv");
-  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.da, ws + p.x0, P->g1, (const float*)(ws + p.r1), ws + p.dx1, ws + p.dx0, (float*)G->g1, dgp, dt, s), "rmsnorm1 bwd");
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.da, ws + p.x0, P->g1, (const float*)(ws + p.r1), ws + p.dx1, ws + p.dx0, (float*)G->g1, dgp, dt, nullptr, s), "rmsnorm1 bwd");
   // x0 = Hcat W_fc^T: weight gradient only, the captured states are data
   TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.KH, T, ws + p.dx0, p.d, hidden_buf, p.KH, G->w_fc, p.KH, dt, kF32), s), "gemm dW_fc");
 
@@ -502,7 +529,7 @@ int tide_rmsnorm_fwd(int64_t rows, int64_t d, const void* x, const void* g, floa
                      int dtype, void* stream) {
   if (!x || !g || !y || !rstd) return fail(TIDE_ERR_NULL, "NULL argument");
   if (rows <= 0 || d <= 0 || d > (1 << 24)) return fail(TIDE_ERR_CONFIG, "bad sizes");
-  TIDE_HIP(launch_rmsnorm_fwd(rows, (int)d, x, g, eps, y, rstd, dtype, (hipStream_t)stream), "rmsnorm fwd");
+  TIDE_HIP(launch_rmsnorm_fwd(rows, (int)d, x, g, eps, y, rstd, dtype, nullptr, (hipStream_t)stream), "rmsnorm fwd");
   return TIDE_OK;
 }
 
@@ -513,7 +540,7 @@ int tide_rmsnorm_bwd(int64_t rows, int64_t d, const void* dy, const void* x, con
   if (!dy || !x || !g || !rstd || !dx || !dg || !dg_partial) return fail(TIDE_ERR_NULL, "NULL argument");
   const bool ok = (d % 8 == 0 && d <= 8192) || d <= 1024;
   if (rows <= 0 || d <= 0 || !ok) return fail(TIDE_ERR_CONFIG, "bad sizes");
-  TIDE_HIP(launch_rmsnorm_bwd(rows, (int)d, dy, x, g, rstd, residual_grad, dx, dg, (float*)dg_partial, dtype, (hipStream_t)stream), "rmsnorm bwd");
+  TIDE_HIP(launch_rmsnorm_bwd(rows, (int)d, dy, x, g, rstd, residual_grad, dx, dg, (float*)dg_partial, dtype, nullptr, (hipStream_t)stream), "rmsnorm bwd");
   return TIDE_OK;
 }
 

@@ -116,6 +116,22 @@ def test_fp32_all_masked_and_bad_labels():
     _check_fp32(cfg, wl)
 
 
+@pytest.mark.parametrize("dtype,keep", [("fp32", 0.5), ("fp32", 0.03), ("bf16", 0.5)])
+def test_scattered_loss_rows(dtype, keep):
+    """Loss on a random subset of positions (not a prefix / suffix pattern): everything after the attention
+    runs on those rows only, yet positions without loss still feed keys and values to later ones.  The
+    oracle computes every row; loss, gradients and the AdamW step must agree as for any other batch.  One
+    case keeps a single sequence entirely without loss and very few rows overall."""
+    cfg = W.get_config("tiny", batch=3, seq=96, dtype=dtype)
+    wl = W.make_workload(cfg)
+    rng = np.random.default_rng(11)
+    wl["mask"] = (rng.random(wl["mask"].shape) < keep).astype(np.uint8)
+    wl["mask"][1, :] = 0 if keep < 0.1 else wl["mask"][1, :]
+    wl["mask"][0, -1] = 1                                   # the last row of a sequence keeps its loss
+    assert 0 < int(wl["mask"].sum()) < wl["mask"].size
+    (_check_fp32 if dtype == "fp32" else _check_bf16)(cfg, wl)
+
+
 def test_top1_matches_oracle():
     from paper_2602_05145_amd import runtime
     cfg = W.get_config("tiny")
