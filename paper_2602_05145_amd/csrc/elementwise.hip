@@ -293,11 +293,24 @@ hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g,
 
 // ----------------------------------------------------------------------------------------------
 // RMSNorm backward.  u = g*dy; dx = r*u - x*r^3*<u,x>/d (+ residual gradient);
-// dg[c] = sum_rows dy*x*r, reduced in two stages: each block owns kRowsPerBlock rows and keeps its
+// dg[c] = sum_rows dy*x*r, reduced in two stages: each block owns a contiguous share of the rows and keeps its
 // column partials in registers, then a column-sum kernel folds the per-block partials.
 // Vector path: d % 8 == 0 and d <= 8192.  Scalar path: d <= 1024.
 // ----------------------------------------------------------------------------------------------
-constexpr int kRowsPerBlock = 32;
+// The grid is what the chip holds at once (256 CUs x blocks per CU at the kernel's register count), at
+// least kMinRowsPerBlock rows each, and the rows are split evenly over it: one round, no partly filled second.
+constexpr int kMinRowsPerBlock = 8;
+__host__ __device__ inline int rmsnorm_bwd_nit(int d) {
+  const bool vec = (d % 8) == 0 && d <= 8192;
+  const int per = vec ? 8 * 256 : 256;   // columns covered by one pass of the block
+  return (d + per - 1) / per;
+}
+inline int64_t rmsnorm_bwd_blocks(int64_t rows, int d) {
+  const int nit = rmsnorm_bwd_nit(d);
+  const int64_t cap = 256 * (nit <= 1 ? 5 : nit == 2 ? 3 : 2);
+  const int64_t want = (rows + kMinRowsPerBlock - 1) / kMinRowsPerBlock;
+  return want < 1 ? 1 : (want < cap ? want : cap);
+}
 
 template <typename T, bool VEC, int NIT>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ dy,
@@ -316,8 +329,9 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
 #pragma unroll
     for (int j = 0; j < W; ++j) acc[it][j] = 0.f;
 
-  const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlock;
-  const int64_t r1 = min(rows, r0 + (int64_t)kRowsPerBlock);
+  const int64_t per_block = (rows + (int64_t)gridDim.x - 1) / (int64_t)gridDim.x;
+  const int64_t r0 = min(rows, (int64_t)blockIdx.x * per_block);
+  const int64_t r1 = min(rows, r0 + per_block);
   const float inv_d = 1.0f / (float)d;
   float gg[NIT][W];
 #pragma unroll
@@ -332,24 +346,32 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
   }
   // The rows of a block are walked with a one-row look-ahead: the loads of row+1 are issued before the
   // block-wide reduction of row, whose two barriers would otherwise expose the full memory latency per row.
-  float xn[NIT][W], dyn[NIT][W], rn[NIT][W], rstd_n = 0.f;
+  // Two things keep those loads in flight: they are held as loaded (no conversion, which would need the
+  // value at once) until the next iteration, and the reduction uses barriers that order LDS only.
+  struct RowRaw {
+    Raw8<T> x[NIT], dy[NIT], res[NIT];   // vector path
+    float xs[NIT], dys[NIT], ress[NIT];  // scalar path
+    float rstd;
+  } nxt;
   auto load_row = [&](int64_t row) {
     const size_t base = (size_t)row * (size_t)d;
-    rstd_n = rstd[row];
+    nxt.rstd = rstd[row];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int c = (threadIdx.x + it * 256) * W;
-#pragma unroll
-      for (int j = 0; j < W; ++j) { xn[it][j] = 0.f; dyn[it][j] = 0.f; rn[it][j] = 0.f; }
-      if (c < d) {
-        if constexpr (VEC) {
-          ld8(dy, base + c, dyn[it]);
-          ld8(x, base + c, xn[it]);
-          if (res) ld8(res, base + c, rn[it]);
-        } else {
-          dyn[it][0] = ldf(dy, base + c);
-          xn[it][0] = ldf(x, base + c);
-          if (res) rn[it][0] = ldf(res, base + c);
+      if constexpr (VEC) {
+        nxt.x[it].zero(); nxt.dy[it].zero(); nxt.res[it].zero();
+        if (c < d) {
+          nxt.dy[it].load(dy, base + c);
+          nxt.x[it].load(x, base + c);
+          if (res) nxt.res[it].load(res, base + c);
+        }
+      } else {
+        nxt.xs[it] = nxt.dys[it] = nxt.ress[it] = 0.f;
+        if (c < d) {
+          nxt.dys[it] = ldf(dy, base + c);
+          nxt.xs[it] = ldf(x, base + c);
+          if (res) nxt.ress[it] = ldf(res, base + c);
         }
       }
     }
@@ -357,18 +379,21 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
   if (r0 < r1) load_row(r0);
   for (int64_t row = r0; row < r1; ++row) {
     const size_t base = (size_t)row * (size_t)d;
-    const float r = rstd_n;
+    const float r = nxt.rstd;
     float xv[NIT][W], dyv[NIT][W], rv[NIT][W];
     float dot = 0.f;
 #pragma unroll
-    for (int it = 0; it < NIT; ++it)
-#pragma unroll
-      for (int j = 0; j < W; ++j) {
-        xv[it][j] = xn[it][j]; dyv[it][j] = dyn[it][j]; rv[it][j] = rn[it][j];
-        dot += gg[it][j] * dyv[it][j] * xv[it][j];
+    for (int it = 0; it < NIT; ++it) {
+      if constexpr (VEC) {
+        nxt.x[it].get(xv[it]); nxt.dy[it].get(dyv[it]); nxt.res[it].get(rv[it]);
+      } else {
+        xv[it][0] = nxt.xs[it]; dyv[it][0] = nxt.dys[it]; rv[it][0] = nxt.ress[it];
       }
+#pragma unroll
+      for (int j = 0; j < W; ++j) dot += gg[it][j] * dyv[it][j] * xv[it][j];
+    }
     if (row + 1 < r1) load_row(row + 1);
-    const float tot = block_sum(dot, red);
+    const float tot = block_sum_lds(dot, red);   // LDS-only barriers: the loads just issued stay in flight
     const float coef = r * r * r * tot * inv_d;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
@@ -411,7 +436,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ p
 }
 
 size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d) {
-  int64_t nblk = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int64_t nblk = rmsnorm_bwd_blocks(rows, d);
   return (size_t)nblk * (size_t)d * sizeof(float);
 }
 
@@ -423,7 +448,7 @@ hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x
   if (!vec && d > 1024) return hipErrorInvalidValue;
   ProfScope ps("rmsnorm_bwd", 0, (double)rows * d * (res ? 4.0 : 3.0) * dtype_size(dtype) + 4.0 * rows, s);
   if (rows_dev) prof_dynamic(rows_dev, 0, rows);
-  const int64_t nblk = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int64_t nblk = rmsnorm_bwd_blocks(rows, d);
   dim3 grid((unsigned)nblk), blk(256);
   const int per = vec ? 8 * 256 : 256;            // columns covered by one pass of the block
   const int nit = (d + per - 1) / per;            // <= 4 by the limits above

@@ -52,6 +52,34 @@ __device__ __forceinline__ void st8(bf16_t* p, size_t i, const float (&v)[8]) {
   *reinterpret_cast<uint4*>(p + i) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// 8 consecutive elements as loaded, conversion to float deferred: a load whose value is not converted stays
+// in flight until `get`, so it can overlap whatever is issued in between
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+  uint4 a;
+  __device__ __forceinline__ void load(const bf16_t* p, size_t i) { a = *reinterpret_cast<const uint4*>(p + i); }
+  __device__ __forceinline__ void zero() { a = make_uint4(0u, 0u, 0u, 0u); }
+  __device__ __forceinline__ void get(float (&v)[8]) const {
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      v[2 * j] = __uint_as_float(w[j] << 16);
+      v[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+    }
+  }
+};
+template <> struct Raw8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float* p, size_t i) {
+    a = reinterpret_cast<const float4*>(p + i)[0];
+    b = reinterpret_cast<const float4*>(p + i)[1];
+  }
+  __device__ __forceinline__ void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); b = a; }
+  __device__ __forceinline__ void get(float (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -71,6 +99,24 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[w] = v;
   __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+
+// The same sum with barriers that order LDS only.  __syncthreads() also waits for every global load the
+// wave has in flight, which defeats a look-ahead; here loads issued before the call stay in flight across
+// it.  Global stores of other threads are NOT made visible by this call.
+__device__ __forceinline__ float block_sum_lds(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();            // everybody has read the previous result
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   float t = 0.f;
   for (int i = 0; i < nw; ++i) t += red[i];
   return t;
