@@ -91,6 +91,33 @@ __global__ __launch_bounds__(64) void attn_delta_kernel(const T* __restrict__ ou
   if (threadIdx.x == 0) delta[stat_index(cu, Trows, sv, b, h, nh, Smax, i)] = a;
 }
 
+// The same for head sizes whose 16-byte pieces form a power-of-two group of lanes (8 <= dh <= 512): one
+// block per row, 8 channels per lane, the dh/8 lanes of a head combine by shuffles.
+template <typename T>
+__global__ __launch_bounds__(256) void attn_delta_vec_kernel(const T* __restrict__ out, const T* __restrict__ dout,
+                                                             float* __restrict__ delta, int Smax, int nh, int dh,
+                                                             const int* __restrict__ cu, int64_t Trows) {
+  const int i = blockIdx.x, b = blockIdx.y;
+  const SeqView sv = seq_view(cu, b, Smax, Trows);
+  if (i >= sv.len) return;
+  const int lph = dh >> 3;                         // lanes per head
+  const int width = nh * dh;
+  const size_t base = ((size_t)sv.row0 + i) * (size_t)width;
+  for (int c0 = 0; c0 < width; c0 += 256 * 8) {    // uniform trip count: the shuffles below are wave-wide
+    const int c = c0 + (int)threadIdx.x * 8;
+    float a = 0.f;
+    if (c < width) {
+      float o[8], g[8];
+      ld8(out, base + c, o);
+      ld8(dout, base + c, g);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) a += o[j] * g[j];
+    }
+    for (int off = lph >> 1; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
+    if (c < width && (threadIdx.x & (lph - 1)) == 0) delta[stat_index(cu, Trows, sv, b, c / dh, nh, Smax, i)] = a;
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(64) void attn_dq_simple_kernel(const T* __restrict__ qkv, const T* __restrict__ dout,
                                                             const float* __restrict__ lse,
@@ -244,6 +271,14 @@ hipError_t launch_attn_fwd_simple(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_delta(const AttnArgs& a, hipStream_t s) {
   ProfScope ps("attn_delta", 0, 2.0 * a.B * a.S * a.nh * a.dh * dtype_size(a.dtype), s);
+  const int lph = a.dh / 8;
+  if (a.dh % 8 == 0 && lph >= 1 && lph <= 64 && (lph & (lph - 1)) == 0 &&
+      (((uintptr_t)a.out | (uintptr_t)a.dout) & 15) == 0) {
+    dim3 grid(a.S, a.B), blk(256);
+    if (a.dtype == kBF16) hipLaunchKernelGGL(attn_delta_vec_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)a.out, (const bf16_t*)a.dout, a.delta, a.S, a.nh, a.dh, a.cu_seqlens, a.total_rows);
+    else hipLaunchKernelGGL(attn_delta_vec_kernel<float>, grid, blk, 0, s, (const float*)a.out, (const float*)a.dout, a.delta, a.S, a.nh, a.dh, a.cu_seqlens, a.total_rows);
+    return hipGetLastError();
+  }
   dim3 grid(a.S, a.nh, a.B), blk(64);
   if (a.dtype == kBF16) hipLaunchKernelGGL(attn_delta_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)a.out, (const bf16_t*)a.dout, a.delta, a.S, a.nh, a.dh, a.cu_seqlens, a.total_rows);
   else hipLaunchKernelGGL(attn_delta_kernel<float>, grid, blk, 0, s, (const float*)a.out, (const float*)a.dout, a.delta, a.S, a.nh, a.dh, a.cu_seqlens, a.total_rows);
