@@ -30,6 +30,19 @@ attention, GQA == MHA with replicated K/V rows, RoPE relative-position and
 isometry properties, RMSNorm scale invariance, AdamW first-step closed form and
 torch.optim.AdamW, and the whole forward/backward against torch CPU fp64
 autograd built from library primitives.  No function here is "parity unpinned".
+
+Token-input variant (optional `tok` argument of forward / train_step).  Sec. 3.2
+names EAGLE-3 as the draft architecture without restating it.  That
+architecture joins the projected features with the embedding of the token
+sampled at the position: the two vectors are concatenated and a second fully
+connected layer brings them back to the model width before the decoder layer.
+Here: g = Hcat W_fc^T, e = E[input_id] (E frozen, an out-of-range id gives a zero
+row), x0 = [g ; e] W_in^T with one more trainable tensor W_in [d, 2d].  The TIDE
+paper fixes none of this (no equation, no number), so against the paper this
+variant is "parity unpinned"; what pins it is mathematics: W_in = [I | 0]
+reproduces the base model exactly, W_in = [0 | I] makes the result independent
+of the captured states, and central finite differences on W_in and W_fc.  The
+multi-step training unroll of that architecture is not part of this oracle.
 """
 from __future__ import annotations
 
@@ -38,6 +51,7 @@ import numpy as np
 F64 = np.float64
 
 PARAM_NAMES = ("w_fc", "g1", "w_qkv", "w_o", "g2", "w_gate", "w_up", "w_down", "g3", "w_lm")
+TOKEN_PARAM = "w_in"   # [d, 2d], present only in the token-input variant
 
 
 def param_shapes(cfg):
@@ -251,11 +265,23 @@ def _as64(params):
     return {k: np.asarray(v, F64) for k, v in params.items()}
 
 
-def forward(cfg, params, hidden_buf, tokens, loss_mask, want_top1=False):
+def embed_rows(embed, input_ids):
+    """e[t] = E[input_ids[t]]; an id outside [0, rows) gives a zero row."""
+    E = np.asarray(embed, F64)
+    ids = np.asarray(input_ids).reshape(-1).astype(np.int64)
+    ok = (ids >= 0) & (ids < E.shape[0])
+    e = np.zeros((ids.shape[0], E.shape[1]), F64)
+    e[ok] = E[ids[ok]]
+    return e
+
+
+def forward(cfg, params, hidden_buf, tokens, loss_mask, want_top1=False, tok=None):
     """Forward pass of the draft on captured hidden states (Sec. 3.2, 3.3).
 
     hidden_buf [B,S,K*H_t]; tokens [B,S] (label already aligned to the
-    position); loss_mask [B,S].  Returns (loss, cache)."""
+    position); loss_mask [B,S].  tok (optional, token-input variant, see the
+    module header): dict(embed [rows, d], input_ids [B,S]); params then holds
+    "w_in" [d, 2d].  Returns (loss, cache)."""
     p = _as64(params)
     B, S = cfg["batch"], cfg["seq"]
     d, nh, nkv, dh = cfg["hidden"], cfg["n_heads"], cfg["n_kv_heads"], cfg["head_dim"]
@@ -263,7 +289,12 @@ def forward(cfg, params, hidden_buf, tokens, loss_mask, want_top1=False):
     T = B * S
     Hc = np.asarray(hidden_buf, F64).reshape(T, -1)
 
-    x0 = Hc @ p["w_fc"].T
+    g0 = Hc @ p["w_fc"].T
+    if tok is None:
+        x0, ge = g0, None
+    else:
+        ge = np.concatenate([g0, embed_rows(tok["embed"], tok["input_ids"])], axis=1)   # [T, 2d]
+        x0 = ge @ p[TOKEN_PARAM].T
     a, r1 = rmsnorm_fwd(x0, p["g1"], eps)
     qkv = a @ p["w_qkv"].T
     nq, nk = nh * dh, nkv * dh
@@ -286,7 +317,7 @@ def forward(cfg, params, hidden_buf, tokens, loss_mask, want_top1=False):
     loss, lse, N = res[:3]
     cache = dict(Hc=Hc, x0=x0, r1=r1, a=a, qr=qr, kr=kr, v=v, P=P, A=A2, x1=x1, r2=r2,
                  bn=bn, gt=gt, u=u, h=h, x2=x2, r3=r3, yhat=yhat, lse=lse, N=N,
-                 cos=cos, sin=sin, qkv=qkv)
+                 cos=cos, sin=sin, qkv=qkv, ge=ge)
     if want_top1:
         cache["top1"] = res[3]
     return loss, cache
@@ -325,7 +356,14 @@ def backward(cfg, params, cache, tokens, loss_mask):
     g["w_qkv"] = dqkv.T @ c["a"]
     dx0n, g["g1"] = rmsnorm_bwd(da, c["x0"], p["g1"], c["r1"])
     dx0 = dx1 + dx0n
-    g["w_fc"] = dx0.T @ c["Hc"]
+    if c.get("ge") is None:
+        g["w_fc"] = dx0.T @ c["Hc"]
+    else:
+        # x0 = [g ; e] W_in^T: the embedding table is frozen, the feature half carries on to W_fc
+        d = dx0.shape[1]
+        g[TOKEN_PARAM] = dx0.T @ c["ge"]
+        dg0 = dx0 @ p[TOKEN_PARAM][:, :d]
+        g["w_fc"] = dg0.T @ c["Hc"]
     return g
 
 
@@ -347,9 +385,9 @@ def adamw_step(cfg, params, grads, m, v, step, lr):
     return np_, nm, nv, t
 
 
-def train_step(cfg, params, m, v, step, hidden_buf, tokens, loss_mask, lr):
+def train_step(cfg, params, m, v, step, hidden_buf, tokens, loss_mask, lr, tok=None):
     """forward + backward + AdamW.  Returns loss, grads, new params, m, v, step."""
-    loss, cache = forward(cfg, params, hidden_buf, tokens, loss_mask)
+    loss, cache = forward(cfg, params, hidden_buf, tokens, loss_mask, tok=tok)
     grads = backward(cfg, params, cache, tokens, loss_mask)
     np_, nm, nv, t = adamw_step(cfg, params, grads, m, v, step, lr)
     return loss, grads, np_, nm, nv, t

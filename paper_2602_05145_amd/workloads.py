@@ -143,6 +143,25 @@ def make_inputs(cfg, rng):
     return hidden, tokens, mask
 
 
+def make_token_input(cfg, seed=None, embed_rows=None):
+    """Seeded inputs of the token-input variant: a frozen embedding table [rows, d] (N(0, 0.5^2), the
+    scale of the projected features), the id of the token sampled at every position (Zipf, like the
+    labels) and the second projection W_in [d, 2d] (N(0, 0.02^2) like every matrix).  bf16 mode rounds
+    the floats to bf16 values, as make_workload does."""
+    rng = np.random.default_rng((cfg["seed"] if seed is None else seed) + 7919)
+    d, V = cfg["hidden"], cfg["vocab"]
+    rows = V if embed_rows is None else embed_rows
+    embed = rng.standard_normal((rows, d), dtype=np.float32) * np.float32(0.5)
+    w = np.arange(1, rows + 1, dtype=np.float64) ** (-cfg["zipf_s"])
+    cdf = np.cumsum(w / w.sum())
+    ranks = np.minimum(np.searchsorted(cdf, rng.random((cfg["batch"], cfg["seq"])), side="right"), rows - 1)
+    input_ids = rng.permutation(rows)[ranks].astype(np.int32)
+    w_in = rng.standard_normal((d, 2 * d), dtype=np.float32) * np.float32(0.02)
+    if cfg["dtype"] == "bf16":
+        embed, w_in = round_to_bf16(embed), round_to_bf16(w_in)
+    return dict(embed=embed, input_ids=input_ids, w_in=w_in)
+
+
 def make_workload(cfg, seed=None):
     """Seeded host workload.  In bf16 mode every float tensor is rounded to the
     nearest bf16 value once (still returned as fp32), so the HIP path gets the

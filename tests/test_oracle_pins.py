@@ -546,3 +546,67 @@ def test_packed_equals_right_padded_batch():
     # moving a boundary does change the result (the attention span of the moved rows differs)
     loss_r, _, _ = O.train_quantities_packed(dict(cfg, batch=1, seq=T), params, hr, tr, mr, [0, 4, 6, 13, 16])
     assert abs(loss_r - loss_p) > 1e-6
+
+
+# ------------------------------------------------------------------ token-input variant
+def _tok_setup(**kw):
+    cfg = micro_cfg(**kw)
+    wl = micro_workload(cfg)
+    ti = W.make_token_input(cfg, embed_rows=9)
+    ti = {k: np.asarray(v, np.float64) if k != "input_ids" else v for k, v in ti.items()}
+    params = dict(wl["params"], w_in=ti["w_in"])
+    tok = dict(embed=ti["embed"], input_ids=ti["input_ids"])
+    return cfg, wl, params, tok
+
+
+def test_token_input_identity_projection_is_the_base_model():
+    """W_in = [I | 0] passes the projected features through unchanged: loss and the ten base gradients are
+    those of the model without token input (an independent code path of the oracle)."""
+    cfg, wl, params, tok = _tok_setup()
+    d = cfg["hidden"]
+    params["w_in"] = np.concatenate([np.eye(d), np.zeros((d, d))], axis=1)
+    base = {k: params[k] for k in O.PARAM_NAMES}
+    l0, c0 = O.forward(cfg, base, wl["hidden"], wl["tokens"], wl["mask"])
+    g0 = O.backward(cfg, base, c0, wl["tokens"], wl["mask"])
+    l1, c1 = O.forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], tok=tok)
+    g1 = O.backward(cfg, params, c1, wl["tokens"], wl["mask"])
+    assert abs(l1 - l0) <= 1e-13 * abs(l0)
+    for k in O.PARAM_NAMES:
+        assert np.max(np.abs(g1[k] - g0[k])) <= 1e-12 * max(1.0, np.max(np.abs(g0[k]))), k
+    assert g1["w_in"].shape == (d, 2 * d) and np.max(np.abs(g1["w_in"])) > 0
+
+
+def test_token_input_embedding_only_ignores_the_captured_states():
+    """W_in = [0 | I]: the layer sees the embeddings alone, so the captured states cannot matter: changing
+    them leaves the loss unchanged and dW_fc is exactly zero.  An out-of-range id is a zero embedding."""
+    cfg, wl, params, tok = _tok_setup()
+    d = cfg["hidden"]
+    params["w_in"] = np.concatenate([np.zeros((d, d)), np.eye(d)], axis=1)
+    l1, c1 = O.forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], tok=tok)
+    l2, _ = O.forward(cfg, params, wl["hidden"] * -3.0 + 1.0, wl["tokens"], wl["mask"], tok=tok)
+    assert l1 == l2
+    g = O.backward(cfg, params, c1, wl["tokens"], wl["mask"])
+    assert not np.any(g["w_fc"] != 0)
+    assert np.allclose(c1["x0"], O.embed_rows(tok["embed"], tok["input_ids"]), rtol=0, atol=0)
+    bad = dict(tok, input_ids=tok["input_ids"].copy())
+    bad["input_ids"][0, 0], bad["input_ids"][-1, -1] = -1, tok["embed"].shape[0]
+    e = O.embed_rows(bad["embed"], bad["input_ids"])
+    assert not np.any(e[0] != 0) and not np.any(e[-1] != 0) and np.any(e[1] != 0)
+
+
+def test_token_input_finite_differences():
+    cfg, wl, params, tok = _tok_setup(batch=2, seq=4, n_heads=4, n_kv_heads=2, hidden=16, ffn=10, vocab=13)
+    loss, cache = O.forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], tok=tok)
+    grads = O.backward(cfg, params, cache, wl["tokens"], wl["mask"])
+    rng = np.random.default_rng(1)
+    h = 1e-6
+    for name in ("w_in", "w_fc", "w_qkv", "g1", "w_lm"):
+        flat = params[name].reshape(-1)
+        for i in rng.choice(flat.size, size=min(16, flat.size), replace=False):
+            pp = copy.deepcopy(params)
+            pp[name].reshape(-1)[i] += h
+            lp = O.forward(cfg, pp, wl["hidden"], wl["tokens"], wl["mask"], tok=tok)[0]
+            pp[name].reshape(-1)[i] -= 2 * h
+            lm = O.forward(cfg, pp, wl["hidden"], wl["tokens"], wl["mask"], tok=tok)[0]
+            fd, an = (lp - lm) / (2 * h), grads[name].reshape(-1)[i]
+            assert abs(fd - an) <= 1e-6 * max(1.0, abs(fd)) + 2e-8, (name, i, fd, an)
