@@ -176,6 +176,42 @@ int tide_draft_train_step(const tide_draft_config *cfg, tide_draft_tensors *para
                           float lr, float *loss_out,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* Token-input variant.  Sec. 3.2 names EAGLE-3 as the draft architecture; that architecture joins the
+ * projected features with the embedding of the token sampled at the position: both vectors are
+ * concatenated and a second fully connected layer brings them back to the model width before the decoder
+ * layer.  With this struct the first line of the model above becomes
+ *     g = Hcat W_fc^T,  e = embed[input_ids]  (a zero row for an id outside [0, embed_rows)),
+ *     x0 = [g ; e] W_in^T
+ * and everything after x0 is unchanged.  embed is frozen (no gradient); W_in is one more trainable tensor
+ * with its own gradient and Adam state.  The paper restates none of this, so it is a reading of the cited
+ * architecture; the multi-step training unroll of that architecture is not implemented.
+ *   embed       DEVICE [embed_rows, d], dtype per cfg, read-only
+ *   input_ids   DEVICE int32 [B,S]: the token whose embedding joins the features of the position
+ *   w_in        DEVICE [d, 2d], dtype per cfg: columns [0, d) act on g, columns [d, 2d) on e
+ *   grad_w_in, m_w_in, v_w_in   DEVICE float [d, 2d]; master_w_in likewise, bf16 mode only.  These four are
+ *               used by tide_draft_train_step_tok only and may be NULL for tide_draft_forward_tok.
+ * Fixed-layout batches only.  Other arguments, ownership and errors as in tide_draft_forward /
+ * tide_draft_train_step (top1_out and the AdamW step included); TIDE_ERR_NULL for a NULL member that the
+ * call needs, TIDE_ERR_CONFIG for embed_rows < 1. */
+typedef struct tide_token_input {
+  const void *embed;
+  int32_t embed_rows;
+  const int32_t *input_ids;
+  void *w_in;
+  void *grad_w_in, *m_w_in, *v_w_in, *master_w_in;
+} tide_token_input;
+int tide_draft_forward_tok(const tide_draft_config *cfg, const tide_draft_tensors *params,
+                           const tide_token_input *tok,
+                           const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                           float *loss_out, int32_t *top1_out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+int tide_draft_train_step_tok(const tide_draft_config *cfg, tide_draft_tensors *params,
+                              tide_draft_tensors *grads, tide_adam_state *adam_state,
+                              const tide_token_input *tok,
+                              const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                              float lr, float *loss_out,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
 /* Message of the last error on the calling thread (static storage, never NULL). */
 const char *tide_last_error(void);
 

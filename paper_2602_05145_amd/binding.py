@@ -39,6 +39,12 @@ class TideAdamState(C.Structure):
                 ("step", C.c_int64)]
 
 
+class TideTokenInput(C.Structure):
+    """tide_token_input: the token-input variant's frozen embedding table, ids, W_in and its training state."""
+    _fields_ = [("embed", C.c_void_p), ("embed_rows", C.c_int32), ("input_ids", C.c_void_p), ("w_in", C.c_void_p),
+                ("grad_w_in", C.c_void_p), ("m_w_in", C.c_void_p), ("v_w_in", C.c_void_p), ("master_w_in", C.c_void_p)]
+
+
 class TideError(RuntimeError):
     def __init__(self, code, msg):
         super().__init__(f"tide error {code}: {msg}")
@@ -74,6 +80,11 @@ _lib.tide_draft_eval.restype = _i32
 _lib.tide_draft_eval.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.tide_draft_train_step.restype = _i32
 _lib.tide_draft_train_step.argtypes = [_cfgp, _tp, _tp, _ap, _vp, _vp, _vp, _f32, _vp, _vp, _sz, _vp]
+_tokp = C.POINTER(TideTokenInput)
+_lib.tide_draft_forward_tok.restype = _i32
+_lib.tide_draft_forward_tok.argtypes = [_cfgp, _tp, _tokp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.tide_draft_train_step_tok.restype = _i32
+_lib.tide_draft_train_step_tok.argtypes = [_cfgp, _tp, _tp, _ap, _tokp, _vp, _vp, _vp, _f32, _vp, _vp, _sz, _vp]
 _lib.tide_gemm_workspace_bytes.restype = _sz
 _lib.tide_gemm_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32]
 _lib.tide_gemm.restype = _i32
@@ -98,7 +109,7 @@ _lib.tide_profile_stop.argtypes = [C.c_char_p, _sz]
 
 EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
             "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_draft_forward_packed",
-    "tide_draft_train_step_packed",
+    "tide_draft_train_step_packed", "tide_draft_forward_tok", "tide_draft_train_step_tok",
     "tide_mfma_probe",
     "tide_ingest_create", "tide_ingest_destroy", "tide_ingest_acquire", "tide_ingest_submit", "tide_ingest_wait",
     "tide_ingest_done", "tide_ingest_last_error", "tide_gemm_workspace_bytes", "tide_gemm",
@@ -150,6 +161,36 @@ def make_tensors(d) -> TideDraftTensors:
     for n in TENSOR_NAMES:
         setattr(t, n, _ptr(d.get(n)) if d is not None else None)
     return t
+
+
+def make_token_input(embed, input_ids, w_in, grad_w_in=None, m_w_in=None, v_w_in=None, master_w_in=None) -> TideTokenInput:
+    """torch tensors (or int pointers / None) -> C struct; embed_rows is embed's first dimension."""
+    t = TideTokenInput()
+    t.embed, t.embed_rows, t.input_ids, t.w_in = _ptr(embed), int(embed.shape[0]), _ptr(input_ids), _ptr(w_in)
+    t.grad_w_in, t.m_w_in, t.v_w_in, t.master_w_in = _ptr(grad_w_in), _ptr(m_w_in), _ptr(v_w_in), _ptr(master_w_in)
+    return t
+
+
+def tide_draft_forward_tok(cfg, params, tok, hidden_buf, tokens, loss_mask, loss_out, top1_out, workspace,
+                           workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_forward_tok(C.byref(cfg) if cfg is not None else None,
+                                     C.byref(params) if params is not None else None,
+                                     C.byref(tok) if tok is not None else None,
+                                     _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(loss_out),
+                                     _ptr(top1_out), _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_draft_train_step_tok(cfg, params, grads, adam_state, tok, hidden_buf, tokens, loss_mask, lr, loss_out,
+                              workspace, workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_train_step_tok(C.byref(cfg) if cfg is not None else None,
+                                        C.byref(params) if params is not None else None,
+                                        C.byref(grads) if grads is not None else None,
+                                        C.byref(adam_state) if adam_state is not None else None,
+                                        C.byref(tok) if tok is not None else None,
+                                        _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), float(lr), _ptr(loss_out),
+                                        _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
 
 
 def tide_draft_workspace_bytes(cfg: TideDraftConfig) -> int:

@@ -174,6 +174,27 @@ __device__ __forceinline__ void zero_row(T* b, int d) {
   }
 }
 
+// Embedding lookup of the token-input variant: one block per position.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_rows_kernel(const T* __restrict__ embed, int rows,
+                                                         const int32_t* __restrict__ ids, T* __restrict__ out, int d) {
+  const size_t t = blockIdx.x;
+  const int id = ids[t];
+  T* b = out + t * (size_t)d;
+  if (id >= 0 && id < rows) copy_row(embed + (size_t)id * (size_t)d, b, d);
+  else zero_row(b, d);
+}
+
+hipError_t launch_embed_rows(int64_t T, int d, const void* embed, int rows, const int32_t* ids, void* out, int dtype,
+                             hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  ProfScope ps("embed_rows", 0, 2.0 * (double)T * d * dtype_size(dtype), s);
+  dim3 grid((unsigned)T), blk(256);
+  if (dtype == kBF16) hipLaunchKernelGGL(embed_rows_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)embed, rows, ids, (bf16_t*)out, d);
+  else hipLaunchKernelGGL(embed_rows_kernel<float>, grid, blk, 0, s, (const float*)embed, rows, ids, (float*)out, d);
+  return hipGetLastError();
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void gather_rows_kernel(const T* __restrict__ src0, T* __restrict__ dst0, int d0,
                                                           const T* __restrict__ src1, T* __restrict__ dst1, int d1,
@@ -831,8 +852,8 @@ hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, con
 // 1/sqrt(1-beta2^t) computed in double on the host.
 // ----------------------------------------------------------------------------------------------
 struct AdamDev {
-  AdamTensor t[10];
-  int64_t blk_start[11];
+  AdamTensor t[kMaxAdamTensors];
+  int64_t blk_start[kMaxAdamTensors + 1];
   int nt;
   float lr, beta1, beta2, eps, decay, inv_bc1, inv_sqrt_bc2;
 };
@@ -842,7 +863,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(AdamDev a) {
   int ti = 0;
   const int64_t b = blockIdx.x;
 #pragma unroll
-  for (int i = 1; i < 10; ++i)
+  for (int i = 1; i < kMaxAdamTensors; ++i)
     if (i < a.nt && b >= a.blk_start[i]) ti = i;
   const AdamTensor t = a.t[ti];
   const int64_t i0 = ((b - a.blk_start[ti]) * 256 + threadIdx.x) * 8;
@@ -891,8 +912,8 @@ hipError_t launch_adamw(const AdamArgs& a, hipStream_t s) {
     d.blk_start[i] = nb;
     nb += (a.t[i].n + 2047) / 2048;
   }
-  for (int i = a.nt; i < 10; ++i) d.t[i] = AdamTensor{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
-  for (int i = a.nt; i <= 10; ++i) d.blk_start[i] = nb;
+  for (int i = a.nt; i < kMaxAdamTensors; ++i) d.t[i] = AdamTensor{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  for (int i = a.nt; i <= kMaxAdamTensors; ++i) d.blk_start[i] = nb;
   d.lr = a.lr; d.beta1 = a.beta1; d.beta2 = a.beta2; d.eps = a.eps;
   d.decay = 1.0f - a.lr * a.wd;
   d.inv_bc1 = a.inv_bc1; d.inv_sqrt_bc2 = a.inv_sqrt_bc2;

@@ -49,6 +49,9 @@ hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t 
 // of the rows of a [T, row_bytes] array that no sequence owns
 hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int max_len, int32_t* pos, hipStream_t s);
 hipError_t launch_zero_padding_rows(void* p, const int* cu, int nseq, int64_t T, int64_t row_bytes, hipStream_t s);
+// out[t] = embed[ids[t]] for 0 <= ids[t] < rows, else a zero row (rows of width d)
+hipError_t launch_embed_rows(int64_t T, int d, const void* embed, int rows, const int32_t* ids, void* out, int dtype,
+                             hipStream_t s);
 // dst0[i] = src0[kept_idx[i]] for i < *cnt (rows of width d0), likewise src1 -> dst1 (width d1; src1 may be
 // NULL), tokens and mask
 hipError_t launch_gather_rows(int64_t T, int d0, const void* src0, void* dst0, int d1, const void* src1, void* dst1,
@@ -90,8 +93,9 @@ hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, con
                               float* loss_out, float* acc_out, int* status, hipStream_t s);
 
 struct AdamTensor { void* p; const float* g; float* m; float* v; float* master; int64_t n; };
+constexpr int kMaxAdamTensors = 11;   // the ten tensors of the draft and W_in of the token-input variant
 struct AdamArgs {
-  AdamTensor t[10];
+  AdamTensor t[kMaxAdamTensors];
   int nt;
   float lr, beta1, beta2, eps, wd, inv_bc1, inv_sqrt_bc2;
   int dtype;

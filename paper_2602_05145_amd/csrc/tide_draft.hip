@@ -72,6 +72,7 @@ struct Plan {
   size_t scal, cnt, status, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, rope_cs, x0, r1, a, qkv, attn_lse, A, A_c, x0_c, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
   size_t fwd_end;
   size_t dyhat, dx2, dx1_c, dx1, dx0, dh, dbn, dA_c, dA, dqkv, da, delta, dg_partial;
+  size_t g0, e0, dg0;   // token-input variant: projected features, looked-up embeddings, gradient of the features
   size_t total;
 };
 
@@ -152,6 +153,9 @@ Plan make_plan(const tide_draft_config* c) {
   p.da = b.take(T * p.d * es);
   p.delta = b.take((size_t)c->batch * c->n_heads * c->seq * 4);
   p.dg_partial = b.take(rmsnorm_bwd_scratch_bytes(p.T, (int)p.d));
+  p.g0 = b.take(T * p.d * es);
+  p.e0 = b.take(T * p.d * es);
+  p.dg0 = b.take(T * p.d * es);
   p.total = b.off;
   return p;
 }
@@ -162,6 +166,17 @@ bool tensors_ok(const tide_draft_tensors* t, const char* what) {
   for (int i = 0; i < 10; ++i)
     if (!ptrs[i]) { fail(TIDE_ERR_NULL, "%s has a NULL tensor (index %d)", what, i); return false; }
   return true;
+}
+
+int check_token_input(const tide_token_input* tok, bool train, int dtype) {
+  if (!tok) return fail(TIDE_ERR_NULL, "tok is NULL");
+  if (!tok->embed || !tok->input_ids || !tok->w_in) return fail(TIDE_ERR_NULL, "tok.embed, tok.input_ids and tok.w_in must not be NULL");
+  if (tok->embed_rows < 1) return fail(TIDE_ERR_CONFIG, "tok.embed_rows must be >= 1");
+  if (train) {
+    if (!tok->grad_w_in || !tok->m_w_in || !tok->v_w_in) return fail(TIDE_ERR_NULL, "tok.grad_w_in, tok.m_w_in and tok.v_w_in must not be NULL for a training step");
+    if (dtype == TIDE_DTYPE_BF16 && !tok->master_w_in) return fail(TIDE_ERR_NULL, "tok.master_w_in must not be NULL in bf16 mode");
+  }
+  return TIDE_OK;
 }
 
 int check_common(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
@@ -222,16 +237,26 @@ int enqueue_rope(const tide_draft_config* c, const Seqs& q, char* ws, const Plan
 }
 
 // Forward pass up to the final RMSNorm (everything except the LM head).
-int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const void* hidden_buf,
-                  const int32_t* tokens, const uint8_t* mask, int select_all, const Seqs& q, char* ws, const Plan& p,
-                  hipStream_t s) {
+int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const tide_token_input* tok,
+                  const void* hidden_buf, const int32_t* tokens, const uint8_t* mask, int select_all, const Seqs& q,
+                  char* ws, const Plan& p, hipStream_t s) {
   const int dt = c->dtype;
   const int64_t T = p.T;
   float* scal = (float*)(ws + p.scal);
   TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), q.cu, q.n, q.max_len, (uint8_t*)(ws + p.mask_eff), (int*)(ws + p.status), s), "plan_rows");
   if (q.cu) TIDE_HIP(launch_seq_pos(q.cu, q.n, T, q.max_len, (int32_t*)(ws + p.seq_pos), s), "sequence positions");
-  // x0 = Hcat W_fc^T
-  TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.x0, p.d, dt, dt), s), "gemm fc");
+  if (!tok) {
+    // x0 = Hcat W_fc^T
+    TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.x0, p.d, dt, dt), s), "gemm fc");
+  } else {
+    // token-input variant: g = Hcat W_fc^T, e = embed[input_ids], x0 = [g ; e] W_in^T as ONE contraction over
+    // the two operand pairs (g, W_in[:, :d]) and (e, W_in[:, d:]); W_in's row stride is 2d for both halves
+    TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.g0, p.d, dt, dt), s), "gemm fc");
+    TIDE_HIP(launch_embed_rows(T, (int)p.d, tok->embed, tok->embed_rows, tok->input_ids, ws + p.e0, dt, s), "embed rows");
+    GemmArgs g = gemm_args(kNT, T, p.d, p.d, ws + p.g0, p.d, tok->w_in, 2 * p.d, ws + p.x0, p.d, dt, dt);
+    g.A2 = ws + p.e0; g.B2 = (const char*)tok->w_in + (size_t)p.d * p.es; g.K2 = p.d;
+    TIDE_HIP(launch_gemm(g, s), "gemm in");
+  }
   TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x0, P->g1, c->rms_eps, ws + p.a, (float*)(ws + p.r1), dt, nullptr, s), "rmsnorm1");
   TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.nqkv, p.d, ws + p.a, p.d, P->w_qkv, p.d, ws + p.qkv, p.nqkv, dt, dt), s), "gemm qkv");
   TIDE_HIP(launch_rope_table(q.max_len, c->head_dim, c->rope_theta, (float*)(ws + p.rope_cs), s), "rope table");
@@ -342,14 +367,15 @@ int64_t tide_draft_workspace_offset(const tide_draft_config* cfg, const char* na
       {"A", p.A}, {"x1", p.x1}, {"r2", p.r2}, {"bn", p.bn}, {"gt", p.gt}, {"u", p.u}, {"h", p.h},
       {"x2", p.x2}, {"r3", p.r3}, {"yhat", p.yhat}, {"lse", p.lse}, {"loss_rows", p.loss_rows}, {"z", p.z},
       {"dyhat", p.dyhat}, {"A_c", p.A_c}, {"x0_c", p.x0_c}, {"dx1_c", p.dx1_c}, {"dA_c", p.dA_c}, {"row_pos", p.row_pos}, {"cnt", p.cnt}, {"kept_idx", p.kept_idx}, {"dx2", p.dx2}, {"dx1", p.dx1}, {"dx0", p.dx0}, {"dh", p.dh}, {"dbn", p.dbn},
-      {"dA", p.dA}, {"dqkv", p.dqkv}, {"da", p.da}};
+      {"dA", p.dA}, {"dqkv", p.dqkv}, {"da", p.da}, {"g0", p.g0}, {"e0", p.e0}, {"dg0", p.dg0}};
   for (auto& e : tab)
     if (std::strcmp(e.n, name) == 0) return (int64_t)e.o;
   if (std::strcmp(name, "lm_rows") == 0) return p.lm_rows;
   return -1;
 }
 
-static int forward_impl(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
+static int forward_impl(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,
+                        const void* hidden_buf,
                         const int32_t* tokens, const uint8_t* loss_mask, const Seqs* packed, float* loss_out,
                         int32_t* top1_out, float* accuracy_out, void* workspace, size_t workspace_bytes, void* stream) {
   const Plan p = make_plan(cfg);
@@ -358,7 +384,7 @@ static int forward_impl(const tide_draft_config* cfg, const tide_draft_tensors* 
   const Seqs q = packed ? *packed : fixed_seqs(cfg);
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  rc = enqueue_trunk(cfg, params, hidden_buf, tokens, loss_mask, top1_out != nullptr, q, ws, p, s);
+  rc = enqueue_trunk(cfg, params, tok, hidden_buf, tokens, loss_mask, top1_out != nullptr, q, ws, p, s);
   if (rc) return rc;
   return enqueue_lm_head(cfg, params, nullptr, tokens, loss_mask, top1_out, loss_out, accuracy_out, ws, p, false, s);
 }
@@ -367,7 +393,7 @@ int tide_draft_forward(const tide_draft_config* cfg, const tide_draft_tensors* p
                        const int32_t* tokens, const uint8_t* loss_mask, float* loss_out, int32_t* top1_out,
                        void* workspace, size_t workspace_bytes, void* stream) {
   if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
-  return forward_impl(cfg, params, hidden_buf, tokens, loss_mask, nullptr, loss_out, top1_out, nullptr, workspace, workspace_bytes, stream);
+  return forward_impl(cfg, params, nullptr, hidden_buf, tokens, loss_mask, nullptr, loss_out, top1_out, nullptr, workspace, workspace_bytes, stream);
 }
 
 int tide_draft_forward_packed(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
@@ -378,7 +404,7 @@ int tide_draft_forward_packed(const tide_draft_config* cfg, const tide_draft_ten
   const int rc = check_packed(cfg, cu_seqlens, n_seqs, max_seqlen);
   if (rc) return rc;
   const Seqs q{cu_seqlens, n_seqs, max_seqlen};
-  return forward_impl(cfg, params, hidden_buf, tokens, loss_mask, &q, loss_out, top1_out, nullptr, workspace, workspace_bytes, stream);
+  return forward_impl(cfg, params, nullptr, hidden_buf, tokens, loss_mask, &q, loss_out, top1_out, nullptr, workspace, workspace_bytes, stream);
 }
 
 int tide_draft_eval(const tide_draft_config* cfg, const tide_draft_tensors* params, const void* hidden_buf,
@@ -386,11 +412,11 @@ int tide_draft_eval(const tide_draft_config* cfg, const tide_draft_tensors* para
                     void* workspace, size_t workspace_bytes, void* stream) {
   if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
   if (!accuracy_out) return fail(TIDE_ERR_NULL, "accuracy_out is NULL");
-  return forward_impl(cfg, params, hidden_buf, tokens, loss_mask, nullptr, loss_out, nullptr, accuracy_out, workspace, workspace_bytes, stream);
+  return forward_impl(cfg, params, nullptr, hidden_buf, tokens, loss_mask, nullptr, loss_out, nullptr, accuracy_out, workspace, workspace_bytes, stream);
 }
 
 static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
-                      tide_adam_state* st, const void* hidden_buf, const int32_t* tokens,
+                      tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf, const int32_t* tokens,
                       const uint8_t* loss_mask, const Seqs* packed, float lr, float* loss_out, void* workspace,
                       size_t workspace_bytes, void* stream) {
   const Plan p = make_plan(cfg);
@@ -411,7 +437,7 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
   tide_draft_tensors* G = grads;
   const int64_t T = p.T;
 
-  rc = enqueue_trunk(cfg, P, hidden_buf, tokens, loss_mask, 0, q, ws, p, s);
+  rc = enqueue_trunk(cfg, P, tok, hidden_buf, tokens, loss_mask, 0, q, ws, p, s);
   if (rc) return rc;
   rc = enqueue_lm_head(cfg, P, G, tokens, loss_mask, nullptr, loss_out, nullptr, ws, p, true, s);
   if (rc) return rc;
@@ -461,10 +487,20 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
   TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.nqkv, ws + p.dqkv, p.nqkv, P->w_qkv, p.d, ws + p.da, p.d, dt, dt), s), "gemm da");
   TIDE_HIP(launch_gemm(gemm_args(kTN, p.nqkv, p.d, T, ws + p.dqkv, p.nqkv, ws + p.a, p.d, G->w_qkv, p.d, dt, kF32), s), "gemm dW_qkv");
   TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.da, ws + p.x0, P->g1, (const float*)(ws + p.r1), ws + p.dx1, ws + p.dx0, (float*)G->g1, dgp, dt, nullptr, s), "rmsnorm1 bwd");
-  // x0 = Hcat W_fc^T: weight gradient only, the captured states are data
-  TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.KH, T, ws + p.dx0, p.d, hidden_buf, p.KH, G->w_fc, p.KH, dt, kF32), s), "gemm dW_fc");
+  if (!tok) {
+    // x0 = Hcat W_fc^T: weight gradient only, the captured states are data
+    TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.KH, T, ws + p.dx0, p.d, hidden_buf, p.KH, G->w_fc, p.KH, dt, kF32), s), "gemm dW_fc");
+  } else {
+    // x0 = [g ; e] W_in^T: dW_in = dx0^T [g ; e] (two products into the column halves of dW_in), dg = dx0 W_in[:, :d]
+    // (the embedding table is frozen), then dW_fc = dg^T Hcat
+    float* dwin = (float*)tok->grad_w_in;
+    TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.d, T, ws + p.dx0, p.d, ws + p.g0, p.d, dwin, 2 * p.d, dt, kF32), s), "gemm dW_in (features)");
+    TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.d, T, ws + p.dx0, p.d, ws + p.e0, p.d, dwin + p.d, 2 * p.d, dt, kF32), s), "gemm dW_in (embeddings)");
+    TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.d, ws + p.dx0, p.d, tok->w_in, 2 * p.d, ws + p.dg0, p.d, dt, dt), s), "gemm dg");
+    TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.KH, T, ws + p.dg0, p.d, hidden_buf, p.KH, G->w_fc, p.KH, dt, kF32), s), "gemm dW_fc");
+  }
 
-  // AdamW over all ten tensors in one launch
+  // AdamW over all tensors in one launch
   {
     AdamArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -476,6 +512,11 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
     const int64_t nn[10] = {p.d * p.KH, p.d, p.nqkv * p.d, p.d * p.nq, p.d, p.F * p.d, p.F * p.d, p.d * p.F, p.d, p.V * p.d};
     for (int i = 0; i < 10; ++i) a.t[i] = AdamTensor{pp[i], (const float*)gg[i], (float*)mm[i], (float*)vv[i], dt == TIDE_DTYPE_BF16 ? (float*)ms[i] : nullptr, nn[i]};
     a.nt = 10;
+    if (tok) {
+      a.t[10] = AdamTensor{tok->w_in, (const float*)tok->grad_w_in, (float*)tok->m_w_in, (float*)tok->v_w_in,
+                           dt == TIDE_DTYPE_BF16 ? (float*)tok->master_w_in : nullptr, 2 * p.d * p.d};
+      a.nt = 11;
+    }
     const double t = (double)(st->step + 1);
     a.lr = lr; a.beta1 = cfg->beta1; a.beta2 = cfg->beta2; a.eps = cfg->adam_eps; a.wd = cfg->weight_decay;
     a.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta1, t)));
@@ -492,7 +533,26 @@ int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* para
                           const uint8_t* loss_mask, float lr, float* loss_out, void* workspace,
                           size_t workspace_bytes, void* stream) {
   if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
-  return train_impl(cfg, params, grads, st, hidden_buf, tokens, loss_mask, nullptr, lr, loss_out, workspace, workspace_bytes, stream);
+  return train_impl(cfg, params, grads, st, nullptr, hidden_buf, tokens, loss_mask, nullptr, lr, loss_out, workspace, workspace_bytes, stream);
+}
+
+int tide_draft_forward_tok(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,
+                           const void* hidden_buf, const int32_t* tokens, const uint8_t* loss_mask, float* loss_out,
+                           int32_t* top1_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const int rc = check_token_input(tok, false, cfg->dtype);
+  if (rc) return rc;
+  return forward_impl(cfg, params, tok, hidden_buf, tokens, loss_mask, nullptr, loss_out, top1_out, nullptr, workspace, workspace_bytes, stream);
+}
+
+int tide_draft_train_step_tok(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                              tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf,
+                              const int32_t* tokens, const uint8_t* loss_mask, float lr, float* loss_out,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const int rc = check_token_input(tok, true, cfg->dtype);
+  if (rc) return rc;
+  return train_impl(cfg, params, grads, st, tok, hidden_buf, tokens, loss_mask, nullptr, lr, loss_out, workspace, workspace_bytes, stream);
 }
 
 int tide_draft_train_step_packed(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
@@ -504,7 +564,7 @@ int tide_draft_train_step_packed(const tide_draft_config* cfg, tide_draft_tensor
   const int rc = check_packed(cfg, cu_seqlens, n_seqs, max_seqlen);
   if (rc) return rc;
   const Seqs q{cu_seqlens, n_seqs, max_seqlen};
-  return train_impl(cfg, params, grads, st, hidden_buf, tokens, loss_mask, &q, lr, loss_out, workspace, workspace_bytes, stream);
+  return train_impl(cfg, params, grads, st, nullptr, hidden_buf, tokens, loss_mask, &q, lr, loss_out, workspace, workspace_bytes, stream);
 }
 
 // ---- building blocks ---------------------------------------------------------------------------

@@ -98,6 +98,33 @@ class DraftTrainer:
                                        self.workspace, self.ws_bytes, self._stream())
         return self.loss
 
+    # ---- token-input variant: features joined with the sampled token's embedding through W_in ----
+    def set_token_input(self, embed, input_ids, w_in):
+        """numpy (host) arrays: embed [rows, d] (frozen), input_ids [B, S], w_in [d, 2d] (trainable); kept resident
+        together with W_in's gradient and Adam state."""
+        f32 = dict(dtype=torch.float32, device=self.device)
+        self.embed = _np_to_dev(np.asarray(embed, np.float32), self.dtype, self.device)
+        self.input_ids = torch.from_numpy(np.ascontiguousarray(input_ids, dtype=np.int32)).to(self.device)
+        self.w_in = _np_to_dev(np.asarray(w_in, np.float32), self.dtype, self.device)
+        self.grad_w_in = torch.zeros(self.w_in.shape, **f32)
+        self.m_w_in = torch.zeros(self.w_in.shape, **f32)
+        self.v_w_in = torch.zeros(self.w_in.shape, **f32)
+        self.master_w_in = self.w_in.to(torch.float32) if self.dtype == "bf16" else None
+        self.c_tok = B.make_token_input(self.embed, self.input_ids, self.w_in, self.grad_w_in, self.m_w_in,
+                                        self.v_w_in, self.master_w_in)
+
+    def forward_tok(self, want_top1=False):
+        top1 = (torch.empty(self.cfg["batch"] * self.cfg["seq"], dtype=torch.int32, device=self.device)
+                if want_top1 else None)
+        B.tide_draft_forward_tok(self.ccfg, self.c_params, self.c_tok, self.hidden, self.tokens, self.mask, self.loss,
+                                 top1, self.workspace, self.ws_bytes, self._stream())
+        return (self.loss, top1) if want_top1 else self.loss
+
+    def train_step_tok(self, lr):
+        B.tide_draft_train_step_tok(self.ccfg, self.c_params, self.c_grads, self.c_adam, self.c_tok, self.hidden,
+                                    self.tokens, self.mask, lr, self.loss, self.workspace, self.ws_bytes, self._stream())
+        return self.loss
+
     def train_step(self, lr):
         B.tide_draft_train_step(self.ccfg, self.c_params, self.c_grads, self.c_adam, self.hidden, self.tokens,
                                 self.mask, lr, self.loss, self.workspace, self.ws_bytes, self._stream())

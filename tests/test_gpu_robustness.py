@@ -87,6 +87,31 @@ def test_poisoned_workspace_packed():
     assert guards_intact(big, tr.ws_bytes)
 
 
+def test_poisoned_workspace_token_input():
+    from paper_2602_05145_amd import runtime
+    cfg = W.get_config("small", batch=2, seq=120, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128,
+                       ffn=256, vocab=512)
+    wl = W.make_workload(cfg)
+    ti = W.make_token_input(cfg)
+    trainers = []
+    for poison in (False, True):
+        tr = runtime.trainer_from_workload(cfg, wl)
+        tr.set_token_input(ti["embed"], ti["input_ids"], ti["w_in"])
+        big = poisoned(tr) if poison else None
+        if poison:
+            tr.grad_w_in.fill_(float("nan"))
+        tr.train_step_tok(cfg["lr"])
+        sync()
+        trainers.append((tr, big))
+    (clean, _), (tr, big) = trainers
+    assert float(tr.loss.item()) == float(clean.loss.item())
+    for k in O.PARAM_NAMES:
+        assert torch.equal(tr.grads[k], clean.grads[k]), k
+    assert bool(torch.isfinite(tr.grad_w_in).all()) and torch.equal(tr.grad_w_in, clean.grad_w_in)
+    assert torch.equal(tr.w_in, clean.w_in)
+    assert guards_intact(big, tr.ws_bytes)
+
+
 def test_checkpoint_resume():
     """Parameters, both moments, the master copy and the step counter are caller-owned: copying them out and
     into a fresh trainer continues the run bit for bit."""
