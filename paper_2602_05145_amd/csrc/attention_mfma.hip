@@ -147,6 +147,33 @@ __device__ __forceinline__ void copy_out(const bf16_t* tile, bf16_t* dst, int64_
 constexpr int BQ = 128, BKV = 64;
 constexpr int KV_TILE = BKV * PITCH;  // elements
 
+// Work item (x, y, z) of an nx * ny * nz problem from the block's place in the 1-D dispatch order.
+// Work-groups go to the 8 XCDs round-robin and every XCD has its own L2.  The blocks of a "group" (all x of gy
+// consecutive y of one z: the query blocks of the heads that share a kv head, or the key blocks of one kv
+// head) stream the same K/V resp. Q/dO rows, so a whole group is given to ONE XCD, group after group, x
+// fastest.  With the plain (x, y, z) order the 16 key blocks of a kv head were spread over all XCDs and the
+// dK / dV passes hit L2 on 2 % of their requests.  Falls back to the plain order when the number of
+// groups is not a multiple of 8.
+struct Work3 { int x, y, z; };
+__device__ __forceinline__ Work3 xcd_group_work(int nx, int ny, int nz, int gy) {
+  const int n = blockIdx.x;
+  const int per_group = nx * gy, groups_per_z = ny / gy, ngroups = groups_per_z * nz;
+  int grp, in_g;
+  if ((ngroups & 7) == 0) {
+    const int xcd = n & 7, slot = n >> 3;
+    grp = (slot / per_group) * 8 + xcd;
+    in_g = slot % per_group;
+  } else {
+    grp = n / per_group;
+    in_g = n % per_group;
+  }
+  Work3 w;
+  w.x = in_g % nx;
+  w.y = (grp % groups_per_z) * gy + in_g / nx;
+  w.z = grp / groups_per_z;
+  return w;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -154,15 +181,16 @@ constexpr int KV_TILE = BKV * PITCH;  // elements
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                             float* __restrict__ lse, int Smax, int nh, int nkv,
-                                                            const int* __restrict__ cu, int64_t T) {
+                                                            const int* __restrict__ cu, int64_t T, int nseq) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   bf16_t* sK = smem;                 // [2][KV_TILE]
   bf16_t* sV = smem + 2 * KV_TILE;   // [2][KV_TILE]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int nqb = (Smax + BQ - 1) / BQ;
-  const int qb = nqb - 1 - blockIdx.x;  // heavy (late) query blocks first
-  const int h = blockIdx.y, b = blockIdx.z;
+  const Work3 wk = xcd_group_work(nqb, nh, nseq, nh / nkv);
+  const int qb = nqb - 1 - wk.x;  // heavy (late) query blocks first
+  const int h = wk.y, b = wk.z;
   const SeqView sv = seq_view(cu, b, Smax, T);
   const int S = sv.len;
   const int G = nh / nkv, kh = h / G;
@@ -275,15 +303,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
 __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, int Smax, int nh, int nkv,
-                                                           const int* __restrict__ cu, int64_t T) {
+                                                           const int* __restrict__ cu, int64_t T, int nseq) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   bf16_t* sK = smem;
   bf16_t* sV = smem + 2 * KV_TILE;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int nqb = (Smax + BQ - 1) / BQ;
-  const int qb = nqb - 1 - blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const Work3 wk = xcd_group_work(nqb, nh, nseq, nh / nkv);
+  const int qb = nqb - 1 - wk.x;
+  const int h = wk.y, b = wk.z;
   const SeqView sv = seq_view(cu, b, Smax, T);
   const int S = sv.len;
   const int G = nh / nkv, kh = h / G;
@@ -384,11 +413,12 @@ template <int WHICH>
 __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16_t* __restrict__ dqkv, int Smax, int nh, int nkv,
-                                                            const int* __restrict__ cu, int64_t T) {
+                                                            const int* __restrict__ cu, int64_t T, int nseq) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  const int jb = blockIdx.x, kh = blockIdx.y, b = blockIdx.z;  // early key blocks are the heavy ones
+  const Work3 wk = xcd_group_work((Smax + 127) / 128, nkv, nseq, 1);
+  const int jb = wk.x, kh = wk.y, b = wk.z;  // early key blocks are the heavy ones
   const SeqView sv = seq_view(cu, b, Smax, T);
   const int S = sv.len;
   const int G = nh / nkv;
@@ -496,6 +526,7 @@ bool attn_mfma_supported(const AttnArgs& a) {
   const int64_t ld = (int64_t)(a.nh + 2 * a.nkv) * D;
   if ((int64_t)a.S * ld * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit offsets inside one sequence
   if (((uintptr_t)a.qkv | (uintptr_t)a.out | (uintptr_t)a.dout | (uintptr_t)a.dqkv) & 15) return false;
+  if ((int64_t)((a.S + BQ - 1) / BQ) * a.nh * a.B >= ((int64_t)1 << 31)) return false;   // 1-D grids
   return true;
 }
 
@@ -517,9 +548,9 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
   hipError_t e = set_smem((const void*)attn_fwd_mfma_kernel, kFwdSmem, done);
   if (e != hipSuccess) return e;
-  dim3 grid((a.S + BQ - 1) / BQ, a.nh, a.B);
+  const dim3 grid((unsigned)((int64_t)((a.S + BQ - 1) / BQ) * a.nh * a.B));   // 1-D: the kernel maps blocks to work itself
   ProfScope ps("attn_fwd_mfma", 2.0 * a.B * a.nh * D * (double)a.S * (a.S + 1), 0, s);
-  hipLaunchKernelGGL(attn_fwd_mfma_kernel, grid, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
+  hipLaunchKernelGGL(attn_fwd_mfma_kernel, grid, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows, a.B);
   return hipGetLastError();
 }
 
@@ -529,11 +560,11 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
   if (e != hipSuccess) return e;
   e = set_smem((const void*)attn_dq_mfma_kernel, kFwdSmem, done_q);
   if (e != hipSuccess) return e;
-  dim3 gq((a.S + BQ - 1) / BQ, a.nh, a.B), gkv((a.S + 127) / 128, a.nkv, a.B);
+  const dim3 gq((unsigned)((int64_t)((a.S + BQ - 1) / BQ) * a.nh * a.B)), gkv((unsigned)((int64_t)((a.S + 127) / 128) * a.nkv * a.B));
   const double pairs = (double)a.B * a.nh * D * (double)a.S * (a.S + 1) / 2.0;  // (query, key, channel) triples
   {
     ProfScope ps("attn_dq_mfma", 6.0 * pairs, 0, s);   // S, dP and dQ products
-    hipLaunchKernelGGL(attn_dq_mfma_kernel, gq, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
+    hipLaunchKernelGGL(attn_dq_mfma_kernel, gq, dim3(256), kFwdSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows, a.B);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -543,8 +574,8 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
   e = set_smem((const void*)attn_dkv_mfma_kernel<1>, kDkvSmem, done_k);
   if (e != hipSuccess) return e;
   ProfScope ps("attn_dkv_mfma", 10.0 * pairs, 0, s);   // dV pass: S, dV; dK pass: S, dP, dK
-  hipLaunchKernelGGL(attn_dkv_mfma_kernel<0>, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
-  hipLaunchKernelGGL(attn_dkv_mfma_kernel<1>, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows);
+  hipLaunchKernelGGL(attn_dkv_mfma_kernel<0>, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows, a.B);
+  hipLaunchKernelGGL(attn_dkv_mfma_kernel<1>, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows, a.B);
   return hipGetLastError();
 }
 
