@@ -84,10 +84,11 @@ hipError_t launch_ce_stats(int64_t rows, int V, const void* z, int64_t ldz, cons
                            const uint8_t* mask, float* lse, float* loss_rows, int32_t* top1,
                            const int32_t* top1_idx, float* hit_rows, const int* rows_dev, int64_t rows_off,
                            int dtype, hipStream_t s);
-// dz = keep * (exp(z - lse) - onehot(label)), written over z (unscaled by 1/N)
-hipError_t launch_ce_dz(int64_t rows, int V, void* z, int64_t ldz, const int32_t* tokens,
-                        const uint8_t* mask, const float* lse, const int* rows_dev, int64_t rows_off, int dtype,
-                        hipStream_t s);
+// training pass: the outputs of ce_stats (without arg-max) and dz = keep * (exp(z - lse) - onehot(label)) written
+// over z (unscaled by 1/N), in one kernel
+hipError_t launch_ce_train(int64_t rows, int V, void* z, int64_t ldz, const int32_t* tokens, const uint8_t* mask,
+                           float* lse, float* loss_rows, const int* rows_dev, int64_t rows_off, int dtype,
+                           hipStream_t s);
 // loss = scal[1] * sum of loss_rows[0 .. *cnt); optionally accuracy = scal[1] * sum of hit_rows[0 .. *cnt)
 hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, const int* cnt, const float* scal,
                               float* loss_out, float* acc_out, int* status, hipStream_t s);

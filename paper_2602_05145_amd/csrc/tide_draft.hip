@@ -324,9 +324,12 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
       g.m_dev = cnt; g.m_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm lm_head");
     }
-    TIDE_HIP(launch_ce_stats(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, loss_rows + r0, top1, top1 ? kept_idx + r0 : nullptr, hit_rows ? hit_rows + r0 : nullptr, cnt, r0, dt, s), "ce stats");
-    if (!train) continue;
-    TIDE_HIP(launch_ce_dz(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, cnt, r0, dt, s), "ce dz");
+    if (train) {
+      TIDE_HIP(launch_ce_train(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, loss_rows + r0, cnt, r0, dt, s), "ce train");
+    } else {
+      TIDE_HIP(launch_ce_stats(rows, (int)p.V, z, p.ldz, tokens_c + r0, mask_c + r0, lse + r0, loss_rows + r0, top1, top1 ? kept_idx + r0 : nullptr, hit_rows ? hit_rows + r0 : nullptr, cnt, r0, dt, s), "ce stats");
+      continue;
+    }
     {
       // dyhat = (1/N) dZ W_lm
       GemmArgs g = gemm_args(kNN, rows, p.d, p.V, z, p.ldz, P->w_lm, p.d, ws + p.dyhat + (size_t)r0 * p.d * p.es, p.d, dt, dt);
