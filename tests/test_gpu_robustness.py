@@ -169,3 +169,44 @@ def test_status_word_flags_malformed_offsets_and_non_finite_loss():
     tr.forward()
     sync()
     assert tr.status() == 1 and not np.isfinite(float(tr.loss.item()))
+
+
+def test_forward_and_eval_replay_from_a_hip_graph():
+    """The forward-only entry points enqueue kernels and nothing else (no allocation, no memset, no host
+    synchronisation), so a caller can capture them into a HIP graph.  The replays (with eager work and
+    synchronisations in between, and new inputs written into the captured buffers) must match eager calls."""
+    from paper_2602_05145_amd import runtime
+    cfg = W.get_config("small", batch=2, seq=160, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128,
+                       ffn=264, vocab=1000)
+    wl = W.make_workload(cfg)
+    tr = runtime.trainer_from_workload(cfg, wl)
+    eager = runtime.trainer_from_workload(cfg, wl)
+    tr.eval()                                              # warm-up: one-time function attributes are set outside the capture
+    sync()
+    acc = torch.zeros(1, dtype=torch.float32, device=tr.device)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            from paper_2602_05145_amd import binding as B
+            B.tide_draft_eval(tr.ccfg, tr.c_params, tr.hidden, tr.tokens, tr.mask, tr.loss, acc, tr.workspace, tr.ws_bytes,
+                              torch.cuda.current_stream().cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(3):
+        wl_i = W.make_workload(cfg, seed=500 + i)
+        for dst, src in ((tr.hidden, wl_i["hidden"]), (eager.hidden, wl_i["hidden"])):
+            dst.copy_(torch.from_numpy(src).to(dst.device).to(dst.dtype))
+        for t in (tr, eager):
+            t.tokens.copy_(torch.from_numpy(wl_i["tokens"]).to(t.device))
+            t.mask.copy_(torch.from_numpy(wl_i["mask"]).to(t.device))
+        tr.loss.fill_(-1.0)
+        acc.fill_(-1.0)
+        sync()
+        graph.replay()
+        sync()
+        loss_e, acc_e = eager.eval()
+        sync()
+        assert float(tr.loss.item()) == float(loss_e.item()), i
+        assert float(acc.item()) == float(acc_e.item()), i
+        assert tr.status() == 0
