@@ -224,7 +224,13 @@ const char *tide_last_error(void);
  * "yhat", "lse", "dyhat", "dx2", "dx1", "dx0", "dqkv", ...; activations have the
  * config's dtype, "lse"/"r1"/"r2"/"r3" are float); "lm_rows" returns the number
  * of rows per logits block instead.  -1 if the name or config is unknown.  After
- * a training step "gt"/"u" hold their gradients.  For tests and profiling.  *
+ * a training step "gt"/"u" hold their gradients.  For tests and profiling.
+ * Rows: a position without loss acts on the result only through its key and value, so everything after the
+ * attention runs on the selected positions alone (those with loss; every position when top1_out is given).
+ * "x0", "a", "qkv", "A", "dA", "dx1", "dx0", "dqkv", "da" have one row per position; "x1", "bn", "gt", "u", "h",
+ * "x2", "yhat", "dyhat", "dx2", "dh", "dbn", "A_c", "x0_c", "dx1_c", "dA_c" hold the selected positions densely,
+ * row i being position "kept_idx"[i] (int32, "cnt" of them; "row_pos" is the inverse, -1 where not selected).
+ *
  * "status" names a device int32 that every forward / eval / train call rewrites: 0 when all is well, else
  * bit 0 (value 1) = the loss came out NaN or infinite, bit 1 (value 2) = packed batch whose cu_seqlens is not
  * ascending inside [0, batch*seq] or holds a sequence longer than max_seqlen (the kernels clamp such offsets
