@@ -113,7 +113,10 @@ typedef struct tide_adam_state {
 } tide_adam_state;
 
 /* Bytes of DEVICE scratch the two calls below need for this config (the larger
- * of the two).  Returns 0 if the config is invalid (see tide_last_error). */
+ * of the two).  Returns 0 if the config is invalid (see tide_last_error).  The largest part is the logit
+ * buffer, batch*seq x vocab elements when that is at most 16 GiB (8.4 GB at the 8B shape), else one row block of
+ * at most 6 GiB; the environment variable TIDE_LOGIT_BUFFER_LIMIT_MB replaces the 16 GiB limit (read on every
+ * call: keep it unchanged between this call and the calls that use the workspace). */
 size_t tide_draft_workspace_bytes(const tide_draft_config *cfg);
 
 /* Forward only (what the evaluation step of the paper's Algorithm 1 runs on held-out signals):

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include <mutex>
@@ -66,7 +67,7 @@ bool check_config(const tide_draft_config* c) {
 
 // ---- workspace plan ----------------------------------------------------------------------------
 struct Plan {
-  int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows;
+  int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows, z_rows;
   size_t es;  // activation element size
   // offsets (bytes)
   size_t scal, cnt, status, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, rope_cs, x0, r1, a, qkv, attn_lse, A, A_c, x0_c, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
@@ -97,13 +98,22 @@ Plan make_plan(const tide_draft_config* c) {
   p.V = c->vocab;
   p.ldz = (int64_t)align_up((size_t)p.V, 64);
   p.es = c->dtype == TIDE_DTYPE_BF16 ? 2 : 4;
-  // The logits exist only for a block of rows at a time: half of the batch, at most 16384 rows and 6 GiB.
-  // Larger blocks mean fewer read-modify-write passes over dW_lm (one per block after the first): at the
-  // 8B shape 16384 rows measured 3 ms per step faster than 8192, and one block of 32768 no better.
+  // The LM head works by blocks of lm_rows rows: half of the batch, at most 16384 rows (the forward and the
+  // input-gradient products measured faster at that height than over all rows at once).  The logit buffer
+  // holds ALL rows when that takes at most 16 GiB: the logit gradients of every block are then still there
+  // after the loop and dW_lm is one product over all rows, without a read-modify-write pass over the fp32
+  // dW_lm per block (1 ms per step at the 8B shape).  Otherwise it holds one block (at most 6 GiB) and
+  // dW_lm accumulates block by block.
   int64_t rows = (int64_t)align_up((size_t)((p.T + 1) / 2), 64);
   if (rows > 16384) rows = 16384;
-  while (rows > 256 && (size_t)rows * p.ldz * p.es > ((size_t)6 << 30)) rows /= 2;
   if (rows > p.T) rows = p.T;
+  p.z_rows = p.T;
+  size_t limit = (size_t)16 << 30;
+  if (const char* e = std::getenv("TIDE_LOGIT_BUFFER_LIMIT_MB")) limit = (size_t)std::strtoull(e, nullptr, 10) << 20;   // tests force the block-wise path
+  if ((size_t)p.T * p.ldz * p.es > limit) {
+    while (rows > 256 && (size_t)rows * p.ldz * p.es > ((size_t)6 << 30)) rows /= 2;
+    p.z_rows = rows;
+  }
   p.lm_rows = rows;
   const size_t T = (size_t)p.T, es = p.es;
   Bump b;
@@ -138,7 +148,7 @@ Plan make_plan(const tide_draft_config* c) {
   p.lse = b.take(T * 4);
   p.loss_rows = b.take(T * 4);
   p.hit_rows = b.take(T * 4);
-  p.z = b.take((size_t)p.lm_rows * p.ldz * es);
+  p.z = b.take((size_t)p.z_rows * p.ldz * es);
   p.fwd_end = b.off;
   p.dyhat = b.take(T * p.d * es);
   p.dx2 = b.take(T * p.d * es);
@@ -313,12 +323,13 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
   float* loss_rows = (float*)(ws + p.loss_rows);
   float* hit_rows = acc_out ? (float*)(ws + p.hit_rows) : nullptr;
   char* yhat_c = ws + p.yhat;   // dense over the selected rows, as everything after the attention
-  char* z = ws + p.z;
   (void)tokens; (void)mask;
+  const bool all_rows = p.z_rows >= p.T;   // the logit buffer holds every row (see make_plan)
   int blk = 0;
   for (int64_t r0 = 0; r0 < p.T; r0 += p.lm_rows, ++blk) {
     const int64_t rows = (p.T - r0 < p.lm_rows) ? (p.T - r0) : p.lm_rows;
     const char* yb = yhat_c + (size_t)r0 * p.d * p.es;
+    char* z = ws + p.z + (all_rows ? (size_t)r0 * p.ldz * p.es : 0);
     {
       GemmArgs g = gemm_args(kNT, rows, p.V, p.d, yb, p.d, P->w_lm, p.d, z, p.ldz, dt, dt);
       g.m_dev = cnt; g.m_off = r0;
@@ -337,14 +348,21 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
       g.m_dev = cnt; g.m_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm dyhat");
     }
-    {
-      // dW_lm (+)= (1/N) dZ^T yhat
+    if (!all_rows) {
+      // dW_lm (+)= (1/N) dZ^T yhat of this block
       GemmArgs g = gemm_args(kTN, p.V, p.d, rows, z, p.ldz, yb, p.d, G->w_lm, p.d, dt, kF32);
       g.alpha_dev = scal + 1;
       g.accumulate = blk > 0;
       g.k_dev = cnt; g.k_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
     }
+  }
+  if (train && all_rows) {
+    // dW_lm = (1/N) dZ^T yhat over all selected rows at once
+    GemmArgs g = gemm_args(kTN, p.V, p.d, p.T, ws + p.z, p.ldz, yhat_c, p.d, G->w_lm, p.d, dt, kF32);
+    g.alpha_dev = scal + 1;
+    g.k_dev = cnt; g.k_off = 0;
+    TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
   }
   TIDE_HIP(launch_loss_reduce(loss_rows, hit_rows, cnt, scal, loss_out, acc_out, (int*)(ws + p.status), s), "loss reduce");
   return TIDE_OK;

@@ -42,7 +42,7 @@ def test_workspace_sizes_and_config_validation(B):
         c = B.make_config(W.get_config(name))
         assert B.tide_draft_workspace_bytes(c) > 0, name
     c = B.make_config(W.get_config("8b"))
-    assert B.tide_draft_workspace_offset(c, "lm_rows") == 16384       # logits exist for 1/2 of the rows
+    assert B.tide_draft_workspace_offset(c, "lm_rows") == 16384       # the LM head works by blocks of half the rows
     assert B.tide_draft_workspace_offset(c, "nonsense") == -1
     bad = [("n_heads", 3, "multiple"), ("hidden", 250, "hidden"), ("head_dim", 63, "hidden"),
            ("vocab", 0, "positive"), ("dtype", 7, "dtype"), ("rms_eps", 0.0, "rms_eps"), ("batch", -1, "positive")]
