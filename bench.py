@@ -133,6 +133,9 @@ def main():
                          "the device through the ingest ring (copy stream), and the step after it trains on them: "
                          "the PCIe-inclusive rate.  Reported as an extra field; `value` stays the resident-input rate "
                          "measured by a default run.")
+    ap.add_argument("--token-input", action="store_true",
+                    help="time the token-input variant (features joined with the sampled token's embedding through "
+                         "W_in) instead of the benchmarked north-star path")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -152,9 +155,24 @@ def main():
     tr = DeviceTrainer(cfg, params, hidden, tokens, mask)
     lr = cfg["lr"]
     T = cfg["batch"] * cfg["seq"]
+    step = tr.train_step
+    if args.token_input:
+        # frozen embedding table (the target's vocabulary, draft width), the token sampled at every position, W_in
+        g = torch.Generator(device=dev)
+        g.manual_seed(cfg["seed"] + 7919)
+        d = cfg["hidden"]
+        adt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+        tr.embed = (torch.randn((cfg["vocab"], d), device=dev, generator=g) * 0.5).to(adt)
+        tr.input_ids = torch.randint(0, cfg["vocab"], (cfg["batch"], cfg["seq"]), device=dev, generator=g, dtype=torch.int32)
+        tr.w_in = (torch.randn((d, 2 * d), device=dev, generator=g) * 0.02).to(adt)
+        f32 = dict(dtype=torch.float32, device=dev)
+        tr.grad_w_in, tr.m_w_in, tr.v_w_in = (torch.zeros((d, 2 * d), **f32) for _ in range(3))
+        tr.master_w_in = tr.w_in.float() if cfg["dtype"] == "bf16" else None
+        tr.c_tok = B.make_token_input(tr.embed, tr.input_ids, tr.w_in, tr.grad_w_in, tr.m_w_in, tr.v_w_in, tr.master_w_in)
+        step = tr.train_step_tok
 
     for _ in range(args.warmup):
-        tr.train_step(lr)
+        step(lr)
     torch.cuda.synchronize()
 
     # timed region: exactly K steps; the library brackets each of its launches with HIP events on the
@@ -186,7 +204,7 @@ def main():
             assert rc == 0, B.tide_ingest_last_error()
             ctypes.memmove(addr, src_addr, nbytes)
             assert B.tide_ingest_submit(ring, slot, bufs[cur ^ 1], nbytes) == 0
-        tr.train_step(lr)
+        step(lr)
         if ring is not None:
             # the next step reads the freshly copied buffer: order it after the copy on the compute stream
             assert B.tide_ingest_wait(ring, slot, tr._stream()) == 0
@@ -230,6 +248,10 @@ def main():
     ps = {k: int(np.prod(v)) for k, v in W.param_shapes(cfg).items()}
     after_attention = ps["w_o"] + ps["w_gate"] + ps["w_up"] + ps["w_down"] + ps["w_lm"]
     flops = flops_all - 6.0 * after_attention * (T - n_loss)
+    if args.token_input:
+        extra = 6.0 * 2 * cfg["hidden"] * cfg["hidden"] * T   # W_in [d, 2d]: forward, dW_in (both halves) and dg, on every position
+        flops_all += extra
+        flops += extra
     prof.sort(key=lambda r: -r["total_ms"])
     kernel_ms = sum(r["total_ms"] for r in prof)
     dom = max((r for r in prof if r["kernel"].startswith("gemm_mfma")), key=lambda r: r["total_ms"], default=None)
@@ -249,7 +271,7 @@ def main():
         "ms_per_step": ms, "inputs": ("pinned host -> device through the ingest ring, overlapped with the step"
                                       if args.ingest else "resident in HBM"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": f"{cfg['name']}: batch {cfg['batch']} x seq {cfg['seq']}, 3x{cfg['target_hidden']} captured "
+        "config": {"workload": ("token-input variant, " if args.token_input else "") + f"{cfg['name']}: batch {cfg['batch']} x seq {cfg['seq']}, 3x{cfg['target_hidden']} captured "
                                f"states -> d {cfg['hidden']}, {cfg['n_heads']}/{cfg['n_kv_heads']} heads x {cfg['head_dim']}, "
                                f"FFN {cfg['ffn']}, vocab {cfg['vocab']}", "global_batch": cfg["batch"], "seq_len": cfg["seq"],
                    "params_M": W.n_params(cfg) / 1e6, "loss_positions": n_loss, "positions": T},
