@@ -305,3 +305,40 @@ def test_blockwise_logit_buffer_gives_the_same_step(monkeypatch):
             assert rel_max(a, b) <= 1e-5, k
         else:
             assert np.array_equal(a, b), k
+
+
+def _random_cfg(rng, dtype):
+    """A seeded random small shape: odd widths, every GQA ratio, vocabularies off the vector width, all mask kinds."""
+    dh = int(rng.choice([4, 8, 16, 32, 64])) if dtype == "fp32" else int(rng.choice([16, 64, 128]))
+    nkv = int(rng.integers(1, 4))
+    nh = nkv * int(rng.integers(1, 4))
+    kw = dict(batch=int(rng.integers(1, 4)), seq=int(rng.integers(1, 97)), head_dim=dh, n_heads=nh, n_kv_heads=nkv,
+              hidden=nh * dh, target_hidden=int(rng.integers(3, 70)), ffn=int(rng.integers(5, 300)),
+              vocab=int(rng.integers(7, 1500)), dtype=dtype,
+              mask=str(rng.choice(["prefix", "bernoulli", "lengths", "none"])), mask_p=float(rng.uniform(0.0, 0.9)))
+    if kw["mask"] == "lengths":
+        kw["len_lo"], kw["len_hi"] = 1, kw["seq"]
+    return kw
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shapes_fp32(seed):
+    kw = _random_cfg(np.random.default_rng(1000 + seed), "fp32")
+    print(kw, flush=True)
+    cfg = W.get_config("tiny", **kw)
+    wl = W.make_workload(cfg)
+    if wl["mask"].sum() == 0:
+        wl["mask"][0, -1] = 1
+    _check_fp32(cfg, wl)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_bf16(seed):
+    kw = _random_cfg(np.random.default_rng(2000 + seed), "bf16")
+    kw["seq"] = max(kw["seq"], 8)
+    print(kw, flush=True)
+    cfg = W.get_config("tiny", **kw)
+    wl = W.make_workload(cfg)
+    if wl["mask"].sum() < 4:
+        wl["mask"][:, -4:] = 1
+    _check_bf16(cfg, wl)
