@@ -114,3 +114,30 @@ def test_adam_first_step_law(full):
         assert float((step[big] - law).abs().max()) <= 1e-3 * lr, k
         # bf16 parameters are the master weights rounded to nearest
         assert torch.equal(tr.params[k], tr.master[k].to(torch.bfloat16)), k
+
+
+def test_sampled_rows_of_the_lm_head_gradient(full):
+    """dW_lm[v] = (1/N) sum_t keep_t (softmax(z_t)[v] - [y_t == v]) yhat_t for a few vocabulary entries, recomputed
+    in fp64 from the step's final-norm output and log-sum-exp (the rows that carry loss, in position order) and
+    the initial W_lm: the largest tensor's gradient checked at full size, launch configuration and row blocking
+    of the benchmark.  The library rounds the logits to bf16 before the softmax, hence the tolerance."""
+    cfg, tr, p0, snap = full
+    T, d, V = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["vocab"]
+    keep = ((tr.mask != 0) & (tr.tokens >= 0) & (tr.tokens < V)).reshape(-1)
+    n = int(keep.sum().item())
+    assert n > 0
+    y = tr.intermediate("yhat", (T, d))[:n].double()                    # dense over the kept rows after a training step
+    lse = tr.intermediate("lse", (T,), kind="f32")[:n].double()
+    labels = tr.tokens.reshape(-1)[keep].long()
+    counts = torch.bincount(labels, minlength=V)
+    picks = [int(counts.argmax().item()), int((counts == 0).nonzero()[0].item()), V - 1, 12345 % V]
+    for v in picks:
+        w = p0["w_lm"][v].double()
+        z = y @ w
+        p = torch.exp(z - lse) - (labels == v).double()
+        ref = (p[:, None] * y).sum(0) / n
+        got = tr.grads["w_lm"][v].double()
+        cos = float((ref * got).sum() / (ref.norm() * got.norm()))
+        err = float((ref - got).abs().max() / ref.abs().max())
+        print(f"dW_lm[{v}]: label count {int(counts[v])}, cosine {cos:.6f}, max rel err {err:.2e}", flush=True)
+        assert cos >= 0.9999 and err <= 1e-2, (v, cos, err)
