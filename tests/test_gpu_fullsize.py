@@ -141,3 +141,60 @@ def test_sampled_rows_of_the_lm_head_gradient(full):
         err = float((ref - got).abs().max() / ref.abs().max())
         print(f"dW_lm[{v}]: label count {int(counts[v])}, cosine {cos:.6f}, max rel err {err:.2e}", flush=True)
         assert cos >= 0.9999 and err <= 1e-2, (v, cos, err)
+
+
+def test_layer_weight_gradients_against_a_library_matmul_of_the_step_s_own_operands(full):
+    """Every dW = dY^T X of the layer at full size (the 256x256-tile TN kernel, K trimmed on the device to the rows
+    that carry loss) against an fp32 library matmul of the very operands the step left in its workspace.  Checks
+    the kernel, its tile order and the row selection; what produced the operands is checked elsewhere."""
+    cfg, tr, p0, snap = full
+    T, d, F = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["ffn"]
+    nq = cfg["n_heads"] * cfg["head_dim"]
+    nqkv = nq + 2 * cfg["n_kv_heads"] * cfg["head_dim"]
+    KH = cfg["n_capture"] * cfg["target_hidden"]
+    keep = ((tr.mask != 0) & (tr.tokens >= 0) & (tr.tokens < cfg["vocab"])).reshape(-1)
+    n = int(keep.sum().item())
+    cases = [("w_down", "dx2", d, "h", F, n), ("w_gate", "gt", F, "bn", d, n), ("w_up", "u", F, "bn", d, n),
+             ("w_o", "dx1_c", d, "A_c", nq, n), ("w_qkv", "dqkv", nqkv, "a", d, T)]
+    for name, dy_name, m, x_name, k, rows in cases:
+        dy = tr.intermediate(dy_name, (T, m))[:rows].float()
+        x = tr.intermediate(x_name, (T, k))[:rows].float()
+        ref = dy.T @ x
+        got = tr.grads[name]
+        err = float((ref - got).abs().max() / ref.abs().max())
+        print(f"dW {name}: max rel err {err:.2e} over {rows} rows", flush=True)
+        assert err <= 1e-4, (name, err)
+        del dy, x, ref
+    ref = tr.intermediate("dx0", (T, d)).float().T @ tr.hidden.reshape(T, KH).float()
+    err = float((ref - tr.grads["w_fc"]).abs().max() / ref.abs().max())
+    print(f"dW w_fc: max rel err {err:.2e}", flush=True)
+    assert err <= 1e-4, err
+
+
+def test_forward_and_input_gradient_products_against_a_library_matmul(full):
+    """The NT (forward, fused residual) and NN (input gradient, one of them over two operand pairs) products of
+    the layer at full size against an fp32 library matmul of the operands left in the workspace and the
+    initial weights.  Outputs are bf16: a result may differ from the rounded reference by one bf16 step."""
+    cfg, tr, p0, snap = full
+    T, d, F = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["ffn"]
+    nq = cfg["n_heads"] * cfg["head_dim"]
+    nqkv = nq + 2 * cfg["n_kv_heads"] * cfg["head_dim"]
+    keep = ((tr.mask != 0) & (tr.tokens >= 0) & (tr.tokens < cfg["vocab"])).reshape(-1)
+    n = int(keep.sum().item())
+
+    def buf(name, cols, rows):
+        return tr.intermediate(name, (T, cols))[:rows].float()
+
+    def check(what, got, ref):
+        scale = float(ref.abs().max())
+        err = float(((got - ref).abs() / (ref.abs() + 1e-3 * scale)).max())
+        print(f"{what}: max error relative to |ref| + 1e-3 max|ref| = {err:.2e}", flush=True)
+        assert err <= 2.0 ** -7, (what, err)
+
+    W_ = {k: p0[k].float() for k in ("w_o", "w_down", "w_gate", "w_up", "w_qkv")}
+    check("x1 = x0 + A W_o^T", buf("x1", d, n), buf("x0_c", d, n) + buf("A_c", nq, n) @ W_["w_o"].T)
+    check("x2 = x1 + h W_down^T", buf("x2", d, n), buf("x1", d, n) + buf("h", F, n) @ W_["w_down"].T)
+    check("dh = dx2 W_down", buf("dh", F, n), buf("dx2", d, n) @ W_["w_down"])
+    check("dbn = dGate W_gate + dUp W_up", buf("dbn", d, n), buf("gt", F, n) @ W_["w_gate"] + buf("u", F, n) @ W_["w_up"])
+    check("dA = dx1 W_o", buf("dA_c", nq, n), buf("dx1_c", d, n) @ W_["w_o"])
+    check("da = dqkv W_qkv", buf("da", d, T), buf("dqkv", nqkv, T) @ W_["w_qkv"])
