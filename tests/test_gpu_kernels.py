@@ -184,6 +184,8 @@ def _attn_case(B, dtype, Bn, S, nh, nkv, dh, seed):
 @pytest.mark.parametrize("dtype,shape", [
     ("fp32", (2, 70, 4, 2, 64)), ("fp32", (1, 1, 2, 1, 8)), ("fp32", (1, 130, 2, 2, 16)),
     ("bf16", (2, 70, 4, 2, 64)), ("bf16", (1, 200, 4, 1, 128)), ("bf16", (2, 333, 4, 2, 128)),
+    # batch * kv heads a multiple of 8: the blocks of a kv head are then numbered so that they share an XCD
+    ("bf16", (4, 300, 4, 2, 128)), ("bf16", (8, 129, 2, 1, 128)), ("bf16", (16, 40, 3, 3, 128)),
 ])
 def test_attention_fwd_bwd(B, dtype, shape):
     got, ref, lse, lse_ref, dgot, dref, (nq, nk) = _attn_case(B, dtype, *shape, seed=sum(shape))
