@@ -215,3 +215,50 @@ def test_mfma_probe_runs_and_counts(B):
     import ctypes
     assert B.lib().tide_mfma_probe(0, 10, ctypes.c_void_p(sink.data_ptr()), None, s) == B.TIDE_ERR_CONFIG
     assert B.lib().tide_mfma_probe(4, 10, None, None, s) == B.TIDE_ERR_NULL
+
+
+@pytest.mark.parametrize("shape", [(16, 2048, 32, 8), (2, 8192, 32, 8)])
+def test_attention_at_benchmark_shapes_against_library_attention(B, shape):
+    """Forward and backward of the flash kernels at the benchmark's head layout and sequence lengths against the
+    framework's scaled_dot_product_attention (fp32 math on the same bf16 inputs, autograd for the gradients):
+    an independent implementation at sizes the CPU oracle cannot reach."""
+    import torch.nn.functional as F
+    Bn, S, nh, nkv = shape
+    dh, G = 128, nh // nkv
+    g = torch.Generator(device=DEV)
+    g.manual_seed(S)
+    ld = (nh + 2 * nkv) * dh
+    qkv = torch.randn((Bn * S, ld), device=DEV, generator=g).to(torch.bfloat16)
+    dout = torch.randn((Bn * S, nh * dh), device=DEV, generator=g).to(torch.bfloat16)
+    out = torch.empty((Bn * S, nh * dh), device=DEV, dtype=torch.bfloat16)
+    lse = torch.empty(Bn * nh * S, device=DEV)
+    delta = torch.empty(Bn * nh * S, device=DEV)
+    dqkv = torch.empty_like(qkv)
+    print(f"attention at B={Bn} S={S} nh={nh} nkv={nkv}", flush=True)
+    B.tide_attention_fwd(Bn, S, nh, nkv, dh, qkv, out, lse, DT["bf16"], stream())
+    B.tide_attention_bwd(Bn, S, nh, nkv, dh, qkv, out, dout, lse, delta, dqkv, DT["bf16"], stream())
+    sync()
+    # reference: one batch element at a time to bound memory (fp32 scores of 32 heads x S x S)
+    worst = {}
+    for b in range(0, Bn, max(1, Bn // 2)):                      # two batch elements are enough
+        rows = slice(b * S, (b + 1) * S)
+        x = qkv[rows].float().requires_grad_(True)
+        q = x[:, :nh * dh].reshape(S, nh, dh).transpose(0, 1)
+        k = x[:, nh * dh:(nh + nkv) * dh].reshape(S, nkv, dh).transpose(0, 1).repeat_interleave(G, dim=0)
+        v = x[:, (nh + nkv) * dh:].reshape(S, nkv, dh).transpose(0, 1).repeat_interleave(G, dim=0)
+        chunks = []
+        for h0 in range(0, nh, 8):                               # 8 heads at a time
+            chunks.append(F.scaled_dot_product_attention(q[h0:h0 + 8][None], k[h0:h0 + 8][None], v[h0:h0 + 8][None],
+                                                         is_causal=True)[0])
+        ref = torch.cat(chunks, 0).transpose(0, 1).reshape(S, nh * dh)
+        ref.backward(dout[rows].float())
+        for name, got, want in (("out", out[rows].float(), ref.detach()), ("dq", dqkv[rows, :nh * dh].float(), x.grad[:, :nh * dh]),
+                                ("dk", dqkv[rows, nh * dh:(nh + nkv) * dh].float(), x.grad[:, nh * dh:(nh + nkv) * dh]),
+                                ("dv", dqkv[rows, (nh + nkv) * dh:].float(), x.grad[:, (nh + nkv) * dh:])):
+            cos = float((got * want).sum() / (got.norm() * want.norm()))
+            err = float((got - want).abs().max() / want.abs().max())
+            worst[name] = (min(cos, worst.get(name, (1.0, 0.0))[0]), max(err, worst.get(name, (1.0, 0.0))[1]))
+        del x, q, k, v, ref, chunks
+    print(worst, flush=True)
+    for name, (cos, err) in worst.items():
+        assert cos >= 0.9999 and err <= 1e-2, (name, cos, err)
