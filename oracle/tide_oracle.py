@@ -41,7 +41,8 @@ row), x0 = [g ; e] W_in^T with one more trainable tensor W_in [d, 2d].  The TIDE
 paper fixes none of this (no equation, no number), so against the paper this
 variant is "parity unpinned"; what pins it is mathematics: W_in = [I | 0]
 reproduces the base model exactly, W_in = [0 | I] makes the result independent
-of the captured states, and central finite differences on W_in and W_fc.  The
+of the captured states, central finite differences on W_in and W_fc, and torch CPU
+fp64 autograd over F.embedding / torch.cat / F.linear.  The
 multi-step training unroll of that architecture is not part of this oracle.
 """
 from __future__ import annotations

@@ -47,8 +47,9 @@ def test_finite_differences_every_tensor(kw):
             assert abs(fd - an) <= 1e-6 * max(1.0, abs(fd)) + 2e-8, (name, i, fd, an)
 
 
-def _torch_reference(cfg, params, wl):
-    """Same model composed from torch CPU fp64 library primitives + autograd."""
+def _torch_reference(cfg, params, wl, tok_in=None):
+    """Same model composed from torch CPU fp64 library primitives + autograd (tok_in: the token-input variant's
+    embedding table and ids, joined through F.embedding, torch.cat and F.linear)."""
     import torch.nn.functional as F
     B, S = cfg["batch"], cfg["seq"]
     nh, nkv, dh = cfg["n_heads"], cfg["n_kv_heads"], cfg["head_dim"]
@@ -59,6 +60,10 @@ def _torch_reference(cfg, params, wl):
         return g * x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + cfg["rms_eps"])
 
     x0 = F.linear(Hc, P["w_fc"])
+    if tok_in is not None:
+        E = torch.tensor(np.asarray(tok_in["embed"], np.float64))
+        ids = torch.tensor(np.asarray(tok_in["input_ids"]).reshape(-1).astype(np.int64))
+        x0 = F.linear(torch.cat([x0, F.embedding(ids, E)], dim=1), P["w_in"])
     a = rms(x0, P["g1"])
     qkv = F.linear(a, P["w_qkv"])
     nq, nk = nh * dh, nkv * dh
@@ -549,6 +554,16 @@ def test_packed_equals_right_padded_batch():
 
 
 # ------------------------------------------------------------------ token-input variant
+def test_token_input_against_torch_autograd():
+    cfg, wl, params, tok = _tok_setup(batch=2, seq=9, n_heads=4, n_kv_heads=2, hidden=16, head_dim=4, ffn=12, vocab=37)
+    loss, cache = O.forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], tok=tok)
+    grads = O.backward(cfg, params, cache, wl["tokens"], wl["mask"])
+    tl, tg, _ = _torch_reference(cfg, params, wl, tok_in=tok)
+    assert abs(loss - tl) <= 1e-12 * abs(tl)
+    for k in O.PARAM_NAMES + ("w_in",):
+        np.testing.assert_allclose(grads[k], tg[k], rtol=1e-9, atol=1e-13, err_msg=k)
+
+
 def _tok_setup(**kw):
     cfg = micro_cfg(**kw)
     wl = micro_workload(cfg)
