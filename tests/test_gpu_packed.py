@@ -85,6 +85,36 @@ def test_packed_bf16_against_oracle(lens, tail):
         assert cosine(g[k], g_ref[k]) >= 0.999, (k, cosine(g[k], g_ref[k]))
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_packed_random_segmentations_bf16(seed):
+    """Seeded random segmentations: 1 to 24 sequences of 0 to 300 rows (several empty ones, runs of length 1,
+    batch x kv heads sometimes a multiple of 8, which switches the attention's block numbering), random tail."""
+    rng = np.random.default_rng(300 + seed)
+    n = int(rng.choice([1, 3, 8, 16, 24]))
+    lens = [int(x) for x in rng.integers(0, 301, size=n)]
+    for i in rng.choice(n, size=max(1, n // 4), replace=False):
+        lens[int(i)] = int(rng.choice([0, 1, 2]))
+    if sum(lens) == 0:
+        lens[0] = 17
+    tail = int(rng.integers(0, 20))
+    nkv = int(rng.choice([1, 2]))
+    cfg = W.get_config("small", batch=1, seq=64, target_hidden=48, hidden=256, n_heads=2, n_kv_heads=nkv,
+                       head_dim=128, ffn=200, vocab=777)
+    print(f"seed {seed}: {n} sequences, {sum(lens)} rows + {tail} padding, n_kv_heads {nkv}", flush=True)
+    c, wl, cu = ragged_workload(cfg, lens, tail, seed=400 + seed)
+    p0 = {k: np.asarray(v, np.float64) for k, v in wl["params"].items()}
+    T = c["seq"]
+    loss_ref, g_ref, _ = O.train_quantities_packed(c, p0, wl["hidden"].astype(np.float64).reshape(T, -1), wl["tokens"].reshape(-1),
+                                                   wl["mask"].reshape(-1), cu)
+    tr, loss_fwd, top1, loss = run_packed(c, wl, cu, cfg["lr"])
+    assert tr.status() == 0
+    assert abs(loss - loss_ref) <= 1e-2 * abs(loss_ref), (loss, loss_ref)
+    g = tr.host(tr.grads)
+    for k in O.PARAM_NAMES:
+        assert np.all(np.isfinite(g[k])), k
+        assert cosine(g[k], g_ref[k]) >= 0.999, (k, cosine(g[k], g_ref[k]))
+
+
 def test_packed_equals_right_padded_fixed_batch_on_the_gpu():
     """The same sequences through the fixed-layout entry point (right-padded, pads masked) and packed."""
     from paper_2602_05145_amd import runtime
