@@ -276,6 +276,7 @@ def main():
                                f"FFN {cfg['ffn']}, vocab {cfg['vocab']}", "global_batch": cfg["batch"], "seq_len": cfg["seq"],
                    "params_M": W.n_params(cfg) / 1e6, "loss_positions": n_loss, "positions": T},
         "tflops_per_step_executed": flops / 1e12, "tflops_per_step_all_positions": flops_all / 1e12,
+        "loss_positions_per_s": n_loss / (ms * 1e-3),
         "achieved_tflops": flops / (ms * 1e-3) / 1e12,
         "mfu_vs_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "mfu_vs_bf16_peak_all_positions": flops_all / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
