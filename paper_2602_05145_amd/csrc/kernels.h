@@ -42,9 +42,10 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);  // picks the MFMA pat
 // Row plan of the LM head.  keep_t = mask_t != 0 and 0 <= token_t < V.  scal[0] = N = max(1, #keep),
 // scal[1] = 1/N.  The rows the LM head processes are the kept ones (or all of them if select_all):
 // kept_idx[0..cnt[0]) lists them in ascending order, row_pos[t] is the position of row t in that list or -1.
+size_t plan_rows_scratch_bytes(int64_t T);   // blk_counts below
 hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
                             float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, const int* cu, int nseq,
-                            int max_len, uint8_t* mask_eff, int* status, hipStream_t s);
+                            int max_len, uint8_t* mask_eff, int* status, int* blk_counts, hipStream_t s);
 // packed batches (cu = device offsets of nseq sequences): position of each row in its sequence, and zeroing
 // of the rows of a [T, row_bytes] array that no sequence owns
 hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int max_len, int32_t* pos, hipStream_t s);

@@ -70,7 +70,7 @@ struct Plan {
   int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows, z_rows;
   size_t es;  // activation element size
   // offsets (bytes)
-  size_t scal, cnt, status, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, rope_cs, x0, r1, a, qkv, attn_lse, A, A_c, x0_c, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
+  size_t scal, cnt, status, plan_cnt, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, rope_cs, x0, r1, a, qkv, attn_lse, A, A_c, x0_c, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
   size_t fwd_end;
   size_t dyhat, dx2, dx1_c, dx1, dx0, dh, dbn, dA_c, dA, dqkv, da, delta, dg_partial;
   size_t g0, e0, dg0;   // token-input variant: projected features, looked-up embeddings, gradient of the features
@@ -120,6 +120,7 @@ Plan make_plan(const tide_draft_config* c) {
   p.scal = b.take(64);
   p.cnt = b.take(64);
   p.status = b.take(64);
+  p.plan_cnt = b.take(plan_rows_scratch_bytes(p.T));
   p.kept_idx = b.take(T * 4);
   p.row_pos = b.take(T * 4);
   p.tokens_c = b.take(T * 4);
@@ -253,7 +254,7 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
   const int dt = c->dtype;
   const int64_t T = p.T;
   float* scal = (float*)(ws + p.scal);
-  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), q.cu, q.n, q.max_len, (uint8_t*)(ws + p.mask_eff), (int*)(ws + p.status), s), "plan_rows");
+  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), q.cu, q.n, q.max_len, (uint8_t*)(ws + p.mask_eff), (int*)(ws + p.status), (int*)(ws + p.plan_cnt), s), "plan_rows");
   if (q.cu) TIDE_HIP(launch_seq_pos(q.cu, q.n, T, q.max_len, (int32_t*)(ws + p.seq_pos), s), "sequence positions");
   if (!tok) {
     // x0 = Hcat W_fc^T
