@@ -1,0 +1,119 @@
+"""Pins for the multi-step unroll oracle (forward).  The unroll stands for chain drafting with the true tokens
+as inputs: process the verified prefix once, then append one position per draft step, each fed the layer output
+of the step before.  That process is written here on its own, with a growing key/value cache, one start position
+at a time and from plain NumPy (none of the oracle's functions), and every step of the oracle's batched unroll
+must reproduce it row by row."""
+import numpy as np
+import pytest
+
+from oracle import tide_oracle as O
+from oracle import unroll_oracle as U
+from tests.helpers import micro_cfg, micro_workload
+
+
+def _token_input(cfg, seed=3):
+    rng = np.random.default_rng(seed)
+    d = cfg["hidden"]
+    return dict(embed=rng.standard_normal((cfg["vocab"], d)), input_ids=rng.integers(0, cfg["vocab"], (cfg["batch"], cfg["seq"])),
+                w_in=0.3 * rng.standard_normal((d, 2 * d)))
+
+
+class ChainDrafter:
+    """One sequence, one start position: the layer as a key/value-cache decoder."""
+
+    def __init__(self, cfg, p, w_in=None, embed=None):
+        self.c, self.p, self.w_in, self.embed = cfg, p, w_in, embed
+        self.K, self.V = [], []   # one [n_kv, d_h] entry per cached position
+
+    def _norm(self, x, g):
+        return g * x / np.sqrt(np.mean(x * x) + self.c["rms_eps"])
+
+    def _rot(self, x, pos):
+        dh = self.c["head_dim"]
+        half = dh // 2
+        ang = pos * self.c["rope_theta"] ** (-2.0 * np.arange(half) / dh)
+        x1, x2 = x[:, :half], x[:, half:]
+        return np.concatenate([x1 * np.cos(ang) - x2 * np.sin(ang), x2 * np.cos(ang) + x1 * np.sin(ang)], axis=1)
+
+    def step(self, feat, token_id, pos):
+        """Appends position `pos` (feature vector, id of its input token) and returns (layer output, logits)."""
+        c, p = self.c, self.p
+        nh, nkv, dh = c["n_heads"], c["n_kv_heads"], c["head_dim"]
+        x0 = feat if self.w_in is None else self.w_in @ np.concatenate([feat, self.embed[token_id]])
+        qkv = p["w_qkv"] @ self._norm(x0, p["g1"])
+        q = self._rot(qkv[:nh * dh].reshape(nh, dh), pos)
+        k = self._rot(qkv[nh * dh:(nh + nkv) * dh].reshape(nkv, dh), pos)
+        v = qkv[(nh + nkv) * dh:].reshape(nkv, dh)
+        self.K.append(k)
+        self.V.append(v)
+        out = np.zeros((nh, dh))
+        for h in range(nh):
+            kh = h // (nh // nkv)
+            sc = np.array([q[h] @ kk[kh] for kk in self.K]) / np.sqrt(dh)
+            w = np.exp(sc - sc.max())
+            w /= w.sum()
+            out[h] = sum(wi * vv[kh] for wi, vv in zip(w, self.V))
+        x1 = x0 + p["w_o"] @ out.reshape(-1)
+        bn = self._norm(x1, p["g2"])
+        gt = p["w_gate"] @ bn
+        x2 = x1 + p["w_down"] @ (gt / (1.0 + np.exp(-gt)) * (p["w_up"] @ bn))
+        return x2, p["w_lm"] @ self._norm(x2, p["g3"])
+
+
+@pytest.mark.parametrize("token_input", [False, True])
+@pytest.mark.parametrize("kw", [dict(seq=7), dict(seq=9, n_heads=4, n_kv_heads=2, hidden=16, head_dim=4, ffn=10, vocab=13)])
+def test_unroll_equals_chain_drafting_with_a_key_value_cache(kw, token_input):
+    cfg = micro_cfg(mask="none", **kw)
+    wl = micro_workload(cfg)
+    p = {k: np.asarray(v, np.float64) for k, v in wl["params"].items()}
+    tok = _token_input(cfg) if token_input else None
+    params = dict(wl["params"], **({O.TOKEN_PARAM: tok["w_in"]} if tok else {}))
+    n_steps, S = 3, cfg["seq"]
+    steps = U.unroll_forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], n_steps, tok=tok)
+    feats = wl["hidden"].reshape(S, -1) @ p["w_fc"].T
+    ids = tok["input_ids"].reshape(-1) if tok else np.zeros(S, int)
+    labels = wl["tokens"].reshape(-1)
+    nll = [[] for _ in range(n_steps)]
+    for t0 in range(S):
+        dr = ChainDrafter(cfg, p, tok["w_in"] if tok else None, tok["embed"] if tok else None)
+        for pos in range(t0 + 1):                       # the verified prefix, captured features
+            out, z = dr.step(feats[pos], ids[pos], pos)
+        for s in range(1, n_steps + 1):
+            pos = t0 + s - 1
+            if pos >= S:
+                break
+            if s > 1:
+                out, z = dr.step(out, ids[pos], pos)    # fed its own output, the true token as input
+            np.testing.assert_allclose(steps[s - 1]["x2"][t0], out, rtol=1e-10, atol=1e-12)
+            assert steps[s - 1]["top1"][t0] == int(np.argmax(z))
+            nll[s - 1].append(np.log(np.sum(np.exp(z - z.max()))) + z.max() - z[labels[pos]])
+    for s in range(n_steps):
+        assert steps[s]["n"] == S - s == len(nll[s])
+        assert abs(steps[s]["loss"] - np.mean(nll[s])) <= 1e-12 * max(1.0, abs(steps[s]["loss"]))
+
+
+def test_one_step_is_the_ordinary_forward_and_masks_shift_with_the_labels():
+    cfg = micro_cfg(batch=2, seq=6, mask="bernoulli", mask_p=0.4)
+    wl = micro_workload(cfg)
+    loss, cache = O.forward(cfg, wl["params"], wl["hidden"], wl["tokens"], wl["mask"], want_top1=True)
+    steps = U.unroll_forward(cfg, wl["params"], wl["hidden"], wl["tokens"], wl["mask"], 3)
+    assert steps[0]["loss"] == loss and np.array_equal(steps[0]["top1"], cache["top1"])
+    np.testing.assert_array_equal(steps[0]["x2"], cache["x2"])
+    for s, st in enumerate(steps):
+        assert np.array_equal(st["mask"][:, :cfg["seq"] - s], wl["mask"][:, s:])
+        assert not st["mask"][:, cfg["seq"] - s:].any()           # rows whose position left the sequence
+        assert np.array_equal(st["tokens"][:, :cfg["seq"] - s], wl["tokens"][:, s:])
+        assert st["n"] == max(1, int((st["mask"] != 0).sum()))
+
+
+def test_later_steps_do_not_see_other_rows_later_keys():
+    """Changing the captured states of the last row changes no other row at any step (causality carries over)."""
+    cfg = micro_cfg(seq=6, mask="none")
+    wl = micro_workload(cfg)
+    a = U.unroll_forward(cfg, wl["params"], wl["hidden"], wl["tokens"], wl["mask"], 3)
+    h2 = wl["hidden"].copy()
+    h2[0, -1] += 1.0
+    b = U.unroll_forward(cfg, wl["params"], h2, wl["tokens"], wl["mask"], 3)
+    for s in range(3):
+        np.testing.assert_array_equal(a[s]["x2"][:-1], b[s]["x2"][:-1])
+        assert np.abs(a[s]["x2"][-1] - b[s]["x2"][-1]).max() > 1e-6
