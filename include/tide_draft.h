@@ -191,7 +191,7 @@ int tide_draft_train_step(const tide_draft_config *cfg, tide_draft_tensors *para
  *     x0 = [g ; e] W_in^T
  * and everything after x0 is unchanged.  embed is frozen (no gradient); W_in is one more trainable tensor
  * with its own gradient and Adam state.  The paper restates none of this, so it is a reading of the cited
- * architecture; the multi-step training unroll of that architecture is not implemented.
+ * architecture (its multi-step unroll: tide_draft_eval_unroll below).
  *   embed       DEVICE [embed_rows, d], dtype per cfg, read-only
  *   input_ids   DEVICE int32 [B,S]: the token whose embedding joins the features of the position
  *   w_in        DEVICE [d, 2d], dtype per cfg: columns [0, d) act on g, columns [d, 2d) on e
@@ -218,6 +218,36 @@ int tide_draft_train_step_tok(const tide_draft_config *cfg, tide_draft_tensors *
                               const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
                               float lr, float *loss_out,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* Multi-step evaluation unroll (forward only).  Sec. 3.2 names EAGLE-3 as the draft architecture and Sec. 5.1
+ * fixes gamma = 3 draft tokens per round: only the first draft token of a round sees a captured feature, each
+ * later one is fed the draft layer's own output of the step before.  This call runs n_steps such steps over the
+ * whole batch with the true tokens as inputs and labels, and reports how well step s predicts the s-th token of
+ * a round.  Step 1 is tide_draft_eval (tide_draft_forward_tok's model if tok is given).  Step s >= 2, for row
+ * i of a sequence, which then stands for position i + s - 1 (rows whose position leaves the sequence carry
+ * no loss):
+ *     feature   x2 of step s-1 at row i, in place of Hcat W_fc^T (joined with embed[input_ids[i + s - 1]]
+ *               through W_in if tok is given)
+ *     RoPE      position i + s - 1
+ *     attention one softmax over the step-1 keys/values of rows 0..i and the key/value pair the row itself
+ *               produced at each of the steps 2..s
+ *     label     tokens[i + s - 1], loss_mask[i + s - 1]
+ * The paper restates none of this: it is a reading of the cited architecture.
+ *   tok           may be NULL (feature-only model); else as in tide_draft_forward_tok
+ *   n_steps       1 .. 8
+ *   loss_out      DEVICE float [n_steps]: mean cross-entropy of every step over its loss-carrying rows
+ *   accuracy_out  DEVICE float [n_steps]: top-1 accuracy of every step over the same rows
+ *   workspace     DEVICE, 256-byte aligned, at least tide_draft_unroll_workspace_bytes(cfg, n_steps) bytes
+ *                 (0 = invalid config or n_steps): one workspace of the single-step call per step plus the
+ *                 shifted inputs and own key/value pairs
+ * Fixed-layout batches only.  Enqueues kernels on `stream` and nothing else; errors as in tide_draft_forward,
+ * TIDE_ERR_CONFIG for n_steps outside [1, 8]. */
+size_t tide_draft_unroll_workspace_bytes(const tide_draft_config *cfg, int32_t n_steps);
+int tide_draft_eval_unroll(const tide_draft_config *cfg, const tide_draft_tensors *params,
+                           const tide_token_input *tok,
+                           const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                           int32_t n_steps, float *loss_out, float *accuracy_out,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* Message of the last error on the calling thread (static storage, never NULL). */
 const char *tide_last_error(void);

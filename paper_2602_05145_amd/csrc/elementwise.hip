@@ -21,12 +21,12 @@ namespace tide {
 namespace {
 struct RowFlags { int keep, sel; };
 __device__ __forceinline__ RowFlags row_flags(const int32_t* tokens, const uint8_t* mask, int64_t t, int64_t T, int V,
-                                              int select_all, int64_t v0, int64_t v1) {
+                                              int select_all, int64_t v0, int64_t v1, const uint8_t* sel_mask) {
   RowFlags f{0, 0};
   if (t < T) {
     const int tk = tokens[t];
     f.keep = (mask[t] != 0 && tk >= 0 && tk < V && t >= v0 && t < v1) ? 1 : 0;
-    f.sel = select_all ? 1 : f.keep;
+    f.sel = sel_mask ? (sel_mask[t] != 0 ? 1 : 0) : (select_all ? 1 : f.keep);
   }
   return f;
 }
@@ -35,13 +35,14 @@ __device__ __forceinline__ RowFlags row_flags(const int32_t* tokens, const uint8
 __global__ __launch_bounds__(1024) void plan_count_kernel(const int32_t* __restrict__ tokens,
                                                           const uint8_t* __restrict__ mask, int64_t T, int V,
                                                           int select_all, const int* __restrict__ cu, int nseq,
-                                                          int* __restrict__ blk_counts) {
+                                                          int* __restrict__ blk_counts,
+                                                          const uint8_t* __restrict__ sel_mask) {
   __shared__ int ws_sel[16], ws_keep[16];
   // packed batches: only rows inside [cu[0], cu[nseq]) belong to a sequence; the rest is padding
   const int64_t v0 = cu ? min(max((int64_t)cu[0], (int64_t)0), T) : 0;
   const int64_t v1 = cu ? min(max((int64_t)cu[nseq], v0), T) : T;
   const int64_t t = (int64_t)blockIdx.x * 1024 + threadIdx.x;
-  const RowFlags f = row_flags(tokens, mask, t, T, V, select_all, v0, v1);
+  const RowFlags f = row_flags(tokens, mask, t, T, V, select_all, v0, v1, sel_mask);
   int a = f.sel, k = f.keep;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) { a += __shfl_xor(a, o, 64); k += __shfl_xor(k, o, 64); }
@@ -62,7 +63,8 @@ __global__ __launch_bounds__(1024) void plan_write_kernel(const int32_t* __restr
                                                           int32_t* __restrict__ row_pos,
                                                           const int* __restrict__ cu, int nseq, int max_len,
                                                           uint8_t* __restrict__ mask_eff, int* __restrict__ status,
-                                                          const int* __restrict__ blk_counts) {
+                                                          const int* __restrict__ blk_counts,
+                                                          const uint8_t* __restrict__ sel_mask) {
   __shared__ int red_sel[16], red_keep[16], wave_sel[16];
   __shared__ int bad_cu;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(1024) void plan_write_kernel(const int32_t* __restr
   for (int o = 32; o > 0; o >>= 1) { ps += __shfl_xor(ps, o, 64); pk += __shfl_xor(pk, o, 64); }
   if (lane == 0) { red_sel[w] = ps; red_keep[w] = pk; }
   const int64_t t = (int64_t)b * 1024 + tid;
-  const RowFlags f = row_flags(tokens, mask, t, T, V, select_all, v0, v1);
+  const RowFlags f = row_flags(tokens, mask, t, T, V, select_all, v0, v1, sel_mask);
   int incl = f.sel;   // inclusive scan inside the wave
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
@@ -134,13 +136,14 @@ size_t plan_rows_scratch_bytes(int64_t T) { return (size_t)plan_blocks(T) * 2 * 
 
 hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
                             float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, const int* cu, int nseq,
-                            int max_len, uint8_t* mask_eff, int* status, int* blk_counts, hipStream_t s) {
+                            int max_len, uint8_t* mask_eff, int* status, int* blk_counts, const uint8_t* sel_mask,
+                            hipStream_t s) {
   ProfScope ps("plan_rows", 0, 24.0 * (double)T, s);
   const unsigned nb = (unsigned)plan_blocks(T);
-  hipLaunchKernelGGL(plan_count_kernel, dim3(nb), dim3(1024), 0, s, tokens, mask, T, V, select_all, cu, nseq, blk_counts);
+  hipLaunchKernelGGL(plan_count_kernel, dim3(nb), dim3(1024), 0, s, tokens, mask, T, V, select_all, cu, nseq, blk_counts, sel_mask);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(plan_write_kernel, dim3(nb), dim3(1024), 0, s, tokens, mask, T, V, select_all, scal, cnt, kept_idx, row_pos, cu, nseq, max_len, mask_eff, status, blk_counts);
+  hipLaunchKernelGGL(plan_write_kernel, dim3(nb), dim3(1024), 0, s, tokens, mask, T, V, select_all, scal, cnt, kept_idx, row_pos, cu, nseq, max_len, mask_eff, status, blk_counts, sel_mask);
   return hipGetLastError();
 }
 
@@ -553,7 +556,7 @@ hipError_t launch_rope_table(int S, int dh, float theta, float* cs, hipStream_t 
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const float* __restrict__ cs,
                                                    int S, int nrot_heads, int dh, int ld, float sgn,
-                                                   int64_t total, const int32_t* __restrict__ row_pos) {
+                                                   int64_t total, const int32_t* __restrict__ row_pos, int pos_offset) {
   // one thread per (row t, head, i < dh/2); q heads then k heads are the first nrot_heads heads of a row
   const int half = dh >> 1;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -562,7 +565,7 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const fl
   const int64_t th = idx / half;
   const int hd = (int)(th % nrot_heads);
   const int64_t t = th / nrot_heads;
-  const int pos = row_pos ? row_pos[t] : (int)(t % S);
+  const int pos = (row_pos ? row_pos[t] : (int)(t % S)) + pos_offset;
   const float c = cs[2 * ((size_t)pos * half + i)];
   const float sn = sgn * cs[2 * ((size_t)pos * half + i) + 1];
   const size_t o = (size_t)t * ld + (size_t)hd * dh + i;
@@ -575,7 +578,8 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const fl
 template <typename T>
 __global__ __launch_bounds__(256) void rope_vec8_kernel(T* __restrict__ qkv, const float* __restrict__ cs,
                                                         int S, int nrot_heads, int dh, int ld, float sgn,
-                                                        int64_t total8, const int32_t* __restrict__ row_pos) {
+                                                        int64_t total8, const int32_t* __restrict__ row_pos,
+                                                        int pos_offset) {
   const int half = dh >> 1, h8 = half >> 3;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total8) return;
@@ -583,7 +587,7 @@ __global__ __launch_bounds__(256) void rope_vec8_kernel(T* __restrict__ qkv, con
   const int64_t th = idx / h8;
   const int hd = (int)(th % nrot_heads);
   const int64_t t = th / nrot_heads;
-  const int pos = row_pos ? row_pos[t] : (int)(t % S);
+  const int pos = (row_pos ? row_pos[t] : (int)(t % S)) + pos_offset;
   const float4* tab = reinterpret_cast<const float4*>(cs + 2 * ((size_t)pos * half + i));   // (cos, sin) x 8
   const size_t o = (size_t)t * ld + (size_t)hd * dh + i;
   float x1[8], x2[8], y1[8], y2[8];
@@ -603,7 +607,7 @@ __global__ __launch_bounds__(256) void rope_vec8_kernel(T* __restrict__ qkv, con
 }
 
 hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, void* qkv, int inverse,
-                       int dtype, const int32_t* row_pos, hipStream_t s) {
+                       int dtype, const int32_t* row_pos, int pos_offset, hipStream_t s) {
   const int nrot = nh + nkv;
   const int ld = (nh + 2 * nkv) * dh;
   const int64_t total = (int64_t)B * S * nrot * (dh / 2);
@@ -613,13 +617,13 @@ hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, v
   if ((dh % 16) == 0 && (((uintptr_t)qkv | (uintptr_t)cs) & 15) == 0) {
     const int64_t total8 = total / 8;
     dim3 grid8((unsigned)((total8 + 255) / 256)), blk8(256);
-    if (dtype == kBF16) hipLaunchKernelGGL(rope_vec8_kernel<bf16_t>, grid8, blk8, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total8, row_pos);
-    else hipLaunchKernelGGL(rope_vec8_kernel<float>, grid8, blk8, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total8, row_pos);
+    if (dtype == kBF16) hipLaunchKernelGGL(rope_vec8_kernel<bf16_t>, grid8, blk8, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total8, row_pos, pos_offset);
+    else hipLaunchKernelGGL(rope_vec8_kernel<float>, grid8, blk8, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total8, row_pos, pos_offset);
     return hipGetLastError();
   }
   dim3 grid((unsigned)((total + 255) / 256)), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total, row_pos);
-  else hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total, row_pos);
+  if (dtype == kBF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, blk, 0, s, (bf16_t*)qkv, cs, S, nrot, dh, ld, sgn, total, row_pos, pos_offset);
+  else hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, s, (float*)qkv, cs, S, nrot, dh, ld, sgn, total, row_pos, pos_offset);
   return hipGetLastError();
 }
 

@@ -43,9 +43,12 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);  // picks the MFMA pat
 // scal[1] = 1/N.  The rows the LM head processes are the kept ones (or all of them if select_all):
 // kept_idx[0..cnt[0]) lists them in ascending order, row_pos[t] is the position of row t in that list or -1.
 size_t plan_rows_scratch_bytes(int64_t T);   // blk_counts below
+// sel_mask (optional, device, one byte per row) replaces the rule above for WHICH rows are selected (the
+// unroll selects the rows that carry loss at the current or a later step); N still counts the kept rows.
 hipError_t launch_plan_rows(const int32_t* tokens, const uint8_t* mask, int64_t T, int V, int select_all,
                             float* scal, int* cnt, int32_t* kept_idx, int32_t* row_pos, const int* cu, int nseq,
-                            int max_len, uint8_t* mask_eff, int* status, int* blk_counts, hipStream_t s);
+                            int max_len, uint8_t* mask_eff, int* status, int* blk_counts, const uint8_t* sel_mask,
+                            hipStream_t s);
 // packed batches (cu = device offsets of nseq sequences): position of each row in its sequence, and zeroing
 // of the rows of a [T, row_bytes] array that no sequence owns
 hipError_t launch_seq_pos(const int* cu, int nseq, int64_t T, int max_len, int32_t* pos, hipStream_t s);
@@ -69,9 +72,10 @@ hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x
                               const float* rstd, const void* res, void* dx, float* dg,
                               float* dg_partial, int dtype, const int* rows_dev, hipStream_t s);
 hipError_t launch_rope_table(int S, int dh, float theta, float* cs, hipStream_t s);  // cs [S, dh/2, 2]
-// row_pos (optional, device): position of every row in its sequence; NULL = row % S
+// row_pos (optional, device): position of every row in its sequence; NULL = row % S.  pos_offset is added to
+// every position (the table must reach that far).
 hipError_t launch_rope(int B, int S, int nh, int nkv, int dh, const float* cs, void* qkv, int inverse,
-                       int dtype, const int32_t* row_pos, hipStream_t s);
+                       int dtype, const int32_t* row_pos, int pos_offset, hipStream_t s);
 // n = rows * per_row elements; rows_dev (optional, device): only the first *rows_dev rows are processed
 hipError_t launch_swiglu_fwd(int64_t n, const void* gt, const void* u, void* h, int dtype, int64_t per_row,
                              const int* rows_dev, hipStream_t s);
@@ -128,6 +132,20 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
+
+// ---- unroll.hip: the multi-step unroll (the draft fed its own output) ------------------------------
+constexpr int kMaxUnroll = 8;
+// tokens / mask / input ids (ids, ids_s optional) moved left by `shift` inside every sequence of S rows, and
+// sel_s[t] = 1 where row t carries loss at a step in (shift, n_steps]
+hipError_t launch_shift_inputs(const int32_t* tokens, const uint8_t* mask, const int32_t* ids, int64_t T, int S, int V,
+                               int shift, int n_steps, int32_t* tokens_s, uint8_t* mask_s, uint8_t* sel_s,
+                               int32_t* ids_s, hipStream_t s);
+// own[T, 2 nk] = key/value columns of qkv (rows of nq + 2 nk), which then receive those of qkv1
+hipError_t launch_kv_swap(int64_t T, int nq, int nk, void* qkv, const void* qkv1, void* own, int dtype, hipStream_t s);
+struct OwnKV { const void* kv[kMaxUnroll]; };   // per later step: [T, 2 nk], keys then values
+// merges the n_own own key/value pairs of every row into the causal attention result (out, lse) over step 1
+hipError_t launch_own_kv_merge_fwd(int B, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse,
+                                   const OwnKV& own, int n_own, int dtype, hipStream_t s);
 
 // pure-MFMA rate probe: blocks x 8 waves x iters x 8 MFMAs of 2*32*32*16 flop; sink holds blocks*512 floats
 hipError_t launch_mfma_probe(int blocks, int iters, float* sink, hipStream_t s);

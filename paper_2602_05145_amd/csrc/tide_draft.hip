@@ -127,7 +127,7 @@ Plan make_plan(const tide_draft_config* c) {
   p.mask_c = b.take(T);
   p.mask_eff = b.take(T);
   p.seq_pos = b.take(T * 4);
-  p.rope_cs = b.take(T * c->head_dim * sizeof(float));   // up to T positions: one packed sequence may fill the batch
+  p.rope_cs = b.take((T + kMaxUnroll) * c->head_dim * sizeof(float));   // up to T positions (one packed sequence may fill the batch), plus the unroll's shift
   p.x0 = b.take(T * p.d * es);
   p.r1 = b.take(T * 4);
   p.a = b.take(T * p.d * es);
@@ -240,23 +240,46 @@ AttnArgs attn_args(const tide_draft_config* c, const Seqs& q, char* ws, const Pl
 }
 
 // RoPE over all T rows: position = row % seq in the fixed layout, the planned per-row position when packed
-int enqueue_rope(const tide_draft_config* c, const Seqs& q, char* ws, const Plan& p, void* qkv, int inverse, hipStream_t s) {
+int enqueue_rope(const tide_draft_config* c, const Seqs& q, char* ws, const Plan& p, void* qkv, int inverse, int pos_offset, hipStream_t s) {
   const float* cs = (const float*)(ws + p.rope_cs);
-  if (q.cu) TIDE_HIP(launch_rope(1, (int)p.T, c->n_heads, c->n_kv_heads, c->head_dim, cs, qkv, inverse, c->dtype, (const int32_t*)(ws + p.seq_pos), s), "rope");
-  else TIDE_HIP(launch_rope(c->batch, c->seq, c->n_heads, c->n_kv_heads, c->head_dim, cs, qkv, inverse, c->dtype, nullptr, s), "rope");
+  if (q.cu) TIDE_HIP(launch_rope(1, (int)p.T, c->n_heads, c->n_kv_heads, c->head_dim, cs, qkv, inverse, c->dtype, (const int32_t*)(ws + p.seq_pos), pos_offset, s), "rope");
+  else TIDE_HIP(launch_rope(c->batch, c->seq, c->n_heads, c->n_kv_heads, c->head_dim, cs, qkv, inverse, c->dtype, nullptr, pos_offset, s), "rope");
   return TIDE_OK;
 }
+
+// One step of the multi-step unroll (fixed layout only).  Step `shift + 1` works in its own workspace; tokens,
+// mask and the token input handed to enqueue_trunk are already the shifted ones.
+struct UnrollStep {
+  int shift;                    // 0 for the first step
+  int n_steps;
+  const uint8_t* sel;           // rows that carry loss at this or a later step
+  const char* prev_ws;          // workspace of the step before (its x2 and row_pos feed this step); shift > 0
+  const char* first_ws;         // workspace of step 1 (its keys and values); shift > 0
+  char* own_kv[kMaxUnroll];     // [T, 2 nk] own key/value pairs of steps 2 .. shift + 1 (the last one is written here)
+};
 
 // Forward pass up to the final RMSNorm (everything except the LM head).
 int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const tide_token_input* tok,
                   const void* hidden_buf, const int32_t* tokens, const uint8_t* mask, int select_all, const Seqs& q,
-                  char* ws, const Plan& p, hipStream_t s) {
+                  char* ws, const Plan& p, hipStream_t s, const UnrollStep* ur = nullptr) {
   const int dt = c->dtype;
   const int64_t T = p.T;
   float* scal = (float*)(ws + p.scal);
-  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), q.cu, q.n, q.max_len, (uint8_t*)(ws + p.mask_eff), (int*)(ws + p.status), (int*)(ws + p.plan_cnt), s), "plan_rows");
+  const int shift = ur ? ur->shift : 0;
+  TIDE_HIP(launch_plan_rows(tokens, mask, T, c->vocab, select_all, scal, (int*)(ws + p.cnt), (int32_t*)(ws + p.kept_idx), (int32_t*)(ws + p.row_pos), q.cu, q.n, q.max_len, (uint8_t*)(ws + p.mask_eff), (int*)(ws + p.status), (int*)(ws + p.plan_cnt), ur ? ur->sel : nullptr, s), "plan_rows");
   if (q.cu) TIDE_HIP(launch_seq_pos(q.cu, q.n, T, q.max_len, (int32_t*)(ws + p.seq_pos), s), "sequence positions");
-  if (!tok) {
+  if (shift > 0) {
+    // the feature of a later step is the layer output of the step before (dense over that step's selected
+    // rows; rows it did not select carry no loss from here on and get zeros)
+    void* feat = tok ? ws + p.g0 : ws + p.x0;
+    TIDE_HIP(launch_scatter_rows(T, (int)p.d, ur->prev_ws + p.x2, feat, 0, nullptr, nullptr, (const int32_t*)(ur->prev_ws + p.row_pos), dt, s), "scatter features");
+    if (tok) {
+      TIDE_HIP(launch_embed_rows(T, (int)p.d, tok->embed, tok->embed_rows, tok->input_ids, ws + p.e0, dt, s), "embed rows");
+      GemmArgs g = gemm_args(kNT, T, p.d, p.d, ws + p.g0, p.d, tok->w_in, 2 * p.d, ws + p.x0, p.d, dt, dt);
+      g.A2 = ws + p.e0; g.B2 = (const char*)tok->w_in + (size_t)p.d * p.es; g.K2 = p.d;
+      TIDE_HIP(launch_gemm(g, s), "gemm in");
+    }
+  } else if (!tok) {
     // x0 = Hcat W_fc^T
     TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.d, p.KH, hidden_buf, p.KH, P->w_fc, p.KH, ws + p.x0, p.d, dt, dt), s), "gemm fc");
   } else {
@@ -270,11 +293,18 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
   }
   TIDE_HIP(launch_rmsnorm_fwd(T, (int)p.d, ws + p.x0, P->g1, c->rms_eps, ws + p.a, (float*)(ws + p.r1), dt, nullptr, s), "rmsnorm1");
   TIDE_HIP(launch_gemm(gemm_args(kNT, T, p.nqkv, p.d, ws + p.a, p.d, P->w_qkv, p.d, ws + p.qkv, p.nqkv, dt, dt), s), "gemm qkv");
-  TIDE_HIP(launch_rope_table(q.max_len, c->head_dim, c->rope_theta, (float*)(ws + p.rope_cs), s), "rope table");
-  { const int rc = enqueue_rope(c, q, ws, p, ws + p.qkv, 0, s); if (rc) return rc; }
+  TIDE_HIP(launch_rope_table(q.max_len + shift, c->head_dim, c->rope_theta, (float*)(ws + p.rope_cs), s), "rope table");
+  { const int rc = enqueue_rope(c, q, ws, p, ws + p.qkv, 0, shift, s); if (rc) return rc; }
+  // later step of the unroll: keep the step's own key/value pair aside and attend to the step-1 keys/values
+  if (shift > 0) TIDE_HIP(launch_kv_swap(T, (int)p.nq, (int)p.nk, ws + p.qkv, ur->first_ws + p.qkv, ur->own_kv[shift - 1], dt, s), "kv swap");
   {
     const AttnArgs at = attn_args(c, q, ws, p);
     TIDE_HIP(launch_attn_fwd(at, s), "attention fwd");
+    if (shift > 0) {
+      OwnKV own;
+      for (int j = 0; j < kMaxUnroll; ++j) own.kv[j] = j < shift ? ur->own_kv[j] : nullptr;
+      TIDE_HIP(launch_own_kv_merge_fwd(c->batch, c->seq, c->n_heads, c->n_kv_heads, c->head_dim, ws + p.qkv, ws + p.A, (float*)(ws + p.attn_lse), own, shift, dt, s), "own kv merge");
+    }
     // padding rows are written by no sequence: make them finite (they enter weight-gradient contractions)
     if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.A, q.cu, q.n, T, (int64_t)(p.nq * p.es), s), "zero padding rows");
   }
@@ -437,6 +467,79 @@ int tide_draft_eval(const tide_draft_config* cfg, const tide_draft_tensors* para
   return forward_impl(cfg, params, nullptr, hidden_buf, tokens, loss_mask, nullptr, loss_out, nullptr, accuracy_out, workspace, workspace_bytes, stream);
 }
 
+// ---- multi-step evaluation unroll -----------------------------------------------------------------
+namespace {
+struct UnrollPlan {
+  size_t step_bytes;                    // one workspace per step
+  size_t tokens_s, mask_s, sel_s, ids_s, own_kv;   // per-step extras (offset of step 0; stride extra_stride)
+  size_t extra_stride, total;
+};
+UnrollPlan make_unroll_plan(const Plan& p, int n_steps) {
+  UnrollPlan u;
+  u.step_bytes = align_up(p.total, 256);
+  Bump b;
+  const size_t T = (size_t)p.T;
+  u.tokens_s = b.take(T * 4);
+  u.mask_s = b.take(T);
+  u.sel_s = b.take(T);
+  u.ids_s = b.take(T * 4);
+  u.own_kv = b.take(T * 2 * (size_t)p.nk * p.es);
+  u.extra_stride = b.off;
+  u.total = (u.step_bytes + u.extra_stride) * (size_t)n_steps;
+  return u;
+}
+}  // namespace
+
+size_t tide_draft_unroll_workspace_bytes(const tide_draft_config* cfg, int32_t n_steps) {
+  if (!check_config(cfg)) return 0;
+  if (n_steps < 1 || n_steps > kMaxUnroll) { fail(TIDE_ERR_CONFIG, "n_steps must be in [1, %d]", kMaxUnroll); return 0; }
+  return make_unroll_plan(make_plan(cfg), n_steps).total;
+}
+
+int tide_draft_eval_unroll(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,
+                           const void* hidden_buf, const int32_t* tokens, const uint8_t* loss_mask, int32_t n_steps,
+                           float* loss_out, float* accuracy_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  if (n_steps < 1 || n_steps > kMaxUnroll) return fail(TIDE_ERR_CONFIG, "n_steps must be in [1, %d]", kMaxUnroll);
+  if (!accuracy_out) return fail(TIDE_ERR_NULL, "accuracy_out is NULL");
+  if (tok) { const int rc = check_token_input(tok, false, cfg->dtype); if (rc) return rc; }
+  const Plan p = make_plan(cfg);
+  const UnrollPlan u = make_unroll_plan(p, n_steps);
+  {
+    const int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, u.step_bytes, p);
+    if (rc) return rc;
+  }
+  if (workspace_bytes < u.total) return fail(TIDE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, u.total);
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  char* extra = ws + u.step_bytes * (size_t)n_steps;
+  const Seqs q = fixed_seqs(cfg);
+  UnrollStep ur;
+  std::memset(&ur, 0, sizeof(ur));
+  ur.n_steps = n_steps;
+  for (int k = 0; k < n_steps; ++k) {
+    char* wk = ws + u.step_bytes * (size_t)k;
+    char* ek = extra + u.extra_stride * (size_t)k;
+    int32_t* tokens_s = (int32_t*)(ek + u.tokens_s);
+    uint8_t* mask_s = (uint8_t*)(ek + u.mask_s);
+    uint8_t* sel_s = (uint8_t*)(ek + u.sel_s);
+    int32_t* ids_s = tok ? (int32_t*)(ek + u.ids_s) : nullptr;
+    TIDE_HIP(launch_shift_inputs(tokens, loss_mask, tok ? tok->input_ids : nullptr, p.T, cfg->seq, cfg->vocab, k, n_steps, tokens_s, mask_s, sel_s, ids_s, s), "shift inputs");
+    tide_token_input tk;
+    if (tok) { tk = *tok; tk.input_ids = ids_s; }
+    ur.shift = k;
+    ur.sel = sel_s;
+    ur.prev_ws = k ? ws + u.step_bytes * (size_t)(k - 1) : nullptr;
+    ur.first_ws = ws;
+    if (k) ur.own_kv[k - 1] = ek + u.own_kv;
+    int rc = enqueue_trunk(cfg, params, tok ? &tk : nullptr, hidden_buf, tokens_s, mask_s, 0, q, wk, p, s, &ur);
+    if (rc) return rc;
+    rc = enqueue_lm_head(cfg, params, nullptr, tokens_s, mask_s, nullptr, loss_out + k, accuracy_out + k, wk, p, false, s);
+    if (rc) return rc;
+  }
+  return TIDE_OK;
+}
+
 static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
                       tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf, const int32_t* tokens,
                       const uint8_t* loss_mask, const Seqs* packed, float lr, float* loss_out, void* workspace,
@@ -505,7 +608,7 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
     TIDE_HIP(launch_attn_bwd(at, s), "attention bwd");
     if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.dqkv, q.cu, q.n, T, (int64_t)(p.nqkv * p.es), s), "zero padding rows");
   }
-  { const int rc2 = enqueue_rope(cfg, q, ws, p, ws + p.dqkv, 1, s); if (rc2) return rc2; }
+  { const int rc2 = enqueue_rope(cfg, q, ws, p, ws + p.dqkv, 1, 0, s); if (rc2) return rc2; }
   TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.nqkv, ws + p.dqkv, p.nqkv, P->w_qkv, p.d, ws + p.da, p.d, dt, dt), s), "gemm da");
   TIDE_HIP(launch_gemm(gemm_args(kTN, p.nqkv, p.d, T, ws + p.dqkv, p.nqkv, ws + p.a, p.d, G->w_qkv, p.d, dt, kF32), s), "gemm dW_qkv");
   TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.da, ws + p.x0, P->g1, (const float*)(ws + p.r1), ws + p.dx1, ws + p.dx0, (float*)G->g1, dgp, dt, nullptr, s), "rmsnorm1 bwd");
@@ -659,7 +762,7 @@ int tide_rope(int B, int S, int nh, int nkv, int dh, float theta, void* qkv, flo
   if (!qkv || !table) return fail(TIDE_ERR_NULL, "NULL argument");
   if (B <= 0 || S <= 0 || nh <= 0 || nkv <= 0 || dh <= 0 || dh % 2) return fail(TIDE_ERR_CONFIG, "bad rope shape");
   TIDE_HIP(launch_rope_table(S, dh, theta, table, (hipStream_t)stream), "rope table");
-  TIDE_HIP(launch_rope(B, S, nh, nkv, dh, table, qkv, inverse, dtype, nullptr, (hipStream_t)stream), "rope");
+  TIDE_HIP(launch_rope(B, S, nh, nkv, dh, table, qkv, inverse, dtype, nullptr, 0, (hipStream_t)stream), "rope");
   return TIDE_OK;
 }
 

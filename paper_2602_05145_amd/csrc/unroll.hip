@@ -1,0 +1,143 @@
+// Kernels of the multi-step unroll of the draft (Sec. 3.2 names EAGLE-3 as the draft architecture, Sec. 5.1
+// fixes gamma = 3 draft tokens per round): from its second draft token on the draft is fed its own layer
+// output in place of a captured feature.  Row i of step s stands for position i + s - 1; it attends to the
+// step-1 keys/values of rows 0..i (the ordinary causal attention, run by the flash kernels on a buffer that
+// holds the step's queries next to the step-1 keys and values) and to the ONE key/value it produced itself
+// at each of the steps 2..s.  Those few extra pairs per row are merged into the flash result here, one
+// wavefront per (row, query head): HBM-bound streaming work, no contraction.
+#include "kernels.h"
+#include "prof.h"
+#include "tide_common.h"
+
+namespace tide {
+
+// tokens / mask / input ids of step `shift + 1`: moved left by `shift` inside every sequence (label -1, mask 0,
+// id -1 where the position leaves the sequence), and sel = 1 for every row that carries loss at this or a
+// later step (its layer output is needed: for its own logits or as the next step's feature).
+__global__ __launch_bounds__(256) void shift_inputs_kernel(const int32_t* __restrict__ tokens,
+                                                           const uint8_t* __restrict__ mask,
+                                                           const int32_t* __restrict__ ids, int64_t T, int S, int V,
+                                                           int shift, int n_steps, int32_t* __restrict__ tokens_s,
+                                                           uint8_t* __restrict__ mask_s, uint8_t* __restrict__ sel_s,
+                                                           int32_t* __restrict__ ids_s) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int i = (int)(t % S);
+  const bool in = i + shift < S;
+  tokens_s[t] = in ? tokens[t + shift] : -1;
+  mask_s[t] = in ? mask[t + shift] : (uint8_t)0;
+  if (ids_s) ids_s[t] = in ? ids[t + shift] : -1;
+  int sel = 0;
+  for (int j = shift; j < n_steps && i + j < S; ++j) {
+    const int tk = tokens[t + j];
+    if (mask[t + j] != 0 && tk >= 0 && tk < V) sel = 1;
+  }
+  sel_s[t] = (uint8_t)sel;
+}
+
+hipError_t launch_shift_inputs(const int32_t* tokens, const uint8_t* mask, const int32_t* ids, int64_t T, int S, int V,
+                               int shift, int n_steps, int32_t* tokens_s, uint8_t* mask_s, uint8_t* sel_s,
+                               int32_t* ids_s, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  hipLaunchKernelGGL(shift_inputs_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, tokens, mask, ids, T, S, V, shift, n_steps, tokens_s, mask_s, sel_s, ids_s);
+  return hipGetLastError();
+}
+
+// own[t] = key and value columns of qkv[t] (this step's own pair, after RoPE), which are then overwritten
+// by those of qkv1[t] (step 1), so that the flash kernels find the step's queries beside the step-1 keys/values
+template <typename T>
+__global__ __launch_bounds__(256) void kv_swap_kernel(T* __restrict__ qkv, const T* __restrict__ qkv1,
+                                                      T* __restrict__ own, int nq, int nkv2, int ld) {
+  const size_t t = blockIdx.x;
+  T* row = qkv + t * (size_t)ld + nq;
+  const T* row1 = qkv1 + t * (size_t)ld + nq;
+  T* o = own + t * (size_t)nkv2;
+  for (int e = threadIdx.x; e < nkv2; e += 256) {
+    o[e] = row[e];
+    row[e] = row1[e];
+  }
+}
+
+hipError_t launch_kv_swap(int64_t T, int nq, int nk, void* qkv, const void* qkv1, void* own, int dtype, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  ProfScope ps("kv_swap", 0, 6.0 * (double)T * nk * dtype_size(dtype), s);
+  const int ld = nq + 2 * nk;
+  if (dtype == kBF16) hipLaunchKernelGGL(kv_swap_kernel<bf16_t>, dim3((unsigned)T), dim3(256), 0, s, (bf16_t*)qkv, (const bf16_t*)qkv1, (bf16_t*)own, nq, 2 * nk, ld);
+  else hipLaunchKernelGGL(kv_swap_kernel<float>, dim3((unsigned)T), dim3(256), 0, s, (float*)qkv, (const float*)qkv1, (float*)own, nq, 2 * nk, ld);
+  return hipGetLastError();
+}
+
+namespace {
+constexpr int kMaxDhPerLane = 4;   // head_dim <= 256
+}  // namespace
+
+// out[t, h] and lse[b, h, i] hold the causal attention of the step's query over the step-1 keys/values.  With
+// s_j = scale * q . k_j for the n_own own pairs:  L = log(exp(lse) + sum_j exp(s_j)),
+// out <- exp(lse - L) out + sum_j exp(s_j - L) v_j,  lse <- L   (one softmax over prefix and own pairs).
+template <typename T>
+__global__ __launch_bounds__(256) void own_kv_merge_fwd_kernel(const T* __restrict__ qkv, T* __restrict__ out,
+                                                               float* __restrict__ lse, OwnKV own, int n_own,
+                                                               int64_t n_pairs, int nh, int nkv, int dh, int S,
+                                                               float scale) {
+  const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (wid >= n_pairs) return;   // whole wavefronts leave; no barrier below
+  const int lane = threadIdx.x & 63;
+  const int64_t t = wid / nh;
+  const int h = (int)(wid % nh), kh = h / (nh / nkv);
+  const int nq = nh * dh, nk = nkv * dh;
+  const T* q = qkv + (size_t)t * (nq + 2 * nk) + (size_t)h * dh;
+  float qv[kMaxDhPerLane];
+#pragma unroll
+  for (int c = 0; c < kMaxDhPerLane; ++c) {
+    const int e = lane + 64 * c;
+    qv[c] = e < dh ? ldf(q, e) : 0.f;
+  }
+  float sc[kMaxUnroll];
+  for (int j = 0; j < n_own; ++j) {
+    const T* kj = (const T*)own.kv[j] + (size_t)t * (2 * nk) + (size_t)kh * dh;
+    float part = 0.f;
+#pragma unroll
+    for (int c = 0; c < kMaxDhPerLane; ++c) {
+      const int e = lane + 64 * c;
+      if (e < dh) part += qv[c] * ldf(kj, e);
+    }
+    sc[j] = scale * wave_sum(part);
+  }
+  const size_t li = ((size_t)(t / S) * nh + h) * (size_t)S + (size_t)(t % S);
+  const float l0 = lse[li];
+  float m = l0;
+  for (int j = 0; j < n_own; ++j) m = fmaxf(m, sc[j]);
+  float sum = expf(l0 - m);
+  for (int j = 0; j < n_own; ++j) sum += expf(sc[j] - m);
+  const float L = m + logf(sum);
+  const float w0 = expf(l0 - L);
+  T* o = out + (size_t)t * nq + (size_t)h * dh;
+#pragma unroll
+  for (int c = 0; c < kMaxDhPerLane; ++c) {
+    const int e = lane + 64 * c;
+    if (e < dh) {
+      float acc = w0 * ldf(o, e);
+      for (int j = 0; j < n_own; ++j) {
+        const T* vj = (const T*)own.kv[j] + (size_t)t * (2 * nk) + nk + (size_t)kh * dh;
+        acc += expf(sc[j] - L) * ldf(vj, e);
+      }
+      stf(o, e, acc);
+    }
+  }
+  if (lane == 0) lse[li] = L;
+}
+
+hipError_t launch_own_kv_merge_fwd(int B, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse,
+                                   const OwnKV& own, int n_own, int dtype, hipStream_t s) {
+  const int64_t n_pairs = (int64_t)B * S * nh;
+  if (n_pairs <= 0 || n_own <= 0) return hipSuccess;
+  if (n_own > kMaxUnroll || dh > 64 * kMaxDhPerLane || nh % nkv) return hipErrorInvalidValue;
+  ProfScope ps("own_kv_merge_fwd", 0, (double)n_pairs * dh * (3.0 + 2.0 * n_own) * dtype_size(dtype), s);
+  const float scale = 1.0f / sqrtf((float)dh);
+  dim3 grid((unsigned)((n_pairs + 3) / 4)), blk(256);
+  if (dtype == kBF16) hipLaunchKernelGGL(own_kv_merge_fwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)qkv, (bf16_t*)out, lse, own, n_own, n_pairs, nh, nkv, dh, S, scale);
+  else hipLaunchKernelGGL(own_kv_merge_fwd_kernel<float>, grid, blk, 0, s, (const float*)qkv, (float*)out, lse, own, n_own, n_pairs, nh, nkv, dh, S, scale);
+  return hipGetLastError();
+}
+
+}  // namespace tide
