@@ -3,6 +3,8 @@ as inputs: process the verified prefix once, then append one position per draft 
 of the step before.  That process is written here on its own, with a growing key/value cache, one start position
 at a time and from plain NumPy (none of the oracle's functions), and every step of the oracle's batched unroll
 must reproduce it row by row."""
+import copy
+
 import numpy as np
 import pytest
 
@@ -117,3 +119,48 @@ def test_later_steps_do_not_see_other_rows_later_keys():
     for s in range(3):
         np.testing.assert_array_equal(a[s]["x2"][:-1], b[s]["x2"][:-1])
         assert np.abs(a[s]["x2"][-1] - b[s]["x2"][-1]).max() > 1e-6
+
+
+def _weighted_loss(cfg, params, wl, tok, w):
+    steps = U.unroll_forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], len(w), tok=tok)
+    return sum(wi * st["loss"] for wi, st in zip(w, steps))
+
+
+@pytest.mark.parametrize("token_input", [False, True])
+@pytest.mark.parametrize("kw", [dict(seq=6), dict(batch=2, seq=5, n_heads=4, n_kv_heads=2, hidden=16, head_dim=4, ffn=10, vocab=13)])
+def test_unroll_gradients_by_finite_differences(kw, token_input):
+    cfg = micro_cfg(mask="bernoulli", mask_p=0.3, **kw)
+    wl = micro_workload(cfg)
+    tok = _token_input(cfg) if token_input else None
+    params = {k: np.asarray(v, np.float64) for k, v in wl["params"].items()}
+    if tok:
+        params[O.TOKEN_PARAM] = tok["w_in"]
+    w = [1.0, 0.7, 0.45]
+    steps = U.unroll_forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], 3, tok=tok, keep_cache=True)
+    grads = U.unroll_backward(cfg, params, steps, step_weights=w)
+    rng = np.random.default_rng(1)
+    h = 1e-6
+    for name, g in grads.items():
+        assert g.shape == params[name].shape
+        idx = rng.choice(g.size, size=min(10, g.size), replace=False)
+        for i in idx:
+            pp = copy.deepcopy(params)
+            pp[name].reshape(-1)[i] += h
+            lp = _weighted_loss(cfg, pp, wl, tok, w)
+            pp[name].reshape(-1)[i] -= 2 * h
+            lm = _weighted_loss(cfg, pp, wl, tok, w)
+            fd = (lp - lm) / (2 * h)
+            an = g.reshape(-1)[i]
+            assert abs(fd - an) <= 2e-6 * max(1.0, abs(fd)) + 5e-8, (name, i, fd, an)
+
+
+def test_one_step_gradients_are_the_single_step_gradients():
+    cfg = micro_cfg(batch=2, seq=6, mask="bernoulli", mask_p=0.3)
+    wl = micro_workload(cfg)
+    tok = _token_input(cfg)
+    params = dict({k: np.asarray(v, np.float64) for k, v in wl["params"].items()}, **{O.TOKEN_PARAM: tok["w_in"]})
+    _, cache = O.forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], tok=tok)
+    ref = O.backward(cfg, params, cache, wl["tokens"], wl["mask"])
+    got = U.unroll_backward(cfg, params, U.unroll_forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], 1, tok=tok, keep_cache=True))
+    for k in ref:
+        np.testing.assert_allclose(got[k], ref[k], rtol=1e-12, atol=1e-14)
