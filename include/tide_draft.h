@@ -249,6 +249,22 @@ int tide_draft_eval_unroll(const tide_draft_config *cfg, const tide_draft_tensor
                            int32_t n_steps, float *loss_out, float *accuracy_out,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* Training step over the multi-step unroll above: minimises L = sum_s step_weights[s] * loss_s.  The gradient
+ * flows through the whole chain: the feature of step s is the layer output of step s-1, and the keys/values of a
+ * step are read by every later step.  One AdamW update at the end, exactly as in tide_draft_train_step.
+ *   tok           may be NULL (feature-only model); else as in tide_draft_train_step_tok (W_in is trained)
+ *   step_weights  HOST float [n_steps], finite and >= 0, or NULL for all ones (the paper gives none)
+ *   loss_out      DEVICE float [n_steps]: the unweighted mean cross-entropy of every step, before the update
+ *   grads         out: gradients of L, overwritten
+ *   workspace     as in tide_draft_eval_unroll (the same size query covers both calls)
+ * Fixed-layout batches only; errors as in tide_draft_train_step, TIDE_ERR_CONFIG for a bad n_steps or weight. */
+int tide_draft_train_step_unroll(const tide_draft_config *cfg, tide_draft_tensors *params,
+                                 tide_draft_tensors *grads, tide_adam_state *adam_state,
+                                 const tide_token_input *tok,
+                                 const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                                 int32_t n_steps, const float *step_weights, float lr, float *loss_out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
 /* Message of the last error on the calling thread (static storage, never NULL). */
 const char *tide_last_error(void);
 

@@ -488,7 +488,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
 
 // out[c] = sum_r part[r, c]; 64 columns x 4 row lanes per block
 __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ part, int64_t nrows, int d,
-                                                     float* __restrict__ out) {
+                                                     float* __restrict__ out, int accumulate) {
   __shared__ float sm[4][64];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int rl = threadIdx.x >> 6;
@@ -497,7 +497,10 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ p
     for (int64_t r = rl; r < nrows; r += 4) a += part[(size_t)r * d + c];
   sm[rl][threadIdx.x & 63] = a;
   __syncthreads();
-  if (rl == 0 && c < d) out[c] = (sm[0][threadIdx.x] + sm[1][threadIdx.x]) + (sm[2][threadIdx.x] + sm[3][threadIdx.x]);
+  if (rl == 0 && c < d) {
+    const float v = (sm[0][threadIdx.x] + sm[1][threadIdx.x]) + (sm[2][threadIdx.x] + sm[3][threadIdx.x]);
+    out[c] = accumulate ? out[c] + v : v;
+  }
 }
 
 size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d) {
@@ -507,7 +510,7 @@ size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d) {
 
 hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x, const void* g,
                               const float* rstd, const void* res, void* dx, float* dg, float* dg_partial,
-                              int dtype, const int* rows_dev, hipStream_t s) {
+                              int dtype, const int* rows_dev, hipStream_t s, int accumulate) {
   if (rows <= 0) return hipSuccess;
   const bool vec = (d % 8) == 0 && d <= 8192;
   if (!vec && d > 1024) return hipErrorInvalidValue;
@@ -528,7 +531,7 @@ hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x
 #undef TIDE_RMS_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_kernel, dim3((d + 63) / 64), dim3(256), 0, s, dg_partial, nblk, d, dg);
+  hipLaunchKernelGGL(colsum_kernel, dim3((d + 63) / 64), dim3(256), 0, s, dg_partial, nblk, d, dg, accumulate);
   return hipGetLastError();
 }
 

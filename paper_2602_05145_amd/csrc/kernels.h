@@ -70,7 +70,8 @@ hipError_t launch_rmsnorm_fwd(int64_t rows, int d, const void* x, const void* g,
 size_t rmsnorm_bwd_scratch_bytes(int64_t rows, int d);
 hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x, const void* g,
                               const float* rstd, const void* res, void* dx, float* dg,
-                              float* dg_partial, int dtype, const int* rows_dev, hipStream_t s);
+                              float* dg_partial, int dtype, const int* rows_dev, hipStream_t s,
+                              int accumulate = 0);   // accumulate: dg += instead of dg =
 hipError_t launch_rope_table(int S, int dh, float theta, float* cs, hipStream_t s);  // cs [S, dh/2, 2]
 // row_pos (optional, device): position of every row in its sequence; NULL = row % S.  pos_offset is added to
 // every position (the table must reach that far).
@@ -146,6 +147,16 @@ struct OwnKV { const void* kv[kMaxUnroll]; };   // per later step: [T, 2 nk], ke
 // merges the n_own own key/value pairs of every row into the causal attention result (out, lse) over step 1
 hipError_t launch_own_kv_merge_fwd(int B, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse,
                                    const OwnKV& own, int n_own, int dtype, hipStream_t s);
+struct OwnKVGrad { void* kv[kMaxUnroll]; };   // gradient buffers of the same pairs, same layout
+// backward of the merge: adds the pairs' share to the query gradients in dqkv and writes (first) or adds the
+// pairs' own gradients; lse / delta are those of the merged result
+hipError_t launch_own_kv_merge_bwd(int B, int S, int nh, int nkv, int dh, const void* qkv, const void* dout,
+                                   const float* lse, const float* delta, const OwnKV& own, const OwnKVGrad& grad,
+                                   int n_own, int first, void* dqkv, int dtype, hipStream_t s);
+// key/value columns of dqkv <-> the running step-1 key/value gradient acc1 [T, 2 nk]: mode 0 acc1 = columns,
+// mode 1 acc1 += columns (both then put own_grad [T, 2 nk] into the columns), mode 2 columns += acc1
+hipError_t launch_kv_grad_route(int64_t T, int nq, int nk, void* dqkv, void* acc1, const void* own_grad, int mode,
+                                int dtype, hipStream_t s);
 
 // pure-MFMA rate probe: blocks x 8 waves x iters x 8 MFMAs of 2*32*32*16 flop; sink holds blocks*512 floats
 hipError_t launch_mfma_probe(int blocks, int iters, float* sink, hipStream_t s);

@@ -343,7 +343,7 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
 // every launch is sized for the worst case and trims itself.
 int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tide_draft_tensors* G,
                     const int32_t* tokens, const uint8_t* mask, int32_t* top1, float* loss_out, float* acc_out,
-                    char* ws, const Plan& p, bool train, hipStream_t s) {
+                    char* ws, const Plan& p, bool train, hipStream_t s, float grad_weight = 1.f, bool add_to_dw = false) {
   const int dt = c->dtype;
   float* scal = (float*)(ws + p.scal);
   const int* cnt = (const int*)(ws + p.cnt);
@@ -375,15 +375,15 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
     {
       // dyhat = (1/N) dZ W_lm
       GemmArgs g = gemm_args(kNN, rows, p.d, p.V, z, p.ldz, P->w_lm, p.d, ws + p.dyhat + (size_t)r0 * p.d * p.es, p.d, dt, dt);
-      g.alpha_dev = scal + 1;
+      g.alpha = grad_weight; g.alpha_dev = scal + 1;
       g.m_dev = cnt; g.m_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm dyhat");
     }
     if (!all_rows) {
       // dW_lm (+)= (1/N) dZ^T yhat of this block
       GemmArgs g = gemm_args(kTN, p.V, p.d, rows, z, p.ldz, yb, p.d, G->w_lm, p.d, dt, kF32);
-      g.alpha_dev = scal + 1;
-      g.accumulate = blk > 0;
+      g.alpha = grad_weight; g.alpha_dev = scal + 1;
+      g.accumulate = blk > 0 || add_to_dw;
       g.k_dev = cnt; g.k_off = r0;
       TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
     }
@@ -391,7 +391,8 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
   if (train && all_rows) {
     // dW_lm = (1/N) dZ^T yhat over all selected rows at once
     GemmArgs g = gemm_args(kTN, p.V, p.d, p.T, ws + p.z, p.ldz, yhat_c, p.d, G->w_lm, p.d, dt, kF32);
-    g.alpha_dev = scal + 1;
+    g.alpha = grad_weight; g.alpha_dev = scal + 1;
+    g.accumulate = add_to_dw;
     g.k_dev = cnt; g.k_off = 0;
     TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
   }
@@ -471,7 +472,7 @@ int tide_draft_eval(const tide_draft_config* cfg, const tide_draft_tensors* para
 namespace {
 struct UnrollPlan {
   size_t step_bytes;                    // one workspace per step
-  size_t tokens_s, mask_s, sel_s, ids_s, own_kv;   // per-step extras (offset of step 0; stride extra_stride)
+  size_t tokens_s, mask_s, sel_s, ids_s, own_kv, own_grad, dfeat, acc_kv1;   // per-step extras (offset of step 0; stride extra_stride)
   size_t extra_stride, total;
 };
 UnrollPlan make_unroll_plan(const Plan& p, int n_steps) {
@@ -484,6 +485,9 @@ UnrollPlan make_unroll_plan(const Plan& p, int n_steps) {
   u.sel_s = b.take(T);
   u.ids_s = b.take(T * 4);
   u.own_kv = b.take(T * 2 * (size_t)p.nk * p.es);
+  u.own_grad = b.take(T * 2 * (size_t)p.nk * p.es);   // training: gradient of the step's own key/value pair
+  u.dfeat = b.take(T * (size_t)p.d * p.es);           // training: gradient reaching x2 from the step after
+  u.acc_kv1 = b.take(T * 2 * (size_t)p.nk * p.es);    // training: running step-1 key/value gradient (step 0's is used)
   u.extra_stride = b.off;
   u.total = (u.step_bytes + u.extra_stride) * (size_t)n_steps;
   return u;
@@ -540,33 +544,28 @@ int tide_draft_eval_unroll(const tide_draft_config* cfg, const tide_draft_tensor
   return TIDE_OK;
 }
 
-static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
-                      tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf, const int32_t* tokens,
-                      const uint8_t* loss_mask, const Seqs* packed, float lr, float* loss_out, void* workspace,
-                      size_t workspace_bytes, void* stream) {
-  const Plan p = make_plan(cfg);
-  const Seqs q = packed ? *packed : fixed_seqs(cfg);
-  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
-  if (rc) return rc;
-  if (!tensors_ok(grads, "grads")) return TIDE_ERR_NULL;
-  if (!st) return fail(TIDE_ERR_NULL, "adam_state is NULL");
-  if (!tensors_ok(&st->m, "adam_state.m") || !tensors_ok(&st->v, "adam_state.v")) return TIDE_ERR_NULL;
+// What the backward pass of one step of the multi-step unroll needs beyond the single-step one.
+struct BwdOpts {
+  int accumulate = 0;               // weight and gain gradients are added to what the buffers hold
+  const UnrollStep* ur = nullptr;   // nullptr: the ordinary single step
+  const void* dx2_extra = nullptr;  // dense over the selected rows: gradient reaching x2 from the step after
+  OwnKVGrad own_grad{};             // gradient buffers of the own key/value pairs of steps 2 .. n
+  char* acc_kv1 = nullptr;          // running gradient of the step-1 keys/values [T, 2 nk]
+  // shift > 0: where the gradient of this step's input feature goes (dense over the selected rows of the step
+  // before, whose workspace and shifted tokens are given)
+  void* dfeat_out = nullptr;
+  char* prev_ws = nullptr;
+  const int32_t* prev_tokens = nullptr;
+};
+
+// Backward pass of one step from dyhat (left by the LM head) to the weight gradients.
+static int enqueue_backward(const tide_draft_config* cfg, const tide_draft_tensors* P, tide_draft_tensors* G,
+                            const tide_token_input* tok, const void* hidden_buf, const Seqs& q, char* ws, const Plan& p,
+                            hipStream_t s, const BwdOpts& o) {
   const int dt = cfg->dtype;
-  if (dt == TIDE_DTYPE_BF16 && !tensors_ok(&st->master, "adam_state.master")) return TIDE_ERR_NULL;
-  if (st->step < 0) return fail(TIDE_ERR_CONFIG, "adam_state.step must be >= 0");
-  if (!(lr >= 0.f)) return fail(TIDE_ERR_CONFIG, "lr must be >= 0");
-
-  hipStream_t s = (hipStream_t)stream;
-  char* ws = (char*)workspace;
-  const tide_draft_tensors* P = params;
-  tide_draft_tensors* G = grads;
   const int64_t T = p.T;
-
-  rc = enqueue_trunk(cfg, P, tok, hidden_buf, tokens, loss_mask, 0, q, ws, p, s);
-  if (rc) return rc;
-  rc = enqueue_lm_head(cfg, P, G, tokens, loss_mask, nullptr, loss_out, nullptr, ws, p, true, s);
-  if (rc) return rc;
-
+  const int acc = o.accumulate;
+  const int shift = o.ur ? o.ur->shift : 0;
   float* dgp = (float*)(ws + p.dg_partial);
   const int* cnt = (const int*)(ws + p.cnt);
   // Backward over the selected rows (dense, *cnt of them) down to the attention output.  dX products trim
@@ -579,10 +578,16 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
   auto rows_dw = [&](int64_t M, int64_t N, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc) {
     GemmArgs g = gemm_args(kTN, M, N, T, A, lda, B, ldb, C, ldc, dt, kF32);
     g.k_dev = cnt;
+    g.accumulate = acc;
     return g;
   };
-  // final norm
-  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dyhat, ws + p.x2, P->g3, (const float*)(ws + p.r3), nullptr, ws + p.dx2, (float*)G->g3, dgp, dt, cnt, s), "rmsnorm3 bwd");
+  auto full_dw = [&](int64_t M, int64_t N, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int add) {
+    GemmArgs g = gemm_args(kTN, M, N, T, A, lda, B, ldb, C, ldc, dt, kF32);
+    g.accumulate = add;
+    return g;
+  };
+  // final norm (plus, in the unroll, what the step after sends back into x2)
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dyhat, ws + p.x2, P->g3, (const float*)(ws + p.r3), o.dx2_extra, ws + p.dx2, (float*)G->g3, dgp, dt, cnt, s, acc), "rmsnorm3 bwd");
   // x2 = x1 + h W_down^T
   TIDE_HIP(launch_gemm(rows_dx(p.F, p.d, ws + p.dx2, p.d, P->w_down, p.F, ws + p.dh, p.F), s), "gemm dh");
   TIDE_HIP(launch_gemm(rows_dw(p.d, p.F, ws + p.dx2, p.d, ws + p.h, p.F, G->w_down, p.F), s), "gemm dW_down");
@@ -595,7 +600,7 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
   }
   TIDE_HIP(launch_gemm(rows_dw(p.F, p.d, ws + p.gt, p.F, ws + p.bn, p.d, G->w_gate, p.d), s), "gemm dW_gate");
   TIDE_HIP(launch_gemm(rows_dw(p.F, p.d, ws + p.u, p.F, ws + p.bn, p.d, G->w_up, p.d), s), "gemm dW_up");
-  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dbn, ws + p.x1, P->g2, (const float*)(ws + p.r2), ws + p.dx2, ws + p.dx1_c, (float*)G->g2, dgp, dt, cnt, s), "rmsnorm2 bwd");
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.dbn, ws + p.x1, P->g2, (const float*)(ws + p.r2), ws + p.dx2, ws + p.dx1_c, (float*)G->g2, dgp, dt, cnt, s, acc), "rmsnorm2 bwd");
   // x1 = x0 + A W_o^T
   TIDE_HIP(launch_gemm(rows_dx(p.nq, p.d, ws + p.dx1_c, p.d, P->w_o, p.nq, ws + p.dA_c, p.nq), s), "gemm dA");
   TIDE_HIP(launch_gemm(rows_dw(p.d, p.nq, ws + p.dx1_c, p.d, ws + p.A_c, p.nq, G->w_o, p.nq), s), "gemm dW_o");
@@ -608,49 +613,173 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
     TIDE_HIP(launch_attn_bwd(at, s), "attention bwd");
     if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.dqkv, q.cu, q.n, T, (int64_t)(p.nqkv * p.es), s), "zero padding rows");
   }
-  { const int rc2 = enqueue_rope(cfg, q, ws, p, ws + p.dqkv, 1, 0, s); if (rc2) return rc2; }
+  if (o.ur && shift > 0) {
+    // later step of the unroll: the flash backward saw the step's queries beside the STEP-1 keys/values.  Add the
+    // own pairs' share, move the step-1 share to its running sum and put this step's own pair gradient (complete
+    // now: every later step ran before) in its place.
+    OwnKV own;
+    for (int j = 0; j < kMaxUnroll; ++j) own.kv[j] = j < shift ? o.ur->own_kv[j] : nullptr;
+    const int last = shift == o.ur->n_steps - 1;
+    TIDE_HIP(launch_own_kv_merge_bwd(cfg->batch, cfg->seq, cfg->n_heads, cfg->n_kv_heads, cfg->head_dim, ws + p.qkv, ws + p.dA, (const float*)(ws + p.attn_lse), (const float*)(ws + p.delta), own, o.own_grad, shift, last, ws + p.dqkv, dt, s), "own kv merge bwd");
+    TIDE_HIP(launch_kv_grad_route(T, (int)p.nq, (int)p.nk, ws + p.dqkv, o.acc_kv1, o.own_grad.kv[shift - 1], last ? 0 : 1, dt, s), "kv grad route");
+  } else if (o.ur && o.ur->n_steps > 1) {
+    TIDE_HIP(launch_kv_grad_route(T, (int)p.nq, (int)p.nk, ws + p.dqkv, o.acc_kv1, nullptr, 2, dt, s), "kv grad route");
+  }
+  { const int rc2 = enqueue_rope(cfg, q, ws, p, ws + p.dqkv, 1, shift, s); if (rc2) return rc2; }
   TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.nqkv, ws + p.dqkv, p.nqkv, P->w_qkv, p.d, ws + p.da, p.d, dt, dt), s), "gemm da");
-  TIDE_HIP(launch_gemm(gemm_args(kTN, p.nqkv, p.d, T, ws + p.dqkv, p.nqkv, ws + p.a, p.d, G->w_qkv, p.d, dt, kF32), s), "gemm dW_qkv");
-  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.da, ws + p.x0, P->g1, (const float*)(ws + p.r1), ws + p.dx1, ws + p.dx0, (float*)G->g1, dgp, dt, nullptr, s), "rmsnorm1 bwd");
-  if (!tok) {
-    // x0 = Hcat W_fc^T: weight gradient only, the captured states are data
-    TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.KH, T, ws + p.dx0, p.d, hidden_buf, p.KH, G->w_fc, p.KH, dt, kF32), s), "gemm dW_fc");
-  } else {
+  TIDE_HIP(launch_gemm(full_dw(p.nqkv, p.d, ws + p.dqkv, p.nqkv, ws + p.a, p.d, G->w_qkv, p.d, acc), s), "gemm dW_qkv");
+  TIDE_HIP(launch_rmsnorm_bwd(T, (int)p.d, ws + p.da, ws + p.x0, P->g1, (const float*)(ws + p.r1), ws + p.dx1, ws + p.dx0, (float*)G->g1, dgp, dt, nullptr, s, acc), "rmsnorm1 bwd");
+  const void* dfeat = ws + p.dx0;   // gradient of the step's input feature (feature-only model: x0 is the feature)
+  if (tok) {
     // x0 = [g ; e] W_in^T: dW_in = dx0^T [g ; e] (two products into the column halves of dW_in), dg = dx0 W_in[:, :d]
-    // (the embedding table is frozen), then dW_fc = dg^T Hcat
+    // (the embedding table is frozen)
     float* dwin = (float*)tok->grad_w_in;
-    TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.d, T, ws + p.dx0, p.d, ws + p.g0, p.d, dwin, 2 * p.d, dt, kF32), s), "gemm dW_in (features)");
-    TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.d, T, ws + p.dx0, p.d, ws + p.e0, p.d, dwin + p.d, 2 * p.d, dt, kF32), s), "gemm dW_in (embeddings)");
+    TIDE_HIP(launch_gemm(full_dw(p.d, p.d, ws + p.dx0, p.d, ws + p.g0, p.d, dwin, 2 * p.d, acc), s), "gemm dW_in (features)");
+    TIDE_HIP(launch_gemm(full_dw(p.d, p.d, ws + p.dx0, p.d, ws + p.e0, p.d, dwin + p.d, 2 * p.d, acc), s), "gemm dW_in (embeddings)");
     TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.d, ws + p.dx0, p.d, tok->w_in, 2 * p.d, ws + p.dg0, p.d, dt, dt), s), "gemm dg");
-    TIDE_HIP(launch_gemm(gemm_args(kTN, p.d, p.KH, T, ws + p.dg0, p.d, hidden_buf, p.KH, G->w_fc, p.KH, dt, kF32), s), "gemm dW_fc");
+    dfeat = ws + p.dg0;
   }
+  if (shift == 0) {
+    // the feature is Hcat W_fc^T: weight gradient only, the captured states are data (step 1 is the only one
+    // that reads W_fc, so this is never an accumulation)
+    TIDE_HIP(launch_gemm(full_dw(p.d, p.KH, dfeat, p.d, hidden_buf, p.KH, G->w_fc, p.KH, 0), s), "gemm dW_fc");
+  } else {
+    // the feature is the layer output of the step before: hand its gradient over, dense over that step's rows
+    TIDE_HIP(launch_gather_rows(T, (int)p.d, dfeat, o.dfeat_out, 0, nullptr, nullptr, o.prev_tokens, (const uint8_t*)(o.prev_ws + p.mask_eff),
+                                (const int32_t*)(o.prev_ws + p.kept_idx), (const int*)(o.prev_ws + p.cnt), (int32_t*)(o.prev_ws + p.tokens_c),
+                                (uint8_t*)(o.prev_ws + p.mask_c), dt, s), "gather feature gradient");
+  }
+  return TIDE_OK;
+}
 
-  // AdamW over all tensors in one launch
-  {
-    AdamArgs a;
-    std::memset(&a, 0, sizeof(a));
-    void* pp[10] = {params->w_fc, params->g1, params->w_qkv, params->w_o, params->g2, params->w_gate, params->w_up, params->w_down, params->g3, params->w_lm};
-    void* gg[10] = {G->w_fc, G->g1, G->w_qkv, G->w_o, G->g2, G->w_gate, G->w_up, G->w_down, G->g3, G->w_lm};
-    void* mm[10] = {st->m.w_fc, st->m.g1, st->m.w_qkv, st->m.w_o, st->m.g2, st->m.w_gate, st->m.w_up, st->m.w_down, st->m.g3, st->m.w_lm};
-    void* vv[10] = {st->v.w_fc, st->v.g1, st->v.w_qkv, st->v.w_o, st->v.g2, st->v.w_gate, st->v.w_up, st->v.w_down, st->v.g3, st->v.w_lm};
-    void* ms[10] = {st->master.w_fc, st->master.g1, st->master.w_qkv, st->master.w_o, st->master.g2, st->master.w_gate, st->master.w_up, st->master.w_down, st->master.g3, st->master.w_lm};
-    const int64_t nn[10] = {p.d * p.KH, p.d, p.nqkv * p.d, p.d * p.nq, p.d, p.F * p.d, p.F * p.d, p.d * p.F, p.d, p.V * p.d};
-    for (int i = 0; i < 10; ++i) a.t[i] = AdamTensor{pp[i], (const float*)gg[i], (float*)mm[i], (float*)vv[i], dt == TIDE_DTYPE_BF16 ? (float*)ms[i] : nullptr, nn[i]};
-    a.nt = 10;
-    if (tok) {
-      a.t[10] = AdamTensor{tok->w_in, (const float*)tok->grad_w_in, (float*)tok->m_w_in, (float*)tok->v_w_in,
-                           dt == TIDE_DTYPE_BF16 ? (float*)tok->master_w_in : nullptr, 2 * p.d * p.d};
-      a.nt = 11;
-    }
-    const double t = (double)(st->step + 1);
-    a.lr = lr; a.beta1 = cfg->beta1; a.beta2 = cfg->beta2; a.eps = cfg->adam_eps; a.wd = cfg->weight_decay;
-    a.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta1, t)));
-    a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)cfg->beta2, t)));
-    a.dtype = dt;
-    TIDE_HIP(launch_adamw(a, s), "adamw");
+// AdamW over all tensors in one launch
+static int enqueue_adamw(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* G, tide_adam_state* st,
+                         const tide_token_input* tok, float lr, const Plan& p, hipStream_t s) {
+  const int dt = cfg->dtype;
+  AdamArgs a;
+  std::memset(&a, 0, sizeof(a));
+  void* pp[10] = {params->w_fc, params->g1, params->w_qkv, params->w_o, params->g2, params->w_gate, params->w_up, params->w_down, params->g3, params->w_lm};
+  void* gg[10] = {G->w_fc, G->g1, G->w_qkv, G->w_o, G->g2, G->w_gate, G->w_up, G->w_down, G->g3, G->w_lm};
+  void* mm[10] = {st->m.w_fc, st->m.g1, st->m.w_qkv, st->m.w_o, st->m.g2, st->m.w_gate, st->m.w_up, st->m.w_down, st->m.g3, st->m.w_lm};
+  void* vv[10] = {st->v.w_fc, st->v.g1, st->v.w_qkv, st->v.w_o, st->v.g2, st->v.w_gate, st->v.w_up, st->v.w_down, st->v.g3, st->v.w_lm};
+  void* ms[10] = {st->master.w_fc, st->master.g1, st->master.w_qkv, st->master.w_o, st->master.g2, st->master.w_gate, st->master.w_up, st->master.w_down, st->master.g3, st->master.w_lm};
+  const int64_t nn[10] = {p.d * p.KH, p.d, p.nqkv * p.d, p.d * p.nq, p.d, p.F * p.d, p.F * p.d, p.d * p.F, p.d, p.V * p.d};
+  for (int i = 0; i < 10; ++i) a.t[i] = AdamTensor{pp[i], (const float*)gg[i], (float*)mm[i], (float*)vv[i], dt == TIDE_DTYPE_BF16 ? (float*)ms[i] : nullptr, nn[i]};
+  a.nt = 10;
+  if (tok) {
+    a.t[10] = AdamTensor{tok->w_in, (const float*)tok->grad_w_in, (float*)tok->m_w_in, (float*)tok->v_w_in,
+                         dt == TIDE_DTYPE_BF16 ? (float*)tok->master_w_in : nullptr, 2 * p.d * p.d};
+    a.nt = 11;
   }
+  const double t = (double)(st->step + 1);
+  a.lr = lr; a.beta1 = cfg->beta1; a.beta2 = cfg->beta2; a.eps = cfg->adam_eps; a.wd = cfg->weight_decay;
+  a.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta1, t)));
+  a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)cfg->beta2, t)));
+  a.dtype = dt;
+  TIDE_HIP(launch_adamw(a, s), "adamw");
   st->step += 1;
   return TIDE_OK;
+}
+
+static int check_train_args(const tide_draft_config* cfg, tide_draft_tensors* grads, tide_adam_state* st, float lr) {
+  if (!tensors_ok(grads, "grads")) return TIDE_ERR_NULL;
+  if (!st) return fail(TIDE_ERR_NULL, "adam_state is NULL");
+  if (!tensors_ok(&st->m, "adam_state.m") || !tensors_ok(&st->v, "adam_state.v")) return TIDE_ERR_NULL;
+  if (cfg->dtype == TIDE_DTYPE_BF16 && !tensors_ok(&st->master, "adam_state.master")) return TIDE_ERR_NULL;
+  if (st->step < 0) return fail(TIDE_ERR_CONFIG, "adam_state.step must be >= 0");
+  if (!(lr >= 0.f)) return fail(TIDE_ERR_CONFIG, "lr must be >= 0");
+  return TIDE_OK;
+}
+
+static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                      tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf, const int32_t* tokens,
+                      const uint8_t* loss_mask, const Seqs* packed, float lr, float* loss_out, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  const Plan p = make_plan(cfg);
+  const Seqs q = packed ? *packed : fixed_seqs(cfg);
+  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
+  if (rc) return rc;
+  rc = check_train_args(cfg, grads, st, lr);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  rc = enqueue_trunk(cfg, params, tok, hidden_buf, tokens, loss_mask, 0, q, ws, p, s);
+  if (rc) return rc;
+  rc = enqueue_lm_head(cfg, params, grads, tokens, loss_mask, nullptr, loss_out, nullptr, ws, p, true, s);
+  if (rc) return rc;
+  rc = enqueue_backward(cfg, params, grads, tok, hidden_buf, q, ws, p, s, BwdOpts{});
+  if (rc) return rc;
+  return enqueue_adamw(cfg, params, grads, st, tok, lr, p, s);
+}
+
+int tide_draft_train_step_unroll(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                                 tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf,
+                                 const int32_t* tokens, const uint8_t* loss_mask, int32_t n_steps,
+                                 const float* step_weights, float lr, float* loss_out, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  if (n_steps < 1 || n_steps > kMaxUnroll) return fail(TIDE_ERR_CONFIG, "n_steps must be in [1, %d]", kMaxUnroll);
+  if (tok) { const int rc = check_token_input(tok, true, cfg->dtype); if (rc) return rc; }
+  if (step_weights)
+    for (int k = 0; k < n_steps; ++k)
+      if (!(step_weights[k] >= 0.f) || !std::isfinite(step_weights[k])) return fail(TIDE_ERR_CONFIG, "step_weights must be finite and >= 0");
+  const Plan p = make_plan(cfg);
+  const UnrollPlan u = make_unroll_plan(p, n_steps);
+  int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, u.step_bytes, p);
+  if (rc) return rc;
+  if (workspace_bytes < u.total) return fail(TIDE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, u.total);
+  rc = check_train_args(cfg, grads, st, lr);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  char* extra = ws + u.step_bytes * (size_t)n_steps;
+  const Seqs q = fixed_seqs(cfg);
+  UnrollStep ur[kMaxUnroll];
+  tide_token_input tk[kMaxUnroll];
+  std::memset(ur, 0, sizeof(ur));
+  // forward, step by step; the LM head of every step leaves dyhat in the step's workspace and adds its share of dW_lm
+  for (int k = 0; k < n_steps; ++k) {
+    char* wk = ws + u.step_bytes * (size_t)k;
+    char* ek = extra + u.extra_stride * (size_t)k;
+    int32_t* tokens_s = (int32_t*)(ek + u.tokens_s);
+    uint8_t* mask_s = (uint8_t*)(ek + u.mask_s);
+    uint8_t* sel_s = (uint8_t*)(ek + u.sel_s);
+    int32_t* ids_s = tok ? (int32_t*)(ek + u.ids_s) : nullptr;
+    TIDE_HIP(launch_shift_inputs(tokens, loss_mask, tok ? tok->input_ids : nullptr, p.T, cfg->seq, cfg->vocab, k, n_steps, tokens_s, mask_s, sel_s, ids_s, s), "shift inputs");
+    if (tok) { tk[k] = *tok; tk[k].input_ids = ids_s; }
+    if (k) ur[k] = ur[k - 1];          // the own pairs of the steps before
+    ur[k].shift = k;
+    ur[k].n_steps = n_steps;
+    ur[k].sel = sel_s;
+    ur[k].prev_ws = k ? ws + u.step_bytes * (size_t)(k - 1) : nullptr;
+    ur[k].first_ws = ws;
+    if (k) ur[k].own_kv[k - 1] = ek + u.own_kv;
+    rc = enqueue_trunk(cfg, params, tok ? &tk[k] : nullptr, hidden_buf, tokens_s, mask_s, 0, q, wk, p, s, &ur[k]);
+    if (rc) return rc;
+    rc = enqueue_lm_head(cfg, params, grads, tokens_s, mask_s, nullptr, loss_out + k, nullptr, wk, p, true, s,
+                         step_weights ? step_weights[k] : 1.f, k > 0);
+    if (rc) return rc;
+  }
+  // backward, last step first: a step's backward needs what every later step sends back into its output and
+  // into its keys and values
+  for (int k = n_steps - 1; k >= 0; --k) {
+    char* wk = ws + u.step_bytes * (size_t)k;
+    BwdOpts o;
+    o.accumulate = k != n_steps - 1;
+    o.ur = &ur[k];
+    o.dx2_extra = k < n_steps - 1 ? extra + u.extra_stride * (size_t)k + u.dfeat : nullptr;
+    for (int j = 0; j < kMaxUnroll; ++j) o.own_grad.kv[j] = j + 1 < n_steps ? extra + u.extra_stride * (size_t)(j + 1) + u.own_grad : nullptr;
+    o.acc_kv1 = extra + u.acc_kv1;
+    if (k) {
+      char* ep = extra + u.extra_stride * (size_t)(k - 1);
+      o.dfeat_out = ep + u.dfeat;
+      o.prev_ws = ws + u.step_bytes * (size_t)(k - 1);
+      o.prev_tokens = (const int32_t*)(ep + u.tokens_s);
+    }
+    rc = enqueue_backward(cfg, params, grads, tok ? &tk[k] : nullptr, hidden_buf, q, wk, p, s, o);
+    if (rc) return rc;
+  }
+  return enqueue_adamw(cfg, params, grads, st, tok, lr, p, s);
 }
 
 int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,

@@ -140,4 +140,122 @@ hipError_t launch_own_kv_merge_fwd(int B, int S, int nh, int nkv, int dh, const 
   return hipGetLastError();
 }
 
+// Backward of the merge, one wavefront per (row, key/value head), which owns the group of query heads that read
+// the pair.  With L, delta = rowsum(dO * O) of the merged result, for own pair j and query head h:
+//   p = exp(s_j - L),  ds = p * (dO_h . v_j - delta_h),
+//   dq_h += scale ds k_j,  dk_j += scale ds q_h,  dv_j += p dO_h.
+// dq is added to what the flash backward wrote into dqkv; (dk_j, dv_j) go to the pair's own gradient buffer,
+// written if first (the last step of the unroll, which reads every pair, runs its backward first), else added.
+template <typename T>
+__global__ __launch_bounds__(256) void own_kv_merge_bwd_kernel(const T* __restrict__ qkv, const T* __restrict__ dout,
+                                                               const float* __restrict__ lse,
+                                                               const float* __restrict__ delta, OwnKV own,
+                                                               OwnKVGrad grad, int n_own, int first, T* __restrict__ dqkv,
+                                                               int64_t n_pairs, int nh, int nkv, int dh, int S,
+                                                               float scale) {
+  const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (wid >= n_pairs) return;   // whole wavefronts leave; no barrier below
+  const int lane = threadIdx.x & 63;
+  const int64_t t = wid / nkv;
+  const int kh = (int)(wid % nkv), G = nh / nkv;
+  const int nq = nh * dh, nk = nkv * dh, ld = nq + 2 * nk;
+  const size_t stat0 = ((size_t)(t / S) * nh) * (size_t)S + (size_t)(t % S);
+  for (int j = 0; j < n_own; ++j) {
+    const T* kj = (const T*)own.kv[j] + (size_t)t * (2 * nk) + (size_t)kh * dh;
+    const T* vj = kj + nk;
+    float kv[kMaxDhPerLane], vv[kMaxDhPerLane], dk[kMaxDhPerLane], dv[kMaxDhPerLane];
+#pragma unroll
+    for (int c = 0; c < kMaxDhPerLane; ++c) {
+      const int e = lane + 64 * c;
+      kv[c] = e < dh ? ldf(kj, e) : 0.f;
+      vv[c] = e < dh ? ldf(vj, e) : 0.f;
+      dk[c] = dv[c] = 0.f;
+    }
+    for (int g = 0; g < G; ++g) {
+      const int h = kh * G + g;
+      const T* q = qkv + (size_t)t * ld + (size_t)h * dh;
+      const T* dO = dout + (size_t)t * nq + (size_t)h * dh;
+      T* dq = dqkv + (size_t)t * ld + (size_t)h * dh;
+      float qv[kMaxDhPerLane], dov[kMaxDhPerLane];
+      float sp = 0.f, dp = 0.f;
+#pragma unroll
+      for (int c = 0; c < kMaxDhPerLane; ++c) {
+        const int e = lane + 64 * c;
+        qv[c] = e < dh ? ldf(q, e) : 0.f;
+        dov[c] = e < dh ? ldf(dO, e) : 0.f;
+        sp += qv[c] * kv[c];
+        dp += dov[c] * vv[c];
+      }
+      sp = scale * wave_sum(sp);
+      dp = wave_sum(dp);
+      const size_t li = stat0 + (size_t)h * (size_t)S;
+      const float p = expf(sp - lse[li]);
+      const float ds = p * (dp - delta[li]);
+#pragma unroll
+      for (int c = 0; c < kMaxDhPerLane; ++c) {
+        const int e = lane + 64 * c;
+        if (e < dh) stf(dq, e, ldf(dq, e) + scale * ds * kv[c]);
+        dk[c] += scale * ds * qv[c];
+        dv[c] += p * dov[c];
+      }
+    }
+    T* gk = (T*)grad.kv[j] + (size_t)t * (2 * nk) + (size_t)kh * dh;
+    T* gv = gk + nk;
+#pragma unroll
+    for (int c = 0; c < kMaxDhPerLane; ++c) {
+      const int e = lane + 64 * c;
+      if (e < dh) {
+        stf(gk, e, first ? dk[c] : ldf(gk, e) + dk[c]);
+        stf(gv, e, first ? dv[c] : ldf(gv, e) + dv[c]);
+      }
+    }
+  }
+}
+
+hipError_t launch_own_kv_merge_bwd(int B, int S, int nh, int nkv, int dh, const void* qkv, const void* dout,
+                                   const float* lse, const float* delta, const OwnKV& own, const OwnKVGrad& grad,
+                                   int n_own, int first, void* dqkv, int dtype, hipStream_t s) {
+  const int64_t n_pairs = (int64_t)B * S * nkv;
+  if (n_pairs <= 0 || n_own <= 0) return hipSuccess;
+  if (n_own > kMaxUnroll || dh > 64 * kMaxDhPerLane || nh % nkv) return hipErrorInvalidValue;
+  ProfScope ps("own_kv_merge_bwd", 0, (double)B * S * nh * dh * (4.0 * n_own) * dtype_size(dtype), s);
+  const float scale = 1.0f / sqrtf((float)dh);
+  dim3 grid((unsigned)((n_pairs + 3) / 4)), blk(256);
+  if (dtype == kBF16) hipLaunchKernelGGL(own_kv_merge_bwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, delta, own, grad, n_own, first, (bf16_t*)dqkv, n_pairs, nh, nkv, dh, S, scale);
+  else hipLaunchKernelGGL(own_kv_merge_bwd_kernel<float>, grid, blk, 0, s, (const float*)qkv, (const float*)dout, lse, delta, own, grad, n_own, first, (float*)dqkv, n_pairs, nh, nkv, dh, S, scale);
+  return hipGetLastError();
+}
+
+// Key/value columns of a step's dqkv after the flash backward: for a later step they hold its share of the
+// STEP-1 key/value gradient.  mode 0: acc1 = them (first share), mode 1: acc1 += them; both then put the step's
+// own pair gradient (own_grad) in their place.  mode 2 (step 1 itself): them += acc1.
+template <typename T>
+__global__ __launch_bounds__(256) void kv_grad_route_kernel(T* __restrict__ dqkv, T* __restrict__ acc1,
+                                                            const T* __restrict__ own_grad, int nq, int nkv2, int ld,
+                                                            int mode) {
+  const size_t t = blockIdx.x;
+  T* row = dqkv + t * (size_t)ld + nq;
+  T* a = acc1 + t * (size_t)nkv2;
+  for (int e = threadIdx.x; e < nkv2; e += 256) {
+    const float v = ldf(row, e);
+    if (mode == 2) {
+      stf(row, e, v + ldf(a, e));
+    } else {
+      stf(a, e, mode == 0 ? v : v + ldf(a, e));
+      row[e] = own_grad[t * (size_t)nkv2 + e];
+    }
+  }
+}
+
+hipError_t launch_kv_grad_route(int64_t T, int nq, int nk, void* dqkv, void* acc1, const void* own_grad, int mode,
+                                int dtype, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  if (mode < 0 || mode > 2 || (mode != 2 && !own_grad)) return hipErrorInvalidValue;
+  ProfScope ps("kv_grad_route", 0, 8.0 * (double)T * nk * dtype_size(dtype), s);
+  const int ld = nq + 2 * nk;
+  if (dtype == kBF16) hipLaunchKernelGGL(kv_grad_route_kernel<bf16_t>, dim3((unsigned)T), dim3(256), 0, s, (bf16_t*)dqkv, (bf16_t*)acc1, (const bf16_t*)own_grad, nq, 2 * nk, ld, mode);
+  else hipLaunchKernelGGL(kv_grad_route_kernel<float>, dim3((unsigned)T), dim3(256), 0, s, (float*)dqkv, (float*)acc1, (const float*)own_grad, nq, 2 * nk, ld, mode);
+  return hipGetLastError();
+}
+
 }  // namespace tide

@@ -126,13 +126,25 @@ class DraftTrainer:
         return self.loss
 
     # ---- multi-step unroll: the draft fed its own output from the second step on ----
-    def eval_unroll(self, n_steps, token_input=False):
-        """(loss [n_steps], accuracy [n_steps]) device vectors; the unroll keeps a workspace of its own."""
+    def _unroll_workspace(self, n_steps):
         need = B.tide_draft_unroll_workspace_bytes(self.ccfg, n_steps)
         if need == 0:
             raise B.TideError(B.TIDE_ERR_CONFIG, B.tide_last_error())
         if getattr(self, "unroll_ws", None) is None or self.unroll_ws.numel() < need:
             self.unroll_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+
+    def train_step_unroll(self, lr, n_steps, step_weights=None, token_input=False):
+        """One AdamW step on sum_s step_weights[s] * loss_s; returns the per-step losses (device vector)."""
+        self._unroll_workspace(n_steps)
+        loss = torch.zeros(n_steps, dtype=torch.float32, device=self.device)
+        B.tide_draft_train_step_unroll(self.ccfg, self.c_params, self.c_grads, self.c_adam,
+                                       self.c_tok if token_input else None, self.hidden, self.tokens, self.mask, n_steps,
+                                       step_weights, lr, loss, self.unroll_ws, self.unroll_ws.numel(), self._stream())
+        return loss
+
+    def eval_unroll(self, n_steps, token_input=False):
+        """(loss [n_steps], accuracy [n_steps]) device vectors; the unroll keeps a workspace of its own."""
+        self._unroll_workspace(n_steps)
         loss = torch.zeros(n_steps, dtype=torch.float32, device=self.device)
         acc = torch.zeros(n_steps, dtype=torch.float32, device=self.device)
         B.tide_draft_eval_unroll(self.ccfg, self.c_params, self.c_tok if token_input else None, self.hidden, self.tokens,

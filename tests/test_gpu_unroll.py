@@ -1,6 +1,8 @@
-"""Multi-step evaluation unroll (the draft fed its own output from the second step on) through the C ABI against
-the fp64 oracle: per-step loss within 1e-4 (fp32) / 1e-2 (bf16) relative, per-step accuracy within a few rows
-(an arg-max can flip on a near tie), and the layer output of every step on the rows it selected."""
+"""Multi-step unroll (the draft fed its own output from the second step on) through the C ABI against the fp64
+oracle.  Evaluation: per-step loss within 1e-4 (fp32) / 1e-2 (bf16) relative, per-step accuracy within a few rows
+(an arg-max can flip on a near tie), and the layer output of every step on the rows it selected.  Training:
+the tolerances of the single step (fp32 1e-4 relative on losses and gradients; bf16 1e-2 on the losses, gradient
+cosine >= 0.999, parameters after the AdamW update within 2e-3)."""
 import numpy as np
 import pytest
 import torch
@@ -9,7 +11,7 @@ from oracle import tide_oracle as O
 from oracle import unroll_oracle as U
 from paper_2602_05145_amd import binding as B
 from paper_2602_05145_amd import workloads as W
-from tests.gpu_util import rel_max, sync
+from tests.gpu_util import cosine, rel_max, sync
 
 pytestmark = pytest.mark.gpu
 
@@ -84,6 +86,90 @@ def test_unroll_bf16(token_input):
     _check(cfg, token_input, 3, 1e-2, 3e-2)
 
 
+def _train_reference(cfg, wl, params, tok, n_steps, w, lr):
+    steps = U.unroll_forward(cfg, params, wl["hidden"].astype(np.float64), wl["tokens"], wl["mask"], n_steps, tok=tok, keep_cache=True)
+    grads = U.unroll_backward(cfg, params, steps, step_weights=w)
+    zeros = {k: np.zeros_like(v) for k, v in params.items()}
+    new_p, m, v, _ = O.adamw_step(cfg, params, grads, zeros, zeros, 0, lr)
+    return [st["loss"] for st in steps], grads, new_p
+
+
+def _device_grads(tr, token_input):
+    g = tr.host(tr.grads)
+    if token_input:
+        g["w_in"] = tr.grad_w_in.cpu().numpy().astype(np.float64)
+    return g
+
+
+@pytest.mark.parametrize("token_input", [False, True])
+@pytest.mark.parametrize("kw", [dict(), dict(batch=3, seq=37, target_hidden=24, hidden=48, n_heads=6, n_kv_heads=2,
+                                             head_dim=8, ffn=100, vocab=203)])
+def test_train_unroll_fp32(kw, token_input):
+    cfg = W.get_config("tiny", **kw)
+    wl, tr, params, tok = _setup(cfg, token_input)
+    w = [1.0, 0.7, 0.45]
+    loss_ref, g_ref, p1_ref = _train_reference(cfg, wl, params, tok, 3, w, cfg["lr"])
+    loss = tr.train_step_unroll(cfg["lr"], 3, step_weights=w, token_input=token_input)
+    sync()
+    assert tr.step == 1
+    for s in range(3):
+        assert abs(float(loss[s].item()) - loss_ref[s]) <= 1e-4 * abs(loss_ref[s]), s
+    g = _device_grads(tr, token_input)
+    for k in g_ref:
+        assert rel_max(g[k], g_ref[k]) <= 1e-4, (k, rel_max(g[k], g_ref[k]))
+    p = tr.host(tr.params)
+    for k in O.PARAM_NAMES:
+        solid = np.abs(g_ref[k]) >= 1e-4 * np.max(np.abs(g_ref[k]))
+        assert np.max(np.abs(p[k] - p1_ref[k])[solid]) <= 0.01 * cfg["lr"], k
+
+
+def test_train_unroll_fp32_two_and_five_steps_default_weights():
+    cfg = W.get_config("tiny", batch=2, seq=41, target_hidden=24, hidden=64, n_heads=4, n_kv_heads=2, head_dim=16, ffn=72, vocab=157)
+    for n in (2, 5):
+        wl, tr, params, tok = _setup(cfg, True)
+        loss_ref, g_ref, _ = _train_reference(cfg, wl, params, tok, n, None, cfg["lr"])
+        loss = tr.train_step_unroll(cfg["lr"], n, token_input=True)
+        sync()
+        g = _device_grads(tr, True)
+        for s in range(n):
+            assert abs(float(loss[s].item()) - loss_ref[s]) <= 1e-4 * abs(loss_ref[s]), (n, s)
+        for k in g_ref:
+            assert rel_max(g[k], g_ref[k]) <= 1e-4, (n, k, rel_max(g[k], g_ref[k]))
+
+
+def test_train_unroll_one_step_is_the_ordinary_training_step():
+    cfg = W.get_config("small", batch=2, seq=96, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128,
+                       ffn=256, vocab=512)
+    wl, a, _, _ = _setup(cfg, True)
+    _, b, _, _ = _setup(cfg, True)
+    la = a.train_step_unroll(cfg["lr"], 1, token_input=True)
+    b.train_step_tok(cfg["lr"])
+    sync()
+    assert float(la[0].item()) == float(b.loss.item())
+    for k in O.PARAM_NAMES:
+        assert torch.equal(a.grads[k], b.grads[k]) and torch.equal(a.params[k], b.params[k]), k
+    assert torch.equal(a.grad_w_in, b.grad_w_in) and torch.equal(a.w_in, b.w_in)
+
+
+@pytest.mark.parametrize("token_input", [False, True])
+def test_train_unroll_bf16(token_input):
+    cfg = W.get_config("small", batch=2, seq=160, target_hidden=64, hidden=512, n_heads=4, n_kv_heads=2, head_dim=128,
+                       ffn=256, vocab=512)
+    wl, tr, params, tok = _setup(cfg, token_input)
+    w = [1.0, 0.8, 0.64]
+    loss_ref, g_ref, p1_ref = _train_reference(cfg, wl, params, tok, 3, w, cfg["lr"])
+    loss = tr.train_step_unroll(cfg["lr"], 3, step_weights=w, token_input=token_input)
+    sync()
+    for s in range(3):
+        assert abs(float(loss[s].item()) - loss_ref[s]) <= 1e-2 * abs(loss_ref[s]), s
+    g = _device_grads(tr, token_input)
+    for k in g_ref:
+        assert cosine(g[k], g_ref[k]) >= 0.999, (k, cosine(g[k], g_ref[k]))
+    p = tr.host(tr.master)
+    for k in O.PARAM_NAMES:
+        assert np.max(np.abs(p[k] - p1_ref[k])) <= 2e-3, k
+
+
 def test_first_step_equals_the_single_step_evaluation():
     """One step selects the same rows as the plain evaluation: the same bits.  With more steps the first one also
     carries rows that only later steps need, so its sums run in another order."""
@@ -116,3 +202,9 @@ def test_argument_errors():
     assert B.tide_draft_eval_unroll(*args, 3, out, None, ws, need, stream, check=False) == B.TIDE_ERR_NULL
     assert B.tide_draft_eval_unroll(*args, 3, out, out, ws, need, stream, check=False) == B.TIDE_OK
     sync()
+    targs = (tr.ccfg, tr.c_params, tr.c_grads, tr.c_adam, None, tr.hidden, tr.tokens, tr.mask)
+    assert B.tide_draft_train_step_unroll(*targs, 3, [1.0, -1.0, 1.0], 1e-4, out, ws, need, stream, check=False) == B.TIDE_ERR_CONFIG
+    assert B.tide_draft_train_step_unroll(*targs, 3, [1.0, float("nan"), 1.0], 1e-4, out, ws, need, stream, check=False) == B.TIDE_ERR_CONFIG
+    assert B.tide_draft_train_step_unroll(*targs, 9, None, 1e-4, out, ws, need, stream, check=False) == B.TIDE_ERR_CONFIG
+    assert B.tide_draft_train_step_unroll(*targs, 3, None, 1e-4, out, ws, need - 1, stream, check=False) == B.TIDE_ERR_WORKSPACE
+    assert tr.step == 0
