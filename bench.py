@@ -136,6 +136,10 @@ def main():
     ap.add_argument("--token-input", action="store_true",
                     help="time the token-input variant (features joined with the sampled token's embedding through "
                          "W_in) instead of the benchmarked north-star path")
+    ap.add_argument("--unroll", type=int, default=0,
+                    help="time the training step over the multi-step unroll (the draft fed its own output from the "
+                         "second step on) with this many steps instead of the benchmarked single-step path; "
+                         "combines with --token-input")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -170,6 +174,11 @@ def main():
         tr.master_w_in = tr.w_in.float() if cfg["dtype"] == "bf16" else None
         tr.c_tok = B.make_token_input(tr.embed, tr.input_ids, tr.w_in, tr.grad_w_in, tr.m_w_in, tr.v_w_in, tr.master_w_in)
         step = tr.train_step_tok
+    if args.unroll:
+        unroll_loss = []
+
+        def step(lr_):
+            unroll_loss[:] = [tr.train_step_unroll(lr_, args.unroll, token_input=args.token_input)]
 
     for _ in range(args.warmup):
         step(lr)
@@ -222,7 +231,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    loss = float(tr.loss.item())
+    loss = float(tr.loss.item()) if not args.unroll else float(unroll_loss[0][0].item())
     assert loss == loss and loss > 0, f"bad loss {loss}"
 
     # what the matrix pipes sustain on this machine with nothing else going on (registers only): the practical ceiling
@@ -252,6 +261,21 @@ def main():
         extra = 6.0 * 2 * cfg["hidden"] * cfg["hidden"] * T   # W_in [d, 2d]: forward, dW_in (both halves) and dg, on every position
         flops_all += extra
         flops += extra
+    unroll_info = None
+    if args.unroll:
+        # step s >= 2 has no W_fc product, runs the layer up to the attention on every row and everything after
+        # it on the rows that carry loss at step s or later (their count comes from the shifted masks)
+        keep = ((tr.mask != 0) & (tr.tokens >= 0) & (tr.tokens < cfg["vocab"])).view(cfg["batch"], cfg["seq"])
+        shifted = [torch.nn.functional.pad(keep[:, j:], (0, j)) for j in range(args.unroll)]
+        rows = [int(torch.stack(shifted[j:]).any(dim=0).sum().item()) for j in range(args.unroll)]
+        per_step_all = flops_all - (6.0 * 2 * cfg["hidden"] * cfg["hidden"] * T if args.token_input else 0.0)
+        fc = 4.0 * ps["w_fc"] * T
+        in_proj = 6.0 * 2 * cfg["hidden"] * cfg["hidden"] * T if args.token_input else 0.0
+        flops = sum(per_step_all - (fc if j else 0.0) + in_proj - 6.0 * after_attention * (T - rows[j]) for j in range(args.unroll))
+        flops_all = args.unroll * (per_step_all + in_proj) - (args.unroll - 1) * fc
+        unroll_info = {"steps": args.unroll, "rows_after_attention_per_step": rows,
+                       "loss_per_step": [float(x) for x in unroll_loss[0].cpu()],
+                       "workspace_GiB": B.tide_draft_unroll_workspace_bytes(tr.ccfg, args.unroll) / 2**30}
     prof.sort(key=lambda r: -r["total_ms"])
     kernel_ms = sum(r["total_ms"] for r in prof)
     dom = max((r for r in prof if r["kernel"].startswith("gemm_mfma")), key=lambda r: r["total_ms"], default=None)
@@ -271,7 +295,7 @@ def main():
         "ms_per_step": ms, "inputs": ("pinned host -> device through the ingest ring, overlapped with the step"
                                       if args.ingest else "resident in HBM"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": ("token-input variant, " if args.token_input else "") + f"{cfg['name']}: batch {cfg['batch']} x seq {cfg['seq']}, 3x{cfg['target_hidden']} captured "
+        "config": {"workload": (f"{args.unroll}-step unroll, " if args.unroll else "") + ("token-input variant, " if args.token_input else "") + f"{cfg['name']}: batch {cfg['batch']} x seq {cfg['seq']}, 3x{cfg['target_hidden']} captured "
                                f"states -> d {cfg['hidden']}, {cfg['n_heads']}/{cfg['n_kv_heads']} heads x {cfg['head_dim']}, "
                                f"FFN {cfg['ffn']}, vocab {cfg['vocab']}", "global_batch": cfg["batch"], "seq_len": cfg["seq"],
                    "params_M": W.n_params(cfg) / 1e6, "loss_positions": n_loss, "positions": T},
@@ -289,7 +313,9 @@ def main():
                     for r in prof],
         "kernel_ms_per_step": kernel_ms / args.steps,
     }
-    if not args.no_cpu_baseline:
+    if unroll_info:
+        out["unroll"] = unroll_info
+    if not args.no_cpu_baseline and not args.unroll:
         del tr
         torch.cuda.empty_cache()
         sb, ss = (int(x) for x in args.cpu_sample.lower().split("x"))

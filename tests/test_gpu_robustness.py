@@ -112,6 +112,46 @@ def test_poisoned_workspace_token_input():
     assert guards_intact(big, tr.ws_bytes)
 
 
+def test_poisoned_workspace_unroll():
+    """The unroll's workspace holds sums that later steps add to (own key/value gradients, the step-1 key/value
+    gradient, weight gradients): every one of them must be written before it is added to."""
+    from paper_2602_05145_amd import binding as B
+    from paper_2602_05145_amd import runtime
+    cfg = W.get_config("small", batch=2, seq=120, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128,
+                       ffn=256, vocab=512)
+    wl = W.make_workload(cfg)
+    ti = W.make_token_input(cfg)
+    results = []
+    for poison in (False, True):
+        tr = runtime.trainer_from_workload(cfg, wl)
+        tr.set_token_input(ti["embed"], ti["input_ids"], ti["w_in"])
+        need = B.tide_draft_unroll_workspace_bytes(tr.ccfg, 3)
+        big = torch.full((need + 2 * GUARD,), 0xFF if poison else 0, dtype=torch.uint8, device=tr.device)
+        tr.unroll_ws = big[GUARD:GUARD + need]
+        if poison:
+            for g in tr.grads.values():
+                g.fill_(float("nan"))
+            tr.grad_w_in.fill_(float("nan"))
+        ev = tr.eval_unroll(3, token_input=True)
+        sync()
+        ev = [x.clone() for x in ev]
+        if poison:
+            assert bool((big[:GUARD] == 0xFF).all()) and bool((big[GUARD + need:] == 0xFF).all())
+            big.fill_(0xFF)
+        loss = tr.train_step_unroll(cfg["lr"], 3, step_weights=[1.0, 0.5, 0.25], token_input=True).clone()
+        sync()
+        if poison:
+            assert bool((big[:GUARD] == 0xFF).all()) and bool((big[GUARD + need:] == 0xFF).all())
+        results.append((tr, ev, loss))
+    (a, ev_a, loss_a), (b, ev_b, loss_b) = results
+    assert torch.equal(ev_a[0], ev_b[0]) and torch.equal(ev_a[1], ev_b[1]) and torch.equal(loss_a, loss_b)
+    assert bool(torch.isfinite(loss_b).all())
+    for k in O.PARAM_NAMES:
+        assert bool(torch.isfinite(b.grads[k]).all()), k
+        assert torch.equal(a.grads[k], b.grads[k]) and torch.equal(a.params[k], b.params[k]), k
+    assert torch.equal(a.grad_w_in, b.grad_w_in) and torch.equal(a.w_in, b.w_in)
+
+
 def test_checkpoint_resume():
     """Parameters, both moments, the master copy and the step counter are caller-owned: copying them out and
     into a fresh trainer continues the run bit for bit."""
