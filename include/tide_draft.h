@@ -243,6 +243,12 @@ int tide_draft_train_step_tok(const tide_draft_config *cfg, tide_draft_tensors *
  * Fixed-layout batches only.  Enqueues kernels on `stream` and nothing else; errors as in tide_draft_forward,
  * TIDE_ERR_CONFIG for n_steps outside [1, 8]. */
 size_t tide_draft_unroll_workspace_bytes(const tide_draft_config *cfg, int32_t n_steps);
+/* For tests and profiling: byte offset, inside the unroll workspace of n_steps steps, of intermediate `name` of
+ * step `step` (0-based).  Names: those of tide_draft_workspace_offset (the step's own single-step workspace),
+ * and "tokens_s", "mask_s", "sel_s", "ids_s" (the step's shifted inputs and row selection), "own_kv" ([B*S,
+ * 2*n_kv_heads*head_dim]: the step's own keys then values), "own_grad", "dfeat", "acc_kv1".  -1 if unknown. */
+int64_t tide_draft_unroll_workspace_offset(const tide_draft_config *cfg, int32_t n_steps, int32_t step,
+                                           const char *name);
 int tide_draft_eval_unroll(const tide_draft_config *cfg, const tide_draft_tensors *params,
                            const tide_token_input *tok,
                            const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,

@@ -43,7 +43,7 @@ variant is "parity unpinned"; what pins it is mathematics: W_in = [I | 0]
 reproduces the base model exactly, W_in = [0 | I] makes the result independent
 of the captured states, central finite differences on W_in and W_fc, and torch CPU
 fp64 autograd over F.embedding / torch.cat / F.linear.  The
-multi-step training unroll of that architecture is not part of this oracle.
+multi-step unroll of that architecture (the draft fed its own output) is in unroll_oracle.py.
 """
 from __future__ import annotations
 

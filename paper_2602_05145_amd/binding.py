@@ -87,6 +87,8 @@ _lib.tide_draft_train_step_tok.restype = _i32
 _lib.tide_draft_train_step_tok.argtypes = [_cfgp, _tp, _tp, _ap, _tokp, _vp, _vp, _vp, _f32, _vp, _vp, _sz, _vp]
 _lib.tide_draft_unroll_workspace_bytes.restype = _sz
 _lib.tide_draft_unroll_workspace_bytes.argtypes = [_cfgp, _i32]
+_lib.tide_draft_unroll_workspace_offset.restype = _i64
+_lib.tide_draft_unroll_workspace_offset.argtypes = [_cfgp, _i32, _i32, C.c_char_p]
 _lib.tide_draft_eval_unroll.restype = _i32
 _lib.tide_draft_eval_unroll.argtypes = [_cfgp, _tp, _tokp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
 _lib.tide_draft_train_step_unroll.restype = _i32
@@ -116,7 +118,7 @@ _lib.tide_profile_stop.argtypes = [C.c_char_p, _sz]
 EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
             "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_draft_forward_packed",
     "tide_draft_train_step_packed", "tide_draft_forward_tok", "tide_draft_train_step_tok",
-    "tide_draft_unroll_workspace_bytes", "tide_draft_eval_unroll", "tide_draft_train_step_unroll",
+    "tide_draft_unroll_workspace_bytes", "tide_draft_unroll_workspace_offset", "tide_draft_eval_unroll", "tide_draft_train_step_unroll",
     "tide_mfma_probe",
     "tide_ingest_create", "tide_ingest_destroy", "tide_ingest_acquire", "tide_ingest_submit", "tide_ingest_wait",
     "tide_ingest_done", "tide_ingest_last_error", "tide_gemm_workspace_bytes", "tide_gemm",
@@ -202,6 +204,10 @@ def tide_draft_train_step_tok(cfg, params, grads, adam_state, tok, hidden_buf, t
 
 def tide_draft_unroll_workspace_bytes(cfg: TideDraftConfig, n_steps: int) -> int:
     return int(_lib.tide_draft_unroll_workspace_bytes(C.byref(cfg), int(n_steps)))
+
+
+def tide_draft_unroll_workspace_offset(cfg: TideDraftConfig, n_steps: int, step: int, name: str) -> int:
+    return int(_lib.tide_draft_unroll_workspace_offset(C.byref(cfg), int(n_steps), int(step), name.encode()))
 
 
 def tide_draft_eval_unroll(cfg, params, tok, hidden_buf, tokens, loss_mask, n_steps, loss_out, accuracy_out, workspace,

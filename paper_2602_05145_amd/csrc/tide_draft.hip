@@ -500,6 +500,20 @@ size_t tide_draft_unroll_workspace_bytes(const tide_draft_config* cfg, int32_t n
   return make_unroll_plan(make_plan(cfg), n_steps).total;
 }
 
+// Byte offset inside the unroll workspace: of a single-step intermediate of step `step` (names as in
+// tide_draft_workspace_offset), or of one of the step's extras; -1 if unknown.
+int64_t tide_draft_unroll_workspace_offset(const tide_draft_config* cfg, int32_t n_steps, int32_t step, const char* name) {
+  if (!check_config(cfg) || !name || n_steps < 1 || n_steps > kMaxUnroll || step < 0 || step >= n_steps) return -1;
+  const UnrollPlan u = make_unroll_plan(make_plan(cfg), n_steps);
+  const size_t extra = u.step_bytes * (size_t)n_steps + u.extra_stride * (size_t)step;
+  struct { const char* n; size_t o; } tab[] = {{"tokens_s", u.tokens_s}, {"mask_s", u.mask_s}, {"sel_s", u.sel_s}, {"ids_s", u.ids_s},
+                                               {"own_kv", u.own_kv}, {"own_grad", u.own_grad}, {"dfeat", u.dfeat}, {"acc_kv1", u.acc_kv1}};
+  for (auto& e : tab)
+    if (std::strcmp(e.n, name) == 0) return (int64_t)(extra + e.o);
+  const int64_t o = tide_draft_workspace_offset(cfg, name);
+  return o < 0 ? -1 : (int64_t)(u.step_bytes * (size_t)step) + o;
+}
+
 int tide_draft_eval_unroll(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,
                            const void* hidden_buf, const int32_t* tokens, const uint8_t* loss_mask, int32_t n_steps,
                            float* loss_out, float* accuracy_out, void* workspace, size_t workspace_bytes, void* stream) {

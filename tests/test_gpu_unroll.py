@@ -31,13 +31,13 @@ def _setup(cfg, token_input):
     return wl, tr, params, tok
 
 
-def _step_rows(tr, step, name, width):
+def _step_rows(tr, n_steps, step, name, width):
     """Dense rows of a named intermediate of one step, and the row indices they belong to."""
-    base = step * ((tr.ws_bytes + 255) // 256 * 256)
     ws = tr.unroll_ws
 
     def view(nm, nbytes, dt):
-        off = base + B.tide_draft_workspace_offset(tr.ccfg, nm)
+        off = B.tide_draft_unroll_workspace_offset(tr.ccfg, n_steps, step, nm)
+        assert off >= 0
         return ws[off:off + nbytes].view(dt)
     cnt = int(view("cnt", 4, torch.int32).item())
     idx = view("kept_idx", 4 * cnt, torch.int32).cpu().numpy()
@@ -56,7 +56,7 @@ def _check(cfg, token_input, n_steps, tol, x_tol):
     for s in range(n_steps):
         assert abs(loss[s] - ref[s]["loss"]) <= tol * abs(ref[s]["loss"]), (s, loss[s], ref[s]["loss"])
         assert abs(acc[s] - ref[s]["accuracy"]) <= max(2.0, 0.01 * ref[s]["n"]) / ref[s]["n"] + 1e-6, (s, acc[s], ref[s]["accuracy"])
-        idx, x2 = _step_rows(tr, s, "x2", cfg["hidden"])
+        idx, x2 = _step_rows(tr, n_steps, s, "x2", cfg["hidden"])
         # the rows a step selects: those that carry loss at this or a later step
         need = np.zeros(T, bool)
         for j in range(s, n_steps):
@@ -208,3 +208,51 @@ def test_argument_errors():
     assert B.tide_draft_train_step_unroll(*targs, 9, None, 1e-4, out, ws, need, stream, check=False) == B.TIDE_ERR_CONFIG
     assert B.tide_draft_train_step_unroll(*targs, 3, None, 1e-4, out, ws, need - 1, stream, check=False) == B.TIDE_ERR_WORKSPACE
     assert tr.step == 0
+
+
+def test_unroll_at_the_benchmarked_size_prefix_of_one_sequence_against_oracle():
+    """8B-shaped batch in bf16, 3 steps.  By causality the first rows of a sequence depend on that prefix alone at
+    every step (step s row i needs the step-1 keys of rows 0..i and the labels up to i + s - 1), so an oracle unroll
+    over the prefix gives their layer outputs and loss terms exactly."""
+    import bench
+    cfg = W.get_config("8b")
+    dev = torch.device("cuda:0")
+    print("generating the 8b workload on the device", flush=True)
+    params, hidden, tokens, mask = bench.device_workload(cfg, dev, cfg["seed"])
+    tr = bench.DeviceTrainer(cfg, params, hidden, tokens, mask)
+    n_steps = 3
+    print("3-step evaluation unroll at full size", flush=True)
+    loss, acc = tr.eval_unroll(n_steps)
+    l1, a1 = tr.eval()
+    sync()
+    assert bool(torch.isfinite(loss).all()) and bool(((acc >= 0) & (acc <= 1)).all())
+    assert abs(float(loss[0].item()) - float(l1.item())) <= 1e-5 * float(l1.item())
+    b, S, d = cfg["batch"] - 1, cfg["seq"], cfg["hidden"]
+    first_loss = int(torch.nonzero(tr.mask[b] != 0)[0].item())
+    L = first_loss + 48
+    sub = dict(cfg, batch=1, seq=L)
+    params64 = {k: v.float().cpu().numpy().astype(np.float64) for k, v in params.items()}
+    hid = tr.hidden[b, :L].float().cpu().numpy().astype(np.float64)[None]
+    tok = tr.tokens[b, :L].cpu().numpy()[None]
+    msk = tr.mask[b, :L].cpu().numpy()[None]
+    print(f"oracle unroll over the {L}-position prefix", flush=True)
+    ref = U.unroll_forward(sub, params64, hid, tok, msk, n_steps)
+    for s in range(n_steps):
+        idx, x2 = _step_rows(tr, n_steps, s, "x2", d)
+        sel = (idx >= b * S) & (idx < b * S + L - (n_steps - 1))        # rows whose whole chain lies inside the prefix
+        assert sel.sum() >= 40
+        local = idx[sel] - b * S
+        x_ref = ref[s]["x2"][local]
+        assert cosine(x2[sel], x_ref) > 0.9995, (s, cosine(x2[sel], x_ref))
+        assert np.max(np.abs(x2[sel] - x_ref)) <= 3e-2 * np.max(np.abs(x_ref)), s
+        # loss terms of the same rows: lse - z[label] where the step's shifted mask is set
+        off = B.tide_draft_unroll_workspace_offset(tr.ccfg, n_steps, s, "loss_rows")
+        terms = tr.unroll_ws[off:off + 4 * len(idx)].view(torch.float32).cpu().numpy()[sel]
+        yhat, _ = O.rmsnorm_fwd(x_ref, params64["g3"], cfg["rms_eps"])
+        z = yhat @ params64["w_lm"].T
+        lab = ref[s]["tokens"].reshape(-1)[local]
+        keep = O.effective_mask(lab, ref[s]["mask"].reshape(-1)[local], cfg["vocab"])
+        zmax = z.max(axis=-1)
+        t_ref = np.where(keep, zmax + np.log(np.exp(z - zmax[:, None]).sum(-1)) - z[np.arange(len(lab)), np.where(keep, lab, 0)], 0.0)
+        assert np.all(terms[~keep] == 0.0)
+        assert abs(terms.sum() - t_ref.sum()) <= 1e-2 * abs(t_ref.sum()), (s, terms.sum(), t_ref.sum())
