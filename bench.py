@@ -22,8 +22,8 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 fl
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the GEMM instantiations at the 8B shape, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0 after calibration against a plain copy): profiles/gemm_8b_hbm_traffic.txt
-MEASURED_TRAFFIC_8B = {"gemm_mfma_tn_256_f32out": 11.29e9, "gemm_mfma_nt_256_bf16out": 10.35e9,
-                       "gemm_mfma_nn_256_bf16out": 11.89e9}
+MEASURED_TRAFFIC_8B = {"gemm_mfma_tn_256_f32out": 11.31e9, "gemm_mfma_nt_256_bf16out": 10.78e9,
+                       "gemm_mfma_nn_256_bf16out": 11.86e9}
 
 
 def device_workload(cfg, device, seed):
