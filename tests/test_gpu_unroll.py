@@ -170,6 +170,36 @@ def test_train_unroll_bf16(token_input):
         assert np.max(np.abs(p[k] - p1_ref[k])) <= 2e-3, k
 
 
+def test_more_steps_than_positions_and_an_all_masked_batch():
+    """Steps whose positions have all left the sequence carry no loss: loss 0, and they add nothing to the
+    gradients.  A batch without any loss row gives zero losses and exactly zero gradients at every step."""
+    cfg = W.get_config("tiny", batch=3, seq=2, target_hidden=24, hidden=48, n_heads=6, n_kv_heads=2, head_dim=8, ffn=100,
+                       vocab=203, mask="none")
+    wl, tr, params, tok = _setup(cfg, True)
+    loss_ref, g_ref, _ = _train_reference(cfg, wl, params, tok, 4, None, cfg["lr"])
+    assert loss_ref[2] == 0.0 and loss_ref[3] == 0.0
+    loss = tr.train_step_unroll(cfg["lr"], 4, token_input=True)
+    sync()
+    assert float(loss[2].item()) == 0.0 and float(loss[3].item()) == 0.0
+    for s in range(2):
+        assert abs(float(loss[s].item()) - loss_ref[s]) <= 1e-4 * abs(loss_ref[s]), s
+    g = _device_grads(tr, True)
+    for k in g_ref:
+        assert rel_max(g[k], g_ref[k]) <= 1e-4, (k, rel_max(g[k], g_ref[k]))
+    # nothing carries loss
+    cfg2 = W.get_config("tiny")
+    wl2, tr2, _, _ = _setup(cfg2, False)
+    tr2.mask.zero_()
+    for g_ in tr2.grads.values():
+        g_.fill_(7.0)
+    loss2 = tr2.train_step_unroll(cfg2["lr"], 3)
+    ev_loss, ev_acc = tr2.eval_unroll(3)
+    sync()
+    assert bool((loss2 == 0).all()) and bool((ev_loss == 0).all()) and bool((ev_acc == 0).all())
+    for k in O.PARAM_NAMES:
+        assert bool((tr2.grads[k] == 0).all()), k
+
+
 def test_first_step_equals_the_single_step_evaluation():
     """One step selects the same rows as the plain evaluation: the same bits.  With more steps the first one also
     carries rows that only later steps need, so its sums run in another order."""
