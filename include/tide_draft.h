@@ -240,8 +240,8 @@ int tide_draft_train_step_tok(const tide_draft_config *cfg, tide_draft_tensors *
  *   workspace     DEVICE, 256-byte aligned, at least tide_draft_unroll_workspace_bytes(cfg, n_steps) bytes
  *                 (0 = invalid config or n_steps): one workspace of the single-step call per step plus the
  *                 shifted inputs and own key/value pairs
- * Fixed-layout batches only.  Enqueues kernels on `stream` and nothing else; errors as in tide_draft_forward,
- * TIDE_ERR_CONFIG for n_steps outside [1, 8]. */
+ * Fixed-layout batches (packed ones: the _packed forms below).  Enqueues kernels on `stream` and nothing else;
+ * errors as in tide_draft_forward, TIDE_ERR_CONFIG for n_steps outside [1, 8]. */
 size_t tide_draft_unroll_workspace_bytes(const tide_draft_config *cfg, int32_t n_steps);
 /* For tests and profiling: byte offset, inside the unroll workspace of n_steps steps, of intermediate `name` of
  * step `step` (0-based).  Names: those of tide_draft_workspace_offset (the step's own single-step workspace),
@@ -263,13 +263,32 @@ int tide_draft_eval_unroll(const tide_draft_config *cfg, const tide_draft_tensor
  *   loss_out      DEVICE float [n_steps]: the unweighted mean cross-entropy of every step, before the update
  *   grads         out: gradients of L, overwritten
  *   workspace     as in tide_draft_eval_unroll (the same size query covers both calls)
- * Fixed-layout batches only; errors as in tide_draft_train_step, TIDE_ERR_CONFIG for a bad n_steps or weight. */
+ * Errors as in tide_draft_train_step, TIDE_ERR_CONFIG for a bad n_steps or weight. */
 int tide_draft_train_step_unroll(const tide_draft_config *cfg, tide_draft_tensors *params,
                                  tide_draft_tensors *grads, tide_adam_state *adam_state,
                                  const tide_token_input *tok,
                                  const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
                                  int32_t n_steps, const float *step_weights, float lr, float *loss_out,
                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* The two unroll calls on PACKED (variable-length) batches: cu_seqlens, n_seqs, max_seqlen as in
+ * tide_draft_forward_packed; every sequence is unrolled by itself (a row's position i + s - 1 must stay inside its
+ * own sequence), padding rows carry nothing, and every step's loss is the mean over that step's loss-carrying
+ * rows of the whole batch.  With n_steps = 1 and tok given this is the token-input model on a packed batch.
+ * Errors as in the fixed-layout calls plus those of tide_draft_forward_packed (malformed offsets: status word). */
+int tide_draft_eval_unroll_packed(const tide_draft_config *cfg, const tide_draft_tensors *params,
+                                  const tide_token_input *tok,
+                                  const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                                  const int32_t *cu_seqlens, int32_t n_seqs, int32_t max_seqlen,
+                                  int32_t n_steps, float *loss_out, float *accuracy_out,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+int tide_draft_train_step_unroll_packed(const tide_draft_config *cfg, tide_draft_tensors *params,
+                                        tide_draft_tensors *grads, tide_adam_state *adam_state,
+                                        const tide_token_input *tok,
+                                        const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                                        const int32_t *cu_seqlens, int32_t n_seqs, int32_t max_seqlen,
+                                        int32_t n_steps, const float *step_weights, float lr, float *loss_out,
+                                        void *workspace, size_t workspace_bytes, void *stream);
 
 /* Message of the last error on the calling thread (static storage, never NULL). */
 const char *tide_last_error(void);

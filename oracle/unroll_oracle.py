@@ -226,3 +226,38 @@ def unroll_backward(cfg, params, steps, step_weights=None):
         else:
             dx2_next = dfeat
     return g
+
+
+def unroll_train_quantities_packed(cfg, params, hidden_rows, tokens, loss_mask, cu_seqlens, n_steps, tok=None,
+                                   step_weights=None):
+    """Per-step losses and the gradients of L = sum_s w_s loss_s for a PACKED batch (row t belongs to sequence i iff
+    cu_seqlens[i] <= t < cu_seqlens[i+1]; other rows are padding).  Sequences are independent samples and every
+    step's loss is the mean over that step's loss-carrying rows of the whole batch, so each sequence runs the
+    single-sequence unroll above and enters step s with its share n_is / N_s of that step's loss rows.
+    tok: dict(embed, input_ids [T]).  Returns (losses [n_steps], grads)."""
+    cu = [int(c) for c in cu_seqlens]
+    tokens = np.asarray(tokens).reshape(-1)
+    T = tokens.shape[0]
+    hidden_rows = np.asarray(hidden_rows, F64).reshape(T, -1)
+    mask = np.asarray(loss_mask).reshape(-1)
+    w = np.ones(n_steps, F64) if step_weights is None else np.asarray(step_weights, F64)
+    runs = []
+    for i in range(len(cu) - 1):
+        a, b = cu[i], cu[i + 1]
+        if b <= a:
+            continue
+        sub = dict(cfg, batch=1, seq=b - a)
+        tk = None if tok is None else dict(embed=tok["embed"], input_ids=np.asarray(tok["input_ids"]).reshape(-1)[a:b][None])
+        steps = unroll_forward(sub, params, hidden_rows[a:b][None], tokens[a:b][None], mask[a:b][None], n_steps, tok=tk, keep_cache=True)
+        counts = [int(O.effective_mask(st["tokens"], st["mask"], cfg["vocab"]).sum()) for st in steps]
+        runs.append((sub, steps, counts))
+    N = [max(1, sum(r[2][s] for r in runs)) for s in range(n_steps)]
+    losses = [sum(r[1][s]["loss"] * r[2][s] / N[s] for r in runs) for s in range(n_steps)]
+    grads = {k: np.zeros(np.asarray(v).shape, F64) for k, v in params.items()}
+    for sub, steps, counts in runs:
+        if not any(counts):
+            continue
+        g = unroll_backward(sub, params, steps, step_weights=[w[s] * counts[s] / N[s] for s in range(n_steps)])
+        for k in grads:
+            grads[k] += g[k]
+    return [float(x) for x in losses], grads

@@ -93,6 +93,11 @@ _lib.tide_draft_eval_unroll.restype = _i32
 _lib.tide_draft_eval_unroll.argtypes = [_cfgp, _tp, _tokp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
 _lib.tide_draft_train_step_unroll.restype = _i32
 _lib.tide_draft_train_step_unroll.argtypes = [_cfgp, _tp, _tp, _ap, _tokp, _vp, _vp, _vp, _i32, C.POINTER(C.c_float), _f32, _vp, _vp, _sz, _vp]
+_lib.tide_draft_eval_unroll_packed.restype = _i32
+_lib.tide_draft_eval_unroll_packed.argtypes = [_cfgp, _tp, _tokp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
+_lib.tide_draft_train_step_unroll_packed.restype = _i32
+_lib.tide_draft_train_step_unroll_packed.argtypes = [_cfgp, _tp, _tp, _ap, _tokp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
+                                                     C.POINTER(C.c_float), _f32, _vp, _vp, _sz, _vp]
 _lib.tide_gemm_workspace_bytes.restype = _sz
 _lib.tide_gemm_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32]
 _lib.tide_gemm.restype = _i32
@@ -119,6 +124,7 @@ EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspa
             "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_draft_forward_packed",
     "tide_draft_train_step_packed", "tide_draft_forward_tok", "tide_draft_train_step_tok",
     "tide_draft_unroll_workspace_bytes", "tide_draft_unroll_workspace_offset", "tide_draft_eval_unroll", "tide_draft_train_step_unroll",
+    "tide_draft_eval_unroll_packed", "tide_draft_train_step_unroll_packed",
     "tide_mfma_probe",
     "tide_ingest_create", "tide_ingest_destroy", "tide_ingest_acquire", "tide_ingest_submit", "tide_ingest_wait",
     "tide_ingest_done", "tide_ingest_last_error", "tide_gemm_workspace_bytes", "tide_gemm",
@@ -231,6 +237,32 @@ def tide_draft_train_step_unroll(cfg, params, grads, adam_state, tok, hidden_buf
                                            C.byref(tok) if tok is not None else None,
                                            _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), int(n_steps), w, float(lr),
                                            _ptr(loss_out), _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_draft_eval_unroll_packed(cfg, params, tok, hidden_buf, tokens, loss_mask, cu_seqlens, n_seqs, max_seqlen, n_steps,
+                                  loss_out, accuracy_out, workspace, workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_eval_unroll_packed(C.byref(cfg) if cfg is not None else None,
+                                            C.byref(params) if params is not None else None,
+                                            C.byref(tok) if tok is not None else None,
+                                            _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(cu_seqlens), int(n_seqs),
+                                            int(max_seqlen), int(n_steps), _ptr(loss_out), _ptr(accuracy_out),
+                                            _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_draft_train_step_unroll_packed(cfg, params, grads, adam_state, tok, hidden_buf, tokens, loss_mask, cu_seqlens,
+                                        n_seqs, max_seqlen, n_steps, step_weights, lr, loss_out, workspace,
+                                        workspace_bytes, stream, check=True):
+    w = None if step_weights is None else (C.c_float * len(step_weights))(*[float(x) for x in step_weights])
+    rc = _lib.tide_draft_train_step_unroll_packed(C.byref(cfg) if cfg is not None else None,
+                                                  C.byref(params) if params is not None else None,
+                                                  C.byref(grads) if grads is not None else None,
+                                                  C.byref(adam_state) if adam_state is not None else None,
+                                                  C.byref(tok) if tok is not None else None,
+                                                  _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(cu_seqlens),
+                                                  int(n_seqs), int(max_seqlen), int(n_steps), w, float(lr),
+                                                  _ptr(loss_out), _ptr(workspace), int(workspace_bytes), stream)
     return _check(rc) if check else rc
 
 

@@ -136,23 +136,25 @@ hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 
 // ---- unroll.hip: the multi-step unroll (the draft fed its own output) ------------------------------
 constexpr int kMaxUnroll = 8;
-// tokens / mask / input ids (ids, ids_s optional) moved left by `shift` inside every sequence of S rows, and
-// sel_s[t] = 1 where row t carries loss at a step in (shift, n_steps]
+// tokens / mask / input ids (ids, ids_s optional) moved left by `shift` inside every sequence (S rows each, or
+// the packed sequences given by the device offsets cu[0..nseq]; padding rows carry nothing), and sel_s[t] = 1
+// where row t carries loss at a step in (shift, n_steps]
 hipError_t launch_shift_inputs(const int32_t* tokens, const uint8_t* mask, const int32_t* ids, int64_t T, int S, int V,
                                int shift, int n_steps, int32_t* tokens_s, uint8_t* mask_s, uint8_t* sel_s,
-                               int32_t* ids_s, hipStream_t s);
+                               int32_t* ids_s, const int* cu, int nseq, hipStream_t s);
 // own[T, 2 nk] = key/value columns of qkv (rows of nq + 2 nk), which then receive those of qkv1
 hipError_t launch_kv_swap(int64_t T, int nq, int nk, void* qkv, const void* qkv1, void* own, int dtype, hipStream_t s);
 struct OwnKV { const void* kv[kMaxUnroll]; };   // per later step: [T, 2 nk], keys then values
 // merges the n_own own key/value pairs of every row into the causal attention result (out, lse) over step 1
-hipError_t launch_own_kv_merge_fwd(int B, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse,
-                                   const OwnKV& own, int n_own, int dtype, hipStream_t s);
+// T rows; lse / delta are [T / S, nh, S], or [nh, T] if packed
+hipError_t launch_own_kv_merge_fwd(int64_t T, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse,
+                                   const OwnKV& own, int n_own, int packed, int dtype, hipStream_t s);
 struct OwnKVGrad { void* kv[kMaxUnroll]; };   // gradient buffers of the same pairs, same layout
 // backward of the merge: adds the pairs' share to the query gradients in dqkv and writes (first) or adds the
 // pairs' own gradients; lse / delta are those of the merged result
-hipError_t launch_own_kv_merge_bwd(int B, int S, int nh, int nkv, int dh, const void* qkv, const void* dout,
+hipError_t launch_own_kv_merge_bwd(int64_t T, int S, int nh, int nkv, int dh, const void* qkv, const void* dout,
                                    const float* lse, const float* delta, const OwnKV& own, const OwnKVGrad& grad,
-                                   int n_own, int first, void* dqkv, int dtype, hipStream_t s);
+                                   int n_own, int first, void* dqkv, int packed, int dtype, hipStream_t s);
 // key/value columns of dqkv <-> the running step-1 key/value gradient acc1 [T, 2 nk]: mode 0 acc1 = columns,
 // mode 1 acc1 += columns (both then put own_grad [T, 2 nk] into the columns), mode 2 columns += acc1
 hipError_t launch_kv_grad_route(int64_t T, int nq, int nk, void* dqkv, void* acc1, const void* own_grad, int mode,

@@ -303,7 +303,7 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
     if (shift > 0) {
       OwnKV own;
       for (int j = 0; j < kMaxUnroll; ++j) own.kv[j] = j < shift ? ur->own_kv[j] : nullptr;
-      TIDE_HIP(launch_own_kv_merge_fwd(c->batch, c->seq, c->n_heads, c->n_kv_heads, c->head_dim, ws + p.qkv, ws + p.A, (float*)(ws + p.attn_lse), own, shift, dt, s), "own kv merge");
+      TIDE_HIP(launch_own_kv_merge_fwd(T, c->seq, c->n_heads, c->n_kv_heads, c->head_dim, ws + p.qkv, ws + p.A, (float*)(ws + p.attn_lse), own, shift, q.cu != nullptr, dt, s), "own kv merge");
     }
     // padding rows are written by no sequence: make them finite (they enter weight-gradient contractions)
     if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.A, q.cu, q.n, T, (int64_t)(p.nq * p.es), s), "zero padding rows");
@@ -514,10 +514,10 @@ int64_t tide_draft_unroll_workspace_offset(const tide_draft_config* cfg, int32_t
   return o < 0 ? -1 : (int64_t)(u.step_bytes * (size_t)step) + o;
 }
 
-int tide_draft_eval_unroll(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,
-                           const void* hidden_buf, const int32_t* tokens, const uint8_t* loss_mask, int32_t n_steps,
-                           float* loss_out, float* accuracy_out, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+static int eval_unroll_impl(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,
+                            const void* hidden_buf, const int32_t* tokens, const uint8_t* loss_mask, const Seqs* packed,
+                            int32_t n_steps, float* loss_out, float* accuracy_out, void* workspace, size_t workspace_bytes,
+                            void* stream) {
   if (n_steps < 1 || n_steps > kMaxUnroll) return fail(TIDE_ERR_CONFIG, "n_steps must be in [1, %d]", kMaxUnroll);
   if (!accuracy_out) return fail(TIDE_ERR_NULL, "accuracy_out is NULL");
   if (tok) { const int rc = check_token_input(tok, false, cfg->dtype); if (rc) return rc; }
@@ -531,7 +531,7 @@ int tide_draft_eval_unroll(const tide_draft_config* cfg, const tide_draft_tensor
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
   char* extra = ws + u.step_bytes * (size_t)n_steps;
-  const Seqs q = fixed_seqs(cfg);
+  const Seqs q = packed ? *packed : fixed_seqs(cfg);
   UnrollStep ur;
   std::memset(&ur, 0, sizeof(ur));
   ur.n_steps = n_steps;
@@ -542,7 +542,7 @@ int tide_draft_eval_unroll(const tide_draft_config* cfg, const tide_draft_tensor
     uint8_t* mask_s = (uint8_t*)(ek + u.mask_s);
     uint8_t* sel_s = (uint8_t*)(ek + u.sel_s);
     int32_t* ids_s = tok ? (int32_t*)(ek + u.ids_s) : nullptr;
-    TIDE_HIP(launch_shift_inputs(tokens, loss_mask, tok ? tok->input_ids : nullptr, p.T, cfg->seq, cfg->vocab, k, n_steps, tokens_s, mask_s, sel_s, ids_s, s), "shift inputs");
+    TIDE_HIP(launch_shift_inputs(tokens, loss_mask, tok ? tok->input_ids : nullptr, p.T, cfg->seq, cfg->vocab, k, n_steps, tokens_s, mask_s, sel_s, ids_s, q.cu, q.n, s), "shift inputs");
     tide_token_input tk;
     if (tok) { tk = *tok; tk.input_ids = ids_s; }
     ur.shift = k;
@@ -625,7 +625,6 @@ static int enqueue_backward(const tide_draft_config* cfg, const tide_draft_tenso
     AttnArgs at = attn_args(cfg, q, ws, p);
     at.dout = ws + p.dA; at.delta = (float*)(ws + p.delta); at.dqkv = ws + p.dqkv;
     TIDE_HIP(launch_attn_bwd(at, s), "attention bwd");
-    if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.dqkv, q.cu, q.n, T, (int64_t)(p.nqkv * p.es), s), "zero padding rows");
   }
   if (o.ur && shift > 0) {
     // later step of the unroll: the flash backward saw the step's queries beside the STEP-1 keys/values.  Add the
@@ -634,11 +633,14 @@ static int enqueue_backward(const tide_draft_config* cfg, const tide_draft_tenso
     OwnKV own;
     for (int j = 0; j < kMaxUnroll; ++j) own.kv[j] = j < shift ? o.ur->own_kv[j] : nullptr;
     const int last = shift == o.ur->n_steps - 1;
-    TIDE_HIP(launch_own_kv_merge_bwd(cfg->batch, cfg->seq, cfg->n_heads, cfg->n_kv_heads, cfg->head_dim, ws + p.qkv, ws + p.dA, (const float*)(ws + p.attn_lse), (const float*)(ws + p.delta), own, o.own_grad, shift, last, ws + p.dqkv, dt, s), "own kv merge bwd");
+    TIDE_HIP(launch_own_kv_merge_bwd(T, cfg->seq, cfg->n_heads, cfg->n_kv_heads, cfg->head_dim, ws + p.qkv, ws + p.dA, (const float*)(ws + p.attn_lse), (const float*)(ws + p.delta), own, o.own_grad, shift, last, ws + p.dqkv, q.cu != nullptr, dt, s), "own kv merge bwd");
     TIDE_HIP(launch_kv_grad_route(T, (int)p.nq, (int)p.nk, ws + p.dqkv, o.acc_kv1, o.own_grad.kv[shift - 1], last ? 0 : 1, dt, s), "kv grad route");
   } else if (o.ur && o.ur->n_steps > 1) {
     TIDE_HIP(launch_kv_grad_route(T, (int)p.nq, (int)p.nk, ws + p.dqkv, o.acc_kv1, nullptr, 2, dt, s), "kv grad route");
   }
+  // padding rows of a packed batch are written by no sequence (or hold whatever the merge made of them): make
+  // them zero before the contractions over all rows
+  if (q.cu) TIDE_HIP(launch_zero_padding_rows(ws + p.dqkv, q.cu, q.n, T, (int64_t)(p.nqkv * p.es), s), "zero padding rows");
   { const int rc2 = enqueue_rope(cfg, q, ws, p, ws + p.dqkv, 1, shift, s); if (rc2) return rc2; }
   TIDE_HIP(launch_gemm(gemm_args(kNN, T, p.d, p.nqkv, ws + p.dqkv, p.nqkv, P->w_qkv, p.d, ws + p.da, p.d, dt, dt), s), "gemm da");
   TIDE_HIP(launch_gemm(full_dw(p.nqkv, p.d, ws + p.dqkv, p.nqkv, ws + p.a, p.d, G->w_qkv, p.d, acc), s), "gemm dW_qkv");
@@ -726,12 +728,11 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
   return enqueue_adamw(cfg, params, grads, st, tok, lr, p, s);
 }
 
-int tide_draft_train_step_unroll(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
-                                 tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf,
-                                 const int32_t* tokens, const uint8_t* loss_mask, int32_t n_steps,
-                                 const float* step_weights, float lr, float* loss_out, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
-  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+static int train_unroll_impl(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                             tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf,
+                             const int32_t* tokens, const uint8_t* loss_mask, const Seqs* packed, int32_t n_steps,
+                             const float* step_weights, float lr, float* loss_out, void* workspace,
+                             size_t workspace_bytes, void* stream) {
   if (n_steps < 1 || n_steps > kMaxUnroll) return fail(TIDE_ERR_CONFIG, "n_steps must be in [1, %d]", kMaxUnroll);
   if (tok) { const int rc = check_token_input(tok, true, cfg->dtype); if (rc) return rc; }
   if (step_weights)
@@ -747,7 +748,7 @@ int tide_draft_train_step_unroll(const tide_draft_config* cfg, tide_draft_tensor
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
   char* extra = ws + u.step_bytes * (size_t)n_steps;
-  const Seqs q = fixed_seqs(cfg);
+  const Seqs q = packed ? *packed : fixed_seqs(cfg);
   UnrollStep ur[kMaxUnroll];
   tide_token_input tk[kMaxUnroll];
   std::memset(ur, 0, sizeof(ur));
@@ -759,7 +760,7 @@ int tide_draft_train_step_unroll(const tide_draft_config* cfg, tide_draft_tensor
     uint8_t* mask_s = (uint8_t*)(ek + u.mask_s);
     uint8_t* sel_s = (uint8_t*)(ek + u.sel_s);
     int32_t* ids_s = tok ? (int32_t*)(ek + u.ids_s) : nullptr;
-    TIDE_HIP(launch_shift_inputs(tokens, loss_mask, tok ? tok->input_ids : nullptr, p.T, cfg->seq, cfg->vocab, k, n_steps, tokens_s, mask_s, sel_s, ids_s, s), "shift inputs");
+    TIDE_HIP(launch_shift_inputs(tokens, loss_mask, tok ? tok->input_ids : nullptr, p.T, cfg->seq, cfg->vocab, k, n_steps, tokens_s, mask_s, sel_s, ids_s, q.cu, q.n, s), "shift inputs");
     if (tok) { tk[k] = *tok; tk[k].input_ids = ids_s; }
     if (k) ur[k] = ur[k - 1];          // the own pairs of the steps before
     ur[k].shift = k;
@@ -794,6 +795,45 @@ int tide_draft_train_step_unroll(const tide_draft_config* cfg, tide_draft_tensor
     if (rc) return rc;
   }
   return enqueue_adamw(cfg, params, grads, st, tok, lr, p, s);
+}
+
+int tide_draft_eval_unroll(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,
+                           const void* hidden_buf, const int32_t* tokens, const uint8_t* loss_mask, int32_t n_steps,
+                           float* loss_out, float* accuracy_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  return eval_unroll_impl(cfg, params, tok, hidden_buf, tokens, loss_mask, nullptr, n_steps, loss_out, accuracy_out, workspace, workspace_bytes, stream);
+}
+
+int tide_draft_eval_unroll_packed(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,
+                                  const void* hidden_buf, const int32_t* tokens, const uint8_t* loss_mask,
+                                  const int32_t* cu_seqlens, int32_t n_seqs, int32_t max_seqlen, int32_t n_steps,
+                                  float* loss_out, float* accuracy_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const int rc = check_packed(cfg, cu_seqlens, n_seqs, max_seqlen);
+  if (rc) return rc;
+  const Seqs q{cu_seqlens, n_seqs, max_seqlen};
+  return eval_unroll_impl(cfg, params, tok, hidden_buf, tokens, loss_mask, &q, n_steps, loss_out, accuracy_out, workspace, workspace_bytes, stream);
+}
+
+int tide_draft_train_step_unroll(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                                 tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf,
+                                 const int32_t* tokens, const uint8_t* loss_mask, int32_t n_steps,
+                                 const float* step_weights, float lr, float* loss_out, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  return train_unroll_impl(cfg, params, grads, st, tok, hidden_buf, tokens, loss_mask, nullptr, n_steps, step_weights, lr, loss_out, workspace, workspace_bytes, stream);
+}
+
+int tide_draft_train_step_unroll_packed(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                                        tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf,
+                                        const int32_t* tokens, const uint8_t* loss_mask, const int32_t* cu_seqlens,
+                                        int32_t n_seqs, int32_t max_seqlen, int32_t n_steps, const float* step_weights,
+                                        float lr, float* loss_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  const int rc = check_packed(cfg, cu_seqlens, n_seqs, max_seqlen);
+  if (rc) return rc;
+  const Seqs q{cu_seqlens, n_seqs, max_seqlen};
+  return train_unroll_impl(cfg, params, grads, st, tok, hidden_buf, tokens, loss_mask, &q, n_steps, step_weights, lr, loss_out, workspace, workspace_bytes, stream);
 }
 
 int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,

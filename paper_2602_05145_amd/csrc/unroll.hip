@@ -19,16 +19,33 @@ __global__ __launch_bounds__(256) void shift_inputs_kernel(const int32_t* __rest
                                                            const int32_t* __restrict__ ids, int64_t T, int S, int V,
                                                            int shift, int n_steps, int32_t* __restrict__ tokens_s,
                                                            uint8_t* __restrict__ mask_s, uint8_t* __restrict__ sel_s,
-                                                           int32_t* __restrict__ ids_s) {
+                                                           int32_t* __restrict__ ids_s, const int* __restrict__ cu,
+                                                           int nseq) {
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= T) return;
-  const int i = (int)(t % S);
-  const bool in = i + shift < S;
+  // end = one past the last row of the sequence that owns row t (t itself for a padding row of a packed batch)
+  int64_t end;
+  if (cu) {
+    const int64_t c0 = min(max((int64_t)cu[0], (int64_t)0), T), cN = min(max((int64_t)cu[nseq], c0), T);
+    if (t < c0 || t >= cN) {
+      end = t;
+    } else {
+      int lo = 0, hi = nseq;               // largest b with cu[b] <= t
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= t) lo = mid; else hi = mid;
+      }
+      end = min(max((int64_t)cu[lo + 1], t + 1), cN);   // inside the buffers whatever the offsets hold
+    }
+  } else {
+    end = (t / S + 1) * (int64_t)S;
+  }
+  const bool in = t + shift < end;
   tokens_s[t] = in ? tokens[t + shift] : -1;
   mask_s[t] = in ? mask[t + shift] : (uint8_t)0;
   if (ids_s) ids_s[t] = in ? ids[t + shift] : -1;
   int sel = 0;
-  for (int j = shift; j < n_steps && i + j < S; ++j) {
+  for (int j = shift; j < n_steps && t + j < end; ++j) {
     const int tk = tokens[t + j];
     if (mask[t + j] != 0 && tk >= 0 && tk < V) sel = 1;
   }
@@ -37,9 +54,9 @@ __global__ __launch_bounds__(256) void shift_inputs_kernel(const int32_t* __rest
 
 hipError_t launch_shift_inputs(const int32_t* tokens, const uint8_t* mask, const int32_t* ids, int64_t T, int S, int V,
                                int shift, int n_steps, int32_t* tokens_s, uint8_t* mask_s, uint8_t* sel_s,
-                               int32_t* ids_s, hipStream_t s) {
+                               int32_t* ids_s, const int* cu, int nseq, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  hipLaunchKernelGGL(shift_inputs_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, tokens, mask, ids, T, S, V, shift, n_steps, tokens_s, mask_s, sel_s, ids_s);
+  hipLaunchKernelGGL(shift_inputs_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, tokens, mask, ids, T, S, V, shift, n_steps, tokens_s, mask_s, sel_s, ids_s, cu, nseq);
   return hipGetLastError();
 }
 
@@ -78,7 +95,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void own_kv_merge_fwd_kernel(const T* __restrict__ qkv, T* __restrict__ out,
                                                                float* __restrict__ lse, OwnKV own, int n_own,
                                                                int64_t n_pairs, int nh, int nkv, int dh, int S,
-                                                               float scale) {
+                                                               float scale, int64_t packed_T) {
   const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (wid >= n_pairs) return;   // whole wavefronts leave; no barrier below
   const int lane = threadIdx.x & 63;
@@ -103,7 +120,8 @@ __global__ __launch_bounds__(256) void own_kv_merge_fwd_kernel(const T* __restri
     }
     sc[j] = scale * wave_sum(part);
   }
-  const size_t li = ((size_t)(t / S) * nh + h) * (size_t)S + (size_t)(t % S);
+  // lse is [B, nh, S] in the fixed layout and [nh, T] for a packed batch
+  const size_t li = packed_T ? (size_t)h * (size_t)packed_T + (size_t)t : ((size_t)(t / S) * nh + h) * (size_t)S + (size_t)(t % S);
   const float l0 = lse[li];
   float m = l0;
   for (int j = 0; j < n_own; ++j) m = fmaxf(m, sc[j]);
@@ -127,16 +145,17 @@ __global__ __launch_bounds__(256) void own_kv_merge_fwd_kernel(const T* __restri
   if (lane == 0) lse[li] = L;
 }
 
-hipError_t launch_own_kv_merge_fwd(int B, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse,
-                                   const OwnKV& own, int n_own, int dtype, hipStream_t s) {
-  const int64_t n_pairs = (int64_t)B * S * nh;
+hipError_t launch_own_kv_merge_fwd(int64_t T, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse,
+                                   const OwnKV& own, int n_own, int packed, int dtype, hipStream_t s) {
+  const int64_t n_pairs = T * nh;
+  const int64_t packed_T = packed ? T : 0;
   if (n_pairs <= 0 || n_own <= 0) return hipSuccess;
   if (n_own > kMaxUnroll || dh > 64 * kMaxDhPerLane || nh % nkv) return hipErrorInvalidValue;
   ProfScope ps("own_kv_merge_fwd", 0, (double)n_pairs * dh * (3.0 + 2.0 * n_own) * dtype_size(dtype), s);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)((n_pairs + 3) / 4)), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(own_kv_merge_fwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)qkv, (bf16_t*)out, lse, own, n_own, n_pairs, nh, nkv, dh, S, scale);
-  else hipLaunchKernelGGL(own_kv_merge_fwd_kernel<float>, grid, blk, 0, s, (const float*)qkv, (float*)out, lse, own, n_own, n_pairs, nh, nkv, dh, S, scale);
+  if (dtype == kBF16) hipLaunchKernelGGL(own_kv_merge_fwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)qkv, (bf16_t*)out, lse, own, n_own, n_pairs, nh, nkv, dh, S, scale, packed_T);
+  else hipLaunchKernelGGL(own_kv_merge_fwd_kernel<float>, grid, blk, 0, s, (const float*)qkv, (float*)out, lse, own, n_own, n_pairs, nh, nkv, dh, S, scale, packed_T);
   return hipGetLastError();
 }
 
@@ -152,14 +171,16 @@ __global__ __launch_bounds__(256) void own_kv_merge_bwd_kernel(const T* __restri
                                                                const float* __restrict__ delta, OwnKV own,
                                                                OwnKVGrad grad, int n_own, int first, T* __restrict__ dqkv,
                                                                int64_t n_pairs, int nh, int nkv, int dh, int S,
-                                                               float scale) {
+                                                               float scale, int64_t packed_T) {
   const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (wid >= n_pairs) return;   // whole wavefronts leave; no barrier below
   const int lane = threadIdx.x & 63;
   const int64_t t = wid / nkv;
   const int kh = (int)(wid % nkv), G = nh / nkv;
   const int nq = nh * dh, nk = nkv * dh, ld = nq + 2 * nk;
-  const size_t stat0 = ((size_t)(t / S) * nh) * (size_t)S + (size_t)(t % S);
+  // lse / delta: [B, nh, S] in the fixed layout, [nh, T] for a packed batch; index = stat0 + h * stat_h
+  const size_t stat0 = packed_T ? (size_t)t : ((size_t)(t / S) * nh) * (size_t)S + (size_t)(t % S);
+  const size_t stat_h = packed_T ? (size_t)packed_T : (size_t)S;
   for (int j = 0; j < n_own; ++j) {
     const T* kj = (const T*)own.kv[j] + (size_t)t * (2 * nk) + (size_t)kh * dh;
     const T* vj = kj + nk;
@@ -188,7 +209,7 @@ __global__ __launch_bounds__(256) void own_kv_merge_bwd_kernel(const T* __restri
       }
       sp = scale * wave_sum(sp);
       dp = wave_sum(dp);
-      const size_t li = stat0 + (size_t)h * (size_t)S;
+      const size_t li = stat0 + (size_t)h * stat_h;
       const float p = expf(sp - lse[li]);
       const float ds = p * (dp - delta[li]);
 #pragma unroll
@@ -212,17 +233,18 @@ __global__ __launch_bounds__(256) void own_kv_merge_bwd_kernel(const T* __restri
   }
 }
 
-hipError_t launch_own_kv_merge_bwd(int B, int S, int nh, int nkv, int dh, const void* qkv, const void* dout,
+hipError_t launch_own_kv_merge_bwd(int64_t T, int S, int nh, int nkv, int dh, const void* qkv, const void* dout,
                                    const float* lse, const float* delta, const OwnKV& own, const OwnKVGrad& grad,
-                                   int n_own, int first, void* dqkv, int dtype, hipStream_t s) {
-  const int64_t n_pairs = (int64_t)B * S * nkv;
+                                   int n_own, int first, void* dqkv, int packed, int dtype, hipStream_t s) {
+  const int64_t n_pairs = T * nkv;
+  const int64_t packed_T = packed ? T : 0;
   if (n_pairs <= 0 || n_own <= 0) return hipSuccess;
   if (n_own > kMaxUnroll || dh > 64 * kMaxDhPerLane || nh % nkv) return hipErrorInvalidValue;
-  ProfScope ps("own_kv_merge_bwd", 0, (double)B * S * nh * dh * (4.0 * n_own) * dtype_size(dtype), s);
+  ProfScope ps("own_kv_merge_bwd", 0, (double)T * nh * dh * (4.0 * n_own) * dtype_size(dtype), s);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)((n_pairs + 3) / 4)), blk(256);
-  if (dtype == kBF16) hipLaunchKernelGGL(own_kv_merge_bwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, delta, own, grad, n_own, first, (bf16_t*)dqkv, n_pairs, nh, nkv, dh, S, scale);
-  else hipLaunchKernelGGL(own_kv_merge_bwd_kernel<float>, grid, blk, 0, s, (const float*)qkv, (const float*)dout, lse, delta, own, grad, n_own, first, (float*)dqkv, n_pairs, nh, nkv, dh, S, scale);
+  if (dtype == kBF16) hipLaunchKernelGGL(own_kv_merge_bwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, delta, own, grad, n_own, first, (bf16_t*)dqkv, n_pairs, nh, nkv, dh, S, scale, packed_T);
+  else hipLaunchKernelGGL(own_kv_merge_bwd_kernel<float>, grid, blk, 0, s, (const float*)qkv, (const float*)dout, lse, delta, own, grad, n_own, first, (float*)dqkv, n_pairs, nh, nkv, dh, S, scale, packed_T);
   return hipGetLastError();
 }
 

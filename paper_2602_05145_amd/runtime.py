@@ -133,22 +133,35 @@ class DraftTrainer:
         if getattr(self, "unroll_ws", None) is None or self.unroll_ws.numel() < need:
             self.unroll_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
 
-    def train_step_unroll(self, lr, n_steps, step_weights=None, token_input=False):
-        """One AdamW step on sum_s step_weights[s] * loss_s; returns the per-step losses (device vector)."""
+    def train_step_unroll(self, lr, n_steps, step_weights=None, token_input=False, packed=False):
+        """One AdamW step on sum_s step_weights[s] * loss_s; returns the per-step losses (device vector).
+        packed: the batch is the packed one of set_packed."""
         self._unroll_workspace(n_steps)
         loss = torch.zeros(n_steps, dtype=torch.float32, device=self.device)
-        B.tide_draft_train_step_unroll(self.ccfg, self.c_params, self.c_grads, self.c_adam,
-                                       self.c_tok if token_input else None, self.hidden, self.tokens, self.mask, n_steps,
-                                       step_weights, lr, loss, self.unroll_ws, self.unroll_ws.numel(), self._stream())
+        tok = self.c_tok if token_input else None
+        if packed:
+            B.tide_draft_train_step_unroll_packed(self.ccfg, self.c_params, self.c_grads, self.c_adam, tok, self.hidden,
+                                                  self.tokens, self.mask, self.cu, self.n_seqs, self.max_seqlen, n_steps,
+                                                  step_weights, lr, loss, self.unroll_ws, self.unroll_ws.numel(), self._stream())
+        else:
+            B.tide_draft_train_step_unroll(self.ccfg, self.c_params, self.c_grads, self.c_adam, tok, self.hidden, self.tokens,
+                                           self.mask, n_steps, step_weights, lr, loss, self.unroll_ws, self.unroll_ws.numel(),
+                                           self._stream())
         return loss
 
-    def eval_unroll(self, n_steps, token_input=False):
+    def eval_unroll(self, n_steps, token_input=False, packed=False):
         """(loss [n_steps], accuracy [n_steps]) device vectors; the unroll keeps a workspace of its own."""
         self._unroll_workspace(n_steps)
         loss = torch.zeros(n_steps, dtype=torch.float32, device=self.device)
         acc = torch.zeros(n_steps, dtype=torch.float32, device=self.device)
-        B.tide_draft_eval_unroll(self.ccfg, self.c_params, self.c_tok if token_input else None, self.hidden, self.tokens,
-                                 self.mask, n_steps, loss, acc, self.unroll_ws, self.unroll_ws.numel(), self._stream())
+        tok = self.c_tok if token_input else None
+        if packed:
+            B.tide_draft_eval_unroll_packed(self.ccfg, self.c_params, tok, self.hidden, self.tokens, self.mask, self.cu,
+                                            self.n_seqs, self.max_seqlen, n_steps, loss, acc, self.unroll_ws,
+                                            self.unroll_ws.numel(), self._stream())
+        else:
+            B.tide_draft_eval_unroll(self.ccfg, self.c_params, tok, self.hidden, self.tokens, self.mask, n_steps, loss, acc,
+                                     self.unroll_ws, self.unroll_ws.numel(), self._stream())
         return loss, acc
 
     def train_step(self, lr):

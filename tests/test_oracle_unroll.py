@@ -164,3 +164,23 @@ def test_one_step_gradients_are_the_single_step_gradients():
     got = U.unroll_backward(cfg, params, U.unroll_forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], 1, tok=tok, keep_cache=True))
     for k in ref:
         np.testing.assert_allclose(got[k], ref[k], rtol=1e-12, atol=1e-14)
+
+
+def test_packed_unroll_of_equal_lengths_is_the_batched_unroll():
+    """The per-sequence combination (shares n_is / N_s) reproduces the batched definition when all sequences have
+    the batch's length, losses and gradients alike."""
+    cfg = micro_cfg(batch=3, seq=5, mask="bernoulli", mask_p=0.4)
+    wl = micro_workload(cfg)
+    tok = _token_input(cfg)
+    params = dict({k: np.asarray(v, np.float64) for k, v in wl["params"].items()}, **{O.TOKEN_PARAM: tok["w_in"]})
+    w = [1.0, 0.6, 0.3]
+    steps = U.unroll_forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], 3, tok=tok, keep_cache=True)
+    g_ref = U.unroll_backward(cfg, params, steps, step_weights=w)
+    T = cfg["batch"] * cfg["seq"]
+    losses, g = U.unroll_train_quantities_packed(cfg, params, wl["hidden"].reshape(T, -1), wl["tokens"].reshape(-1),
+                                                 wl["mask"].reshape(-1), [0, 5, 10, 15], 3,
+                                                 tok=dict(embed=tok["embed"], input_ids=tok["input_ids"].reshape(-1)), step_weights=w)
+    for s in range(3):
+        assert abs(losses[s] - steps[s]["loss"]) <= 1e-12 * max(1.0, abs(losses[s]))
+    for k in g_ref:
+        np.testing.assert_allclose(g[k], g_ref[k], rtol=1e-10, atol=1e-13)
