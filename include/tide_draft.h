@@ -39,7 +39,7 @@
  *   - dtype TIDE_DTYPE_FP32: params, hidden_buf are float.  dtype TIDE_DTYPE_BF16:
  *     params and hidden_buf are bfloat16 (raw 16-bit), compute accumulates in
  *     fp32.  Gradients, Adam moments and master weights are always float.
- *   - HIP graphs: the forward-only calls (tide_draft_forward, _eval, _forward_packed, _forward_tok) enqueue
+ *   - HIP graphs: the forward-only calls (tide_draft_forward, _eval, _forward_packed, _forward_tok, _eval_unroll, _eval_unroll_packed) enqueue
  *     kernels and nothing else, so they can be captured on `stream` and replayed (call once before the capture:
  *     the first call on a device sets function attributes).  A training step bakes adam_state->step (bias
  *     corrections) and lr into its launch: a captured step would replay with the captured values.

@@ -250,3 +250,43 @@ def test_forward_and_eval_replay_from_a_hip_graph():
         assert float(tr.loss.item()) == float(loss_e.item()), i
         assert float(acc.item()) == float(acc_e.item()), i
         assert tr.status() == 0
+
+
+def test_eval_unroll_replays_from_a_hip_graph():
+    """The evaluation unroll too enqueues kernels and nothing else: captured once, replayed on new inputs written
+    into the captured buffers, every replay must match an eager call bit for bit."""
+    from paper_2602_05145_amd import binding as B
+    from paper_2602_05145_amd import runtime
+    cfg = W.get_config("small", batch=2, seq=160, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128,
+                       ffn=264, vocab=1000)
+    wl = W.make_workload(cfg)
+    ti = W.make_token_input(cfg)
+    tr, eager = (runtime.trainer_from_workload(cfg, wl) for _ in range(2))
+    for t in (tr, eager):
+        t.set_token_input(ti["embed"], ti["input_ids"], ti["w_in"])
+    tr.eval_unroll(3, token_input=True)                    # warm-up outside the capture; allocates the unroll workspace
+    sync()
+    loss = torch.zeros(3, dtype=torch.float32, device=tr.device)
+    acc = torch.zeros(3, dtype=torch.float32, device=tr.device)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.tide_draft_eval_unroll(tr.ccfg, tr.c_params, tr.c_tok, tr.hidden, tr.tokens, tr.mask, 3, loss, acc, tr.unroll_ws,
+                                     tr.unroll_ws.numel(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(3):
+        wl_i = W.make_workload(cfg, seed=700 + i)
+        for t in (tr, eager):
+            t.hidden.copy_(torch.from_numpy(wl_i["hidden"]).to(t.device).to(t.hidden.dtype))
+            t.tokens.copy_(torch.from_numpy(wl_i["tokens"]).to(t.device))
+            t.mask.copy_(torch.from_numpy(wl_i["mask"]).to(t.device))
+        loss.fill_(-1.0)
+        acc.fill_(-1.0)
+        sync()
+        graph.replay()
+        sync()
+        loss_e, acc_e = eager.eval_unroll(3, token_input=True)
+        sync()
+        assert torch.equal(loss, loss_e) and torch.equal(acc, acc_e), i
