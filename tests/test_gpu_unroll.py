@@ -325,3 +325,54 @@ def test_unroll_training_raises_held_out_accuracy_at_every_step():
     for s in range(3):
         assert np.isfinite(loss1[s]) and loss1[s] < 0.7 * loss0[s], (s, loss0, loss1)
         assert acc0[s] < 0.08 and acc1[s] > 0.15, (s, acc0, acc1)
+
+
+def test_unroll_training_at_the_benchmarked_size_lm_head_gradient_rows_and_properties():
+    """8B-shaped batch in bf16, 3 steps with unequal weights.  dW_lm sums the three steps' shares; a few of its rows
+    are recomputed in fp64 from what every step left in its workspace (final-norm output, log-sum-exp, shifted labels
+    of the rows it selected) and the initial W_lm.  Properties that hold at any size: finite gradients, zero column
+    sums of dW_lm (every logit-gradient row sums to zero), loss of step 1 equal to the single step's."""
+    import bench
+    cfg = W.get_config("8b")
+    dev = torch.device("cuda:0")
+    print("generating the 8b workload on the device", flush=True)
+    params, hidden, tokens, mask = bench.device_workload(cfg, dev, cfg["seed"])
+    w_lm0 = params["w_lm"].clone()
+    tr = bench.DeviceTrainer(cfg, params, hidden, tokens, mask)
+    n_steps, w = 3, [1.0, 0.7, 0.45]
+    l1, _ = tr.eval()
+    print("3-step training unroll at full size", flush=True)
+    loss = tr.train_step_unroll(cfg["lr"], n_steps, step_weights=w)
+    sync()
+    assert bool(torch.isfinite(loss).all())
+    assert abs(float(loss[0].item()) - float(l1.item())) <= 1e-5 * float(l1.item())
+    for k in O.PARAM_NAMES:
+        assert bool(torch.isfinite(tr.grads[k]).all()), k
+    d, V = cfg["hidden"], cfg["vocab"]
+    g = tr.grads["w_lm"]
+    assert float(g.sum(0).abs().max()) <= 2e-3 * float(g.abs().sum(0).max())
+
+    def view(step, name, nbytes, dt):
+        off = B.tide_draft_unroll_workspace_offset(tr.ccfg, n_steps, step, name)
+        assert off >= 0
+        return tr.unroll_ws[off:off + nbytes].view(dt)
+    picks = [0, V - 1, 12345 % V, int(torch.bincount(tr.tokens.reshape(-1)[tr.mask.reshape(-1) != 0].long(), minlength=V).argmax().item())]
+    ref = {v: torch.zeros(d, dtype=torch.float64, device=dev) for v in picks}
+    for s in range(n_steps):
+        cnt = int(view(s, "cnt", 4, torch.int32).item())
+        y = view(s, "yhat", cnt * d * 2, torch.bfloat16).view(cnt, d).double()
+        lse = view(s, "lse", cnt * 4, torch.float32).double()
+        idx = view(s, "kept_idx", cnt * 4, torch.int32).long()
+        labels = view(s, "tokens_s", cfg["batch"] * cfg["seq"] * 4, torch.int32).long()[idx]
+        keep = (view(s, "mask_s", cfg["batch"] * cfg["seq"], torch.uint8)[idx] != 0) & (labels >= 0) & (labels < V)
+        n = max(1, int(keep.sum().item()))
+        for v in picks:
+            z = y @ w_lm0[v].double()
+            p = (torch.exp(z - lse) - (labels == v).double()) * keep.double()
+            ref[v] += (w[s] / n) * (p[:, None] * y).sum(0)
+    for v in picks:
+        got = g[v].double()
+        cos = float((ref[v] * got).sum() / (ref[v].norm() * got.norm()))
+        err = float((ref[v] - got).abs().max() / ref[v].abs().max())
+        print(f"dW_lm[{v}]: cosine {cos:.6f}, max rel err {err:.2e}", flush=True)
+        assert cos >= 0.9999 and err <= 1e-2, (v, cos, err)
