@@ -25,7 +25,8 @@ Every step reports its mean cross-entropy and top-1 accuracy over its own loss-c
 unroll_backward differentiates L = sum_s w_s loss_s through the whole chain (the feature of step s is the output
 of step s-1; the keys/values of a step are read by every later step), with hand-derived gradients as in the
 single-step oracle; it is pinned by central finite differences on every tensor, for both input variants and
-unequal step weights, and by reducing to the single-step gradients for one step.
+unequal step weights, by reducing to the single-step gradients for one step, and by torch CPU fp64 autograd over
+a different formulation (all steps' keys concatenated under a block mask, F.scaled_dot_product_attention).
 
 Against the TIDE paper this is "parity unpinned" (it prints no equation or number for it).  It is pinned by
 mathematics in tests/test_oracle_unroll.py: one step equals the ordinary forward; and, for any start

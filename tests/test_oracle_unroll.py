@@ -184,3 +184,81 @@ def test_packed_unroll_of_equal_lengths_is_the_batched_unroll():
         assert abs(losses[s] - steps[s]["loss"]) <= 1e-12 * max(1.0, abs(losses[s]))
     for k in g_ref:
         np.testing.assert_allclose(g[k], g_ref[k], rtol=1e-10, atol=1e-13)
+
+
+def _torch_unroll(cfg, params, wl, tok, n_steps, w):
+    """The unroll composed from torch CPU fp64 library primitives + autograd.  Attention of step s: the keys and
+    values of ALL steps so far concatenated along the sequence ([s * S] of them) under a mask that is causal on the
+    step-1 block and the identity on every later block, through F.scaled_dot_product_attention."""
+    import torch
+    import torch.nn.functional as F
+    B, S = cfg["batch"], cfg["seq"]
+    nh, nkv, dh = cfg["n_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+    G = nh // nkv
+    P = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for k, v in params.items()}
+    feat = F.linear(torch.tensor(wl["hidden"], dtype=torch.float64).reshape(B * S, -1), P["w_fc"])
+    tokens = torch.tensor(wl["tokens"].astype(np.int64))
+    mask = torch.tensor(wl["mask"].astype(np.float64))
+    ids = torch.tensor(np.asarray(tok["input_ids"]).astype(np.int64)) if tok else None
+    E = torch.tensor(np.asarray(tok["embed"], np.float64)) if tok else None
+    half = dh // 2
+    inv = torch.tensor(cfg["rope_theta"], dtype=torch.float64) ** (-torch.arange(0, dh, 2, dtype=torch.float64) / dh)
+
+    def rms(x, g):
+        return g * x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + cfg["rms_eps"])
+
+    def rope(x, shift):
+        ang = (torch.arange(S, dtype=torch.float64) + shift)[:, None] * inv[None]
+        cos = torch.cat([ang.cos(), ang.cos()], -1)[None, :, None, :]
+        sin = torch.cat([ang.sin(), ang.sin()], -1)[None, :, None, :]
+        return x * cos + torch.cat([-x[..., half:], x[..., :half]], -1) * sin
+
+    keys, vals, losses = [], [], []
+    total = 0.0
+    for s in range(n_steps):
+        valid = torch.zeros(B, S, dtype=torch.float64)
+        valid[:, :S - s] = 1.0 if S - s > 0 else 0.0
+        lab = torch.roll(tokens, -s, dims=1)
+        m = torch.roll(mask, -s, dims=1) * valid
+        if tok:
+            e = F.embedding(torch.roll(ids, -s, dims=1).reshape(-1), E) * valid.reshape(-1, 1)
+            x0 = F.linear(torch.cat([feat, e], dim=1), P["w_in"])
+        else:
+            x0 = feat
+        qkv = F.linear(rms(x0, P["g1"]), P["w_qkv"])
+        q = rope(qkv[:, :nh * dh].reshape(B, S, nh, dh), s)
+        k = rope(qkv[:, nh * dh:(nh + nkv) * dh].reshape(B, S, nkv, dh), s)
+        v = qkv[:, (nh + nkv) * dh:].reshape(B, S, nkv, dh)
+        keys.append(k.repeat_interleave(G, dim=2).transpose(1, 2))
+        vals.append(v.repeat_interleave(G, dim=2).transpose(1, 2))
+        allow = torch.cat([torch.tril(torch.ones(S, S, dtype=torch.bool))] + [torch.eye(S, dtype=torch.bool)] * s, dim=1)
+        A = F.scaled_dot_product_attention(q.transpose(1, 2), torch.cat(keys, dim=2), torch.cat(vals, dim=2), attn_mask=allow)
+        x1 = x0 + F.linear(A.transpose(1, 2).reshape(B * S, nh * dh), P["w_o"])
+        b = rms(x1, P["g2"])
+        x2 = x1 + F.linear(F.silu(F.linear(b, P["w_gate"])) * F.linear(b, P["w_up"]), P["w_down"])
+        z = F.linear(rms(x2, P["g3"]), P["w_lm"])
+        per = F.cross_entropy(z, lab.reshape(-1), reduction="none")
+        loss = (per * m.reshape(-1)).sum() / max(1.0, float(m.sum()))
+        losses.append(float(loss.detach()))
+        total = total + w[s] * loss
+        feat = x2
+    total.backward()
+    return losses, {k: t.grad.numpy() for k, t in P.items()}
+
+
+@pytest.mark.parametrize("token_input", [False, True])
+def test_unroll_against_torch_autograd(token_input):
+    cfg = micro_cfg(batch=2, seq=7, n_heads=4, n_kv_heads=2, hidden=16, head_dim=4, ffn=12, vocab=37, mask="bernoulli", mask_p=0.3)
+    wl = micro_workload(cfg)
+    tok = _token_input(cfg) if token_input else None
+    params = {k: np.asarray(v, np.float64) for k, v in wl["params"].items()}
+    if tok:
+        params[O.TOKEN_PARAM] = tok["w_in"]
+    w = [1.0, 0.7, 0.45]
+    steps = U.unroll_forward(cfg, params, wl["hidden"], wl["tokens"], wl["mask"], 3, tok=tok, keep_cache=True)
+    grads = U.unroll_backward(cfg, params, steps, step_weights=w)
+    t_losses, t_grads = _torch_unroll(cfg, params, wl, tok, 3, w)
+    for s in range(3):
+        assert abs(steps[s]["loss"] - t_losses[s]) <= 1e-12 * max(1.0, abs(t_losses[s])), s
+    for k in grads:
+        np.testing.assert_allclose(grads[k], t_grads[k], rtol=1e-9, atol=1e-13, err_msg=k)
