@@ -140,6 +140,9 @@ def main():
                     help="time the training step over the multi-step unroll (the draft fed its own output from the "
                          "second step on) with this many steps instead of the benchmarked single-step path; "
                          "combines with --token-input")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket the library's launches with HIP events in the timed region (no per-kernel "
+                         "figures and no roofline entry; shows what the events themselves cost)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -202,7 +205,8 @@ def main():
             assert B.tide_ingest_submit(ring, slot, bufs[1], nbytes) == 0
         torch.cuda.synchronize()
 
-    B.tide_profile_start()
+    if not args.no_kernel_events:
+        B.tide_profile_start()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -221,7 +225,10 @@ def main():
             tr.hidden = bufs[cur]
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    prof = B.tide_profile_stop()
+    prof = B.tide_profile_stop() if not args.no_kernel_events else []
+    if args.no_kernel_events:
+        print(json.dumps({"ms_per_step": wall * 1e3 / args.steps, "steps": args.steps, "kernel_events": False}))
+        return
     if ring is not None:
         B.tide_ingest_destroy(ring)
     if args.copy_calibration:
