@@ -145,6 +145,61 @@ __global__ __launch_bounds__(256) void own_kv_merge_fwd_kernel(const T* __restri
   if (lane == 0) lse[li] = L;
 }
 
+// Same merge with 8 consecutive elements per lane (16-byte accesses in bf16): LPH = head_dim / 8 lanes serve one
+// (row, query head), 64 / LPH heads share a wavefront; reductions run inside the LPH-lane group.
+template <typename T, int LPH>
+__global__ __launch_bounds__(256) void own_kv_merge_fwd_vec_kernel(const T* __restrict__ qkv, T* __restrict__ out,
+                                                                   float* __restrict__ lse, OwnKV own, int n_own,
+                                                                   int64_t n_pairs, int nh, int nkv, int S, float scale,
+                                                                   int64_t packed_T) {
+  constexpr int HPW = 64 / LPH, dh = LPH * 8;
+  const int lane = threadIdx.x & 63, sub = lane % LPH;
+  const int64_t pair = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * HPW + lane / LPH;
+  const bool live = pair < n_pairs;
+  const int64_t t = live ? pair / nh : 0;
+  const int h = live ? (int)(pair % nh) : 0, kh = h / (nh / nkv);
+  const int nq = nh * dh, nk = nkv * dh;
+  const size_t qo = (size_t)t * (nq + 2 * nk) + (size_t)h * dh + sub * 8;
+  const size_t ko = (size_t)t * (2 * nk) + (size_t)kh * dh + sub * 8;
+  float qv[8];
+  ld8(qkv, qo, qv);
+  float sc[kMaxUnroll];
+  for (int j = 0; j < n_own; ++j) {
+    float kv[8];
+    ld8((const T*)own.kv[j], ko, kv);
+    float part = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part += qv[e] * kv[e];
+#pragma unroll
+    for (int o = LPH / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+    sc[j] = scale * part;
+  }
+  const size_t li = packed_T ? (size_t)h * (size_t)packed_T + (size_t)t : ((size_t)(t / S) * nh + h) * (size_t)S + (size_t)(t % S);
+  const float l0 = lse[li];
+  float m = l0;
+  for (int j = 0; j < n_own; ++j) m = fmaxf(m, sc[j]);
+  float sum = expf(l0 - m);
+  for (int j = 0; j < n_own; ++j) sum += expf(sc[j] - m);
+  const float L = m + logf(sum);
+  const float w0 = expf(l0 - L);
+  const size_t oo = (size_t)t * nq + (size_t)h * dh + sub * 8;
+  float acc[8];
+  ld8(out, oo, acc);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] *= w0;
+  for (int j = 0; j < n_own; ++j) {
+    float vv[8];
+    ld8((const T*)own.kv[j], ko + nk, vv);
+    const float wj = expf(sc[j] - L);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += wj * vv[e];
+  }
+  if (live) {
+    st8(out, oo, acc);
+    if (sub == 0) lse[li] = L;
+  }
+}
+
 hipError_t launch_own_kv_merge_fwd(int64_t T, int S, int nh, int nkv, int dh, const void* qkv, void* out, float* lse,
                                    const OwnKV& own, int n_own, int packed, int dtype, hipStream_t s) {
   const int64_t n_pairs = T * nh;
@@ -153,6 +208,18 @@ hipError_t launch_own_kv_merge_fwd(int64_t T, int S, int nh, int nkv, int dh, co
   if (n_own > kMaxUnroll || dh > 64 * kMaxDhPerLane || nh % nkv) return hipErrorInvalidValue;
   ProfScope ps("own_kv_merge_fwd", 0, (double)n_pairs * dh * (3.0 + 2.0 * n_own) * dtype_size(dtype), s);
   const float scale = 1.0f / sqrtf((float)dh);
+  const bool aligned = (((uintptr_t)qkv | (uintptr_t)out) & 15) == 0;
+  bool own_aligned = true;
+  for (int j = 0; j < n_own; ++j) own_aligned = own_aligned && (((uintptr_t)own.kv[j]) & 15) == 0;
+  if ((dh == 128 || dh == 64) && aligned && own_aligned) {
+    const int hpw = dh == 128 ? 4 : 8;   // (row, head) pairs per wavefront
+    dim3 gridv((unsigned)((n_pairs + 4 * hpw - 1) / (4 * hpw))), blkv(256);
+#define TIDE_MERGE_FWD(T, LPH) hipLaunchKernelGGL((own_kv_merge_fwd_vec_kernel<T, LPH>), gridv, blkv, 0, s, (const T*)qkv, (T*)out, lse, own, n_own, n_pairs, nh, nkv, S, scale, packed_T)
+    if (dtype == kBF16) { if (dh == 128) TIDE_MERGE_FWD(bf16_t, 16); else TIDE_MERGE_FWD(bf16_t, 8); }
+    else { if (dh == 128) TIDE_MERGE_FWD(float, 16); else TIDE_MERGE_FWD(float, 8); }
+#undef TIDE_MERGE_FWD
+    return hipGetLastError();
+  }
   dim3 grid((unsigned)((n_pairs + 3) / 4)), blk(256);
   if (dtype == kBF16) hipLaunchKernelGGL(own_kv_merge_fwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)qkv, (bf16_t*)out, lse, own, n_own, n_pairs, nh, nkv, dh, S, scale, packed_T);
   else hipLaunchKernelGGL(own_kv_merge_fwd_kernel<float>, grid, blk, 0, s, (const float*)qkv, (float*)out, lse, own, n_own, n_pairs, nh, nkv, dh, S, scale, packed_T);
@@ -233,6 +300,68 @@ __global__ __launch_bounds__(256) void own_kv_merge_bwd_kernel(const T* __restri
   }
 }
 
+// The same backward with 8 consecutive elements per lane: LPH = head_dim / 8 lanes serve one (row, key/value head).
+template <typename T, int LPH>
+__global__ __launch_bounds__(256) void own_kv_merge_bwd_vec_kernel(const T* __restrict__ qkv, const T* __restrict__ dout,
+                                                                   const float* __restrict__ lse,
+                                                                   const float* __restrict__ delta, OwnKV own,
+                                                                   OwnKVGrad grad, int n_own, int first,
+                                                                   T* __restrict__ dqkv, int64_t n_pairs, int nh, int nkv,
+                                                                   int S, float scale, int64_t packed_T) {
+  constexpr int PPW = 64 / LPH, dh = LPH * 8;
+  const int lane = threadIdx.x & 63, sub = lane % LPH;
+  const int64_t pair = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * PPW + lane / LPH;
+  const bool live = pair < n_pairs;
+  const int64_t t = live ? pair / nkv : 0;
+  const int kh = live ? (int)(pair % nkv) : 0, G = nh / nkv;
+  const int nq = nh * dh, nk = nkv * dh, ld = nq + 2 * nk;
+  const size_t stat0 = packed_T ? (size_t)t : ((size_t)(t / S) * nh) * (size_t)S + (size_t)(t % S);
+  const size_t stat_h = packed_T ? (size_t)packed_T : (size_t)S;
+  const size_t ko = (size_t)t * (2 * nk) + (size_t)kh * dh + sub * 8;
+  for (int j = 0; j < n_own; ++j) {
+    float kv[8], vv[8], dk[8], dv[8];
+    ld8((const T*)own.kv[j], ko, kv);
+    ld8((const T*)own.kv[j], ko + nk, vv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dk[e] = dv[e] = 0.f;
+    for (int g = 0; g < G; ++g) {
+      const int h = kh * G + g;
+      const size_t qo = (size_t)t * ld + (size_t)h * dh + sub * 8;
+      float qv[8], dov[8], dq[8];
+      ld8(qkv, qo, qv);
+      ld8(dout, (size_t)t * nq + (size_t)h * dh + sub * 8, dov);
+      float sp = 0.f, dp = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { sp += qv[e] * kv[e]; dp += dov[e] * vv[e]; }
+#pragma unroll
+      for (int o = LPH / 2; o > 0; o >>= 1) { sp += __shfl_xor(sp, o, 64); dp += __shfl_xor(dp, o, 64); }
+      const size_t li = stat0 + (size_t)h * stat_h;
+      const float p = expf(scale * sp - lse[li]);
+      const float ds = p * (dp - delta[li]);
+      ld8(dqkv, qo, dq);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        dq[e] += scale * ds * kv[e];
+        dk[e] += scale * ds * qv[e];
+        dv[e] += p * dov[e];
+      }
+      if (live) st8(dqkv, qo, dq);
+    }
+    T* gbuf = (T*)grad.kv[j];
+    if (!first) {
+      float ok[8], ov[8];
+      ld8(gbuf, ko, ok);
+      ld8(gbuf, ko + nk, ov);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { dk[e] += ok[e]; dv[e] += ov[e]; }
+    }
+    if (live) {
+      st8(gbuf, ko, dk);
+      st8(gbuf, ko + nk, dv);
+    }
+  }
+}
+
 hipError_t launch_own_kv_merge_bwd(int64_t T, int S, int nh, int nkv, int dh, const void* qkv, const void* dout,
                                    const float* lse, const float* delta, const OwnKV& own, const OwnKVGrad& grad,
                                    int n_own, int first, void* dqkv, int packed, int dtype, hipStream_t s) {
@@ -242,6 +371,17 @@ hipError_t launch_own_kv_merge_bwd(int64_t T, int S, int nh, int nkv, int dh, co
   if (n_own > kMaxUnroll || dh > 64 * kMaxDhPerLane || nh % nkv) return hipErrorInvalidValue;
   ProfScope ps("own_kv_merge_bwd", 0, (double)T * nh * dh * (4.0 * n_own) * dtype_size(dtype), s);
   const float scale = 1.0f / sqrtf((float)dh);
+  bool aligned = (((uintptr_t)qkv | (uintptr_t)dout | (uintptr_t)dqkv) & 15) == 0;
+  for (int j = 0; j < n_own; ++j) aligned = aligned && ((((uintptr_t)own.kv[j]) | ((uintptr_t)grad.kv[j])) & 15) == 0;
+  if ((dh == 128 || dh == 64) && aligned) {
+    const int ppw = dh == 128 ? 4 : 8;   // (row, key/value head) pairs per wavefront
+    dim3 gridv((unsigned)((n_pairs + 4 * ppw - 1) / (4 * ppw))), blkv(256);
+#define TIDE_MERGE_BWD(T, LPH) hipLaunchKernelGGL((own_kv_merge_bwd_vec_kernel<T, LPH>), gridv, blkv, 0, s, (const T*)qkv, (const T*)dout, lse, delta, own, grad, n_own, first, (T*)dqkv, n_pairs, nh, nkv, S, scale, packed_T)
+    if (dtype == kBF16) { if (dh == 128) TIDE_MERGE_BWD(bf16_t, 16); else TIDE_MERGE_BWD(bf16_t, 8); }
+    else { if (dh == 128) TIDE_MERGE_BWD(float, 16); else TIDE_MERGE_BWD(float, 8); }
+#undef TIDE_MERGE_BWD
+    return hipGetLastError();
+  }
   dim3 grid((unsigned)((n_pairs + 3) / 4)), blk(256);
   if (dtype == kBF16) hipLaunchKernelGGL(own_kv_merge_bwd_kernel<bf16_t>, grid, blk, 0, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, delta, own, grad, n_own, first, (bf16_t*)dqkv, n_pairs, nh, nkv, dh, S, scale, packed_T);
   else hipLaunchKernelGGL(own_kv_merge_bwd_kernel<float>, grid, blk, 0, s, (const float*)qkv, (const float*)dout, lse, delta, own, grad, n_own, first, (float*)dqkv, n_pairs, nh, nkv, dh, S, scale, packed_T);
