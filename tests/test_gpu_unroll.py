@@ -376,3 +376,29 @@ def test_unroll_training_at_the_benchmarked_size_lm_head_gradient_rows_and_prope
         err = float((ref[v] - got).abs().max() / ref[v].abs().max())
         print(f"dW_lm[{v}]: cosine {cos:.6f}, max rel err {err:.2e}", flush=True)
         assert cos >= 0.9999 and err <= 1e-2, (v, cos, err)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_unroll_random_shapes_fp32(seed):
+    """Seeded random small shapes (odd widths, every GQA ratio, every head_dim path of the merge kernels, all mask
+    kinds, 2-4 steps, with and without token input): losses and all gradients against the oracle."""
+    from tests.test_gpu_step import _random_cfg
+    rng = np.random.default_rng(3000 + seed)
+    kw = _random_cfg(rng, "fp32")
+    kw["seq"] = min(kw["seq"], 48)                      # the oracle keeps every step's [S, S] weights
+    n_steps = int(rng.integers(2, 5))
+    token_input = bool(rng.integers(0, 2))
+    print(kw, n_steps, token_input, flush=True)
+    cfg = W.get_config("tiny", **kw)
+    wl, tr, params, tok = _setup(cfg, token_input)
+    w = [float(x) for x in rng.uniform(0.2, 1.0, n_steps)]
+    loss_ref, g_ref, _ = _train_reference(cfg, wl, params, tok, n_steps, w, cfg["lr"])
+    loss = tr.train_step_unroll(cfg["lr"], n_steps, step_weights=w, token_input=token_input)
+    sync()
+    for s in range(n_steps):
+        assert abs(float(loss[s].item()) - loss_ref[s]) <= 1e-4 * abs(loss_ref[s]) + 1e-7, (s, float(loss[s].item()), loss_ref[s])
+    g = _device_grads(tr, token_input)
+    for k in g_ref:
+        assert np.all(np.isfinite(g[k])), k
+        den = float(np.max(np.abs(g_ref[k])))
+        assert float(np.max(np.abs(g[k] - g_ref[k]))) <= 1e-4 * den + 1e-9, (k, rel_max(g[k], g_ref[k]))
