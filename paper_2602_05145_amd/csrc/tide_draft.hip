@@ -338,9 +338,12 @@ int enqueue_trunk(const tide_draft_config* c, const tide_draft_tensors* P, const
 }
 
 // LM head by row blocks over the selected rows (those that carry loss; every row when arg-max ids are wanted):
-// logits of one block, row statistics, and (training) the logit gradient and the two products that
-// consume it.  The full [T,V] logits never exist.  The number of compacted rows lives on the device, so
-// every launch is sized for the worst case and trims itself.
+// logits of one block (bf16), row statistics, and (training) the logit gradient written over them and the
+// product dyhat that consumes it.  Logits exist for one block at a time: a forward-only call reuses one block
+// region; a training call turns each block into its gradient before the next block's logits are computed, and
+// keeps those bf16 gradients of all blocks (when the buffer may hold them) so that dW_lm is ONE product over
+// all rows afterwards.  fp32 logits or probabilities of [rows, V] never exist.  The number of compacted rows
+// lives on the device, so every launch is sized for the worst case and trims itself.
 int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tide_draft_tensors* G,
                     const int32_t* tokens, const uint8_t* mask, int32_t* top1, float* loss_out, float* acc_out,
                     char* ws, const Plan& p, bool train, hipStream_t s, float grad_weight = 1.f, bool add_to_dw = false) {
@@ -360,7 +363,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
   for (int64_t r0 = 0; r0 < p.T; r0 += p.lm_rows, ++blk) {
     const int64_t rows = (p.T - r0 < p.lm_rows) ? (p.T - r0) : p.lm_rows;
     const char* yb = yhat_c + (size_t)r0 * p.d * p.es;
-    char* z = ws + p.z + (all_rows ? (size_t)r0 * p.ldz * p.es : 0);
+    char* z = ws + p.z + ((all_rows && train) ? (size_t)r0 * p.ldz * p.es : 0);
     {
       GemmArgs g = gemm_args(kNT, rows, p.V, p.d, yb, p.d, P->w_lm, p.d, z, p.ldz, dt, dt);
       g.m_dev = cnt; g.m_off = r0;
