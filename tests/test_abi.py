@@ -67,5 +67,29 @@ def test_calls_reject_bad_arguments_before_touching_the_device(B):
         B.tide_draft_train_step(c, t, t, B.TideAdamState(), 256, 256, 256, 1e-4, 256, 256, 1 << 40, None)
 
 
+def test_unroll_calls_validate_before_touching_the_device(B):
+    c = B.make_config(W.get_config("8b"))
+    one = B.tide_draft_workspace_bytes(c)
+    for n in (1, 3, 8):
+        need = B.tide_draft_unroll_workspace_bytes(c, n)
+        assert need >= n * one
+        assert B.tide_draft_unroll_workspace_offset(c, n, n - 1, "x2") >= (n - 1) * one
+        assert B.tide_draft_unroll_workspace_offset(c, n, n - 1, "own_kv") >= n * one
+        assert B.tide_draft_unroll_workspace_offset(c, n, n, "x2") == -1
+    assert B.tide_draft_unroll_workspace_bytes(c, 0) == 0 and B.tide_draft_unroll_workspace_bytes(c, 9) == 0
+    assert B.tide_draft_unroll_workspace_offset(c, 3, 0, "nonsense") == -1
+    t = B.make_tensors(None)
+    assert B.tide_draft_eval_unroll(c, t, None, 256, 256, 256, 3, 256, 256, 256, 1 << 40, None, check=False) == B.TIDE_ERR_NULL
+    assert B.tide_draft_eval_unroll(c, t, None, 256, 256, 256, 0, 256, 256, 256, 1 << 40, None, check=False) == B.TIDE_ERR_CONFIG
+    assert B.tide_draft_train_step_unroll(c, t, t, B.TideAdamState(), None, 256, 256, 256, 9, None, 1e-4, 256, 256, 1 << 40,
+                                          None, check=False) == B.TIDE_ERR_CONFIG
+    assert B.tide_draft_train_step_unroll(c, t, t, B.TideAdamState(), None, 256, 256, 256, 2, [1.0, -1.0], 1e-4, 256, 256,
+                                          1 << 40, None, check=False) == B.TIDE_ERR_CONFIG
+    assert B.tide_draft_eval_unroll_packed(c, t, None, 256, 256, 256, None, 2, 100, 3, 256, 256, 256, 1 << 40, None,
+                                           check=False) == B.TIDE_ERR_NULL
+    assert B.tide_draft_train_step_unroll_packed(c, t, t, B.TideAdamState(), None, 256, 256, 256, 256, 0, 100, 3, None, 1e-4,
+                                                 256, 256, 1 << 40, None, check=False) == B.TIDE_ERR_CONFIG
+
+
 def test_every_header_in_include_is_covered():
     assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["tide_control.h", "tide_draft.h", "tide_ingest.h"]
