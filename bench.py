@@ -243,11 +243,12 @@ def main():
 
     # what the matrix pipes sustain on this machine with nothing else going on (registers only): the practical ceiling
     sink = torch.empty(2048 * 512, dtype=torch.float32, device=dev)
-    B.tide_mfma_probe(2048, 200, sink, tr._stream())
+    for _ in range(60):                                   # ~0.3 s: let the power limit settle before timing
+        B.tide_mfma_probe(2048, 4000, sink, tr._stream())
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    probe_flops = B.tide_mfma_probe(2048, 4000, sink, tr._stream())
+    probe_flops = sum(B.tide_mfma_probe(2048, 4000, sink, tr._stream()) for _ in range(20))
     e1.record()
     torch.cuda.synchronize()
     mfma_probe_tflops = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12

@@ -368,9 +368,9 @@ int tide_profile_start(void);
 int tide_profile_stop(char *report, size_t report_bytes);
 
 /* Measurement aid: enqueues a kernel that does nothing but bf16 MFMAs from registers (`blocks` work-groups of
- * 8 wavefronts, each issuing iters x 8 independent v_mfma_f32_32x32x16_bf16), so that the caller can time
- * the rate the matrix pipes sustain on this chip at the clock it holds under such load: the practical
- * ceiling next to the nominal 2516.6 TFLOP/s.  sink: DEVICE buffer of blocks*512 floats (written, so that the
+ * 8 wavefronts, each issuing iters x 8 independent v_mfma_f32_32x32x16_bf16 on random operands, a different pair
+ * per instruction), so that the caller can time the rate the matrix pipes sustain on this chip under its power
+ * limit (time a few hundred milliseconds of launches): the practical ceiling next to the nominal 2516.6 TFLOP/s.  sink: DEVICE buffer of blocks*512 floats (written, so that the
  * work is not optimised away); *flops_out (HOST, optional) receives the flop count of the launch. */
 int tide_mfma_probe(int32_t blocks, int32_t iters, float *sink, double *flops_out, void *stream);
 

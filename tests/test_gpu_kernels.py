@@ -203,15 +203,16 @@ def test_attention_fwd_bwd(B, dtype, shape):
 
 
 def test_mfma_probe_runs_and_counts(B):
-    """The pure-MFMA probe: flop count, finite output of the known value, argument checks."""
+    """The pure-MFMA probe: flop count, finite output within the bound its operands allow, argument checks."""
     sink = torch.zeros(4 * 512, dtype=torch.float32, device="cuda:0")
     s = torch.cuda.current_stream().cuda_stream
     fl = B.tide_mfma_probe(4, 10, sink, s)
     sync()
     assert fl == 4 * 8 * 10 * 8 * 2 * 32 * 32 * 16
     assert bool(torch.isfinite(sink).all())
-    # every accumulator element is a sum of 16 products of +-2^-8 per MFMA: |value| <= 8 acc x 16 elem x 10 it x 16 / 256
-    assert float(sink.abs().max()) <= 8 * 16 * 10 * 16 / 256 + 1e-6
+    # operands have magnitude below 2: every accumulator element gains at most 16 products of 4 per MFMA, so
+    # |value| <= 8 acc x 16 elem x 10 it x 64; random signs keep the sums far from zero as well as from the bound
+    assert 0.0 < float(sink.abs().max()) <= 8 * 16 * 10 * 64
     import ctypes
     assert B.lib().tide_mfma_probe(0, 10, ctypes.c_void_p(sink.data_ptr()), None, s) == B.TIDE_ERR_CONFIG
     assert B.lib().tide_mfma_probe(4, 10, None, None, s) == B.TIDE_ERR_NULL
