@@ -93,3 +93,14 @@ def test_unroll_calls_validate_before_touching_the_device(B):
 
 def test_every_header_in_include_is_covered():
     assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["tide_control.h", "tide_draft.h", "tide_ingest.h"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
+    env = dict(os.environ, WORLD_SIZE="4")
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
