@@ -22,8 +22,8 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 fl
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the GEMM instantiations at the 8B shape, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0 after calibration against a plain copy): profiles/gemm_8b_hbm_traffic.txt
-MEASURED_TRAFFIC_8B = {"gemm_mfma_tn_256_f32out": 11.31e9, "gemm_mfma_nt_256_bf16out": 10.78e9,
-                       "gemm_mfma_nn_256_bf16out": 11.86e9}
+MEASURED_TRAFFIC_8B = {"gemm_mfma_tn_256_f32out": 11.29e9, "gemm_mfma_nt_256_bf16out": 10.46e9,
+                       "gemm_mfma_nn_256_bf16out": 11.93e9}
 
 
 def device_workload(cfg, device, seed):
@@ -243,12 +243,12 @@ def main():
 
     # what the matrix pipes sustain on this machine with nothing else going on (registers only): the practical ceiling
     sink = torch.empty(2048 * 512, dtype=torch.float32, device=dev)
-    for _ in range(60):                                   # ~0.3 s: let the power limit settle before timing
+    for _ in range(30):                                   # a quarter of a second of it first: the power limit takes that long to settle
         B.tide_mfma_probe(2048, 4000, sink, tr._stream())
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    probe_flops = sum(B.tide_mfma_probe(2048, 4000, sink, tr._stream()) for _ in range(20))
+    probe_flops = sum(B.tide_mfma_probe(2048, 4000, sink, tr._stream()) for _ in range(10))
     e1.record()
     torch.cuda.synchronize()
     mfma_probe_tflops = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
