@@ -82,10 +82,7 @@ def _check_bf16(cfg, wl):
 def test_tiny_fp32_full_config():
     cfg = W.get_config("tiny")
     wl = W.make_workload(cfg)
-    tr = _check_fp32(cfg, wl)
-    # top-1 ids of the forward entry point against the oracle's arg-max
-    _, cache = O.forward(cfg, {k: np.asarray(v, np.float64) for k, v in wl["params"].items()},
-                         wl["hidden"].astype(np.float64), wl["tokens"], wl["mask"], want_top1=True)
+    _check_fp32(cfg, wl)
 
 
 @pytest.mark.parametrize("kw", [
