@@ -339,6 +339,18 @@ size_t tide_rmsnorm_bwd_scratch_bytes(int64_t rows, int64_t d);
 int tide_rmsnorm_bwd(int64_t rows, int64_t d, const void *dy, const void *x, const void *g,
                      const float *rstd, const void *residual_grad, void *dx, float *dg,
                      void *dg_partial, int dtype, void *stream);
+/* tide_rmsnorm_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same kernels and the same results, but the per-block
+ * partial sums of dg live in a fixed array inside the library (TIDE_RMSNORM_STATIC_SCRATCH_BYTES of device
+ * memory per GPU, held until the process ends) instead of a caller buffer.  The call allocates and frees
+ * nothing.  It fails with TIDE_ERR_WORKSPACE when tide_rmsnorm_bwd_scratch_bytes(rows, d) exceeds that size
+ * (it does not for any shape tide_rmsnorm_bwd accepts: at most 512 blocks x 8192 columns).  Every call on a
+ * GPU shares that GPU's array and every element a call reads it has written itself first, so nothing needs
+ * clearing; two calls that overlap on one GPU (different streams, or different host threads) race. */
+#define TIDE_RMSNORM_STATIC_SCRATCH_BYTES (16u << 20)
+int tide_rmsnorm_bwd_static(int64_t rows, int64_t d, const void *dy, const void *x, const void *g,
+                            const float *rstd, const void *residual_grad, void *dx, float *dg,
+                            int dtype, void *stream);
 
 /* Causal grouped-query attention on a packed activation qkv [B*S, (n_heads+2*n_kv_heads)*head_dim]
  * (q heads, then k heads, then v heads; RoPE already applied).  out [B*S, n_heads*head_dim];

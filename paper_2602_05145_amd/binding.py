@@ -108,6 +108,8 @@ _lib.tide_rmsnorm_bwd_scratch_bytes.restype = _sz
 _lib.tide_rmsnorm_bwd_scratch_bytes.argtypes = [_i64, _i64]
 _lib.tide_rmsnorm_bwd.restype = _i32
 _lib.tide_rmsnorm_bwd.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]
+_lib.tide_rmsnorm_bwd_static.restype = _i32
+_lib.tide_rmsnorm_bwd_static.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.tide_attention_fwd.restype = _i32
 _lib.tide_attention_fwd.argtypes = [_i32] * 5 + [_vp, _vp, _vp, _i32, _vp]
 _lib.tide_attention_bwd.restype = _i32
@@ -128,7 +130,7 @@ EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspa
     "tide_mfma_probe",
     "tide_ingest_create", "tide_ingest_destroy", "tide_ingest_acquire", "tide_ingest_submit", "tide_ingest_wait",
     "tide_ingest_done", "tide_ingest_last_error", "tide_gemm_workspace_bytes", "tide_gemm",
-            "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd",
+            "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd", "tide_rmsnorm_bwd_static",
             "tide_attention_fwd", "tide_attention_bwd", "tide_rope", "tide_profile_start",
             "tide_profile_stop")
 
@@ -343,6 +345,12 @@ def tide_rmsnorm_bwd_scratch_bytes(rows, d):
 def tide_rmsnorm_bwd(rows, d, dy, x, g, rstd, residual_grad, dx, dg, dg_partial, dtype, stream):
     return _check(_lib.tide_rmsnorm_bwd(rows, d, _ptr(dy), _ptr(x), _ptr(g), _ptr(rstd), _ptr(residual_grad),
                                         _ptr(dx), _ptr(dg), _ptr(dg_partial), dtype, stream))
+
+
+def tide_rmsnorm_bwd_static(rows, d, dy, x, g, rstd, residual_grad, dx, dg, dtype, stream, check=True):
+    rc = _lib.tide_rmsnorm_bwd_static(rows, d, _ptr(dy), _ptr(x), _ptr(g), _ptr(rstd), _ptr(residual_grad),
+                                      _ptr(dx), _ptr(dg), dtype, stream)
+    return _check(rc) if check else rc
 
 
 def tide_attention_fwd(B, S, nh, nkv, dh, qkv, out, lse, dtype, stream):

@@ -915,6 +915,52 @@ int tide_rmsnorm_bwd(int64_t rows, int64_t d, const void* dy, const void* x, con
   return TIDE_OK;
 }
 
+}  // extern "C"
+
+// Scratch of tide_rmsnorm_bwd_static: a fixed device array, one copy per GPU.  In host code the array's name is
+// only a handle; its device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char g_rmsnorm_static_scratch[TIDE_RMSNORM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[kMaxDevices] = {};
+
+// device address of the scratch array on the current device (nullptr + error message on failure)
+void* static_scratch_ptr() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { hip_fail(e, "hipGetDevice"); return nullptr; }
+  if (dev < 0 || dev >= kMaxDevices) { fail(TIDE_ERR_HIP, "device index %d outside [0, %d)", dev, kMaxDevices); return nullptr; }
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_rmsnorm_static_scratch));
+    if (e != hipSuccess || !ptr) { hip_fail(e, "hipGetSymbolAddress(static scratch)"); return nullptr; }
+    g_static_ptr[dev] = ptr;
+  }
+  return g_static_ptr[dev];
+}
+}  // namespace
+
+extern "C" {
+
+int tide_rmsnorm_bwd_static(int64_t rows, int64_t d, const void* dy, const void* x, const void* g, const float* rstd,
+                            const void* residual_grad, void* dx, float* dg, int dtype, void* stream) {
+  if (!dy || !x || !g || !rstd || !dx || !dg) return fail(TIDE_ERR_NULL, "NULL argument");
+  const bool ok = (d % 8 == 0 && d <= 8192) || d <= 1024;
+  if (rows <= 0 || d <= 0 || !ok) return fail(TIDE_ERR_CONFIG, "bad sizes");
+  if (dtype != TIDE_DTYPE_FP32 && dtype != TIDE_DTYPE_BF16) return fail(TIDE_ERR_CONFIG, "bad dtype");
+  const size_t need = rmsnorm_bwd_scratch_bytes(rows, (int)d);
+  if (need > (size_t)TIDE_RMSNORM_STATIC_SCRATCH_BYTES)
+    return fail(TIDE_ERR_WORKSPACE, "rows=%lld d=%lld need %zu bytes of scratch, the fixed array holds %u",
+                (long long)rows, (long long)d, need, (unsigned)TIDE_RMSNORM_STATIC_SCRATCH_BYTES);
+  void* scratch = static_scratch_ptr();
+  if (!scratch) return TIDE_ERR_HIP;
+  TIDE_HIP(launch_rmsnorm_bwd(rows, (int)d, dy, x, g, rstd, residual_grad, dx, dg, (float*)scratch, dtype, nullptr, (hipStream_t)stream), "rmsnorm bwd");
+  return TIDE_OK;
+}
+
 static int attn_check(int B, int S, int nh, int nkv, int dh) {
   if (B <= 0 || S <= 0 || nh <= 0 || nkv <= 0 || dh <= 0 || nh % nkv || dh > 256 || B > 65535) return fail(TIDE_ERR_CONFIG, "bad attention shape");
   return 0;
