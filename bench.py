@@ -143,6 +143,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket the library's launches with HIP events in the timed region (no per-kernel "
                          "figures and no roofline entry; shows what the events themselves cost)")
+    ap.add_argument("--set", action="append", default=[], metavar="KEY=INT",
+                    help="override an integer field of the configuration (e.g. lm_keep_all_rows=1, lm_block_rows=8192)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -157,7 +159,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    cfg = W.get_config(args.workload)
+    cfg = W.get_config(args.workload, **{k: int(v) for k, v in (kv.split("=", 1) for kv in args.set)})
     params, hidden, tokens, mask = device_workload(cfg, dev, cfg["seed"])
     tr = DeviceTrainer(cfg, params, hidden, tokens, mask)
     lr = cfg["lr"]
@@ -216,7 +218,9 @@ def main():
             rc, slot, addr = B.tide_ingest_acquire(ring)
             assert rc == 0, B.tide_ingest_last_error()
             ctypes.memmove(addr, src_addr, nbytes)
-            assert B.tide_ingest_submit(ring, slot, bufs[cur ^ 1], nbytes) == 0
+            # (the idle buffer was read by the step before this one, which may still be running: the copy is
+            # ordered after everything enqueued on the compute stream so far)
+            assert B.tide_ingest_submit(ring, slot, bufs[cur ^ 1], nbytes, tr._stream(), True) == 0
         step(lr)
         if ring is not None:
             # the next step reads the freshly copied buffer: order it after the copy on the compute stream

@@ -85,6 +85,18 @@ typedef struct tide_draft_config {
   float rope_theta, rms_eps;
   float beta1, beta2, adam_eps, weight_decay;
   int32_t dtype;
+  /* LM head.  The logits z = y W_lm^T exist for ONE block of rows at a time (bf16, overwritten in place by their
+   * gradient); the forward product, the row statistics, the logit gradient and the input-gradient product run
+   * block by block, and dW_lm accumulates over the blocks.
+   *   lm_block_rows      rows per block; 0 = the library's choice (half of batch*seq rounded up to 64, at most
+   *                      16384 rows and 6 GiB of logits).  Other values are rounded up to a multiple of 64.
+   *   lm_keep_all_rows   0 (default) = as above, the logit buffer is one block.  Non-zero = opt-in: the buffer
+   *                      holds the bf16 logit GRADIENT of every block until the end of the LM head and dW_lm is
+   *                      one product over all rows, which saves the read-modify-write of dW_lm per further
+   *                      block at the price of batch*seq x vocab x 2 bytes of workspace (8.4 GB at batch 16 x
+   *                      seq 2048, vocab 128256).  Forward-only calls never keep more than one block. */
+  int32_t lm_block_rows;
+  int32_t lm_keep_all_rows;
 } tide_draft_config;
 
 /* The ten tensors of the draft; the same struct describes parameters, gradients,
@@ -113,10 +125,8 @@ typedef struct tide_adam_state {
 } tide_adam_state;
 
 /* Bytes of DEVICE scratch the two calls below need for this config (the larger
- * of the two).  Returns 0 if the config is invalid (see tide_last_error).  The largest part is the logit
- * buffer, batch*seq x vocab elements when that is at most 16 GiB (8.4 GB at the 8B shape), else one row block of
- * at most 6 GiB; the environment variable TIDE_LOGIT_BUFFER_LIMIT_MB replaces the 16 GiB limit (read on every
- * call: keep it unchanged between this call and the calls that use the workspace). */
+ * of the two).  Returns 0 if the config is invalid (see tide_last_error).  The logit buffer in it is one row
+ * block (cfg->lm_block_rows x vocab elements; 4.2 GB at the 8B shape) unless cfg->lm_keep_all_rows asks for all. */
 size_t tide_draft_workspace_bytes(const tide_draft_config *cfg);
 
 /* Forward only (what the evaluation step of the paper's Algorithm 1 runs on held-out signals):

@@ -7,8 +7,8 @@
  * the slot is copied to a device buffer the caller owns while the previous batch trains, and the compute
  * stream waits on the copy's event only when it reaches the step that consumes it.
  *
- * Ownership: the ring (pinned host memory from hipHostMalloc), one stream at the default priority and one
- * event per slot belong to the object and are released by tide_ingest_destroy.  Device buffers belong to
+ * Ownership: the ring (pinned host memory from hipHostMalloc), one stream at the default priority and two
+ * events per slot belong to the object and are released by tide_ingest_destroy.  Device buffers belong to
  * the caller.  Nothing here is called from inside a kernel launch path of the training step: create once,
  * then acquire / submit / wait / (poll) per batch.  Not thread-safe: one producer thread per object.
  * Every function returns 0 on success or a negative TIDE_INGEST_* code; tide_ingest_last_error() gives
@@ -41,8 +41,15 @@ int tide_ingest_destroy(tide_ingest *q);
 int tide_ingest_acquire(tide_ingest *q, int32_t *slot, void **host_ptr);
 
 /* Enqueue the copy of the first `bytes` of the slot to device_dst (DEVICE pointer, caller-owned, must stay
- * valid until the copy completed) on the copy stream and record the slot's event.  Returns at once. */
-int tide_ingest_submit(tide_ingest *q, int32_t slot, void *device_dst, size_t bytes);
+ * valid until the copy completed) on the copy stream and record the slot's event.  Returns at once.
+ * The copy OVERWRITES device_dst, so it must not start while earlier work still reads that buffer (a training
+ * step enqueued before, not yet finished, that consumed the buffer's previous contents: the usual state of a
+ * device double buffer driven without host synchronisation).  after_reader != 0: the copy is ordered after
+ * everything enqueued so far on reader_stream (a hipStream_t, NULL = the default stream), by an event recorded
+ * there now that the copy stream waits for.  after_reader == 0: no ordering, reader_stream is ignored; the
+ * caller guarantees that nothing in flight reads device_dst. */
+int tide_ingest_submit(tide_ingest *q, int32_t slot, void *device_dst, size_t bytes, void *reader_stream,
+                       int32_t after_reader);
 
 /* Make `compute_stream` (a hipStream_t) wait for the slot's copy: work enqueued on it afterwards sees the
  * data.  Does not block the host. */

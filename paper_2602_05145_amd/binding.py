@@ -27,7 +27,8 @@ class TideDraftConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "seq", "n_capture", "target_hidden", "hidden",
                                          "n_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + \
                [(n, C.c_float) for n in ("rope_theta", "rms_eps", "beta1", "beta2", "adam_eps",
-                                         "weight_decay")] + [("dtype", C.c_int32)]
+                                         "weight_decay")] + [("dtype", C.c_int32), ("lm_block_rows", C.c_int32),
+                                                               ("lm_keep_all_rows", C.c_int32)]
 
 
 class TideDraftTensors(C.Structure):
@@ -160,6 +161,8 @@ def make_config(cfg: dict) -> TideDraftConfig:
         setattr(c, n, float(cfg[n]))
     dt = cfg["dtype"]
     c.dtype = {"fp32": TIDE_DTYPE_FP32, "bf16": TIDE_DTYPE_BF16}.get(dt, dt)
+    c.lm_block_rows = int(cfg.get("lm_block_rows", 0))
+    c.lm_keep_all_rows = int(cfg.get("lm_keep_all_rows", 0))
     return c
 
 
@@ -398,7 +401,7 @@ _lib.tide_ingest_destroy.argtypes = [_vp]
 _lib.tide_ingest_acquire.restype = _i32
 _lib.tide_ingest_acquire.argtypes = [_vp, C.POINTER(C.c_int32), C.POINTER(_vp)]
 _lib.tide_ingest_submit.restype = _i32
-_lib.tide_ingest_submit.argtypes = [_vp, _i32, _vp, _sz]
+_lib.tide_ingest_submit.argtypes = [_vp, _i32, _vp, _sz, _vp, _i32]
 _lib.tide_ingest_wait.restype = _i32
 _lib.tide_ingest_wait.argtypes = [_vp, _i32, _vp]
 _lib.tide_ingest_done.restype = _i32
@@ -425,8 +428,8 @@ def tide_ingest_acquire(h):
     return rc, int(slot.value), ptr.value
 
 
-def tide_ingest_submit(h, slot, device_dst, nbytes):
-    return _lib.tide_ingest_submit(h, int(slot), _ptr(device_dst), int(nbytes))
+def tide_ingest_submit(h, slot, device_dst, nbytes, reader_stream=None, after_reader=False):
+    return _lib.tide_ingest_submit(h, int(slot), _ptr(device_dst), int(nbytes), reader_stream, int(bool(after_reader)))
 
 
 def tide_ingest_wait(h, slot, stream):

@@ -490,7 +490,33 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
       }
     }
   }
-  if (!staged) {
+  if (!staged && p.accumulate && !R) {
+    // C += alpha * acc.  The old values of a 32-row slice are all requested before the first of them is used
+    // (32 or 64 loads in flight per lane instead of a load-add-store chain per element: the compiler cannot
+    // reorder the loads itself, it does not know that the stores of one element leave the next one alone).
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      float old[16][TN];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int gm = wm0 + 32 * i + 8 * (q >> 2) + 4 * lg + (q & 3);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int gn = wn0 + 32 * j + lr;
+          old[q][j] = (gm < p.M && gn < p.N) ? ldf(C, (size_t)gm * p.ldc + gn) : 0.f;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int gm = wm0 + 32 * i + 8 * (q >> 2) + 4 * lg + (q & 3);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int gn = wn0 + 32 * j + lr;
+          if (gm < p.M && gn < p.N) stf(C, (size_t)gm * p.ldc + gn, alpha * acc[i][j][q] + old[q][j]);
+        }
+      }
+    }
+  } else if (!staged) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll

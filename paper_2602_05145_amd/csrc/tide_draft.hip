@@ -49,6 +49,7 @@ bool check_config(const tide_draft_config* c) {
     fail(TIDE_ERR_CONFIG, "all sizes must be positive");
     return false;
   }
+  if (c->lm_block_rows < 0) { fail(TIDE_ERR_CONFIG, "lm_block_rows must be >= 0"); return false; }
   if (c->dtype != TIDE_DTYPE_FP32 && c->dtype != TIDE_DTYPE_BF16) { fail(TIDE_ERR_CONFIG, "dtype must be TIDE_DTYPE_FP32 or TIDE_DTYPE_BF16"); return false; }
   if (c->n_heads % c->n_kv_heads) { fail(TIDE_ERR_CONFIG, "n_heads (%d) must be a multiple of n_kv_heads (%d)", c->n_heads, c->n_kv_heads); return false; }
   if ((int64_t)c->n_heads * c->head_dim != c->hidden) { fail(TIDE_ERR_CONFIG, "hidden (%d) must equal n_heads*head_dim (%d*%d)", c->hidden, c->n_heads, c->head_dim); return false; }
@@ -99,21 +100,18 @@ Plan make_plan(const tide_draft_config* c) {
   p.ldz = (int64_t)align_up((size_t)p.V, 64);
   p.es = c->dtype == TIDE_DTYPE_BF16 ? 2 : 4;
   // The LM head works by blocks of lm_rows rows: half of the batch, at most 16384 rows (the forward and the
-  // input-gradient products measured faster at that height than over all rows at once).  The logit buffer
-  // holds ALL rows when that takes at most 16 GiB: the logit gradients of every block are then still there
-  // after the loop and dW_lm is one product over all rows, without a read-modify-write pass over the fp32
-  // dW_lm per block (1 ms per step at the 8B shape).  Otherwise it holds one block (at most 6 GiB) and
-  // dW_lm accumulates block by block.
-  int64_t rows = (int64_t)align_up((size_t)((p.T + 1) / 2), 64);
-  if (rows > 16384) rows = 16384;
-  if (rows > p.T) rows = p.T;
-  p.z_rows = p.T;
-  size_t limit = (size_t)16 << 30;
-  if (const char* e = std::getenv("TIDE_LOGIT_BUFFER_LIMIT_MB")) limit = (size_t)std::strtoull(e, nullptr, 10) << 20;   // tests force the block-wise path
-  if ((size_t)p.T * p.ldz * p.es > limit) {
+  // input-gradient products measured faster at that height than over all rows at once) and 6 GiB of logits.
+  // The logit buffer holds ONE block: logits never exist for more rows than that, and dW_lm accumulates block
+  // by block.  With cfg->lm_keep_all_rows it holds all rows instead: the logit gradients of every block are
+  // then still there after the loop and dW_lm is one product over all of them.
+  int64_t rows = c->lm_block_rows > 0 ? (int64_t)c->lm_block_rows : (p.T + 1) / 2;
+  rows = (int64_t)align_up((size_t)rows, 64);
+  if (c->lm_block_rows <= 0) {
+    if (rows > 16384) rows = 16384;
     while (rows > 256 && (size_t)rows * p.ldz * p.es > ((size_t)6 << 30)) rows /= 2;
-    p.z_rows = rows;
   }
+  if (rows > p.T) rows = p.T;
+  p.z_rows = c->lm_keep_all_rows ? p.T : rows;
   p.lm_rows = rows;
   const size_t T = (size_t)p.T, es = p.es;
   Bump b;

@@ -30,6 +30,7 @@ struct tide_ingest {
   char* ring;             // pinned
   hipStream_t copy_stream;
   hipEvent_t events[64];
+  hipEvent_t reader_events[64];   // recorded on the consumer's stream: the last reader of a slot's destination
   int state[64];
   int next;               // round-robin start of the search for a free slot
 };
@@ -63,9 +64,11 @@ int tide_ingest_create(tide_ingest** out, size_t slot_bytes, int32_t n_slots) {
     q->state[made] = kFree;
     e = hipEventCreateWithFlags(&q->events[made], hipEventDisableTiming);
     if (e != hipSuccess) break;
+    e = hipEventCreateWithFlags(&q->reader_events[made], hipEventDisableTiming);
+    if (e != hipSuccess) { (void)hipEventDestroy(q->events[made]); break; }
   }
   if (e != hipSuccess) {
-    for (int i = 0; i < made; ++i) (void)hipEventDestroy(q->events[i]);
+    for (int i = 0; i < made; ++i) { (void)hipEventDestroy(q->events[i]); (void)hipEventDestroy(q->reader_events[i]); }
     if (q->copy_stream) (void)hipStreamDestroy(q->copy_stream);
     if (q->ring) (void)hipHostFree(q->ring);
     delete q;
@@ -78,7 +81,7 @@ int tide_ingest_create(tide_ingest** out, size_t slot_bytes, int32_t n_slots) {
 int tide_ingest_destroy(tide_ingest* q) {
   if (!q) return fail(TIDE_INGEST_ERR_NULL, "queue is NULL");
   (void)hipStreamSynchronize(q->copy_stream);   // copies in flight read the ring
-  for (int i = 0; i < q->n_slots; ++i) (void)hipEventDestroy(q->events[i]);
+  for (int i = 0; i < q->n_slots; ++i) { (void)hipEventDestroy(q->events[i]); (void)hipEventDestroy(q->reader_events[i]); }
   (void)hipStreamDestroy(q->copy_stream);
   (void)hipHostFree(q->ring);
   delete q;
@@ -115,11 +118,18 @@ int tide_ingest_acquire(tide_ingest* q, int32_t* slot, void** host_ptr) {
   return fail(TIDE_INGEST_ERR_BUSY, "no free slot: %d slots are filling or copying", q->n_slots);
 }
 
-int tide_ingest_submit(tide_ingest* q, int32_t slot, void* device_dst, size_t bytes) {
+int tide_ingest_submit(tide_ingest* q, int32_t slot, void* device_dst, size_t bytes, void* reader_stream,
+                       int32_t after_reader) {
   if (!q || !device_dst) return fail(TIDE_INGEST_ERR_NULL, "NULL argument");
   if (slot < 0 || slot >= q->n_slots) return fail(TIDE_INGEST_ERR_ARG, "slot out of range");
   if (bytes == 0 || bytes > q->slot_bytes) return fail(TIDE_INGEST_ERR_ARG, "bytes must be in [1, slot_bytes]");
   if (q->state[slot] != kFilling) return fail(TIDE_INGEST_ERR_BUSY, "slot %d was not acquired", slot);
+  if (after_reader) {
+    // the destination may still be read by work already enqueued on the consumer's stream (the step before last of a
+    // device double buffer): the copy starts only after everything enqueued there so far
+    ING_HIP(hipEventRecord(q->reader_events[slot], (hipStream_t)reader_stream), "reader event record");
+    ING_HIP(hipStreamWaitEvent(q->copy_stream, q->reader_events[slot], 0), "copy stream wait");
+  }
   ING_HIP(hipMemcpyAsync(device_dst, q->ring + (size_t)slot * q->slot_bytes, bytes, hipMemcpyHostToDevice, q->copy_stream), "H2D copy");
   ING_HIP(hipEventRecord(q->events[slot], q->copy_stream), "event record");
   q->state[slot] = kCopying;

@@ -279,29 +279,31 @@ def test_training_raises_held_out_accuracy_on_learnable_labels():
     assert acc0 < 0.08 and acc1 > 0.15, (acc0, acc1)
 
 
-def test_blockwise_logit_buffer_gives_the_same_step(monkeypatch):
-    """The logit buffer normally holds every row and dW_lm is one product; above 16 GiB it holds one row block and
-    dW_lm accumulates block by block.  The second path, forced here through the limit's override, must give the
-    same loss and (up to the summation order of dW_lm) the same gradients, and a smaller workspace."""
-    from paper_2602_05145_amd import binding as B, runtime
-    cfg = W.get_config("small", batch=2, seq=200, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128,
-                       ffn=264, vocab=1000)
+def test_keeping_all_logit_gradients_gives_the_same_step():
+    """By default the logit buffer holds one row block and dW_lm accumulates block by block; with lm_keep_all_rows
+    it holds the logit gradients of all rows and dW_lm is one product.  Same loss, the same gradients up to the
+    summation order of dW_lm, a larger workspace; small forced blocks (several per batch, a ragged last one)
+    agree as well."""
+    from paper_2602_05145_amd import runtime
+    kw = dict(batch=2, seq=200, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128, ffn=264, vocab=1000)
+    cfg = W.get_config("small", **kw)
     wl = W.make_workload(cfg)
-    full = runtime.trainer_from_workload(cfg, wl)
-    full.train_step(cfg["lr"])
-    sync()
-    monkeypatch.setenv("TIDE_LOGIT_BUFFER_LIMIT_MB", "0")
     blockwise = runtime.trainer_from_workload(cfg, wl)
-    assert blockwise.ws_bytes < full.ws_bytes
     blockwise.train_step(cfg["lr"])
     sync()
-    assert float(blockwise.loss.item()) == float(full.loss.item())
-    for k in O.PARAM_NAMES:
-        a, b = blockwise.grads[k].double().cpu().numpy(), full.grads[k].double().cpu().numpy()
-        if k == "w_lm":
-            assert rel_max(a, b) <= 1e-5, k
-        else:
-            assert np.array_equal(a, b), k
+    for extra in (dict(lm_keep_all_rows=1), dict(lm_block_rows=64), dict(lm_block_rows=100, lm_keep_all_rows=1)):
+        other = runtime.trainer_from_workload(W.get_config("small", **kw, **extra), wl)
+        if extra.get("lm_keep_all_rows"):
+            assert other.ws_bytes > blockwise.ws_bytes
+        other.train_step(cfg["lr"])
+        sync()
+        assert float(other.loss.item()) == float(blockwise.loss.item())
+        for k in O.PARAM_NAMES:
+            a, b = other.grads[k].double().cpu().numpy(), blockwise.grads[k].double().cpu().numpy()
+            if k == "w_lm":
+                assert rel_max(a, b) <= 1e-5, (k, extra)
+            else:
+                assert np.array_equal(a, b), (k, extra)
 
 
 def _random_cfg(rng, dtype):
