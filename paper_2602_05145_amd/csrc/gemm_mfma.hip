@@ -80,12 +80,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 #define TIDE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
 // swizzle of a row-major stage: 16-byte piece index ^= (k-row & 3) << 2, i.e. the four k-rows that one
-// transposing read touches sit in four different 64-byte bank groups
+// transposing read touches sit in four different 64-byte bank groups.  The 16x16x32 kernel also flips bit 1 of the
+// piece index with bit 3 of the k-row: there the 16-lane groups of a read differ in k (by 8 rows) and not in the
+// column, and the flip keeps two neighbouring groups on different banks.
 #define TIDE_RSWZ(kq) ((kq) << 2)
+#define TIDE_RSWZ16(krow) ((((krow) & 3) << 2) ^ ((((krow) >> 3) & 1) << 1))
 constexpr uint32_t kOobOffset = 0x7FFFFFF0u;  // beyond any buffer extent used here: the load returns zeros
 
 // One operand (A or B) of one block: R rows (BM or BN) of the tile, either K-major or row-major over K.
-template <int R, int NW, bool RMAJ, int T, int BK>   // T = MFMA tiles per wave along this dimension; BK = slab depth
+template <int R, int NW, bool RMAJ, int T, int BK, int MI = 32>   // T = 32-row MFMA tiles per wave along this dimension; BK = slab depth; MI = MFMA tile edge
 struct Operand {
   static constexpr int STAGE = R * BK;                                   // elements per stage
   static constexpr int CHUNKS = STAGE * 2 / 1024;                        // 1 KiB DMA instructions per stage
@@ -112,7 +115,7 @@ struct Operand {
 #pragma unroll
       for (int i = 0; i < PER_WAVE; ++i) {
         const int krow = (wave * PER_WAVE + i) * RPC + kr;
-        off[i] = (uint32_t)((krow * ld + (pc ^ TIDE_RSWZ(krow & 3)) * 8) * 2);
+        off[i] = (uint32_t)((krow * ld + (pc ^ (MI == 16 ? TIDE_RSWZ16(krow) : TIDE_RSWZ(krow & 3))) * 8) * 2);
         piece[i] = 0;
       }
     } else {
@@ -178,6 +181,50 @@ struct Operand {
     }
 #pragma unroll
     for (int i = 0; i < NRO; ++i) asm("" : "+v"(ro[i]));
+  }
+
+  // ---- 16x16x32 MFMA: a fragment is 16 tile rows x 32 k; lane l holds row l & 15, k = 8 * (l >> 4) .. + 7 ----
+  static constexpr int T16 = 2 * T;                          // 16-row fragments per wave along this dimension
+  static constexpr int NRO16 = RMAJ ? T16 : BK / 32;
+  static constexpr int kReadsPerFrag16 = RMAJ ? 2 : 1;
+  static __device__ __forceinline__ void read_offsets16(int wbase, int lane, uint32_t (&ro)[NRO16]) {
+    const int r16 = lane & 15, g = lane >> 4;
+    if (RMAJ) {
+      // transposing reads: lane j of a 16-lane group addresses k-row j / 4, tile rows 4 * (j % 4) .. + 3 and
+      // receives tile row j for those 4 k; the group's k-rows start at 8 * g
+      const int kq = (lane >> 2) & 3, rq = lane & 3;
+#pragma unroll
+      for (int i = 0; i < T16; ++i) {
+        const int col = wbase + 16 * i + 4 * rq;
+        const int krow = g * 8 + kq;
+        ro[i] = (uint32_t)(krow * R + ((((col >> 3) ^ TIDE_RSWZ16(krow)) << 3) | (col & 7)));
+      }
+    } else {
+      const int sw = (r16 >> SWZ_SHIFT) & (KPIECES - 1);
+#pragma unroll
+      for (int h = 0; h < NRO16; ++h) ro[h] = (uint32_t)((wbase + r16) * BK + (((h * 4 + g) ^ sw) * 8));
+    }
+#pragma unroll
+    for (int i = 0; i < NRO16; ++i) asm("" : "+v"(ro[i]));
+  }
+  // NF fragments starting at fragment index F0, of the k32 step `h` (< BK/32) of a stage
+  template <int F0, int NF, typename StagePtr>
+  static __device__ __forceinline__ void frags16(StagePtr stage, int h, const uint32_t (&ro)[NRO16], u32x4_t (&f)[NF]) {
+    if (RMAJ) {
+      typedef short s16x4_t __attribute__((ext_vector_type(4)));
+      typedef __attribute__((address_space(3))) s16x4_t* lds_tr_t;
+#pragma unroll
+      for (int i = 0; i < NF; ++i) {
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_t)(stage + ro[F0 + i] + (h * 32) * R));
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_t)(stage + ro[F0 + i] + (h * 32 + 4) * R));
+        const uint2 a = __builtin_bit_cast(uint2, lo), b2 = __builtin_bit_cast(uint2, hi);
+        f[i][0] = a.x; f[i][1] = a.y; f[i][2] = b2.x; f[i][3] = b2.y;
+      }
+    } else {
+      typedef __attribute__((address_space(3))) const u32x4_t* lds_v4_t;
+#pragma unroll
+      for (int i = 0; i < NF; ++i) f[i] = *(lds_v4_t)(stage + ro[h] + (F0 + i) * 16 * BK);
+    }
   }
 
   // MFMA operand fragments of k16 step `kk` (< BK/16)
@@ -537,6 +584,327 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// The 256x256 tile with v_mfma_f32_16x16x32_bf16.  Same ring, DMA, swizzles, synchronisation and epilogues as
+// the kernel above; what changes is the matrix instruction: on this chip the matrix pipes sustain a higher rate
+// under the package power limit with the 16x16x32 form (a pure-MFMA loop on random operands: 2.10 against 1.88
+// PFLOP/s), while the LDS operand traffic per flop stays the same (a 16-row x 32-k fragment is one 16-byte
+// read per lane, like a 32-row x 16-k one).  A wave owns 8 x 4 tiles of 16 x 16 (128 x 64); a "quarter" of the
+// schedule is one k32 step of four of its A fragments against its four B fragments: 16 MFMAs (256 clocks, as the
+// 8 MFMAs of a k16 quarter above), with the A fragments double-buffered per quarter and the B fragments per k32
+// step.  Accumulator element q of lane l in tile (i, j) is row 16 i + 4 (l >> 4) + q, column 16 j + (l & 15).
+// ------------------------------------------------------------------------------------------------
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <bool AMM, bool BNM, typename TO, int BK>
+__global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
+  constexpr int BM = 256, BN = 256, NW = 8;
+  static_assert(BK == 32 || BK == 64, "slab depth");
+  constexpr int NST = (BK == 32) ? 4 : 2;
+  constexpr int WAVES_N = 4, WAVES_M = 2;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // 128 x 64
+  constexpr int TM = WM / 16, TN = WN / 16;             // 8 x 4 tiles of 16 x 16
+  constexpr int GA = 4;                                 // A fragments per quarter
+  using OpA = Operand<BM, NW, AMM, WM / 32, BK, 16>;
+  using OpB = Operand<BN, NW, BNM, WN / 32, BK, 16>;
+  constexpr int A_STAGE = OpA::STAGE, B_STAGE = OpB::STAGE;
+  constexpr int NVM = OpA::PER_WAVE + OpB::PER_WAVE;
+  constexpr int RA = GA * OpA::kReadsPerFrag16;         // LDS reads of one A group
+  constexpr int RB = TN * OpB::kReadsPerFrag16;         // LDS reads of the B fragments of a k32 step
+  constexpr int NMF = GA * TN;                          // MFMAs per quarter
+
+  constexpr int STAGE34 = (NST == 4) ? A_STAGE + B_STAGE : 8;
+  __shared__ __attribute__((aligned(1024))) bf16_t s0[A_STAGE + B_STAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t s1[A_STAGE + B_STAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t s2[STAGE34];
+  __shared__ __attribute__((aligned(1024))) bf16_t s3[STAGE34];
+  auto stage = [&](auto ST) -> bf16_t* {
+    if constexpr (decltype(ST)::value == 0) return s0;
+    else if constexpr (decltype(ST)::value == 1) return s1;
+    else if constexpr (decltype(ST)::value == 2) return s2;
+    else return s3;
+  };
+  typedef __attribute__((address_space(3))) const bf16_t* lds_bf_t;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+  const int lc = lane & 15, lg = lane >> 4;
+
+  if (p.m_dev) p.M = max(0, min(p.M, *p.m_dev - p.m_off));
+  if (p.k_dev) p.K = max(0, min(p.K, *p.k_dev - p.k_off));
+  if (p.K == 0 && p.K2 == 0 && p.accumulate) return;
+
+  int tile_m, tile_n;
+  {
+    const int tiles_m = (p.M + BM - 1) / BM;
+    const int nb = tiles_m * p.tiles_n;
+    const int pid = blockIdx.x;
+    if (pid >= nb) return;
+    const int xcd = pid & 7, idx = pid >> 3;
+    const int q = nb >> 3, r = nb & 7;
+    const int v = xcd * q + min(xcd, r) + idx;
+    constexpr int GROUP = 4;
+    const int per_group = GROUP * p.tiles_n;
+    const int gid = v / per_group;
+    const int first_m = gid * GROUP;
+    const int gsz = min(tiles_m - first_m, GROUP);
+    const int in_g = v - gid * per_group;
+    tile_m = first_m + in_g % gsz;
+    tile_n = in_g / gsz;
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const bf16_t* a_tile0 = AMM ? p.A + m0 : p.A + (size_t)m0 * p.lda;
+  const bf16_t* b_tile0 = BNM ? p.B + n0 : p.B + (size_t)n0 * p.ldb;
+  const bf16_t* a_tile1 = p.A2 ? (AMM ? p.A2 + m0 : p.A2 + (size_t)m0 * p.lda) : a_tile0;
+  const bf16_t* b_tile1 = p.B2 ? (BNM ? p.B2 + n0 : p.B2 + (size_t)n0 * p.ldb) : b_tile0;
+  const int a_rows = min(BM, p.M - m0), b_rows = min(BN, p.N - n0);
+  uint32_t a_off[OpA::PER_WAVE], b_off[OpB::PER_WAVE];
+  int a_piece[OpA::PER_WAVE], b_piece[OpB::PER_WAVE];
+  OpA::lane_offsets(p.lda, wave, lane, a_off, a_piece);
+  OpB::lane_offsets(p.ldb, wave, lane, b_off, b_piece);
+
+  f32x4_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[i][j][q] = 0.f;
+
+  const int nk1 = (p.K + BK - 1) / BK;
+  const int nkp2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
+  const int nk = nk1 + nkp2;
+  const int nk_round = (nk + NST - 1) / NST * NST;
+
+  auto issue = [&](auto ST, int kt) {
+    bf16_t* sb = stage(ST);
+    int pr = 0, k0 = kt * BK, Kc = p.K;
+    if (kt >= nk1) {
+      if (kt < nk) { pr = 1; k0 = (kt - nk1) * BK; Kc = p.K2; }
+      else { k0 = p.K + BK; }
+    }
+    OpA::issue(sb, pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc, a_off, a_piece, wave);
+    OpB::issue(sb + A_STAGE, pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc, b_off, b_piece, wave);
+  };
+  uint32_t a_ro[OpA::NRO16], b_ro[OpB::NRO16];
+  OpA::read_offsets16(wave_m * WM, lane, a_ro);
+  OpB::read_offsets16(wave_n * WN, lane, b_ro);
+  // A fragments of group G (0, 1) and the B fragments of the k32 step h of a stage
+  auto frags_a = [&](auto ST, int h, auto G, u32x4_t (&fa)[GA]) {
+    OpA::template frags16<decltype(G)::value * GA, GA>((lds_bf_t)stage(ST), h, a_ro, fa);
+  };
+  auto frags_b = [&](auto ST, int h, u32x4_t (&fb)[TN]) {
+    OpB::template frags16<0, TN>((lds_bf_t)stage(ST) + A_STAGE, h, b_ro, fb);
+  };
+  auto mma = [&](auto G, u32x4_t (&fa)[GA], u32x4_t (&fb)[TN]) {
+    constexpr int g0 = decltype(G)::value * GA;
+#pragma unroll
+    for (int i = 0; i < GA; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[g0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fa[i]),
+                                                                 __builtin_bit_cast(bf16x8_t, fb[j]), acc[g0 + i][j], 0, 0, 0);
+  };
+
+  u32x4_t fa0[GA], fa1[GA], fb0[TN], fb1[TN];
+  if constexpr (BK == 64) {
+    // ---- two stages of 64: two k32 steps of two quarters each; the barrier sits before the last quarter ----
+    issue(Int<0>{}, 0);
+    TIDE_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    frags_a(Int<0>{}, 0, Int<0>{}, fa0);
+    frags_b(Int<0>{}, 0, fb0);
+    issue(Int<1>{}, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    // slab kt lives in ST (fa0 = its first A group, fb0 = its first B fragments), slab kt+1 is in flight into SO
+    auto step = [&](auto ST, auto SO, int kt) {
+      frags_a(ST, 0, Int<1>{}, fa1);
+      mma(Int<0>{}, fa0, fb0);
+      sched_slots<NMF, RA, 0, 0>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+      frags_a(ST, 1, Int<0>{}, fa0);
+      frags_b(ST, 1, fb1);
+      mma(Int<1>{}, fa1, fb0);
+      sched_slots<NMF, RA + RB, 0, 1>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+      frags_a(ST, 1, Int<1>{}, fa1);
+      mma(Int<0>{}, fa0, fb1);
+      sched_slots<NMF, RA, 0, 2>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+      // all operand reads of this wave from ST have returned; its part of slab kt+1 has landed
+      __builtin_amdgcn_s_waitcnt(0);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      frags_a(SO, 0, Int<0>{}, fa0);
+      frags_b(SO, 0, fb0);
+      issue(ST, kt + 2);
+      mma(Int<1>{}, fa1, fb1);
+      __builtin_amdgcn_sched_group_barrier(0x100, RA + RB, 3);
+      sched_slots<NMF, 0, NVM, 3>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int kt = 0; kt < nk_round; kt += 2) {
+      step(Int<0>{}, Int<1>{}, kt);
+      step(Int<1>{}, Int<0>{}, kt + 1);
+    }
+  } else {
+    // ---- four stages of 32: one k32 step of two quarters per slab; the barrier sits between them ----
+    issue(Int<0>{}, 0);
+    issue(Int<1>{}, 1);
+    issue(Int<2>{}, 2);
+    TIDE_WAIT_VMCNT(2 * NVM);
+    __builtin_amdgcn_s_barrier();
+    frags_a(Int<0>{}, 0, Int<0>{}, fa0);
+    frags_b(Int<0>{}, 0, fb0);
+    // slab kt lives in ST (fa0, fbc hold its first quarter's operands), slab kt+1 in SN, slab kt+3 goes to SP
+    auto step = [&](auto ST, auto SN, auto SP, int kt, u32x4_t (&fbc)[TN], u32x4_t (&fbn)[TN]) {
+      frags_a(ST, 0, Int<1>{}, fa1);
+      issue(SP, kt + NST - 1);
+      mma(Int<0>{}, fa0, fbc);
+      sched_slots<NMF, RA, NVM, 0>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+      TIDE_WAIT_VMCNT(2 * NVM);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      frags_a(SN, 0, Int<0>{}, fa0);
+      frags_b(SN, 0, fbn);
+      mma(Int<1>{}, fa1, fbc);
+      sched_slots<NMF, RA + RB, 0, 1>(std::make_integer_sequence<int, NMF>{});
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int kt = 0; kt < nk_round; kt += 4) {
+      step(Int<0>{}, Int<1>{}, Int<3>{}, kt, fb0, fb1);
+      step(Int<1>{}, Int<2>{}, Int<0>{}, kt + 1, fb1, fb0);
+      step(Int<2>{}, Int<3>{}, Int<1>{}, kt + 2, fb0, fb1);
+      step(Int<3>{}, Int<0>{}, Int<2>{}, kt + 3, fb1, fb0);
+    }
+  }
+  TIDE_WAIT_VMCNT(0);
+
+  // ---- epilogue ----
+  float alpha = p.alpha;
+  if (p.alpha_dev) alpha *= *p.alpha_dev;
+  TO* C = (TO*)p.C;
+  const TO* R = (const TO*)p.R;
+  const int wm0 = m0 + wave_m * WM, wn0 = n0 + wave_n * WN;
+
+  bool staged = false;
+  if constexpr (sizeof(TO) == 2) {
+    if (!R && !p.accumulate && (p.ldc % 8) == 0 && (p.N % 8) == 0) {
+      staged = true;
+      // bf16 result through a wave-private LDS patch of 32 rows (two tile rows) x WN
+      __builtin_amdgcn_s_barrier();
+      constexpr int PP = WN + 8;
+      static_assert((NW / 2) * 32 * PP <= A_STAGE + B_STAGE, "epilogue patches of half the waves must fit in one stage");
+      bf16_t* patch = (wave < NW / 2 ? s0 : s1) + (wave % (NW / 2)) * (32 * PP);
+      constexpr int PIECES = WN / 8;
+#pragma unroll
+      for (int i2 = 0; i2 < TM / 2; ++i2) {
+#pragma unroll
+        for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              patch[(16 * ih + 4 * lg + q) * PP + 16 * j + lc] = f2bf(alpha * acc[2 * i2 + ih][j][q]);
+#pragma unroll
+        for (int t = 0; t < 32 * PIECES / 64; ++t) {
+          const int pc = lane + 64 * t;
+          const int row = pc / PIECES, piece = pc % PIECES;
+          const int gm = wm0 + 32 * i2 + row, gn = wn0 + piece * 8;
+          const u32x4_t val = *reinterpret_cast<const u32x4_t*>(patch + row * PP + piece * 8);
+          if (gm < p.M && gn < p.N)
+            *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(C) + (size_t)gm * p.ldc + gn) = val;
+        }
+      }
+    } else if constexpr ((NW / 2) * 32 * (WN + 4) * 2 <= A_STAGE + B_STAGE) {
+     if (R && !p.accumulate && (p.ldc % 8) == 0 && (p.ldr % 8) == 0 && (p.N % 8) == 0) {
+      staged = true;
+      __builtin_amdgcn_s_barrier();
+      constexpr int PF = WN + 4;
+      float* patch = reinterpret_cast<float*>(wave < NW / 2 ? s0 : s1) + (wave % (NW / 2)) * (32 * PF);
+      constexpr int PIECES = WN / 8;
+      const bf16_t* Rb = reinterpret_cast<const bf16_t*>(R);
+#pragma unroll
+      for (int i2 = 0; i2 < TM / 2; ++i2) {
+#pragma unroll
+        for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              patch[(16 * ih + 4 * lg + q) * PF + 16 * j + lc] = alpha * acc[2 * i2 + ih][j][q];
+#pragma unroll
+        for (int t = 0; t < 32 * PIECES / 64; ++t) {
+          const int pc = lane + 64 * t;
+          const int row = pc / PIECES, piece = pc % PIECES;
+          const int gm = wm0 + 32 * i2 + row, gn = wn0 + piece * 8;
+          if (gm < p.M && gn < p.N) {
+            float v[8], r[8];
+            const float4 a0 = *reinterpret_cast<const float4*>(patch + row * PF + piece * 8);
+            const float4 a1 = *reinterpret_cast<const float4*>(patch + row * PF + piece * 8 + 4);
+            v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
+            ld8(Rb, (size_t)gm * p.ldr + gn, r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += r[e];
+            st8(reinterpret_cast<bf16_t*>(C), (size_t)gm * p.ldc + gn, v);
+          }
+        }
+      }
+     }
+    }
+  }
+  if (!staged && p.accumulate && !R) {
+    // C += alpha * acc: the old values of two tile rows are all requested before the first of them is used
+#pragma unroll
+    for (int i2 = 0; i2 < TM / 2; ++i2) {
+      float old[2][TN][4];
+#pragma unroll
+      for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int gm = wm0 + 16 * (2 * i2 + ih) + 4 * lg + q;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int gn = wn0 + 16 * j + lc;
+            old[ih][j][q] = (gm < p.M && gn < p.N) ? ldf(C, (size_t)gm * p.ldc + gn) : 0.f;
+          }
+        }
+#pragma unroll
+      for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int gm = wm0 + 16 * (2 * i2 + ih) + 4 * lg + q;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int gn = wn0 + 16 * j + lc;
+            if (gm < p.M && gn < p.N) stf(C, (size_t)gm * p.ldc + gn, alpha * acc[2 * i2 + ih][j][q] + old[ih][j][q]);
+          }
+        }
+    }
+  } else if (!staged) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int gm = wm0 + 16 * i + 4 * lg + q;
+        if (gm >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int gn = wn0 + 16 * j + lc;
+          if (gn >= p.N) continue;
+          float v = alpha * acc[i][j][q];
+          if (R) v += ldf(R, (size_t)gm * p.ldr + gn);
+          if (p.accumulate) v += ldf(C, (size_t)gm * p.ldc + gn);
+          stf(C, (size_t)gm * p.ldc + gn, v);
+        }
+      }
+  }
+}
+
 bool gemm_mfma_supported(const GemmArgs& a) {
   if (a.in_dtype != kBF16) return false;
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
@@ -572,6 +940,15 @@ template <bool AMM, bool BNM, typename TO>
 hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
   // slab depth: 64 (two stages) as soon as one operand is K-major, else 32 (four stages)
   constexpr int BK = (AMM && BNM) ? 32 : 64;
+#ifndef TIDE_BIG_TILE_MFMA32
+  if (use_big_tiles(p.M, p.N)) {
+    MfmaParams q = p;
+    q.tiles_m = (p.M + 255) / 256;
+    q.tiles_n = (p.N + 255) / 256;
+    hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK>), dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(512), 0, s, q);
+    return hipGetLastError();
+  }
+#endif
   if (use_big_tiles(p.M, p.N)) return launch_cfg<256, 256, 8, AMM, BNM, TO, BK>(p, s);
   return launch_cfg<128, 128, 4, AMM, BNM, TO, BK>(p, s);
 }
