@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libtide_draft.so")
 CONTROL_LIB = os.path.join(HERE, "libtide_control.so")
 SOURCES = ["tide_draft.hip", "elementwise.hip", "gemm_simple.hip", "gemm_mfma.hip",
            "attention_simple.hip", "attention_mfma.hip", "tide_ingest.hip", "unroll.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -87,6 +87,22 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 #define TIDE_RSWZ16(krow) ((((krow) & 3) << 2) ^ ((((krow) >> 3) & 1) << 1))
 constexpr uint32_t kOobOffset = 0x7FFFFFF0u;  // beyond any buffer extent used here: the load returns zeros
 
+// One LDS-DMA load of 16 bytes per lane, written as an instruction: the 64 lanes' data go to 1 KiB of LDS at
+// `lds_addr` (a scalar), each lane fetches from byte `voff` of the buffer `rsrc` (zeros outside its extent).
+// The compiler does not see that this writes LDS, so it never orders an LDS read after it by waiting for every
+// load in flight (which it does for the builtin form as soon as it cannot prove that the read and the loads in
+// flight touch different arrays, e.g. where paths of the loop merge); all waits on these loads are explicit.
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4_t make_rsrc_words(const void* base, uint32_t bytes) {
+  const uint64_t a = (uint64_t)base;
+  i32x4_t r;
+  r[0] = (int)(uint32_t)a; r[1] = (int)((uint32_t)(a >> 32) & 0xffffu); r[2] = (int)bytes; r[3] = 0x00020000;
+  return r;
+}
+__device__ __forceinline__ void dma16(i32x4_t rsrc, uint32_t lds_addr, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(rsrc));
+}
+
 // One operand (A or B) of one block: R rows (BM or BN) of the tile, either K-major or row-major over K.
 template <int R, int NW, bool RMAJ, int T, int BK, int MI = 32>   // T = 32-row MFMA tiles per wave along this dimension; BK = slab depth; MI = MFMA tile edge
 struct Operand {
@@ -154,6 +170,33 @@ struct Operand {
         const uint32_t o = kin ? off[i] + (uint32_t)(k0 * 2) : kOobOffset;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_vp)(stage + (wave * PER_WAVE + i) * 512), 16, o, 0, 0, 0);
       }
+    }
+  }
+
+  // The same loads issued one by one as instructions (dma16): slab_desc is the scalar part of a slab, chunk<I>
+  // issues the wave's I-th chunk into the LDS unit at byte address `unit` (scalar); wave_s is the wave index as a scalar.
+  struct SlabDesc { i32x4_t rs; int k0, Kc; };
+  static __device__ __forceinline__ SlabDesc slab_desc(const bf16_t* tile, int ld, int rows_valid, int cols_left, int k0, int Kc) {
+    SlabDesc d;
+    d.k0 = k0; d.Kc = Kc;
+    if (RMAJ) {
+      const int kv = min(BK, Kc - k0);
+      const bf16_t* base = tile + (size_t)(kv > 0 ? k0 : 0) * ld;
+      d.rs = make_rsrc_words(base, kv > 0 ? (uint32_t)(((int64_t)(kv - 1) * ld + cols_left) * 2) : 0u);
+    } else {
+      d.rs = make_rsrc_words(tile, (uint32_t)(((int64_t)(rows_valid - 1) * ld + Kc) * 2));
+    }
+    return d;
+  }
+  template <int I>
+  static __device__ __forceinline__ void chunk(const SlabDesc& d, uint32_t unit, const uint32_t (&off)[PER_WAVE],
+                                               const int (&piece)[PER_WAVE], int wave_s) {
+    const uint32_t lds = unit + (uint32_t)((wave_s * PER_WAVE + I) * 1024);
+    if (RMAJ) {
+      dma16(d.rs, lds, off[I]);
+    } else {
+      const bool kin = (d.k0 + piece[I] * 8) < d.Kc;
+      dma16(d.rs, lds, kin ? off[I] + (uint32_t)(d.k0 * 2) : kOobOffset);
     }
   }
 
@@ -601,7 +644,6 @@ template <bool AMM, bool BNM, typename TO, int BK>
 __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
   constexpr int BM = 256, BN = 256, NW = 8;
   static_assert(BK == 32 || BK == 64, "slab depth");
-  constexpr int NST = (BK == 32) ? 4 : 2;
   constexpr int WAVES_N = 4, WAVES_M = 2;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // 128 x 64
   constexpr int TM = WM / 16, TN = WN / 16;             // 8 x 4 tiles of 16 x 16
@@ -609,22 +651,10 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
   using OpA = Operand<BM, NW, AMM, WM / 32, BK, 16>;
   using OpB = Operand<BN, NW, BNM, WN / 32, BK, 16>;
   constexpr int A_STAGE = OpA::STAGE, B_STAGE = OpB::STAGE;
-  constexpr int NVM = OpA::PER_WAVE + OpB::PER_WAVE;
+  constexpr int NVA = OpA::PER_WAVE, NVB = OpB::PER_WAVE, NVM = NVA + NVB;
   constexpr int RA = GA * OpA::kReadsPerFrag16;         // LDS reads of one A group
   constexpr int RB = TN * OpB::kReadsPerFrag16;         // LDS reads of the B fragments of a k32 step
   constexpr int NMF = GA * TN;                          // MFMAs per quarter
-
-  constexpr int STAGE34 = (NST == 4) ? A_STAGE + B_STAGE : 8;
-  __shared__ __attribute__((aligned(1024))) bf16_t s0[A_STAGE + B_STAGE];
-  __shared__ __attribute__((aligned(1024))) bf16_t s1[A_STAGE + B_STAGE];
-  __shared__ __attribute__((aligned(1024))) bf16_t s2[STAGE34];
-  __shared__ __attribute__((aligned(1024))) bf16_t s3[STAGE34];
-  auto stage = [&](auto ST) -> bf16_t* {
-    if constexpr (decltype(ST)::value == 0) return s0;
-    else if constexpr (decltype(ST)::value == 1) return s1;
-    else if constexpr (decltype(ST)::value == 2) return s2;
-    else return s3;
-  };
   typedef __attribute__((address_space(3))) const bf16_t* lds_bf_t;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -660,8 +690,8 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
   const bf16_t* a_tile1 = p.A2 ? (AMM ? p.A2 + m0 : p.A2 + (size_t)m0 * p.lda) : a_tile0;
   const bf16_t* b_tile1 = p.B2 ? (BNM ? p.B2 + n0 : p.B2 + (size_t)n0 * p.ldb) : b_tile0;
   const int a_rows = min(BM, p.M - m0), b_rows = min(BN, p.N - n0);
-  uint32_t a_off[OpA::PER_WAVE], b_off[OpB::PER_WAVE];
-  int a_piece[OpA::PER_WAVE], b_piece[OpB::PER_WAVE];
+  uint32_t a_off[NVA], b_off[NVB];
+  int a_piece[NVA], b_piece[NVB];
   OpA::lane_offsets(p.lda, wave, lane, a_off, a_piece);
   OpB::lane_offsets(p.ldb, wave, lane, b_off, b_piece);
 
@@ -676,27 +706,34 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
   const int nk1 = (p.K + BK - 1) / BK;
   const int nkp2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
   const int nk = nk1 + nkp2;
-  const int nk_round = (nk + NST - 1) / NST * NST;
 
-  auto issue = [&](auto ST, int kt) {
-    bf16_t* sb = stage(ST);
-    int pr = 0, k0 = kt * BK, Kc = p.K;
+  // which operand pair and k offset slab kt stands for (slabs past nk are dummies: every load out of range)
+  auto slab = [&](int kt, int& pr, int& k0, int& Kc) {
+    pr = 0; k0 = kt * BK; Kc = p.K;
     if (kt >= nk1) {
       if (kt < nk) { pr = 1; k0 = (kt - nk1) * BK; Kc = p.K2; }
       else { k0 = p.K + BK; }
     }
-    OpA::issue(sb, pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc, a_off, a_piece, wave);
-    OpB::issue(sb + A_STAGE, pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc, b_off, b_piece, wave);
+  };
+  auto issue_a = [&](bf16_t* unit, int kt) {
+    int pr, k0, Kc;
+    slab(kt, pr, k0, Kc);
+    OpA::issue(unit, pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc, a_off, a_piece, wave);
+  };
+  auto issue_b = [&](bf16_t* unit, int kt) {
+    int pr, k0, Kc;
+    slab(kt, pr, k0, Kc);
+    OpB::issue(unit, pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc, b_off, b_piece, wave);
   };
   uint32_t a_ro[OpA::NRO16], b_ro[OpB::NRO16];
   OpA::read_offsets16(wave_m * WM, lane, a_ro);
   OpB::read_offsets16(wave_n * WN, lane, b_ro);
-  // A fragments of group G (0, 1) and the B fragments of the k32 step h of a stage
-  auto frags_a = [&](auto ST, int h, auto G, u32x4_t (&fa)[GA]) {
-    OpA::template frags16<decltype(G)::value * GA, GA>((lds_bf_t)stage(ST), h, a_ro, fa);
+  // A fragments of group G (0, 1) / the B fragments of the k32 step h of an LDS unit
+  auto frags_a = [&](const bf16_t* unit, int h, auto G, u32x4_t (&fa)[GA]) {
+    OpA::template frags16<decltype(G)::value * GA, GA>((lds_bf_t)unit, h, a_ro, fa);
   };
-  auto frags_b = [&](auto ST, int h, u32x4_t (&fb)[TN]) {
-    OpB::template frags16<0, TN>((lds_bf_t)stage(ST) + A_STAGE, h, b_ro, fb);
+  auto frags_b = [&](const bf16_t* unit, int h, u32x4_t (&fb)[TN]) {
+    OpB::template frags16<0, TN>((lds_bf_t)unit, h, b_ro, fb);
   };
   auto mma = [&](auto G, u32x4_t (&fa)[GA], u32x4_t (&fb)[TN]) {
     constexpr int g0 = decltype(G)::value * GA;
@@ -708,69 +745,276 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
                                                                  __builtin_bit_cast(bf16x8_t, fb[j]), acc[g0 + i][j], 0, 0, 0);
   };
 
+  // ---- epilogue: needs, per wave, an LDS patch of 32 x (WN + 4) floats that no DMA is writing any more ----
+  constexpr int kPatchElems = 32 * (WN + 4) * 2;   // in bf16 elements
+  auto epilogue = [&](bf16_t* patch_mem) {
+    float alpha = p.alpha;
+    if (p.alpha_dev) alpha *= *p.alpha_dev;
+    TO* C = (TO*)p.C;
+    const TO* R = (const TO*)p.R;
+    const int wm0 = m0 + wave_m * WM, wn0 = n0 + wave_n * WN;
+    bool staged = false;
+    if constexpr (sizeof(TO) == 2) {
+      constexpr int PIECES = WN / 8;
+      if (!R && !p.accumulate && (p.ldc % 8) == 0 && (p.N % 8) == 0) {
+        staged = true;
+        // bf16 result through the wave's LDS patch (32 rows = two tile rows at a time) so that it leaves as
+        // 16-byte row segments.  Every wave waited for its own DMA; the barrier orders the last operand reads
+        // of the other waves before the patch writes.
+        __builtin_amdgcn_s_barrier();
+        constexpr int PP = WN + 8;
+        bf16_t* patch = patch_mem;
+#pragma unroll
+        for (int i2 = 0; i2 < TM / 2; ++i2) {
+#pragma unroll
+          for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                patch[(16 * ih + 4 * lg + q) * PP + 16 * j + lc] = f2bf(alpha * acc[2 * i2 + ih][j][q]);
+#pragma unroll
+          for (int t = 0; t < 32 * PIECES / 64; ++t) {
+            const int pc = lane + 64 * t;
+            const int row = pc / PIECES, piece = pc % PIECES;
+            const int gm = wm0 + 32 * i2 + row, gn = wn0 + piece * 8;
+            const u32x4_t val = *reinterpret_cast<const u32x4_t*>(patch + row * PP + piece * 8);
+            if (gm < p.M && gn < p.N)
+              *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(C) + (size_t)gm * p.ldc + gn) = val;
+          }
+        }
+      } else if (R && !p.accumulate && (p.ldc % 8) == 0 && (p.ldr % 8) == 0 && (p.N % 8) == 0) {
+        staged = true;
+        // bf16 result plus residual: the patch keeps fp32 so that alpha * acc + residual is rounded once
+        __builtin_amdgcn_s_barrier();
+        constexpr int PF = WN + 4;
+        float* patch = reinterpret_cast<float*>(patch_mem);
+        const bf16_t* Rb = reinterpret_cast<const bf16_t*>(R);
+#pragma unroll
+        for (int i2 = 0; i2 < TM / 2; ++i2) {
+#pragma unroll
+          for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                patch[(16 * ih + 4 * lg + q) * PF + 16 * j + lc] = alpha * acc[2 * i2 + ih][j][q];
+#pragma unroll
+          for (int t = 0; t < 32 * PIECES / 64; ++t) {
+            const int pc = lane + 64 * t;
+            const int row = pc / PIECES, piece = pc % PIECES;
+            const int gm = wm0 + 32 * i2 + row, gn = wn0 + piece * 8;
+            if (gm < p.M && gn < p.N) {
+              float v[8], r[8];
+              const float4 a0 = *reinterpret_cast<const float4*>(patch + row * PF + piece * 8);
+              const float4 a1 = *reinterpret_cast<const float4*>(patch + row * PF + piece * 8 + 4);
+              v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
+              ld8(Rb, (size_t)gm * p.ldr + gn, r);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += r[e];
+              st8(reinterpret_cast<bf16_t*>(C), (size_t)gm * p.ldc + gn, v);
+            }
+          }
+        }
+      }
+    }
+    if (!staged && p.accumulate && !R) {
+      // C += alpha * acc: the old values of two tile rows are all requested before the first of them is used
+#pragma unroll
+      for (int i2 = 0; i2 < TM / 2; ++i2) {
+        float old[2][TN][4];
+#pragma unroll
+        for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int gm = wm0 + 16 * (2 * i2 + ih) + 4 * lg + q;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              const int gn = wn0 + 16 * j + lc;
+              old[ih][j][q] = (gm < p.M && gn < p.N) ? ldf(C, (size_t)gm * p.ldc + gn) : 0.f;
+            }
+          }
+#pragma unroll
+        for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int gm = wm0 + 16 * (2 * i2 + ih) + 4 * lg + q;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              const int gn = wn0 + 16 * j + lc;
+              if (gm < p.M && gn < p.N) stf(C, (size_t)gm * p.ldc + gn, alpha * acc[2 * i2 + ih][j][q] + old[ih][j][q]);
+            }
+          }
+      }
+    } else if (!staged) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int gm = wm0 + 16 * i + 4 * lg + q;
+          if (gm >= p.M) continue;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int gn = wn0 + 16 * j + lc;
+            if (gn >= p.N) continue;
+            float v = alpha * acc[i][j][q];
+            if (R) v += ldf(R, (size_t)gm * p.ldr + gn);
+            if (p.accumulate) v += ldf(C, (size_t)gm * p.ldc + gn);
+            stf(C, (size_t)gm * p.ldc + gn, v);
+          }
+        }
+    }
+  };
+
   u32x4_t fa0[GA], fa1[GA], fb0[TN], fb1[TN];
   if constexpr (BK == 64) {
-    // ---- two stages of 64: two k32 steps of two quarters each; the barrier sits before the last quarter ----
-    issue(Int<0>{}, 0);
+    // ---- slabs of 64: THREE LDS units for A and TWO for B (5 x 32 KiB = all of the 160 KiB) ----
+    // The operand DMA of a slab has to land within one slab time when the ring is two deep on both sides, and
+    // a burst of 64 KiB per CU takes about that long to deliver: the matrix pipes then wait for it every slab.
+    // With a third unit, A is fetched one slab further ahead (two slab times to land) and only B's half of the
+    // bytes is on the one-slab clock.  Slab kt lives in A unit kt % 3 and B unit kt % 2; the barrier of a slab
+    // sits before its last quarter; B of slab kt+2 and A of slab kt+3 are issued (in that order: loads complete
+    // in order, so "all but the youngest NVA" means B has landed) into the units slab kt just vacated.
+    __shared__ __attribute__((aligned(1024))) bf16_t la0[A_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t la1[A_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t la2[A_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t lb0[B_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t lb1[B_STAGE];
+    auto ua = [&](auto U) -> bf16_t* {
+      if constexpr (decltype(U)::value == 0) return la0;
+      else if constexpr (decltype(U)::value == 1) return la1;
+      else return la2;
+    };
+    auto ub = [&](auto U) -> bf16_t* {
+      if constexpr (decltype(U)::value == 0) return lb0;
+      else return lb1;
+    };
+    typedef __attribute__((address_space(3))) bf16_t* lds_wp;
+    auto lds_addr = [](bf16_t* q) -> uint32_t { return (uint32_t)(uintptr_t)(lds_wp)q; };
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    auto desc_a = [&](int kt) {
+      int pr, k0, Kc;
+      slab(kt, pr, k0, Kc);
+      return OpA::slab_desc(pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc);
+    };
+    auto desc_b = [&](int kt) {
+      int pr, k0, Kc;
+      slab(kt, pr, k0, Kc);
+      return OpB::slab_desc(pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc);
+    };
+    auto dma_a = [&](auto I, const typename OpA::SlabDesc& d, bf16_t* unit) {
+      OpA::template chunk<decltype(I)::value>(d, lds_addr(unit), a_off, a_piece, wave_s);
+    };
+    auto dma_b = [&](auto I, const typename OpB::SlabDesc& d, bf16_t* unit) {
+      OpB::template chunk<decltype(I)::value>(d, lds_addr(unit), b_off, b_piece, wave_s);
+    };
+    auto all_a = [&](bf16_t* unit, int kt) {
+      const auto d = desc_a(kt);
+      [&]<int... I>(std::integer_sequence<int, I...>) { (dma_a(Int<I>{}, d, unit), ...); }(std::make_integer_sequence<int, NVA>{});
+    };
+    auto all_b = [&](bf16_t* unit, int kt) {
+      const auto d = desc_b(kt);
+      [&]<int... I>(std::integer_sequence<int, I...>) { (dma_b(Int<I>{}, d, unit), ...); }(std::make_integer_sequence<int, NVB>{});
+    };
+    all_a(la0, 0);
+    all_b(lb0, 0);
     TIDE_WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    frags_a(Int<0>{}, 0, Int<0>{}, fa0);
-    frags_b(Int<0>{}, 0, fb0);
-    issue(Int<1>{}, 1);
+    frags_a(la0, 0, Int<0>{}, fa0);
+    frags_b(lb0, 0, fb0);
+    all_a(la1, 1);
+    all_b(lb1, 1);
+    all_a(la2, 2);
     __builtin_amdgcn_sched_barrier(0);
-    // slab kt lives in ST (fa0 = its first A group, fb0 = its first B fragments), slab kt+1 is in flight into SO
-    auto step = [&](auto ST, auto SO, int kt) {
-      frags_a(ST, 0, Int<1>{}, fa1);
+    // One slab: A unit UA, B unit UB (fa0 / fb0 hold its first quarter's operands); the next slab's units are
+    // UAN, UBN.
+    auto step = [&](auto UA, auto UB, auto UAN, auto UBN, int kt) {
+      frags_a(ua(UA), 0, Int<1>{}, fa1);
       mma(Int<0>{}, fa0, fb0);
       sched_slots<NMF, RA, 0, 0>(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
-      frags_a(ST, 1, Int<0>{}, fa0);
-      frags_b(ST, 1, fb1);
+      frags_a(ua(UA), 1, Int<0>{}, fa0);
+      frags_b(ub(UB), 1, fb1);
       mma(Int<1>{}, fa1, fb0);
       sched_slots<NMF, RA + RB, 0, 1>(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
-      frags_a(ST, 1, Int<1>{}, fa1);
+      frags_a(ua(UA), 1, Int<1>{}, fa1);
       mma(Int<0>{}, fa0, fb1);
       sched_slots<NMF, RA, 0, 2>(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
-      // all operand reads of this wave from ST have returned; its part of slab kt+1 has landed
-      __builtin_amdgcn_s_waitcnt(0);
+      // every operand read of this wave from the slab's units has returned; its share of the next slab's B (and
+      // of everything older) has landed; only its A loads of slab kt+2 may still be in flight
+      __builtin_amdgcn_s_waitcnt((NVA & 15) | ((NVA >> 4) << 14));   // vmcnt(NVA), lgkmcnt(0), expcnt(0)
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      frags_a(SO, 0, Int<0>{}, fa0);
-      frags_b(SO, 0, fb0);
-      issue(ST, kt + 2);
-      mma(Int<1>{}, fa1, fb1);
-      __builtin_amdgcn_sched_group_barrier(0x100, RA + RB, 3);
-      sched_slots<NMF, 0, NVM, 3>(std::make_integer_sequence<int, NMF>{});
+      frags_a(ua(UAN), 0, Int<0>{}, fa0);
+      frags_b(ub(UBN), 0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      // the last quarter's MFMAs, one DMA issue after each of the first NVM of them (B's chunks first)
+      const auto db = desc_b(kt + 2);
+      const auto da = desc_a(kt + 3);
+      [&]<int... X>(std::integer_sequence<int, X...>) {
+        ([&] {
+          constexpr int i = X / TN, j = X % TN;
+          acc[GA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fa1[i]),
+                                                                   __builtin_bit_cast(bf16x8_t, fb1[j]), acc[GA + i][j], 0, 0, 0);
+          if constexpr (X < NVB) dma_b(Int<X>{}, db, ub(UB));
+          else if constexpr (X < NVM) dma_a(Int<X - NVB>{}, da, ua(UA));
+          if constexpr (X < NVM) __builtin_amdgcn_sched_barrier(0);
+        }(), ...);
+      }(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
     };
-    for (int kt = 0; kt < nk_round; kt += 2) {
-      step(Int<0>{}, Int<1>{}, kt);
-      step(Int<1>{}, Int<0>{}, kt + 1);
+    // The unit numbers repeat every six slabs.  The last round skips the slabs past nk one by one (a chain of
+    // uniform branches with the single loop exit at the bottom: early exits out of the middle made the compiler
+    // spill the accumulators).
+    for (int kt = 0; kt < nk; kt += 6) {
+      step(Int<0>{}, Int<0>{}, Int<1>{}, Int<1>{}, kt);
+      if (kt + 1 < nk) step(Int<1>{}, Int<1>{}, Int<2>{}, Int<0>{}, kt + 1);
+      if (kt + 2 < nk) step(Int<2>{}, Int<0>{}, Int<0>{}, Int<1>{}, kt + 2);
+      if (kt + 3 < nk) step(Int<0>{}, Int<1>{}, Int<1>{}, Int<0>{}, kt + 3);
+      if (kt + 4 < nk) step(Int<1>{}, Int<0>{}, Int<2>{}, Int<1>{}, kt + 4);
+      if (kt + 5 < nk) step(Int<2>{}, Int<1>{}, Int<0>{}, Int<0>{}, kt + 5);
     }
+    TIDE_WAIT_VMCNT(0);   // dummy slabs still in flight write LDS: let them land before the patches are written
+    static_assert(3 * kPatchElems <= A_STAGE, "three epilogue patches per A unit");
+    bf16_t* unit = wave < 3 ? la0 : (wave < 6 ? la1 : la2);
+    epilogue(unit + (wave % 3) * kPatchElems);
   } else {
     // ---- four stages of 32: one k32 step of two quarters per slab; the barrier sits between them ----
-    issue(Int<0>{}, 0);
-    issue(Int<1>{}, 1);
-    issue(Int<2>{}, 2);
+    constexpr int NST = 4;
+    const int nk_round = (nk + NST - 1) / NST * NST;
+    __shared__ __attribute__((aligned(1024))) bf16_t s0[A_STAGE + B_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t s1[A_STAGE + B_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t s2[A_STAGE + B_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t s3[A_STAGE + B_STAGE];
+    auto stage = [&](auto ST) -> bf16_t* {
+      if constexpr (decltype(ST)::value == 0) return s0;
+      else if constexpr (decltype(ST)::value == 1) return s1;
+      else if constexpr (decltype(ST)::value == 2) return s2;
+      else return s3;
+    };
+    auto issue = [&](bf16_t* st, int kt) { issue_a(st, kt); issue_b(st + A_STAGE, kt); };
+    issue(s0, 0);
+    issue(s1, 1);
+    issue(s2, 2);
     TIDE_WAIT_VMCNT(2 * NVM);
     __builtin_amdgcn_s_barrier();
-    frags_a(Int<0>{}, 0, Int<0>{}, fa0);
-    frags_b(Int<0>{}, 0, fb0);
+    frags_a(s0, 0, Int<0>{}, fa0);
+    frags_b(s0 + A_STAGE, 0, fb0);
     // slab kt lives in ST (fa0, fbc hold its first quarter's operands), slab kt+1 in SN, slab kt+3 goes to SP
     auto step = [&](auto ST, auto SN, auto SP, int kt, u32x4_t (&fbc)[TN], u32x4_t (&fbn)[TN]) {
-      frags_a(ST, 0, Int<1>{}, fa1);
-      issue(SP, kt + NST - 1);
+      frags_a(stage(ST), 0, Int<1>{}, fa1);
+      issue(stage(SP), kt + NST - 1);
       mma(Int<0>{}, fa0, fbc);
       sched_slots<NMF, RA, NVM, 0>(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
       TIDE_WAIT_VMCNT(2 * NVM);
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      frags_a(SN, 0, Int<0>{}, fa0);
-      frags_b(SN, 0, fbn);
+      frags_a(stage(SN), 0, Int<0>{}, fa0);
+      frags_b(stage(SN) + A_STAGE, 0, fbn);
       mma(Int<1>{}, fa1, fbc);
       sched_slots<NMF, RA + RB, 0, 1>(std::make_integer_sequence<int, NMF>{});
       __builtin_amdgcn_sched_barrier(0);
@@ -781,127 +1025,10 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
       step(Int<2>{}, Int<3>{}, Int<1>{}, kt + 2, fb0, fb1);
       step(Int<3>{}, Int<0>{}, Int<2>{}, kt + 3, fb1, fb0);
     }
-  }
-  TIDE_WAIT_VMCNT(0);
-
-  // ---- epilogue ----
-  float alpha = p.alpha;
-  if (p.alpha_dev) alpha *= *p.alpha_dev;
-  TO* C = (TO*)p.C;
-  const TO* R = (const TO*)p.R;
-  const int wm0 = m0 + wave_m * WM, wn0 = n0 + wave_n * WN;
-
-  bool staged = false;
-  if constexpr (sizeof(TO) == 2) {
-    if (!R && !p.accumulate && (p.ldc % 8) == 0 && (p.N % 8) == 0) {
-      staged = true;
-      // bf16 result through a wave-private LDS patch of 32 rows (two tile rows) x WN
-      __builtin_amdgcn_s_barrier();
-      constexpr int PP = WN + 8;
-      static_assert((NW / 2) * 32 * PP <= A_STAGE + B_STAGE, "epilogue patches of half the waves must fit in one stage");
-      bf16_t* patch = (wave < NW / 2 ? s0 : s1) + (wave % (NW / 2)) * (32 * PP);
-      constexpr int PIECES = WN / 8;
-#pragma unroll
-      for (int i2 = 0; i2 < TM / 2; ++i2) {
-#pragma unroll
-        for (int ih = 0; ih < 2; ++ih)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-              patch[(16 * ih + 4 * lg + q) * PP + 16 * j + lc] = f2bf(alpha * acc[2 * i2 + ih][j][q]);
-#pragma unroll
-        for (int t = 0; t < 32 * PIECES / 64; ++t) {
-          const int pc = lane + 64 * t;
-          const int row = pc / PIECES, piece = pc % PIECES;
-          const int gm = wm0 + 32 * i2 + row, gn = wn0 + piece * 8;
-          const u32x4_t val = *reinterpret_cast<const u32x4_t*>(patch + row * PP + piece * 8);
-          if (gm < p.M && gn < p.N)
-            *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(C) + (size_t)gm * p.ldc + gn) = val;
-        }
-      }
-    } else if constexpr ((NW / 2) * 32 * (WN + 4) * 2 <= A_STAGE + B_STAGE) {
-     if (R && !p.accumulate && (p.ldc % 8) == 0 && (p.ldr % 8) == 0 && (p.N % 8) == 0) {
-      staged = true;
-      __builtin_amdgcn_s_barrier();
-      constexpr int PF = WN + 4;
-      float* patch = reinterpret_cast<float*>(wave < NW / 2 ? s0 : s1) + (wave % (NW / 2)) * (32 * PF);
-      constexpr int PIECES = WN / 8;
-      const bf16_t* Rb = reinterpret_cast<const bf16_t*>(R);
-#pragma unroll
-      for (int i2 = 0; i2 < TM / 2; ++i2) {
-#pragma unroll
-        for (int ih = 0; ih < 2; ++ih)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-              patch[(16 * ih + 4 * lg + q) * PF + 16 * j + lc] = alpha * acc[2 * i2 + ih][j][q];
-#pragma unroll
-        for (int t = 0; t < 32 * PIECES / 64; ++t) {
-          const int pc = lane + 64 * t;
-          const int row = pc / PIECES, piece = pc % PIECES;
-          const int gm = wm0 + 32 * i2 + row, gn = wn0 + piece * 8;
-          if (gm < p.M && gn < p.N) {
-            float v[8], r[8];
-            const float4 a0 = *reinterpret_cast<const float4*>(patch + row * PF + piece * 8);
-            const float4 a1 = *reinterpret_cast<const float4*>(patch + row * PF + piece * 8 + 4);
-            v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
-            ld8(Rb, (size_t)gm * p.ldr + gn, r);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] += r[e];
-            st8(reinterpret_cast<bf16_t*>(C), (size_t)gm * p.ldc + gn, v);
-          }
-        }
-      }
-     }
-    }
-  }
-  if (!staged && p.accumulate && !R) {
-    // C += alpha * acc: the old values of two tile rows are all requested before the first of them is used
-#pragma unroll
-    for (int i2 = 0; i2 < TM / 2; ++i2) {
-      float old[2][TN][4];
-#pragma unroll
-      for (int ih = 0; ih < 2; ++ih)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int gm = wm0 + 16 * (2 * i2 + ih) + 4 * lg + q;
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int gn = wn0 + 16 * j + lc;
-            old[ih][j][q] = (gm < p.M && gn < p.N) ? ldf(C, (size_t)gm * p.ldc + gn) : 0.f;
-          }
-        }
-#pragma unroll
-      for (int ih = 0; ih < 2; ++ih)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int gm = wm0 + 16 * (2 * i2 + ih) + 4 * lg + q;
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int gn = wn0 + 16 * j + lc;
-            if (gm < p.M && gn < p.N) stf(C, (size_t)gm * p.ldc + gn, alpha * acc[2 * i2 + ih][j][q] + old[ih][j][q]);
-          }
-        }
-    }
-  } else if (!staged) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int gm = wm0 + 16 * i + 4 * lg + q;
-        if (gm >= p.M) continue;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int gn = wn0 + 16 * j + lc;
-          if (gn >= p.N) continue;
-          float v = alpha * acc[i][j][q];
-          if (R) v += ldf(R, (size_t)gm * p.ldr + gn);
-          if (p.accumulate) v += ldf(C, (size_t)gm * p.ldc + gn);
-          stf(C, (size_t)gm * p.ldc + gn, v);
-        }
-      }
+    TIDE_WAIT_VMCNT(0);
+    static_assert(2 * kPatchElems <= A_STAGE + B_STAGE, "two epilogue patches per stage");
+    bf16_t* st = wave < 2 ? s0 : (wave < 4 ? s1 : (wave < 6 ? s2 : s3));
+    epilogue(st + (wave & 1) * kPatchElems);
   }
 }
 
