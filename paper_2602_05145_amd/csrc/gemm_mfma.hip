@@ -868,27 +868,38 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
 
   u32x4_t fa0[GA], fa1[GA], fb0[TN], fb1[TN];
   if constexpr (BK == 64) {
-    // ---- slabs of 64: THREE LDS units for A and TWO for B (5 x 32 KiB = all of the 160 KiB) ----
+    // ---- slabs of 64: THREE LDS units for one operand and TWO for the other (5 x 32 KiB = all of the 160 KiB) ----
     // The operand DMA of a slab has to land within one slab time when the ring is two deep on both sides, and
     // a burst of 64 KiB per CU takes about that long to deliver: the matrix pipes then wait for it every slab.
-    // With a third unit, A is fetched one slab further ahead (two slab times to land) and only B's half of the
-    // bytes is on the one-slab clock.  Slab kt lives in A unit kt % 3 and B unit kt % 2; the barrier of a slab
-    // sits before its last quarter; B of slab kt+2 and A of slab kt+3 are issued (in that order: loads complete
-    // in order, so "all but the youngest NVA" means B has landed) into the units slab kt just vacated.
-    __shared__ __attribute__((aligned(1024))) bf16_t la0[A_STAGE];
-    __shared__ __attribute__((aligned(1024))) bf16_t la1[A_STAGE];
-    __shared__ __attribute__((aligned(1024))) bf16_t la2[A_STAGE];
-    __shared__ __attribute__((aligned(1024))) bf16_t lb0[B_STAGE];
-    __shared__ __attribute__((aligned(1024))) bf16_t lb1[B_STAGE];
-    auto ua = [&](auto U) -> bf16_t* {
-      if constexpr (decltype(U)::value == 0) return la0;
-      else if constexpr (decltype(U)::value == 1) return la1;
-      else return la2;
+    // With a third unit, the "deep" operand is fetched one slab further ahead and only the other one's half of
+    // the bytes is on the one-slab clock.  Slab kt lives in deep unit kt % 3 and shallow unit kt % 2; the barrier
+    // of a slab sits before its last quarter.  Loads complete in order, so waiting for "all but the youngest
+    // NDEEP" means everything older than the deep operand's youngest slab has landed.
+#ifndef TIDE_RING_DEEPB
+#define TIDE_RING_DEEPB 0
+#endif
+#ifndef TIDE_RING_DEEPQ
+#define TIDE_RING_DEEPQ 1
+#endif
+    constexpr bool DEEPB = TIDE_RING_DEEPB != 0;   // which operand owns the three units
+    constexpr int DEEPQ = TIDE_RING_DEEPQ;         // the quarter in which the deep operand's loads are issued (1 or 3)
+    static_assert(A_STAGE == B_STAGE, "units are interchangeable");
+    __shared__ __attribute__((aligned(1024))) bf16_t ld0[A_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t ld1[A_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t ld2[A_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t ls0[B_STAGE];
+    __shared__ __attribute__((aligned(1024))) bf16_t ls1[B_STAGE];
+    auto deep = [&](auto U) -> bf16_t* {
+      if constexpr (decltype(U)::value == 0) return ld0;
+      else if constexpr (decltype(U)::value == 1) return ld1;
+      else return ld2;
     };
-    auto ub = [&](auto U) -> bf16_t* {
-      if constexpr (decltype(U)::value == 0) return lb0;
-      else return lb1;
+    auto shal = [&](auto U) -> bf16_t* {
+      if constexpr (decltype(U)::value == 0) return ls0;
+      else return ls1;
     };
+    auto unit_a = [&](auto D, auto S) -> bf16_t* { if constexpr (DEEPB) return shal(S); else return deep(D); };
+    auto unit_b = [&](auto D, auto S) -> bf16_t* { if constexpr (DEEPB) return deep(D); else return shal(S); };
     typedef __attribute__((address_space(3))) bf16_t* lds_wp;
     auto lds_addr = [](bf16_t* q) -> uint32_t { return (uint32_t)(uintptr_t)(lds_wp)q; };
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -908,78 +919,105 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
     auto dma_b = [&](auto I, const typename OpB::SlabDesc& d, bf16_t* unit) {
       OpB::template chunk<decltype(I)::value>(d, lds_addr(unit), b_off, b_piece, wave_s);
     };
-    auto all_a = [&](bf16_t* unit, int kt) {
-      const auto d = desc_a(kt);
-      [&]<int... I>(std::integer_sequence<int, I...>) { (dma_a(Int<I>{}, d, unit), ...); }(std::make_integer_sequence<int, NVA>{});
+    constexpr int NDEEP = DEEPB ? NVB : NVA, NSHAL = DEEPB ? NVA : NVB;
+    auto desc_deep = [&](int kt) { if constexpr (DEEPB) return desc_b(kt); else return desc_a(kt); };
+    auto desc_shal = [&](int kt) { if constexpr (DEEPB) return desc_a(kt); else return desc_b(kt); };
+    auto dma_deep = [&](auto I, const auto& d, bf16_t* unit) { if constexpr (DEEPB) dma_b(I, d, unit); else dma_a(I, d, unit); };
+    auto dma_shal = [&](auto I, const auto& d, bf16_t* unit) { if constexpr (DEEPB) dma_a(I, d, unit); else dma_b(I, d, unit); };
+    auto all_deep = [&](bf16_t* unit, int kt) {
+      const auto d = desc_deep(kt);
+      [&]<int... I>(std::integer_sequence<int, I...>) { (dma_deep(Int<I>{}, d, unit), ...); }(std::make_integer_sequence<int, NDEEP>{});
     };
-    auto all_b = [&](bf16_t* unit, int kt) {
-      const auto d = desc_b(kt);
-      [&]<int... I>(std::integer_sequence<int, I...>) { (dma_b(Int<I>{}, d, unit), ...); }(std::make_integer_sequence<int, NVB>{});
+    auto all_shal = [&](bf16_t* unit, int kt) {
+      const auto d = desc_shal(kt);
+      [&]<int... I>(std::integer_sequence<int, I...>) { (dma_shal(Int<I>{}, d, unit), ...); }(std::make_integer_sequence<int, NSHAL>{});
     };
-    all_a(la0, 0);
-    all_b(lb0, 0);
-    TIDE_WAIT_VMCNT(0);
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    frags_a(la0, 0, Int<0>{}, fa0);
-    frags_b(lb0, 0, fb0);
-    all_a(la1, 1);
-    all_b(lb1, 1);
-    all_a(la2, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    // One slab: A unit UA, B unit UB (fa0 / fb0 hold its first quarter's operands); the next slab's units are
-    // UAN, UBN.
-    auto step = [&](auto UA, auto UB, auto UAN, auto UBN, int kt) {
-      frags_a(ua(UA), 0, Int<1>{}, fa1);
-      mma(Int<0>{}, fa0, fb0);
-      sched_slots<NMF, RA, 0, 0>(std::make_integer_sequence<int, NMF>{});
-      __builtin_amdgcn_sched_barrier(0);
-      frags_a(ua(UA), 1, Int<0>{}, fa0);
-      frags_b(ub(UB), 1, fb1);
-      mma(Int<1>{}, fa1, fb0);
-      sched_slots<NMF, RA + RB, 0, 1>(std::make_integer_sequence<int, NMF>{});
-      __builtin_amdgcn_sched_barrier(0);
-      frags_a(ua(UA), 1, Int<1>{}, fa1);
-      mma(Int<0>{}, fa0, fb1);
-      sched_slots<NMF, RA, 0, 2>(std::make_integer_sequence<int, NMF>{});
-      __builtin_amdgcn_sched_barrier(0);
-      // every operand read of this wave from the slab's units has returned; its share of the next slab's B (and
-      // of everything older) has landed; only its A loads of slab kt+2 may still be in flight
-      __builtin_amdgcn_s_waitcnt((NVA & 15) | ((NVA >> 4) << 14));   // vmcnt(NVA), lgkmcnt(0), expcnt(0)
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      frags_a(ua(UAN), 0, Int<0>{}, fa0);
-      frags_b(ub(UBN), 0, fb0);
-      __builtin_amdgcn_sched_barrier(0);
-      // the last quarter's MFMAs, one DMA issue after each of the first NVM of them (B's chunks first)
-      const auto db = desc_b(kt + 2);
-      const auto da = desc_a(kt + 3);
+    // one fragment of A (index F of group G) / of B (index F) of the k32 step h of a unit
+    auto frag_a = [&](const bf16_t* unit, int h, auto G, auto F, u32x4_t (&fa)[GA]) {
+      u32x4_t t[1];
+      OpA::template frags16<decltype(G)::value * GA + decltype(F)::value, 1>((lds_bf_t)unit, h, a_ro, t);
+      fa[decltype(F)::value] = t[0];
+    };
+    auto frag_b = [&](const bf16_t* unit, int h, auto F, u32x4_t (&fb)[TN]) {
+      u32x4_t t[1];
+      OpB::template frags16<decltype(F)::value, 1>((lds_bf_t)unit, h, b_ro, t);
+      fb[decltype(F)::value] = t[0];
+    };
+    // One quarter, instruction by instruction: MFMA X of A group G, then whatever `after(Int<X>)` issues (operand
+    // reads of a later quarter, DMA loads); the order is pinned.
+    auto quarter = [&](auto G, u32x4_t (&fa)[GA], u32x4_t (&fb)[TN], auto&& after) {
+      constexpr int g0 = decltype(G)::value * GA;
       [&]<int... X>(std::integer_sequence<int, X...>) {
         ([&] {
           constexpr int i = X / TN, j = X % TN;
-          acc[GA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fa1[i]),
-                                                                   __builtin_bit_cast(bf16x8_t, fb1[j]), acc[GA + i][j], 0, 0, 0);
-          if constexpr (X < NVB) dma_b(Int<X>{}, db, ub(UB));
-          else if constexpr (X < NVM) dma_a(Int<X - NVB>{}, da, ua(UA));
-          if constexpr (X < NVM) __builtin_amdgcn_sched_barrier(0);
+          acc[g0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fa[i]),
+                                                                   __builtin_bit_cast(bf16x8_t, fb[j]), acc[g0 + i][j], 0, 0, 0);
+          after(Int<X>{});
+          __builtin_amdgcn_sched_barrier(0);
         }(), ...);
       }(std::make_integer_sequence<int, NMF>{});
+    };
+
+    all_deep(ld0, 0);
+    all_shal(ls0, 0);
+    TIDE_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    frags_a(unit_a(Int<0>{}, Int<0>{}), 0, Int<0>{}, fa0);
+    frags_b(unit_b(Int<0>{}, Int<0>{}), 0, fb0);
+    all_deep(ld1, 1);
+    all_shal(ls1, 1);
+    if constexpr (DEEPQ == 3) all_deep(ld2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    // One slab: deep unit D, shallow unit S (fa0 / fb0 hold its first quarter's operands); the next slab's units
+    // are DN, SN; DP is the deep unit the slab before vacated.
+    auto step = [&](auto D, auto S, auto DN, auto SN, auto DP, int kt) {
+      const bf16_t* ua = unit_a(D, S);
+      const bf16_t* ubb = unit_b(D, S);
+      quarter(Int<0>{}, fa0, fb0, [&](auto X) {
+        if constexpr (decltype(X)::value < GA) frag_a(ua, 0, Int<1>{}, X, fa1);
+      });
+      const auto dd1 = desc_deep(kt + 2);
+      quarter(Int<1>{}, fa1, fb0, [&](auto X) {
+        constexpr int x = decltype(X)::value;
+        if constexpr (x < GA) frag_a(ua, 1, Int<0>{}, X, fa0);
+        else if constexpr (x < GA + TN) frag_b(ubb, 1, Int<x - GA>{}, fb1);
+        else if constexpr (DEEPQ == 1 && x < GA + TN + NDEEP) dma_deep(Int<x - GA - TN>{}, dd1, deep(DP));
+      });
+      quarter(Int<0>{}, fa0, fb1, [&](auto X) {
+        if constexpr (decltype(X)::value < GA) frag_a(ua, 1, Int<1>{}, X, fa1);
+      });
+      // every operand read of this wave from the slab's units has returned; its share of the next slab (and of
+      // everything older) has landed; only its youngest deep-operand loads may still be in flight
+      __builtin_amdgcn_s_waitcnt((NDEEP & 15) | ((NDEEP >> 4) << 14));   // vmcnt(NDEEP), lgkmcnt(0), expcnt(0)
+      __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
+      const bf16_t* uan = unit_a(DN, SN);
+      const bf16_t* ubn = unit_b(DN, SN);
+      const auto ds = desc_shal(kt + 2);
+      const auto dd3 = desc_deep(kt + 3);
+      quarter(Int<1>{}, fa1, fb1, [&](auto X) {
+        constexpr int x = decltype(X)::value;
+        if constexpr (x < GA) frag_a(uan, 0, Int<0>{}, X, fa0);
+        else if constexpr (x < GA + TN) frag_b(ubn, 0, Int<x - GA>{}, fb0);
+        if constexpr (x < NSHAL) dma_shal(X, ds, shal(S));
+        else if constexpr (DEEPQ == 3 && x < NSHAL + NDEEP) dma_deep(Int<x - NSHAL>{}, dd3, deep(D));
+      });
     };
     // The unit numbers repeat every six slabs.  The last round skips the slabs past nk one by one (a chain of
     // uniform branches with the single loop exit at the bottom: early exits out of the middle made the compiler
     // spill the accumulators).
     for (int kt = 0; kt < nk; kt += 6) {
-      step(Int<0>{}, Int<0>{}, Int<1>{}, Int<1>{}, kt);
-      if (kt + 1 < nk) step(Int<1>{}, Int<1>{}, Int<2>{}, Int<0>{}, kt + 1);
-      if (kt + 2 < nk) step(Int<2>{}, Int<0>{}, Int<0>{}, Int<1>{}, kt + 2);
-      if (kt + 3 < nk) step(Int<0>{}, Int<1>{}, Int<1>{}, Int<0>{}, kt + 3);
-      if (kt + 4 < nk) step(Int<1>{}, Int<0>{}, Int<2>{}, Int<1>{}, kt + 4);
-      if (kt + 5 < nk) step(Int<2>{}, Int<1>{}, Int<0>{}, Int<0>{}, kt + 5);
+      step(Int<0>{}, Int<0>{}, Int<1>{}, Int<1>{}, Int<2>{}, kt);
+      if (kt + 1 < nk) step(Int<1>{}, Int<1>{}, Int<2>{}, Int<0>{}, Int<0>{}, kt + 1);
+      if (kt + 2 < nk) step(Int<2>{}, Int<0>{}, Int<0>{}, Int<1>{}, Int<1>{}, kt + 2);
+      if (kt + 3 < nk) step(Int<0>{}, Int<1>{}, Int<1>{}, Int<0>{}, Int<2>{}, kt + 3);
+      if (kt + 4 < nk) step(Int<1>{}, Int<0>{}, Int<2>{}, Int<1>{}, Int<0>{}, kt + 4);
+      if (kt + 5 < nk) step(Int<2>{}, Int<1>{}, Int<0>{}, Int<0>{}, Int<1>{}, kt + 5);
     }
     TIDE_WAIT_VMCNT(0);   // dummy slabs still in flight write LDS: let them land before the patches are written
-    static_assert(3 * kPatchElems <= A_STAGE, "three epilogue patches per A unit");
-    bf16_t* unit = wave < 3 ? la0 : (wave < 6 ? la1 : la2);
+    static_assert(3 * kPatchElems <= A_STAGE, "three epilogue patches per unit");
+    bf16_t* unit = wave < 3 ? ld0 : (wave < 6 ? ld1 : ld2);
     epilogue(unit + (wave % 3) * kPatchElems);
   } else {
     // ---- four stages of 32: one k32 step of two quarters per slab; the barrier sits between them ----
@@ -1066,7 +1104,10 @@ bool use_big_tiles(int64_t M, int64_t N) { return ((M + 255) / 256) * ((N + 255)
 template <bool AMM, bool BNM, typename TO>
 hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
   // slab depth: 64 (two stages) as soon as one operand is K-major, else 32 (four stages)
-  constexpr int BK = (AMM && BNM) ? 32 : 64;
+#ifndef TIDE_TN_BK
+#define TIDE_TN_BK 32
+#endif
+  constexpr int BK = (AMM && BNM) ? TIDE_TN_BK : 64;
 #ifndef TIDE_BIG_TILE_MFMA32
   if (use_big_tiles(p.M, p.N)) {
     MfmaParams q = p;
