@@ -950,8 +950,8 @@ hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, con
 }
 
 // ----------------------------------------------------------------------------------------------
-// Fused multi-tensor AdamW.  One launch covers all tensors: block b works on 2048 consecutive
-// elements of the tensor its index falls in.  m, v and (bf16 mode) the master weights are fp32; the
+// Fused multi-tensor AdamW.  One launch covers all tensors: block b works on 2048 x kAdamGroups consecutive
+// elements of the tensor its index falls in (a thread owns kAdamGroups groups of 8, 2048 elements apart).  m, v and (bf16 mode) the master weights are fp32; the
 // bf16 parameters are re-rounded from the master copy.  The caller passes 1/(1-beta1^t) and
 // 1/sqrt(1-beta2^t) computed in double on the host.
 // ----------------------------------------------------------------------------------------------
@@ -962,6 +962,25 @@ struct AdamDev {
   float lr, beta1, beta2, eps, decay, inv_bc1, inv_sqrt_bc2;
 };
 
+#ifndef TIDE_ADAM_GROUPS
+#define TIDE_ADAM_GROUPS 1
+#endif
+#ifndef TIDE_ADAM_NT_STORES
+#define TIDE_ADAM_NT_STORES 0
+#endif
+constexpr int kAdamGroups = TIDE_ADAM_GROUPS;            // 8-element groups per thread, 256 * 8 elements apart
+constexpr int kAdamPerBlock = 256 * 8 * kAdamGroups;     // elements per block
+
+__device__ __forceinline__ void adam_store16(float4* p, const float4& v) {
+#if TIDE_ADAM_NT_STORES
+  typedef float f32x4_nt __attribute__((ext_vector_type(4)));
+  f32x4_nt x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<f32x4_nt*>(p));
+#else
+  *p = v;
+#endif
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void adamw_kernel(AdamDev a) {
   int ti = 0;
@@ -970,40 +989,56 @@ __global__ __launch_bounds__(256) void adamw_kernel(AdamDev a) {
   for (int i = 1; i < kMaxAdamTensors; ++i)
     if (i < a.nt && b >= a.blk_start[i]) ti = i;
   const AdamTensor t = a.t[ti];
-  const int64_t i0 = ((b - a.blk_start[ti]) * 256 + threadIdx.x) * 8;
-  if (i0 >= t.n) return;
+  const int64_t base = (b - a.blk_start[ti]) * kAdamPerBlock + threadIdx.x * 8;
+  if (base >= t.n) return;
   T* p = (T*)t.p;
   float* w = (sizeof(T) == 2) ? t.master : (float*)t.p;
   const float omb1 = 1.f - a.beta1, omb2 = 1.f - a.beta2;
-  if (i0 + 8 <= t.n) {
-    float g[8], m[8], v[8], th[8];
-    ld8(t.g, i0, g);
-    ld8((const float*)t.m, i0, m);
-    ld8((const float*)t.v, i0, v);
-    ld8((const float*)w, i0, th);
+  if (base + (kAdamGroups - 1) * 2048 + 8 <= t.n) {
+    // every load of the thread's groups is issued before the first value is used
+    float g[kAdamGroups][8], m[kAdamGroups][8], v[kAdamGroups][8], th[kAdamGroups][8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      m[j] = a.beta1 * m[j] + omb1 * g[j];
-      v[j] = a.beta2 * v[j] + omb2 * g[j] * g[j];
-      const float denom = sqrtf(v[j]) * a.inv_sqrt_bc2 + a.eps;
-      th[j] = th[j] * a.decay - a.lr * (m[j] * a.inv_bc1) / denom;
+    for (int k = 0; k < kAdamGroups; ++k) {
+      const int64_t i0 = base + k * 2048;
+      ld8(t.g, i0, g[k]);
+      ld8((const float*)t.m, i0, m[k]);
+      ld8((const float*)t.v, i0, v[k]);
+      ld8((const float*)w, i0, th[k]);
     }
-    st8(t.m, i0, m);
-    st8(t.v, i0, v);
-    st8(w, i0, th);
-    if (sizeof(T) == 2) st8(p, i0, th);
+#pragma unroll
+    for (int k = 0; k < kAdamGroups; ++k) {
+      const int64_t i0 = base + k * 2048;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        m[k][j] = a.beta1 * m[k][j] + omb1 * g[k][j];
+        v[k][j] = a.beta2 * v[k][j] + omb2 * g[k][j] * g[k][j];
+        const float denom = sqrtf(v[k][j]) * a.inv_sqrt_bc2 + a.eps;
+        th[k][j] = th[k][j] * a.decay - a.lr * (m[k][j] * a.inv_bc1) / denom;
+      }
+      float4* qm = reinterpret_cast<float4*>(t.m + i0);
+      float4* qv = reinterpret_cast<float4*>(t.v + i0);
+      float4* qw = reinterpret_cast<float4*>(w + i0);
+      adam_store16(qm, make_float4(m[k][0], m[k][1], m[k][2], m[k][3]));
+      adam_store16(qm + 1, make_float4(m[k][4], m[k][5], m[k][6], m[k][7]));
+      adam_store16(qv, make_float4(v[k][0], v[k][1], v[k][2], v[k][3]));
+      adam_store16(qv + 1, make_float4(v[k][4], v[k][5], v[k][6], v[k][7]));
+      adam_store16(qw, make_float4(th[k][0], th[k][1], th[k][2], th[k][3]));
+      adam_store16(qw + 1, make_float4(th[k][4], th[k][5], th[k][6], th[k][7]));
+      if (sizeof(T) == 2) st8(p, i0, th[k]);
+    }
   } else {
-    for (int64_t i = i0; i < t.n; ++i) {
-      const float g = t.g[i];
-      const float m = a.beta1 * t.m[i] + omb1 * g;
-      const float v = a.beta2 * t.v[i] + omb2 * g * g;
-      const float denom = sqrtf(v) * a.inv_sqrt_bc2 + a.eps;
-      const float th = w[i] * a.decay - a.lr * (m * a.inv_bc1) / denom;
-      t.m[i] = m;
-      t.v[i] = v;
-      w[i] = th;
-      if (sizeof(T) == 2) stf(p, i, th);
-    }
+    for (int k = 0; k < kAdamGroups; ++k)
+      for (int64_t i = base + k * 2048; i < min(base + k * 2048 + 8, t.n); ++i) {
+        const float g = t.g[i];
+        const float m = a.beta1 * t.m[i] + omb1 * g;
+        const float v = a.beta2 * t.v[i] + omb2 * g * g;
+        const float denom = sqrtf(v) * a.inv_sqrt_bc2 + a.eps;
+        const float th = w[i] * a.decay - a.lr * (m * a.inv_bc1) / denom;
+        t.m[i] = m;
+        t.v[i] = v;
+        w[i] = th;
+        if (sizeof(T) == 2) stf(p, i, th);
+      }
   }
 }
 
@@ -1014,7 +1049,7 @@ hipError_t launch_adamw(const AdamArgs& a, hipStream_t s) {
   for (int i = 0; i < a.nt; ++i) {
     d.t[i] = a.t[i];
     d.blk_start[i] = nb;
-    nb += (a.t[i].n + 2047) / 2048;
+    nb += (a.t[i].n + kAdamPerBlock - 1) / kAdamPerBlock;
   }
   for (int i = a.nt; i < kMaxAdamTensors; ++i) d.t[i] = AdamTensor{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
   for (int i = a.nt; i <= kMaxAdamTensors; ++i) d.blk_start[i] = nb;
