@@ -42,7 +42,8 @@
  *   - HIP graphs: the forward-only calls (tide_draft_forward, _eval, _forward_packed, _forward_tok, _eval_unroll, _eval_unroll_packed) enqueue
  *     kernels and nothing else, so they can be captured on `stream` and replayed (call once before the capture:
  *     the first call on a device sets function attributes).  A training step bakes adam_state->step (bias
- *     corrections) and lr into its launch: a captured step would replay with the captured values.
+ *     corrections) and lr into its launch: a captured step would replay with the captured values;
+ *     tide_draft_train_step_dev keeps both in device memory and can be captured and replayed.
  *   - Return value: 0 on success, a negative TIDE_ERR_* code otherwise, with
  *     tide_last_error() describing the problem.  Arguments are validated before
  *     any work is enqueued: on TIDE_ERR_NULL / _CONFIG / _WORKSPACE nothing has
@@ -192,6 +193,21 @@ int tide_draft_train_step(const tide_draft_config *cfg, tide_draft_tensors *para
                           const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
                           float lr, float *loss_out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* The same step with its schedule in DEVICE memory, for callers that capture the step into a HIP graph and replay
+ * it (Sec. 3.3 runs many such steps back to back on the accumulated signals): tide_draft_train_step bakes lr and the
+ * bias corrections of step adam_state->step + 1 into its launch, so a replay would repeat them; here
+ *   lr_dev    DEVICE float: learning rate, read when the enqueued work runs (the caller may change it between replays)
+ *   step_dev  DEVICE int64: number of updates applied so far; read for the bias corrections and incremented on the
+ *             device by every execution of the enqueued work
+ * and adam_state->step (host) is neither read nor changed.  The call enqueues kernels only (no memset, no copy, no
+ * allocation, no host synchronisation); call any entry point once on the device before capturing (the first call
+ * sets one-time function attributes).  Everything else as in tide_draft_train_step. */
+int tide_draft_train_step_dev(const tide_draft_config *cfg, tide_draft_tensors *params,
+                              tide_draft_tensors *grads, tide_adam_state *adam_state,
+                              const void *hidden_buf, const int32_t *tokens, const uint8_t *loss_mask,
+                              const float *lr_dev, int64_t *step_dev, float *loss_out,
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 /* Token-input variant.  Sec. 3.2 names EAGLE-3 as the draft architecture; that architecture joins the
  * projected features with the embedding of the token sampled at the position: both vectors are

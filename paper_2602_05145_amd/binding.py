@@ -77,6 +77,8 @@ _lib.tide_draft_forward_packed.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _i32,
 _lib.tide_draft_train_step_packed.restype = _i32
 _lib.tide_draft_train_step_packed.argtypes = [_cfgp, _tp, _tp, _ap, _vp, _vp, _vp, _vp, _i32, _i32,
                                               C.c_float, _vp, _vp, _sz, _vp]
+_lib.tide_draft_train_step_dev.restype = _i32
+_lib.tide_draft_train_step_dev.argtypes = [_cfgp, _tp, _tp, _ap, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.tide_draft_eval.restype = _i32
 _lib.tide_draft_eval.argtypes = [_cfgp, _tp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.tide_draft_train_step.restype = _i32
@@ -124,7 +126,7 @@ _lib.tide_profile_stop.restype = _i32
 _lib.tide_profile_stop.argtypes = [C.c_char_p, _sz]
 
 EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspace_offset",
-            "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_draft_forward_packed",
+            "tide_draft_forward", "tide_draft_eval", "tide_draft_train_step", "tide_draft_train_step_dev", "tide_draft_forward_packed",
     "tide_draft_train_step_packed", "tide_draft_forward_tok", "tide_draft_train_step_tok",
     "tide_draft_unroll_workspace_bytes", "tide_draft_unroll_workspace_offset", "tide_draft_eval_unroll", "tide_draft_train_step_unroll",
     "tide_draft_eval_unroll_packed", "tide_draft_train_step_unroll_packed",
@@ -198,6 +200,17 @@ def tide_draft_forward_tok(cfg, params, tok, hidden_buf, tokens, loss_mask, loss
                                      C.byref(tok) if tok is not None else None,
                                      _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(loss_out),
                                      _ptr(top1_out), _ptr(workspace), int(workspace_bytes), stream)
+    return _check(rc) if check else rc
+
+
+def tide_draft_train_step_dev(cfg, params, grads, adam_state, hidden_buf, tokens, loss_mask, lr_dev, step_dev, loss_out,
+                              workspace, workspace_bytes, stream, check=True):
+    rc = _lib.tide_draft_train_step_dev(C.byref(cfg) if cfg is not None else None,
+                                        C.byref(params) if params is not None else None,
+                                        C.byref(grads) if grads is not None else None,
+                                        C.byref(adam_state) if adam_state is not None else None,
+                                        _ptr(hidden_buf), _ptr(tokens), _ptr(loss_mask), _ptr(lr_dev), _ptr(step_dev),
+                                        _ptr(loss_out), _ptr(workspace), int(workspace_bytes), stream)
     return _check(rc) if check else rc
 
 

@@ -960,7 +960,27 @@ struct AdamDev {
   int64_t blk_start[kMaxAdamTensors + 1];
   int nt;
   float lr, beta1, beta2, eps, decay, inv_bc1, inv_sqrt_bc2;
+  const float* dyn;   // optional device {lr, decay, inv_bc1, inv_sqrt_bc2}
 };
+
+// The step-dependent scalars of AdamW computed on the device from a device-resident learning rate and step
+// count, so that a captured training step replays with the values of the replay, not of the capture.
+__global__ void adam_schedule_kernel(const float* __restrict__ lr_dev, int64_t* __restrict__ step_dev, float beta1,
+                                     float beta2, float wd, float* __restrict__ dyn) {
+  const long long t = (long long)(*step_dev + 1);
+  const float lr = *lr_dev;
+  dyn[0] = lr;
+  dyn[1] = __fsub_rn(1.0f, __fmul_rn(lr, wd));   // two roundings, as the host computes it (no fused multiply-add)
+  dyn[2] = (float)(1.0 / (1.0 - pow_int((double)beta1, t)));
+  dyn[3] = (float)(1.0 / sqrt(1.0 - pow_int((double)beta2, t)));
+  *step_dev += 1;
+}
+
+hipError_t launch_adam_schedule(const float* lr_dev, int64_t* step_dev, float beta1, float beta2, float wd, float* dyn,
+                                hipStream_t s) {
+  hipLaunchKernelGGL(adam_schedule_kernel, dim3(1), dim3(1), 0, s, lr_dev, step_dev, beta1, beta2, wd, dyn);
+  return hipGetLastError();
+}
 
 #ifndef TIDE_ADAM_GROUPS
 #define TIDE_ADAM_GROUPS 1
@@ -994,6 +1014,9 @@ __global__ __launch_bounds__(256) void adamw_kernel(AdamDev a) {
   T* p = (T*)t.p;
   float* w = (sizeof(T) == 2) ? t.master : (float*)t.p;
   const float omb1 = 1.f - a.beta1, omb2 = 1.f - a.beta2;
+  // (locals: writing into the by-value argument would move the whole struct to scratch memory)
+  const float lr = a.dyn ? a.dyn[0] : a.lr, decay = a.dyn ? a.dyn[1] : a.decay;
+  const float inv_bc1 = a.dyn ? a.dyn[2] : a.inv_bc1, inv_sqrt_bc2 = a.dyn ? a.dyn[3] : a.inv_sqrt_bc2;
   if (base + (kAdamGroups - 1) * 2048 + 8 <= t.n) {
     // every load of the thread's groups is issued before the first value is used
     float g[kAdamGroups][8], m[kAdamGroups][8], v[kAdamGroups][8], th[kAdamGroups][8];
@@ -1012,8 +1035,8 @@ __global__ __launch_bounds__(256) void adamw_kernel(AdamDev a) {
       for (int j = 0; j < 8; ++j) {
         m[k][j] = a.beta1 * m[k][j] + omb1 * g[k][j];
         v[k][j] = a.beta2 * v[k][j] + omb2 * g[k][j] * g[k][j];
-        const float denom = sqrtf(v[k][j]) * a.inv_sqrt_bc2 + a.eps;
-        th[k][j] = th[k][j] * a.decay - a.lr * (m[k][j] * a.inv_bc1) / denom;
+        const float denom = sqrtf(v[k][j]) * inv_sqrt_bc2 + a.eps;
+        th[k][j] = th[k][j] * decay - lr * (m[k][j] * inv_bc1) / denom;
       }
       float4* qm = reinterpret_cast<float4*>(t.m + i0);
       float4* qv = reinterpret_cast<float4*>(t.v + i0);
@@ -1032,8 +1055,8 @@ __global__ __launch_bounds__(256) void adamw_kernel(AdamDev a) {
         const float g = t.g[i];
         const float m = a.beta1 * t.m[i] + omb1 * g;
         const float v = a.beta2 * t.v[i] + omb2 * g * g;
-        const float denom = sqrtf(v) * a.inv_sqrt_bc2 + a.eps;
-        const float th = w[i] * a.decay - a.lr * (m * a.inv_bc1) / denom;
+        const float denom = sqrtf(v) * inv_sqrt_bc2 + a.eps;
+        const float th = w[i] * decay - lr * (m * inv_bc1) / denom;
         t.m[i] = m;
         t.v[i] = v;
         w[i] = th;
@@ -1056,6 +1079,7 @@ hipError_t launch_adamw(const AdamArgs& a, hipStream_t s) {
   d.lr = a.lr; d.beta1 = a.beta1; d.beta2 = a.beta2; d.eps = a.eps;
   d.decay = 1.0f - a.lr * a.wd;
   d.inv_bc1 = a.inv_bc1; d.inv_sqrt_bc2 = a.inv_sqrt_bc2;
+  d.dyn = a.dyn;
   if (nb <= 0) return hipSuccess;
   double np_ = 0;
   for (int i = 0; i < a.nt; ++i) np_ += (double)a.t[i].n;

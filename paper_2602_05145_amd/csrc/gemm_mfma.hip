@@ -636,7 +636,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
 // read per lane, like a 32-row x 16-k one).  A wave owns 8 x 4 tiles of 16 x 16 (128 x 64); a "quarter" of the
 // schedule is one k32 step of four of its A fragments against its four B fragments: 16 MFMAs (256 clocks, as the
 // 8 MFMAs of a k16 quarter above), with the A fragments double-buffered per quarter and the B fragments per k32
-// step.  Accumulator element q of lane l in tile (i, j) is row 16 i + 4 (l >> 4) + q, column 16 j + (l & 15).
+// step.  The MFMAs take the B fragment first, so accumulator element q of lane l in tile (i, j) is row
+// 16 i + (l & 15), column 16 j + 4 (l >> 4) + q (see the epilogue).
 // ------------------------------------------------------------------------------------------------
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
@@ -741,11 +742,15 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
     for (int i = 0; i < GA; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[g0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fa[i]),
-                                                                 __builtin_bit_cast(bf16x8_t, fb[j]), acc[g0 + i][j], 0, 0, 0);
+        acc[g0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fb[j]),
+                                                                 __builtin_bit_cast(bf16x8_t, fa[i]), acc[g0 + i][j], 0, 0, 0);
   };
 
   // ---- epilogue: needs, per wave, an LDS patch of 32 x (WN + 4) floats that no DMA is writing any more ----
+  // The MFMAs are issued with their operands swapped (B fragment first), so an accumulator tile holds the
+  // TRANSPOSE of its 16 x 16 block: element q of lane l in tile (i, j) is row m = 16 i + (l & 15), columns
+  // n = 16 j + 4 (l >> 4) + q.  A lane thus owns four CONSECUTIVE columns of one row: 16 bytes of an fp32 result
+  // (one store instead of four), 8 bytes of a bf16 one (one LDS write per tile into the staging patch).
   constexpr int kPatchElems = 32 * (WN + 4) * 2;   // in bf16 elements
   auto epilogue = [&](bf16_t* patch_mem) {
     float alpha = p.alpha;
@@ -769,10 +774,11 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
 #pragma unroll
           for (int ih = 0; ih < 2; ++ih)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-              for (int q = 0; q < 4; ++q)
-                patch[(16 * ih + 4 * lg + q) * PP + 16 * j + lc] = f2bf(alpha * acc[2 * i2 + ih][j][q]);
+            for (int j = 0; j < TN; ++j) {
+              const f32x4_t v = acc[2 * i2 + ih][j];
+              *reinterpret_cast<uint2*>(patch + (16 * ih + lc) * PP + 16 * j + 4 * lg) =
+                  make_uint2(f2bf2(alpha * v[0], alpha * v[1]), f2bf2(alpha * v[2], alpha * v[3]));
+            }
 #pragma unroll
           for (int t = 0; t < 32 * PIECES / 64; ++t) {
             const int pc = lane + 64 * t;
@@ -795,10 +801,11 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
 #pragma unroll
           for (int ih = 0; ih < 2; ++ih)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-              for (int q = 0; q < 4; ++q)
-                patch[(16 * ih + 4 * lg + q) * PF + 16 * j + lc] = alpha * acc[2 * i2 + ih][j][q];
+            for (int j = 0; j < TN; ++j) {
+              const f32x4_t v = acc[2 * i2 + ih][j];
+              *reinterpret_cast<float4*>(patch + (16 * ih + lc) * PF + 16 * j + 4 * lg) =
+                  make_float4(alpha * v[0], alpha * v[1], alpha * v[2], alpha * v[3]);
+            }
 #pragma unroll
           for (int t = 0; t < 32 * PIECES / 64; ++t) {
             const int pc = lane + 64 * t;
@@ -818,50 +825,54 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
         }
       }
     }
-    if (!staged && p.accumulate && !R) {
-      // C += alpha * acc: the old values of two tile rows are all requested before the first of them is used
+    if (staged) return;
+    if constexpr (sizeof(TO) == 4) {
+      if (!R && (p.ldc % 4) == 0 && (p.N % 4) == 0 && (((uintptr_t)C) & 15) == 0) {
+        // fp32 result: a lane's four columns are one 16-byte access.  With accumulate, the old values of two tile
+        // rows are all requested before the first of them is used.
+        float* Cf = reinterpret_cast<float*>(C);
 #pragma unroll
-      for (int i2 = 0; i2 < TM / 2; ++i2) {
-        float old[2][TN][4];
+        for (int i2 = 0; i2 < TM / 2; ++i2) {
+          float4 old[2][TN];
+          if (p.accumulate) {
 #pragma unroll
-        for (int ih = 0; ih < 2; ++ih)
+            for (int ih = 0; ih < 2; ++ih)
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int gm = wm0 + 16 * (2 * i2 + ih) + 4 * lg + q;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-              const int gn = wn0 + 16 * j + lc;
-              old[ih][j][q] = (gm < p.M && gn < p.N) ? ldf(C, (size_t)gm * p.ldc + gn) : 0.f;
-            }
+              for (int j = 0; j < TN; ++j) {
+                const int gm = wm0 + 16 * (2 * i2 + ih) + lc, gn = wn0 + 16 * j + 4 * lg;
+                old[ih][j] = (gm < p.M && gn < p.N) ? *reinterpret_cast<const float4*>(Cf + (size_t)gm * p.ldc + gn)
+                                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+              }
           }
 #pragma unroll
-        for (int ih = 0; ih < 2; ++ih)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int gm = wm0 + 16 * (2 * i2 + ih) + 4 * lg + q;
+          for (int ih = 0; ih < 2; ++ih)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-              const int gn = wn0 + 16 * j + lc;
-              if (gm < p.M && gn < p.N) stf(C, (size_t)gm * p.ldc + gn, alpha * acc[2 * i2 + ih][j][q] + old[ih][j][q]);
+              const int gm = wm0 + 16 * (2 * i2 + ih) + lc, gn = wn0 + 16 * j + 4 * lg;
+              const f32x4_t v = acc[2 * i2 + ih][j];
+              float4 o = make_float4(alpha * v[0], alpha * v[1], alpha * v[2], alpha * v[3]);
+              if (p.accumulate) { o.x += old[ih][j].x; o.y += old[ih][j].y; o.z += old[ih][j].z; o.w += old[ih][j].w; }
+              if (gm < p.M && gn < p.N) *reinterpret_cast<float4*>(Cf + (size_t)gm * p.ldc + gn) = o;
             }
-          }
+        }
+        return;
       }
-    } else if (!staged) {
+    }
+    // everything else, element by element
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      const int gm = wm0 + 16 * i + lc;
+      if (gm >= p.M) continue;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int gm = wm0 + 16 * i + 4 * lg + q;
-          if (gm >= p.M) continue;
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int gn = wn0 + 16 * j + lc;
-            if (gn >= p.N) continue;
-            float v = alpha * acc[i][j][q];
-            if (R) v += ldf(R, (size_t)gm * p.ldr + gn);
-            if (p.accumulate) v += ldf(C, (size_t)gm * p.ldc + gn);
-            stf(C, (size_t)gm * p.ldc + gn, v);
-          }
+          const int gn = wn0 + 16 * j + 4 * lg + q;
+          if (gn >= p.N) continue;
+          float v = alpha * acc[i][j][q];
+          if (R) v += ldf(R, (size_t)gm * p.ldr + gn);
+          if (p.accumulate) v += ldf(C, (size_t)gm * p.ldc + gn);
+          stf(C, (size_t)gm * p.ldc + gn, v);
         }
     }
   };
@@ -950,8 +961,8 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
       [&]<int... X>(std::integer_sequence<int, X...>) {
         ([&] {
           constexpr int i = X / TN, j = X % TN;
-          acc[g0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fa[i]),
-                                                                   __builtin_bit_cast(bf16x8_t, fb[j]), acc[g0 + i][j], 0, 0, 0);
+          acc[g0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fb[j]),
+                                                                   __builtin_bit_cast(bf16x8_t, fa[i]), acc[g0 + i][j], 0, 0, 0);
           after(Int<X>{});
           __builtin_amdgcn_sched_barrier(0);
         }(), ...);

@@ -99,6 +99,18 @@ hipError_t launch_ce_train(int64_t rows, int V, void* z, int64_t ldz, const int3
 hipError_t launch_loss_reduce(const float* loss_rows, const float* hit_rows, const int* cnt, const float* scal,
                               float* loss_out, float* acc_out, int* status, hipStream_t s);
 
+// b^t for an integer t >= 0 by repeated squaring, in IEEE double multiplications only: the host and the device
+// get the same bits (the bias corrections of AdamW are computed on either side).
+__host__ __device__ inline double pow_int(double b, long long t) {
+  double r = 1.0;
+  while (t > 0) {
+    if (t & 1) r *= b;
+    b *= b;
+    t >>= 1;
+  }
+  return r;
+}
+
 struct AdamTensor { void* p; const float* g; float* m; float* v; float* master; int64_t n; };
 constexpr int kMaxAdamTensors = 11;   // the ten tensors of the draft and W_in of the token-input variant
 struct AdamArgs {
@@ -106,8 +118,14 @@ struct AdamArgs {
   int nt;
   float lr, beta1, beta2, eps, wd, inv_bc1, inv_sqrt_bc2;
   int dtype;
+  // optional (device): {lr, 1 - lr * wd, 1 / (1 - beta1^t), 1 / sqrt(1 - beta2^t)} written by launch_adam_schedule;
+  // when set, the kernel takes these four from device memory instead of the host values above
+  const float* dyn;
 };
 hipError_t launch_adamw(const AdamArgs& a, hipStream_t s);
+// t = *step_dev + 1; dyn[0..3] = {*lr_dev, 1 - *lr_dev * wd, 1 / (1 - beta1^t), 1 / sqrt(1 - beta2^t)}; *step_dev = t
+hipError_t launch_adam_schedule(const float* lr_dev, int64_t* step_dev, float beta1, float beta2, float wd, float* dyn,
+                                hipStream_t s);
 
 // ---- attention_simple.hip / attention_mfma.hip ----------------------------------------------
 // bits of the device status word of a step (written by plan_rows, OR-ed by loss_reduce)

@@ -71,7 +71,7 @@ struct Plan {
   int64_t T, KH, d, nq, nk, nqkv, F, V, ldz, lm_rows, z_rows;
   size_t es;  // activation element size
   // offsets (bytes)
-  size_t scal, cnt, status, plan_cnt, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, rope_cs, x0, r1, a, qkv, attn_lse, A, A_c, x0_c, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
+  size_t scal, adam_dyn, cnt, status, plan_cnt, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, rope_cs, x0, r1, a, qkv, attn_lse, A, A_c, x0_c, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
   size_t fwd_end;
   size_t dyhat, dx2, dx1_c, dx1, dx0, dh, dbn, dA_c, dA, dqkv, da, delta, dg_partial;
   size_t g0, e0, dg0;   // token-input variant: projected features, looked-up embeddings, gradient of the features
@@ -116,6 +116,7 @@ Plan make_plan(const tide_draft_config* c) {
   const size_t T = (size_t)p.T, es = p.es;
   Bump b;
   p.scal = b.take(64);
+  p.adam_dyn = b.take(64);
   p.cnt = b.take(64);
   p.status = b.take(64);
   p.plan_cnt = b.take(plan_rows_scratch_bytes(p.T));
@@ -670,8 +671,13 @@ static int enqueue_backward(const tide_draft_config* cfg, const tide_draft_tenso
 }
 
 // AdamW over all tensors in one launch
+// Device-resident schedule of a training step (the graph-capturable form): learning rate and step count live in
+// device memory, are read by the kernels of the launch, and the count is advanced on the device.
+struct DevSchedule { const float* lr; int64_t* step; float* dyn; };
+
 static int enqueue_adamw(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* G, tide_adam_state* st,
-                         const tide_token_input* tok, float lr, const Plan& p, hipStream_t s) {
+                         const tide_token_input* tok, float lr, const Plan& p, hipStream_t s,
+                         const DevSchedule* dev = nullptr) {
   const int dt = cfg->dtype;
   AdamArgs a;
   std::memset(&a, 0, sizeof(a));
@@ -688,11 +694,18 @@ static int enqueue_adamw(const tide_draft_config* cfg, tide_draft_tensors* param
                          dt == TIDE_DTYPE_BF16 ? (float*)tok->master_w_in : nullptr, 2 * p.d * p.d};
     a.nt = 11;
   }
-  const double t = (double)(st->step + 1);
-  a.lr = lr; a.beta1 = cfg->beta1; a.beta2 = cfg->beta2; a.eps = cfg->adam_eps; a.wd = cfg->weight_decay;
-  a.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta1, t)));
-  a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)cfg->beta2, t)));
+  a.beta1 = cfg->beta1; a.beta2 = cfg->beta2; a.eps = cfg->adam_eps; a.wd = cfg->weight_decay;
   a.dtype = dt;
+  if (dev) {
+    TIDE_HIP(launch_adam_schedule(dev->lr, dev->step, cfg->beta1, cfg->beta2, cfg->weight_decay, dev->dyn, s), "adam schedule");
+    a.dyn = dev->dyn;
+    TIDE_HIP(launch_adamw(a, s), "adamw");
+    return TIDE_OK;
+  }
+  const long long t = (long long)(st->step + 1);
+  a.lr = lr;
+  a.inv_bc1 = (float)(1.0 / (1.0 - pow_int((double)cfg->beta1, t)));
+  a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - pow_int((double)cfg->beta2, t)));
   TIDE_HIP(launch_adamw(a, s), "adamw");
   st->step += 1;
   return TIDE_OK;
@@ -711,7 +724,7 @@ static int check_train_args(const tide_draft_config* cfg, tide_draft_tensors* gr
 static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
                       tide_adam_state* st, const tide_token_input* tok, const void* hidden_buf, const int32_t* tokens,
                       const uint8_t* loss_mask, const Seqs* packed, float lr, float* loss_out, void* workspace,
-                      size_t workspace_bytes, void* stream) {
+                      size_t workspace_bytes, void* stream, const float* lr_dev = nullptr, int64_t* step_dev = nullptr) {
   const Plan p = make_plan(cfg);
   const Seqs q = packed ? *packed : fixed_seqs(cfg);
   int rc = check_common(cfg, params, hidden_buf, tokens, loss_mask, loss_out, workspace, workspace_bytes, p);
@@ -726,6 +739,10 @@ static int train_impl(const tide_draft_config* cfg, tide_draft_tensors* params, 
   if (rc) return rc;
   rc = enqueue_backward(cfg, params, grads, tok, hidden_buf, q, ws, p, s, BwdOpts{});
   if (rc) return rc;
+  if (lr_dev) {
+    const DevSchedule dev{lr_dev, step_dev, (float*)(ws + p.adam_dyn)};
+    return enqueue_adamw(cfg, params, grads, st, tok, 0.f, p, s, &dev);
+  }
   return enqueue_adamw(cfg, params, grads, st, tok, lr, p, s);
 }
 
@@ -843,6 +860,15 @@ int tide_draft_train_step(const tide_draft_config* cfg, tide_draft_tensors* para
                           size_t workspace_bytes, void* stream) {
   if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
   return train_impl(cfg, params, grads, st, nullptr, hidden_buf, tokens, loss_mask, nullptr, lr, loss_out, workspace, workspace_bytes, stream);
+}
+
+int tide_draft_train_step_dev(const tide_draft_config* cfg, tide_draft_tensors* params, tide_draft_tensors* grads,
+                              tide_adam_state* st, const void* hidden_buf, const int32_t* tokens,
+                              const uint8_t* loss_mask, const float* lr_dev, int64_t* step_dev, float* loss_out,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_config(cfg)) return cfg ? TIDE_ERR_CONFIG : TIDE_ERR_NULL;
+  if (!lr_dev || !step_dev) return fail(TIDE_ERR_NULL, "lr_dev and step_dev must not be NULL");
+  return train_impl(cfg, params, grads, st, nullptr, hidden_buf, tokens, loss_mask, nullptr, 0.f, loss_out, workspace, workspace_bytes, stream, lr_dev, step_dev);
 }
 
 int tide_draft_forward_tok(const tide_draft_config* cfg, const tide_draft_tensors* params, const tide_token_input* tok,

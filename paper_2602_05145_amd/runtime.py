@@ -169,6 +169,13 @@ class DraftTrainer:
                                 self.mask, lr, self.loss, self.workspace, self.ws_bytes, self._stream())
         return self.loss
 
+    def train_step_dev(self, lr_dev, step_dev):
+        """The training step with its learning rate (device float) and step count (device int64) in device memory:
+        capturable into a HIP graph; the count is advanced on the device."""
+        B.tide_draft_train_step_dev(self.ccfg, self.c_params, self.c_grads, self.c_adam, self.hidden, self.tokens,
+                                    self.mask, lr_dev, step_dev, self.loss, self.workspace, self.ws_bytes, self._stream())
+        return self.loss
+
     def status(self):
         """Device status word of the last call (0 = fine, 1 = loss not finite, 2 = malformed cu_seqlens); synchronises."""
         off = B.tide_draft_workspace_offset(self.ccfg, "status")

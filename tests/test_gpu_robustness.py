@@ -252,6 +252,64 @@ def test_forward_and_eval_replay_from_a_hip_graph():
         assert tr.status() == 0
 
 
+def test_train_step_with_a_device_schedule_replays_from_a_hip_graph():
+    """tide_draft_train_step_dev keeps the learning rate and the step count in device memory, so the whole training
+    step (forward, backward, AdamW with its bias corrections) can be captured once and replayed: four replays on
+    four different batches, with a learning-rate change and eager work in between, must leave bit-identical
+    parameters, moments and losses to four eager tide_draft_train_step calls, and the device count must read 4."""
+    from paper_2602_05145_amd import runtime
+    cfg = W.get_config("small", batch=2, seq=160, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128,
+                       ffn=264, vocab=1000)
+    wl = W.make_workload(cfg)
+    tr = runtime.trainer_from_workload(cfg, wl)
+    eager = runtime.trainer_from_workload(cfg, wl)
+    tr.forward()                                           # warm-up: one-time function attributes, outside the capture
+    sync()
+    lr_dev = torch.full((1,), 1e-3, dtype=torch.float32, device=tr.device)
+    step_dev = torch.zeros(1, dtype=torch.int64, device=tr.device)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            tr.train_step_dev(lr_dev, step_dev)
+    torch.cuda.current_stream().wait_stream(side)
+    sync()
+    assert int(step_dev.item()) == 0 and tr.step == 0      # capturing runs nothing
+    lrs = [1e-3, 1e-3, 4e-4, 2e-3]
+    for i, lr in enumerate(lrs):
+        wl_i = W.make_workload(cfg, seed=700 + i)
+        for t in (tr, eager):
+            t.hidden.copy_(torch.from_numpy(wl_i["hidden"]).to(t.device).to(t.hidden.dtype))
+            t.tokens.copy_(torch.from_numpy(wl_i["tokens"]).to(t.device))
+            t.mask.copy_(torch.from_numpy(wl_i["mask"]).to(t.device))
+        lr_dev.fill_(lr)
+        tr.loss.fill_(-1.0)
+        sync()
+        graph.replay()
+        sync()
+        eager.train_step(lr)
+        sync()
+        assert float(tr.loss.item()) == float(eager.loss.item()), i
+        assert int(step_dev.item()) == i + 1
+        for k in tr.params:
+            assert torch.equal(tr.params[k], eager.params[k]), (i, k)
+            assert torch.equal(tr.m[k], eager.m[k]) and torch.equal(tr.v[k], eager.v[k]), (i, k)
+            assert torch.equal(tr.master[k], eager.master[k]), (i, k)
+    assert tr.step == 0 and eager.step == 4
+    # eager calls of the device-schedule entry point continue the same sequence
+    tr.train_step_dev(lr_dev, step_dev)
+    eager.train_step(lrs[-1])
+    sync()
+    assert int(step_dev.item()) == 5
+    for k in tr.params:
+        assert torch.equal(tr.params[k], eager.params[k]), k
+    from paper_2602_05145_amd import binding as B
+    rc = B.tide_draft_train_step_dev(tr.ccfg, tr.c_params, tr.c_grads, tr.c_adam, tr.hidden, tr.tokens, tr.mask, None, step_dev,
+                                     tr.loss, tr.workspace, tr.ws_bytes, torch.cuda.current_stream().cuda_stream, check=False)
+    assert rc == B.TIDE_ERR_NULL
+
+
 def test_eval_unroll_replays_from_a_hip_graph():
     """The evaluation unroll too enqueues kernels and nothing else: captured once, replayed on new inputs written
     into the captured buffers, every replay must match an eager call bit for bit."""
