@@ -348,9 +348,14 @@ int64_t tide_draft_workspace_offset(const tide_draft_config *cfg, const char *na
  *   layout 2 ("TN"): C = A[K,M]^T * B[K,N]
  * in_dtype: dtype of A and B; out_dtype: dtype of C (TIDE_DTYPE_*).  accumulate
  * != 0 adds to C instead of overwriting.  residual (may be NULL) is a [M,N]
- * matrix of out_dtype added to the result.  workspace may be NULL when
- * tide_gemm_workspace_bytes returns 0 for the call. */
-size_t tide_gemm_workspace_bytes(int layout, int64_t M, int64_t N, int64_t K, int in_dtype);
+ * matrix of out_dtype added to the result.
+ * workspace (DEVICE, 16-byte aligned, optional): scratch for the split of a partly filled last round of tiles.
+ * A product whose 256 x 256 tiles leave the last round of the 256 compute units at most half full (and whose
+ * result is float, without residual) can have those tiles split over K; the partial sums go to the workspace
+ * and are added to C in a fixed order by a second small kernel (deterministic).  tide_gemm_workspace_bytes
+ * gives the bytes that takes (0: the call is never split; bf16 inputs are assumed); with workspace NULL or
+ * smaller than that, nothing is split and the result is the same up to the order of the fp32 additions. */
+size_t tide_gemm_workspace_bytes(int layout, int64_t M, int64_t N, int64_t K, int out_dtype);
 int tide_gemm(int layout, int64_t M, int64_t N, int64_t K, float alpha,
               const void *A, const void *B, void *C, const void *residual,
               int in_dtype, int out_dtype, int accumulate,

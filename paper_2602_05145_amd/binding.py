@@ -343,10 +343,14 @@ def tide_draft_train_step(cfg, params, grads, adam_state, hidden_buf, tokens, lo
     return _check(rc) if check else rc
 
 
+def tide_gemm_workspace_bytes(layout, M, N, K, out_dtype):
+    return int(_lib.tide_gemm_workspace_bytes(layout, M, N, K, out_dtype))
+
+
 def tide_gemm(layout, M, N, K, alpha, A, B, Cmat, residual, in_dtype, out_dtype, accumulate, stream,
-              check=True):
+              check=True, workspace=None, workspace_bytes=0):
     rc = _lib.tide_gemm(layout, M, N, K, float(alpha), _ptr(A), _ptr(B), _ptr(Cmat), _ptr(residual),
-                        in_dtype, out_dtype, int(accumulate), None, 0, stream)
+                        in_dtype, out_dtype, int(accumulate), _ptr(workspace), int(workspace_bytes), stream)
     return _check(rc) if check else rc
 
 

@@ -70,7 +70,25 @@ struct MfmaParams {
   int tiles_m, tiles_n;
   const int* m_dev; int m_off;   // optional device-side M: effective M = clamp(*m_dev - m_off, 0, M)
   const int* k_dev; int k_off;   // optional device-side K (pair 0 only)
+  // Split of the last, partly filled round of tiles over K (fp32 results only): tiles [0, split_full) are whole;
+  // each later tile is worked on by split_s blocks, each over 1/split_s of the slabs; part 0 writes C, part
+  // j > 0 writes its 256 x 256 partial sum to split_scratch[(j - 1) * (tiles - split_full) + tile - split_full],
+  // and splitk_fixup_kernel adds the partial sums to C in a fixed order afterwards.  split_s <= 1: no split.
+  int split_s, split_full;
+  float* split_scratch;
 };
+
+// tile index (XCD-contiguous order, groups of 4 tile rows) -> tile coordinates
+__device__ __forceinline__ void tile_coords(int v, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+  constexpr int GROUP = 4;
+  const int per_group = GROUP * tiles_n;
+  const int gid = v / per_group;
+  const int first_m = gid * GROUP;
+  const int gsz = min(tiles_m - first_m, GROUP);
+  const int in_g = v - gid * per_group;
+  tile_m = first_m + in_g % gsz;
+  tile_n = in_g / gsz;
+}
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
@@ -664,25 +682,33 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
 
   if (p.m_dev) p.M = max(0, min(p.M, *p.m_dev - p.m_off));
   if (p.k_dev) p.K = max(0, min(p.K, *p.k_dev - p.k_off));
-  if (p.K == 0 && p.K2 == 0 && p.accumulate) return;
+  if (p.K == 0 && p.K2 == 0 && p.accumulate && p.split_s <= 1) return;
 
   int tile_m, tile_n;
+  int part = 0, nparts = 1, tail_index = 0;   // K split of the tiles of the last round (see MfmaParams)
   {
     const int tiles_m = (p.M + BM - 1) / BM;
     const int nb = tiles_m * p.tiles_n;
-    const int pid = blockIdx.x;
-    if (pid >= nb) return;
+    const bool split = p.split_s > 1;        // (never together with a device-side M: nb is then the grid's count)
+    const int items = split ? p.split_full + (nb - p.split_full) * p.split_s : nb;
+    int pid = blockIdx.x;
+    if (pid >= items) return;
+    // Work-groups go to the XCDs round-robin in the order of their index: the whole tiles (a multiple of 256)
+    // come first and each XCD gets a contiguous range of them; the parts of the split tiles come last, again
+    // spread over all XCDs, so that they fill the last round everywhere.
+    int count = split ? p.split_full : nb, base = 0;
+    if (split && pid >= p.split_full) { base = p.split_full; pid -= base; count = items - base; }
     const int xcd = pid & 7, idx = pid >> 3;
-    const int q = nb >> 3, r = nb & 7;
-    const int v = xcd * q + min(xcd, r) + idx;
-    constexpr int GROUP = 4;
-    const int per_group = GROUP * p.tiles_n;
-    const int gid = v / per_group;
-    const int first_m = gid * GROUP;
-    const int gsz = min(tiles_m - first_m, GROUP);
-    const int in_g = v - gid * per_group;
-    tile_m = first_m + in_g % gsz;
-    tile_n = in_g / gsz;
+    const int q = count >> 3, r = count & 7;
+    int v = base + xcd * q + min(xcd, r) + idx;
+    if (split && v >= p.split_full) {
+      const int u = v - p.split_full;
+      tail_index = u / p.split_s;
+      part = u - tail_index * p.split_s;
+      nparts = p.split_s;
+      v = p.split_full + tail_index;
+    }
+    tile_coords(v, tiles_m, p.tiles_n, tile_m, tile_n);
   }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
@@ -706,15 +732,18 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
 
   const int nk1 = (p.K + BK - 1) / BK;
   const int nkp2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
-  const int nk = nk1 + nkp2;
+  // this block's slabs: all of them, or its part of a split tile (slab numbers below are relative to kt_lo)
+  const int nk_all = nk1 + nkp2;
+  const int per_part = (nk_all + nparts - 1) / nparts;
+  const int kt_lo = min(nk_all, part * per_part);
+  const int nk = min(nk_all, kt_lo + per_part) - kt_lo;
 
   // which operand pair and k offset slab kt stands for (slabs past nk are dummies: every load out of range)
   auto slab = [&](int kt, int& pr, int& k0, int& Kc) {
-    pr = 0; k0 = kt * BK; Kc = p.K;
-    if (kt >= nk1) {
-      if (kt < nk) { pr = 1; k0 = (kt - nk1) * BK; Kc = p.K2; }
-      else { k0 = p.K + BK; }
-    }
+    const int g = kt_lo + kt;
+    pr = 0; k0 = g * BK; Kc = p.K;
+    if (kt >= nk) { k0 = p.K + BK; }
+    else if (g >= nk1) { pr = 1; k0 = (g - nk1) * BK; Kc = p.K2; }
   };
   auto issue_a = [&](bf16_t* unit, int kt) {
     int pr, k0, Kc;
@@ -829,18 +858,27 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
     if constexpr (sizeof(TO) == 4) {
       if (!R && (p.ldc % 4) == 0 && (p.N % 4) == 0 && (((uintptr_t)C) & 15) == 0) {
         // fp32 result: a lane's four columns are one 16-byte access.  With accumulate, the old values of two tile
-        // rows are all requested before the first of them is used.
+        // rows are all requested before the first of them is used.  A later part of a split tile stores its
+        // partial sum to its scratch tile instead (pitch 256, tile-local coordinates, never accumulating).
         float* Cf = reinterpret_cast<float*>(C);
+        size_t pitch = (size_t)p.ldc;
+        int mo = 0, no = 0;
+        bool add = p.accumulate != 0;
+        if (part > 0) {
+          const int ntail = ((p.M + BM - 1) / BM) * p.tiles_n - p.split_full;
+          Cf = p.split_scratch + ((size_t)(part - 1) * ntail + tail_index) * (size_t)(BM * BN);
+          pitch = BN; mo = m0; no = n0; add = false;
+        }
 #pragma unroll
         for (int i2 = 0; i2 < TM / 2; ++i2) {
           float4 old[2][TN];
-          if (p.accumulate) {
+          if (add) {
 #pragma unroll
             for (int ih = 0; ih < 2; ++ih)
 #pragma unroll
               for (int j = 0; j < TN; ++j) {
                 const int gm = wm0 + 16 * (2 * i2 + ih) + lc, gn = wn0 + 16 * j + 4 * lg;
-                old[ih][j] = (gm < p.M && gn < p.N) ? *reinterpret_cast<const float4*>(Cf + (size_t)gm * p.ldc + gn)
+                old[ih][j] = (gm < p.M && gn < p.N) ? *reinterpret_cast<const float4*>(Cf + (size_t)gm * pitch + gn)
                                                     : make_float4(0.f, 0.f, 0.f, 0.f);
               }
           }
@@ -851,8 +889,8 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
               const int gm = wm0 + 16 * (2 * i2 + ih) + lc, gn = wn0 + 16 * j + 4 * lg;
               const f32x4_t v = acc[2 * i2 + ih][j];
               float4 o = make_float4(alpha * v[0], alpha * v[1], alpha * v[2], alpha * v[3]);
-              if (p.accumulate) { o.x += old[ih][j].x; o.y += old[ih][j].y; o.z += old[ih][j].z; o.w += old[ih][j].w; }
-              if (gm < p.M && gn < p.N) *reinterpret_cast<float4*>(Cf + (size_t)gm * p.ldc + gn) = o;
+              if (add) { o.x += old[ih][j].x; o.y += old[ih][j].y; o.z += old[ih][j].z; o.w += old[ih][j].w; }
+              if (gm < p.M && gn < p.N) *reinterpret_cast<float4*>(Cf + (size_t)(gm - mo) * pitch + (gn - no)) = o;
             }
         }
         return;
@@ -1081,6 +1119,57 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
   }
 }
 
+// C[tile] += the partial sums of the later parts of every split tile, in the order of the parts (deterministic).
+// One block per split tile; 256 threads, a thread adds 4 consecutive columns at a time.
+__global__ __launch_bounds__(256) void splitk_fixup_kernel(float* __restrict__ C, int ldc, int M, int N, int tiles_n,
+                                                           int split_full, int split_s, const float* __restrict__ scratch) {
+  const int tiles_m = (M + 255) / 256;
+  const int ntail = tiles_m * tiles_n - split_full;
+  int tile_m, tile_n;
+  tile_coords(split_full + blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * 256, n0 = tile_n * 256;
+  const int c4 = (threadIdx.x & 63) * 4, r0 = threadIdx.x >> 6;
+  for (int r = r0; r < 256; r += 4) {
+    const int gm = m0 + r, gn = n0 + c4;
+    if (gm >= M || gn >= N) continue;
+    float4* dst = reinterpret_cast<float4*>(C + (size_t)gm * ldc + gn);
+    float4 v = *dst;
+    for (int j = 1; j < split_s; ++j) {
+      const float4 x = *reinterpret_cast<const float4*>(scratch + ((size_t)(j - 1) * ntail + blockIdx.x) * 65536 + (size_t)r * 256 + c4);
+      v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
+    }
+    *dst = v;
+  }
+}
+
+namespace {
+// How the last round of a 256 x 256-tile launch is split over K: fp32 results without residual on tiles that do
+// not fill the last round of the 256 CUs (at most half of it: otherwise two parts per tile would not fit the round).
+struct SplitPlan { int s, full; size_t bytes; };
+SplitPlan plan_split(const GemmArgs& a) {
+  SplitPlan sp{1, 0, 0};
+#ifdef TIDE_NO_SPLITK
+  return sp;
+#endif
+  if (a.out_dtype != kF32 || a.residual || a.A2 || a.m_dev) return sp;
+  if ((a.ldc % 4) || (a.N % 4) || (((uintptr_t)a.C) & 15)) return sp;
+  const int64_t tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+  if (tiles < 200) return sp;
+  const int rem = (int)(tiles % 256);
+  if (rem == 0 || rem > 128) return sp;
+  const int64_t slabs = (a.K + 31) / 32;
+  int s = 256 / rem;
+  if (s > 8) s = 8;
+  while (s > 1 && slabs / s < 32) --s;       // a part keeps at least 32 slabs (1024 k): below that its fixed cost dominates
+  if (s <= 1) return sp;
+  sp.s = s; sp.full = (int)(tiles - rem);
+  sp.bytes = (size_t)(s - 1) * (size_t)rem * 65536 * sizeof(float);
+  return sp;
+}
+}  // namespace
+
+size_t gemm_splitk_scratch_bytes(const GemmArgs& a) { return gemm_mfma_supported(a) ? plan_split(a).bytes : 0; }
+
 bool gemm_mfma_supported(const GemmArgs& a) {
   if (a.in_dtype != kBF16) return false;
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
@@ -1124,10 +1213,13 @@ hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
     MfmaParams q = p;
     q.tiles_m = (p.M + 255) / 256;
     q.tiles_n = (p.N + 255) / 256;
-    hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK>), dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(512), 0, s, q);
+    const int tiles = q.tiles_m * q.tiles_n;
+    const int items = q.split_s > 1 ? q.split_full + (tiles - q.split_full) * q.split_s : tiles;
+    hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK>), dim3((unsigned)items), dim3(512), 0, s, q);
     return hipGetLastError();
   }
 #endif
+  if (p.split_s > 1) return hipErrorInvalidValue;   // only the 16x16x32 kernel knows the split
   if (use_big_tiles(p.M, p.N)) return launch_cfg<256, 256, 8, AMM, BNM, TO, BK>(p, s);
   return launch_cfg<128, 128, 4, AMM, BNM, TO, BK>(p, s);
 }
@@ -1154,13 +1246,24 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   p.lda = (int)a.lda; p.ldb = (int)a.ldb; p.ldc = (int)a.ldc; p.ldr = (int)a.ldr;
   p.alpha = a.alpha; p.accumulate = a.accumulate; p.tiles_m = p.tiles_n = 0;
   p.m_dev = a.m_dev; p.m_off = (int)a.m_off; p.k_dev = a.k_dev; p.k_off = (int)a.k_off;
-  const bool f32out = a.out_dtype == kF32;
-  switch (a.layout) {
-    case kNT: return f32out ? launch_layout<false, false, float>(p, s) : launch_layout<false, false, bf16_t>(p, s);
-    case kNN: return f32out ? launch_layout<false, true, float>(p, s) : launch_layout<false, true, bf16_t>(p, s);
-    case kTN: return f32out ? launch_layout<true, true, float>(p, s) : launch_layout<true, true, bf16_t>(p, s);
+  p.split_s = 1; p.split_full = 0; p.split_scratch = nullptr;
+  const SplitPlan sp = plan_split(a);
+  if (sp.s > 1 && a.scratch && a.scratch_bytes >= sp.bytes && (((uintptr_t)a.scratch) & 15) == 0) {
+    p.split_s = sp.s; p.split_full = sp.full; p.split_scratch = (float*)a.scratch;
   }
-  return hipErrorInvalidValue;
+  const bool f32out = a.out_dtype == kF32;
+  hipError_t e = hipErrorInvalidValue;
+  switch (a.layout) {
+    case kNT: e = f32out ? launch_layout<false, false, float>(p, s) : launch_layout<false, false, bf16_t>(p, s); break;
+    case kNN: e = f32out ? launch_layout<false, true, float>(p, s) : launch_layout<false, true, bf16_t>(p, s); break;
+    case kTN: e = f32out ? launch_layout<true, true, float>(p, s) : launch_layout<true, true, bf16_t>(p, s); break;
+  }
+  if (e != hipSuccess || p.split_s <= 1) return e;
+  const int tiles_n = (p.N + 255) / 256;
+  const int ntail = ((p.M + 255) / 256) * tiles_n - p.split_full;
+  hipLaunchKernelGGL(splitk_fixup_kernel, dim3((unsigned)ntail), dim3(256), 0, s, (float*)p.C, p.ldc, p.M, p.N, tiles_n,
+                     p.split_full, p.split_s, p.split_scratch);
+  return hipGetLastError();
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {

@@ -32,8 +32,13 @@ struct GemmArgs {
   // M / K above stay the upper bounds the grid is sized for; tiles past the effective size exit at once.
   const int* m_dev; int64_t m_off;
   const int* k_dev; int64_t k_off;
+  // Optional device scratch (16-byte aligned) of gemm_splitk_scratch_bytes(args) bytes: with it, a launch whose
+  // tiles leave the last round of the 256 CUs at most half full splits those tiles over K (fp32 results only;
+  // the partial sums are added in a fixed order by a second small kernel).  Without it nothing is split.
+  void* scratch; size_t scratch_bytes;
 };
 bool gemm_mfma_supported(const GemmArgs& a);
+size_t gemm_splitk_scratch_bytes(const GemmArgs& a);   // 0 when the launch would not be split
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_simple(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);  // picks the MFMA path when supported

@@ -74,6 +74,7 @@ struct Plan {
   size_t scal, adam_dyn, cnt, status, plan_cnt, kept_idx, row_pos, tokens_c, mask_c, mask_eff, seq_pos, rope_cs, x0, r1, a, qkv, attn_lse, A, A_c, x0_c, x1, r2, bn, gt, u, h, x2, r3, yhat, lse, loss_rows, hit_rows, z;
   size_t fwd_end;
   size_t dyhat, dx2, dx1_c, dx1, dx0, dh, dbn, dA_c, dA, dqkv, da, delta, dg_partial;
+  size_t splitk; size_t splitk_bytes;   // scratch of the weight-gradient products whose last tile round is split over K
   size_t g0, e0, dg0;   // token-input variant: projected features, looked-up embeddings, gradient of the features
   size_t total;
 };
@@ -163,6 +164,22 @@ Plan make_plan(const tide_draft_config* c) {
   p.da = b.take(T * p.d * es);
   p.delta = b.take((size_t)c->batch * c->n_heads * c->seq * 4);
   p.dg_partial = b.take(rmsnorm_bwd_scratch_bytes(p.T, (int)p.d));
+  {
+    // the largest split-K scratch any weight-gradient product of this configuration asks for
+    const int64_t shapes[7][2] = {{p.V, p.d}, {p.d, p.F}, {p.F, p.d}, {p.d, p.nq}, {p.nqkv, p.d}, {p.d, p.KH}, {p.d, 2 * p.d}};
+    size_t need = 0;
+    for (auto& sh : shapes) {
+      GemmArgs g;
+      std::memset(&g, 0, sizeof(g));
+      g.layout = kTN; g.M = sh[0]; g.N = sh[1]; g.K = p.T; g.lda = sh[0]; g.ldb = sh[1]; g.ldc = sh[1];
+      g.in_dtype = c->dtype == TIDE_DTYPE_BF16 ? kBF16 : kF32; g.out_dtype = kF32;
+      g.A = g.B = g.C = (void*)256;   // alignment only
+      const size_t n = gemm_splitk_scratch_bytes(g);
+      if (n > need) need = n;
+    }
+    p.splitk_bytes = need;
+    p.splitk = b.take(need ? need : 16);
+  }
   p.g0 = b.take(T * p.d * es);
   p.e0 = b.take(T * p.d * es);
   p.dg0 = b.take(T * p.d * es);
@@ -387,6 +404,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
       g.alpha = grad_weight; g.alpha_dev = scal + 1;
       g.accumulate = blk > 0 || add_to_dw;
       g.k_dev = cnt; g.k_off = r0;
+      g.scratch = ws + p.splitk; g.scratch_bytes = p.splitk_bytes;
       TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
     }
   }
@@ -396,6 +414,7 @@ int enqueue_lm_head(const tide_draft_config* c, const tide_draft_tensors* P, tid
     g.alpha = grad_weight; g.alpha_dev = scal + 1;
     g.accumulate = add_to_dw;
     g.k_dev = cnt; g.k_off = 0;
+    g.scratch = ws + p.splitk; g.scratch_bytes = p.splitk_bytes;
     TIDE_HIP(launch_gemm(g, s), "gemm dW_lm");
   }
   TIDE_HIP(launch_loss_reduce(loss_rows, hit_rows, cnt, scal, loss_out, acc_out, (int*)(ws + p.status), s), "loss reduce");
@@ -595,11 +614,13 @@ static int enqueue_backward(const tide_draft_config* cfg, const tide_draft_tenso
     GemmArgs g = gemm_args(kTN, M, N, T, A, lda, B, ldb, C, ldc, dt, kF32);
     g.k_dev = cnt;
     g.accumulate = acc;
+    g.scratch = ws + p.splitk; g.scratch_bytes = p.splitk_bytes;
     return g;
   };
   auto full_dw = [&](int64_t M, int64_t N, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int add) {
     GemmArgs g = gemm_args(kTN, M, N, T, A, lda, B, ldb, C, ldc, dt, kF32);
     g.accumulate = add;
+    g.scratch = ws + p.splitk; g.scratch_bytes = p.splitk_bytes;
     return g;
   };
   // final norm (plus, in the unroll, what the step after sends back into x2)
@@ -903,12 +924,16 @@ int tide_draft_train_step_packed(const tide_draft_config* cfg, tide_draft_tensor
 }
 
 // ---- building blocks ---------------------------------------------------------------------------
-size_t tide_gemm_workspace_bytes(int, int64_t, int64_t, int64_t, int) { return 0; }
+size_t tide_gemm_workspace_bytes(int layout, int64_t M, int64_t N, int64_t K, int out_dtype) {
+  if (layout < 0 || layout > 2 || M <= 0 || N <= 0 || K <= 0) return 0;
+  const int64_t lda = layout == kTN ? M : K, ldb = layout == kNT ? K : N;
+  GemmArgs g = gemm_args(layout, M, N, K, (void*)256, lda, (void*)256, ldb, (void*)256, N, kBF16, out_dtype);
+  return gemm_splitk_scratch_bytes(g);
+}
 
 int tide_gemm(int layout, int64_t M, int64_t N, int64_t K, float alpha, const void* A, const void* B, void* C,
               const void* residual, int in_dtype, int out_dtype, int accumulate, void* workspace,
               size_t workspace_bytes, void* stream) {
-  (void)workspace; (void)workspace_bytes;
   if (!A || !B || !C) return fail(TIDE_ERR_NULL, "A, B and C must not be NULL");
   if (layout < 0 || layout > 2 || M <= 0 || N <= 0 || K <= 0) return fail(TIDE_ERR_CONFIG, "bad layout or sizes");
   if ((in_dtype != 0 && in_dtype != 1) || (out_dtype != 0 && out_dtype != 1) || (in_dtype == 0 && out_dtype == 1))
@@ -916,6 +941,7 @@ int tide_gemm(int layout, int64_t M, int64_t N, int64_t K, float alpha, const vo
   const int64_t lda = layout == kTN ? M : K, ldb = layout == kNT ? K : N;
   GemmArgs g = gemm_args(layout, M, N, K, A, lda, B, ldb, C, N, in_dtype, out_dtype);
   g.alpha = alpha; g.residual = residual; g.ldr = N; g.accumulate = accumulate;
+  if (workspace && (((uintptr_t)workspace) & 15) == 0) { g.scratch = workspace; g.scratch_bytes = workspace_bytes; }
   TIDE_HIP(launch_gemm(g, (hipStream_t)stream), "gemm");
   return TIDE_OK;
 }

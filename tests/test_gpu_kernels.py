@@ -65,6 +65,40 @@ def test_gemm_bf16_large_tiles_ragged(B, layout):
     assert cosine(got, ref) > 0.99999
 
 
+@pytest.mark.parametrize("layout,accumulate", [(2, False), (2, True), (0, False), (1, True)])
+def test_gemm_split_of_the_last_tile_round(B, layout, accumulate):
+    """fp32 results whose tiles leave the last round of the 256 compute units at most half full: with a workspace
+    those tiles are split over K and a second kernel adds the partial sums.  Against the oracle product, and
+    against the unsplit launch (same tiles, different order of the fp32 additions).  17 x 16 tiles of 256 =
+    272 = one round + 16 tiles, split four ways (a part keeps at least 1024 of K); ragged M, N and K."""
+    M, N, K = 17 * 256 - 40, 16 * 256 - 8, 4408
+    need = B.tide_gemm_workspace_bytes(layout, M, N, K, DT["fp32"])
+    assert need == 3 * 16 * 256 * 256 * 4
+    assert B.tide_gemm_workspace_bytes(layout, M, N, K, DT["bf16"]) == 0             # bf16 results are never split
+    assert B.tide_gemm_workspace_bytes(layout, 16 * 256, 16 * 256, K, DT["fp32"]) == 0   # a full round
+    rng = np.random.default_rng(71 + layout)
+    shapeA = (K, M) if layout == B.LAYOUT_TN else (M, K)
+    shapeB = (N, K) if layout == B.LAYOUT_NT else (K, N)
+    A, Bm = quantize(rng.standard_normal(shapeA), "bf16"), quantize(rng.standard_normal(shapeB), "bf16")
+    C0 = rng.standard_normal((M, N)).astype(np.float32).astype(np.float64)
+    opA = A.T if layout == B.LAYOUT_TN else A
+    opB = Bm.T if layout == B.LAYOUT_NT else Bm
+    ref = 0.5 * (opA @ opB) + (C0 if accumulate else 0.0)
+    dA, dB = to_dev(A, "bf16"), to_dev(Bm, "bf16")
+    out = []
+    for ws_bytes in (need, 0):
+        dC = to_dev(C0, "fp32")
+        ws = torch.full((max(ws_bytes, 16),), 0xFF, dtype=torch.uint8, device=DEV)       # NaN patterns: every partial must be written
+        print(f"gemm split layout={layout} acc={accumulate} workspace={ws_bytes}", flush=True)
+        B.tide_gemm(layout, M, N, K, 0.5, dA, dB, dC, None, DT["bf16"], DT["fp32"], accumulate, stream(),
+                    workspace=ws if ws_bytes else None, workspace_bytes=ws_bytes)
+        sync()
+        out.append(to_host(dC))
+    assert rel_max(out[0], ref) < 2e-5 and rel_max(out[1], ref) < 2e-5
+    assert rel_max(out[0], out[1]) < 5e-6
+    assert not np.array_equal(out[0], out[1])          # the split really happened (another summation order)
+
+
 @pytest.mark.parametrize("layout", [0, 1, 2])
 def test_gemm_unaligned_falls_back(B, layout):
     # K, M, N not multiples of 8: the shape-agnostic kernel takes over
