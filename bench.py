@@ -168,6 +168,10 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket the library's launches with HIP events in the timed region (no per-kernel "
                          "figures and no roofline entry; shows what the events themselves cost)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture tide_draft_train_step_dev (learning rate and step count in device memory) into a HIP "
+                         "graph once and time its replays: what a launch-bound configuration (small) gains from "
+                         "replaying; no per-kernel figures in this mode")
     ap.add_argument("--set", action="append", default=[], metavar="KEY=INT",
                     help="override an integer field of the configuration (e.g. lm_keep_all_rows=1, lm_block_rows=8192)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -209,6 +213,24 @@ def main():
 
         def step(lr_):
             unroll_loss[:] = [tr.train_step_unroll(lr_, args.unroll, token_input=args.token_input)]
+
+    if args.graph:
+        assert not (args.token_input or args.unroll or args.ingest), "--graph times the base training step"
+        lr_dev = torch.full((1,), lr, dtype=torch.float32, device=dev)
+        step_dev = torch.zeros(1, dtype=torch.int64, device=dev)
+        tr.train_step_dev(lr_dev, step_dev)                      # one-time function attributes, outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                tr.train_step_dev(lr_dev, step_dev)
+        torch.cuda.current_stream().wait_stream(side)
+        args.no_kernel_events = True
+
+        def step(lr_):
+            graph.replay()
 
     for _ in range(args.warmup):
         step(lr)
@@ -256,7 +278,9 @@ def main():
     wall = time.perf_counter() - t0
     prof = B.tide_profile_stop() if not args.no_kernel_events else []
     if args.no_kernel_events:
-        print(json.dumps({"ms_per_step": wall * 1e3 / args.steps, "steps": args.steps, "kernel_events": False}))
+        print(json.dumps({"ms_per_step": wall * 1e3 / args.steps, "steps": args.steps, "kernel_events": False,
+                          "workload": cfg["name"], "graph_replay": bool(args.graph),
+                          "tokens_per_s": T / (wall / args.steps)}))
         return
     if ring is not None:
         B.tide_ingest_destroy(ring)

@@ -79,8 +79,11 @@ struct MfmaParams {
 };
 
 // tile index (XCD-contiguous order, groups of 4 tile rows) -> tile coordinates
+#ifndef TIDE_TILE_GROUP
+#define TIDE_TILE_GROUP 4
+#endif
 __device__ __forceinline__ void tile_coords(int v, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
-  constexpr int GROUP = 4;
+  constexpr int GROUP = TIDE_TILE_GROUP;
   const int per_group = GROUP * tiles_n;
   const int gid = v / per_group;
   const int first_m = gid * GROUP;
