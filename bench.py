@@ -20,7 +20,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 PEAK_HBM_GBS = 8000.0
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_8b_hbm_traffic.txt")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "train_step_8b_hbm_traffic.txt")
 
 
 def measured_traffic(kernel):
