@@ -262,7 +262,11 @@ def main():
         if ring is not None:
             # producer: fill a pinned slot, start its copy into the idle device buffer; the copy runs while
             # this step trains on the other buffer
-            rc, slot, addr = B.tide_ingest_acquire(ring)
+            while True:
+                rc, slot, addr = B.tide_ingest_acquire(ring)
+                if rc != B.TIDE_INGEST_ERR_BUSY:
+                    break
+                time.sleep(2e-4)    # back-pressure: every pinned slot still waits for its copy (the host runs ahead of the GPU)
             assert rc == 0, B.tide_ingest_last_error()
             ctypes.memmove(addr, src_addr, nbytes)
             # (the idle buffer was read by the step before this one, which may still be running: the copy is
@@ -345,7 +349,8 @@ def main():
     dom_tflops = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": dom_tflops / PEAK_BF16_TFLOPS,
-                "traffic": measured_traffic(dom["kernel"]) if cfg["name"] == "8b" else None,
+                "traffic": (measured_traffic(dom["kernel"])
+                            if cfg["name"] == "8b" and not args.unroll and not args.token_input else None),
                 "launches_per_step": dom["launches"] / args.steps,
                 "avg_launch_ms": dom["total_ms"] / dom["launches"],
                 "flops_per_launch": dom["flops"] / dom["launches"],
