@@ -901,6 +901,192 @@ __global__ __launch_bounds__(512) void ce_train_kernel(T* __restrict__ z, int64_
   }
 }
 
+// The same pass for bf16 logits with the ROW HELD ON THE CU between the statistics and the gradient, so that it
+// is read from memory once and written once (2 x 7.1 GB instead of 3 x at the 8B shape).  A block of 512 threads
+// owns a row; thread t keeps the 16-byte chunks t, t + 512, ...: the first NREG of them in registers, the other
+// n_lds in LDS (its own slots: no sharing).  NREG is chosen by the launcher so that every register chunk lies
+// wholly below V: only LDS chunks can hold padded columns or lie past the row, and they are cleaned on their way
+// into LDS.  At 128256 columns that is 24 chunks in registers + 8 in LDS = 64 KiB per block, so TWO blocks fit a
+// CU and the arithmetic of one overlaps the loads and stores of the other (the whole row in the registers of one
+// 1024-thread block measured 5.5 ms against 3.4 ms for the two-read kernel: the pass needs some 15 vector
+// instructions per element, as long per row as the memory traffic takes).
+// The softmax is the exact two-step one: block maximum first, then one exponential per element for the sum and
+// one for the gradient, each as exp2(fma(z, log2 e, -shift * log2 e)).  Same outputs as ce_train_kernel.
+// cache policy bits of the row's loads and stores (0 = default, 2 = non-temporal).  Measured at the 8B shape:
+// 2.75 ms with default policy on both, 2.68 with non-temporal loads, 2.65 with non-temporal stores, 2.59 with both
+// (the two-read kernel in the same call: 3.41 ms).
+#ifndef TIDE_CE_LOAD_AUX
+#define TIDE_CE_LOAD_AUX 2
+#endif
+#ifndef TIDE_CE_STORE_AUX
+#define TIDE_CE_STORE_AUX 2
+#endif
+template <int NREG>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void ce_train_resident_kernel(bf16_t* __restrict__ z, int64_t ldz, int V, int n_lds,
+                              const int32_t* __restrict__ tokens, const uint8_t* __restrict__ mask,
+                              float* __restrict__ lse, float* __restrict__ loss_rows,
+                              const int* __restrict__ rows_dev, int rows_off) {
+  constexpr int NT = 512, STEP = NT * 8;                     // columns between two chunks of a thread
+  constexpr float LOG2E = 1.4426950408889634f;
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  extern __shared__ u32x4_t ce_row_lds[];                      // n_lds x NT chunks
+  __shared__ float sm_red[8];
+  __shared__ float sm_bc[3];
+  const size_t row = blockIdx.x;
+  if (rows_dev && (int)row >= *rows_dev - rows_off) return;   // whole block, before any barrier
+  bf16_t* zr = z + row * (size_t)ldz;
+  const int tk = tokens[row];
+  const bool keep = mask[row] != 0 && tk >= 0 && tk < V;
+  const int c0 = threadIdx.x * 8;
+  u32x4_t* mine_lds = ce_row_lds + threadIdx.x;
+  // The row as a buffer resource: one 32-bit offset register per thread serves every chunk (the chunk's
+  // distance is a scalar offset), and the hardware drops what lies past the row (loads give 0, stores vanish).
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(zr, 0, (int)((uint32_t)ldz * 2u), 0x00020000);
+  const uint32_t off0 = (uint32_t)c0 * 2u;
+  auto fetch = [&](uint32_t voff, int soff) {
+    return __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, TIDE_CE_LOAD_AUX));
+  };
+  auto store = [&](u32x4_t v, uint32_t voff, int soff) { __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff, soff, TIDE_CE_STORE_AUX); };
+  const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+  u32x4_t buf[NREG > 0 ? NREG : 1];
+  // all loads first, none of them conditional
+#pragma unroll
+  for (int i = 0; i < NREG; ++i) buf[i] = fetch(off0, i * STEP * 2);
+  for (int i = 0; i < n_lds; ++i) {
+    // columns >= V become -inf (bf16 0xFF80) in the packed chunk itself, so that no pass needs a column test
+    // (the whole distance in the vector offset here: that is the part the range check surely covers)
+    const int c = c0 + (NREG + i) * STEP;
+    u32x4_t v = fetch((uint32_t)c * 2u, 0);
+    const int nv = V - c;
+    if (nv < 8) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        v[k] = (2 * k + 1 < nv) ? v[k] : (2 * k < nv) ? ((v[k] & 0xFFFFu) | 0xFF800000u) : 0xFF80FF80u;
+    }
+    mine_lds[i * NT] = v;
+  }
+  // the owner of the label's element: chunk and position (chunk -1: not in this thread)
+  const int dl = tk - c0;
+  const bool mine = keep && dl >= 0 && (dl & (STEP - 1)) < 8;
+  const int sel_i = mine ? dl / STEP : -1, sel_j = dl & 7;
+  // Every pass walks the register chunks strictly one after the other: a chunk is made opaque to the compiler
+  // together with the pass's running value right before its turn, so neither the unpacked floats of a whole
+  // pass nor those of an earlier pass are kept alive (8 registers per chunk instead of 4, and spills).
+  auto turn = [&](int i, float& running) {
+    asm volatile("" : "+v"(running), "+v"(buf[i]));
+  };
+  auto lo = [](uint32_t w) { return __uint_as_float(w << 16); };
+  auto hi = [](uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); };
+  auto max3 = [](float a, float b, float c) {                 // (plain fmaxf first quiets each unpacked operand)
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+  };
+  auto chunk_max = [&](u32x4_t v, float m) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) m = max3(m, lo(v[k]), hi(v[k]));
+    return m;
+  };
+  auto pick = [&](u32x4_t v) {                                // the label's logit (one thread of the block, once)
+    const uint32_t w = sel_j < 2 ? v[0] : sel_j < 4 ? v[1] : sel_j < 6 ? v[2] : v[3];
+    sm_bc[2] = (sel_j & 1) ? hi(w) : lo(w);
+  };
+  auto chunk_sum = [&](u32x4_t wv, float sh) {                // sum of exp2(z log2e + sh); exp2(-inf) = 0
+    float part = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      part += __builtin_amdgcn_exp2f(fmaf(lo(wv[k]), LOG2E, sh)) + __builtin_amdgcn_exp2f(fmaf(hi(wv[k]), LOG2E, sh));
+    return part;
+  };
+  auto chunk_grad = [&](u32x4_t wv, float sh, bool owner) {   // exp(z - lse), minus 1 at the label, packed
+    u32x4_t pk;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      pk[k] = f2bf2(__builtin_amdgcn_exp2f(fmaf(lo(wv[k]), LOG2E, sh)), __builtin_amdgcn_exp2f(fmaf(hi(wv[k]), LOG2E, sh)));
+    if (owner) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (sel_j == j) {
+          const float e = (j & 1) ? hi(wv[j >> 1]) : lo(wv[j >> 1]);
+          const uint32_t h = f2bf(__builtin_amdgcn_exp2f(fmaf(e, LOG2E, sh)) - 1.f);
+          pk[j >> 1] = (j & 1) ? ((pk[j >> 1] & 0xFFFFu) | (h << 16)) : ((pk[j >> 1] & 0xFFFF0000u) | h);
+        }
+    }
+    return pk;
+  };
+
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NREG; ++i) {
+    turn(i, m);
+    m = chunk_max(buf[i], m);
+    if (sel_i == i) pick(buf[i]);
+  }
+  for (int i = 0; i < n_lds; ++i) {
+    const u32x4_t v = mine_lds[i * NT];
+    m = chunk_max(v, m);
+    if (sel_i == NREG + i) pick(v);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) sm_red[w] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float M = sm_red[0];
+    for (int i = 1; i < 8; ++i) M = fmaxf(M, sm_red[i]);
+    sm_bc[0] = M;
+  }
+  __syncthreads();
+  const float M = sm_bc[0];
+  const float nM = -M * LOG2E;
+  float ssum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NREG; ++i) {
+    turn(i, ssum);
+    ssum += chunk_sum(buf[i], nM);
+  }
+  for (int i = 0; i < n_lds; ++i) ssum += chunk_sum(mine_lds[i * NT], nM);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ssum += __shfl_xor(ssum, o, 64);
+  if ((threadIdx.x & 63) == 0) sm_red[w] = ssum;                 // the maxima were all read before the second barrier
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float Sx = 0.f;
+    for (int i = 0; i < 8; ++i) Sx += sm_red[i];
+    const float l = M + logf(Sx);
+    lse[row] = l;
+    loss_rows[row] = keep ? (l - sm_bc[2]) : 0.f;
+    sm_bc[1] = l;
+  }
+  __syncthreads();
+  if (!keep) {                                                   // uniform over the block
+#pragma unroll
+    for (int i = 0; i < NREG; ++i) store(zero4, off0, i * STEP * 2);
+    for (int i = 0; i < n_lds; ++i) store(zero4, (uint32_t)(c0 + (NREG + i) * STEP) * 2u, 0);
+    return;
+  }
+  float nl = -sm_bc[1] * LOG2E;
+#pragma unroll
+  for (int i = 0; i < NREG; ++i) {
+    turn(i, nl);
+    buf[i] = chunk_grad(buf[i], nl, sel_i == i);                 // takes the chunk's place: the next turn waits for it
+    store(buf[i], off0, i * STEP * 2);
+  }
+  for (int i = 0; i < n_lds; ++i)
+    store(chunk_grad(mine_lds[i * NT], nl, sel_i == NREG + i), (uint32_t)(c0 + (NREG + i) * STEP) * 2u, 0);
+}
+
+// 0 = take the resident-row kernel whenever the row fits; 1 = always the two-read kernel (for A/B timing)
+#ifndef TIDE_CE_TWO_READS
+#define TIDE_CE_TWO_READS 0
+#endif
+// most LDS chunks per thread the resident-row kernel is used with (8 = 64 KiB: two blocks per CU; up to 18 fit one block)
+#ifndef TIDE_CE_MAX_LDS_CHUNKS
+#define TIDE_CE_MAX_LDS_CHUNKS 18
+#endif
+
 hipError_t launch_ce_train(int64_t rows, int V, void* z, int64_t ldz, const int32_t* tokens, const uint8_t* mask,
                            float* lse, float* loss_rows, const int* rows_dev, int64_t rows_off, int dtype,
                            hipStream_t s) {
@@ -911,6 +1097,34 @@ hipError_t launch_ce_train(int64_t rows, int V, void* z, int64_t ldz, const int3
   constexpr size_t pad = 48 * 1024;   // occupancy limiter, see the kernel's comment
   dim3 grid((unsigned)rows), blk(512);
   const int ro = (int)rows_off;
+  // resident-row kernel: chunks wholly below V go to registers (a template count, at most 24), the rest to LDS
+  const int64_t nch = (ldz + 4095) / 4096, full = V / 4096;    // 16-byte chunks per thread of a 512-thread block
+  static const int kRegs[] = {24, 20, 16, 12, 8, 4, 2, 1, 0};
+  int nreg = 0;
+  for (int r : kRegs)
+    if (r <= full) { nreg = r; break; }
+  const int64_t n_lds = nch - nreg;
+  if (dtype == kBF16 && !TIDE_CE_TWO_READS && n_lds <= TIDE_CE_MAX_LDS_CHUNKS) {
+    bf16_t* zb = (bf16_t*)z;
+    dim3 blk_r(512);
+    const size_t lds = (size_t)n_lds * 512 * 16;
+    if (lds > 65536) {                          // only with 24 register chunks; one block per CU then
+      static bool raised = false;
+      if (!raised) {
+        const hipError_t e = hipFuncSetAttribute((const void*)ce_train_resident_kernel<24>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 TIDE_CE_MAX_LDS_CHUNKS * 512 * 16);
+        if (e != hipSuccess) return e;
+        raised = true;
+      }
+    }
+#define TIDE_CE_RES(R) case R: hipLaunchKernelGGL((ce_train_resident_kernel<R>), grid, blk_r, lds, s, zb, ldz, V, (int)n_lds, tokens, mask, lse, loss_rows, rows_dev, ro); break
+    switch (nreg) {
+      TIDE_CE_RES(24); TIDE_CE_RES(20); TIDE_CE_RES(16); TIDE_CE_RES(12); TIDE_CE_RES(8);
+      TIDE_CE_RES(4); TIDE_CE_RES(2); TIDE_CE_RES(1); TIDE_CE_RES(0);
+    }
+#undef TIDE_CE_RES
+    return hipGetLastError();
+  }
   if (dtype == kBF16) hipLaunchKernelGGL(ce_train_kernel<bf16_t>, grid, blk, pad, s, (bf16_t*)z, ldz, V, tokens, mask, lse, loss_rows, rows_dev, ro);
   else hipLaunchKernelGGL(ce_train_kernel<float>, grid, blk, pad, s, (float*)z, ldz, V, tokens, mask, lse, loss_rows, rows_dev, ro);
   return hipGetLastError();
