@@ -486,19 +486,31 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
   }
 }
 
-// out[c] = sum_r part[r, c]; 64 columns x 4 row lanes per block
+// out[c] = sum_r part[r, c]; 16 columns x 16 row lanes per block, four loads in flight per thread, fixed
+// summation order.  (64 columns x 4 row lanes, i.e. 64 blocks at d = 4096 with one load in flight per thread, took
+// 49 us for the 768 x 4096 partials of the 8B shape: a fifth of the RMSNorm backward it finishes.)
 __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ part, int64_t nrows, int d,
                                                      float* __restrict__ out, int accumulate) {
-  __shared__ float sm[4][64];
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
-  const int rl = threadIdx.x >> 6;
-  float a = 0.f;
-  if (c < d)
-    for (int64_t r = rl; r < nrows; r += 4) a += part[(size_t)r * d + c];
-  sm[rl][threadIdx.x & 63] = a;
+  __shared__ float sm[16][17];
+  const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  if (c < d) {
+    int64_t r = rl;
+    for (; r + 48 < nrows; r += 64) {
+      a0 += part[(size_t)r * d + c];
+      a1 += part[(size_t)(r + 16) * d + c];
+      a2 += part[(size_t)(r + 32) * d + c];
+      a3 += part[(size_t)(r + 48) * d + c];
+    }
+    for (; r < nrows; r += 16) a0 += part[(size_t)r * d + c];
+  }
+  sm[rl][cl] = (a0 + a1) + (a2 + a3);
   __syncthreads();
   if (rl == 0 && c < d) {
-    const float v = (sm[0][threadIdx.x] + sm[1][threadIdx.x]) + (sm[2][threadIdx.x] + sm[3][threadIdx.x]);
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v += sm[i][cl];
     out[c] = accumulate ? out[c] + v : v;
   }
 }
@@ -531,7 +543,7 @@ hipError_t launch_rmsnorm_bwd(int64_t rows, int d, const void* dy, const void* x
 #undef TIDE_RMS_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_kernel, dim3((d + 63) / 64), dim3(256), 0, s, dg_partial, nblk, d, dg, accumulate);
+  hipLaunchKernelGGL(colsum_kernel, dim3((d + 15) / 16), dim3(256), 0, s, dg_partial, nblk, d, dg, accumulate);
   return hipGetLastError();
 }
 

@@ -1123,25 +1123,44 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
 }
 
 // C[tile] += the partial sums of the later parts of every split tile, in the order of the parts (deterministic).
-// One block per split tile; 256 threads, a thread adds 4 consecutive columns at a time.
+// Eight blocks per split tile (32 rows each); 256 threads, a thread adds 4 consecutive columns of 4 rows at a
+// time, with the old values and every part's addends of those rows requested before the first sum.
 __global__ __launch_bounds__(256) void splitk_fixup_kernel(float* __restrict__ C, int ldc, int M, int N, int tiles_n,
                                                            int split_full, int split_s, const float* __restrict__ scratch) {
   const int tiles_m = (M + 255) / 256;
   const int ntail = tiles_m * tiles_n - split_full;
+  const int tile = blockIdx.x >> 3, rblk = blockIdx.x & 7;
   int tile_m, tile_n;
-  tile_coords(split_full + blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  tile_coords(split_full + tile, tiles_m, tiles_n, tile_m, tile_n);
   const int m0 = tile_m * 256, n0 = tile_n * 256;
-  const int c4 = (threadIdx.x & 63) * 4, r0 = threadIdx.x >> 6;
-  for (int r = r0; r < 256; r += 4) {
-    const int gm = m0 + r, gn = n0 + c4;
-    if (gm >= M || gn >= N) continue;
-    float4* dst = reinterpret_cast<float4*>(C + (size_t)gm * ldc + gn);
-    float4 v = *dst;
-    for (int j = 1; j < split_s; ++j) {
-      const float4 x = *reinterpret_cast<const float4*>(scratch + ((size_t)(j - 1) * ntail + blockIdx.x) * 65536 + (size_t)r * 256 + c4);
-      v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
+  const int c4 = (threadIdx.x & 63) * 4, r0 = rblk * 32 + (threadIdx.x >> 6);
+  const int gn = n0 + c4;
+  if (gn >= N) return;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    float4 v[4];
+    bool ok[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = r0 + (half * 4 + i) * 4;
+      ok[i] = m0 + r < M;
+      v[i] = ok[i] ? *reinterpret_cast<const float4*>(C + (size_t)(m0 + r) * ldc + gn) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    *dst = v;
+    for (int j = 1; j < split_s; ++j) {
+      float4 x[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = r0 + (half * 4 + i) * 4;
+        x[i] = *reinterpret_cast<const float4*>(scratch + ((size_t)(j - 1) * ntail + tile) * 65536 + (size_t)r * 256 + c4);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { v[i].x += x[i].x; v[i].y += x[i].y; v[i].z += x[i].z; v[i].w += x[i].w; }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = r0 + (half * 4 + i) * 4;
+      if (ok[i]) *reinterpret_cast<float4*>(C + (size_t)(m0 + r) * ldc + gn) = v[i];
+    }
   }
 }
 
@@ -1264,7 +1283,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   if (e != hipSuccess || p.split_s <= 1) return e;
   const int tiles_n = (p.N + 255) / 256;
   const int ntail = ((p.M + 255) / 256) * tiles_n - p.split_full;
-  hipLaunchKernelGGL(splitk_fixup_kernel, dim3((unsigned)ntail), dim3(256), 0, s, (float*)p.C, p.ldc, p.M, p.N, tiles_n,
+  hipLaunchKernelGGL(splitk_fixup_kernel, dim3((unsigned)ntail * 8u), dim3(256), 0, s, (float*)p.C, p.ldc, p.M, p.N, tiles_n,
                      p.split_full, p.split_s, p.split_scratch);
   return hipGetLastError();
 }
