@@ -41,7 +41,14 @@ typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 namespace {
 
 constexpr int D = 128;          // head_dim
-constexpr int PITCH = D + 8;    // LDS row pitch in elements (272 B: conflict-free 16-byte row reads)
+constexpr int PITCH = D + 8;    // LDS row pitch in elements (272 B = 4 banks past a multiple of 64)
+// Streamed tiles (K, V, Q, dO) keep row r of the tile in LDS row perm(r): inside every group of 16 rows the two
+// 2-bit fields of the row number are exchanged.  A row read (16 lanes = 16 consecutive tile rows, 16 bytes each)
+// still meets 16 different LDS rows, 4 banks apart: all 64 banks once.  A transposing read (32 lanes = 4
+// consecutive tile rows x 64 contiguous bytes) now meets LDS rows that are 4 apart, i.e. 16 banks apart: four
+// disjoint windows.  With the rows in natural order those four windows overlapped (4 banks apart), and half of all
+// LDS cycles of the three kernels were bank-conflict cycles (by counter).  Every address stays base + constant.
+__device__ __forceinline__ int perm(int r) { return (r & ~15) | ((r & 3) << 2) | ((r >> 2) & 3); }
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* base, uint32_t bytes) {
@@ -52,9 +59,10 @@ __device__ __forceinline__ f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-// A/B operand whose contraction index is contiguous in the LDS tile [row][PITCH]
-__device__ __forceinline__ u32x4_t frag(const bf16_t* tile, int row, int kofs) {
-  return *reinterpret_cast<const u32x4_t*>(tile + row * PITCH + kofs);
+// A/B operand whose contraction index is contiguous in the LDS tile: tile row row0 + r with row0 a multiple of 16
+// and prow = perm(r) (computed once per lane)
+__device__ __forceinline__ u32x4_t frag(const bf16_t* tile, int row0, int prow, int kofs) {
+  return *reinterpret_cast<const u32x4_t*>(tile + (row0 + prow) * PITCH + kofs);
 }
 
 // A operand taken from the tile TRANSPOSED: tile is [k][PITCH] (k = contraction index, 16 rows starting
@@ -64,10 +72,10 @@ __device__ __forceinline__ u32x4_t frag_tr(const bf16_t* tile, int kbase, int nb
   const int g = lane >> 5;
   const int l16 = lane & 15;
   const int col = nbase + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
-  const int row = kbase + 4 * g + (l16 >> 2);
+  const int row = kbase + ((l16 >> 2) << 2) + g;   // perm(kbase + 4 g + (l16 >> 2)); kbase is a multiple of 16
   typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
   const bf16_t* p0 = tile + row * PITCH + col;
-  const bf16_t* p1 = p0 + 8 * PITCH;
+  const bf16_t* p1 = p0 + 2 * PITCH;                // perm of the tile row 8 further on
   s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0));
   s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p1));
   u32x2_t a = __builtin_bit_cast(u32x2_t, lo), b = __builtin_bit_cast(u32x2_t, hi);
@@ -109,7 +117,7 @@ struct TileLoader {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int p = tid + i * 256;
-      const int row = p >> 4, piece = p & 15;
+      const int row = i * 16 + perm(tid >> 4), piece = p & 15;   // perm(p >> 4)
       *reinterpret_cast<i32x4_t*>(tile + row * PITCH + piece * 8) = r[i];
     }
   }
@@ -186,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
   bf16_t* sK = smem;                 // [2][KV_TILE]
   bf16_t* sV = smem + 2 * KV_TILE;   // [2][KV_TILE]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lr = lane & 31, g = lane >> 5;
+  const int lr = lane & 31, g = lane >> 5, plr = perm(lr);
   const int nqb = (Smax + BQ - 1) / BQ;
   const Work3 wk = xcd_group_work(nqb, nh, nseq, nh / nkv);
   const int qb = nqb - 1 - wk.x;  // heavy (late) query blocks first
@@ -239,7 +247,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
 #pragma unroll
         for (int q = 0; q < 16; ++q) s[jt][q] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) s[jt] = mfma(frag(K, jt * 32 + lr, kk * 16 + g * 8), qf[kk], s[jt]);
+        for (int kk = 0; kk < 8; ++kk) s[jt] = mfma(frag(K, jt * 32, plr, kk * 16 + g * 8), qf[kk], s[jt]);
       }
       if (j0 + BKV - 1 > qw) {  // the tile touches the diagonal of this wave
 #pragma unroll
@@ -308,7 +316,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
   bf16_t* sK = smem;
   bf16_t* sV = smem + 2 * KV_TILE;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lr = lane & 31, g = lane >> 5;
+  const int lr = lane & 31, g = lane >> 5, plr = perm(lr);
   const int nqb = (Smax + BQ - 1) / BQ;
   const Work3 wk = xcd_group_work(nqb, nh, nseq, nh / nkv);
   const int qb = nqb - 1 - wk.x;
@@ -369,8 +377,8 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
         for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-          s = mfma(frag(K, jt * 32 + lr, kk * 16 + g * 8), qf[kk], s);
-          dp = mfma(frag(V, jt * 32 + lr, kk * 16 + g * 8), dof[kk], dp);
+          s = mfma(frag(K, jt * 32, plr, kk * 16 + g * 8), qf[kk], s);
+          dp = mfma(frag(V, jt * 32, plr, kk * 16 + g * 8), dof[kk], dp);
         }
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
@@ -416,7 +424,7 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
                                                             const int* __restrict__ cu, int64_t T, int nseq) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lr = lane & 31, g = lane >> 5;
+  const int lr = lane & 31, g = lane >> 5, plr = perm(lr);
   const Work3 wk = xcd_group_work((Smax + 127) / 128, nkv, nseq, 1);
   const int jb = wk.x, kh = wk.y, b = wk.z;  // early key blocks are the heavy ones
   const SeqView sv = seq_view(cu, b, Smax, T);
@@ -484,8 +492,8 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
       for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
-        s = mfma(frag(Qt, lr, kk * 16 + g * 8), kf[kk], s);
-        if constexpr (DK) dp = mfma(frag(dOt, lr, kk * 16 + g * 8), vf[kk], dp);
+        s = mfma(frag(Qt, 0, plr, kk * 16 + g * 8), kf[kk], s);
+        if constexpr (DK) dp = mfma(frag(dOt, 0, plr, kk * 16 + g * 8), vf[kk], dp);
       }
       const bool diag = i0 < jw + 32;  // some (query, key) pair of the tile is above the diagonal
 #pragma unroll
