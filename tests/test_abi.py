@@ -53,6 +53,25 @@ def test_workspace_sizes_and_config_validation(B):
         assert word in B.tide_last_error(), (field, B.tide_last_error())
 
 
+def test_split_plan_of_a_partly_filled_last_tile_round(B):
+    """Host logic of the split over K (no device call): only float results whose 256 x 256 tiles leave the last round
+    of the 256 compute units at most half full are split, into as many parts as fit that round (at most 8, each at
+    least 32 slabs of 32 long); the workspace is one 256 x 256 float tile per further part and split tile."""
+    TN, F32, BF16 = 2, B.TIDE_DTYPE_FP32, B.TIDE_DTYPE_BF16
+    tile = 256 * 256 * 4
+    need = B.tide_gemm_workspace_bytes
+    assert need(TN, 14336, 4096, 27856, F32) == 1 * 128 * tile        # 896 tiles = 3.5 rounds: 128 tiles in two parts
+    assert need(TN, 6144, 4096, 32768, F32) == 1 * 128 * tile         # 384 tiles = 1.5 rounds
+    assert need(TN, 128256, 4096, 16384, F32) == 2 * 80 * tile        # 8016 tiles = 31 rounds + 80: three parts each
+    assert need(TN, 4096, 4096, 27856, F32) == 0                      # 256 tiles: the round is full
+    assert need(TN, 4096 + 256 * 9, 4096, 27856, F32) == 0            # 400 tiles: 144 left, more than half a round
+    assert need(TN, 14336, 4096, 27856, BF16) == 0                    # bf16 results are never split
+    assert need(TN, 2048, 4096, 27856, F32) == 0                      # 128 tiles: the small-tile kernel takes those
+    assert need(TN, 14336, 4096, 1024, F32) == 0                      # K too short for two parts of 32 slabs
+    assert need(TN, 4096 + 256, 4096, 1 << 20, F32) == 7 * 16 * tile  # 16 tiles left: 8 parts at most
+    assert need(0, 14336 + 128, 4096, 27856, F32) == need(TN, 14336 + 128, 4096, 27856, F32)   # any layout
+
+
 def test_calls_reject_bad_arguments_before_touching_the_device(B):
     c = B.make_config(W.get_config("tiny"))
     t = B.make_tensors(None)
