@@ -399,6 +399,17 @@ int tide_attention_bwd(int B, int S, int n_heads, int n_kv_heads, int head_dim,
 int tide_rope(int B, int S, int n_heads, int n_kv_heads, int head_dim, float theta,
               void *qkv, float *table, int inverse, int dtype, void *stream);
 
+/* Cross-entropy pass of a training call over a block of logits (Sec. 3.3: the draft is
+ * trained on the target's emitted tokens; mean CE over the loss-carrying rows):
+ * z [rows, ldz] (DEVICE, dtype TIDE_DTYPE_*, ldz a multiple of 8 and >= vocab, rows 16-byte
+ * aligned) holds the logits on entry and, on return,
+ *     dz[r, c] = keep_r * (exp(z[r, c] - lse_r) - [c == tokens[r]])   for c < vocab, 0 for c in [vocab, ldz)
+ * (not divided by the number of loss rows), with keep_r = mask[r] != 0 and 0 <= tokens[r] < vocab.
+ * lse [rows] and loss_rows [rows] (DEVICE floats) receive the log-sum-exp of every row and
+ * keep_r * (lse_r - z[r, tokens[r]]).  Everything is caller-owned; nothing is allocated. */
+int tide_ce_train(int64_t rows, int32_t vocab, void *z, int64_t ldz, const int32_t *tokens,
+                  const uint8_t *mask, float *lse, float *loss_rows, int dtype, void *stream);
+
 /* ---- Measurement support ----
  * Between tide_profile_start and tide_profile_stop every kernel the library
  * enqueues is bracketed by a pair of HIP events recorded on the caller's stream

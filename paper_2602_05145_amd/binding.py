@@ -117,6 +117,8 @@ _lib.tide_attention_fwd.restype = _i32
 _lib.tide_attention_fwd.argtypes = [_i32] * 5 + [_vp, _vp, _vp, _i32, _vp]
 _lib.tide_attention_bwd.restype = _i32
 _lib.tide_attention_bwd.argtypes = [_i32] * 5 + [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]
+_lib.tide_ce_train.restype = _i32
+_lib.tide_ce_train.argtypes = [_i64, _i32, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _vp]
 _lib.tide_rope.restype = _i32
 _lib.tide_rope.argtypes = [_i32] * 5 + [_f32, _vp, _vp, _i32, _i32, _vp]
 
@@ -134,7 +136,7 @@ EXPORTED = ("tide_last_error", "tide_draft_workspace_bytes", "tide_draft_workspa
     "tide_ingest_create", "tide_ingest_destroy", "tide_ingest_acquire", "tide_ingest_submit", "tide_ingest_wait",
     "tide_ingest_done", "tide_ingest_last_error", "tide_gemm_workspace_bytes", "tide_gemm",
             "tide_rmsnorm_fwd", "tide_rmsnorm_bwd_scratch_bytes", "tide_rmsnorm_bwd", "tide_rmsnorm_bwd_static",
-            "tide_attention_fwd", "tide_attention_bwd", "tide_rope", "tide_profile_start",
+            "tide_attention_fwd", "tide_attention_bwd", "tide_rope", "tide_ce_train", "tide_profile_start",
             "tide_profile_stop")
 
 
@@ -384,6 +386,11 @@ def tide_attention_bwd(B, S, nh, nkv, dh, qkv, out, dout, lse, delta, dqkv, dtyp
 
 def tide_rope(B, S, nh, nkv, dh, theta, qkv, table, inverse, dtype, stream):
     return _check(_lib.tide_rope(B, S, nh, nkv, dh, float(theta), _ptr(qkv), _ptr(table), int(inverse), dtype, stream))
+
+
+def tide_ce_train(rows, vocab, z, ldz, tokens, mask, lse, loss_rows, dtype, stream, check=True):
+    rc = _lib.tide_ce_train(int(rows), int(vocab), _ptr(z), int(ldz), _ptr(tokens), _ptr(mask), _ptr(lse), _ptr(loss_rows), dtype, stream)
+    return _check(rc) if check else rc
 
 
 def tide_profile_start():

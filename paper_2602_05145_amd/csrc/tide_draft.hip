@@ -1048,6 +1048,17 @@ int tide_rope(int B, int S, int nh, int nkv, int dh, float theta, void* qkv, flo
   return TIDE_OK;
 }
 
+int tide_ce_train(int64_t rows, int32_t vocab, void* z, int64_t ldz, const int32_t* tokens, const uint8_t* mask,
+                  float* lse, float* loss_rows, int dtype, void* stream) {
+  if (!z || !tokens || !mask || !lse || !loss_rows) return fail(TIDE_ERR_NULL, "NULL argument");
+  if (rows < 0 || rows > 0x7fffffff || vocab <= 0 || ldz < vocab || ldz % 8) return fail(TIDE_ERR_CONFIG, "bad logit block shape");
+  if (dtype != TIDE_DTYPE_FP32 && dtype != TIDE_DTYPE_BF16) return fail(TIDE_ERR_CONFIG, "bad dtype");
+  if (((uintptr_t)z) & 15) return fail(TIDE_ERR_CONFIG, "z must be 16-byte aligned");
+  TIDE_HIP(launch_ce_train(rows, vocab, z, ldz, tokens, mask, lse, loss_rows, nullptr, 0,
+                           dtype == TIDE_DTYPE_BF16 ? kBF16 : kF32, (hipStream_t)stream), "ce train");
+  return TIDE_OK;
+}
+
 }  // extern "C"
 
 // ---- optional per-launch profiler (prof.h) --------------------------------------------------------

@@ -116,6 +116,65 @@ def test_gemm_bad_arguments(B):
     assert "layout" in B.tide_last_error() or "size" in B.tide_last_error()
 
 
+# ------------------------------------------------------------------ cross-entropy pass
+@pytest.mark.parametrize("dtype,vocab", [
+    ("bf16", 11), ("bf16", 4093), ("bf16", 9001), ("bf16", 16391), ("bf16", 40003), ("bf16", 70001),
+    ("bf16", 128256), ("bf16", 131080), ("bf16", 152064), ("bf16", 250007), ("fp32", 9001)])
+def test_cross_entropy_pass_of_a_logit_block(B, dtype, vocab):
+    """tide_ce_train on a block of logits against the oracle's ce_dz on the same (storage-rounded) logits: lse and
+    the loss terms to fp32 accuracy, every gradient element to the rounding of its storage type, padded columns
+    exactly zero, masked rows and rows with an out-of-range label exactly zero.  The bf16 kernel keeps a row in the
+    registers and LDS of a 512-thread block (16-byte chunks 4096 columns apart): the vocabulary sizes end inside a
+    chunk, are no multiple of 8, leave whole chunks past the end of the row, need one block per CU (152064), or do
+    not fit at all and take the two-read kernel (250007)."""
+    rng = np.random.default_rng(vocab)
+    rows = 37
+    ldz = (vocab + 63) // 64 * 64
+    z = quantize(rng.standard_normal((rows, vocab)) * 3.0, dtype)
+    z[5, :] += 40.0 * (rng.random(vocab) < 1e-3)              # a row dominated by a few large logits
+    z[6, :] = quantize(-30.0 + rng.standard_normal(vocab), dtype)
+    z = quantize(z, dtype)
+    tokens = rng.integers(0, vocab, rows).astype(np.int32)
+    tokens[0], tokens[1], tokens[2] = vocab - 1, 0, min(vocab - 1, 4096)
+    tokens[3], tokens[4] = vocab + 3, -1                      # out of range: the row keeps no loss
+    mask = np.ones(rows, np.uint8)
+    mask[7] = 0
+    zp = np.full((rows, ldz), 7.0)                            # the padding holds garbage on entry
+    zp[:, :vocab] = z
+    dz_d = to_dev(zp, dtype)
+    tok_d = torch.from_numpy(tokens).to(DEV)
+    mask_d = torch.from_numpy(mask).to(DEV)
+    lse_d = torch.empty(rows, dtype=torch.float32, device=DEV)
+    loss_d = torch.empty(rows, dtype=torch.float32, device=DEV)
+    print(f"ce pass {dtype} rows={rows} vocab={vocab} ldz={ldz}", flush=True)
+    B.tide_ce_train(rows, vocab, dz_d, ldz, tok_d, mask_d, lse_d, loss_d, DT[dtype], stream())
+    sync()
+    dz, lse, loss = to_host(dz_d), to_host(lse_d), to_host(loss_d)
+    keep = O.effective_mask(tokens, mask, vocab)
+    assert int(keep.sum()) == rows - 3
+    ref = O.ce_dz(z, tokens, mask) * int(keep.sum())          # the pass leaves the 1/N to the products that read dz
+    zmax = z.max(-1)
+    lse_ref = np.log(np.sum(np.exp(z - zmax[:, None]), -1)) + zmax
+    assert np.max(np.abs(lse - lse_ref)) <= 1e-5 * np.max(np.abs(lse_ref)) + 1e-5
+    loss_ref = np.where(keep, lse_ref - z[np.arange(rows), np.clip(tokens, 0, vocab - 1)], 0.0)
+    assert np.max(np.abs(loss - loss_ref)) <= 1e-4
+    assert not np.any(dz[:, vocab:] != 0)
+    assert not np.any(dz[~keep] != 0)
+    ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -16        # storage rounding plus the fp32 exponential of |z - lse| <= 64
+    assert np.all(np.abs(dz[:, :vocab] - ref) <= ulp * np.abs(ref) + 1e-9)
+
+
+def test_cross_entropy_pass_rejects_bad_arguments(B):
+    t = torch.zeros(64, dtype=torch.float32, device=DEV)
+    i = torch.zeros(4, dtype=torch.int32, device=DEV)
+    m = torch.ones(4, dtype=torch.uint8, device=DEV)
+    assert B.tide_ce_train(1, 16, None, 16, i, m, t, t, 0, stream(), check=False) == B.TIDE_ERR_NULL
+    assert B.tide_ce_train(1, 16, t, 8, i, m, t, t, 0, stream(), check=False) == B.TIDE_ERR_CONFIG     # ldz < vocab
+    assert B.tide_ce_train(1, 12, t, 12, i, m, t, t, 0, stream(), check=False) == B.TIDE_ERR_CONFIG    # ldz % 8
+    assert B.tide_ce_train(1, 16, t, 16, i, m, t, t, 5, stream(), check=False) == B.TIDE_ERR_CONFIG    # dtype
+    assert B.tide_ce_train(0, 16, t, 16, i, m, t, t, 0, stream()) == 0                                  # no rows: nothing to do
+
+
 # ------------------------------------------------------------------ RMSNorm
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("rows,d", [(70, 256), (33, 4096), (5, 24), (40, 100)])

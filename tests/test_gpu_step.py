@@ -341,45 +341,3 @@ def test_random_shapes_bf16(seed):
     if wl["mask"].sum() < 4:
         wl["mask"][:, -4:] = 1
     _check_bf16(cfg, wl)
-
-
-@pytest.mark.parametrize("vocab", [9001, 16391, 40003, 70001, 131080])
-def test_logit_gradient_of_vocabularies_that_end_inside_a_chunk(vocab):
-    """The cross-entropy pass of a training call (statistics and gradient of a row of logits held in registers by
-    a 1024-thread block, 16-byte chunks 8192 columns apart) at vocabulary sizes that are no multiple of 8, end inside
-    a chunk, and leave whole chunks of a thread past the end of the row.  The forward-only call leaves the bf16
-    logits of the row block in the workspace; the training call overwrites them by their gradient (without the
-    1/N).  Oracle: ce_dz on those very bf16 logits, so the comparison isolates the pass: lse to fp32 accuracy,
-    every gradient element to bf16 rounding, padded columns exactly zero, out-of-range labels as masked rows."""
-    from paper_2602_05145_amd import runtime
-    cfg = W.get_config("tiny", dtype="bf16", vocab=vocab, batch=2, seq=20, mask="none")
-    wl = W.make_workload(cfg)
-    wl["tokens"][0, 0] = vocab - 1                     # a label in the last, partly filled chunk
-    wl["tokens"][0, 1] = 0
-    wl["tokens"][1, 2] = vocab + 3                     # out of range: the row keeps no loss
-    wl["tokens"][1, 3] = -1
-    tr = runtime.trainer_from_workload(cfg, wl)
-    T, V = cfg["batch"] * cfg["seq"], vocab
-    ldz = (V + 63) // 64 * 64
-    tok = wl["tokens"].reshape(-1)
-    keep = O.effective_mask(tok, wl["mask"], V)
-    n = int(keep.sum())
-    assert n == T - 2
-    tr.forward()
-    sync()
-    z = tr.intermediate("z", (n, ldz)).float().cpu().numpy().astype(np.float64)[:, :V]
-    tr.train_step(cfg["lr"])
-    sync()
-    dz = tr.intermediate("z", (n, ldz)).float().cpu().numpy().astype(np.float64)
-    lse = tr.intermediate("lse", (T,), kind="f32").cpu().numpy().astype(np.float64)[:n]
-    loss_rows = tr.intermediate("loss_rows", (T,), kind="f32").cpu().numpy().astype(np.float64)[:n]
-    labels = tok[keep]
-    ones = np.ones(n, np.uint8)
-    ref = O.ce_dz(z, labels, ones) * n                 # the pass leaves the 1/N to the products that read dz
-    lse_ref = np.log(np.sum(np.exp(z - z.max(-1, keepdims=True)), -1)) + z.max(-1)
-    assert np.max(np.abs(lse - lse_ref)) <= 1e-5 * np.max(np.abs(lse_ref))
-    assert np.max(np.abs(loss_rows - (lse_ref - z[np.arange(n), labels]))) <= 1e-4
-    assert not np.any(dz[:, V:] != 0)
-    # bf16 rounding of a value of magnitude |ref| (2^-9 relative) plus the fp32 exponential
-    assert np.all(np.abs(dz[:, :V] - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-9)
-    assert float(tr.loss.item()) == pytest.approx(float(loss_rows.sum() / n), rel=1e-5)
