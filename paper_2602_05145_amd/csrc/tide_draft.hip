@@ -149,21 +149,32 @@ Plan make_plan(const tide_draft_config* c) {
   p.lse = b.take(T * 4);
   p.loss_rows = b.take(T * 4);
   p.hit_rows = b.take(T * 4);
-  p.z = b.take((size_t)p.z_rows * p.ldz * es);
+  const size_t z_bytes = (size_t)p.z_rows * p.ldz * es;
+  p.z = b.take(z_bytes);
   p.fwd_end = b.off;
   p.dyhat = b.take(T * p.d * es);
-  p.dx2 = b.take(T * p.d * es);
-  p.dx1_c = b.take(T * p.d * es);
-  p.dx1 = b.take(T * p.d * es);
-  p.dx0 = b.take(T * p.d * es);
-  p.dh = b.take(T * p.F * es);
-  p.dbn = b.take(T * p.d * es);
-  p.dA_c = b.take(T * p.nq * es);
-  p.dA = b.take(T * p.nq * es);
-  p.dqkv = b.take(T * p.nqkv * es);
-  p.da = b.take(T * p.d * es);
-  p.delta = b.take((size_t)c->batch * c->n_heads * c->seq * 4);
-  p.dg_partial = b.take(rmsnorm_bwd_scratch_bytes(p.T, (int)p.d));
+  // What only the layer's backward pass touches lives INSIDE the logit buffer as far as that reaches: the
+  // backward pass starts after the LM head has finished (in the unroll: after the LM heads of all steps, each in
+  // its own workspace), and the last block of logit gradients is dead by then.
+  Bump zb;
+  zb.off = p.z;
+  auto bwd_take = [&](size_t bytes) {
+    if (align_up(zb.off + bytes, 256) <= p.z + z_bytes) return zb.take(bytes);
+    return b.take(bytes);
+  };
+  p.dh = bwd_take(T * p.F * es);
+  p.dx2 = bwd_take(T * p.d * es);
+  p.dx1_c = bwd_take(T * p.d * es);
+  p.dx1 = bwd_take(T * p.d * es);
+  p.dx0 = bwd_take(T * p.d * es);
+  p.dbn = bwd_take(T * p.d * es);
+  p.dA_c = bwd_take(T * p.nq * es);
+  p.dA = bwd_take(T * p.nq * es);
+  p.dqkv = bwd_take(T * p.nqkv * es);
+  p.da = bwd_take(T * p.d * es);
+  p.dg0 = bwd_take(T * p.d * es);
+  p.delta = bwd_take((size_t)c->batch * c->n_heads * c->seq * 4);
+  p.dg_partial = bwd_take(rmsnorm_bwd_scratch_bytes(p.T, (int)p.d));
   {
     // the largest split-K scratch any weight-gradient product of this configuration asks for
     const int64_t shapes[7][2] = {{p.V, p.d}, {p.d, p.F}, {p.F, p.d}, {p.d, p.nq}, {p.nqkv, p.d}, {p.d, p.KH}, {p.d, 2 * p.d}};
@@ -182,7 +193,6 @@ Plan make_plan(const tide_draft_config* c) {
   }
   p.g0 = b.take(T * p.d * es);
   p.e0 = b.take(T * p.d * es);
-  p.dg0 = b.take(T * p.d * es);
   p.total = b.off;
   return p;
 }
