@@ -162,6 +162,18 @@ constexpr int KV_TILE = BKV * PITCH;  // elements
 // fastest.  With the plain (x, y, z) order the 16 key blocks of a kv head were spread over all XCDs and the
 // dK / dV passes hit L2 on 2 % of their requests.  Falls back to the plain order when the number of
 // groups is not a multiple of 8.
+// Depth of the operand-fragment rings of the three kernels (0 in the dQ kernel: the plain loop).  Measured, backward at
+// 16 x 2048 / 2 x 16384: dQ 0 / dK-dV 4: 3.56 / 21.4 ms; 2 / 4: 3.48 / 21.0; 4 / 4: 3.79 / 22.7 (the dQ kernel is at 256
+// registers: a ring of four makes it spill 84 bytes per lane); 0 / 2: 3.60 / 21.2; before the rings 3.65 / 21.6.
+#ifndef TIDE_ATTN_DQ_RING
+#define TIDE_ATTN_DQ_RING 2
+#endif
+#ifndef TIDE_ATTN_DKV_RING
+#define TIDE_ATTN_DKV_RING 4
+#endif
+#ifndef TIDE_ATTN_KRING
+#define TIDE_ATTN_KRING 4
+#endif
 struct Work3 { int x, y, z; };
 __device__ __forceinline__ Work3 xcd_group_work(int nx, int ny, int nz, int gy) {
   const int n = blockIdx.x;
@@ -229,6 +241,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
   lv.load(rs, 0, ld, vcol, tid);
   lk.store(sK, tid);
   lv.store(sV, tid);
+  // vmcnt(0): nothing of the prologue is in flight inside the loop.  The Q (and dO) fragments are first used there, so
+  // the compiler issues their loads last and, at the loop's head, still counts them as outstanding; inside the loop
+  // the next tile's eight loads are then younger than they are, and the waits it puts in front of the first MFMAs
+  // ("all but 7, 6, ... 0 loads done") make every tile wait for the tile after it to arrive from memory.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
 
   for (int t = 0; t < nt; ++t) {
@@ -243,11 +260,23 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
       const bf16_t* V = sV + st * KV_TILE;
       f32x16_t s[2];
 #pragma unroll
-      for (int jt = 0; jt < 2; ++jt) {
+      for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
         for (int q = 0; q < 16; ++q) s[jt][q] = 0.f;
+      {
+        // the 16 K fragments of the tile through a ring of TIDE_ATTN_KRING registers sets: a fragment is requested
+        // that many MFMAs before its own (read, wait, MFMA one after the other leaves the LDS latency, three
+        // MFMA times, exposed at every step)
+        constexpr int RING = TIDE_ATTN_KRING;
+        u32x4_t kb[RING];
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) s[jt] = mfma(frag(K, jt * 32, plr, kk * 16 + g * 8), qf[kk], s[jt]);
+        for (int i = 0; i < RING; ++i) kb[i] = frag(K, (i >> 3) * 32, plr, (i & 7) * 16 + g * 8);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          s[i >> 3] = mfma(kb[i % RING], qf[i & 7], s[i >> 3]);
+          if (i + RING < 16) kb[i % RING] = frag(K, ((i + RING) >> 3) * 32, plr, ((i + RING) & 7) * 16 + g * 8);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       if (j0 + BKV - 1 > qw) {  // the tile touches the diagonal of this wave
 #pragma unroll
@@ -356,6 +385,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
   lv.load(rs, 0, ld, vcol, tid);
   lk.store(sK, tid);
   lv.store(sV, tid);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): nothing of the prologue is in flight inside the loop (see the forward kernel)
   __syncthreads();
 
   for (int t = 0; t < nt; ++t) {
@@ -375,11 +405,29 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
         f32x16_t s, dp;
 #pragma unroll
         for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
+#if TIDE_ATTN_DQ_RING == 0
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
           s = mfma(frag(K, jt * 32, plr, kk * 16 + g * 8), qf[kk], s);
           dp = mfma(frag(V, jt * 32, plr, kk * 16 + g * 8), dof[kk], dp);
         }
+#else
+        {
+          // K and V fragments alternately through a ring, each requested TIDE_ATTN_DQ_RING MFMAs ahead (see the forward kernel)
+          constexpr int RING = TIDE_ATTN_DQ_RING;
+          u32x4_t fb[RING];
+          auto fetch = [&](int i) { return frag((i & 1) ? V : K, jt * 32, plr, (i >> 1) * 16 + g * 8); };
+#pragma unroll
+          for (int i = 0; i < RING; ++i) fb[i] = fetch(i);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            if (i & 1) dp = mfma(fb[i % RING], dof[i >> 1], dp);
+            else s = mfma(fb[i % RING], qf[i >> 1], s);
+            if (i + RING < 16) fb[i % RING] = fetch(i + RING);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+#endif
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
           float p = __builtin_amdgcn_exp2f(s[q] * c - lse_i);
@@ -485,6 +533,7 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
 
   gload(0);
   sstore(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the K / V fragments have arrived before the loop, see the forward kernel
   __syncthreads();
   for (int u = 0; u < ntiles; ++u) {
     const int st = u & 1;
@@ -497,10 +546,27 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
       f32x16_t s, dp;
 #pragma unroll
       for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
+      {
+        // Q (and, in the dK pass, dO) fragments through a ring, each requested TIDE_ATTN_DKV_RING MFMAs ahead
+        constexpr int RING = TIDE_ATTN_DKV_RING, NF = DK ? 16 : 8;
+        u32x4_t fb[RING];
+        auto fetch = [&](int i) {
+          if constexpr (DK) return frag((i & 1) ? dOt : Qt, 0, plr, (i >> 1) * 16 + g * 8);
+          else return frag(Qt, 0, plr, i * 16 + g * 8);
+        };
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        s = mfma(frag(Qt, 0, plr, kk * 16 + g * 8), kf[kk], s);
-        if constexpr (DK) dp = mfma(frag(dOt, 0, plr, kk * 16 + g * 8), vf[kk], dp);
+        for (int i = 0; i < RING; ++i) fb[i] = fetch(i);
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
+          if constexpr (DK) {
+            if (i & 1) dp = mfma(fb[i % RING], vf[i >> 1], dp);
+            else s = mfma(fb[i % RING], kf[i >> 1], s);
+          } else {
+            s = mfma(fb[i % RING], kf[i], s);
+          }
+          if (i + RING < NF) fb[i % RING] = fetch(i + RING);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       const bool diag = i0 < jw + 32;  // some (query, key) pair of the tile is above the diagonal
 #pragma unroll
