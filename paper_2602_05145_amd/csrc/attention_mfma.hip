@@ -123,6 +123,48 @@ struct TileLoader {
   }
 };
 
+// The same staging WITHOUT registers: LDS-DMA loads (16 bytes per lane straight into LDS, written as instructions so
+// that the waits are this file's own: the compiler does not see that they write LDS).  A 64-row tile with its 272-byte
+// pitch is 17 chunks of 1 KiB of consecutive LDS bytes; wave w issues the chunks w, w + 4, ... and lane l of chunk c
+// fills the bytes c * 1024 + 16 l .. + 16, i.e. LDS row (c * 1024 + 16 l) / 272 = tile row perm(LDS row), 16-byte
+// piece ((c * 1024 + 16 l) % 272) / 16; the 17th piece of a row is its padding and loads from beyond the buffer
+// (zeros).  Rows past the end of the sequence lie beyond the buffer as well.
+__device__ __forceinline__ i32x4_t rsrc_words(const void* base, uint32_t bytes) {
+  const uint64_t a = (uint64_t)base;
+  i32x4_t r;
+  r[0] = (int)(uint32_t)a; r[1] = (int)((uint32_t)(a >> 32) & 0xffffu); r[2] = (int)bytes; r[3] = 0x00020000;
+  return r;
+}
+__device__ __forceinline__ void dma16(i32x4_t rs, uint32_t lds_addr, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(rs) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const bf16_t* p) {
+  typedef __attribute__((address_space(3))) const bf16_t* lds_p;
+  return (uint32_t)(uintptr_t)(lds_p)p;
+}
+struct TileDma {
+  static constexpr int CHUNKS = 64 * PITCH * 2 / 1024;   // 17
+  static constexpr int PER_WAVE = (CHUNKS + 3) / 4;      // 5 (the fifth only in wave 0)
+  uint32_t voff[PER_WAVE];   // byte offset of the lane's piece from the tile's first element (beyond any buffer: padding)
+  __device__ __forceinline__ void init(int ld, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+      const int o = (wave + 4 * i) * 1024 + lane * 16;
+      const int R = o / (PITCH * 2), piece = (o % (PITCH * 2)) / 16;
+      // 2^31 plus any offset inside a sequence (below 2^31, see attn_mfma_supported) stays beyond the buffer and does not wrap
+      voff[i] = piece < 16 ? (uint32_t)(perm(R) * ld + piece * 8) * 2u : 0x80000000u;
+    }
+  }
+  // tile_bytes: byte offset of the tile's first element in the buffer; wave_s: the wave index as a scalar
+  __device__ __forceinline__ void issue(i32x4_t rs, const bf16_t* tile, uint32_t tile_bytes, int wave_s) const {
+    const uint32_t base = lds_address(tile);
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i)
+      if (wave_s + 4 * i < CHUNKS) dma16(rs, base + (uint32_t)(wave_s + 4 * i) * 1024u, voff[i] + tile_bytes);
+  }
+};
+#define TIDE_ATTN_WAIT_DMA() __builtin_amdgcn_s_waitcnt(0x0F70)   /* vmcnt(0) */
+
 // Write a wave's 32 x 128 result, held transposed in 4 accumulators (acc[ct] = rows ct*32.., column =
 // lane % 32 = the wave-local output row), into an LDS tile [128][PITCH] at rows wave*32.. as bf16.
 __device__ __forceinline__ void stage_out(bf16_t* tile, const f32x16_t (&acc)[4], float mul, int wave, int lane) {
@@ -236,11 +278,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
 
   const int kv_end = min(S, q0 + BQ);
   const int nt = (kv_end + BKV - 1) / BKV;
-  TileLoader<4> lk, lv;
-  lk.load(rs, 0, ld, kcol, tid);
-  lv.load(rs, 0, ld, vcol, tid);
-  lk.store(sK, tid);
-  lv.store(sV, tid);
+  const i32x4_t rsw = rsrc_words(base, (uint32_t)((size_t)S * ld * 2));
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  TileDma dma;
+  dma.init(ld, wave, lane);
+  dma.issue(rsw, sK, (uint32_t)kcol * 2u, wave_s);
+  dma.issue(rsw, sV, (uint32_t)vcol * 2u, wave_s);
   // vmcnt(0): nothing of the prologue is in flight inside the loop.  The Q (and dO) fragments are first used there, so
   // the compiler issues their loads last and, at the loop's head, still counts them as outstanding; inside the loop
   // the next tile's eight loads are then younger than they are, and the waits it puts in front of the first MFMAs
@@ -251,9 +294,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
   for (int t = 0; t < nt; ++t) {
     const int st = t & 1;
     const int j0 = t * BKV;
-    if (t + 1 < nt) {
-      lk.load(rs, j0 + BKV, ld, kcol, tid);
-      lv.load(rs, j0 + BKV, ld, vcol, tid);
+    if (t + 1 < nt) {   // the next tile, into the stage whose last readers passed the barrier at the end of the step before
+      const uint32_t row_bytes = (uint32_t)(j0 + BKV) * (uint32_t)ld * 2u;
+      dma.issue(rsw, sK + (st ^ 1) * KV_TILE, row_bytes + (uint32_t)kcol * 2u, wave_s);
+      dma.issue(rsw, sV + (st ^ 1) * KV_TILE, row_bytes + (uint32_t)vcol * 2u, wave_s);
     }
     if (j0 <= qw + 31) {  // wave-uniform: the tile has at least one unmasked key for this wave
       const bf16_t* K = sK + st * KV_TILE;
@@ -320,10 +364,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) o[ct] = mfma(frag_tr(V, ks * 16, ct * 32, lane), pf[ks], o[ct]);
     }
-    if (t + 1 < nt) {
-      lk.store(sK + (st ^ 1) * KV_TILE, tid);
-      lv.store(sV + (st ^ 1) * KV_TILE, tid);
-    }
+    TIDE_ATTN_WAIT_DMA();
     __syncthreads();
   }
 
@@ -381,11 +422,12 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
 
   const int kv_end = min(S, q0 + BQ);
   const int nt = (kv_end + BKV - 1) / BKV;
-  TileLoader<4> lk, lv;
-  lk.load(rs, 0, ld, kcol, tid);
-  lv.load(rs, 0, ld, vcol, tid);
-  lk.store(sK, tid);
-  lv.store(sV, tid);
+  const i32x4_t rsw = rsrc_words(qkv + (size_t)sv.row0 * ld, (uint32_t)((size_t)S * ld * 2));
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  TileDma dma;
+  dma.init(ld, wave, lane);
+  dma.issue(rsw, sK, (uint32_t)kcol * 2u, wave_s);
+  dma.issue(rsw, sV, (uint32_t)vcol * 2u, wave_s);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): nothing of the prologue is in flight inside the loop (see the forward kernel)
   __syncthreads();
 
@@ -393,8 +435,9 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
     const int st = t & 1;
     const int j0 = t * BKV;
     if (t + 1 < nt) {
-      lk.load(rs, j0 + BKV, ld, kcol, tid);
-      lv.load(rs, j0 + BKV, ld, vcol, tid);
+      const uint32_t row_bytes = (uint32_t)(j0 + BKV) * (uint32_t)ld * 2u;
+      dma.issue(rsw, sK + (st ^ 1) * KV_TILE, row_bytes + (uint32_t)kcol * 2u, wave_s);
+      dma.issue(rsw, sV + (st ^ 1) * KV_TILE, row_bytes + (uint32_t)vcol * 2u, wave_s);
     }
     if (j0 <= qw + 31) {
       const bf16_t* K = sK + st * KV_TILE;
@@ -448,10 +491,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) dq[ct] = mfma(frag_tr(K, ks * 16, ct * 32, lane), dsf[ks], dq[ct]);
     }
-    if (t + 1 < nt) {
-      lk.store(sK + (st ^ 1) * KV_TILE, tid);
-      lv.store(sV + (st ^ 1) * KV_TILE, tid);
-    }
+    TIDE_ATTN_WAIT_DMA();
     __syncthreads();
   }
   stage_out(smem, dq, scale, wave, lane);
