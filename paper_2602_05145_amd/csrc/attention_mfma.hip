@@ -567,14 +567,14 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
     if (tid < 64) {
       const int i = i0 + (tid & 31);
       const float* src = (tid < 32) ? lse : delta;
-      stat = (i < S) ? src[stat_index(cu, T, sv, b, hh, nh, Smax, i)] * ((tid < 32) ? kLog2e : 1.f) : 0.f;
+      stat = (i < S) ? src[stat_index(cu, T, sv, b, hh, nh, Smax, i)] : 0.f;   // used in sstore only: the load stays in flight
     }
   };
   auto sstore = [&](int st) {
     bf16_t* base = smem + st * DKV_STAGE;
     lq.store(base, tid);
     ldo_.store(base + Q_TILE, tid);
-    if (tid < 64) reinterpret_cast<float*>(base + 2 * Q_TILE)[tid] = stat;
+    if (tid < 64) reinterpret_cast<float*>(base + 2 * Q_TILE)[tid] = stat * ((tid < 32) ? kLog2e : 1.f);   // lse * log2(e), delta
   };
 
   gload(0);
