@@ -100,31 +100,9 @@ __device__ __forceinline__ u32x4_t pack_half(const f32x16_t& v, int half) {
 // row index (0..31) that accumulator register q of this lane holds
 __device__ __forceinline__ int acc_row(int q, int g) { return 8 * (q >> 2) + 4 * g + (q & 3); }
 
-// Stage `rows` rows x 128 columns (bf16) of a row-major global matrix into an LDS tile through registers.
-// NP = 16-byte pieces per thread (rows * 16 / 256).
-template <int NP>
-struct TileLoader {
-  i32x4_t r[NP];
-  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rs, int row0, int ld, int col0, int tid) {
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      const int p = tid + i * 256;
-      const int row = p >> 4, piece = p & 15;
-      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)(row0 + row) * (uint32_t)ld + (uint32_t)(col0 + piece * 8)) * 2u, 0, 0);
-    }
-  }
-  __device__ __forceinline__ void store(bf16_t* tile, int tid) const {
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      const int p = tid + i * 256;
-      const int row = i * 16 + perm(tid >> 4), piece = p & 15;   // perm(p >> 4)
-      *reinterpret_cast<i32x4_t*>(tile + row * PITCH + piece * 8) = r[i];
-    }
-  }
-};
-
-// The same staging WITHOUT registers: LDS-DMA loads (16 bytes per lane straight into LDS, written as instructions so
-// that the waits are this file's own: the compiler does not see that they write LDS).  A 64-row tile with its 272-byte
+// Staging of a tile of 64 or 32 rows x 128 columns (bf16) of a row-major global matrix in LDS, without registers:
+// LDS-DMA loads (16 bytes per lane straight into LDS, written as instructions so that the waits are this file's
+// own: the compiler does not see that they write LDS).  A 64-row tile with its 272-byte
 // pitch is 17 chunks of 1 KiB of consecutive LDS bytes; wave w issues the chunks w, w + 4, ... and lane l of chunk c
 // fills the bytes c * 1024 + 16 l .. + 16, i.e. LDS row (c * 1024 + 16 l) / 272 = tile row perm(LDS row), 16-byte
 // piece ((c * 1024 + 16 l) % 272) / 16; the 17th piece of a row is its padding and loads from beyond the buffer
@@ -142,9 +120,11 @@ __device__ __forceinline__ uint32_t lds_address(const bf16_t* p) {
   typedef __attribute__((address_space(3))) const bf16_t* lds_p;
   return (uint32_t)(uintptr_t)(lds_p)p;
 }
+template <int ROWS>   // rows of the tile (64, or 32: 8.5 chunks, the second half of the ninth is not part of the tile)
 struct TileDma {
-  static constexpr int CHUNKS = 64 * PITCH * 2 / 1024;   // 17
-  static constexpr int PER_WAVE = (CHUNKS + 3) / 4;      // 5 (the fifth only in wave 0)
+  static constexpr int BYTES = ROWS * PITCH * 2;
+  static constexpr int CHUNKS = (BYTES + 1023) / 1024;   // 17 / 9
+  static constexpr int PER_WAVE = (CHUNKS + 3) / 4;      // 5 / 3 (the last only in wave 0)
   uint32_t voff[PER_WAVE];   // byte offset of the lane's piece from the tile's first element (beyond any buffer: padding)
   __device__ __forceinline__ void init(int ld, int wave, int lane) {
 #pragma unroll
@@ -152,7 +132,7 @@ struct TileDma {
       const int o = (wave + 4 * i) * 1024 + lane * 16;
       const int R = o / (PITCH * 2), piece = (o % (PITCH * 2)) / 16;
       // 2^31 plus any offset inside a sequence (below 2^31, see attn_mfma_supported) stays beyond the buffer and does not wrap
-      voff[i] = piece < 16 ? (uint32_t)(perm(R) * ld + piece * 8) * 2u : 0x80000000u;
+      voff[i] = (piece < 16 && o < BYTES) ? (uint32_t)(perm(R) * ld + piece * 8) * 2u : 0x80000000u;
     }
   }
   // tile_bytes: byte offset of the tile's first element in the buffer; wave_s: the wave index as a scalar
@@ -280,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16_t* __r
   const int nt = (kv_end + BKV - 1) / BKV;
   const i32x4_t rsw = rsrc_words(base, (uint32_t)((size_t)S * ld * 2));
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  TileDma dma;
+  TileDma<64> dma;
   dma.init(ld, wave, lane);
   dma.issue(rsw, sK, (uint32_t)kcol * 2u, wave_s);
   dma.issue(rsw, sV, (uint32_t)vcol * 2u, wave_s);
@@ -424,7 +404,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
   const int nt = (kv_end + BKV - 1) / BKV;
   const i32x4_t rsw = rsrc_words(qkv + (size_t)sv.row0 * ld, (uint32_t)((size_t)S * ld * 2));
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  TileDma dma;
+  TileDma<64> dma;
   dma.init(ld, wave, lane);
   dma.issue(rsw, sK, (uint32_t)kcol * 2u, wave_s);
   dma.issue(rsw, sV, (uint32_t)vcol * 2u, wave_s);
@@ -503,9 +483,19 @@ __global__ __launch_bounds__(256, 2) void attn_dq_mfma_kernel(const bf16_t* __re
 // backward, dK and dV
 // ------------------------------------------------------------------------------------------------
 namespace {
-constexpr int BI = 32;                          // query rows per streamed tile
-constexpr int Q_TILE = BI * PITCH;              // elements
-constexpr int DKV_STAGE = 2 * Q_TILE + 2 * 64;  // Q tile, dO tile, then lse[32] and delta[32] as floats
+// Query rows per streamed tile (32 or 64: two halves of 32 between two barriers) of the dV and of the dK pass.
+// Measured, backward at 16 x 2048 / 2 x 16384 (dV rows / dK rows): 32 / 32: 3.18 / 18.2 ms; 32 / 64: 3.08 / 18.0;
+// 64 / 32: 3.14 / 18.7; 64 / 64: 3.09 / 18.5 (with 64 rows the dV pass loses its third block per CU to the LDS).
+#ifndef TIDE_ATTN_DV_ROWS
+#define TIDE_ATTN_DV_ROWS 32
+#endif
+#ifndef TIDE_ATTN_DK_ROWS
+#define TIDE_ATTN_DK_ROWS 64
+#endif
+template <int BI> struct DkvStage {
+  static constexpr int Q_TILE = TileDma<BI>::CHUNKS * 512;   // elements: the tile rounded up to whole 1 KiB chunks of the LDS-DMA loads
+  static constexpr int STAGE = 2 * Q_TILE + 4 * BI;          // Q tile, dO tile, then lse[BI] and delta[BI] as floats
+};
 }  // namespace
 
 // One gradient per pass (WHICH = 0: dV, 1: dK).  Half the accumulators and, for dV, half the operand
@@ -528,12 +518,13 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
   const int j0 = jb * 128, jw = j0 + wave * 32, jk = jw + lr;
   if (j0 >= S) return;   // the whole block, before any barrier
   const __amdgpu_buffer_rsrc_t rs = rsrc(qkv + (size_t)sv.row0 * ld, (uint32_t)((size_t)S * ld * 2));
-  const __amdgpu_buffer_rsrc_t rso = rsrc(dout + (size_t)sv.row0 * ldo, (uint32_t)((size_t)S * ldo * 2));
   const int kcol = (nh + kh) * D, vcol = (nh + nkv + kh) * D;
   const float scale = 1.0f / sqrtf((float)D);
   const float c = kLog2e * scale;
 
   constexpr bool DK = WHICH == 1;
+  constexpr int BI = DK ? TIDE_ATTN_DK_ROWS : TIDE_ATTN_DV_ROWS;
+  constexpr int Q_TILE = DkvStage<BI>::Q_TILE, DKV_STAGE = DkvStage<BI>::STAGE;
   u32x4_t kf[8], vf[DK ? 8 : 1];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
@@ -550,8 +541,13 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
   const int nit = (S - i_begin + BI - 1) / BI;         // query tiles per head
   const int ntiles = G * nit;
 
-  TileLoader<2> lq, ldo_;
-  float stat = 0.f;  // threads 0..31 carry lse, 32..63 carry delta of the staged tile
+  const i32x4_t rsq = rsrc_words(qkv + (size_t)sv.row0 * ld, (uint32_t)((size_t)S * ld * 2));
+  const i32x4_t rsdo = rsrc_words(dout + (size_t)sv.row0 * ldo, (uint32_t)((size_t)S * ldo * 2));
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  TileDma<BI> dmq, dmo;   // LDS-DMA loads of the Q and the dO tile (their row pitches in memory differ)
+  dmq.init(ld, wave, lane);
+  dmo.init(ldo, wave, lane);
+  float stat = 0.f;  // threads 0..BI-1 carry lse, BI..2BI-1 carry delta of the staged tile
   // Query tiles are walked from the END of the sequence down to the first one that sees this block's keys: the key
   // blocks of a kv head run side by side on one XCD, and this way all of them want the same Q / dO tile at about
   // the same time (walking up from each block's own first tile, they were spread over the whole sequence and the
@@ -559,36 +555,38 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
   // (and tile by tile over the G query heads, not head by head: blocks with fewer tiles would otherwise move on
   // to the next head early)
   auto tile_i0 = [&](int u) { return i_begin + (nit - 1 - u / G) * BI; };
-  auto gload = [&](int u) {
+  auto gload = [&](int u, int st) {   // tile u into stage st (whose last readers have passed a barrier)
     const int hh = kh * G + u % G;
     const int i0 = tile_i0(u);
-    lq.load(rs, i0, ld, hh * D, tid);
-    ldo_.load(rso, i0, ldo, hh * D, tid);
-    if (tid < 64) {
-      const int i = i0 + (tid & 31);
-      const float* src = (tid < 32) ? lse : delta;
+    bf16_t* base = smem + st * DKV_STAGE;
+    dmq.issue(rsq, base, ((uint32_t)i0 * (uint32_t)ld + (uint32_t)(hh * D)) * 2u, wave_s);
+    dmo.issue(rsdo, base + Q_TILE, ((uint32_t)i0 * (uint32_t)ldo + (uint32_t)(hh * D)) * 2u, wave_s);
+    if (tid < 2 * BI) {
+      const int i = i0 + (tid & (BI - 1));
+      const float* src = (tid < BI) ? lse : delta;
       stat = (i < S) ? src[stat_index(cu, T, sv, b, hh, nh, Smax, i)] : 0.f;   // used in sstore only: the load stays in flight
     }
   };
   auto sstore = [&](int st) {
     bf16_t* base = smem + st * DKV_STAGE;
-    lq.store(base, tid);
-    ldo_.store(base + Q_TILE, tid);
-    if (tid < 64) reinterpret_cast<float*>(base + 2 * Q_TILE)[tid] = stat * ((tid < 32) ? kLog2e : 1.f);   // lse * log2(e), delta
+    if (tid < 2 * BI) reinterpret_cast<float*>(base + 2 * Q_TILE)[tid] = stat * ((tid < BI) ? kLog2e : 1.f);   // lse * log2(e), delta
   };
 
-  gload(0);
+  gload(0, 0);
   sstore(0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the K / V fragments have arrived before the loop, see the forward kernel
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the tile and the K / V fragments have arrived before the loop
   __syncthreads();
   for (int u = 0; u < ntiles; ++u) {
     const int st = u & 1;
-    if (u + 1 < ntiles) gload(u + 1);
-    const int i0 = tile_i0(u);
-    if (i0 + BI - 1 >= jw) {  // wave-uniform: some query of the tile sees some key of this wave
+    if (u + 1 < ntiles) gload(u + 1, st ^ 1);
+    const int it0 = tile_i0(u);
+#pragma unroll
+    for (int hf = 0; hf < BI / 32; ++hf) {
+    const int i0 = it0 + hf * 32;   // this half's first query
+    if (i0 + 31 >= jw && i0 < S) {  // wave-uniform: some query of the half sees some key of this wave
       const bf16_t* Qt = smem + st * DKV_STAGE;
       const bf16_t* dOt = Qt + Q_TILE;
-      const float* stats = reinterpret_cast<const float*>(Qt + 2 * Q_TILE);
+      const float* stats = reinterpret_cast<const float*>(Qt + 2 * Q_TILE) + hf * 32;
       f32x16_t s, dp;
 #pragma unroll
       for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
@@ -597,8 +595,8 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
         constexpr int RING = TIDE_ATTN_DKV_RING, NF = DK ? 16 : 8;
         u32x4_t fb[RING];
         auto fetch = [&](int i) {
-          if constexpr (DK) return frag((i & 1) ? dOt : Qt, 0, plr, (i >> 1) * 16 + g * 8);
-          else return frag(Qt, 0, plr, i * 16 + g * 8);
+          if constexpr (DK) return frag((i & 1) ? dOt : Qt, hf * 32, plr, (i >> 1) * 16 + g * 8);
+          else return frag(Qt, hf * 32, plr, i * 16 + g * 8);
         };
 #pragma unroll
         for (int i = 0; i < RING; ++i) fb[i] = fetch(i);
@@ -618,7 +616,7 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
 #pragma unroll
       for (int qq = 0; qq < 4; ++qq) {
         const float4 l4 = *reinterpret_cast<const float4*>(stats + 8 * qq + 4 * g);   // lse * log2(e), see sstore
-        const float4 d4 = *reinterpret_cast<const float4*>(stats + 32 + 8 * qq + 4 * g);
+        const float4 d4 = *reinterpret_cast<const float4*>(stats + BI + 8 * qq + 4 * g);
         const float lv4[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -636,9 +634,11 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) dacc[ct] = mfma(frag_tr(Xt, ks * 16, ct * 32, lane), pf[ks], dacc[ct]);
+        for (int ks = 0; ks < 2; ++ks) dacc[ct] = mfma(frag_tr(Xt, hf * 32 + ks * 16, ct * 32, lane), pf[ks], dacc[ct]);
+    }
     }
     if (u + 1 < ntiles) sstore(st ^ 1);
+    TIDE_ATTN_WAIT_DMA();
     __syncthreads();
   }
   const int64_t r0 = sv.row0 + j0, r1 = sv.row0 + min(S, j0 + 128);
@@ -661,9 +661,12 @@ bool attn_mfma_supported(const AttnArgs& a) {
 
 namespace {
 constexpr size_t kFwdSmem = (size_t)4 * KV_TILE * sizeof(bf16_t);           // 69632 B (>= the 128 x PITCH output tile)
-constexpr size_t kDkvSmemStages = (size_t)2 * DKV_STAGE * sizeof(bf16_t);
 constexpr size_t kOutTile = (size_t)128 * PITCH * sizeof(bf16_t);
-constexpr size_t kDkvSmem = kDkvSmemStages > kOutTile ? kDkvSmemStages : kOutTile;
+constexpr size_t dkv_smem(int bi) {
+  const size_t st = (size_t)2 * (bi == 64 ? DkvStage<64>::STAGE : DkvStage<32>::STAGE) * sizeof(bf16_t);
+  return st > kOutTile ? st : kOutTile;
+}
+constexpr size_t kDvSmem = dkv_smem(TIDE_ATTN_DV_ROWS), kDkSmem = dkv_smem(TIDE_ATTN_DK_ROWS);
 
 hipError_t set_smem(const void* f, size_t bytes, bool& done) {
   if (done) return hipSuccess;
@@ -698,13 +701,13 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
   }
   static bool done_v = false, done_k = false;
-  e = set_smem((const void*)attn_dkv_mfma_kernel<0>, kDkvSmem, done_v);
+  e = set_smem((const void*)attn_dkv_mfma_kernel<0>, kDvSmem, done_v);
   if (e != hipSuccess) return e;
-  e = set_smem((const void*)attn_dkv_mfma_kernel<1>, kDkvSmem, done_k);
+  e = set_smem((const void*)attn_dkv_mfma_kernel<1>, kDkSmem, done_k);
   if (e != hipSuccess) return e;
   ProfScope ps("attn_dkv_mfma", 10.0 * pairs, 0, s);   // dV pass: S, dV; dK pass: S, dP, dK
-  hipLaunchKernelGGL(attn_dkv_mfma_kernel<0>, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows, a.B);
-  hipLaunchKernelGGL(attn_dkv_mfma_kernel<1>, gkv, dim3(256), kDkvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows, a.B);
+  hipLaunchKernelGGL(attn_dkv_mfma_kernel<0>, gkv, dim3(256), kDvSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows, a.B);
+  hipLaunchKernelGGL(attn_dkv_mfma_kernel<1>, gkv, dim3(256), kDkSmem, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.delta, (bf16_t*)a.dqkv, a.S, a.nh, a.nkv, a.cu_seqlens, a.total_rows, a.B);
   return hipGetLastError();
 }
 
