@@ -25,6 +25,8 @@
 // halves need 162 and 222, run 3 and 2 blocks per CU, and together take 0.7x the fused time although
 // S = Q K^T is computed twice.
 // Causality: tiles entirely above the diagonal are never loaded; heavy blocks are scheduled first.
+#include <type_traits>
+
 #include "kernels.h"
 #include "prof.h"
 #include "tide_common.h"
@@ -502,7 +504,7 @@ template <int BI> struct DkvStage {
 // registers of the fused kernel: the pass fits 256 VGPRs, two blocks share a CU, and one block's
 // exponentials overlap the other's MFMAs.  The price is that S = Q K^T is computed in both passes.
 template <int WHICH>
-__global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+__global__ __launch_bounds__(256, (WHICH == 0 ? 3 : 2)) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16_t* __restrict__ dqkv, int Smax, int nh, int nkv,
                                                             const int* __restrict__ cu, int64_t T, int nseq) {
@@ -564,7 +566,8 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
     if (tid < 2 * BI) {
       const int i = i0 + (tid & (BI - 1));
       const float* src = (tid < BI) ? lse : delta;
-      stat = (i < S) ? src[stat_index(cu, T, sv, b, hh, nh, Smax, i)] : 0.f;   // used in sstore only: the load stays in flight
+      // (used in sstore only: the load stays in flight; a row past the sequence gets lse = +inf there, delta = 0)
+      stat = (i < S) ? src[stat_index(cu, T, sv, b, hh, nh, Smax, i)] : ((tid < BI) ? INFINITY : 0.f);
     }
   };
   auto sstore = [&](int st) {
@@ -612,23 +615,28 @@ __global__ __launch_bounds__(256, 2) void attn_dkv_mfma_kernel(const bf16_t* __r
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      const bool diag = i0 < jw + 32;  // some (query, key) pair of the tile is above the diagonal
+      // Rows past the end of the sequence carry lse = +inf (see sstore), i.e. p = 0 without a test; the causal test is
+      // per element, and only a half that touches the diagonal makes it (wave-uniform branch).
+      const bool diag = i0 < jw + 32;  // some (query, key) pair of the half is above the diagonal
+      auto probs = [&](auto MASK) {
 #pragma unroll
-      for (int qq = 0; qq < 4; ++qq) {
-        const float4 l4 = *reinterpret_cast<const float4*>(stats + 8 * qq + 4 * g);   // lse * log2(e), see sstore
-        const float4 d4 = *reinterpret_cast<const float4*>(stats + BI + 8 * qq + 4 * g);
-        const float lv4[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+        for (int qq = 0; qq < 4; ++qq) {
+          const float4 l4 = *reinterpret_cast<const float4*>(stats + 8 * qq + 4 * g);   // lse * log2(e), see sstore
+          const float4 d4 = *reinterpret_cast<const float4*>(stats + BI + 8 * qq + 4 * g);
+          const float lv4[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int q = qq * 4 + e;
-          const int i = i0 + 8 * qq + 4 * g + e;
-          float p = __builtin_amdgcn_exp2f(s[q] * c - lv4[e]);
-          // (tested per element on every tile: a wave-uniform branch around the tests for the tiles away from the
-          // diagonal and the end of the sequence made both passes 3 % slower)
-          if (i >= S || (diag && i < jk)) p = 0.f;
-          s[q] = DK ? p * (dp[q] - dv4[e]) : p;   // dS for the dK pass, P for the dV pass
+          for (int e = 0; e < 4; ++e) {
+            const int q = qq * 4 + e;
+            float p = __builtin_amdgcn_exp2f(s[q] * c - lv4[e]);
+            if constexpr (decltype(MASK)::value) {
+              if (i0 + 8 * qq + 4 * g + e < jk) p = 0.f;
+            }
+            s[q] = DK ? p * (dp[q] - dv4[e]) : p;   // dS for the dK pass, P for the dV pass
+          }
         }
-      }
+      };
+      if (diag) probs(std::true_type{});
+      else probs(std::false_type{});
       const u32x4_t pf[2] = {pack_half(s, 0), pack_half(s, 1)};
       const bf16_t* Xt = DK ? Qt : dOt;   // dK += dS^T Q, dV += P^T dO
 #pragma unroll
