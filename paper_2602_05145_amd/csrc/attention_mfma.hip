@@ -17,14 +17,17 @@
 //
 // Tiles.  Forward and dQ: one block = 128 queries of one head (4 waves x 32 queries, Q in registers; capped
 // at 256 VGPRs so that two blocks share a CU and one block's softmax overlaps the other's MFMAs),
-// K/V streamed in 64-key tiles, double buffered through LDS.  dK/dV: one block = 128 keys of one kv
-// head (4 waves x 32 keys, K [and V] in registers), Q/dO streamed in 32-query tiles for each of the G
-// query heads of the group, so dK/dV are summed over the group in registers: no atomics, deterministic.
-// dV and dK are two launches of one template: a fused pass needs 350 registers (K, V fragments and two
-// 32x128 accumulators), i.e. one block per CU with nothing to hide the exponentials behind; the two
-// halves need 162 and 222, run 3 and 2 blocks per CU, and together take 0.7x the fused time although
+// K/V streamed in 64-key tiles, double buffered in LDS.  dK/dV: one block = 128 keys of one kv
+// head (4 waves x 32 keys, K [and V] in registers), Q/dO streamed in tiles of 32 (dV pass) or 64 (dK pass)
+// queries for each of the G query heads of the group, so dK/dV are summed over the group in registers: no
+// atomics, deterministic.  dV and dK are two launches of one template: a fused pass needs 350 registers (K, V
+// fragments and two 32x128 accumulators), i.e. one block per CU with nothing to hide the exponentials behind;
+// the two halves need 168 and 212, run 3 and 2 blocks per CU, and together take 0.7x the fused time although
 // S = Q K^T is computed twice.
-// Causality: tiles entirely above the diagonal are never loaded; heavy blocks are scheduled first.
+// Every streamed tile reaches LDS by LDS-DMA loads (no staging registers); operand fragments are read from LDS
+// through small register rings, a few MFMAs ahead of their use.
+// Causality: tiles entirely above the diagonal are never loaded; heavy blocks are scheduled first; the
+// per-element causal test is made only by the (wave-uniformly chosen) tiles that touch the diagonal.
 #include <type_traits>
 
 #include "kernels.h"
