@@ -182,16 +182,10 @@ __device__ __forceinline__ void copy_out(const bf16_t* tile, bf16_t* dst, int64_
 constexpr int BQ = 128, BKV = 64;
 constexpr int KV_TILE = BKV * PITCH;  // elements
 
-// Work item (x, y, z) of an nx * ny * nz problem from the block's place in the 1-D dispatch order.
-// Work-groups go to the 8 XCDs round-robin and every XCD has its own L2.  The blocks of a "group" (all x of gy
-// consecutive y of one z: the query blocks of the heads that share a kv head, or the key blocks of one kv
-// head) stream the same K/V resp. Q/dO rows, so a whole group is given to ONE XCD, group after group, x
-// fastest.  With the plain (x, y, z) order the 16 key blocks of a kv head were spread over all XCDs and the
-// dK / dV passes hit L2 on 2 % of their requests.  Falls back to the plain order when the number of
-// groups is not a multiple of 8.
-// Depth of the operand-fragment rings of the three kernels (0 in the dQ kernel: the plain loop).  Measured, backward at
-// 16 x 2048 / 2 x 16384: dQ 0 / dK-dV 4: 3.56 / 21.4 ms; 2 / 4: 3.48 / 21.0; 4 / 4: 3.79 / 22.7 (the dQ kernel is at 256
-// registers: a ring of four makes it spill 84 bytes per lane); 0 / 2: 3.60 / 21.2; before the rings 3.65 / 21.6.
+// Depth of the operand-fragment rings of the three kernels (0 in the dQ kernel: the plain loop).  Measured when the tiles
+// were still staged through registers, backward at 16 x 2048 / 2 x 16384: dQ 0 / dK-dV 4: 3.56 / 21.4 ms; 2 / 4: 3.48 /
+// 21.0; 4 / 4: 3.79 / 22.7 (the dQ kernel, then at 256 registers, spilled with a ring of four); 0 / 2: 3.60 / 21.2;
+// before the rings 3.65 / 21.6.  With LDS-DMA tile loads (dQ at 233 registers) depths of 2 to 6 measure the same.
 #ifndef TIDE_ATTN_DQ_RING
 #define TIDE_ATTN_DQ_RING 2
 #endif
@@ -201,6 +195,13 @@ constexpr int KV_TILE = BKV * PITCH;  // elements
 #ifndef TIDE_ATTN_KRING
 #define TIDE_ATTN_KRING 4
 #endif
+// Work item (x, y, z) of an nx * ny * nz problem from the block's place in the 1-D dispatch order.
+// Work-groups go to the 8 XCDs round-robin and every XCD has its own L2.  The blocks of a "group" (all x of gy
+// consecutive y of one z: the query blocks of the heads that share a kv head, or the key blocks of one kv
+// head) stream the same K/V resp. Q/dO rows, so a whole group is given to ONE XCD, group after group, x
+// fastest.  With the plain (x, y, z) order the 16 key blocks of a kv head were spread over all XCDs and the
+// dK / dV passes hit L2 on 2 % of their requests.  Falls back to the plain order when the number of
+// groups is not a multiple of 8.
 struct Work3 { int x, y, z; };
 __device__ __forceinline__ Work3 xcd_group_work(int nx, int ny, int nz, int gy) {
   const int n = blockIdx.x;
