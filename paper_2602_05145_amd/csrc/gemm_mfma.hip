@@ -7,7 +7,9 @@
 //   * A block computes a BM x BN tile (256x256 with 8 wavefronts = 2 per SIMD, or 128x128 with 4) with
 //     v_mfma_f32_32x32x16_bf16; a wave owns TM x TN MFMA tiles (4x2 or 2x2).  Two waves per SIMD matter:
 //     one wave alone cannot issue MFMAs back to back (measured ~83 % of the multi-wave MFMA rate), and a
-//     four-wave 256x256 variant (128x128 per wave, less LDS traffic) measured 10-20 % slower.
+//     four-wave 256x256 variant (128x128 per wave, a third less LDS read traffic) is slower: 10-20 % under the
+//     compiler's schedule, and still 2.5 % (NT), 3 % (NN) and 8 % (TN) with the pinned schedule of the
+//     16x16x32 kernel below (its WAVES_N = 2 instantiation: 256 accumulator registers in AGPRs, no spills).
 //   * K is walked in slabs through an LDS ring that always holds 128 k-columns and is filled by LDS-DMA
 //     buffer loads (global -> LDS without passing through registers, hardware zero-fill outside the valid
 //     extent, so ragged M / N / K need no special code).  What bounds this kernel is the memory side: with
@@ -658,15 +660,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
 // schedule is one k32 step of four of its A fragments against its four B fragments: 16 MFMAs (256 clocks, as the
 // 8 MFMAs of a k16 quarter above), with the A fragments double-buffered per quarter and the B fragments per k32
 // step.  The MFMAs take the B fragment first, so accumulator element q of lane l in tile (i, j) is row
-// 16 i + (l & 15), column 16 j + 4 (l >> 4) + q (see the epilogue).
+// 16 i + (l & 15), column 16 j + 4 (l >> 4) + q (see the epilogue).  WAVES_N = 4 is the layout in use; with
+// WAVES_N = 2 the block has four waves of 128 x 128 (one per SIMD), kept as the measured alternative.
 // ------------------------------------------------------------------------------------------------
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-template <bool AMM, bool BNM, typename TO, int BK>
-__global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
-  constexpr int BM = 256, BN = 256, NW = 8;
+template <bool AMM, bool BNM, typename TO, int BK, int WAVES_N>
+__global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParams p) {
+  constexpr int BM = 256, BN = 256, WAVES_M = 2, NW = WAVES_M * WAVES_N;
   static_assert(BK == 32 || BK == 64, "slab depth");
-  constexpr int WAVES_N = 4, WAVES_M = 2;
+  static_assert(WAVES_N == 4 || WAVES_N == 2, "eight waves of 128 x 64 or four of 128 x 128");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // 128 x 64
   constexpr int TM = WM / 16, TN = WN / 16;             // 8 x 4 tiles of 16 x 16
   constexpr int GA = 4;                                 // A fragments per quarter
@@ -1068,9 +1071,11 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
       if (kt + 5 < nk) step(Int<2>{}, Int<1>{}, Int<0>{}, Int<0>{}, Int<1>{}, kt + 5);
     }
     TIDE_WAIT_VMCNT(0);   // dummy slabs still in flight write LDS: let them land before the patches are written
-    static_assert(3 * kPatchElems <= A_STAGE, "three epilogue patches per unit");
-    bf16_t* unit = wave < 3 ? ld0 : (wave < 6 ? ld1 : ld2);
-    epilogue(unit + (wave % 3) * kPatchElems);
+    constexpr int PPU = A_STAGE / kPatchElems;   // epilogue patches per unit
+    static_assert(PPU >= 1 && (NW + PPU - 1) / PPU <= 4, "the epilogue patches fit four units");
+    const int pu = wave / PPU;
+    bf16_t* unit = pu == 0 ? ld0 : (pu == 1 ? ld1 : (pu == 2 ? ld2 : ls0));
+    epilogue(unit + (wave % PPU) * kPatchElems);
   } else {
     // ---- four stages of 32: one k32 step of two quarters per slab; the barrier sits between them ----
     constexpr int NST = 4;
@@ -1116,9 +1121,11 @@ __global__ __launch_bounds__(512) void gemm_mfma16_kernel(MfmaParams p) {
       step(Int<3>{}, Int<0>{}, Int<2>{}, kt + 3, fb1, fb0);
     }
     TIDE_WAIT_VMCNT(0);
-    static_assert(2 * kPatchElems <= A_STAGE + B_STAGE, "two epilogue patches per stage");
-    bf16_t* st = wave < 2 ? s0 : (wave < 4 ? s1 : (wave < 6 ? s2 : s3));
-    epilogue(st + (wave & 1) * kPatchElems);
+    constexpr int PPS = NW / 4;   // epilogue patches per stage
+    static_assert(PPS * kPatchElems <= A_STAGE + B_STAGE, "the epilogue patches fit the stages");
+    const int ps = wave / PPS;
+    bf16_t* st = ps == 0 ? s0 : (ps == 1 ? s1 : (ps == 2 ? s2 : s3));
+    epilogue(st + (wave % PPS) * kPatchElems);
   }
 }
 
@@ -1237,7 +1244,11 @@ hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
     q.tiles_n = (p.N + 255) / 256;
     const int tiles = q.tiles_m * q.tiles_n;
     const int items = q.split_s > 1 ? q.split_full + (tiles - q.split_full) * q.split_s : tiles;
-    hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK>), dim3((unsigned)items), dim3(512), 0, s, q);
+#ifndef TIDE_GEMM_WAVES_N
+#define TIDE_GEMM_WAVES_N 4
+#endif
+    constexpr int WAVES_N = TIDE_GEMM_WAVES_N;
+    hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK, WAVES_N>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
     return hipGetLastError();
   }
 #endif
