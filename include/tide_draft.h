@@ -90,7 +90,8 @@ typedef struct tide_draft_config {
    * gradient); the forward product, the row statistics, the logit gradient and the input-gradient product run
    * block by block, and dW_lm accumulates over the blocks.
    *   lm_block_rows      rows per block; 0 = the library's choice (half of batch*seq rounded up to 64, at most
-   *                      16384 rows and 6 GiB of logits).  Other values are rounded up to a multiple of 64.
+   *                      16384 rows and 6 GiB of logits, at least min(batch*seq, 4096) rows).  Other values are
+   *                      rounded up to a multiple of 64.
    *   lm_keep_all_rows   0 (default) = as above, the logit buffer is one block.  Non-zero = opt-in: the buffer
    *                      holds the bf16 logit GRADIENT of every block until the end of the LM head and dW_lm is
    *                      one product over all rows, which saves the read-modify-write of dW_lm per further

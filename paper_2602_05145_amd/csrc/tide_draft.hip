@@ -3,6 +3,7 @@
 // step runs in the kernels of this directory.
 #include "../../include/tide_draft.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -101,11 +102,13 @@ Plan make_plan(const tide_draft_config* c) {
   p.ldz = (int64_t)align_up((size_t)p.V, 64);
   p.es = c->dtype == TIDE_DTYPE_BF16 ? 2 : 4;
   // The LM head works by blocks of lm_rows rows: half of the batch, at most 16384 rows (the forward and the
-  // input-gradient products measured faster at that height than over all rows at once) and 6 GiB of logits.
+  // input-gradient products measured faster at that height than over all rows at once) and 6 GiB of logits,
+  // but not fewer than 4096 rows (a batch that small is one block: a second block would cost another pass
+  // over dW_lm and another set of launches for a few hundred rows).
   // The logit buffer holds ONE block: logits never exist for more rows than that, and dW_lm accumulates block
   // by block.  With cfg->lm_keep_all_rows it holds all rows instead: the logit gradients of every block are
   // then still there after the loop and dW_lm is one product over all of them.
-  int64_t rows = c->lm_block_rows > 0 ? (int64_t)c->lm_block_rows : (p.T + 1) / 2;
+  int64_t rows = c->lm_block_rows > 0 ? (int64_t)c->lm_block_rows : std::max<int64_t>((p.T + 1) / 2, std::min<int64_t>(p.T, 4096));
   rows = (int64_t)align_up((size_t)rows, 64);
   if (c->lm_block_rows <= 0) {
     if (rows > 16384) rows = 16384;

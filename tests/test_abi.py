@@ -43,6 +43,9 @@ def test_workspace_sizes_and_config_validation(B):
         assert B.tide_draft_workspace_bytes(c) > 0, name
     c = B.make_config(W.get_config("8b"))
     assert B.tide_draft_workspace_offset(c, "lm_rows") == 16384       # the LM head works by blocks of half the rows
+    assert B.tide_draft_workspace_offset(B.make_config(W.get_config("small")), "lm_rows") == 4096   # ... of at least 4096
+    assert B.tide_draft_workspace_offset(B.make_config(W.get_config("small", batch=12)), "lm_rows") == 4096
+    assert B.tide_draft_workspace_offset(B.make_config(W.get_config("small", batch=20)), "lm_rows") == 5120
     assert B.tide_draft_workspace_offset(c, "nonsense") == -1
     bad = [("n_heads", 3, "multiple"), ("hidden", 250, "hidden"), ("head_dim", 63, "hidden"),
            ("vocab", 0, "positive"), ("dtype", 7, "dtype"), ("rms_eps", 0.0, "rms_eps"), ("batch", -1, "positive")]

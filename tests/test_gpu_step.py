@@ -280,18 +280,18 @@ def test_training_raises_held_out_accuracy_on_learnable_labels():
 
 
 def test_keeping_all_logit_gradients_gives_the_same_step():
-    """By default the logit buffer holds one row block and dW_lm accumulates block by block; with lm_keep_all_rows
-    it holds the logit gradients of all rows and dW_lm is one product.  Same loss, the same gradients up to the
-    summation order of dW_lm, a larger workspace; small forced blocks (several per batch, a ragged last one)
-    agree as well."""
+    """The logit buffer holds one row block and dW_lm accumulates block by block; with lm_keep_all_rows it holds
+    the logit gradients of all rows and dW_lm is one product.  Same loss, the same gradients up to the summation
+    order of dW_lm, a larger workspace; the library's own block height (one block for a batch this small) and
+    small forced blocks (several per batch, a ragged last one) agree as well."""
     from paper_2602_05145_amd import runtime
     kw = dict(batch=2, seq=200, target_hidden=64, hidden=256, n_heads=2, n_kv_heads=1, head_dim=128, ffn=264, vocab=1000)
     cfg = W.get_config("small", **kw)
     wl = W.make_workload(cfg)
-    blockwise = runtime.trainer_from_workload(cfg, wl)
+    blockwise = runtime.trainer_from_workload(W.get_config("small", **kw, lm_block_rows=256), wl)   # two blocks
     blockwise.train_step(cfg["lr"])
     sync()
-    for extra in (dict(lm_keep_all_rows=1), dict(lm_block_rows=64), dict(lm_block_rows=100, lm_keep_all_rows=1)):
+    for extra in (dict(), dict(lm_keep_all_rows=1), dict(lm_block_rows=64), dict(lm_block_rows=100, lm_keep_all_rows=1)):
         other = runtime.trainer_from_workload(W.get_config("small", **kw, **extra), wl)
         if extra.get("lm_keep_all_rows"):
             assert other.ws_bytes > blockwise.ws_bytes
