@@ -211,6 +211,21 @@ struct Operand {
     }
     return d;
   }
+  // When every slab is whole (K a multiple of BK), a K-major operand needs no per-lane test and no per-lane k
+  // offset either: the slab's k0 goes into the descriptor's base (and shortens its extent by as much, so the row
+  // bound stays where it was), a dummy slab gets an empty extent, and the lane offsets are loop constants.
+  static __device__ __forceinline__ SlabDesc slab_desc_whole(const bf16_t* tile, int ld, int rows_valid, int cols_left, int k0, int Kc) {
+    if (RMAJ) return slab_desc(tile, ld, rows_valid, cols_left, k0, Kc);
+    SlabDesc d;
+    d.k0 = k0; d.Kc = Kc;
+    const bool live = k0 < Kc;
+    d.rs = make_rsrc_words(tile + (live ? k0 : 0), live ? (uint32_t)(((int64_t)(rows_valid - 1) * ld + Kc - k0) * 2) : 0u);
+    return d;
+  }
+  template <int I>
+  static __device__ __forceinline__ void chunk_whole(const SlabDesc& d, uint32_t unit, const uint32_t (&off)[PER_WAVE], int wave_s) {
+    dma16(d.rs, unit + (uint32_t)((wave_s * PER_WAVE + I) * 1024), off[I]);
+  }
   template <int I>
   static __device__ __forceinline__ void chunk(const SlabDesc& d, uint32_t unit, const uint32_t (&off)[PER_WAVE],
                                                const int (&piece)[PER_WAVE], int wave_s) {
@@ -665,7 +680,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
 // ------------------------------------------------------------------------------------------------
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-template <bool AMM, bool BNM, typename TO, int BK, int WAVES_N>
+template <bool AMM, bool BNM, typename TO, int BK, int WAVES_N, bool KWHOLE>
 __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParams p) {
   constexpr int BM = 256, BN = 256, WAVES_M = 2, NW = WAVES_M * WAVES_N;
   static_assert(BK == 32 || BK == 64, "slab depth");
@@ -961,18 +976,22 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
     auto desc_a = [&](int kt) {
       int pr, k0, Kc;
       slab(kt, pr, k0, Kc);
-      return OpA::slab_desc(pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc);
+      if constexpr (KWHOLE) return OpA::slab_desc_whole(pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc);
+      else return OpA::slab_desc(pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc);
     };
     auto desc_b = [&](int kt) {
       int pr, k0, Kc;
       slab(kt, pr, k0, Kc);
-      return OpB::slab_desc(pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc);
+      if constexpr (KWHOLE) return OpB::slab_desc_whole(pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc);
+      else return OpB::slab_desc(pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc);
     };
     auto dma_a = [&](auto I, const typename OpA::SlabDesc& d, bf16_t* unit) {
-      OpA::template chunk<decltype(I)::value>(d, lds_addr(unit), a_off, a_piece, wave_s);
+      if constexpr (KWHOLE) OpA::template chunk_whole<decltype(I)::value>(d, lds_addr(unit), a_off, wave_s);
+      else OpA::template chunk<decltype(I)::value>(d, lds_addr(unit), a_off, a_piece, wave_s);
     };
     auto dma_b = [&](auto I, const typename OpB::SlabDesc& d, bf16_t* unit) {
-      OpB::template chunk<decltype(I)::value>(d, lds_addr(unit), b_off, b_piece, wave_s);
+      if constexpr (KWHOLE) OpB::template chunk_whole<decltype(I)::value>(d, lds_addr(unit), b_off, wave_s);
+      else OpB::template chunk<decltype(I)::value>(d, lds_addr(unit), b_off, b_piece, wave_s);
     };
     constexpr int NDEEP = DEEPB ? NVB : NVA, NSHAL = DEEPB ? NVA : NVB;
     auto desc_deep = [&](int kt) { if constexpr (DEEPB) return desc_b(kt); else return desc_a(kt); };
@@ -1248,7 +1267,10 @@ hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
 #define TIDE_GEMM_WAVES_N 4
 #endif
     constexpr int WAVES_N = TIDE_GEMM_WAVES_N;
-    hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK, WAVES_N>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
+    // every slab whole (and K known on the host): the DMA loads of a K-major operand take loop-constant lane offsets
+    const bool whole = BK == 64 && !p.k_dev && p.K % BK == 0 && (!p.A2 || p.K2 % BK == 0);
+    if (whole) hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK, WAVES_N, BK == 64>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
+    else hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK, WAVES_N, false>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
     return hipGetLastError();
   }
 #endif

@@ -55,9 +55,12 @@ def test_gemm_bf16_small_tiles(B, layout, shape):
 
 
 @pytest.mark.parametrize("layout", [0, 1, 2])
-def test_gemm_bf16_large_tiles_ragged(B, layout):
-    # >= 200 tiles of 256x256 selects the large-tile kernel; M, N, K all ragged w.r.t. 256 / 64
-    M, N, K = 3720, 3656, 200
+@pytest.mark.parametrize("K", [200, 192, 448])
+def test_gemm_bf16_large_tiles_ragged(B, layout, K):
+    # >= 200 tiles of 256x256 selects the large-tile kernel; M and N ragged w.r.t. 256, K ragged w.r.t. the slab
+    # depth of 64 (200) or a whole number of slabs (192, 448: the path with loop-constant load offsets; 3 slabs
+    # and 7 slabs end in different positions of the ring)
+    M, N = 3720, 3656
     got, ref = _gemm_case(B, layout, M, N, K, "bf16", "fp32", seed=31 + layout, accumulate=True)
     assert rel_max(got, ref) < 2e-5
     got, ref = _gemm_case(B, layout, M, N, K, "bf16", "bf16", seed=41 + layout)
