@@ -14,10 +14,11 @@
 //     buffer loads (global -> LDS without passing through registers, hardware zero-fill outside the valid
 //     extent, so ragged M / N / K need no special code).  What bounds this kernel is the memory side: with
 //     every operand row aliased to one line (all loads hit) the same code runs 25-40 % faster.  The ring
-//     shape follows the operand layout: with a K-major operand the slab is 64 deep (TWO stages): each of
-//     its rows then fetches one whole 128-byte line instead of two 64-byte halves; when both operands are
-//     row-major over K (TN) their rows are contiguous anyway and FOUR stages of 32 win because the loads
-//     of slab k+3 are issued while slab k is multiplied.
+//     shape of the 32x32x16 kernel follows the operand layout: with a K-major operand the slab is 64 deep
+//     (TWO stages): each of its rows then fetches one whole 128-byte line instead of two 64-byte halves;
+//     when both operands are row-major over K (TN) their rows are contiguous anyway and FOUR stages of 32
+//     win because the loads of slab k+3 are issued while slab k is multiplied.  The 16x16x32 kernel (the
+//     one the large launches use) walks slabs of 64 through five units in every layout (see there).
 //   * Synchronisation is manual: one `s_waitcnt vmcnt(n)` (own DMA of the next slab has landed, younger
 //     slabs stay in flight) and one `s_barrier` per slab.  Each stage is its own __shared__ array and every
 //     read address is "array + per-lane offset + constant": the compiler can then tell that the operand
@@ -677,13 +678,18 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(MfmaParams p) {
 // step.  The MFMAs take the B fragment first, so accumulator element q of lane l in tile (i, j) is row
 // 16 i + (l & 15), column 16 j + 4 (l >> 4) + q (see the epilogue).  WAVES_N = 4 is the layout in use; with
 // WAVES_N = 2 the block has four waves of 128 x 128 (one per SIMD), kept as the measured alternative.
+// KWHOLE: every slab of the launch is whole (K, and K2 of a second operand pair, multiples of 64 known on the
+// host).  A K-major operand's loads then need neither the per-lane test "is this piece still inside K" nor a
+// per-lane k offset: k0 moves into the buffer descriptor and the lane offsets are loop constants, which takes
+// three vector instructions per load out of the loop (they compete with the MFMAs for the vector issue port;
+// NT 33.2 -> 32.2 ms and NN 30.1 -> 29.5 ms per training step at the 8B shape).
 // ------------------------------------------------------------------------------------------------
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <bool AMM, bool BNM, typename TO, int BK, int WAVES_N, bool KWHOLE>
 __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParams p) {
   constexpr int BM = 256, BN = 256, WAVES_M = 2, NW = WAVES_M * WAVES_N;
-  static_assert(BK == 32 || BK == 64, "slab depth");
+  static_assert(BK == 64, "slab depth");
   static_assert(WAVES_N == 4 || WAVES_N == 2, "eight waves of 128 x 64 or four of 128 x 128");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // 128 x 64
   constexpr int TM = WM / 16, TN = WN / 16;             // 8 x 4 tiles of 16 x 16
@@ -691,9 +697,7 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
   using OpA = Operand<BM, NW, AMM, WM / 32, BK, 16>;
   using OpB = Operand<BN, NW, BNM, WN / 32, BK, 16>;
   constexpr int A_STAGE = OpA::STAGE, B_STAGE = OpB::STAGE;
-  constexpr int NVA = OpA::PER_WAVE, NVB = OpB::PER_WAVE, NVM = NVA + NVB;
-  constexpr int RA = GA * OpA::kReadsPerFrag16;         // LDS reads of one A group
-  constexpr int RB = TN * OpB::kReadsPerFrag16;         // LDS reads of the B fragments of a k32 step
+  constexpr int NVA = OpA::PER_WAVE, NVB = OpB::PER_WAVE;
   constexpr int NMF = GA * TN;                          // MFMAs per quarter
   typedef __attribute__((address_space(3))) const bf16_t* lds_bf_t;
 
@@ -766,16 +770,6 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
     if (kt >= nk) { k0 = p.K + BK; }
     else if (g >= nk1) { pr = 1; k0 = (g - nk1) * BK; Kc = p.K2; }
   };
-  auto issue_a = [&](bf16_t* unit, int kt) {
-    int pr, k0, Kc;
-    slab(kt, pr, k0, Kc);
-    OpA::issue(unit, pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc, a_off, a_piece, wave);
-  };
-  auto issue_b = [&](bf16_t* unit, int kt) {
-    int pr, k0, Kc;
-    slab(kt, pr, k0, Kc);
-    OpB::issue(unit, pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc, b_off, b_piece, wave);
-  };
   uint32_t a_ro[OpA::NRO16], b_ro[OpB::NRO16];
   OpA::read_offsets16(wave_m * WM, lane, a_ro);
   OpB::read_offsets16(wave_n * WN, lane, b_ro);
@@ -786,16 +780,6 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
   auto frags_b = [&](const bf16_t* unit, int h, u32x4_t (&fb)[TN]) {
     OpB::template frags16<0, TN>((lds_bf_t)unit, h, b_ro, fb);
   };
-  auto mma = [&](auto G, u32x4_t (&fa)[GA], u32x4_t (&fb)[TN]) {
-    constexpr int g0 = decltype(G)::value * GA;
-#pragma unroll
-    for (int i = 0; i < GA; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[g0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fb[j]),
-                                                                 __builtin_bit_cast(bf16x8_t, fa[i]), acc[g0 + i][j], 0, 0, 0);
-  };
-
   // ---- epilogue: needs, per wave, an LDS patch of 32 x (WN + 4) floats that no DMA is writing any more ----
   // The MFMAs are issued with their operands swapped (B fragment first), so an accumulator tile holds the
   // TRANSPOSE of its 16 x 16 block: element q of lane l in tile (i, j) is row m = 16 i + (l & 15), columns
@@ -937,7 +921,7 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
   };
 
   u32x4_t fa0[GA], fa1[GA], fb0[TN], fb1[TN];
-  if constexpr (BK == 64) {
+  {
     // ---- slabs of 64: THREE LDS units for one operand and TWO for the other (5 x 32 KiB = all of the 160 KiB) ----
     // The operand DMA of a slab has to land within one slab time when the ring is two deep on both sides, and
     // a burst of 64 KiB per CU takes about that long to deliver: the matrix pipes then wait for it every slab.
@@ -1095,56 +1079,6 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
     const int pu = wave / PPU;
     bf16_t* unit = pu == 0 ? ld0 : (pu == 1 ? ld1 : (pu == 2 ? ld2 : ls0));
     epilogue(unit + (wave % PPU) * kPatchElems);
-  } else {
-    // ---- four stages of 32: one k32 step of two quarters per slab; the barrier sits between them ----
-    constexpr int NST = 4;
-    const int nk_round = (nk + NST - 1) / NST * NST;
-    __shared__ __attribute__((aligned(1024))) bf16_t s0[A_STAGE + B_STAGE];
-    __shared__ __attribute__((aligned(1024))) bf16_t s1[A_STAGE + B_STAGE];
-    __shared__ __attribute__((aligned(1024))) bf16_t s2[A_STAGE + B_STAGE];
-    __shared__ __attribute__((aligned(1024))) bf16_t s3[A_STAGE + B_STAGE];
-    auto stage = [&](auto ST) -> bf16_t* {
-      if constexpr (decltype(ST)::value == 0) return s0;
-      else if constexpr (decltype(ST)::value == 1) return s1;
-      else if constexpr (decltype(ST)::value == 2) return s2;
-      else return s3;
-    };
-    auto issue = [&](bf16_t* st, int kt) { issue_a(st, kt); issue_b(st + A_STAGE, kt); };
-    issue(s0, 0);
-    issue(s1, 1);
-    issue(s2, 2);
-    TIDE_WAIT_VMCNT(2 * NVM);
-    __builtin_amdgcn_s_barrier();
-    frags_a(s0, 0, Int<0>{}, fa0);
-    frags_b(s0 + A_STAGE, 0, fb0);
-    // slab kt lives in ST (fa0, fbc hold its first quarter's operands), slab kt+1 in SN, slab kt+3 goes to SP
-    auto step = [&](auto ST, auto SN, auto SP, int kt, u32x4_t (&fbc)[TN], u32x4_t (&fbn)[TN]) {
-      frags_a(stage(ST), 0, Int<1>{}, fa1);
-      issue(stage(SP), kt + NST - 1);
-      mma(Int<0>{}, fa0, fbc);
-      sched_slots<NMF, RA, NVM, 0>(std::make_integer_sequence<int, NMF>{});
-      __builtin_amdgcn_sched_barrier(0);
-      TIDE_WAIT_VMCNT(2 * NVM);
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      frags_a(stage(SN), 0, Int<0>{}, fa0);
-      frags_b(stage(SN) + A_STAGE, 0, fbn);
-      mma(Int<1>{}, fa1, fbc);
-      sched_slots<NMF, RA + RB, 0, 1>(std::make_integer_sequence<int, NMF>{});
-      __builtin_amdgcn_sched_barrier(0);
-    };
-    for (int kt = 0; kt < nk_round; kt += 4) {
-      step(Int<0>{}, Int<1>{}, Int<3>{}, kt, fb0, fb1);
-      step(Int<1>{}, Int<2>{}, Int<0>{}, kt + 1, fb1, fb0);
-      step(Int<2>{}, Int<3>{}, Int<1>{}, kt + 2, fb0, fb1);
-      step(Int<3>{}, Int<0>{}, Int<2>{}, kt + 3, fb1, fb0);
-    }
-    TIDE_WAIT_VMCNT(0);
-    constexpr int PPS = NW / 4;   // epilogue patches per stage
-    static_assert(PPS * kPatchElems <= A_STAGE + B_STAGE, "the epilogue patches fit the stages");
-    const int ps = wave / PPS;
-    bf16_t* st = ps == 0 ? s0 : (ps == 1 ? s1 : (ps == 2 ? s2 : s3));
-    epilogue(st + (wave % PPS) * kPatchElems);
   }
 }
 
@@ -1251,11 +1185,9 @@ bool use_big_tiles(int64_t M, int64_t N) { return ((M + 255) / 256) * ((N + 255)
 
 template <bool AMM, bool BNM, typename TO>
 hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
-  // slab depth: 64 (two stages) as soon as one operand is K-major, else 32 (four stages)
-#ifndef TIDE_TN_BK
-#define TIDE_TN_BK 32
-#endif
-  constexpr int BK = (AMM && BNM) ? TIDE_TN_BK : 64;
+  // slab depth of the 32x32x16 kernels: 64 (two stages) as soon as one operand is K-major, else 32 (four stages);
+  // the 16x16x32 kernel walks slabs of 64 in every layout
+  constexpr int BK = (AMM && BNM) ? 32 : 64;
 #ifndef TIDE_BIG_TILE_MFMA32
   if (use_big_tiles(p.M, p.N)) {
     MfmaParams q = p;
@@ -1268,9 +1200,9 @@ hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
 #endif
     constexpr int WAVES_N = TIDE_GEMM_WAVES_N;
     // every slab whole (and K known on the host): the DMA loads of a K-major operand take loop-constant lane offsets
-    const bool whole = BK == 64 && !p.k_dev && p.K % BK == 0 && (!p.A2 || p.K2 % BK == 0);
-    if (whole) hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK, WAVES_N, BK == 64>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
-    else hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, BK, WAVES_N, false>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
+    const bool whole = !p.k_dev && p.K % 64 == 0 && (!p.A2 || p.K2 % 64 == 0);
+    if (whole) hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, 64, WAVES_N, true>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
+    else hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, 64, WAVES_N, false>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
     return hipGetLastError();
   }
 #endif
