@@ -212,17 +212,10 @@ struct Operand {
     }
     return d;
   }
-  // When every slab is whole (K a multiple of BK), a K-major operand needs no per-lane test and no per-lane k
-  // offset either: the slab's k0 goes into the descriptor's base (and shortens its extent by as much, so the row
-  // bound stays where it was), a dummy slab gets an empty extent, and the lane offsets are loop constants.
-  static __device__ __forceinline__ SlabDesc slab_desc_whole(const bf16_t* tile, int ld, int rows_valid, int cols_left, int k0, int Kc) {
-    if (RMAJ) return slab_desc(tile, ld, rows_valid, cols_left, k0, Kc);
-    SlabDesc d;
-    d.k0 = k0; d.Kc = Kc;
-    const bool live = k0 < Kc;
-    d.rs = make_rsrc_words(tile + (live ? k0 : 0), live ? (uint32_t)(((int64_t)(rows_valid - 1) * ld + Kc - k0) * 2) : 0u);
-    return d;
-  }
+  // A load whose lane offset is a loop constant: a row-major operand always, a K-major one when every slab is
+  // whole (K a multiple of BK), where neither the per-lane test "is this piece still inside K" nor a per-lane k
+  // offset is needed: the slab's k0 sits in the descriptor's base (and its extent ends k0 earlier, so the row
+  // bound stays where it was), and a dummy slab has an empty extent.
   template <int I>
   static __device__ __forceinline__ void chunk_whole(const SlabDesc& d, uint32_t unit, const uint32_t (&off)[PER_WAVE], int wave_s) {
     dma16(d.rs, unit + (uint32_t)((wave_s * PER_WAVE + I) * 1024), off[I]);
@@ -932,11 +925,7 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
 #ifndef TIDE_RING_DEEPB
 #define TIDE_RING_DEEPB 0
 #endif
-#ifndef TIDE_RING_DEEPQ
-#define TIDE_RING_DEEPQ 1
-#endif
     constexpr bool DEEPB = TIDE_RING_DEEPB != 0;   // which operand owns the three units
-    constexpr int DEEPQ = TIDE_RING_DEEPQ;         // the quarter in which the deep operand's loads are issued (1 or 3)
     static_assert(A_STAGE == B_STAGE, "units are interchangeable");
     __shared__ __attribute__((aligned(1024))) bf16_t ld0[A_STAGE];
     __shared__ __attribute__((aligned(1024))) bf16_t ld1[A_STAGE];
@@ -957,24 +946,68 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
     typedef __attribute__((address_space(3))) bf16_t* lds_wp;
     auto lds_addr = [](bf16_t* q) -> uint32_t { return (uint32_t)(uintptr_t)(lds_wp)q; };
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    // The descriptor of an operand's next slab.  The loop asks for every slab of an operand once and in order, so
+    // a running base address and a count of the k still to come are enough: a handful of scalar operations per
+    // slab and no branch (computing pair, offset and extent from the slab number took twice as many, with
+    // branches, in one burst between two quarters that the matrix pipes spent waiting).  When the count runs out
+    // the walk moves on to the second operand pair, if there is one, and then to empty extents (the dummy slabs).
+    // A K-major operand can be walked when every slab is whole; one with ragged K keeps the per-slab form
+    // because its loads need k0 and K for their per-lane test.
+    constexpr bool WALK_A = KWHOLE || AMM, WALK_B = KWHOLE || BNM;
+    const int k_first = kt_lo * BK;                      // a split launch has one operand pair, so this is in pair 0
+    const int k_span0 = min(p.K, (kt_lo + nk) * BK) - k_first;
+    uint64_t a_base = (uint64_t)(a_tile0 + (AMM ? (size_t)k_first * p.lda : (size_t)k_first));
+    uint64_t b_base = (uint64_t)(b_tile0 + (BNM ? (size_t)k_first * p.ldb : (size_t)k_first));
+    uint64_t a_next = (uint64_t)a_tile1, b_next = (uint64_t)b_tile1;
+    int a_rem = k_span0, b_rem = k_span0;
+    int a_nrem = nkp2 > 0 ? p.K2 : 0, b_nrem = a_nrem;
+    const uint32_t a_step = AMM ? (uint32_t)(2 * BK) * (uint32_t)p.lda : (uint32_t)(2 * BK);
+    const uint32_t b_step = BNM ? (uint32_t)(2 * BK) * (uint32_t)p.ldb : (uint32_t)(2 * BK);
+    // extent of a live slab: row-major over K: (rows of the slab - 1) * ld + columns left; K-major: (tile rows - 1) * ld + k left
+    const uint32_t a_ext0 = AMM ? (uint32_t)(2 * (p.M - m0)) : (uint32_t)(2 * (a_rows - 1)) * (uint32_t)p.lda;
+    const uint32_t b_ext0 = BNM ? (uint32_t)(2 * (p.N - n0)) : (uint32_t)(2 * (b_rows - 1)) * (uint32_t)p.ldb;
+    auto walk = [&](auto RM, uint64_t& base, uint64_t& next, int& rem, int& nrem, uint32_t step, uint32_t ext0, int ld) {
+      i32x4_t rs;
+      const uint32_t bytes = decltype(RM)::value ? ext0 + (uint32_t)(min(rem, BK) - 1) * (uint32_t)(2 * ld) : ext0 + (uint32_t)(2 * rem);
+      rs[0] = (int)(uint32_t)base; rs[1] = (int)((uint32_t)(base >> 32) & 0xffffu); rs[2] = rem > 0 ? (int)bytes : 0; rs[3] = 0x00020000;
+      base += step;
+      rem -= BK;
+      const bool over = rem <= 0;
+      base = over ? next : base;
+      rem = over ? nrem : rem;
+      nrem = over ? 0 : nrem;
+      return rs;
+    };
     auto desc_a = [&](int kt) {
-      int pr, k0, Kc;
-      slab(kt, pr, k0, Kc);
-      if constexpr (KWHOLE) return OpA::slab_desc_whole(pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc);
-      else return OpA::slab_desc(pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc);
+      typename OpA::SlabDesc d;
+      if constexpr (WALK_A) {
+        d.k0 = 0; d.Kc = 0;
+        d.rs = walk(std::bool_constant<AMM>{}, a_base, a_next, a_rem, a_nrem, a_step, a_ext0, p.lda);
+      } else {
+        int pr, k0, Kc;
+        slab(kt, pr, k0, Kc);
+        d = OpA::slab_desc(pr ? a_tile1 : a_tile0, p.lda, a_rows, p.M - m0, k0, Kc);
+      }
+      return d;
     };
     auto desc_b = [&](int kt) {
-      int pr, k0, Kc;
-      slab(kt, pr, k0, Kc);
-      if constexpr (KWHOLE) return OpB::slab_desc_whole(pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc);
-      else return OpB::slab_desc(pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc);
+      typename OpB::SlabDesc d;
+      if constexpr (WALK_B) {
+        d.k0 = 0; d.Kc = 0;
+        d.rs = walk(std::bool_constant<BNM>{}, b_base, b_next, b_rem, b_nrem, b_step, b_ext0, p.ldb);
+      } else {
+        int pr, k0, Kc;
+        slab(kt, pr, k0, Kc);
+        d = OpB::slab_desc(pr ? b_tile1 : b_tile0, p.ldb, b_rows, p.N - n0, k0, Kc);
+      }
+      return d;
     };
     auto dma_a = [&](auto I, const typename OpA::SlabDesc& d, bf16_t* unit) {
-      if constexpr (KWHOLE) OpA::template chunk_whole<decltype(I)::value>(d, lds_addr(unit), a_off, wave_s);
+      if constexpr (WALK_A) OpA::template chunk_whole<decltype(I)::value>(d, lds_addr(unit), a_off, wave_s);
       else OpA::template chunk<decltype(I)::value>(d, lds_addr(unit), a_off, a_piece, wave_s);
     };
     auto dma_b = [&](auto I, const typename OpB::SlabDesc& d, bf16_t* unit) {
-      if constexpr (KWHOLE) OpB::template chunk_whole<decltype(I)::value>(d, lds_addr(unit), b_off, wave_s);
+      if constexpr (WALK_B) OpB::template chunk_whole<decltype(I)::value>(d, lds_addr(unit), b_off, wave_s);
       else OpB::template chunk<decltype(I)::value>(d, lds_addr(unit), b_off, b_piece, wave_s);
     };
     constexpr int NDEEP = DEEPB ? NVB : NVA, NSHAL = DEEPB ? NVA : NVB;
@@ -1025,7 +1058,6 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
     frags_b(unit_b(Int<0>{}, Int<0>{}), 0, fb0);
     all_deep(ld1, 1);
     all_shal(ls1, 1);
-    if constexpr (DEEPQ == 3) all_deep(ld2, 2);
     __builtin_amdgcn_sched_barrier(0);
     // One slab: deep unit D, shallow unit S (fa0 / fb0 hold its first quarter's operands); the next slab's units
     // are DN, SN; DP is the deep unit the slab before vacated.
@@ -1040,7 +1072,7 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
         constexpr int x = decltype(X)::value;
         if constexpr (x < GA) frag_a(ua, 1, Int<0>{}, X, fa0);
         else if constexpr (x < GA + TN) frag_b(ubb, 1, Int<x - GA>{}, fb1);
-        else if constexpr (DEEPQ == 1 && x < GA + TN + NDEEP) dma_deep(Int<x - GA - TN>{}, dd1, deep(DP));
+        else if constexpr (x < GA + TN + NDEEP) dma_deep(Int<x - GA - TN>{}, dd1, deep(DP));
       });
       quarter(Int<0>{}, fa0, fb1, [&](auto X) {
         if constexpr (decltype(X)::value < GA) frag_a(ua, 1, Int<1>{}, X, fa1);
@@ -1053,13 +1085,11 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
       const bf16_t* uan = unit_a(DN, SN);
       const bf16_t* ubn = unit_b(DN, SN);
       const auto ds = desc_shal(kt + 2);
-      const auto dd3 = desc_deep(kt + 3);
       quarter(Int<1>{}, fa1, fb1, [&](auto X) {
         constexpr int x = decltype(X)::value;
         if constexpr (x < GA) frag_a(uan, 0, Int<0>{}, X, fa0);
         else if constexpr (x < GA + TN) frag_b(ubn, 0, Int<x - GA>{}, fb0);
         if constexpr (x < NSHAL) dma_shal(X, ds, shal(S));
-        else if constexpr (DEEPQ == 3 && x < NSHAL + NDEEP) dma_deep(Int<x - NSHAL>{}, dd3, deep(D));
       });
     };
     // The unit numbers repeat every six slabs.  The last round skips the slabs past nk one by one (a chain of
