@@ -1230,7 +1230,8 @@ hipError_t launch_layout(const MfmaParams& p, hipStream_t s) {
 #endif
     constexpr int WAVES_N = TIDE_GEMM_WAVES_N;
     // every slab whole (and K known on the host): the DMA loads of a K-major operand take loop-constant lane offsets
-    const bool whole = !p.k_dev && p.K % 64 == 0 && (!p.A2 || p.K2 % 64 == 0);
+    // (with both operands row-major over K the two forms are the same code: one instantiation)
+    const bool whole = !(AMM && BNM) && !p.k_dev && p.K % 64 == 0 && (!p.A2 || p.K2 % 64 == 0);
     if (whole) hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, 64, WAVES_N, true>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
     else hipLaunchKernelGGL((gemm_mfma16_kernel<AMM, BNM, TO, 64, WAVES_N, false>), dim3((unsigned)items), dim3(2 * WAVES_N * 64), 0, s, q);
     return hipGetLastError();
