@@ -1097,11 +1097,11 @@ __global__ __launch_bounds__(2 * WAVES_N * 64) void gemm_mfma16_kernel(MfmaParam
     // spill the accumulators).
     for (int kt = 0; kt < nk; kt += 6) {
       step(Int<0>{}, Int<0>{}, Int<1>{}, Int<1>{}, Int<2>{}, kt);
-      if (kt + 1 < nk) step(Int<1>{}, Int<1>{}, Int<2>{}, Int<0>{}, Int<0>{}, kt + 1);
-      if (kt + 2 < nk) step(Int<2>{}, Int<0>{}, Int<0>{}, Int<1>{}, Int<1>{}, kt + 2);
-      if (kt + 3 < nk) step(Int<0>{}, Int<1>{}, Int<1>{}, Int<0>{}, Int<2>{}, kt + 3);
-      if (kt + 4 < nk) step(Int<1>{}, Int<0>{}, Int<2>{}, Int<1>{}, Int<0>{}, kt + 4);
-      if (kt + 5 < nk) step(Int<2>{}, Int<1>{}, Int<0>{}, Int<0>{}, Int<1>{}, kt + 5);
+      if (__builtin_expect(kt + 1 < nk, 1)) step(Int<1>{}, Int<1>{}, Int<2>{}, Int<0>{}, Int<0>{}, kt + 1);
+      if (__builtin_expect(kt + 2 < nk, 1)) step(Int<2>{}, Int<0>{}, Int<0>{}, Int<1>{}, Int<1>{}, kt + 2);
+      if (__builtin_expect(kt + 3 < nk, 1)) step(Int<0>{}, Int<1>{}, Int<1>{}, Int<0>{}, Int<2>{}, kt + 3);
+      if (__builtin_expect(kt + 4 < nk, 1)) step(Int<1>{}, Int<0>{}, Int<2>{}, Int<1>{}, Int<0>{}, kt + 4);
+      if (__builtin_expect(kt + 5 < nk, 1)) step(Int<2>{}, Int<1>{}, Int<0>{}, Int<0>{}, Int<1>{}, kt + 5);
     }
     TIDE_WAIT_VMCNT(0);   // dummy slabs still in flight write LDS: let them land before the patches are written
     constexpr int PPU = A_STAGE / kPatchElems;   // epilogue patches per unit
