@@ -68,13 +68,15 @@ def test_gemm_bf16_large_tiles_ragged(B, layout, K):
     assert cosine(got, ref) > 0.99999
 
 
+@pytest.mark.parametrize("K", [4408, 4416])
 @pytest.mark.parametrize("layout,accumulate", [(2, False), (2, True), (0, False), (1, True)])
-def test_gemm_split_of_the_last_tile_round(B, layout, accumulate):
+def test_gemm_split_of_the_last_tile_round(B, layout, accumulate, K):
     """fp32 results whose tiles leave the last round of the 256 compute units at most half full: with a workspace
     those tiles are split over K and a second kernel adds the partial sums.  Against the oracle product, and
     against the unsplit launch (same tiles, different order of the fp32 additions).  17 x 16 tiles of 256 =
-    272 = one round + 16 tiles, split four ways (a part keeps at least 1024 of K); ragged M, N and K."""
-    M, N, K = 17 * 256 - 40, 16 * 256 - 8, 4408
+    272 = one round + 16 tiles, split four ways (a part keeps at least 1024 of K); ragged M and N; K ragged (4408)
+    or a whole number of 64-deep slabs (4416: the launches whose loads take loop-constant offsets)."""
+    M, N = 17 * 256 - 40, 16 * 256 - 8
     need = B.tide_gemm_workspace_bytes(layout, M, N, K, DT["fp32"])
     assert need == 3 * 16 * 256 * 256 * 4
     assert B.tide_gemm_workspace_bytes(layout, M, N, K, DT["bf16"]) == 0             # bf16 results are never split
